@@ -1,0 +1,229 @@
+/*
+ * hch -- the hot path of H-CNN (spatial-hashing based CNN for 3D shapes) on one
+ * AMD MI355X (gfx950): 3x3x3 convolution and 2x2x2 max-pooling over the sparse
+ * surface voxels of a mini-batch of shapes held in per-level perfect spatial hash
+ * (PSH) tables.
+ *
+ * C ABI.  Plain pointers and sizes only.  Every function returns an hch_status
+ * (0 = HCH_OK); nothing throws, aborts or prints.  hch_last_error() returns a
+ * thread-local message for the last non-OK status.
+ *
+ * Pointer kinds are stated per argument: HOST = ordinary process memory,
+ * DEVICE = memory of the current HIP device (e.g. torch tensor storage).
+ * `stream` is a hipStream_t passed as void* (NULL = the default stream).  Kernels
+ * are enqueued on it and NOT synchronised, except where stated.
+ *
+ * Data layout (differs from the paper, Section 3.2, which stores a level's data
+ * array channel-major c x N): feature / gradient tensors are VOXEL-MAJOR rows,
+ *     X[N_l][c]      row i = the c features of the voxel with global data index i,
+ * so one neighbour fetch is one contiguous read.  Global data index = N*[v] + the
+ * voxel's rank inside model v (Eq.6).  At the finest level the rank is the order of
+ * the caller's coordinates; at coarser levels voxels of a model are ordered by their
+ * linear position (x*u + y)*u + z.
+ * Weights are W[27][c_in][c_out], tap k = (dx+1)*9 + (dy+1)*3 + (dz+1) for the
+ * neighbour offset (dx,dy,dz) in {-1,0,1}^3  (the paper's W is c_out x (c_in*27)
+ * with column i_c*27 + k: the same numbers transposed).
+ * The column matrix of hash2col (Algorithm 1) is col[N_l][27*c_in], element
+ * (i, k*c_in + c) = X[neighbour k of voxel i][c], or 0 where that neighbour is
+ * empty or outside the grid.
+ */
+#ifndef HCH_H
+#define HCH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HCH_OK = 0,
+    HCH_EINVAL = 1,        /* null pointer, bad size, coordinates out of range / duplicated ... */
+    HCH_ENOMEM = 2,        /* host or device allocation failed                                   */
+    HCH_EBUILD = 3,        /* PSH construction did not succeed even with singleton buckets       */
+    HCH_EHIP = 4,          /* a HIP runtime call failed (message has the HIP error string)       */
+    HCH_EUNSUPPORTED = 5,  /* a model needs a hash table side above 256 (8-bit offsets), ...     */
+    HCH_EWORKSPACE = 6     /* workspace smaller than hch_conv_workspace_bytes(..., HCH_WS_MIN)   */
+} hch_status;
+
+typedef enum {
+    HCH_F32 = 0,           /* X, W, dY are float; all arithmetic in fp32                          */
+    HCH_BF16 = 1           /* X, W, dY are bfloat16 bit patterns (uint16); products accumulate in
+                              fp32; outputs Y, dX, dW are float                                   */
+} hch_dtype;
+
+typedef struct hch_levels hch_levels;   /* opaque; owned by the library */
+
+/* Read-only view of one level of the mini-batch "super-PSH" (Section 3.2).  All
+ * pointers are owned by the hch_levels object and stay valid until hch_free_levels. */
+typedef struct {
+    int32_t ubar;            /* grid resolution of this level                                   */
+    int32_t batch;           /* b                                                               */
+    int64_t n_total;         /* N*[b]: occupied voxels of the whole batch                       */
+    int64_t m_total;         /* M*[b]: hash slots of the whole batch                            */
+    int64_t r_total;         /* R*[b]: offset-table cells of the whole batch                    */
+    /* HOST arrays */
+    const int32_t *mbar;     /* [b]   hash table side per model (Section 5.2: m^3 > n)          */
+    const int32_t *rbar;     /* [b]   offset table side per model                               */
+    const int32_t *attempts; /* [b]   number of offset-table sizes tried during construction    */
+    const int64_t *M;        /* [b+1] exclusive prefix of m^3, leading 0                        */
+    const int64_t *R;        /* [b+1] exclusive prefix of r^3                                   */
+    const int64_t *N;        /* [b+1] exclusive prefix of n                                     */
+    const int32_t *coords_host; /* [n_total][3] voxel positions in data order                   */
+    const int32_t *H_host;   /* host copies of the four super tables below, same shapes         */
+    const uint16_t *T_host;
+    const uint8_t *Phi_host;
+    const int32_t *V_host;
+    /* DEVICE arrays */
+    const int32_t *H;        /* [m_total]     H*: local data index of the slot, -1 = redundant  */
+    const uint16_t *T;       /* [m_total][3]  T*: position tag, 0xFFFF x3 on redundant slots    */
+    const uint8_t *Phi;      /* [r_total][3]  Phi*: per-axis offsets, each < m                  */
+    const int32_t *V;        /* [m_total]     V*: model index of the slot (0-based)             */
+    const int32_t *coords;   /* [n_total][3]  voxel positions in data order                     */
+    const int32_t *nbr27;    /* [n_total][27] global data index of neighbour k, or -1           */
+    const int32_t *child8;   /* [n_total][8]  global data index AT THE NEXT FINER LEVEL of child
+                                k = dx*4 + dy*2 + dz at 2p + (dx,dy,dz), or -1; NULL at level 0  */
+} hch_level_desc;
+
+const char *hch_last_error(void);
+
+/*
+ * Build the multi-level PSH of a mini-batch (Section 3.1, 3.2, 5.2).
+ *
+ *   coords_xyz     HOST  [n_total][3] int32, finest level, 0 <= x,y,z < resolution; the
+ *                        voxels of model v are rows model_offsets[v] .. model_offsets[v+1]-1;
+ *                        no duplicates inside a model
+ *   model_offsets  HOST  [batch+1] int64, model_offsets[0] = 0, strictly increasing
+ *   resolution     grid side of the finest level: a power of two, 2 .. 32768 (positions are
+ *                  tagged with 16 bits per axis and 0xFFFF marks an empty slot)
+ *   n_levels       number of levels, >= 1; level l has side resolution >> l (must stay >= 1);
+ *                  a coarse voxel is occupied iff one of its 8 children is (Section 5.1)
+ *
+ * Per model and level: hash table side m = smallest with m^3 > n; offset table side r starts
+ * at the smallest with 6 r^3 >= n and, whenever construction fails, grows to the smallest
+ * side with at least double the cells (Section 5.2); both are kept coprime.  The tables are
+ * concatenated into the super tables with prefix arrays M*, R*, N* and the model index V*.
+ * Construction runs on the host; the tables are then uploaded and the per-voxel neighbour and
+ * child index lists are produced on the device by PSH lookups (hch_build_neighbours).
+ * BLOCKS until everything is resident.  *out is owned by the library; release it with
+ * hch_free_levels.  Errors: HCH_EINVAL (arguments, range, duplicates, empty model),
+ * HCH_EUNSUPPORTED (m > 256), HCH_EBUILD, HCH_ENOMEM, HCH_EHIP; *out is NULL on error.
+ */
+hch_status hch_build_levels(const int32_t *coords_xyz, const int64_t *model_offsets,
+                            int32_t batch, int32_t resolution, int32_t n_levels,
+                            void *stream, hch_levels **out);
+
+/*
+ * The host half of hch_build_levels only: occupancy of every level, PSH construction and the
+ * super tables, kept in host memory.  Touches no GPU.  The object serves hch_level_info (all
+ * DEVICE pointers are NULL) and hch_free_levels; every other call rejects it with HCH_EINVAL.
+ */
+hch_status hch_build_tables_host(const int32_t *coords_xyz, const int64_t *model_offsets,
+                                 int32_t batch, int32_t resolution, int32_t n_levels,
+                                 hch_levels **out);
+
+void hch_free_levels(hch_levels *levels);
+
+int32_t hch_num_levels(const hch_levels *levels);
+
+/* Fill *out with the view of `level` (0 = finest).  HCH_EINVAL if out of range. */
+hch_status hch_level_info(const hch_levels *levels, int32_t level, hch_level_desc *out);
+
+/*
+ * (Re)compute on the device, by hash lookups through the level's PSH (Eq.1, Eq.4-6 and the
+ * tag test of Section 3.1), the "pre-stored neighbour information" of Section 5.3:
+ * nbr27 of `level`, and child8 of `level` (looked up in level-1's tables) when level > 0.
+ * This is the index side of the traversal of Algorithm 1, done once per level and batch
+ * instead of once per channel.  Asynchronous on `stream`.
+ */
+hch_status hch_build_neighbours(hch_levels *levels, int32_t level, void *stream);
+
+/*
+ * hash2col (Algorithm 1), rows [row_begin, row_begin + row_count) of the column matrix:
+ *   X    DEVICE [N_l][c_in]              (float or bf16 per dtype)
+ *   col  DEVICE [row_count][27*c_in]     same element type as X; written completely
+ *                                        (zeros for empty neighbours)
+ */
+hch_status hch_hash2col(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                        const void *X, int32_t c_in, int64_t row_begin, int64_t row_count,
+                        void *col, void *stream);
+
+/*
+ * col2hash (Algorithm 2): dX[j][:] = sum over (i,k) with neighbour k of voxel i equal to j of
+ * dcol[i][k*c_in + :].  dcol DEVICE [N_l][27*c_in] float; dX DEVICE [N_l][c_in] float,
+ * overwritten (no need to zero it).  The sum is taken per destination row in fixed tap
+ * order, so results are bit-reproducible run to run.
+ */
+hch_status hch_col2hash(const hch_levels *levels, int32_t level, const float *dcol,
+                        int32_t c_in, float *dX, void *stream);
+
+typedef enum {
+    HCH_WS_FWD = 0,         /* hch_conv_fwd: whole column matrix                               */
+    HCH_WS_BWD_DATA = 1,    /* hch_conv_bwd_data: required size                                */
+    HCH_WS_BWD_WEIGHT = 2,  /* hch_conv_bwd_weight: required size                              */
+    HCH_WS_MIN = 3          /* smallest workspace hch_conv_fwd accepts                         */
+} hch_ws_kind;
+
+/* Bytes of DEVICE workspace for a 3x3x3 stride-1 convolution on `level`.  Returns 0 on bad
+ * arguments.  hch_conv_fwd accepts any size >= the HCH_WS_MIN value and walks the voxels in
+ * chunks when given less than HCH_WS_FWD; the two backward calls need their full size. */
+size_t hch_conv_workspace_bytes(const hch_levels *levels, int32_t level, int32_t c_in,
+                                int32_t c_out, hch_dtype dtype, hch_ws_kind kind);
+
+/*
+ * Convolution forward (Eq.2 = Eq.3):  Y = hash2col(X) . W
+ *   X  DEVICE [N_l][c_in], W DEVICE [27][c_in][c_out]  (dtype);  Y DEVICE [N_l][c_out] float,
+ *   overwritten.  workspace DEVICE, ws_bytes as above, 256-byte aligned.  No bias.
+ */
+hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                        const void *X, const void *W, float *Y, int32_t c_in, int32_t c_out,
+                        void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * Back-propagation to the input (Eq.8 followed by col2hash, Algorithm 2):
+ *   dcol = dY . W^T ;  dX = col2hash(dcol)
+ *   dY DEVICE [N_l][c_out], W DEVICE [27][c_in][c_out] (dtype); dX DEVICE [N_l][c_in] float,
+ *   overwritten.
+ */
+hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                             const void *dY, const void *W, float *dX, int32_t c_in,
+                             int32_t c_out, void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * Weight gradient (Eq.7):  dW = hash2col(X)^T . dY
+ *   X DEVICE [N_l][c_in], dY DEVICE [N_l][c_out] (dtype); dW DEVICE [27][c_in][c_out] float,
+ *   overwritten.  Partial sums over blocks of voxels are combined in a fixed order
+ *   (bit-reproducible).
+ */
+hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                               const void *X, const void *dY, float *dW, int32_t c_in,
+                               int32_t c_out, void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * 2x2x2 stride-2 max-pooling from level_in (fine) to level_in + 1 (coarse) (Section 4,
+ * pooling): per coarse voxel and channel the maximum over the OCCUPIED children, and the
+ * switch = global data index (at level_in) of the child holding it; the first child in
+ * k order wins ties, a NaN never replaces an earlier value.
+ *   X DEVICE [N_fine][c] float; Y DEVICE [N_coarse][c] float; argmax DEVICE [N_coarse][c] int32.
+ */
+hch_status hch_pool_fwd(const hch_levels *levels, int32_t level_in, const float *X, float *Y,
+                        int32_t *argmax, int32_t c, void *stream);
+
+/*
+ * Max-pool backward (= max-unpooling, Section 4): dX[argmax[o][ch]][ch] = dY[o][ch], every
+ * other element of dX is 0.  dX DEVICE [N_fine][c] float is overwritten completely.
+ * argmax must hold, per coarse voxel, indices of its own children (what hch_pool_fwd wrote).
+ */
+hch_status hch_pool_bwd(const hch_levels *levels, int32_t level_in, const float *dY,
+                        const int32_t *argmax, float *dX, int32_t c, void *stream);
+
+/* Element-wise ReLU over a compact data array of n floats (Section 4, "other CNN
+ * operations"): y = max(x, 0);  backward dx = (y > 0) ? dy : 0.  In-place use is allowed. */
+hch_status hch_relu_fwd(const float *x, float *y, int64_t n, void *stream);
+hch_status hch_relu_bwd(const float *y, const float *dy, float *dx, int64_t n, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HCH_H */

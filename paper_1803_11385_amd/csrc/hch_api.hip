@@ -1,0 +1,629 @@
+// C ABI of the hch library: host logic, table upload and kernel launches.
+#include "../../include/hch.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <atomic>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include "kernels.hip.hpp"
+#include "psh_build.hpp"
+
+namespace {
+
+thread_local std::string g_err;
+
+hch_status fail(hch_status st, const std::string &msg)
+{
+    g_err = msg;
+    return st;
+}
+
+#define HCH_HIP(call)                                                                      \
+    do {                                                                                   \
+        hipError_t e_ = (call);                                                            \
+        if (e_ != hipSuccess)                                                              \
+            return fail(HCH_EHIP, std::string(#call) + ": " + hipGetErrorString(e_));      \
+    } while (0)
+
+#define HCH_LAUNCH_CHECK(name)                                                             \
+    do {                                                                                   \
+        hipError_t e_ = hipGetLastError();                                                 \
+        if (e_ != hipSuccess)                                                              \
+            return fail(HCH_EHIP, std::string("launch ") + name + ": " + hipGetErrorString(e_)); \
+    } while (0)
+
+// One level of the super-PSH, host and device side.
+struct Level {
+    int32_t ubar = 0, b = 0;
+    int64_t n_total = 0, m_total = 0, r_total = 0;
+    int32_t max_n = 0;                         // largest model of the level
+    std::vector<int32_t> mbar, rbar, attempts, coords;
+    std::vector<int64_t> M, R, N;
+    std::vector<int32_t> H, V;                 // host copies of the super tables
+    std::vector<uint16_t> T;
+    std::vector<uint8_t> Phi;
+    // device
+    int32_t *dH = nullptr, *dV = nullptr, *dcoords = nullptr, *dnbr = nullptr, *dchild = nullptr;
+    uint16_t *dT = nullptr;
+    uint8_t *dPhi = nullptr;
+    int32_t *dmeta = nullptr;                  // mbar[b] rbar[b] M[b+1] R[b+1] N[b+1] as int32
+
+    hch::PshView view() const
+    {
+        hch::PshView v;
+        v.H = dH; v.T = dT; v.Phi = dPhi;
+        v.mbar = dmeta; v.rbar = dmeta + b; v.M = dmeta + 2 * b; v.R = dmeta + 3 * b + 1;
+        v.N = dmeta + 4 * b + 2; v.ubar = ubar;
+        return v;
+    }
+    const int32_t *dN() const { return dmeta + 4 * b + 2; }
+};
+
+void free_level(Level &L)
+{
+    void *ptrs[] = {L.dH, L.dV, L.dcoords, L.dnbr, L.dchild, L.dT, L.dPhi, L.dmeta};
+    for (void *p : ptrs) if (p) (void)hipFree(p);
+    L.dH = L.dV = L.dcoords = L.dnbr = L.dchild = L.dmeta = nullptr;
+    L.dT = nullptr; L.dPhi = nullptr;
+}
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline unsigned blocks_for(int64_t items) { return (unsigned)((items + 255) / 256); }
+
+constexpr int64_t MAX_GRID_ITEMS = (int64_t)2147483647 * 256;   // grid.x limit * block size
+
+}  // namespace
+
+struct hch_levels {
+    std::vector<Level> lv;
+};
+
+extern "C" const char *hch_last_error(void) { return g_err.c_str(); }
+
+extern "C" void hch_free_levels(hch_levels *levels)
+{
+    if (!levels) return;
+    for (Level &L : levels->lv) free_level(L);
+    delete levels;
+}
+
+extern "C" int32_t hch_num_levels(const hch_levels *levels)
+{
+    return levels ? (int32_t)levels->lv.size() : 0;
+}
+
+// ---------------------------------------------------------------------------------------
+// build
+// ---------------------------------------------------------------------------------------
+
+static hch_status upload(void **dst, const void *src, size_t bytes, hipStream_t s)
+{
+    *dst = nullptr;
+    hipError_t e = hipMalloc(dst, bytes ? bytes : 16);
+    if (e != hipSuccess) { *dst = nullptr; return fail(HCH_ENOMEM, std::string("hipMalloc: ") + hipGetErrorString(e)); }
+    if (bytes) HCH_HIP(hipMemcpyAsync(*dst, src, bytes, hipMemcpyHostToDevice, s));
+    return HCH_OK;
+}
+
+static hch_status launch_field_index(const Level &Li, const Level &Lo, int F, int Ss, int Sp,
+                                     int32_t *out, hipStream_t s)
+{
+    const int64_t items = (int64_t)Lo.max_n * F * F * F;
+    if (items == 0) return HCH_OK;
+    dim3 grid(blocks_for(items), (unsigned)Lo.b);
+    hipLaunchKernelGGL(hch::field_index_kernel, grid, dim3(256), 0, s, Li.view(), Lo.dcoords,
+                       Lo.dN(), F, Ss, Sp, out);
+    HCH_LAUNCH_CHECK("field_index_kernel");
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_build_neighbours(hch_levels *levels, int32_t level, void *stream)
+{
+    if (!levels || level < 0 || level >= (int32_t)levels->lv.size())
+        return fail(HCH_EINVAL, "hch_build_neighbours: bad level");
+    hipStream_t s = (hipStream_t)stream;
+    Level &L = levels->lv[level];
+    if (!L.dnbr) return fail(HCH_EINVAL, "hch_build_neighbours: levels were built without device tables");
+    hch_status st = launch_field_index(L, L, 3, 1, 0, L.dnbr, s);
+    if (st != HCH_OK) return st;
+    if (level > 0) st = launch_field_index(levels->lv[level - 1], L, 2, 2, 0, L.dchild, s);
+    return st;
+}
+
+static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_offsets,
+                             int32_t batch, int32_t resolution, int32_t n_levels,
+                             void *stream, bool with_device, hch_levels **out)
+{
+    if (out) *out = nullptr;
+    if (!coords_xyz || !model_offsets || !out) return fail(HCH_EINVAL, "hch_build_levels: null pointer");
+    if (batch <= 0 || batch > 65535) return fail(HCH_EINVAL, "hch_build_levels: batch must be 1..65535");
+    if (resolution < 2 || resolution > 32768 || (resolution & (resolution - 1)))
+        return fail(HCH_EINVAL, "hch_build_levels: resolution must be a power of two in 2..32768");
+    if (n_levels < 1 || (resolution >> (n_levels - 1)) < 1)
+        return fail(HCH_EINVAL, "hch_build_levels: n_levels out of range for this resolution");
+    if (model_offsets[0] != 0) return fail(HCH_EINVAL, "hch_build_levels: model_offsets[0] must be 0");
+    for (int v = 0; v < batch; ++v)
+        if (model_offsets[v + 1] <= model_offsets[v])
+            return fail(HCH_EINVAL, "hch_build_levels: empty model or decreasing model_offsets");
+    const int64_t n_total = model_offsets[batch];
+    if (n_total >= ((int64_t)1 << 31) / 27)
+        return fail(HCH_EUNSUPPORTED, "hch_build_levels: more than 2^31/27 voxels in a batch");
+    for (int64_t i = 0; i < 3 * n_total; ++i)
+        if (coords_xyz[i] < 0 || coords_xyz[i] >= resolution)
+            return fail(HCH_EINVAL, "hch_build_levels: coordinate outside [0, resolution)");
+    // duplicates inside a model
+    {
+        std::vector<int64_t> lin;
+        for (int v = 0; v < batch; ++v) {
+            const int64_t a = model_offsets[v], n = model_offsets[v + 1] - a;
+            lin.resize((size_t)n);
+            for (int64_t i = 0; i < n; ++i) {
+                const int32_t *p = coords_xyz + 3 * (a + i);
+                lin[i] = ((int64_t)p[0] * resolution + p[1]) * resolution + p[2];
+            }
+            std::sort(lin.begin(), lin.end());
+            if (std::adjacent_find(lin.begin(), lin.end()) != lin.end())
+                return fail(HCH_EINVAL, "hch_build_levels: duplicate voxel inside a model");
+        }
+    }
+
+    hch_levels *hl = new (std::nothrow) hch_levels;
+    if (!hl) return fail(HCH_ENOMEM, "hch_build_levels: out of host memory");
+    hipStream_t s = (hipStream_t)stream;
+    hch_status st = HCH_OK;
+
+    try {
+        hl->lv.resize((size_t)n_levels);
+        // ---- occupancy of every level (host) ----
+        for (int l = 0; l < n_levels; ++l) {
+            Level &L = hl->lv[l];
+            L.ubar = resolution >> l;
+            L.b = batch;
+            L.N.assign((size_t)batch + 1, 0);
+            if (l == 0) {
+                L.coords.assign(coords_xyz, coords_xyz + 3 * n_total);
+                for (int v = 0; v <= batch; ++v) L.N[v] = model_offsets[v];
+            } else {
+                const Level &Lf = hl->lv[l - 1];
+                std::vector<int32_t> tmp;
+                for (int v = 0; v < batch; ++v) {
+                    hch::coarsen_model(Lf.coords.data() + 3 * Lf.N[v], Lf.N[v + 1] - Lf.N[v], Lf.ubar, tmp);
+                    L.coords.insert(L.coords.end(), tmp.begin(), tmp.end());
+                    L.N[v + 1] = L.N[v] + (int64_t)tmp.size() / 3;
+                }
+            }
+            L.n_total = L.N[batch];
+            L.max_n = 0;
+            for (int v = 0; v < batch; ++v) L.max_n = std::max<int32_t>(L.max_n, (int32_t)(L.N[v + 1] - L.N[v]));
+        }
+
+        // ---- PSH construction of every (level, model), spread over host threads ----
+        std::vector<std::vector<hch::ModelTables>> tabs((size_t)n_levels);
+        for (auto &t : tabs) t.resize((size_t)batch);
+        const int n_tasks = n_levels * batch;
+        std::vector<int> result((size_t)n_tasks, 0);
+        std::atomic<int> next(0);
+        auto worker = [&]() {
+            for (;;) {
+                const int t = next.fetch_add(1);
+                if (t >= n_tasks) break;
+                const int l = t / batch, v = t % batch;     // finest (largest) levels first
+                const Level &L = hl->lv[l];
+                result[t] = (int)hch::build_model_tables(L.coords.data() + 3 * L.N[v],
+                                                         L.N[v + 1] - L.N[v], L.ubar, tabs[l][v]);
+            }
+        };
+        {
+            unsigned nthr = std::thread::hardware_concurrency();
+            nthr = std::max(1u, std::min(nthr, 16u));
+            nthr = std::min<unsigned>(nthr, (unsigned)n_tasks);
+            std::vector<std::thread> pool;
+            for (unsigned i = 1; i < nthr; ++i) pool.emplace_back(worker);
+            worker();
+            for (auto &th : pool) th.join();
+        }
+        for (int t = 0; t < n_tasks && st == HCH_OK; ++t) {
+            if (result[t] == hch::BUILD_UNSUPPORTED)
+                st = fail(HCH_EUNSUPPORTED, "hch_build_levels: a model needs a hash table side above 256");
+            else if (result[t] == hch::BUILD_FAILED)
+                st = fail(HCH_EBUILD, "hch_build_levels: perfect hash construction failed");
+        }
+
+        // ---- super tables (Section 3.2) and upload ----
+        for (int l = 0; l < n_levels && st == HCH_OK; ++l) {
+            Level &L = hl->lv[l];
+            L.mbar.resize((size_t)batch); L.rbar.resize((size_t)batch); L.attempts.resize((size_t)batch);
+            L.M.assign((size_t)batch + 1, 0); L.R.assign((size_t)batch + 1, 0);
+            for (int v = 0; v < batch; ++v) {
+                const hch::ModelTables &t = tabs[l][v];
+                L.mbar[v] = t.m; L.rbar[v] = t.r; L.attempts[v] = t.attempts;
+                L.M[v + 1] = L.M[v] + (int64_t)t.m * t.m * t.m;
+                L.R[v + 1] = L.R[v] + (int64_t)t.r * t.r * t.r;
+            }
+            L.m_total = L.M[batch]; L.r_total = L.R[batch];
+            if (L.m_total >= ((int64_t)1 << 31) || L.r_total >= ((int64_t)1 << 31) / 3) {
+                st = fail(HCH_EUNSUPPORTED, "hch_build_levels: super table exceeds 32-bit indexing");
+                break;
+            }
+            L.H.resize((size_t)L.m_total); L.V.resize((size_t)L.m_total);
+            L.T.resize((size_t)L.m_total * 3); L.Phi.resize((size_t)L.r_total * 3);
+            for (int v = 0; v < batch; ++v) {
+                hch::ModelTables &t = tabs[l][v];
+                std::copy(t.H.begin(), t.H.end(), L.H.begin() + L.M[v]);
+                std::copy(t.T.begin(), t.T.end(), L.T.begin() + 3 * L.M[v]);
+                std::copy(t.Phi.begin(), t.Phi.end(), L.Phi.begin() + 3 * L.R[v]);
+                std::fill(L.V.begin() + L.M[v], L.V.begin() + L.M[v + 1], v);
+                t = hch::ModelTables();
+            }
+            if (!with_device) continue;
+            std::vector<int32_t> meta;
+            meta.insert(meta.end(), L.mbar.begin(), L.mbar.end());
+            meta.insert(meta.end(), L.rbar.begin(), L.rbar.end());
+            for (int64_t x : L.M) meta.push_back((int32_t)x);
+            for (int64_t x : L.R) meta.push_back((int32_t)x);
+            for (int64_t x : L.N) meta.push_back((int32_t)x);
+
+            if ((st = upload((void **)&L.dH, L.H.data(), L.H.size() * 4, s)) != HCH_OK) break;
+            if ((st = upload((void **)&L.dV, L.V.data(), L.V.size() * 4, s)) != HCH_OK) break;
+            if ((st = upload((void **)&L.dT, L.T.data(), L.T.size() * 2, s)) != HCH_OK) break;
+            if ((st = upload((void **)&L.dPhi, L.Phi.data(), L.Phi.size(), s)) != HCH_OK) break;
+            if ((st = upload((void **)&L.dcoords, L.coords.data(), L.coords.size() * 4, s)) != HCH_OK) break;
+            if ((st = upload((void **)&L.dmeta, meta.data(), meta.size() * 4, s)) != HCH_OK) break;
+            if (hipMalloc((void **)&L.dnbr, (size_t)L.n_total * 27 * 4) != hipSuccess) {
+                L.dnbr = nullptr; st = fail(HCH_ENOMEM, "hipMalloc(nbr27) failed"); break;
+            }
+            if (l > 0 && hipMalloc((void **)&L.dchild, (size_t)L.n_total * 8 * 4) != hipSuccess) {
+                L.dchild = nullptr; st = fail(HCH_ENOMEM, "hipMalloc(child8) failed"); break;
+            }
+            // `meta` dies at the end of this iteration: finish the copies first
+            hipError_t e = hipStreamSynchronize(s);
+            if (e != hipSuccess) { st = fail(HCH_EHIP, std::string("hipStreamSynchronize: ") + hipGetErrorString(e)); break; }
+        }
+        for (int l = 0; l < n_levels && st == HCH_OK && with_device; ++l) st = hch_build_neighbours(hl, l, s);
+        if (st == HCH_OK && with_device) {
+            hipError_t e = hipStreamSynchronize(s);
+            if (e != hipSuccess) st = fail(HCH_EHIP, std::string("hipStreamSynchronize: ") + hipGetErrorString(e));
+        }
+    } catch (const std::bad_alloc &) {
+        st = fail(HCH_ENOMEM, "hch_build_levels: out of host memory");
+    }
+
+    if (st != HCH_OK) { hch_free_levels(hl); return st; }
+    *out = hl;
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_build_levels(const int32_t *coords_xyz, const int64_t *model_offsets,
+                                       int32_t batch, int32_t resolution, int32_t n_levels,
+                                       void *stream, hch_levels **out)
+{
+    return build_impl(coords_xyz, model_offsets, batch, resolution, n_levels, stream, true, out);
+}
+
+extern "C" hch_status hch_build_tables_host(const int32_t *coords_xyz, const int64_t *model_offsets,
+                                            int32_t batch, int32_t resolution, int32_t n_levels,
+                                            hch_levels **out)
+{
+    return build_impl(coords_xyz, model_offsets, batch, resolution, n_levels, nullptr, false, out);
+}
+
+extern "C" hch_status hch_level_info(const hch_levels *levels, int32_t level, hch_level_desc *out)
+{
+    if (!levels || !out || level < 0 || level >= (int32_t)levels->lv.size())
+        return fail(HCH_EINVAL, "hch_level_info: bad argument");
+    const Level &L = levels->lv[level];
+    out->ubar = L.ubar; out->batch = L.b;
+    out->n_total = L.n_total; out->m_total = L.m_total; out->r_total = L.r_total;
+    out->mbar = L.mbar.data(); out->rbar = L.rbar.data(); out->attempts = L.attempts.data();
+    out->M = L.M.data(); out->R = L.R.data(); out->N = L.N.data();
+    out->coords_host = L.coords.data();
+    out->H_host = L.H.data(); out->T_host = L.T.data(); out->Phi_host = L.Phi.data();
+    out->V_host = L.V.data();
+    out->H = L.dH; out->T = L.dT; out->Phi = L.dPhi; out->V = L.dV; out->coords = L.dcoords;
+    out->nbr27 = L.dnbr; out->child8 = L.dchild;
+    return HCH_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// hash2col / col2hash
+// ---------------------------------------------------------------------------------------
+
+static hch_status get_level(const hch_levels *levels, int32_t level, const Level **L, const char *who)
+{
+    if (!levels || level < 0 || level >= (int32_t)levels->lv.size())
+        return fail(HCH_EINVAL, std::string(who) + ": bad level");
+    *L = &levels->lv[level];
+    if (!(*L)->dnbr) return fail(HCH_EINVAL, std::string(who) + ": levels were built without device tables");
+    return HCH_OK;
+}
+
+static inline int elem_size(hch_dtype d) { return d == HCH_BF16 ? 2 : 4; }
+
+static hch_status do_hash2col(const Level &L, hch_dtype dtype, const void *X, int c_in,
+                              int64_t row_begin, int64_t rows, void *col, hipStream_t s)
+{
+    if (rows == 0) return HCH_OK;
+    const int es = elem_size(dtype);
+    const int row_bytes = c_in * es;
+    if (row_bytes % 16 == 0 && aligned16(X) && aligned16(col)) {
+        const int cv = row_bytes / 16;
+        const int64_t items = rows * 27 * cv;
+        if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hash2col: too many rows in one launch");
+        hipLaunchKernelGGL(hch::hash2col_vec_kernel, dim3(blocks_for(items)), dim3(256), 0, s,
+                           (const uint4 *)X, L.dnbr, (uint4 *)col, row_begin, rows, cv);
+    } else {
+        const int64_t items = rows * 27 * c_in;
+        if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hash2col: too many rows in one launch");
+        if (dtype == HCH_F32)
+            hipLaunchKernelGGL(hch::hash2col_elem_kernel<float>, dim3(blocks_for(items)), dim3(256), 0, s,
+                               (const float *)X, L.dnbr, (float *)col, row_begin, rows, c_in);
+        else
+            hipLaunchKernelGGL(hch::hash2col_elem_kernel<uint16_t>, dim3(blocks_for(items)), dim3(256), 0, s,
+                               (const uint16_t *)X, L.dnbr, (uint16_t *)col, row_begin, rows, c_in);
+    }
+    HCH_LAUNCH_CHECK("hash2col");
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_hash2col(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                                   const void *X, int32_t c_in, int64_t row_begin,
+                                   int64_t row_count, void *col, void *stream)
+{
+    const Level *L;
+    hch_status st = get_level(levels, level, &L, "hch_hash2col");
+    if (st != HCH_OK) return st;
+    if (!X || !col || c_in <= 0 || (dtype != HCH_F32 && dtype != HCH_BF16))
+        return fail(HCH_EINVAL, "hch_hash2col: bad argument");
+    if (row_begin < 0 || row_count < 0 || row_begin + row_count > L->n_total)
+        return fail(HCH_EINVAL, "hch_hash2col: row range outside the level");
+    return do_hash2col(*L, dtype, X, c_in, row_begin, row_count, col, (hipStream_t)stream);
+}
+
+static hch_status do_col2hash(const Level &L, const float *dcol, int c_in, float *dX, hipStream_t s)
+{
+    if (c_in % 4 == 0 && aligned16(dcol) && aligned16(dX)) {
+        const int64_t items = L.n_total * (c_in / 4);
+        hipLaunchKernelGGL(hch::col2hash_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, s,
+                           dcol, L.dnbr, dX, L.n_total, c_in);
+    } else {
+        const int64_t items = L.n_total * c_in;
+        hipLaunchKernelGGL(hch::col2hash_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, s,
+                           dcol, L.dnbr, dX, L.n_total, c_in);
+    }
+    HCH_LAUNCH_CHECK("col2hash");
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_col2hash(const hch_levels *levels, int32_t level, const float *dcol,
+                                   int32_t c_in, float *dX, void *stream)
+{
+    const Level *L;
+    hch_status st = get_level(levels, level, &L, "hch_col2hash");
+    if (st != HCH_OK) return st;
+    if (!dcol || !dX || c_in <= 0) return fail(HCH_EINVAL, "hch_col2hash: bad argument");
+    return do_col2hash(*L, dcol, c_in, dX, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------
+// GEMM launches
+// ---------------------------------------------------------------------------------------
+
+template <bool A_KC, bool B_KC>
+static hch_status launch_gemm(const float *A, const float *B, float *C, int M, int N, int K,
+                              int64_t lda, int64_t ldb, int64_t ldc, int splits, int k_per_split,
+                              int64_t c_split_stride, hipStream_t s)
+{
+    if (M <= 0 || N <= 0) return HCH_OK;
+    const int vec_ok = (lda % 4 == 0) && (ldb % 4 == 0) && aligned16(A) && aligned16(B);
+    const unsigned gx = (unsigned)((M + hch::GEMM_BM - 1) / hch::GEMM_BM);
+    if (N <= 16) {
+        hipLaunchKernelGGL((hch::gemm_f32_kernel<16, A_KC, B_KC>), dim3(gx, 1, splits), dim3(256), 0, s,
+                           A, B, C, M, N, K, lda, ldb, ldc, k_per_split, c_split_stride, vec_ok);
+    } else if (N <= 32) {
+        hipLaunchKernelGGL((hch::gemm_f32_kernel<32, A_KC, B_KC>), dim3(gx, 1, splits), dim3(256), 0, s,
+                           A, B, C, M, N, K, lda, ldb, ldc, k_per_split, c_split_stride, vec_ok);
+    } else {
+        hipLaunchKernelGGL((hch::gemm_f32_kernel<64, A_KC, B_KC>), dim3(gx, (unsigned)((N + 63) / 64), splits),
+                           dim3(256), 0, s, A, B, C, M, N, K, lda, ldb, ldc, k_per_split,
+                           c_split_stride, vec_ok);
+    }
+    HCH_LAUNCH_CHECK("gemm_f32_kernel");
+    return HCH_OK;
+}
+
+// split plan of the weight-gradient reduction over the voxels
+struct WgradPlan { int splits; int rows_per_split; };
+
+static WgradPlan wgrad_plan(int64_t n, int c_in, int c_out)
+{
+    const int Kc = 27 * c_in;
+    const int64_t tiles = (int64_t)((Kc + hch::GEMM_BM - 1) / hch::GEMM_BM) * ((c_out + 63) / 64);
+    int64_t want = std::max<int64_t>(1, 2048 / tiles);
+    want = std::min<int64_t>(want, std::max<int64_t>(1, (n + 255) / 256));
+    int64_t rows = (n + want - 1) / want;
+    rows = std::max<int64_t>(hch::GEMM_BK, (rows + hch::GEMM_BK - 1) / hch::GEMM_BK * hch::GEMM_BK);
+    WgradPlan p;
+    p.rows_per_split = (int)rows;
+    p.splits = (int)std::max<int64_t>(1, (n + rows - 1) / rows);
+    return p;
+}
+
+extern "C" size_t hch_conv_workspace_bytes(const hch_levels *levels, int32_t level, int32_t c_in,
+                                           int32_t c_out, hch_dtype dtype, hch_ws_kind kind)
+{
+    if (!levels || level < 0 || level >= (int32_t)levels->lv.size() || c_in <= 0 || c_out <= 0) return 0;
+    const Level &L = levels->lv[level];
+    const size_t Kc = (size_t)27 * c_in;
+    const size_t n = (size_t)L.n_total;
+    switch (kind) {
+    case HCH_WS_FWD: return round_up(n * Kc * elem_size(dtype), 256);
+    case HCH_WS_BWD_DATA: return round_up(n * Kc * 4, 256);
+    case HCH_WS_BWD_WEIGHT: {
+        const WgradPlan p = wgrad_plan(L.n_total, c_in, c_out);
+        return round_up(n * Kc * elem_size(dtype), 256) + round_up((size_t)p.splits * Kc * c_out * 4, 256);
+    }
+    case HCH_WS_MIN: return round_up(std::min<size_t>(n, 1024) * Kc * elem_size(dtype), 256);
+    }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------------------
+// convolution
+// ---------------------------------------------------------------------------------------
+
+static hch_status conv_args(const hch_levels *levels, int32_t level, hch_dtype dtype, const void *a,
+                            const void *b, const void *c, int32_t c_in, int32_t c_out,
+                            const void *ws, const Level **L, const char *who)
+{
+    hch_status st = get_level(levels, level, L, who);
+    if (st != HCH_OK) return st;
+    if (!a || !b || !c || !ws || c_in <= 0 || c_out <= 0)
+        return fail(HCH_EINVAL, std::string(who) + ": null pointer or non-positive channel count");
+    if ((int64_t)27 * c_in * c_out >= ((int64_t)1 << 31))
+        return fail(HCH_EINVAL, std::string(who) + ": weight tensor too large");
+    if (dtype != HCH_F32)
+        return fail(HCH_EUNSUPPORTED, std::string(who) + ": only HCH_F32 is implemented");
+    if (reinterpret_cast<uintptr_t>(ws) & 255u)
+        return fail(HCH_EINVAL, std::string(who) + ": workspace must be 256-byte aligned");
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                                   const void *X, const void *W, float *Y, int32_t c_in,
+                                   int32_t c_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    const Level *L;
+    hch_status st = conv_args(levels, level, dtype, X, W, Y, c_in, c_out, workspace, &L, "hch_conv_fwd");
+    if (st != HCH_OK) return st;
+    if (ws_bytes < hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, HCH_WS_MIN))
+        return fail(HCH_EWORKSPACE, "hch_conv_fwd: workspace too small");
+    hipStream_t s = (hipStream_t)stream;
+    const int Kc = 27 * c_in;
+    // as many rows of the column matrix as the workspace holds, in multiples of the GEMM tile
+    int64_t chunk = (int64_t)(ws_bytes / ((size_t)Kc * 4));
+    if (chunk < L->n_total) chunk = std::max<int64_t>(hch::GEMM_BM, chunk / hch::GEMM_BM * hch::GEMM_BM);
+    chunk = std::min<int64_t>(chunk, (int64_t)1 << 30);
+    for (int64_t r0 = 0; r0 < L->n_total; r0 += chunk) {
+        const int64_t rows = std::min<int64_t>(chunk, L->n_total - r0);
+        st = do_hash2col(*L, dtype, X, c_in, r0, rows, workspace, s);
+        if (st != HCH_OK) return st;
+        st = launch_gemm<true, false>((const float *)workspace, (const float *)W, Y + r0 * c_out,
+                                      (int)rows, c_out, Kc, Kc, c_out, c_out, 1, Kc + hch::GEMM_BK, 0, s);
+        if (st != HCH_OK) return st;
+    }
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                                        const void *dY, const void *W, float *dX, int32_t c_in,
+                                        int32_t c_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    const Level *L;
+    hch_status st = conv_args(levels, level, dtype, dY, W, dX, c_in, c_out, workspace, &L, "hch_conv_bwd_data");
+    if (st != HCH_OK) return st;
+    if (ws_bytes < hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, HCH_WS_BWD_DATA))
+        return fail(HCH_EWORKSPACE, "hch_conv_bwd_data: workspace too small");
+    if (L->n_total >= ((int64_t)1 << 31)) return fail(HCH_EUNSUPPORTED, "hch_conv_bwd_data: too many voxels");
+    hipStream_t s = (hipStream_t)stream;
+    const int Kc = 27 * c_in;
+    float *dcol = (float *)workspace;
+    // dcol[N x Kc] = dY[N x c_out] . W^T   (W is [Kc x c_out]: its rows are B's columns)
+    st = launch_gemm<true, true>((const float *)dY, (const float *)W, dcol, (int)L->n_total, Kc, c_out,
+                                 c_out, c_out, Kc, 1, c_out + hch::GEMM_BK, 0, s);
+    if (st != HCH_OK) return st;
+    return do_col2hash(*L, dcol, c_in, dX, s);
+}
+
+extern "C" hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                                          const void *X, const void *dY, float *dW, int32_t c_in,
+                                          int32_t c_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    const Level *L;
+    hch_status st = conv_args(levels, level, dtype, X, dY, dW, c_in, c_out, workspace, &L, "hch_conv_bwd_weight");
+    if (st != HCH_OK) return st;
+    if (ws_bytes < hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, HCH_WS_BWD_WEIGHT))
+        return fail(HCH_EWORKSPACE, "hch_conv_bwd_weight: workspace too small");
+    if (L->n_total >= ((int64_t)1 << 31)) return fail(HCH_EUNSUPPORTED, "hch_conv_bwd_weight: too many voxels");
+    hipStream_t s = (hipStream_t)stream;
+    const int Kc = 27 * c_in;
+    const size_t col_bytes = round_up((size_t)L->n_total * Kc * 4, 256);
+    float *col = (float *)workspace;
+    float *part = (float *)((char *)workspace + col_bytes);
+    st = do_hash2col(*L, dtype, X, c_in, 0, L->n_total, col, s);
+    if (st != HCH_OK) return st;
+    const WgradPlan p = wgrad_plan(L->n_total, c_in, c_out);
+    const int64_t wsize = (int64_t)Kc * c_out;
+    // dW[Kc x c_out] = col^T[Kc x N] . dY[N x c_out], reduction over the voxels split in slices
+    float *dst = (p.splits == 1) ? dW : part;
+    st = launch_gemm<false, false>(col, (const float *)dY, dst, Kc, c_out, (int)L->n_total, Kc, c_out,
+                                   c_out, p.splits, p.rows_per_split, wsize, s);
+    if (st != HCH_OK) return st;
+    if (p.splits > 1) {
+        hipLaunchKernelGGL(hch::splitk_reduce_kernel, dim3((unsigned)((wsize + 63) / 64)), dim3(256), 0, s,
+                           part, dW, wsize, p.splits, wsize);
+        HCH_LAUNCH_CHECK("splitk_reduce_kernel");
+    }
+    return HCH_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// pooling, ReLU
+// ---------------------------------------------------------------------------------------
+
+extern "C" hch_status hch_pool_fwd(const hch_levels *levels, int32_t level_in, const float *X,
+                                   float *Y, int32_t *argmax, int32_t c, void *stream)
+{
+    if (!levels || level_in < 0 || level_in + 1 >= (int32_t)levels->lv.size())
+        return fail(HCH_EINVAL, "hch_pool_fwd: level_in must have a coarser level");
+    if (!X || !Y || !argmax || c <= 0) return fail(HCH_EINVAL, "hch_pool_fwd: bad argument");
+    const Level &Lc = levels->lv[level_in + 1];
+    if (!Lc.dchild) return fail(HCH_EINVAL, "hch_pool_fwd: levels were built without device tables");
+    const int64_t items = Lc.n_total * c;
+    if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hch_pool_fwd: too large");
+    hipLaunchKernelGGL(hch::pool_fwd_kernel, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                       X, Lc.dchild, Y, argmax, Lc.n_total, c);
+    HCH_LAUNCH_CHECK("pool_fwd_kernel");
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_pool_bwd(const hch_levels *levels, int32_t level_in, const float *dY,
+                                   const int32_t *argmax, float *dX, int32_t c, void *stream)
+{
+    if (!levels || level_in < 0 || level_in + 1 >= (int32_t)levels->lv.size())
+        return fail(HCH_EINVAL, "hch_pool_bwd: level_in must have a coarser level");
+    if (!dY || !argmax || !dX || c <= 0) return fail(HCH_EINVAL, "hch_pool_bwd: bad argument");
+    const Level &Lc = levels->lv[level_in + 1];
+    if (!Lc.dchild) return fail(HCH_EINVAL, "hch_pool_bwd: levels were built without device tables");
+    const int64_t items = Lc.n_total * 8 * c;
+    if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hch_pool_bwd: too large");
+    hipLaunchKernelGGL(hch::pool_bwd_kernel, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                       dY, argmax, Lc.dchild, dX, Lc.n_total, c);
+    HCH_LAUNCH_CHECK("pool_bwd_kernel");
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_relu_fwd(const float *x, float *y, int64_t n, void *stream)
+{
+    if (!x || !y || n < 0) return fail(HCH_EINVAL, "hch_relu_fwd: bad argument");
+    if (n == 0) return HCH_OK;
+    hipLaunchKernelGGL(hch::relu_fwd_kernel, dim3(blocks_for(n)), dim3(256), 0, (hipStream_t)stream, x, y, n);
+    HCH_LAUNCH_CHECK("relu_fwd_kernel");
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_relu_bwd(const float *y, const float *dy, float *dx, int64_t n, void *stream)
+{
+    if (!y || !dy || !dx || n < 0) return fail(HCH_EINVAL, "hch_relu_bwd: bad argument");
+    if (n == 0) return HCH_OK;
+    hipLaunchKernelGGL(hch::relu_bwd_kernel, dim3(blocks_for(n)), dim3(256), 0, (hipStream_t)stream, y, dy, dx, n);
+    HCH_LAUNCH_CHECK("relu_bwd_kernel");
+    return HCH_OK;
+}

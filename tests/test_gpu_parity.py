@@ -1,0 +1,285 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs.  Integer results (tables, neighbour / child lists, pooling switches,
+gathered columns) must match bit for bit; floating-point results must satisfy
+    |gpu - oracle| <= tol * (|oracle| + rms(oracle)),  tol = 1e-4 for fp32.
+"""
+import numpy as np
+import pytest
+
+import synth_shapes as S
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+hch = pytest.importorskip("paper_1803_11385_amd")
+
+TOL_F32 = 1e-4
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
+
+
+def assert_close(got, want, tol=TOL_F32, what=""):
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    assert got.shape == want.shape, (got.shape, want.shape)
+    assert np.isfinite(got).all(), what
+    rms = float(np.sqrt((want ** 2).mean())) if want.size else 0.0
+    err = np.abs(got - want)
+    bound = tol * (np.abs(want) + rms)
+    worst = float((err / np.maximum(bound, 1e-300)).max()) if want.size else 0.0
+    assert worst <= 1.0, f"{what}: max err/bound = {worst:.3g}, max abs err = {err.max():.3g}, rms = {rms:.3g}"
+
+
+def workspace(nbytes):
+    t = torch.empty(max(nbytes, 256) + 256, dtype=torch.uint8, device="cuda")
+    off = (-t.data_ptr()) % 256
+    return t[off: off + max(nbytes, 256)]
+
+
+class Case:
+    """Geometry + both implementations' levels."""
+
+    def __init__(self, oracle, coords, offs, u, n_levels):
+        self.coords, self.offs, self.u = coords, np.asarray(offs, np.int64), u
+        self.olv = oracle.build_hierarchy(coords, offs, u, n_levels)
+        self.glv = hch.hch_build_levels(coords, offs, u, n_levels)
+        torch.cuda.synchronize()
+
+
+@pytest.fixture(scope="module")
+def case_sphere(oracle):
+    coords, normals = S.sphere_shell_32()
+    c = Case(oracle, coords, [0, coords.shape[0]], 32, 2)
+    c.normals = normals
+    return c
+
+
+@pytest.fixture(scope="module")
+def case_batch64(oracle):
+    coords, offs, normals = S.config_batch(2, with_normals=True)
+    c = Case(oracle, coords, offs, 64, 3)
+    c.normals = normals
+    return c
+
+
+@pytest.fixture(scope="module")
+def case_small(oracle):
+    # several GEMM tiles and a ragged tail, small enough for the oracle's column matrix
+    coords, offs, _ = S.config_batch(3, batch=4, u=64)
+    return Case(oracle, coords, offs, 64, 3)
+
+
+# --------------------------------------------------------------------------------------
+# tables and index lists: bit-exact
+# --------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["case_sphere", "case_batch64", "case_small"])
+def test_tables_and_index_lists_bit_exact(request, oracle, name):
+    case = request.getfixturevalue(name)
+    for l, L in enumerate(case.olv):
+        info = case.glv.info(l)
+        assert np.array_equal(info.mbar, L.mbar) and np.array_equal(info.rbar, L.rbar)
+        assert np.array_equal(info.M, L.M) and np.array_equal(info.R, L.R) and np.array_equal(info.N, L.N)
+        assert np.array_equal(info.device_H(), L.H)
+        assert np.array_equal(info.device_T(), L.T)
+        assert np.array_equal(info.device_Phi(), L.Phi)
+        assert np.array_equal(info.device_V(), L.V)
+        assert np.array_equal(info.device_coords(), L.coords)
+        assert np.array_equal(info.device_nbr27(), oracle.neighbours(L)), f"nbr27 level {l}"
+        if l > 0:
+            assert np.array_equal(info.device_child8(), oracle.children(case.olv[l - 1], L)), f"child8 level {l}"
+
+
+def test_neighbour_rebuild_is_idempotent(oracle, case_batch64):
+    case = case_batch64
+    for l in range(3):
+        hch.hch_build_neighbours(case.glv, l)
+    torch.cuda.synchronize()
+    assert np.array_equal(case.glv.info(1).device_nbr27(), oracle.neighbours(case.olv[1]))
+    assert np.array_equal(case.glv.info(2).device_child8(), oracle.children(case.olv[1], case.olv[2]))
+
+
+# --------------------------------------------------------------------------------------
+# hash2col / col2hash
+# --------------------------------------------------------------------------------------
+
+def _oracle_col(oracle, L, X):
+    """oracle's (c*27) x N column matrix rearranged to the library's [N][27*c] (k-major)."""
+    c = X.shape[1]
+    Dt = oracle.hash2col(L, L, oracle.to_paper_X(X))
+    return np.ascontiguousarray(Dt.reshape(c, 27, L.Ntot).transpose(2, 1, 0).reshape(L.Ntot, 27 * c))
+
+
+@pytest.mark.parametrize("c_in", [3, 4, 32])
+def test_hash2col_bit_exact(oracle, case_batch64, c_in):
+    case = case_batch64
+    L = case.olv[1]
+    X = S.gaussian((L.Ntot, c_in), 1.0, 11)
+    col = torch.full((L.Ntot, 27 * c_in), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_hash2col(case.glv, 1, hch.HCH_F32, dev(X), c_in, 0, L.Ntot, col)
+    want = _oracle_col(oracle, L, X).astype(np.float32)
+    assert np.array_equal(col.cpu().numpy(), want)
+    # a row range in the middle
+    r0, rows = 1000, 777
+    part = torch.full((rows, 27 * c_in), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_hash2col(case.glv, 1, hch.HCH_F32, dev(X), c_in, r0, rows, part)
+    assert np.array_equal(part.cpu().numpy(), want[r0:r0 + rows])
+
+
+def test_hash2col_bf16_bit_exact(oracle, case_batch64):
+    case = case_batch64
+    L = case.olv[1]
+    for c_in in (8, 5):
+        X = S.to_bf16_grid(S.gaussian((L.Ntot, c_in), 1.0, 12))
+        bits = S.bf16_bits(X)
+        col = torch.full((L.Ntot, 27 * c_in), 0x7FC0, dtype=torch.int16, device="cuda")
+        hch.hch_hash2col(case.glv, 1, hch.HCH_BF16, dev(bits.view(np.int16)), c_in, 0, L.Ntot, col)
+        want = S.bf16_bits(_oracle_col(oracle, L, X).astype(np.float32))
+        assert np.array_equal(col.cpu().numpy().view(np.uint16), want)
+
+
+@pytest.mark.parametrize("c_in", [3, 8])
+def test_col2hash(oracle, case_small, c_in):
+    case = case_small
+    L = case.olv[0]
+    dcol = S.gaussian((L.Ntot, 27 * c_in), 1.0, 13)
+    dX = torch.full((L.Ntot, c_in), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_col2hash(case.glv, 0, dev(dcol), c_in, dX)
+    dDt = dcol.astype(np.float64).reshape(L.Ntot, 27, c_in).transpose(2, 1, 0).reshape(c_in * 27, L.Ntot)
+    want = oracle.col2hash(L, L, dDt, c_in).T
+    assert_close(dX.cpu().numpy(), want, what="col2hash")
+    # run-to-run reproducibility
+    dX2 = torch.empty_like(dX)
+    hch.hch_col2hash(case.glv, 0, dev(dcol), c_in, dX2)
+    assert torch.equal(dX, dX2)
+
+
+# --------------------------------------------------------------------------------------
+# convolution forward and backward
+# --------------------------------------------------------------------------------------
+
+def _conv_fwd_gpu(case, level, X, W, ws_bytes=None):
+    n, c_in = X.shape
+    c_out = W.shape[2]
+    if ws_bytes is None:
+        ws_bytes = hch.hch_conv_workspace_bytes(case.glv, level, c_in, c_out, hch.HCH_F32, hch.HCH_WS_FWD)
+    ws = workspace(ws_bytes)
+    Y = torch.full((n, c_out), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_conv_fwd(case.glv, level, hch.HCH_F32, dev(X), dev(W), Y, c_in, c_out, ws)
+    return Y.cpu().numpy()
+
+
+def test_conv_fwd_sphere_3_to_16(oracle, case_sphere):
+    """Single shape, 32^3, 3 -> 16 channels, weights N(0, 0.1) seed 0, then max-pool to 16^3."""
+    case = case_sphere
+    L = case.olv[0]
+    W = S.gaussian((27, 3, 16), 0.1, 0)
+    Y = _conv_fwd_gpu(case, 0, case.normals, W)
+    want = oracle.conv_fwd(L, oracle.to_paper_X(case.normals), oracle.to_paper_W(W))
+    assert_close(Y, want.T, what="conv fwd sphere")
+    # pool the GPU's own conv output on both sides: same fp32 inputs, so the switches must agree
+    Yp = torch.empty((case.olv[1].Ntot, 16), dtype=torch.float32, device="cuda")
+    sw = torch.empty((case.olv[1].Ntot, 16), dtype=torch.int32, device="cuda")
+    hch.hch_pool_fwd(case.glv, 0, dev(Y), Yp, sw, 16)
+    Po, swo = oracle.pool_max_fwd(L, case.olv[1], oracle.to_paper_X(Y))
+    assert np.array_equal(sw.cpu().numpy(), swo.T)
+    assert np.array_equal(Yp.cpu().numpy(), Po.T.astype(np.float32))
+
+
+def test_conv_fwd_batch64_4_to_32(oracle, case_batch64):
+    case = case_batch64
+    L = case.olv[0]
+    X = S.normals_plus_one(case.normals)
+    W = S.gaussian((27, 4, 32), 0.05, 2000)
+    want = oracle.conv_fwd(L, oracle.to_paper_X(X), oracle.to_paper_W(W)).T
+    assert_close(_conv_fwd_gpu(case, 0, X, W), want, what="conv fwd 4->32")
+    # the same through a workspace that forces several chunks
+    small = hch.hch_conv_workspace_bytes(case.glv, 0, 4, 32, hch.HCH_F32, hch.HCH_WS_MIN)
+    assert_close(_conv_fwd_gpu(case, 0, X, W, ws_bytes=small * 5 + 4096), want, what="conv fwd chunked")
+
+
+@pytest.mark.parametrize("c_in,c_out,level", [(32, 64, 0), (16, 32, 1), (5, 7, 1), (64, 128, 2), (8, 80, 2)])
+def test_conv_fwd_and_gradients(oracle, case_small, c_in, c_out, level):
+    case = case_small
+    L = case.olv[level]
+    n = L.Ntot
+    X = S.gaussian((n, c_in), 1.0, 21)
+    W = S.he_weights(c_in, c_out, 22)
+    G = S.gaussian((n, c_out), 1.0, 23)
+    Xp, Wp, Gp = oracle.to_paper_X(X), oracle.to_paper_W(W), oracle.to_paper_X(G)
+
+    assert_close(_conv_fwd_gpu(case, level, X, W), oracle.conv_fwd(L, Xp, Wp).T, what="fwd")
+
+    ws = workspace(hch.hch_conv_workspace_bytes(case.glv, level, c_in, c_out, hch.HCH_F32, hch.HCH_WS_BWD_DATA))
+    dX = torch.full((n, c_in), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_conv_bwd_data(case.glv, level, hch.HCH_F32, dev(G), dev(W), dX, c_in, c_out, ws)
+    assert_close(dX.cpu().numpy(), oracle.conv_bwd_data(L, Gp, Wp, c_in).T, what="bwd data")
+
+    ws = workspace(hch.hch_conv_workspace_bytes(case.glv, level, c_in, c_out, hch.HCH_F32, hch.HCH_WS_BWD_WEIGHT))
+    dW = torch.full((27, c_in, c_out), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_conv_bwd_weight(case.glv, level, hch.HCH_F32, dev(X), dev(G), dW, c_in, c_out, ws)
+    want_dW = oracle.from_paper_W(oracle.conv_bwd_weight(L, Xp, Gp), c_in)
+    assert_close(dW.cpu().numpy(), want_dW, what="bwd weight")
+    dW2 = torch.empty_like(dW)
+    hch.hch_conv_bwd_weight(case.glv, level, hch.HCH_F32, dev(X), dev(G), dW2, c_in, c_out, ws)
+    assert torch.equal(dW, dW2)
+
+
+# --------------------------------------------------------------------------------------
+# pooling, ReLU
+# --------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("c", [1, 16, 37])
+def test_pool_fwd_bwd(oracle, case_batch64, c):
+    case = case_batch64
+    lf, lc = case.olv[0], case.olv[1]
+    X = S.gaussian((lf.Ntot, c), 1.0, 31)
+    X[np.random.default_rng(32).random(X.shape) < 0.5] = 0.0        # ties, as after ReLU
+    Y = torch.full((lc.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
+    sw = torch.full((lc.Ntot, c), -7, dtype=torch.int32, device="cuda")
+    hch.hch_pool_fwd(case.glv, 0, dev(X), Y, sw, c)
+    Yo, swo = oracle.pool_max_fwd(lf, lc, oracle.to_paper_X(X))
+    assert np.array_equal(sw.cpu().numpy(), swo.T)
+    assert np.array_equal(Y.cpu().numpy(), Yo.T.astype(np.float32))
+    dY = S.gaussian((lc.Ntot, c), 1.0, 33)
+    dX = torch.full((lf.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_pool_bwd(case.glv, 0, dev(dY), sw, dX, c)
+    want = oracle.pool_max_bwd(lf.Ntot, oracle.to_paper_X(dY), swo).T
+    assert np.array_equal(dX.cpu().numpy(), want.astype(np.float32))
+
+
+def test_relu():
+    x = S.gaussian((100003,), 1.0, 41)
+    y = torch.empty(x.size, dtype=torch.float32, device="cuda")
+    hch.hch_relu_fwd(dev(x), y, x.size)
+    assert np.array_equal(y.cpu().numpy(), np.maximum(x, 0))
+    g = S.gaussian((100003,), 1.0, 42)
+    dx = torch.empty_like(y)
+    hch.hch_relu_bwd(y, dev(g), dx, x.size)
+    assert np.array_equal(dx.cpu().numpy(), np.where(x > 0, g, 0).astype(np.float32))
+
+
+# --------------------------------------------------------------------------------------
+# errors
+# --------------------------------------------------------------------------------------
+
+def test_error_paths(case_sphere):
+    case = case_sphere
+    n = case.olv[0].Ntot
+    X = dev(case.normals)
+    W = dev(S.gaussian((27, 3, 16), 0.1, 0))
+    Y = torch.empty((n, 16), dtype=torch.float32, device="cuda")
+    with pytest.raises(hch.HchError) as ei:
+        hch.hch_conv_fwd(case.glv, 0, hch.HCH_F32, X, W, Y, 3, 16, workspace(256))
+    assert ei.value.status == 6
+    with pytest.raises(hch.HchError) as ei:
+        hch.hch_conv_fwd(case.glv, 5, hch.HCH_F32, X, W, Y, 3, 16, workspace(1 << 20))
+    assert ei.value.status == 1
+    with pytest.raises(hch.HchError) as ei:
+        hch.hch_pool_fwd(case.glv, 1, X, Y, Y, 3)          # no coarser level below level 1
+    assert ei.value.status == 1
+    with pytest.raises(hch.HchError) as ei:
+        hch.hch_hash2col(case.glv, 0, hch.HCH_F32, X, 3, n - 5, 10, Y)
+    assert ei.value.status == 1
