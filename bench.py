@@ -1,0 +1,184 @@
+"""Benchmark of the H-CNN hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch: neighbour / child index lists
+by hash lookups, then a 5-level encoder (conv3x3x3 -> ReLU -> 2x2x2 max-pool per level,
+256^3 -> 8^3, channels 4-16-32-64-128-256) forward and backward (weight and data gradients at
+every level), on the 256^3 / batch 8 workload.  Inputs are resident in HBM before the timed
+region; PSH construction is pre-processing and is not timed.
+
+Prints ONE JSON line (see README / DESIGN for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_F32_PEAK_TFLOPS = 157.3  # dense fp32 matrix
+CHANNELS = [4, 16, 32, 64, 128, 256]
+
+
+def make_inputs(config, batch, u):
+    import synth_shapes as S
+    coords, offs, normals = S.config_batch(config, batch=batch, u=u, with_normals=True)
+    X0 = S.normals_plus_one(normals)
+    W = [S.he_weights(CHANNELS[l], CHANNELS[l + 1], 4000 + l) for l in range(5)]
+    return coords, offs, X0, W
+
+
+def cpu_baseline(coords, offs, X0, W, u, max_shapes, budget_s=24.0):
+    """The oracle, as it stands, on the first shapes of the same batch: encoder forward and
+    backward with the paper's algorithms in double precision.  Returns (TFLOP/s, cores, note)."""
+    from oracle import oracle as O
+    import synth_shapes as S
+
+    def run(ns):
+        c, o = coords[: offs[ns]], offs[: ns + 1]
+        lv = O.build_hierarchy(c, o, u, 6)           # construction is pre-processing: not timed
+        t0 = time.perf_counter()
+        X = [O.to_paper_X(X0[: offs[ns]])]
+        A, sw = [], []
+        flops = 0
+        for l in range(5):
+            Wp = O.to_paper_W(W[l])
+            Y = O.conv_fwd(lv[l], X[l], Wp)
+            A.append(np.maximum(Y, 0.0))
+            P, s = O.pool_max_fwd(lv[l], lv[l + 1], A[l])
+            X.append(P); sw.append(s)
+            flops += 3 * 2 * 27 * CHANNELS[l] * CHANNELS[l + 1] * lv[l].Ntot
+        g = O.to_paper_X(S.gaussian((lv[5].Ntot, CHANNELS[5]), 1.0, 4100))
+        for l in reversed(range(5)):
+            dA = O.pool_max_bwd(lv[l].Ntot, g, sw[l])
+            dY = np.where(A[l] > 0, dA, 0.0)
+            O.conv_bwd_weight(lv[l], X[l], dY)
+            g = O.conv_bwd_data(lv[l], dY, O.to_paper_W(W[l]), CHANNELS[l])
+        return time.perf_counter() - t0, flops
+
+    # whole passes over a growing prefix of the batch until about budget_s of CPU work is spent
+    ns, total_t, total_f, passes = 1, 0.0, 0.0, 0
+    dt, flops = run(ns)
+    if dt * max_shapes / ns < budget_s:
+        ns = max_shapes
+    else:
+        ns = max(1, min(max_shapes, int(ns * budget_s / max(dt, 1e-3))))
+    while total_t < budget_s / 2 and passes < 20:
+        dt, flops = run(ns)
+        total_t += dt; total_f += flops; passes += 1
+    return (total_f / total_t / 1e12, O.threads(),
+            f"first {ns} of {len(offs) - 1} shapes, {passes} fwd+bwd passes, {total_t:.1f} s")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--resolution", type=int, default=256, help="finest grid side (256 = the headline workload)")
+    ap.add_argument("--batch", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-all", action="store_true", help="time every kernel (adds event overhead)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_1803_11385_amd as hch
+    from paper_1803_11385_amd.pipeline import Encoder
+    import synth_shapes as S
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    u, b = args.resolution, args.batch
+    t0 = time.perf_counter()
+    coords, offs, X0, W = make_inputs(4, b, u)
+    t_gen = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    levels = hch.hch_build_levels(coords, offs, u, 6)
+    t_build = time.perf_counter() - t0
+    enc = Encoder(levels, CHANNELS)
+    enc.X[0].copy_(torch.from_numpy(X0))
+    for l in range(5):
+        enc.W[l].copy_(torch.from_numpy(W[l]))
+    enc.dX[5].copy_(torch.from_numpy(S.gaussian((enc.n[5], CHANNELS[5]), 1.0, 4100)))
+    torch.cuda.synchronize()
+
+    nk = hch.hch_kernel_count()
+    names = [hch.hch_kernel_name(i) for i in range(nk)]
+
+    # warm-up; the first warm-up step times every kernel to find the dominant one
+    hch.hch_profile_reset()
+    hch.hch_profile_enable((1 << nk) - 1)
+    enc.step()
+    torch.cuda.synchronize()
+    per_kernel = {names[i]: hch.hch_profile_read(i) for i in range(nk)}
+    dominant = max(range(nk), key=lambda i: per_kernel[names[i]]["ms"])
+    hch.hch_profile_enable((1 << nk) - 1 if args.profile_all else (1 << dominant))
+    for _ in range(max(0, args.warmup - 1)):
+        enc.step()
+    torch.cuda.synchronize()
+    hch.hch_profile_reset()
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        enc.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    hch.hch_profile_enable(0)
+
+    ms_per_step = dt / args.steps * 1e3
+    flops = enc.flops_per_step()
+    value = flops / (ms_per_step * 1e-3) / 1e12
+
+    st = hch.hch_profile_read(dominant)
+    avg_ms = st["ms"] / max(1, st["launches"])
+    ai = st["flops"] / max(1.0, st["bytes"])
+    if st["flops"] > 0 and ai >= MFMA_F32_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
+        bound, achieved, peak, unit = "mfma", st["flops"] / (st["ms"] * 1e-3) / 1e12, MFMA_F32_PEAK_TFLOPS, "TFLOP/s"
+    else:
+        bound, achieved, peak, unit = "hbm", st["bytes"] / (st["ms"] * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(names[dominant], {}).get(f"{u}^3x{b}")
+        except Exception:
+            traffic = None
+    roofline = {"kernel": names[dominant], "bound": bound, "achieved": round(achieved, 3), "peak": peak,
+                "unit": unit, "frac": round(achieved / peak, 4), "traffic": traffic,
+                "launches_per_step": st["launches"] / args.steps, "avg_launch_ms": round(avg_ms, 5),
+                "algorithmic_bytes_per_launch": st["bytes"] / max(1, st["launches"]),
+                "flops_per_launch": st["flops"] / max(1, st["launches"])}
+
+    out = {
+        "metric": "sparse conv fwd+bwd TFLOP/s and gather/scatter HBM GB/s, 256^3 grid, batch 8",
+        "value": round(value, 4), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"5-level encoder fwd+bwd, {u}^3 grid, batch {b}, random-primitive surfaces, "
+                               f"channels 4-16-32-64-128-256, N per level = {enc.n}",
+                   "flop_count": "paper-method 3 * 2*27*c_in*c_out*N_l per level",
+                   "gflop_per_step": round(flops / 1e9, 3), "psh_build_s": round(t_build, 2),
+                   "shape_gen_s": round(t_gen, 2)},
+        "roofline": roofline,
+        "kernels_ms_first_step": {k: round(v["ms"], 4) for k, v in per_kernel.items() if v["launches"]},
+    }
+    if not args.no_cpu_baseline:
+        v, cores, note = cpu_baseline(coords, offs, X0, W, u, b)
+        out["cpu_baseline"] = {"value": round(v, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+                               "sample": note}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

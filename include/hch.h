@@ -63,6 +63,7 @@ typedef struct {
     int64_t n_total;         /* N*[b]: occupied voxels of the whole batch                       */
     int64_t m_total;         /* M*[b]: hash slots of the whole batch                            */
     int64_t r_total;         /* R*[b]: offset-table cells of the whole batch                    */
+    int64_t nbr_valid;       /* occupied entries of nbr27 (centre included); 0 for host-only    */
     /* HOST arrays */
     const int32_t *mbar;     /* [b]   hash table side per model (Section 5.2: m^3 > n)          */
     const int32_t *rbar;     /* [b]   offset table side per model                               */
@@ -222,6 +223,29 @@ hch_status hch_pool_bwd(const hch_levels *levels, int32_t level_in, const float 
  * operations"): y = max(x, 0);  backward dx = (y > 0) ? dy : 0.  In-place use is allowed. */
 hch_status hch_relu_fwd(const float *x, float *y, int64_t n, void *stream);
 hch_status hch_relu_bwd(const float *y, const float *dy, float *dx, int64_t n, void *stream);
+
+/*
+ * Optional per-kernel timing, for benchmarks.  Each kernel of the library has an id in
+ * [0, hch_kernel_count()); hch_kernel_name gives the name of its __global__ function.
+ * hch_profile_enable(mask): launches of kernel i are bracketed by two HIP events on their
+ * stream while bit i of mask is set (0 = off, the default).  hch_profile_read blocks until the
+ * bracketed launches so far have finished and returns, for one kernel, the number of timed
+ * launches, the sum of their durations, and the sums of their ALGORITHMIC bytes and flops
+ * (every operand moved once, as counted from the launch's shapes; not a hardware counter).
+ * hch_profile_reset clears the sums.
+ */
+typedef struct {
+    int64_t launches;
+    double ms;
+    double bytes;
+    double flops;
+} hch_kernel_stats;
+
+int32_t hch_kernel_count(void);
+const char *hch_kernel_name(int32_t kernel_id);
+hch_status hch_profile_enable(uint64_t kernel_mask);
+hch_status hch_profile_read(int32_t kernel_id, hch_kernel_stats *out);
+hch_status hch_profile_reset(void);
 
 #ifdef __cplusplus
 }

@@ -14,6 +14,8 @@ __all__ = [
     "hch_build_levels", "hch_build_tables_host", "hch_build_neighbours", "hch_hash2col",
     "hch_col2hash", "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data",
     "hch_conv_bwd_weight", "hch_pool_fwd", "hch_pool_bwd", "hch_relu_fwd", "hch_relu_bwd",
+    "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
+    "hch_profile_reset",
 ]
 
 HCH_F32, HCH_BF16 = 0, 1
@@ -28,6 +30,8 @@ exported_symbols = [
     "hch_num_levels", "hch_level_info", "hch_build_neighbours", "hch_hash2col", "hch_col2hash",
     "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data", "hch_conv_bwd_weight",
     "hch_pool_fwd", "hch_pool_bwd", "hch_relu_fwd", "hch_relu_bwd",
+    "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
+    "hch_profile_reset",
 ]
 
 
@@ -39,13 +43,18 @@ class HchError(RuntimeError):
 
 class _Desc(C.Structure):
     _fields_ = [("ubar", C.c_int32), ("batch", C.c_int32), ("n_total", C.c_int64),
-                ("m_total", C.c_int64), ("r_total", C.c_int64),
+                ("m_total", C.c_int64), ("r_total", C.c_int64), ("nbr_valid", C.c_int64),
                 ("mbar", C.c_void_p), ("rbar", C.c_void_p), ("attempts", C.c_void_p),
                 ("M", C.c_void_p), ("R", C.c_void_p), ("N", C.c_void_p),
                 ("coords_host", C.c_void_p), ("H_host", C.c_void_p), ("T_host", C.c_void_p),
                 ("Phi_host", C.c_void_p), ("V_host", C.c_void_p),
                 ("H", C.c_void_p), ("T", C.c_void_p), ("Phi", C.c_void_p), ("V", C.c_void_p),
                 ("coords", C.c_void_p), ("nbr27", C.c_void_p), ("child8", C.c_void_p)]
+
+
+class _KernelStats(C.Structure):
+    _fields_ = [("launches", C.c_int64), ("ms", C.c_double), ("bytes", C.c_double),
+                ("flops", C.c_double)]
 
 
 _lib = None
@@ -84,6 +93,11 @@ def load_library():
     L.hch_pool_bwd.argtypes = [vp, i32, vp, vp, vp, i32, vp]
     L.hch_relu_fwd.argtypes = [vp, vp, i64, vp]
     L.hch_relu_bwd.argtypes = [vp, vp, vp, i64, vp]
+    L.hch_kernel_count.restype = i32
+    L.hch_kernel_name.argtypes = [i32]
+    L.hch_kernel_name.restype = C.c_char_p
+    L.hch_profile_enable.argtypes = [C.c_uint64]
+    L.hch_profile_read.argtypes = [i32, C.POINTER(_KernelStats)]
     _lib = L
     return L
 
@@ -109,6 +123,7 @@ class LevelInfo:
         b = d.batch
         self.ubar, self.batch = d.ubar, b
         self.n_total, self.m_total, self.r_total = d.n_total, d.m_total, d.r_total
+        self.nbr_valid = d.nbr_valid
         self.mbar = _host_array(d.mbar, (b,), np.int32)
         self.rbar = _host_array(d.rbar, (b,), np.int32)
         self.attempts = _host_array(d.attempts, (b,), np.int32)
@@ -323,6 +338,28 @@ def hch_relu_fwd(x, y, n, stream=None):
 
 def hch_relu_bwd(y, dy, dx, n, stream=None):
     _check(load_library().hch_relu_bwd(_dp(y), _dp(dy), _dp(dx), n, _stream(stream)))
+
+
+def hch_kernel_count():
+    return int(load_library().hch_kernel_count())
+
+
+def hch_kernel_name(kernel_id):
+    return load_library().hch_kernel_name(kernel_id).decode()
+
+
+def hch_profile_enable(mask):
+    _check(load_library().hch_profile_enable(int(mask)))
+
+
+def hch_profile_read(kernel_id):
+    st = _KernelStats()
+    _check(load_library().hch_profile_read(kernel_id, C.byref(st)))
+    return dict(launches=st.launches, ms=st.ms, bytes=st.bytes, flops=st.flops)
+
+
+def hch_profile_reset():
+    _check(load_library().hch_profile_reset())
 
 
 load_library()

@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "kernels.hip.hpp"
+#include "profile.hpp"
 #include "psh_build.hpp"
 
 namespace {
@@ -44,6 +45,7 @@ struct Level {
     int32_t ubar = 0, b = 0;
     int64_t n_total = 0, m_total = 0, r_total = 0;
     int32_t max_n = 0;                         // largest model of the level
+    int64_t nbr_valid = 0;                     // occupied entries of nbr27 (incl. the centre)
     std::vector<int32_t> mbar, rbar, attempts, coords;
     std::vector<int64_t> M, R, N;
     std::vector<int32_t> H, V;                 // host copies of the super tables
@@ -119,8 +121,14 @@ static hch_status launch_field_index(const Level &Li, const Level &Lo, int F, in
     const int64_t items = (int64_t)Lo.max_n * F * F * F;
     if (items == 0) return HCH_OK;
     dim3 grid(blocks_for(items), (unsigned)Lo.b);
-    hipLaunchKernelGGL(hch::field_index_kernel, grid, dim3(256), 0, s, Li.view(), Lo.dcoords,
-                       Lo.dN(), F, Ss, Sp, out);
+    {
+        // per output voxel: its position in, F^3 indices out; the input level's tables once
+        const double bytes = (double)Lo.n_total * (12.0 + 4.0 * F * F * F) +
+                             (double)Li.m_total * 10.0 + (double)Li.r_total * 3.0;
+        hch::LaunchTimer lt(hch::K_FIELD_INDEX, s, bytes, 0.0);
+        hipLaunchKernelGGL(hch::field_index_kernel, grid, dim3(256), 0, s, Li.view(), Lo.dcoords,
+                           Lo.dN(), F, Ss, Sp, out);
+    }
     HCH_LAUNCH_CHECK("field_index_kernel");
     return HCH_OK;
 }
@@ -292,6 +300,16 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
             hipError_t e = hipStreamSynchronize(s);
             if (e != hipSuccess) st = fail(HCH_EHIP, std::string("hipStreamSynchronize: ") + hipGetErrorString(e));
         }
+        // occupied-neighbour count of every level (used only for reporting algorithmic traffic)
+        for (int l = 0; l < n_levels && st == HCH_OK && with_device; ++l) {
+            Level &L = hl->lv[l];
+            std::vector<int32_t> nb((size_t)L.n_total * 27);
+            hipError_t e = hipMemcpy(nb.data(), L.dnbr, nb.size() * 4, hipMemcpyDeviceToHost);
+            if (e != hipSuccess) { st = fail(HCH_EHIP, std::string("hipMemcpy(nbr27): ") + hipGetErrorString(e)); break; }
+            int64_t cnt = 0;
+            for (int32_t x : nb) cnt += (x >= 0);
+            L.nbr_valid = cnt;
+        }
     } catch (const std::bad_alloc &) {
         st = fail(HCH_ENOMEM, "hch_build_levels: out of host memory");
     }
@@ -322,6 +340,7 @@ extern "C" hch_status hch_level_info(const hch_levels *levels, int32_t level, hc
     const Level &L = levels->lv[level];
     out->ubar = L.ubar; out->batch = L.b;
     out->n_total = L.n_total; out->m_total = L.m_total; out->r_total = L.r_total;
+    out->nbr_valid = L.nbr_valid;
     out->mbar = L.mbar.data(); out->rbar = L.rbar.data(); out->attempts = L.attempts.data();
     out->M = L.M.data(); out->R = L.R.data(); out->N = L.N.data();
     out->coords_host = L.coords.data();
@@ -353,15 +372,20 @@ static hch_status do_hash2col(const Level &L, hch_dtype dtype, const void *X, in
     if (rows == 0) return HCH_OK;
     const int es = elem_size(dtype);
     const int row_bytes = c_in * es;
+    // per voxel: 27 indices and its own feature row in (neighbour re-reads are cache hits),
+    // 27 rows out (zeros included: the GEMM operand needs them)
+    const double bytes = (double)rows * (108.0 + 28.0 * row_bytes);
     if (row_bytes % 16 == 0 && aligned16(X) && aligned16(col)) {
         const int cv = row_bytes / 16;
         const int64_t items = rows * 27 * cv;
         if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hash2col: too many rows in one launch");
+        hch::LaunchTimer lt(hch::K_HASH2COL_VEC, s, bytes, 0.0);
         hipLaunchKernelGGL(hch::hash2col_vec_kernel, dim3(blocks_for(items)), dim3(256), 0, s,
                            (const uint4 *)X, L.dnbr, (uint4 *)col, row_begin, rows, cv);
     } else {
         const int64_t items = rows * 27 * c_in;
         if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hash2col: too many rows in one launch");
+        hch::LaunchTimer lt(hch::K_HASH2COL_ELEM, s, bytes, 0.0);
         if (dtype == HCH_F32)
             hipLaunchKernelGGL(hch::hash2col_elem_kernel<float>, dim3(blocks_for(items)), dim3(256), 0, s,
                                (const float *)X, L.dnbr, (float *)col, row_begin, rows, c_in);
@@ -389,6 +413,9 @@ extern "C" hch_status hch_hash2col(const hch_levels *levels, int32_t level, hch_
 
 static hch_status do_col2hash(const Level &L, const float *dcol, int c_in, float *dX, hipStream_t s)
 {
+    // per voxel: 27 indices in, one c_in row per occupied neighbour in, one row out
+    const double bytes = (double)L.n_total * (108.0 + 4.0 * c_in) + (double)L.nbr_valid * 4.0 * c_in;
+    hch::LaunchTimer lt(hch::K_COL2HASH, s, bytes, (double)L.nbr_valid * c_in);
     if (c_in % 4 == 0 && aligned16(dcol) && aligned16(dX)) {
         const int64_t items = L.n_total * (c_in / 4);
         hipLaunchKernelGGL(hch::col2hash_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, s,
@@ -417,11 +444,14 @@ extern "C" hch_status hch_col2hash(const hch_levels *levels, int32_t level, cons
 // ---------------------------------------------------------------------------------------
 
 template <bool A_KC, bool B_KC>
-static hch_status launch_gemm(const float *A, const float *B, float *C, int M, int N, int K,
+static hch_status launch_gemm(int kernel_id, const float *A, const float *B, float *C, int M, int N, int K,
                               int64_t lda, int64_t ldb, int64_t ldc, int splits, int k_per_split,
                               int64_t c_split_stride, hipStream_t s)
 {
     if (M <= 0 || N <= 0) return HCH_OK;
+    // every operand once: A, B in, C out (split-K partials count as output)
+    const double bytes = 4.0 * ((double)M * K + (double)K * N + (double)M * N * splits);
+    hch::LaunchTimer lt(kernel_id, s, bytes, 2.0 * M * (double)N * K);
     const int vec_ok = (lda % 4 == 0) && (ldb % 4 == 0) && aligned16(A) && aligned16(B);
     const unsigned gx = (unsigned)((M + hch::GEMM_BM - 1) / hch::GEMM_BM);
     if (N <= 16) {
@@ -515,7 +545,7 @@ extern "C" hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_
         const int64_t rows = std::min<int64_t>(chunk, L->n_total - r0);
         st = do_hash2col(*L, dtype, X, c_in, r0, rows, workspace, s);
         if (st != HCH_OK) return st;
-        st = launch_gemm<true, false>((const float *)workspace, (const float *)W, Y + r0 * c_out,
+        st = launch_gemm<true, false>(hch::K_GEMM_FWD, (const float *)workspace, (const float *)W, Y + r0 * c_out,
                                       (int)rows, c_out, Kc, Kc, c_out, c_out, 1, Kc + hch::GEMM_BK, 0, s);
         if (st != HCH_OK) return st;
     }
@@ -536,7 +566,7 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
     const int Kc = 27 * c_in;
     float *dcol = (float *)workspace;
     // dcol[N x Kc] = dY[N x c_out] . W^T   (W is [Kc x c_out]: its rows are B's columns)
-    st = launch_gemm<true, true>((const float *)dY, (const float *)W, dcol, (int)L->n_total, Kc, c_out,
+    st = launch_gemm<true, true>(hch::K_GEMM_DGRAD, (const float *)dY, (const float *)W, dcol, (int)L->n_total, Kc, c_out,
                                  c_out, c_out, Kc, 1, c_out + hch::GEMM_BK, 0, s);
     if (st != HCH_OK) return st;
     return do_col2hash(*L, dcol, c_in, dX, s);
@@ -563,10 +593,11 @@ extern "C" hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t leve
     const int64_t wsize = (int64_t)Kc * c_out;
     // dW[Kc x c_out] = col^T[Kc x N] . dY[N x c_out], reduction over the voxels split in slices
     float *dst = (p.splits == 1) ? dW : part;
-    st = launch_gemm<false, false>(col, (const float *)dY, dst, Kc, c_out, (int)L->n_total, Kc, c_out,
+    st = launch_gemm<false, false>(hch::K_GEMM_WGRAD, col, (const float *)dY, dst, Kc, c_out, (int)L->n_total, Kc, c_out,
                                    c_out, p.splits, p.rows_per_split, wsize, s);
     if (st != HCH_OK) return st;
     if (p.splits > 1) {
+        hch::LaunchTimer lt(hch::K_SPLITK_REDUCE, s, 4.0 * wsize * (p.splits + 1.0), (double)wsize * p.splits);
         hipLaunchKernelGGL(hch::splitk_reduce_kernel, dim3((unsigned)((wsize + 63) / 64)), dim3(256), 0, s,
                            part, dW, wsize, p.splits, wsize);
         HCH_LAUNCH_CHECK("splitk_reduce_kernel");
@@ -588,8 +619,14 @@ extern "C" hch_status hch_pool_fwd(const hch_levels *levels, int32_t level_in, c
     if (!Lc.dchild) return fail(HCH_EINVAL, "hch_pool_fwd: levels were built without device tables");
     const int64_t items = Lc.n_total * c;
     if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hch_pool_fwd: too large");
-    hipLaunchKernelGGL(hch::pool_fwd_kernel, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
-                       X, Lc.dchild, Y, argmax, Lc.n_total, c);
+    {
+        // per coarse voxel: 8 child indices, its children's rows in; value and switch rows out
+        const Level &Lf = levels->lv[level_in];
+        const double bytes = (double)Lc.n_total * (32.0 + 8.0 * c) + (double)Lf.n_total * 4.0 * c;
+        hch::LaunchTimer lt(hch::K_POOL_FWD, (hipStream_t)stream, bytes, 0.0);
+        hipLaunchKernelGGL(hch::pool_fwd_kernel, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                           X, Lc.dchild, Y, argmax, Lc.n_total, c);
+    }
     HCH_LAUNCH_CHECK("pool_fwd_kernel");
     return HCH_OK;
 }
@@ -604,8 +641,13 @@ extern "C" hch_status hch_pool_bwd(const hch_levels *levels, int32_t level_in, c
     if (!Lc.dchild) return fail(HCH_EINVAL, "hch_pool_bwd: levels were built without device tables");
     const int64_t items = Lc.n_total * 8 * c;
     if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hch_pool_bwd: too large");
-    hipLaunchKernelGGL(hch::pool_bwd_kernel, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
-                       dY, argmax, Lc.dchild, dX, Lc.n_total, c);
+    {
+        const Level &Lf = levels->lv[level_in];
+        const double bytes = (double)Lc.n_total * (32.0 + 8.0 * c) + (double)Lf.n_total * 4.0 * c;
+        hch::LaunchTimer lt(hch::K_POOL_BWD, (hipStream_t)stream, bytes, 0.0);
+        hipLaunchKernelGGL(hch::pool_bwd_kernel, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                           dY, argmax, Lc.dchild, dX, Lc.n_total, c);
+    }
     HCH_LAUNCH_CHECK("pool_bwd_kernel");
     return HCH_OK;
 }
@@ -614,7 +656,10 @@ extern "C" hch_status hch_relu_fwd(const float *x, float *y, int64_t n, void *st
 {
     if (!x || !y || n < 0) return fail(HCH_EINVAL, "hch_relu_fwd: bad argument");
     if (n == 0) return HCH_OK;
-    hipLaunchKernelGGL(hch::relu_fwd_kernel, dim3(blocks_for(n)), dim3(256), 0, (hipStream_t)stream, x, y, n);
+    {
+        hch::LaunchTimer lt(hch::K_RELU_FWD, (hipStream_t)stream, 8.0 * n, 0.0);
+        hipLaunchKernelGGL(hch::relu_fwd_kernel, dim3(blocks_for(n)), dim3(256), 0, (hipStream_t)stream, x, y, n);
+    }
     HCH_LAUNCH_CHECK("relu_fwd_kernel");
     return HCH_OK;
 }
@@ -623,7 +668,40 @@ extern "C" hch_status hch_relu_bwd(const float *y, const float *dy, float *dx, i
 {
     if (!y || !dy || !dx || n < 0) return fail(HCH_EINVAL, "hch_relu_bwd: bad argument");
     if (n == 0) return HCH_OK;
-    hipLaunchKernelGGL(hch::relu_bwd_kernel, dim3(blocks_for(n)), dim3(256), 0, (hipStream_t)stream, y, dy, dx, n);
+    {
+        hch::LaunchTimer lt(hch::K_RELU_BWD, (hipStream_t)stream, 12.0 * n, 0.0);
+        hipLaunchKernelGGL(hch::relu_bwd_kernel, dim3(blocks_for(n)), dim3(256), 0, (hipStream_t)stream, y, dy, dx, n);
+    }
     HCH_LAUNCH_CHECK("relu_bwd_kernel");
+    return HCH_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// per-kernel timing
+// ---------------------------------------------------------------------------------------
+
+extern "C" int32_t hch_kernel_count(void) { return hch::K_COUNT; }
+
+extern "C" const char *hch_kernel_name(int32_t id) { return hch::kernel_name(id); }
+
+extern "C" hch_status hch_profile_enable(uint64_t kernel_mask)
+{
+    hch::Profiler::get().set_mask(kernel_mask);
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_profile_read(int32_t kernel_id, hch_kernel_stats *out)
+{
+    if (!out || kernel_id < 0 || kernel_id >= hch::K_COUNT) return fail(HCH_EINVAL, "hch_profile_read: bad argument");
+    hch::Profiler::get().collect();
+    const hch::KernelStats st = hch::Profiler::get().read(kernel_id);
+    out->launches = st.launches; out->ms = st.ms; out->bytes = st.bytes; out->flops = st.flops;
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_profile_reset(void)
+{
+    hch::Profiler::get().collect();
+    hch::Profiler::get().reset();
     return HCH_OK;
 }

@@ -1,0 +1,72 @@
+"""Sequencing of the library calls for a multi-level encoder (conv3x3x3 -> ReLU -> 2x2x2
+max-pool per level) forward and backward.  Only call order and buffer ownership live here;
+every arithmetic step is a call into libhch.so."""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+def _aligned_bytes(nbytes, device):
+    t = torch.empty(int(nbytes) + 256, dtype=torch.uint8, device=device)
+    off = (-t.data_ptr()) % 256
+    return t[off: off + int(nbytes)]
+
+
+class Encoder:
+    """channels = [c0, c1, ..., cL]: level l runs conv c_l -> c_{l+1}, ReLU, pool to level l+1.
+    `levels` must hold L+1 levels.  All buffers are allocated once here."""
+
+    def __init__(self, levels, channels, device="cuda"):
+        self.levels, self.channels = levels, list(channels)
+        self.L = len(channels) - 1
+        assert levels.n_levels >= self.L + 1
+        self.n = [levels.n(l) for l in range(self.L + 1)]
+        f32 = dict(dtype=torch.float32, device=device)
+        ch = self.channels
+        self.X = [torch.empty((self.n[l], ch[l]), **f32) for l in range(self.L + 1)]    # level inputs
+        self.Y = [torch.empty((self.n[l], ch[l + 1]), **f32) for l in range(self.L)]    # conv outputs
+        self.A = [torch.empty((self.n[l], ch[l + 1]), **f32) for l in range(self.L)]    # after ReLU
+        self.sw = [torch.empty((self.n[l + 1], ch[l + 1]), dtype=torch.int32, device=device)
+                   for l in range(self.L)]
+        self.W = [torch.empty((27, ch[l], ch[l + 1]), **f32) for l in range(self.L)]
+        self.dW = [torch.empty((27, ch[l], ch[l + 1]), **f32) for l in range(self.L)]
+        self.dX = [torch.empty((self.n[l], ch[l]), **f32) for l in range(self.L + 1)]   # dX[L] = upstream
+        self.dA = [torch.empty((self.n[l], ch[l + 1]), **f32) for l in range(self.L)]
+        self.dY = [torch.empty((self.n[l], ch[l + 1]), **f32) for l in range(self.L)]
+        need = 256
+        for l in range(self.L):
+            for kind in (B.HCH_WS_FWD, B.HCH_WS_BWD_DATA, B.HCH_WS_BWD_WEIGHT):
+                need = max(need, B.hch_conv_workspace_bytes(levels, l, ch[l], ch[l + 1], B.HCH_F32, kind))
+        self.ws = _aligned_bytes(need, device)
+
+    def flops_per_step(self):
+        """paper-method count: forward, data-gradient and weight-gradient products, each
+        2 * 27 * c_in * c_out * N_l."""
+        return sum(3 * 2 * 27 * self.channels[l] * self.channels[l + 1] * self.n[l] for l in range(self.L))
+
+    def build_indices(self):
+        for l in range(self.L + 1):
+            B.hch_build_neighbours(self.levels, l)
+
+    def forward(self):
+        ch = self.channels
+        for l in range(self.L):
+            B.hch_conv_fwd(self.levels, l, B.HCH_F32, self.X[l], self.W[l], self.Y[l], ch[l], ch[l + 1], self.ws)
+            B.hch_relu_fwd(self.Y[l], self.A[l], self.A[l].numel())
+            B.hch_pool_fwd(self.levels, l, self.A[l], self.X[l + 1], self.sw[l], ch[l + 1])
+
+    def backward(self):
+        ch = self.channels
+        for l in reversed(range(self.L)):
+            B.hch_pool_bwd(self.levels, l, self.dX[l + 1], self.sw[l], self.dA[l], ch[l + 1])
+            B.hch_relu_bwd(self.A[l], self.dA[l], self.dY[l], self.dY[l].numel())
+            B.hch_conv_bwd_weight(self.levels, l, B.HCH_F32, self.X[l], self.dY[l], self.dW[l], ch[l], ch[l + 1], self.ws)
+            B.hch_conv_bwd_data(self.levels, l, B.HCH_F32, self.dY[l], self.W[l], self.dX[l], ch[l], ch[l + 1], self.ws)
+
+    def step(self):
+        """One pass of the whole hot path: index lists by hash lookup, forward, backward."""
+        self.build_indices()
+        self.forward()
+        self.backward()
