@@ -86,6 +86,8 @@ def main():
     ap.add_argument("--batch", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-all", action="store_true", help="time every kernel (adds event overhead)")
+    ap.add_argument("--algo", choices=["columns", "fused"], default="columns",
+                    help="columns: hash2col -> GEMM -> col2hash through memory; fused: gathered GEMM operand")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -105,7 +107,8 @@ def main():
     t0 = time.perf_counter()
     levels = hch.hch_build_levels(coords, offs, u, 6)
     t_build = time.perf_counter() - t0
-    enc = Encoder(levels, CHANNELS)
+    algo = hch.HCH_ALGO_FUSED if args.algo == "fused" else hch.HCH_ALGO_COLUMNS
+    enc = Encoder(levels, CHANNELS, algo)
     enc.X[0].copy_(torch.from_numpy(X0))
     for l in range(5):
         enc.W[l].copy_(torch.from_numpy(W[l]))
@@ -167,7 +170,7 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"5-level encoder fwd+bwd, {u}^3 grid, batch {b}, random-primitive surfaces, "
                                f"channels 4-16-32-64-128-256, N per level = {enc.n}",
-                   "flop_count": "paper-method 3 * 2*27*c_in*c_out*N_l per level",
+                   "algo": args.algo, "flop_count": "paper-method 3 * 2*27*c_in*c_out*N_l per level",
                    "gflop_per_step": round(flops / 1e9, 3), "psh_build_s": round(t_build, 2),
                    "shape_gen_s": round(t_gen, 2)},
         "roofline": roofline,

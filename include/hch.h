@@ -159,18 +159,30 @@ hch_status hch_hash2col(const hch_levels *levels, int32_t level, hch_dtype dtype
 hch_status hch_col2hash(const hch_levels *levels, int32_t level, const float *dcol,
                         int32_t c_in, float *dX, void *stream);
 
+/* How a convolution call computes its products.  Both give the same results up to the order
+ * of fp32 additions.
+ *   HCH_ALGO_COLUMNS  the paper's three steps: hash2col writes the column matrix to the
+ *                     workspace, a dense GEMM consumes it, col2hash folds gradients back.
+ *   HCH_ALGO_FUSED    the same products with the column matrix gathered through the index rows
+ *                     straight into the GEMM's operand tile, so it never goes to memory.  */
+typedef enum { HCH_ALGO_COLUMNS = 0, HCH_ALGO_FUSED = 1 } hch_algo;
+
 typedef enum {
-    HCH_WS_FWD = 0,         /* hch_conv_fwd: whole column matrix                               */
+    HCH_WS_FWD = 0,         /* hch_conv_fwd: everything in one pass                            */
     HCH_WS_BWD_DATA = 1,    /* hch_conv_bwd_data: required size                                */
     HCH_WS_BWD_WEIGHT = 2,  /* hch_conv_bwd_weight: required size                              */
     HCH_WS_MIN = 3          /* smallest workspace hch_conv_fwd accepts                         */
 } hch_ws_kind;
 
-/* Bytes of DEVICE workspace for a 3x3x3 stride-1 convolution on `level`.  Returns 0 on bad
- * arguments.  hch_conv_fwd accepts any size >= the HCH_WS_MIN value and walks the voxels in
- * chunks when given less than HCH_WS_FWD; the two backward calls need their full size. */
+/* Bytes of DEVICE workspace for a 3x3x3 stride-1 convolution on `level` (at least 256).
+ * Returns 0 on bad arguments.  With HCH_ALGO_COLUMNS the workspace holds the column matrix
+ * (N_l x 27*c_in elements) and, for small levels, partial sums of a split reduction;
+ * hch_conv_fwd accepts any size >= the HCH_WS_MIN value and walks the voxels in chunks when
+ * given less than HCH_WS_FWD; the two backward calls need their full size.  With
+ * HCH_ALGO_FUSED only the partial sums (and, for bwd_data, one rearranged copy of the
+ * weights) live there. */
 size_t hch_conv_workspace_bytes(const hch_levels *levels, int32_t level, int32_t c_in,
-                                int32_t c_out, hch_dtype dtype, hch_ws_kind kind);
+                                int32_t c_out, hch_dtype dtype, hch_ws_kind kind, hch_algo algo);
 
 /*
  * Convolution forward (Eq.2 = Eq.3):  Y = hash2col(X) . W
@@ -179,7 +191,7 @@ size_t hch_conv_workspace_bytes(const hch_levels *levels, int32_t level, int32_t
  */
 hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_dtype dtype,
                         const void *X, const void *W, float *Y, int32_t c_in, int32_t c_out,
-                        void *workspace, size_t ws_bytes, void *stream);
+                        void *workspace, size_t ws_bytes, hch_algo algo, void *stream);
 
 /*
  * Back-propagation to the input (Eq.8 followed by col2hash, Algorithm 2):
@@ -189,7 +201,8 @@ hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_dtype dtype
  */
 hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level, hch_dtype dtype,
                              const void *dY, const void *W, float *dX, int32_t c_in,
-                             int32_t c_out, void *workspace, size_t ws_bytes, void *stream);
+                             int32_t c_out, void *workspace, size_t ws_bytes, hch_algo algo,
+                             void *stream);
 
 /*
  * Weight gradient (Eq.7):  dW = hash2col(X)^T . dY
@@ -199,7 +212,8 @@ hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level, hch_dtype 
  */
 hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t level, hch_dtype dtype,
                                const void *X, const void *dY, float *dW, int32_t c_in,
-                               int32_t c_out, void *workspace, size_t ws_bytes, void *stream);
+                               int32_t c_out, void *workspace, size_t ws_bytes, hch_algo algo,
+                               void *stream);
 
 /*
  * 2x2x2 stride-2 max-pooling from level_in (fine) to level_in + 1 (coarse) (Section 4,

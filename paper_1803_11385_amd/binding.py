@@ -10,6 +10,7 @@ import numpy as np
 __all__ = [
     "HchError", "Levels", "LevelInfo", "HCH_F32", "HCH_BF16",
     "HCH_WS_FWD", "HCH_WS_BWD_DATA", "HCH_WS_BWD_WEIGHT", "HCH_WS_MIN",
+    "HCH_ALGO_COLUMNS", "HCH_ALGO_FUSED",
     "library_path", "load_library", "exported_symbols",
     "hch_build_levels", "hch_build_tables_host", "hch_build_neighbours", "hch_hash2col",
     "hch_col2hash", "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data",
@@ -20,6 +21,7 @@ __all__ = [
 
 HCH_F32, HCH_BF16 = 0, 1
 HCH_WS_FWD, HCH_WS_BWD_DATA, HCH_WS_BWD_WEIGHT, HCH_WS_MIN = 0, 1, 2, 3
+HCH_ALGO_COLUMNS, HCH_ALGO_FUSED = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIBPATH = os.path.join(_HERE, "libhch.so")
@@ -85,10 +87,10 @@ def load_library():
     L.hch_build_neighbours.argtypes = [vp, i32, vp]
     L.hch_hash2col.argtypes = [vp, i32, C.c_int, vp, i32, i64, i64, vp, vp]
     L.hch_col2hash.argtypes = [vp, i32, vp, i32, vp, vp]
-    L.hch_conv_workspace_bytes.argtypes = [vp, i32, i32, i32, C.c_int, C.c_int]
+    L.hch_conv_workspace_bytes.argtypes = [vp, i32, i32, i32, C.c_int, C.c_int, C.c_int]
     L.hch_conv_workspace_bytes.restype = sz
     for name in ("hch_conv_fwd", "hch_conv_bwd_data", "hch_conv_bwd_weight"):
-        getattr(L, name).argtypes = [vp, i32, C.c_int, vp, vp, vp, i32, i32, vp, sz, vp]
+        getattr(L, name).argtypes = [vp, i32, C.c_int, vp, vp, vp, i32, i32, vp, sz, C.c_int, vp]
     L.hch_pool_fwd.argtypes = [vp, i32, vp, vp, vp, i32, vp]
     L.hch_pool_bwd.argtypes = [vp, i32, vp, vp, vp, i32, vp]
     L.hch_relu_fwd.argtypes = [vp, vp, i64, vp]
@@ -296,29 +298,32 @@ def hch_col2hash(levels, level, dcol, c_in, dX, stream=None):
                                        _stream(stream)))
 
 
-def hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, kind):
+def hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, kind, algo=HCH_ALGO_COLUMNS):
     return int(load_library().hch_conv_workspace_bytes(levels.handle, level, c_in, c_out, dtype,
-                                                       kind))
+                                                       kind, algo))
 
 
-def hch_conv_fwd(levels, level, dtype, X, W, Y, c_in, c_out, workspace, stream=None):
+def hch_conv_fwd(levels, level, dtype, X, W, Y, c_in, c_out, workspace,
+                 algo=HCH_ALGO_COLUMNS, stream=None):
     _check(load_library().hch_conv_fwd(levels.handle, level, dtype, _dp(X), _dp(W), _dp(Y), c_in,
                                        c_out, _dp(workspace),
-                                       workspace.numel() * workspace.element_size(),
+                                       workspace.numel() * workspace.element_size(), algo,
                                        _stream(stream)))
 
 
-def hch_conv_bwd_data(levels, level, dtype, dY, W, dX, c_in, c_out, workspace, stream=None):
+def hch_conv_bwd_data(levels, level, dtype, dY, W, dX, c_in, c_out, workspace,
+                      algo=HCH_ALGO_COLUMNS, stream=None):
     _check(load_library().hch_conv_bwd_data(levels.handle, level, dtype, _dp(dY), _dp(W), _dp(dX),
                                             c_in, c_out, _dp(workspace),
-                                            workspace.numel() * workspace.element_size(),
+                                            workspace.numel() * workspace.element_size(), algo,
                                             _stream(stream)))
 
 
-def hch_conv_bwd_weight(levels, level, dtype, X, dY, dW, c_in, c_out, workspace, stream=None):
+def hch_conv_bwd_weight(levels, level, dtype, X, dY, dW, c_in, c_out, workspace,
+                        algo=HCH_ALGO_COLUMNS, stream=None):
     _check(load_library().hch_conv_bwd_weight(levels.handle, level, dtype, _dp(X), _dp(dY),
                                               _dp(dW), c_in, c_out, _dp(workspace),
-                                              workspace.numel() * workspace.element_size(),
+                                              workspace.numel() * workspace.element_size(), algo,
                                               _stream(stream)))
 
 

@@ -55,12 +55,13 @@ struct Level {
     int32_t *dH = nullptr, *dV = nullptr, *dcoords = nullptr, *dnbr = nullptr, *dchild = nullptr;
     uint16_t *dT = nullptr;
     uint8_t *dPhi = nullptr;
+    uint32_t *dslot3 = nullptr, *dphi4 = nullptr;   // packed copies of H*,T* and Phi* for the lookups
     int32_t *dmeta = nullptr;                  // mbar[b] rbar[b] M[b+1] R[b+1] N[b+1] as int32
 
     hch::PshView view() const
     {
         hch::PshView v;
-        v.H = dH; v.T = dT; v.Phi = dPhi;
+        v.slot3 = dslot3; v.phi4 = dphi4;
         v.mbar = dmeta; v.rbar = dmeta + b; v.M = dmeta + 2 * b; v.R = dmeta + 3 * b + 1;
         v.N = dmeta + 4 * b + 2; v.ubar = ubar;
         return v;
@@ -70,10 +71,10 @@ struct Level {
 
 void free_level(Level &L)
 {
-    void *ptrs[] = {L.dH, L.dV, L.dcoords, L.dnbr, L.dchild, L.dT, L.dPhi, L.dmeta};
+    void *ptrs[] = {L.dH, L.dV, L.dcoords, L.dnbr, L.dchild, L.dT, L.dPhi, L.dmeta, L.dslot3, L.dphi4};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     L.dH = L.dV = L.dcoords = L.dnbr = L.dchild = L.dmeta = nullptr;
-    L.dT = nullptr; L.dPhi = nullptr;
+    L.dT = nullptr; L.dPhi = nullptr; L.dslot3 = L.dphi4 = nullptr;
 }
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -115,21 +116,31 @@ static hch_status upload(void **dst, const void *src, size_t bytes, hipStream_t 
     return HCH_OK;
 }
 
-static hch_status launch_field_index(const Level &Li, const Level &Lo, int F, int Ss, int Sp,
-                                     int32_t *out, hipStream_t s)
+// grid.x tiles of 256 voxels over the largest model, grid.y = model
+static hch_status launch_neighbours(const Level &L, hipStream_t s)
 {
-    const int64_t items = (int64_t)Lo.max_n * F * F * F;
-    if (items == 0) return HCH_OK;
-    dim3 grid(blocks_for(items), (unsigned)Lo.b);
+    if (L.max_n == 0) return HCH_OK;
+    dim3 grid(blocks_for(L.max_n), (unsigned)L.b);
     {
-        // per output voxel: its position in, F^3 indices out; the input level's tables once
-        const double bytes = (double)Lo.n_total * (12.0 + 4.0 * F * F * F) +
-                             (double)Li.m_total * 10.0 + (double)Li.r_total * 3.0;
-        hch::LaunchTimer lt(hch::K_FIELD_INDEX, s, bytes, 0.0);
-        hipLaunchKernelGGL(hch::field_index_kernel, grid, dim3(256), 0, s, Li.view(), Lo.dcoords,
-                           Lo.dN(), F, Ss, Sp, out);
+        // per voxel: its position in, 27 indices out; the level's tables once
+        const double bytes = (double)L.n_total * (12.0 + 108.0) + (double)L.m_total * 10.0 + (double)L.r_total * 3.0;
+        hch::LaunchTimer lt(hch::K_NEIGHBOUR, s, bytes, 0.0);
+        hipLaunchKernelGGL(hch::neighbour_kernel, grid, dim3(256), 0, s, L.view(), L.dcoords, L.dnbr);
     }
-    HCH_LAUNCH_CHECK("field_index_kernel");
+    HCH_LAUNCH_CHECK("neighbour_kernel");
+    return HCH_OK;
+}
+
+static hch_status launch_children(const Level &Lf, const Level &Lc, hipStream_t s)
+{
+    if (Lc.max_n == 0) return HCH_OK;
+    dim3 grid(blocks_for(Lc.max_n), (unsigned)Lc.b);
+    {
+        const double bytes = (double)Lc.n_total * (12.0 + 32.0) + (double)Lf.m_total * 10.0 + (double)Lf.r_total * 3.0;
+        hch::LaunchTimer lt(hch::K_CHILD, s, bytes, 0.0);
+        hipLaunchKernelGGL(hch::child_kernel, grid, dim3(256), 0, s, Lf.view(), Lc.dcoords, Lc.dN(), Lc.dchild);
+    }
+    HCH_LAUNCH_CHECK("child_kernel");
     return HCH_OK;
 }
 
@@ -140,9 +151,9 @@ extern "C" hch_status hch_build_neighbours(hch_levels *levels, int32_t level, vo
     hipStream_t s = (hipStream_t)stream;
     Level &L = levels->lv[level];
     if (!L.dnbr) return fail(HCH_EINVAL, "hch_build_neighbours: levels were built without device tables");
-    hch_status st = launch_field_index(L, L, 3, 1, 0, L.dnbr, s);
+    hch_status st = launch_neighbours(L, s);
     if (st != HCH_OK) return st;
-    if (level > 0) st = launch_field_index(levels->lv[level - 1], L, 2, 2, 0, L.dchild, s);
+    if (level > 0) st = launch_children(levels->lv[level - 1], L, s);
     return st;
 }
 
@@ -285,13 +296,23 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
             if ((st = upload((void **)&L.dPhi, L.Phi.data(), L.Phi.size(), s)) != HCH_OK) break;
             if ((st = upload((void **)&L.dcoords, L.coords.data(), L.coords.size() * 4, s)) != HCH_OK) break;
             if ((st = upload((void **)&L.dmeta, meta.data(), meta.size() * 4, s)) != HCH_OK) break;
+            std::vector<uint32_t> slot3((size_t)L.m_total * 3), phi4((size_t)L.r_total);
+            for (int64_t q = 0; q < L.m_total; ++q) {
+                slot3[3 * q + 0] = (uint32_t)L.H[q];
+                slot3[3 * q + 1] = (uint32_t)L.T[3 * q] | ((uint32_t)L.T[3 * q + 1] << 16);
+                slot3[3 * q + 2] = (uint32_t)L.T[3 * q + 2];
+            }
+            for (int64_t q = 0; q < L.r_total; ++q)
+                phi4[q] = (uint32_t)L.Phi[3 * q] | ((uint32_t)L.Phi[3 * q + 1] << 8) | ((uint32_t)L.Phi[3 * q + 2] << 16);
+            if ((st = upload((void **)&L.dslot3, slot3.data(), slot3.size() * 4, s)) != HCH_OK) break;
+            if ((st = upload((void **)&L.dphi4, phi4.data(), phi4.size() * 4, s)) != HCH_OK) break;
             if (hipMalloc((void **)&L.dnbr, (size_t)L.n_total * 27 * 4) != hipSuccess) {
                 L.dnbr = nullptr; st = fail(HCH_ENOMEM, "hipMalloc(nbr27) failed"); break;
             }
             if (l > 0 && hipMalloc((void **)&L.dchild, (size_t)L.n_total * 8 * 4) != hipSuccess) {
                 L.dchild = nullptr; st = fail(HCH_ENOMEM, "hipMalloc(child8) failed"); break;
             }
-            // `meta` dies at the end of this iteration: finish the copies first
+            // the staging vectors die at the end of this iteration: finish the copies first
             hipError_t e = hipStreamSynchronize(s);
             if (e != hipSuccess) { st = fail(HCH_EHIP, std::string("hipStreamSynchronize: ") + hipGetErrorString(e)); break; }
         }
@@ -366,6 +387,15 @@ static hch_status get_level(const hch_levels *levels, int32_t level, const Level
 
 static inline int elem_size(hch_dtype d) { return d == HCH_BF16 ? 2 : 4; }
 
+// voxels per workgroup for the gather / scatter kernels: large tiles when there are many voxels,
+// smaller ones when the level is small so that the chip still gets a few thousand workgroups
+static int tile_voxels(int64_t n, int lo, int hi)
+{
+    int64_t tv = n / 2048;
+    tv = std::max<int64_t>(lo, std::min<int64_t>(hi, tv));
+    return (int)tv;
+}
+
 static hch_status do_hash2col(const Level &L, hch_dtype dtype, const void *X, int c_in,
                               int64_t row_begin, int64_t rows, void *col, hipStream_t s)
 {
@@ -375,23 +405,21 @@ static hch_status do_hash2col(const Level &L, hch_dtype dtype, const void *X, in
     // per voxel: 27 indices and its own feature row in (neighbour re-reads are cache hits),
     // 27 rows out (zeros included: the GEMM operand needs them)
     const double bytes = (double)rows * (108.0 + 28.0 * row_bytes);
+    const int tv = tile_voxels(rows, 8, 256);
+    const unsigned n_tiles = (unsigned)((rows + tv - 1) / tv);
+    const unsigned grid = (n_tiles + hch::NUM_XCD - 1) / hch::NUM_XCD * hch::NUM_XCD;
     if (row_bytes % 16 == 0 && aligned16(X) && aligned16(col)) {
-        const int cv = row_bytes / 16;
-        const int64_t items = rows * 27 * cv;
-        if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hash2col: too many rows in one launch");
         hch::LaunchTimer lt(hch::K_HASH2COL_VEC, s, bytes, 0.0);
-        hipLaunchKernelGGL(hch::hash2col_vec_kernel, dim3(blocks_for(items)), dim3(256), 0, s,
-                           (const uint4 *)X, L.dnbr, (uint4 *)col, row_begin, rows, cv);
+        hipLaunchKernelGGL(hch::hash2col_kernel<uint4>, dim3(grid), dim3(256), 0, s,
+                           (const uint4 *)X, L.dnbr, (uint4 *)col, row_begin, rows, row_bytes / 16, tv, n_tiles);
     } else {
-        const int64_t items = rows * 27 * c_in;
-        if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hash2col: too many rows in one launch");
         hch::LaunchTimer lt(hch::K_HASH2COL_ELEM, s, bytes, 0.0);
         if (dtype == HCH_F32)
-            hipLaunchKernelGGL(hch::hash2col_elem_kernel<float>, dim3(blocks_for(items)), dim3(256), 0, s,
-                               (const float *)X, L.dnbr, (float *)col, row_begin, rows, c_in);
+            hipLaunchKernelGGL(hch::hash2col_kernel<float>, dim3(grid), dim3(256), 0, s,
+                               (const float *)X, L.dnbr, (float *)col, row_begin, rows, c_in, tv, n_tiles);
         else
-            hipLaunchKernelGGL(hch::hash2col_elem_kernel<uint16_t>, dim3(blocks_for(items)), dim3(256), 0, s,
-                               (const uint16_t *)X, L.dnbr, (uint16_t *)col, row_begin, rows, c_in);
+            hipLaunchKernelGGL(hch::hash2col_kernel<uint16_t>, dim3(grid), dim3(256), 0, s,
+                               (const uint16_t *)X, L.dnbr, (uint16_t *)col, row_begin, rows, c_in, tv, n_tiles);
     }
     HCH_LAUNCH_CHECK("hash2col");
     return HCH_OK;
@@ -413,18 +441,21 @@ extern "C" hch_status hch_hash2col(const hch_levels *levels, int32_t level, hch_
 
 static hch_status do_col2hash(const Level &L, const float *dcol, int c_in, float *dX, hipStream_t s)
 {
+    if (L.n_total == 0) return HCH_OK;
     // per voxel: 27 indices in, one c_in row per occupied neighbour in, one row out
     const double bytes = (double)L.n_total * (108.0 + 4.0 * c_in) + (double)L.nbr_valid * 4.0 * c_in;
     hch::LaunchTimer lt(hch::K_COL2HASH, s, bytes, (double)L.nbr_valid * c_in);
-    if (c_in % 4 == 0 && aligned16(dcol) && aligned16(dX)) {
-        const int64_t items = L.n_total * (c_in / 4);
-        hipLaunchKernelGGL(hch::col2hash_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, s,
-                           dcol, L.dnbr, dX, L.n_total, c_in);
-    } else {
-        const int64_t items = L.n_total * c_in;
-        hipLaunchKernelGGL(hch::col2hash_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, s,
-                           dcol, L.dnbr, dX, L.n_total, c_in);
-    }
+    const bool vec = c_in % 4 == 0 && aligned16(dcol) && aligned16(dX);
+    const int cu = vec ? c_in / 4 : c_in;
+    const int tv = std::max(4, std::min(256, 256 / cu));
+    const unsigned n_tiles = (unsigned)((L.n_total + tv - 1) / tv);
+    const unsigned grid = (n_tiles + hch::NUM_XCD - 1) / hch::NUM_XCD * hch::NUM_XCD;
+    if (vec)
+        hipLaunchKernelGGL(hch::col2hash_kernel<4>, dim3(grid), dim3(256), 0, s, dcol, L.dnbr, dX,
+                           L.n_total, c_in, tv, n_tiles);
+    else
+        hipLaunchKernelGGL(hch::col2hash_kernel<1>, dim3(grid), dim3(256), 0, s, dcol, L.dnbr, dX,
+                           L.n_total, c_in, tv, n_tiles);
     HCH_LAUNCH_CHECK("col2hash");
     return HCH_OK;
 }
@@ -443,66 +474,132 @@ extern "C" hch_status hch_col2hash(const hch_levels *levels, int32_t level, cons
 // GEMM launches
 // ---------------------------------------------------------------------------------------
 
-template <bool A_KC, bool B_KC>
-static hch_status launch_gemm(int kernel_id, const float *A, const float *B, float *C, int M, int N, int K,
-                              int64_t lda, int64_t ldb, int64_t ldc, int splits, int k_per_split,
-                              int64_t c_split_stride, hipStream_t s)
+// tile shape and split of one product
+struct GemmPlan {
+    int bm, bn, wm;
+    int splits, k_per_split;
+};
+
+// fwd-like products (M = voxels): wide tiles when there are many row tiles, 64-row tiles and a
+// split of the reduction when the level is too small to fill the chip
+static GemmPlan plan_rows(int64_t M, int N, int K, bool allow_split)
 {
-    if (M <= 0 || N <= 0) return HCH_OK;
-    // every operand once: A, B in, C out (split-K partials count as output)
-    const double bytes = 4.0 * ((double)M * K + (double)K * N + (double)M * N * splits);
-    hch::LaunchTimer lt(kernel_id, s, bytes, 2.0 * M * (double)N * K);
-    const int vec_ok = (lda % 4 == 0) && (ldb % 4 == 0) && aligned16(A) && aligned16(B);
-    const unsigned gx = (unsigned)((M + hch::GEMM_BM - 1) / hch::GEMM_BM);
-    if (N <= 16) {
-        hipLaunchKernelGGL((hch::gemm_f32_kernel<16, A_KC, B_KC>), dim3(gx, 1, splits), dim3(256), 0, s,
-                           A, B, C, M, N, K, lda, ldb, ldc, k_per_split, c_split_stride, vec_ok);
-    } else if (N <= 32) {
-        hipLaunchKernelGGL((hch::gemm_f32_kernel<32, A_KC, B_KC>), dim3(gx, 1, splits), dim3(256), 0, s,
-                           A, B, C, M, N, K, lda, ldb, ldc, k_per_split, c_split_stride, vec_ok);
-    } else {
-        hipLaunchKernelGGL((hch::gemm_f32_kernel<64, A_KC, B_KC>), dim3(gx, (unsigned)((N + 63) / 64), splits),
-                           dim3(256), 0, s, A, B, C, M, N, K, lda, ldb, ldc, k_per_split,
-                           c_split_stride, vec_ok);
+    GemmPlan p;
+    p.bn = N <= 16 ? 16 : (N <= 32 ? 32 : 64);
+    p.bm = 128; p.wm = 4;
+    const int64_t n_tiles = (N + p.bn - 1) / p.bn;
+    int64_t blocks = (M + 127) / 128 * n_tiles;
+    if (p.bn == 64 && blocks < 1024) { p.bm = 64; p.wm = 2; blocks = (M + 63) / 64 * n_tiles; }
+    p.splits = 1; p.k_per_split = K + hch::GEMM_BK;
+    if (allow_split && blocks < 512 && K >= 512) {
+        int64_t want = std::min<int64_t>((768 + blocks - 1) / blocks, K / 256);
+        want = std::max<int64_t>(1, want);
+        int64_t kps = (K + want - 1) / want;
+        kps = (kps + hch::GEMM_BK - 1) / hch::GEMM_BK * hch::GEMM_BK;
+        p.k_per_split = (int)kps;
+        p.splits = (int)((K + kps - 1) / kps);
     }
-    HCH_LAUNCH_CHECK("gemm_f32_kernel");
-    return HCH_OK;
+    return p;
 }
 
-// split plan of the weight-gradient reduction over the voxels
-struct WgradPlan { int splits; int rows_per_split; };
-
-static WgradPlan wgrad_plan(int64_t n, int c_in, int c_out)
+// weight-gradient product (M = 27*c_in, N = c_out, reduction over n voxels split in slices)
+static GemmPlan plan_wgrad(int64_t n, int c_in, int c_out)
 {
+    GemmPlan p;
     const int Kc = 27 * c_in;
-    const int64_t tiles = (int64_t)((Kc + hch::GEMM_BM - 1) / hch::GEMM_BM) * ((c_out + 63) / 64);
-    int64_t want = std::max<int64_t>(1, 2048 / tiles);
+    p.bn = c_out <= 16 ? 16 : (c_out <= 32 ? 32 : 64);
+    p.bm = 128; p.wm = 4;
+    const int64_t tiles = (int64_t)((Kc + 127) / 128) * ((c_out + p.bn - 1) / p.bn);
+    int64_t want = std::max<int64_t>(1, 1024 / tiles);
     want = std::min<int64_t>(want, std::max<int64_t>(1, (n + 255) / 256));
     int64_t rows = (n + want - 1) / want;
     rows = std::max<int64_t>(hch::GEMM_BK, (rows + hch::GEMM_BK - 1) / hch::GEMM_BK * hch::GEMM_BK);
-    WgradPlan p;
-    p.rows_per_split = (int)rows;
+    p.k_per_split = (int)rows;
     p.splits = (int)std::max<int64_t>(1, (n + rows - 1) / rows);
     return p;
 }
 
+template <int AMODE, bool B_KC>
+static hch_status launch_gemm(int kernel_id, const GemmPlan &p, const float *A, const float *B, float *C,
+                              const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
+                              int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s)
+{
+    if (M <= 0 || N <= 0) return HCH_OK;
+    const bool gather = (AMODE == hch::A_GATHER || AMODE == hch::A_GATHER_T);
+    const int vec_ok = (lda % 4 == 0) && (ldb % 4 == 0) && aligned16(A) && aligned16(B);
+    const int c_vec_ok = (ldc % 4 == 0) && (c_split_stride % 4 == 0) && aligned16(C);
+    const unsigned m_tiles = (unsigned)((M + p.bm - 1) / p.bm);
+    const unsigned gx = (m_tiles + hch::NUM_XCD - 1) / hch::NUM_XCD * hch::NUM_XCD;
+    const dim3 grid(gx, (unsigned)((N + p.bn - 1) / p.bn), (unsigned)p.splits);
+    (void)gather;
+    hch::LaunchTimer lt(kernel_id, s, alg_bytes, 2.0 * M * (double)N * K);
+#define HCH_GEMM_CASE(BM_, BN_, BK_, WM_)                                                               \
+    hipLaunchKernelGGL((hch::gemm_f32_kernel<BM_, BN_, BK_, WM_, AMODE, B_KC>), grid, dim3(256), 0, s, \
+                       A, B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split, c_split_stride, vec_ok,     \
+                       c_vec_ok, m_tiles)
+    if (p.bm == 64) HCH_GEMM_CASE(64, 64, 32, 2);
+    else if (p.bn == 16) HCH_GEMM_CASE(128, 16, 32, 4);
+    else if (p.bn == 32) HCH_GEMM_CASE(128, 32, 32, 4);
+    else HCH_GEMM_CASE(128, 64, 32, 4);
+#undef HCH_GEMM_CASE
+    HCH_LAUNCH_CHECK("gemm_f32_kernel");
+    return HCH_OK;
+}
+
+static hch_status launch_reduce(const float *part, float *out, int64_t n, int splits, hipStream_t s)
+{
+    hch::LaunchTimer lt(hch::K_SPLITK_REDUCE, s, 4.0 * n * (splits + 1.0), (double)n * splits);
+    hipLaunchKernelGGL(hch::splitk_reduce_kernel, dim3((unsigned)((n + 15) / 16)), dim3(256), 0, s,
+                       part, out, n, splits, n);
+    HCH_LAUNCH_CHECK("splitk_reduce_kernel");
+    return HCH_OK;
+}
+
+// workspace layout, all offsets 256-byte aligned:
+//   columns algorithm : [ column matrix | split-K partial sums ]
+//   fused algorithm   : [ flipped+transposed weights (bwd_data only) | split-K partial sums ]
+struct WsLayout { size_t first_bytes, part_bytes; };
+
+static WsLayout ws_layout(const Level &L, int c_in, int c_out, hch_dtype dtype, hch_ws_kind kind, hch_algo algo)
+{
+    const size_t Kc = (size_t)27 * c_in, n = (size_t)L.n_total;
+    WsLayout w{0, 0};
+    if (kind == HCH_WS_FWD) {
+        const GemmPlan p = plan_rows(L.n_total, c_out, (int)Kc, true);
+        if (algo == HCH_ALGO_COLUMNS) w.first_bytes = round_up(n * Kc * elem_size(dtype), 256);
+        if (p.splits > 1) w.part_bytes = round_up((size_t)p.splits * n * c_out * 4, 256);
+    } else if (kind == HCH_WS_BWD_DATA) {
+        if (algo == HCH_ALGO_COLUMNS) w.first_bytes = round_up(n * Kc * 4, 256);
+        else {
+            const GemmPlan p = plan_rows(L.n_total, c_in, 27 * c_out, true);
+            w.first_bytes = round_up(Kc * c_out * 4, 256);
+            if (p.splits > 1) w.part_bytes = round_up((size_t)p.splits * n * c_in * 4, 256);
+        }
+    } else if (kind == HCH_WS_BWD_WEIGHT) {
+        const GemmPlan p = plan_wgrad(L.n_total, c_in, c_out);
+        if (algo == HCH_ALGO_COLUMNS) w.first_bytes = round_up(n * Kc * elem_size(dtype), 256);
+        if (p.splits > 1) w.part_bytes = round_up((size_t)p.splits * Kc * c_out * 4, 256);
+    }
+    return w;
+}
+
 extern "C" size_t hch_conv_workspace_bytes(const hch_levels *levels, int32_t level, int32_t c_in,
-                                           int32_t c_out, hch_dtype dtype, hch_ws_kind kind)
+                                           int32_t c_out, hch_dtype dtype, hch_ws_kind kind, hch_algo algo)
 {
     if (!levels || level < 0 || level >= (int32_t)levels->lv.size() || c_in <= 0 || c_out <= 0) return 0;
+    if (algo != HCH_ALGO_COLUMNS && algo != HCH_ALGO_FUSED) return 0;
     const Level &L = levels->lv[level];
-    const size_t Kc = (size_t)27 * c_in;
-    const size_t n = (size_t)L.n_total;
-    switch (kind) {
-    case HCH_WS_FWD: return round_up(n * Kc * elem_size(dtype), 256);
-    case HCH_WS_BWD_DATA: return round_up(n * Kc * 4, 256);
-    case HCH_WS_BWD_WEIGHT: {
-        const WgradPlan p = wgrad_plan(L.n_total, c_in, c_out);
-        return round_up(n * Kc * elem_size(dtype), 256) + round_up((size_t)p.splits * Kc * c_out * 4, 256);
+    if (kind == HCH_WS_MIN) {
+        // hch_conv_fwd with the columns algorithm: room for 1024 rows of the column matrix
+        // next to the split-K area
+        const WsLayout w = ws_layout(L, c_in, c_out, dtype, HCH_WS_FWD, algo);
+        const size_t rows = std::min<size_t>((size_t)L.n_total, 1024);
+        const size_t first = algo == HCH_ALGO_COLUMNS ? round_up(rows * 27 * c_in * elem_size(dtype), 256) : 0;
+        return std::max<size_t>(256, first + w.part_bytes);
     }
-    case HCH_WS_MIN: return round_up(std::min<size_t>(n, 1024) * Kc * elem_size(dtype), 256);
-    }
-    return 0;
+    if (kind != HCH_WS_FWD && kind != HCH_WS_BWD_DATA && kind != HCH_WS_BWD_WEIGHT) return 0;
+    const WsLayout w = ws_layout(L, c_in, c_out, dtype, kind, algo);
+    return std::max<size_t>(256, w.first_bytes + w.part_bytes);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -511,7 +608,7 @@ extern "C" size_t hch_conv_workspace_bytes(const hch_levels *levels, int32_t lev
 
 static hch_status conv_args(const hch_levels *levels, int32_t level, hch_dtype dtype, const void *a,
                             const void *b, const void *c, int32_t c_in, int32_t c_out,
-                            const void *ws, const Level **L, const char *who)
+                            const void *ws, hch_algo algo, const Level **L, const char *who)
 {
     hch_status st = get_level(levels, level, L, who);
     if (st != HCH_OK) return st;
@@ -519,90 +616,147 @@ static hch_status conv_args(const hch_levels *levels, int32_t level, hch_dtype d
         return fail(HCH_EINVAL, std::string(who) + ": null pointer or non-positive channel count");
     if ((int64_t)27 * c_in * c_out >= ((int64_t)1 << 31))
         return fail(HCH_EINVAL, std::string(who) + ": weight tensor too large");
+    if (algo != HCH_ALGO_COLUMNS && algo != HCH_ALGO_FUSED)
+        return fail(HCH_EINVAL, std::string(who) + ": unknown algorithm");
     if (dtype != HCH_F32)
         return fail(HCH_EUNSUPPORTED, std::string(who) + ": only HCH_F32 is implemented");
     if (reinterpret_cast<uintptr_t>(ws) & 255u)
         return fail(HCH_EINVAL, std::string(who) + ": workspace must be 256-byte aligned");
+    if ((*L)->n_total >= ((int64_t)1 << 31) / 64)
+        return fail(HCH_EUNSUPPORTED, std::string(who) + ": too many voxels");
     return HCH_OK;
 }
 
 extern "C" hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_dtype dtype,
                                    const void *X, const void *W, float *Y, int32_t c_in,
-                                   int32_t c_out, void *workspace, size_t ws_bytes, void *stream)
+                                   int32_t c_out, void *workspace, size_t ws_bytes, hch_algo algo,
+                                   void *stream)
 {
     const Level *L;
-    hch_status st = conv_args(levels, level, dtype, X, W, Y, c_in, c_out, workspace, &L, "hch_conv_fwd");
+    hch_status st = conv_args(levels, level, dtype, X, W, Y, c_in, c_out, workspace, algo, &L, "hch_conv_fwd");
     if (st != HCH_OK) return st;
-    if (ws_bytes < hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, HCH_WS_MIN))
+    if (ws_bytes < hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, HCH_WS_MIN, algo))
         return fail(HCH_EWORKSPACE, "hch_conv_fwd: workspace too small");
     hipStream_t s = (hipStream_t)stream;
     const int Kc = 27 * c_in;
+    const int64_t n = L->n_total;
+    const WsLayout w = ws_layout(*L, c_in, c_out, dtype, HCH_WS_FWD, algo);
+    const GemmPlan p = plan_rows(n, c_out, Kc, true);
+    float *part = (float *)((char *)workspace + ((ws_bytes - w.part_bytes) & ~(size_t)255));   // split-K area at the end
+
+    if (algo == HCH_ALGO_FUSED) {
+        // Y = gathered columns . W, the column matrix never leaves the chip.  Per voxel: 27
+        // indices and its feature row in, one output row out; the weights once.
+        const double bytes = (double)n * (108.0 + 4.0 * c_in + 4.0 * c_out * p.splits) + 4.0 * Kc * c_out;
+        st = launch_gemm<hch::A_GATHER, false>(hch::K_GEMM_GATHER, p, (const float *)X, (const float *)W,
+                                               p.splits > 1 ? part : Y, L->dnbr, (int)n, c_out, Kc, c_in,
+                                               c_out, c_out, n * c_out, bytes, s);
+        if (st != HCH_OK) return st;
+        if (p.splits > 1) st = launch_reduce(part, Y, n * c_out, p.splits, s);
+        return st;
+    }
+
     // as many rows of the column matrix as the workspace holds, in multiples of the GEMM tile
-    int64_t chunk = (int64_t)(ws_bytes / ((size_t)Kc * 4));
-    if (chunk < L->n_total) chunk = std::max<int64_t>(hch::GEMM_BM, chunk / hch::GEMM_BM * hch::GEMM_BM);
-    chunk = std::min<int64_t>(chunk, (int64_t)1 << 30);
-    for (int64_t r0 = 0; r0 < L->n_total; r0 += chunk) {
-        const int64_t rows = std::min<int64_t>(chunk, L->n_total - r0);
+    int64_t chunk = (int64_t)(((ws_bytes - w.part_bytes) & ~(size_t)255) / ((size_t)Kc * 4));
+    if (chunk < n) chunk = std::max<int64_t>(128, chunk / 128 * 128);
+    for (int64_t r0 = 0; r0 < n; r0 += chunk) {
+        const int64_t rows = std::min<int64_t>(chunk, n - r0);
         st = do_hash2col(*L, dtype, X, c_in, r0, rows, workspace, s);
         if (st != HCH_OK) return st;
-        st = launch_gemm<true, false>(hch::K_GEMM_FWD, (const float *)workspace, (const float *)W, Y + r0 * c_out,
-                                      (int)rows, c_out, Kc, Kc, c_out, c_out, 1, Kc + hch::GEMM_BK, 0, s);
+        const double bytes = 4.0 * ((double)rows * Kc + (double)Kc * c_out + (double)rows * c_out * p.splits);
+        // the split plan was made for all n rows; slices of a chunk land in the same places
+        st = launch_gemm<hch::A_ROWS, false>(hch::K_GEMM_ROWS, p, (const float *)workspace, (const float *)W,
+                                             p.splits > 1 ? part + r0 * c_out : Y + r0 * c_out, nullptr,
+                                             (int)rows, c_out, Kc, Kc, c_out, c_out, n * c_out, bytes, s);
         if (st != HCH_OK) return st;
     }
-    return HCH_OK;
+    if (p.splits > 1) st = launch_reduce(part, Y, n * c_out, p.splits, s);
+    return st;
 }
 
 extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level, hch_dtype dtype,
                                         const void *dY, const void *W, float *dX, int32_t c_in,
-                                        int32_t c_out, void *workspace, size_t ws_bytes, void *stream)
+                                        int32_t c_out, void *workspace, size_t ws_bytes, hch_algo algo,
+                                        void *stream)
 {
     const Level *L;
-    hch_status st = conv_args(levels, level, dtype, dY, W, dX, c_in, c_out, workspace, &L, "hch_conv_bwd_data");
+    hch_status st = conv_args(levels, level, dtype, dY, W, dX, c_in, c_out, workspace, algo, &L, "hch_conv_bwd_data");
     if (st != HCH_OK) return st;
-    if (ws_bytes < hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, HCH_WS_BWD_DATA))
+    if (ws_bytes < hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, HCH_WS_BWD_DATA, algo))
         return fail(HCH_EWORKSPACE, "hch_conv_bwd_data: workspace too small");
-    if (L->n_total >= ((int64_t)1 << 31)) return fail(HCH_EUNSUPPORTED, "hch_conv_bwd_data: too many voxels");
     hipStream_t s = (hipStream_t)stream;
     const int Kc = 27 * c_in;
+    const int64_t n = L->n_total;
+
+    if (algo == HCH_ALGO_FUSED) {
+        // dX[q] = sum_k dY[neighbour 26-k of q] . W[k]^T: a gathered product over the output
+        // gradients with the flipped, transposed weights; dcol is never formed.
+        const WsLayout w = ws_layout(*L, c_in, c_out, dtype, HCH_WS_BWD_DATA, algo);
+        float *Wt = (float *)workspace;
+        float *part = (float *)((char *)workspace + w.first_bytes);
+        const int64_t wn = (int64_t)Kc * c_out;
+        {
+            hch::LaunchTimer lt(hch::K_FLIP_WEIGHTS, s, 8.0 * wn, 0.0);
+            hipLaunchKernelGGL(hch::flip_transpose_weights_kernel, dim3(blocks_for(wn)), dim3(256), 0, s,
+                               (const float *)W, Wt, c_in, c_out);
+        }
+        HCH_LAUNCH_CHECK("flip_transpose_weights_kernel");
+        const int Kd = 27 * c_out;
+        const GemmPlan p = plan_rows(n, c_in, Kd, true);
+        const double bytes = (double)n * (108.0 + 4.0 * c_out + 4.0 * c_in * p.splits) + 4.0 * wn;
+        st = launch_gemm<hch::A_GATHER, false>(hch::K_GEMM_GATHER, p, (const float *)dY, Wt,
+                                               p.splits > 1 ? part : dX, L->dnbr, (int)n, c_in, Kd, c_out,
+                                               c_in, c_in, n * c_in, bytes, s);
+        if (st != HCH_OK) return st;
+        if (p.splits > 1) st = launch_reduce(part, dX, n * c_in, p.splits, s);
+        return st;
+    }
+
     float *dcol = (float *)workspace;
     // dcol[N x Kc] = dY[N x c_out] . W^T   (W is [Kc x c_out]: its rows are B's columns)
-    st = launch_gemm<true, true>(hch::K_GEMM_DGRAD, (const float *)dY, (const float *)W, dcol, (int)L->n_total, Kc, c_out,
-                                 c_out, c_out, Kc, 1, c_out + hch::GEMM_BK, 0, s);
+    const GemmPlan p = plan_rows(n, Kc, c_out, false);
+    const double bytes = 4.0 * ((double)n * c_out + (double)Kc * c_out + (double)n * Kc);
+    st = launch_gemm<hch::A_ROWS, true>(hch::K_GEMM_ROWS_BT, p, (const float *)dY, (const float *)W, dcol, nullptr,
+                                        (int)n, Kc, c_out, c_out, c_out, Kc, 0, bytes, s);
     if (st != HCH_OK) return st;
     return do_col2hash(*L, dcol, c_in, dX, s);
 }
 
 extern "C" hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t level, hch_dtype dtype,
                                           const void *X, const void *dY, float *dW, int32_t c_in,
-                                          int32_t c_out, void *workspace, size_t ws_bytes, void *stream)
+                                          int32_t c_out, void *workspace, size_t ws_bytes, hch_algo algo,
+                                          void *stream)
 {
     const Level *L;
-    hch_status st = conv_args(levels, level, dtype, X, dY, dW, c_in, c_out, workspace, &L, "hch_conv_bwd_weight");
+    hch_status st = conv_args(levels, level, dtype, X, dY, dW, c_in, c_out, workspace, algo, &L, "hch_conv_bwd_weight");
     if (st != HCH_OK) return st;
-    if (ws_bytes < hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, HCH_WS_BWD_WEIGHT))
+    if (ws_bytes < hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, HCH_WS_BWD_WEIGHT, algo))
         return fail(HCH_EWORKSPACE, "hch_conv_bwd_weight: workspace too small");
-    if (L->n_total >= ((int64_t)1 << 31)) return fail(HCH_EUNSUPPORTED, "hch_conv_bwd_weight: too many voxels");
     hipStream_t s = (hipStream_t)stream;
     const int Kc = 27 * c_in;
-    const size_t col_bytes = round_up((size_t)L->n_total * Kc * 4, 256);
-    float *col = (float *)workspace;
-    float *part = (float *)((char *)workspace + col_bytes);
-    st = do_hash2col(*L, dtype, X, c_in, 0, L->n_total, col, s);
-    if (st != HCH_OK) return st;
-    const WgradPlan p = wgrad_plan(L->n_total, c_in, c_out);
+    const int64_t n = L->n_total;
+    const WsLayout w = ws_layout(*L, c_in, c_out, dtype, HCH_WS_BWD_WEIGHT, algo);
+    const GemmPlan p = plan_wgrad(n, c_in, c_out);
     const int64_t wsize = (int64_t)Kc * c_out;
-    // dW[Kc x c_out] = col^T[Kc x N] . dY[N x c_out], reduction over the voxels split in slices
+    float *part = (float *)((char *)workspace + w.first_bytes);
     float *dst = (p.splits == 1) ? dW : part;
-    st = launch_gemm<false, false>(hch::K_GEMM_WGRAD, col, (const float *)dY, dst, Kc, c_out, (int)L->n_total, Kc, c_out,
-                                   c_out, p.splits, p.rows_per_split, wsize, s);
-    if (st != HCH_OK) return st;
-    if (p.splits > 1) {
-        hch::LaunchTimer lt(hch::K_SPLITK_REDUCE, s, 4.0 * wsize * (p.splits + 1.0), (double)wsize * p.splits);
-        hipLaunchKernelGGL(hch::splitk_reduce_kernel, dim3((unsigned)((wsize + 63) / 64)), dim3(256), 0, s,
-                           part, dW, wsize, p.splits, wsize);
-        HCH_LAUNCH_CHECK("splitk_reduce_kernel");
+
+    // dW[Kc x c_out] = col^T[Kc x N] . dY[N x c_out], reduction over the voxels split in slices
+    if (algo == HCH_ALGO_FUSED) {
+        const double bytes = (double)n * (108.0 + 4.0 * c_in + 4.0 * c_out) + 4.0 * wsize * p.splits;
+        st = launch_gemm<hch::A_GATHER_T, false>(hch::K_GEMM_GATHER_T, p, (const float *)X, (const float *)dY, dst,
+                                                 L->dnbr, Kc, c_out, (int)n, c_in, c_out, c_out, wsize, bytes, s);
+    } else {
+        float *col = (float *)workspace;
+        st = do_hash2col(*L, dtype, X, c_in, 0, n, col, s);
+        if (st != HCH_OK) return st;
+        const double bytes = 4.0 * ((double)n * Kc + (double)n * c_out + (double)wsize * p.splits);
+        st = launch_gemm<hch::A_COLS, false>(hch::K_GEMM_COLS, p, col, (const float *)dY, dst, nullptr,
+                                             Kc, c_out, (int)n, Kc, c_out, c_out, wsize, bytes, s);
     }
-    return HCH_OK;
+    if (st != HCH_OK) return st;
+    if (p.splits > 1) st = launch_reduce(part, dW, wsize, p.splits, s);
+    return st;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -617,15 +771,20 @@ extern "C" hch_status hch_pool_fwd(const hch_levels *levels, int32_t level_in, c
     if (!X || !Y || !argmax || c <= 0) return fail(HCH_EINVAL, "hch_pool_fwd: bad argument");
     const Level &Lc = levels->lv[level_in + 1];
     if (!Lc.dchild) return fail(HCH_EINVAL, "hch_pool_fwd: levels were built without device tables");
-    const int64_t items = Lc.n_total * c;
+    const bool vec = c % 4 == 0 && aligned16(X) && aligned16(Y) && aligned16(argmax);
+    const int64_t items = Lc.n_total * (vec ? c / 4 : c);
     if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hch_pool_fwd: too large");
     {
         // per coarse voxel: 8 child indices, its children's rows in; value and switch rows out
         const Level &Lf = levels->lv[level_in];
         const double bytes = (double)Lc.n_total * (32.0 + 8.0 * c) + (double)Lf.n_total * 4.0 * c;
         hch::LaunchTimer lt(hch::K_POOL_FWD, (hipStream_t)stream, bytes, 0.0);
-        hipLaunchKernelGGL(hch::pool_fwd_kernel, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
-                           X, Lc.dchild, Y, argmax, Lc.n_total, c);
+        if (vec)
+            hipLaunchKernelGGL(hch::pool_fwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                               X, Lc.dchild, Y, argmax, Lc.n_total, c);
+        else
+            hipLaunchKernelGGL(hch::pool_fwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                               X, Lc.dchild, Y, argmax, Lc.n_total, c);
     }
     HCH_LAUNCH_CHECK("pool_fwd_kernel");
     return HCH_OK;
@@ -639,14 +798,19 @@ extern "C" hch_status hch_pool_bwd(const hch_levels *levels, int32_t level_in, c
     if (!dY || !argmax || !dX || c <= 0) return fail(HCH_EINVAL, "hch_pool_bwd: bad argument");
     const Level &Lc = levels->lv[level_in + 1];
     if (!Lc.dchild) return fail(HCH_EINVAL, "hch_pool_bwd: levels were built without device tables");
-    const int64_t items = Lc.n_total * 8 * c;
+    const bool vec = c % 4 == 0 && aligned16(dY) && aligned16(dX) && aligned16(argmax);
+    const int64_t items = Lc.n_total * 8 * (vec ? c / 4 : c);
     if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hch_pool_bwd: too large");
     {
         const Level &Lf = levels->lv[level_in];
         const double bytes = (double)Lc.n_total * (32.0 + 8.0 * c) + (double)Lf.n_total * 4.0 * c;
         hch::LaunchTimer lt(hch::K_POOL_BWD, (hipStream_t)stream, bytes, 0.0);
-        hipLaunchKernelGGL(hch::pool_bwd_kernel, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
-                           dY, argmax, Lc.dchild, dX, Lc.n_total, c);
+        if (vec)
+            hipLaunchKernelGGL(hch::pool_bwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                               dY, argmax, Lc.dchild, dX, Lc.n_total, c);
+        else
+            hipLaunchKernelGGL(hch::pool_bwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                               dY, argmax, Lc.dchild, dX, Lc.n_total, c);
     }
     HCH_LAUNCH_CHECK("pool_bwd_kernel");
     return HCH_OK;
@@ -658,7 +822,9 @@ extern "C" hch_status hch_relu_fwd(const float *x, float *y, int64_t n, void *st
     if (n == 0) return HCH_OK;
     {
         hch::LaunchTimer lt(hch::K_RELU_FWD, (hipStream_t)stream, 8.0 * n, 0.0);
-        hipLaunchKernelGGL(hch::relu_fwd_kernel, dim3(blocks_for(n)), dim3(256), 0, (hipStream_t)stream, x, y, n);
+        const int64_t n4 = (aligned16(x) && aligned16(y)) ? n / 4 : 0;
+        hipLaunchKernelGGL(hch::relu_fwd_kernel, dim3(blocks_for(std::max(n4, n - 4 * n4))), dim3(256), 0,
+                           (hipStream_t)stream, x, y, n, n4);
     }
     HCH_LAUNCH_CHECK("relu_fwd_kernel");
     return HCH_OK;
@@ -670,7 +836,9 @@ extern "C" hch_status hch_relu_bwd(const float *y, const float *dy, float *dx, i
     if (n == 0) return HCH_OK;
     {
         hch::LaunchTimer lt(hch::K_RELU_BWD, (hipStream_t)stream, 12.0 * n, 0.0);
-        hipLaunchKernelGGL(hch::relu_bwd_kernel, dim3(blocks_for(n)), dim3(256), 0, (hipStream_t)stream, y, dy, dx, n);
+        const int64_t n4 = (aligned16(y) && aligned16(dy) && aligned16(dx)) ? n / 4 : 0;
+        hipLaunchKernelGGL(hch::relu_bwd_kernel, dim3(blocks_for(std::max(n4, n - 4 * n4))), dim3(256), 0,
+                           (hipStream_t)stream, y, dy, dx, n, n4);
     }
     HCH_LAUNCH_CHECK("relu_bwd_kernel");
     return HCH_OK;

@@ -10,233 +10,399 @@ namespace hch {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// Workgroups are handed to the 8 XCDs (each with its own L2) round-robin.  Kernels whose
+// neighbouring tiles touch the same memory launch 8*per_xcd workgroups and use this mapping
+// so that every XCD works on one contiguous range of tiles.
+constexpr unsigned NUM_XCD = 8;
+__device__ __forceinline__ unsigned xcd_tile(unsigned bid, unsigned per_xcd)
+{
+    return (bid % NUM_XCD) * per_xcd + bid / NUM_XCD;
+}
+
 // ---------------------------------------------------------------------------------------
 // PSH lookup (paper Section 3.1, Eq.1; super tables Eq.4-6)
 // ---------------------------------------------------------------------------------------
 
-// Device view of one level of the mini-batch super-PSH.  Prefix arrays are 32-bit on the
-// device (the host checks that they fit).
+// Device view of one level of the mini-batch super-PSH.  The lookup kernels read packed
+// copies of the paper's tables: one 12-byte record per hash slot
+//   slot3[3s] = H*[s],  slot3[3s+1] = T*[s].x | T*[s].y << 16,  slot3[3s+2] = T*[s].z
+// and one 32-bit word per offset cell, phi4[c] = Phi*[c].x | .y << 8 | .z << 16.
+// Prefix arrays are 32-bit on the device (the host checks that they fit).
 struct PshView {
-    const int32_t *H;      // [M_total]     local data index or -1
-    const uint16_t *T;     // [M_total][3]  position tag
-    const uint8_t *Phi;    // [R_total][3]  offsets
-    const int32_t *mbar;   // [b]
-    const int32_t *rbar;   // [b]
-    const int32_t *M;      // [b+1]
-    const int32_t *R;      // [b+1]
-    const int32_t *N;      // [b+1]
+    const uint32_t *slot3;  // [M_total][3]
+    const uint32_t *phi4;   // [R_total]
+    const int32_t *mbar;    // [b]
+    const int32_t *rbar;    // [b]
+    const int32_t *M;       // [b+1]
+    const int32_t *R;       // [b+1]
+    const int32_t *N;       // [b+1]
     int32_t ubar;
 };
 
-// Global data index of position (x,y,z) of model v, or -1 if it is outside the grid, lands
-// on a redundant slot, or lands on a slot tagged with another position.
-__device__ __forceinline__ int32_t psh_lookup(const PshView &L, int v, int x, int y, int z)
+// residues of q-1, q, q+1 modulo d, given q mod d
+__device__ __forceinline__ void residues3(unsigned q_mod, unsigned d, unsigned out[3])
 {
-    const unsigned u = (unsigned)L.ubar;
-    if ((unsigned)x >= u || (unsigned)y >= u || (unsigned)z >= u) return -1;
-    const unsigned m = (unsigned)L.mbar[v], r = (unsigned)L.rbar[v];
-    const unsigned ux = (unsigned)x, uy = (unsigned)y, uz = (unsigned)z;
-    const unsigned iphi = (unsigned)L.R[v] + ((ux % r) * r + (uy % r)) * r + (uz % r);   // Eq.4
-    const uint8_t *ph = L.Phi + 3u * (size_t)iphi;
-    const unsigned hx = (ux % m + ph[0]) % m;                                            // Eq.1
-    const unsigned hy = (uy % m + ph[1]) % m;
-    const unsigned hz = (uz % m + ph[2]) % m;
-    const unsigned s = (unsigned)L.M[v] + (hx * m + hy) * m + hz;                        // Eq.5
-    const int32_t h = L.H[s];
-    if (h < 0) return -1;
-    const uint16_t *t = L.T + 3u * (size_t)s;
-    if (t[0] != ux || t[1] != uy || t[2] != uz) return -1;
-    return L.N[v] + h;                                                                   // Eq.6
+    out[0] = q_mod == 0 ? d - 1 : q_mod - 1;
+    out[1] = q_mod;
+    out[2] = q_mod + 1 == d ? 0 : q_mod + 1;
 }
 
-// Index side of the traversal of Algorithm 1: for every output voxel i of model
-// v = blockIdx.y and every position `row` of its F^3 receptive field (x slowest, z fastest),
-// the global input data index or -1.  out[(No[v] + i) * F^3 + row].
-//   Ss == 1:  field = [p - (F-1)/2, p + (F-1)/2]^3        (same level)
-//   Ss  > 1:  field = [p*Ss - Sp, p*Ss - Sp + F - 1]^3    (input level is finer)
-__global__ __launch_bounds__(256) void field_index_kernel(
-    PshView Li, const int32_t *__restrict__ out_coords, const int32_t *__restrict__ No,
-    int F, int Ss, int Sp, int32_t *__restrict__ out)
+// One probe: position (x,y,z) with residues (xm,ym,zm) mod m and (xr,yr,zr) mod r in the
+// tables of a model whose slots start at Mv and offset cells at Rv.  Returns the local data
+// index, or -1 on a redundant slot or a slot tagged with another position (Section 3.1).
+__device__ __forceinline__ int32_t psh_probe(const PshView &L, unsigned Mv, unsigned Rv, unsigned m,
+                                             unsigned r, unsigned xm, unsigned ym, unsigned zm,
+                                             unsigned xr, unsigned yr, unsigned zr,
+                                             unsigned x, unsigned y, unsigned z)
+{
+    const uint32_t ph = L.phi4[Rv + (xr * r + yr) * r + zr];                 // Eq.4
+    unsigned hx = xm + (ph & 255u);         if (hx >= m) hx -= m;             // Eq.1
+    unsigned hy = ym + ((ph >> 8) & 255u);  if (hy >= m) hy -= m;
+    unsigned hz = zm + ((ph >> 16) & 255u); if (hz >= m) hz -= m;
+    const uint32_t *rec = L.slot3 + 3u * (size_t)(Mv + (hx * m + hy) * m + hz);   // Eq.5
+    const uint32_t h = rec[0], xy = rec[1], zz = rec[2];
+    return ((int32_t)h >= 0 && xy == (x | (y << 16)) && zz == z) ? (int32_t)h : -1;
+}
+
+// "Pre-stored neighbour information": for every voxel i of model v = blockIdx.y the global
+// data indices of its 27 neighbours p + (dx,dy,dz), tap k = (dx+1)*9 + (dy+1)*3 + (dz+1), or -1
+// (empty, or outside the grid: never hashed).  This is the index side of the stride-1
+// traversal of Algorithm 1.  One thread per voxel: the six residues are computed once and
+// stepped to the neighbours; the 256 x 27 tile goes through LDS so that the rows are written
+// coalesced.
+__global__ __launch_bounds__(256) void neighbour_kernel(
+    PshView L, const int32_t *__restrict__ coords, int32_t *__restrict__ nbr)
+{
+    __shared__ int32_t tile[256 * 27];
+    const int v = blockIdx.y;
+    const int32_t base = L.N[v];
+    const int32_t n = L.N[v + 1] - base;
+    const int32_t blk0 = blockIdx.x * 256;
+    if (blk0 >= n) return;
+    const int32_t i = blk0 + threadIdx.x;
+    if (i < n) {
+        const unsigned m = (unsigned)L.mbar[v], r = (unsigned)L.rbar[v];
+        const unsigned Mv = (unsigned)L.M[v], Rv = (unsigned)L.R[v], u = (unsigned)L.ubar;
+        const int32_t *p = coords + 3 * (int64_t)(base + i);
+        const unsigned x = (unsigned)p[0], y = (unsigned)p[1], z = (unsigned)p[2];
+        unsigned xm[3], ym[3], zm[3], xr[3], yr[3], zr[3];
+        residues3(x % m, m, xm); residues3(y % m, m, ym); residues3(z % m, m, zm);
+        residues3(x % r, r, xr); residues3(y % r, r, yr); residues3(z % r, r, zr);
+        int32_t *row = tile + threadIdx.x * 27;
+#pragma unroll
+        for (int a = 0; a < 3; ++a)
+#pragma unroll
+            for (int b = 0; b < 3; ++b)
+#pragma unroll
+                for (int c = 0; c < 3; ++c) {
+                    const unsigned qx = x + a - 1, qy = y + b - 1, qz = z + c - 1;   // wraps below 0
+                    int32_t h = -1;
+                    if (qx < u && qy < u && qz < u)
+                        h = psh_probe(L, Mv, Rv, m, r, xm[a], ym[b], zm[c], xr[a], yr[b], zr[c], qx, qy, qz);
+                    row[a * 9 + b * 3 + c] = h >= 0 ? base + h : -1;                 // Eq.6
+                }
+    }
+    __syncthreads();
+    const int32_t cnt = min(256, n - blk0) * 27;
+    int32_t *dst = nbr + (int64_t)(base + blk0) * 27;
+    for (int t = threadIdx.x; t < cnt; t += 256) dst[t] = tile[t];
+}
+
+// For every coarse voxel i of model v = blockIdx.y the global data indices, at the next finer
+// level, of its 8 children 2p + (dx,dy,dz), k = dx*4 + dy*2 + dz, or -1: the stride-2, F = 2,
+// no-padding traversal of Algorithm 1 (receptive field [2p, 2p+1]^3).  Lf = the FINE level.
+__global__ __launch_bounds__(256) void child_kernel(
+    PshView Lf, const int32_t *__restrict__ coarse_coords, const int32_t *__restrict__ Nc,
+    int32_t *__restrict__ child)
 {
     const int v = blockIdx.y;
-    const int F3 = F * F * F;
-    const int32_t base = No[v];
-    const int64_t n_items = (int64_t)(No[v + 1] - base) * F3;
-    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (t >= n_items) return;
-    const int32_t i = (int32_t)(t / F3);
-    const int row = (int)(t - (int64_t)i * F3);
-    const int fx = row / (F * F), fy = (row / F) % F, fz = row % F;
-    const int32_t *p = out_coords + 3 * (int64_t)(base + i);
-    int lx, ly, lz;
-    if (Ss == 1) {
-        const int h = (F - 1) / 2;
-        lx = p[0] - h; ly = p[1] - h; lz = p[2] - h;
-    } else {
-        lx = p[0] * Ss - Sp; ly = p[1] * Ss - Sp; lz = p[2] * Ss - Sp;
-    }
-    out[(int64_t)(base + i) * F3 + row] = psh_lookup(Li, v, lx + fx, ly + fy, lz + fz);
+    const int32_t cbase = Nc[v];
+    const int32_t n = Nc[v + 1] - cbase;
+    const int32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const unsigned m = (unsigned)Lf.mbar[v], r = (unsigned)Lf.rbar[v];
+    const unsigned Mv = (unsigned)Lf.M[v], Rv = (unsigned)Lf.R[v];
+    const int32_t fbase = Lf.N[v];
+    const int32_t *p = coarse_coords + 3 * (int64_t)(cbase + i);
+    const unsigned x = 2u * (unsigned)p[0], y = 2u * (unsigned)p[1], z = 2u * (unsigned)p[2];
+    unsigned xm[2], ym[2], zm[2], xr[2], yr[2], zr[2];
+    xm[0] = x % m; xm[1] = xm[0] + 1 == m ? 0 : xm[0] + 1;
+    ym[0] = y % m; ym[1] = ym[0] + 1 == m ? 0 : ym[0] + 1;
+    zm[0] = z % m; zm[1] = zm[0] + 1 == m ? 0 : zm[0] + 1;
+    xr[0] = x % r; xr[1] = xr[0] + 1 == r ? 0 : xr[0] + 1;
+    yr[0] = y % r; yr[1] = yr[0] + 1 == r ? 0 : yr[0] + 1;
+    zr[0] = z % r; zr[1] = zr[0] + 1 == r ? 0 : zr[0] + 1;
+    int32_t out[8];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                // 2p + 1 < 2 * (coarse side) = fine side: always inside the grid
+                const int32_t h = psh_probe(Lf, Mv, Rv, m, r, xm[a], ym[b], zm[c], xr[a], yr[b], zr[c],
+                                            x + a, y + b, z + c);
+                out[a * 4 + b * 2 + c] = h >= 0 ? fbase + h : -1;
+            }
+    int4 *dst = reinterpret_cast<int4 *>(child + (int64_t)(cbase + i) * 8);
+    dst[0] = make_int4(out[0], out[1], out[2], out[3]);
+    dst[1] = make_int4(out[4], out[5], out[6], out[7]);
 }
 
 // ---------------------------------------------------------------------------------------
 // hash2col (Algorithm 1) through the pre-stored neighbour indices
 // ---------------------------------------------------------------------------------------
 
-// 16-byte units: cv = c_in * sizeof(element) / 16.  One thread moves one unit:
-// col[r][k][u] = X[nbr[row_begin + r][k]][u] or 0.
-__global__ __launch_bounds__(256) void hash2col_vec_kernel(
-    const uint4 *__restrict__ X, const int32_t *__restrict__ nbr, uint4 *__restrict__ col,
-    int64_t row_begin, int64_t rows, int cv)
+// Tile of `tv` voxels per workgroup (tv * 27 <= 6912 indices staged in LDS).  A unit is `UB`
+// bytes (16: uint4, or one element); a voxel row has cu units.  Threads are split into groups
+// of g = min(cu, 256) lanes; group q moves the units of one (voxel, tap) pair per step, so a
+// step of the whole workgroup writes one contiguous stretch of col.
+template <typename U>
+__global__ __launch_bounds__(256) void hash2col_kernel(
+    const U *__restrict__ X, const int32_t *__restrict__ nbr, U *__restrict__ col,
+    int64_t row_begin, int64_t rows, int cu, int tv, unsigned n_tiles)
 {
-    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int per_row = 27 * cv;
-    if (item >= rows * per_row) return;
-    const int64_t r = item / per_row;
-    const int rem = (int)(item - r * per_row);
-    const int k = rem / cv, u = rem - k * cv;
-    const int32_t j = nbr[(row_begin + r) * 27 + k];
-    uint4 val = make_uint4(0u, 0u, 0u, 0u);
-    if (j >= 0) val = X[(int64_t)j * cv + u];
-    col[item] = val;
-}
-
-// any channel count, one element per thread
-template <typename E>
-__global__ __launch_bounds__(256) void hash2col_elem_kernel(
-    const E *__restrict__ X, const int32_t *__restrict__ nbr, E *__restrict__ col,
-    int64_t row_begin, int64_t rows, int c)
-{
-    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int per_row = 27 * c;
-    if (item >= rows * per_row) return;
-    const int64_t r = item / per_row;
-    const int rem = (int)(item - r * per_row);
-    const int k = rem / c, ch = rem - k * c;
-    const int32_t j = nbr[(row_begin + r) * 27 + k];
-    E val = (E)0;
-    if (j >= 0) val = X[(int64_t)j * c + ch];
-    col[item] = val;
+    __shared__ int32_t idx[256 * 27];
+    const unsigned tile = xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
+    if (tile >= n_tiles) return;
+    const int64_t r0 = (int64_t)tile * tv;
+    const int nv = (int)min((int64_t)tv, rows - r0);
+    const int32_t *src = nbr + (row_begin + r0) * 27;
+    for (int t = threadIdx.x; t < nv * 27; t += 256) idx[t] = src[t];
+    __syncthreads();
+    const int g = min(cu, 256);
+    const int groups = 256 / g;
+    const int grp = threadIdx.x / g, lane = threadIdx.x - grp * g;
+    if (grp >= groups) return;
+    U *dst = col + r0 * 27 * cu;
+    U zero;
+    __builtin_memset(&zero, 0, sizeof(U));
+    for (int q = grp; q < nv * 27; q += groups) {
+        const int32_t j = idx[q];
+        for (int u = lane; u < cu; u += g) {
+            U val = zero;
+            if (j >= 0) val = X[(int64_t)j * cu + u];
+            dst[(int64_t)q * cu + u] = val;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------
 // col2hash (Algorithm 2) as a gather: the 3x3x3 stride-1 neighbourhood is symmetric, so the
 // voxels that hold row j as their neighbour k are exactly nbr[j][26-k].  Summing per
 // destination row in tap order needs no atomics and is bit-reproducible.
+// Tile of tv destination voxels per workgroup, their index rows staged in LDS; a thread owns
+// (voxel, VEC-float unit) pairs.  The sources of neighbouring destinations share cache lines
+// of dcol, hence the XCD-contiguous tile order.
 // ---------------------------------------------------------------------------------------
 template <int VEC>
 __global__ __launch_bounds__(256) void col2hash_kernel(
     const float *__restrict__ dcol, const int32_t *__restrict__ nbr, float *__restrict__ dX,
-    int64_t n, int c)
+    int64_t n, int c, int tv, unsigned n_tiles)
 {
-    const int cv = c / VEC;
-    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (item >= n * cv) return;
-    const int64_t j = item / cv;
-    const int u = (int)(item - j * cv);
-    float acc[VEC];
+    __shared__ int32_t idx[256 * 27];
+    const unsigned tile = xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
+    if (tile >= n_tiles) return;
+    const int64_t j0 = (int64_t)tile * tv;
+    const int nv = (int)min((int64_t)tv, n - j0);
+    const int32_t *src = nbr + j0 * 27;
+    for (int t = threadIdx.x; t < nv * 27; t += 256) idx[t] = src[t];
+    __syncthreads();
+    const int cu = c / VEC;
+    for (int item = threadIdx.x; item < nv * cu; item += 256) {
+        const int jl = item / cu, u = item - jl * cu;
+        float acc[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
-    const int32_t *nb = nbr + j * 27;
-    for (int k = 0; k < 27; ++k) {
-        const int32_t i = nb[26 - k];
-        if (i < 0) continue;
-        const float *src = dcol + ((int64_t)i * 27 + k) * c + u * VEC;
+        for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+        const int32_t *nb = idx + jl * 27;
+#pragma unroll 9
+        for (int k = 0; k < 27; ++k) {
+            const int32_t i = nb[26 - k];
+            if (i < 0) continue;
+            const float *s = dcol + ((int64_t)i * 27 + k) * c + u * VEC;
+            if constexpr (VEC == 4) {
+                const f32x4 v = *reinterpret_cast<const f32x4 *>(s);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] += v[e];
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[e] += s[e];
+            }
+        }
+        float *d = dX + (j0 + jl) * c + u * VEC;
         if constexpr (VEC == 4) {
-            const f32x4 v = *reinterpret_cast<const f32x4 *>(src);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] += v[e];
+            *reinterpret_cast<f32x4 *>(d) = f32x4{acc[0], acc[1], acc[2], acc[3]};
         } else {
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] += src[e];
+            for (int e = 0; e < VEC; ++e) d[e] = acc[e];
         }
     }
-    float *dst = dX + j * c + u * VEC;
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) dst[e] = acc[e];
 }
 
 // ---------------------------------------------------------------------------------------
 // fp32 GEMM on the matrix cores:  C[M x N] (+split) = A[M x K] * B[K x N]
 //
-//   A_KC : A(i,k) = A[i*lda + k]  (k contiguous)   else  A(i,k) = A[k*lda + i]
-//   B_KC : B(k,j) = B[j*ldb + k]  (k contiguous)   else  B(k,j) = B[k*ldb + j]
+// A operand (AMODE):
+//   A_ROWS    A(i,k) = A[i*lda + k]                       plain, k contiguous
+//   A_COLS    A(i,k) = A[k*lda + i]                       plain, i contiguous
+//   A_GATHER  A(i,k) = X[nbr[i][k / c]][k % c] or 0       row i of the column matrix of
+//             hash2col (Algorithm 1) read straight from the feature rows: i = voxel,
+//             k = tap*c + channel.  `A` = X, `lda` = c, `nbr` = the level's index rows.
+//   A_GATHER_T  A(i,k) = X[nbr[k][i / c]][i % c] or 0     the transpose of the above:
+//             i = tap*c + channel, k = voxel (reduction over the voxels, Eq.7).
+// B operand:  B_KC : B(k,j) = B[j*ldb + k]   else   B(k,j) = B[k*ldb + j]
 //
-// Block = 256 threads = 4 waves, tile 128 x BN x 32.  Operands are staged in LDS k-major
-// (As[k][i], Bs[k][j]) so that the 16 lanes of an MFMA operand row read consecutive words.
-// Wave w owns rows [32w, 32w+32) of the tile as 2 x (BN/16) tiles of v_mfma_f32_16x16x4_f32.
-// blockIdx.z selects a slice of the reduction dimension (split-K): slice z covers
-// k in [z*k_per_split, (z+1)*k_per_split) and writes to C + z*c_split_stride.
+// Block = 256 threads = 4 waves arranged WM x (4/WM); tile BM x BN x BK, staged in LDS.  Each
+// wave owns a (BM/WM) x (BN*WM/4) sub-tile as MT x NT tiles of v_mfma_f32_16x16x4_f32 and reads
+// its operands from LDS with 64/128-bit accesses.  blockIdx.z selects a slice of the reduction dimension (split-K):
+// slice z covers k in [z*k_per_split, (z+1)*k_per_split) and writes to C + z*c_split_stride.
 // The next tile's global loads are issued before the current tile's MFMAs.
+// Row tiles (blockIdx.x) are remapped so that each XCD owns a contiguous range of them:
+// gathered rows of neighbouring voxels then meet in one L2.
 // ---------------------------------------------------------------------------------------
-constexpr int GEMM_BM = 128;
-constexpr int GEMM_BK = 32;
+constexpr int GEMM_BK = 32;   // granularity of reduction slices (split-K)
+enum { A_ROWS = 0, A_COLS = 1, A_GATHER = 2, A_GATHER_T = 3 };
 
-template <int BN, bool A_KC, bool B_KC>
+template <int N> struct FVec;
+template <> struct FVec<1> { typedef float type; };
+template <> struct FVec<2> { typedef float type __attribute__((ext_vector_type(2))); };
+template <> struct FVec<4> { typedef float type __attribute__((ext_vector_type(4))); };
+template <int N> __device__ __forceinline__ float vget(const typename FVec<N>::type &v, int i) { return v[i]; }
+template <> __device__ __forceinline__ float vget<1>(const float &v, int) { return v; }
+
+template <int BM, int BN, int BK, int WM, int AMODE, bool B_KC>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(
     const float *__restrict__ A, const float *__restrict__ B, float *__restrict__ C,
-    int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
-    int k_per_split, int64_t c_split_stride, int vec_ok)
+    const int32_t *__restrict__ nbr, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
+    int k_per_split, int64_t c_split_stride, int vec_ok, int c_vec_ok, unsigned m_tiles)
 {
-    constexpr int BM = GEMM_BM, BK = GEMM_BK;
-    constexpr int AS = BM + 16;                       // row strides chosen so that the four
-    constexpr int BS = (BN == 16) ? 16 : BN + 16;     // k-rows of an operand hit distinct banks
-    constexpr int A_UNITS = BM * BK / 4 / 256;        // float4 units per thread (= 4)
-    constexpr int B_TOTAL = BK * BN / 4;              // float4 units in a B tile
+    constexpr int WN = 4 / WM;
+    constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
+    constexpr int MT = WTM / 16, NT = WTN / 16;       // MFMA tiles per wave
+    static_assert(WTM % 16 == 0 && WTN % 16 == 0, "wave tile must be a multiple of 16x16");
+    static_assert((MT == 1 || MT == 2 || MT == 4) && (NT == 1 || NT == 2 || NT == 4), "1, 2 or 4 tiles");
+    static_assert(BK % 16 == 0, "BK must be a multiple of 16");
+    constexpr bool A_K_FAST = (AMODE == A_ROWS || AMODE == A_GATHER);   // k contiguous in memory
+    // LDS layouts.  A with k fast in memory is kept row-major As[i][k] (a lane reads 4
+    // consecutive k of its row at once); A with i fast is kept k-major As[k][i] and the MT MFMA
+    // tiles of a wave take interleaved rows (tile mt: rows r*MT + mt) so that a lane reads its MT
+    // operands at once.  B is always k-major Bs[k][j], tile nt taking columns r*NT + nt.
+    // The +4 padding keeps rows 16-byte aligned and spreads consecutive rows over the banks.
+    constexpr int AS = A_K_FAST ? BK + 4 : BM + 4;
+    constexpr int BS = BN + 4;
+    constexpr int A_ROWLEN = A_K_FAST ? BK : BM;      // floats per LDS row that are loaded
+    constexpr int A_TOTAL = BM * BK / 4;              // float4 units in an A tile
+    constexpr int A_UNITS = A_TOTAL / 256;
+    constexpr int A_UPR = A_ROWLEN / 4;               // units per LDS row
+    constexpr int B_TOTAL = BK * BN / 4;
     constexpr int B_UNITS = (B_TOTAL + 255) / 256;
-    constexpr int NT = BN / 16;
+    static_assert(A_TOTAL % 256 == 0 && 256 % A_UPR == 0, "A tile must split evenly over the threads");
+    typedef typename FVec<MT>::type avec_t;
+    typedef typename FVec<NT>::type bvec_t;
 
-    __shared__ __attribute__((aligned(16))) float As[BK * AS];
+    __shared__ __attribute__((aligned(16))) float As[A_K_FAST ? BM * AS : BK * AS];
     __shared__ __attribute__((aligned(16))) float Bs[BK * BS];
+    __shared__ int32_t idx[AMODE == A_GATHER ? BM * 27 : 1];
+
+    const unsigned mtile = xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
+    if (mtile >= m_tiles) return;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const int wm = wave % WM, wn = wave / WM;
+    const int m0 = (int)mtile * BM, n0 = blockIdx.y * BN;
     const int kbeg = blockIdx.z * k_per_split;
     const int kend = min(K, kbeg + k_per_split);
+    const int c = (int)lda;                           // channels per tap in the gather modes
     C += (int64_t)blockIdx.z * c_split_stride;
 
-    f32x4 acc[2][NT];
+    if (AMODE == A_GATHER) {
+        const int rows = min(BM, M - m0);
+        const int32_t *src = nbr + (int64_t)m0 * 27;
+        for (int t = tid; t < rows * 27; t += 256) idx[t] = src[t];
+        __syncthreads();
+    }
+
+    f32x4 acc[MT][NT];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < MT; ++a)
 #pragma unroll
         for (int b = 0; b < NT; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     f32x4 ra[A_UNITS], rb[B_UNITS];
 
+    // 4 consecutive elements starting at src; `left` = how many are inside the matrix
+    auto load4 = [&](const float *src, int left) {
+        f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (vec_ok && left >= 4) v = *reinterpret_cast<const f32x4 *>(src);
+        else {
+            v[0] = src[0];
+            if (left > 1) v[1] = src[1];
+            if (left > 2) v[2] = src[2];
+            if (left > 3) v[3] = src[3];
+        }
+        return v;
+    };
+    auto gather1 = [&](int32_t j, int cc) { return j >= 0 ? A[(int64_t)j * c + cc] : 0.f; };
+
+    // position of this thread's units inside a tile: the same column of units in every row
+    const int a_col = (tid % A_UPR) * 4;              // first of 4 elements along the fast axis
+    const int a_row0 = tid / A_UPR;                   // unit uu sits in row a_row0 + uu*(256/A_UPR)
+    constexpr int A_RSTEP = 256 / A_UPR;
+
     // fetch the tile starting at reduction index k0 into registers (zero outside the matrices)
     auto fetch = [&](int k0) {
+        if (A_K_FAST) {
+            const int gk = k0 + a_col;
+            int tap = 0, cc = 0;
+            if (AMODE == A_GATHER) { tap = gk / c; cc = gk - tap * c; }
 #pragma unroll
-        for (int uu = 0; uu < A_UNITS; ++uu) {
-            const int f = tid + 256 * uu;
-            f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (A_KC) {
-                const int i = f / (BK / 4), kq = f % (BK / 4);
-                const int gi = m0 + i, gk = k0 + kq * 4;
+            for (int uu = 0; uu < A_UNITS; ++uu) {
+                const int i = a_row0 + uu * A_RSTEP;
+                const int gi = m0 + i;
+                f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
                 if (gi < M && gk < kend) {
-                    const float *src = A + (int64_t)gi * lda + gk;
-                    if (vec_ok && gk + 3 < kend) v = *reinterpret_cast<const f32x4 *>(src);
-                    else {
-                        v[0] = src[0];
-                        if (gk + 1 < kend) v[1] = src[1];
-                        if (gk + 2 < kend) v[2] = src[2];
-                        if (gk + 3 < kend) v[3] = src[3];
+                    if (AMODE == A_ROWS) {
+                        v = load4(A + (int64_t)gi * lda + gk, kend - gk);
+                    } else if (vec_ok) {              // c % 4 == 0: the 4 elements share a tap
+                        const int32_t j = idx[i * 27 + tap];
+                        if (j >= 0) v = *reinterpret_cast<const f32x4 *>(A + (int64_t)j * c + cc);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (gk + e < kend) {
+                                const int t2 = (gk + e) / c;
+                                v[e] = gather1(idx[i * 27 + t2], gk + e - t2 * c);
+                            }
                     }
                 }
-            } else {
-                const int k = f / (BM / 4), iq = f % (BM / 4);
-                const int gk = k0 + k, gi = m0 + iq * 4;
-                if (gk < kend && gi < M) {
-                    const float *src = A + (int64_t)gk * lda + gi;
-                    if (vec_ok && gi + 3 < M) v = *reinterpret_cast<const f32x4 *>(src);
-                    else {
-                        v[0] = src[0];
-                        if (gi + 1 < M) v[1] = src[1];
-                        if (gi + 2 < M) v[2] = src[2];
-                        if (gi + 3 < M) v[3] = src[3];
-                    }
-                }
+                ra[uu] = v;
             }
-            ra[uu] = v;
+        } else {
+            const int gi = m0 + a_col;
+            int tap = 0, cc = 0;
+            if (AMODE == A_GATHER_T) { tap = gi / c; cc = gi - tap * c; }
+#pragma unroll
+            for (int uu = 0; uu < A_UNITS; ++uu) {
+                const int gk = k0 + a_row0 + uu * A_RSTEP;
+                f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (gk < kend && gi < M) {
+                    if (AMODE == A_COLS) {
+                        v = load4(A + (int64_t)gk * lda + gi, M - gi);
+                    } else if (vec_ok) {
+                        const int32_t j = nbr[(int64_t)gk * 27 + tap];
+                        if (j >= 0) v = *reinterpret_cast<const f32x4 *>(A + (int64_t)j * c + cc);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (gi + e < M) {
+                                const int t2 = (gi + e) / c;
+                                v[e] = gather1(nbr[(int64_t)gk * 27 + t2], gi + e - t2 * c);
+                            }
+                    }
+                }
+                ra[uu] = v;
+            }
         }
 #pragma unroll
         for (int uu = 0; uu < B_UNITS; ++uu) {
@@ -246,49 +412,22 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
                 if (B_KC) {
                     const int j = f / (BK / 4), kq = f % (BK / 4);
                     const int gj = n0 + j, gk = k0 + kq * 4;
-                    if (gj < N && gk < kend) {
-                        const float *src = B + (int64_t)gj * ldb + gk;
-                        if (vec_ok && gk + 3 < kend) v = *reinterpret_cast<const f32x4 *>(src);
-                        else {
-                            v[0] = src[0];
-                            if (gk + 1 < kend) v[1] = src[1];
-                            if (gk + 2 < kend) v[2] = src[2];
-                            if (gk + 3 < kend) v[3] = src[3];
-                        }
-                    }
+                    if (gj < N && gk < kend) v = load4(B + (int64_t)gj * ldb + gk, kend - gk);
                 } else {
                     const int k = f / (BN / 4), jq = f % (BN / 4);
                     const int gk = k0 + k, gj = n0 + jq * 4;
-                    if (gk < kend && gj < N) {
-                        const float *src = B + (int64_t)gk * ldb + gj;
-                        if (vec_ok && gj + 3 < N) v = *reinterpret_cast<const f32x4 *>(src);
-                        else {
-                            v[0] = src[0];
-                            if (gj + 1 < N) v[1] = src[1];
-                            if (gj + 2 < N) v[2] = src[2];
-                            if (gj + 3 < N) v[3] = src[3];
-                        }
-                    }
+                    if (gk < kend && gj < N) v = load4(B + (int64_t)gk * ldb + gj, N - gj);
                 }
             }
             rb[uu] = v;
         }
     };
 
-    // registers -> LDS (k-major)
+    // registers -> LDS
     auto stash = [&]() {
 #pragma unroll
-        for (int uu = 0; uu < A_UNITS; ++uu) {
-            const int f = tid + 256 * uu;
-            if (A_KC) {
-                const int i = f / (BK / 4), kq = f % (BK / 4);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) As[(kq * 4 + e) * AS + i] = ra[uu][e];
-            } else {
-                const int k = f / (BM / 4), iq = f % (BM / 4);
-                *reinterpret_cast<f32x4 *>(&As[k * AS + iq * 4]) = ra[uu];
-            }
-        }
+        for (int uu = 0; uu < A_UNITS; ++uu)
+            *reinterpret_cast<f32x4 *>(&As[(a_row0 + uu * A_RSTEP) * AS + a_col]) = ra[uu];
 #pragma unroll
         for (int uu = 0; uu < B_UNITS; ++uu) {
             const int f = tid + 256 * uu;
@@ -312,109 +451,208 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
         stash();
         __syncthreads();
         if (k0 + BK < kend) fetch(k0 + BK);
+        if (A_K_FAST) {
 #pragma unroll
-        for (int kk = 0; kk < BK / 4; ++kk) {
-            float a[2], b[NT];
+            for (int slab = 0; slab < BK / 16; ++slab) {
+                f32x4 a[MT];
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) a[mt] = As[(kk * 4 + lk) * AS + wave * 32 + mt * 16 + li];
+                for (int mt = 0; mt < MT; ++mt)
+                    a[mt] = *reinterpret_cast<const f32x4 *>(&As[(wm * WTM + mt * 16 + li) * AS + slab * 16 + lk * 4]);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) b[nt] = Bs[(kk * 4 + lk) * BS + nt * 16 + li];
+                for (int e = 0; e < 4; ++e) {
+                    const bvec_t b = *reinterpret_cast<const bvec_t *>(&Bs[(slab * 16 + lk * 4 + e) * BS + wn * WTN + li * NT]);
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
+                    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
+                        for (int nt = 0; nt < NT; ++nt)
+                            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[mt][e], vget<NT>(b, nt), acc[mt][nt], 0, 0, 0);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < BK / 4; ++kk) {
+                const avec_t a = *reinterpret_cast<const avec_t *>(&As[(kk * 4 + lk) * AS + wm * WTM + li * MT]);
+                const bvec_t b = *reinterpret_cast<const bvec_t *>(&Bs[(kk * 4 + lk) * BS + wn * WTN + li * NT]);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(vget<MT>(a, mt), vget<NT>(b, nt), acc[mt][nt], 0, 0, 0);
+            }
         }
         __syncthreads();
     }
 
-    // D layout of v_mfma_f32_16x16x4_f32: register e of lane l holds D[4*(l/16) + e][l%16]
+    // D layout of v_mfma_f32_16x16x4_f32: register e of lane l holds D[4*(l/16) + e][l%16].
+    // Lane li fed columns li*NT + nt of the wave's stretch to tile nt, so for one row it holds NT
+    // neighbouring columns.  Rows: tile mt covers mt*16 + r (row-major A) or r*MT + mt (k-major A).
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
+        for (int e = 0; e < 4; ++e) {
+            const int r = 4 * lk + e;
+            const int gi = m0 + wm * WTM + (A_K_FAST ? mt * 16 + r : r * MT + mt);
+            if (gi >= M) continue;
+            const int gj = n0 + wn * WTN + li * NT;
+            float *dst = C + (int64_t)gi * ldc + gj;
+            if (NT == 4 && c_vec_ok && gj + 4 <= N) {
+                *reinterpret_cast<f32x4 *>(dst) = f32x4{acc[mt][0][e], acc[mt][1 % NT][e], acc[mt][2 % NT][e], acc[mt][3 % NT][e]};
+            } else if (NT == 2 && c_vec_ok && gj + 2 <= N) {
+                typedef float f32x2 __attribute__((ext_vector_type(2)));
+                *reinterpret_cast<f32x2 *>(dst) = f32x2{acc[mt][0][e], acc[mt][1 % NT][e]};
+            } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int gi = m0 + wave * 32 + mt * 16 + 4 * lk + e;
-                const int gj = n0 + nt * 16 + li;
-                if (gi < M && gj < N) C[(int64_t)gi * ldc + gj] = acc[mt][nt][e];
+                for (int nt = 0; nt < NT; ++nt)
+                    if (gj + nt < N) dst[nt] = acc[mt][nt][e];
             }
+        }
 }
 
-// out[i] = sum_z part[z*stride + i], z ascending inside four interleaved groups that are then
-// added in group order: the same order on every run.
+// Wt[k][co][ci] = W[26-k][ci][co]: the weights of the convolution that maps output gradients
+// back to the input (Eq.8 read through the symmetry of the 3x3x3 stride-1 neighbourhood)
+__global__ __launch_bounds__(256) void flip_transpose_weights_kernel(
+    const float *__restrict__ W, float *__restrict__ Wt, int c_in, int c_out)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t per = (int64_t)c_in * c_out;
+    if (t >= 27 * per) return;
+    const int k = (int)(t / per);
+    const int r = (int)(t - k * per);
+    const int co = r / c_in, ci = r - co * c_in;
+    Wt[t] = W[((int64_t)(26 - k) * c_in + ci) * c_out + co];
+}
+
+// out[i] = sum_z part[z*stride + i].  A workgroup owns 16 outputs; 16 lanes per output each add
+// every 16th slice (z ascending), then the 16 partial sums are added in lane order: the same
+// order on every run.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(
     const float *__restrict__ part, float *__restrict__ out, int64_t n, int splits, int64_t stride)
 {
-    __shared__ float sh[4][64];
-    const int ex = threadIdx.x & 63, zg = threadIdx.x >> 6;
-    const int64_t i = (int64_t)blockIdx.x * 64 + ex;
+    __shared__ float sh[16][17];
+    const int ex = threadIdx.x & 15, zg = threadIdx.x >> 4;
+    const int64_t i = (int64_t)blockIdx.x * 16 + ex;
     float s = 0.f;
     if (i < n)
-        for (int z = zg; z < splits; z += 4) s += part[(int64_t)z * stride + i];
+        for (int z = zg; z < splits; z += 16) s += part[(int64_t)z * stride + i];
     sh[zg][ex] = s;
     __syncthreads();
-    if (zg == 0 && i < n) out[i] = ((sh[0][ex] + sh[1][ex]) + sh[2][ex]) + sh[3][ex];
+    if (zg == 0 && i < n) {
+        float t = sh[0][ex];
+#pragma unroll
+        for (int q = 1; q < 16; ++q) t += sh[q][ex];
+        out[i] = t;
+    }
 }
 
 // ---------------------------------------------------------------------------------------
-// 2x2x2 max-pooling through the child index rows
+// 2x2x2 max-pooling through the child index rows.  VEC channels per thread (4 when the
+// channel count allows 16-byte accesses).
 // ---------------------------------------------------------------------------------------
 
-// one thread per (coarse voxel, channel); the first occupied child seeds the maximum and a
-// later child replaces it only when strictly greater
+// one thread per (coarse voxel, channel unit); the first occupied child seeds the maximum and
+// a later child replaces it only when strictly greater
+template <int VEC>
 __global__ __launch_bounds__(256) void pool_fwd_kernel(
     const float *__restrict__ X, const int32_t *__restrict__ child8, float *__restrict__ Y,
     int32_t *__restrict__ argmax, int64_t n_coarse, int c)
 {
+    const int cu = c / VEC;
     const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (item >= n_coarse * c) return;
-    const int64_t o = item / c;
-    const int ch = (int)(item - o * c);
+    if (item >= n_coarse * cu) return;
+    const int64_t o = item / cu;
+    const int u = (int)(item - o * cu);
     const int32_t *kids = child8 + o * 8;
-    float best = 0.f;
-    int32_t arg = -1;
+    float best[VEC];
+    int32_t arg[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { best[e] = 0.f; arg[e] = -1; }
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
         const int32_t j = kids[k];
         if (j < 0) continue;
-        const float v = X[(int64_t)j * c + ch];
-        if (arg < 0 || v > best) { best = v; arg = j; }
+        float v[VEC];
+        const float *s = X + (int64_t)j * c + u * VEC;
+        if constexpr (VEC == 4) {
+            const f32x4 t = *reinterpret_cast<const f32x4 *>(s);
+            v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+        } else {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) v[e] = s[e];
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+            if (arg[e] < 0 || v[e] > best[e]) { best[e] = v[e]; arg[e] = j; }
     }
-    Y[item] = best;
-    argmax[item] = arg;
+    float *dy = Y + o * c + u * VEC;
+    int32_t *da = argmax + o * c + u * VEC;
+    if constexpr (VEC == 4) {
+        *reinterpret_cast<f32x4 *>(dy) = f32x4{best[0], best[1], best[2], best[3]};
+        *reinterpret_cast<int4 *>(da) = make_int4(arg[0], arg[1], arg[2], arg[3]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { dy[e] = best[e]; da[e] = arg[e]; }
+    }
 }
 
-// one thread per (coarse voxel, child, channel): every fine row is the child of exactly one
-// coarse voxel, so this writes all of dX exactly once (the zero fill is part of it)
+// one thread per (coarse voxel, child, channel unit): every fine row is the child of exactly
+// one coarse voxel, so this writes all of dX exactly once (the zero fill is part of it)
+template <int VEC>
 __global__ __launch_bounds__(256) void pool_bwd_kernel(
     const float *__restrict__ dY, const int32_t *__restrict__ argmax,
     const int32_t *__restrict__ child8, float *__restrict__ dX, int64_t n_coarse, int c)
 {
+    const int cu = c / VEC;
     const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (item >= n_coarse * 8 * c) return;
-    const int64_t ok = item / c;            // coarse voxel * 8 + child
-    const int ch = (int)(item - ok * c);
+    if (item >= n_coarse * 8 * cu) return;
+    const int64_t ok = item / cu;            // coarse voxel * 8 + child
+    const int u = (int)(item - ok * cu);
     const int32_t j = child8[ok];
     if (j < 0) return;
     const int64_t o = ok >> 3;
-    const float g = dY[o * c + ch];
-    dX[(int64_t)j * c + ch] = (argmax[o * c + ch] == j) ? g : 0.f;
+    const float *g = dY + o * c + u * VEC;
+    const int32_t *a = argmax + o * c + u * VEC;
+    float *d = dX + (int64_t)j * c + u * VEC;
+    if constexpr (VEC == 4) {
+        const f32x4 gv = *reinterpret_cast<const f32x4 *>(g);
+        const int4 av = *reinterpret_cast<const int4 *>(a);
+        *reinterpret_cast<f32x4 *>(d) = f32x4{av.x == j ? gv[0] : 0.f, av.y == j ? gv[1] : 0.f,
+                                             av.z == j ? gv[2] : 0.f, av.w == j ? gv[3] : 0.f};
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) d[e] = (a[e] == j) ? g[e] : 0.f;
+    }
 }
 
+// element-wise ReLU; n4 = number of float4 units, the remaining n - 4*n4 floats are done one
+// per thread by the first threads (n4 = 0 when the pointers are not 16-byte aligned)
 __global__ __launch_bounds__(256) void relu_fwd_kernel(const float *__restrict__ x,
-                                                       float *__restrict__ y, int64_t n)
+                                                       float *__restrict__ y, int64_t n, int64_t n4)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) { const float v = x[i]; y[i] = v > 0.f ? v : 0.f; }
+    if (i < n4) {
+        f32x4 v = reinterpret_cast<const f32x4 *>(x)[i];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+        reinterpret_cast<f32x4 *>(y)[i] = v;
+    }
+    const int64_t t = 4 * n4 + i;
+    if (t < n) { const float v = x[t]; y[t] = v > 0.f ? v : 0.f; }
 }
 
 __global__ __launch_bounds__(256) void relu_bwd_kernel(const float *__restrict__ y,
                                                        const float *__restrict__ dy,
-                                                       float *__restrict__ dx, int64_t n)
+                                                       float *__restrict__ dx, int64_t n, int64_t n4)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) dx[i] = y[i] > 0.f ? dy[i] : 0.f;
+    if (i < n4) {
+        const f32x4 a = reinterpret_cast<const f32x4 *>(y)[i];
+        f32x4 g = reinterpret_cast<const f32x4 *>(dy)[i];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) g[e] = a[e] > 0.f ? g[e] : 0.f;
+        reinterpret_cast<f32x4 *>(dx)[i] = g;
+    }
+    const int64_t t = 4 * n4 + i;
+    if (t < n) dx[t] = y[t] > 0.f ? dy[t] : 0.f;
 }
 
 }  // namespace hch

@@ -12,10 +12,11 @@
 namespace hch {
 
 enum KernelId : int {
-    K_FIELD_INDEX = 0,
+    K_NEIGHBOUR = 0, K_CHILD,
     K_HASH2COL_VEC, K_HASH2COL_ELEM,
     K_COL2HASH,
-    K_GEMM_FWD, K_GEMM_DGRAD, K_GEMM_WGRAD, K_SPLITK_REDUCE,
+    K_GEMM_ROWS, K_GEMM_ROWS_BT, K_GEMM_COLS, K_GEMM_GATHER, K_GEMM_GATHER_T, K_FLIP_WEIGHTS,
+    K_SPLITK_REDUCE,
     K_POOL_FWD, K_POOL_BWD, K_RELU_FWD, K_RELU_BWD,
     K_COUNT
 };
@@ -23,8 +24,9 @@ enum KernelId : int {
 inline const char *kernel_name(int id)
 {
     static const char *names[K_COUNT] = {
-        "field_index_kernel", "hash2col_vec_kernel", "hash2col_elem_kernel", "col2hash_kernel",
-        "gemm_f32_kernel<fwd>", "gemm_f32_kernel<dgrad>", "gemm_f32_kernel<wgrad>",
+        "neighbour_kernel", "child_kernel", "hash2col_kernel<uint4>", "hash2col_kernel<elem>", "col2hash_kernel",
+        "gemm_f32_kernel<A_ROWS,B_KC=0>", "gemm_f32_kernel<A_ROWS,B_KC=1>", "gemm_f32_kernel<A_COLS>",
+        "gemm_f32_kernel<A_GATHER>", "gemm_f32_kernel<A_GATHER_T>", "flip_transpose_weights_kernel",
         "splitk_reduce_kernel", "pool_fwd_kernel", "pool_bwd_kernel", "relu_fwd_kernel",
         "relu_bwd_kernel"};
     return (id >= 0 && id < K_COUNT) ? names[id] : "";

@@ -18,8 +18,8 @@ class Encoder:
     """channels = [c0, c1, ..., cL]: level l runs conv c_l -> c_{l+1}, ReLU, pool to level l+1.
     `levels` must hold L+1 levels.  All buffers are allocated once here."""
 
-    def __init__(self, levels, channels, device="cuda"):
-        self.levels, self.channels = levels, list(channels)
+    def __init__(self, levels, channels, algo=B.HCH_ALGO_COLUMNS, device="cuda"):
+        self.levels, self.channels, self.algo = levels, list(channels), algo
         self.L = len(channels) - 1
         assert levels.n_levels >= self.L + 1
         self.n = [levels.n(l) for l in range(self.L + 1)]
@@ -38,7 +38,7 @@ class Encoder:
         need = 256
         for l in range(self.L):
             for kind in (B.HCH_WS_FWD, B.HCH_WS_BWD_DATA, B.HCH_WS_BWD_WEIGHT):
-                need = max(need, B.hch_conv_workspace_bytes(levels, l, ch[l], ch[l + 1], B.HCH_F32, kind))
+                need = max(need, B.hch_conv_workspace_bytes(levels, l, ch[l], ch[l + 1], B.HCH_F32, kind, algo))
         self.ws = _aligned_bytes(need, device)
 
     def flops_per_step(self):
@@ -53,7 +53,8 @@ class Encoder:
     def forward(self):
         ch = self.channels
         for l in range(self.L):
-            B.hch_conv_fwd(self.levels, l, B.HCH_F32, self.X[l], self.W[l], self.Y[l], ch[l], ch[l + 1], self.ws)
+            B.hch_conv_fwd(self.levels, l, B.HCH_F32, self.X[l], self.W[l], self.Y[l], ch[l], ch[l + 1], self.ws,
+                           self.algo)
             B.hch_relu_fwd(self.Y[l], self.A[l], self.A[l].numel())
             B.hch_pool_fwd(self.levels, l, self.A[l], self.X[l + 1], self.sw[l], ch[l + 1])
 
@@ -62,8 +63,10 @@ class Encoder:
         for l in reversed(range(self.L)):
             B.hch_pool_bwd(self.levels, l, self.dX[l + 1], self.sw[l], self.dA[l], ch[l + 1])
             B.hch_relu_bwd(self.A[l], self.dA[l], self.dY[l], self.dY[l].numel())
-            B.hch_conv_bwd_weight(self.levels, l, B.HCH_F32, self.X[l], self.dY[l], self.dW[l], ch[l], ch[l + 1], self.ws)
-            B.hch_conv_bwd_data(self.levels, l, B.HCH_F32, self.dY[l], self.W[l], self.dX[l], ch[l], ch[l + 1], self.ws)
+            B.hch_conv_bwd_weight(self.levels, l, B.HCH_F32, self.X[l], self.dY[l], self.dW[l], ch[l], ch[l + 1], self.ws,
+                                  self.algo)
+            B.hch_conv_bwd_data(self.levels, l, B.HCH_F32, self.dY[l], self.W[l], self.dX[l], ch[l], ch[l + 1], self.ws,
+                                self.algo)
 
     def step(self):
         """One pass of the whole hot path: index lists by hash lookup, forward, backward."""

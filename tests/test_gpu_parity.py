@@ -160,23 +160,28 @@ def test_col2hash(oracle, case_small, c_in):
 # convolution forward and backward
 # --------------------------------------------------------------------------------------
 
-def _conv_fwd_gpu(case, level, X, W, ws_bytes=None):
+ALGOS = [hch.HCH_ALGO_COLUMNS, hch.HCH_ALGO_FUSED]
+ALGO_IDS = ["columns", "fused"]
+
+
+def _conv_fwd_gpu(case, level, X, W, ws_bytes=None, algo=hch.HCH_ALGO_COLUMNS):
     n, c_in = X.shape
     c_out = W.shape[2]
     if ws_bytes is None:
-        ws_bytes = hch.hch_conv_workspace_bytes(case.glv, level, c_in, c_out, hch.HCH_F32, hch.HCH_WS_FWD)
+        ws_bytes = hch.hch_conv_workspace_bytes(case.glv, level, c_in, c_out, hch.HCH_F32, hch.HCH_WS_FWD, algo)
     ws = workspace(ws_bytes)
     Y = torch.full((n, c_out), float("nan"), dtype=torch.float32, device="cuda")
-    hch.hch_conv_fwd(case.glv, level, hch.HCH_F32, dev(X), dev(W), Y, c_in, c_out, ws)
+    hch.hch_conv_fwd(case.glv, level, hch.HCH_F32, dev(X), dev(W), Y, c_in, c_out, ws, algo)
     return Y.cpu().numpy()
 
 
-def test_conv_fwd_sphere_3_to_16(oracle, case_sphere):
+@pytest.mark.parametrize("algo", ALGOS, ids=ALGO_IDS)
+def test_conv_fwd_sphere_3_to_16(oracle, case_sphere, algo):
     """Single shape, 32^3, 3 -> 16 channels, weights N(0, 0.1) seed 0, then max-pool to 16^3."""
     case = case_sphere
     L = case.olv[0]
     W = S.gaussian((27, 3, 16), 0.1, 0)
-    Y = _conv_fwd_gpu(case, 0, case.normals, W)
+    Y = _conv_fwd_gpu(case, 0, case.normals, W, algo=algo)
     want = oracle.conv_fwd(L, oracle.to_paper_X(case.normals), oracle.to_paper_W(W))
     assert_close(Y, want.T, what="conv fwd sphere")
     # pool the GPU's own conv output on both sides: same fp32 inputs, so the switches must agree
@@ -188,20 +193,25 @@ def test_conv_fwd_sphere_3_to_16(oracle, case_sphere):
     assert np.array_equal(Yp.cpu().numpy(), Po.T.astype(np.float32))
 
 
-def test_conv_fwd_batch64_4_to_32(oracle, case_batch64):
+@pytest.mark.parametrize("algo", ALGOS, ids=ALGO_IDS)
+def test_conv_fwd_batch64_4_to_32(oracle, case_batch64, algo):
     case = case_batch64
     L = case.olv[0]
     X = S.normals_plus_one(case.normals)
     W = S.gaussian((27, 4, 32), 0.05, 2000)
     want = oracle.conv_fwd(L, oracle.to_paper_X(X), oracle.to_paper_W(W)).T
-    assert_close(_conv_fwd_gpu(case, 0, X, W), want, what="conv fwd 4->32")
+    assert_close(_conv_fwd_gpu(case, 0, X, W, algo=algo), want, what="conv fwd 4->32")
+    if algo == hch.HCH_ALGO_FUSED:
+        return
     # the same through a workspace that forces several chunks
     small = hch.hch_conv_workspace_bytes(case.glv, 0, 4, 32, hch.HCH_F32, hch.HCH_WS_MIN)
     assert_close(_conv_fwd_gpu(case, 0, X, W, ws_bytes=small * 5 + 4096), want, what="conv fwd chunked")
 
 
-@pytest.mark.parametrize("c_in,c_out,level", [(32, 64, 0), (16, 32, 1), (5, 7, 1), (64, 128, 2), (8, 80, 2)])
-def test_conv_fwd_and_gradients(oracle, case_small, c_in, c_out, level):
+@pytest.mark.parametrize("algo", ALGOS, ids=ALGO_IDS)
+@pytest.mark.parametrize("c_in,c_out,level", [(32, 64, 0), (16, 32, 1), (5, 7, 1), (64, 128, 2), (8, 80, 2),
+                                              (128, 256, 2), (4, 16, 0)])
+def test_conv_fwd_and_gradients(oracle, case_small, c_in, c_out, level, algo):
     case = case_small
     L = case.olv[level]
     n = L.Ntot
@@ -210,20 +220,20 @@ def test_conv_fwd_and_gradients(oracle, case_small, c_in, c_out, level):
     G = S.gaussian((n, c_out), 1.0, 23)
     Xp, Wp, Gp = oracle.to_paper_X(X), oracle.to_paper_W(W), oracle.to_paper_X(G)
 
-    assert_close(_conv_fwd_gpu(case, level, X, W), oracle.conv_fwd(L, Xp, Wp).T, what="fwd")
+    assert_close(_conv_fwd_gpu(case, level, X, W, algo=algo), oracle.conv_fwd(L, Xp, Wp).T, what="fwd")
 
-    ws = workspace(hch.hch_conv_workspace_bytes(case.glv, level, c_in, c_out, hch.HCH_F32, hch.HCH_WS_BWD_DATA))
+    ws = workspace(hch.hch_conv_workspace_bytes(case.glv, level, c_in, c_out, hch.HCH_F32, hch.HCH_WS_BWD_DATA, algo))
     dX = torch.full((n, c_in), float("nan"), dtype=torch.float32, device="cuda")
-    hch.hch_conv_bwd_data(case.glv, level, hch.HCH_F32, dev(G), dev(W), dX, c_in, c_out, ws)
+    hch.hch_conv_bwd_data(case.glv, level, hch.HCH_F32, dev(G), dev(W), dX, c_in, c_out, ws, algo)
     assert_close(dX.cpu().numpy(), oracle.conv_bwd_data(L, Gp, Wp, c_in).T, what="bwd data")
 
-    ws = workspace(hch.hch_conv_workspace_bytes(case.glv, level, c_in, c_out, hch.HCH_F32, hch.HCH_WS_BWD_WEIGHT))
+    ws = workspace(hch.hch_conv_workspace_bytes(case.glv, level, c_in, c_out, hch.HCH_F32, hch.HCH_WS_BWD_WEIGHT, algo))
     dW = torch.full((27, c_in, c_out), float("nan"), dtype=torch.float32, device="cuda")
-    hch.hch_conv_bwd_weight(case.glv, level, hch.HCH_F32, dev(X), dev(G), dW, c_in, c_out, ws)
+    hch.hch_conv_bwd_weight(case.glv, level, hch.HCH_F32, dev(X), dev(G), dW, c_in, c_out, ws, algo)
     want_dW = oracle.from_paper_W(oracle.conv_bwd_weight(L, Xp, Gp), c_in)
     assert_close(dW.cpu().numpy(), want_dW, what="bwd weight")
     dW2 = torch.empty_like(dW)
-    hch.hch_conv_bwd_weight(case.glv, level, hch.HCH_F32, dev(X), dev(G), dW2, c_in, c_out, ws)
+    hch.hch_conv_bwd_weight(case.glv, level, hch.HCH_F32, dev(X), dev(G), dW2, c_in, c_out, ws, algo)
     assert torch.equal(dW, dW2)
 
 
