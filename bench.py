@@ -86,7 +86,8 @@ def main():
     ap.add_argument("--batch", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-all", action="store_true", help="time every kernel (adds event overhead)")
-    ap.add_argument("--algo", choices=["columns", "fused"], default="columns",
+    ap.add_argument("--no-other-algo", action="store_true", help="skip the second, fully timed pass")
+    ap.add_argument("--algo", choices=["columns", "fused"], default="fused",
                     help="columns: hash2col -> GEMM -> col2hash through memory; fused: gathered GEMM operand")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -115,17 +116,53 @@ def main():
     enc.dX[5].copy_(torch.from_numpy(S.gaussian((enc.n[5], CHANNELS[5]), 1.0, 4100)))
     torch.cuda.synchronize()
 
-    nk = hch.hch_kernel_count()
-    names = [hch.hch_kernel_name(i) for i in range(nk)]
+    def kernel_table():
+        out = {}
+        for i in range(hch.hch_kernel_count()):
+            st = hch.hch_profile_read(i)
+            if st["launches"]:
+                out[hch.hch_kernel_name(i)] = (i, st)
+        return out
+
+    def roofline_of(name, st, steps):
+        """achieved = algorithmic bytes (or flops) of the timed launches / their event-measured
+        time; a kernel counts as MFMA-bound when its arithmetic intensity is above the ridge."""
+        ai = st["flops"] / max(1.0, st["bytes"])
+        if "gemm" in name and ai >= MFMA_F32_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
+            bound, achieved, peak, unit = "mfma", st["flops"] / (st["ms"] * 1e-3) / 1e12, MFMA_F32_PEAK_TFLOPS, "TFLOP/s"
+        else:
+            bound, achieved, peak, unit = "hbm", st["bytes"] / (st["ms"] * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
+        return {"kernel": name, "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
+                "frac": round(achieved / peak, 4), "traffic": traffic_of(name),
+                "launches_per_step": st["launches"] / steps,
+                "avg_launch_ms": round(st["ms"] / max(1, st["launches"]), 5),
+                "algorithmic_bytes_per_launch": round(st["bytes"] / max(1, st["launches"])),
+                "flops_per_launch": round(st["flops"] / max(1, st["launches"]))}
+
+    traffic_db = {}
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic_db = json.load(open(tpath))
+        except Exception:
+            traffic_db = {}
+
+    def traffic_of(name):
+        """HBM bytes per launch from the committed rocprofv3 --pmc summary, if it has this
+        kernel on this workload (the counters cannot be read from inside this process)."""
+        return traffic_db.get(f"{u}^3x{b}", {}).get(args.algo, {}).get(name)
 
     # warm-up; the first warm-up step times every kernel to find the dominant one
     hch.hch_profile_reset()
-    hch.hch_profile_enable((1 << nk) - 1)
+    hch.hch_profile_enable(-1, True)
     enc.step()
     torch.cuda.synchronize()
-    per_kernel = {names[i]: hch.hch_profile_read(i) for i in range(nk)}
-    dominant = max(range(nk), key=lambda i: per_kernel[names[i]]["ms"])
-    hch.hch_profile_enable((1 << nk) - 1 if args.profile_all else (1 << dominant))
+    first = kernel_table()
+    dom_name = max(first, key=lambda k: first[k][1]["ms"])
+    dominant = first[dom_name][0]
+    if not args.profile_all:
+        hch.hch_profile_enable(-1, False)
+        hch.hch_profile_enable(dominant, True)
     for _ in range(max(0, args.warmup - 1)):
         enc.step()
     torch.cuda.synchronize()
@@ -137,31 +174,12 @@ def main():
         enc.step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    hch.hch_profile_enable(0)
+    hch.hch_profile_enable(-1, False)
 
     ms_per_step = dt / args.steps * 1e3
     flops = enc.flops_per_step()
     value = flops / (ms_per_step * 1e-3) / 1e12
-
-    st = hch.hch_profile_read(dominant)
-    avg_ms = st["ms"] / max(1, st["launches"])
-    ai = st["flops"] / max(1.0, st["bytes"])
-    if st["flops"] > 0 and ai >= MFMA_F32_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
-        bound, achieved, peak, unit = "mfma", st["flops"] / (st["ms"] * 1e-3) / 1e12, MFMA_F32_PEAK_TFLOPS, "TFLOP/s"
-    else:
-        bound, achieved, peak, unit = "hbm", st["bytes"] / (st["ms"] * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(names[dominant], {}).get(f"{u}^3x{b}")
-        except Exception:
-            traffic = None
-    roofline = {"kernel": names[dominant], "bound": bound, "achieved": round(achieved, 3), "peak": peak,
-                "unit": unit, "frac": round(achieved / peak, 4), "traffic": traffic,
-                "launches_per_step": st["launches"] / args.steps, "avg_launch_ms": round(avg_ms, 5),
-                "algorithmic_bytes_per_launch": st["bytes"] / max(1, st["launches"]),
-                "flops_per_launch": st["flops"] / max(1, st["launches"])}
+    roofline = roofline_of(dom_name, hch.hch_profile_read(dominant), args.steps)
 
     out = {
         "metric": "sparse conv fwd+bwd TFLOP/s and gather/scatter HBM GB/s, 256^3 grid, batch 8",
@@ -174,8 +192,38 @@ def main():
                    "gflop_per_step": round(flops / 1e9, 3), "psh_build_s": round(t_build, 2),
                    "shape_gen_s": round(t_gen, 2)},
         "roofline": roofline,
-        "kernels_ms_first_step": {k: round(v["ms"], 4) for k, v in per_kernel.items() if v["launches"]},
+        "kernels_ms_first_step": {k: round(v[1]["ms"], 4) for k, v in first.items()},
     }
+
+    if not args.no_other_algo:
+        # the other algorithm on the same inputs, every kernel timed (event overhead included in
+        # its step time): per-kernel rooflines of the gather, GEMM and scatter kernels
+        other = "columns" if args.algo == "fused" else "fused"
+        enc2 = Encoder(levels, CHANNELS, hch.HCH_ALGO_COLUMNS if other == "columns" else hch.HCH_ALGO_FUSED)
+        enc2.X[0].copy_(enc.X[0]); enc2.dX[5].copy_(enc.dX[5])
+        for l in range(5):
+            enc2.W[l].copy_(enc.W[l])
+        for _ in range(2):
+            enc2.step()
+        torch.cuda.synchronize()
+        hch.hch_profile_reset()
+        hch.hch_profile_enable(-1, True)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            enc2.step()
+        torch.cuda.synchronize()
+        dt2 = time.perf_counter() - t0
+        hch.hch_profile_enable(-1, False)
+        save_algo, args.algo = args.algo, other
+        tab = kernel_table()
+        out["other_algo"] = {
+            "algo": other, "ms_per_step_all_kernels_timed": round(dt2 / args.steps * 1e3, 4),
+            "value": round(flops / (dt2 / args.steps) / 1e12, 4), "unit": "TFLOP/s",
+            "kernels": [roofline_of(k, v[1], args.steps) for k, v in
+                        sorted(tab.items(), key=lambda kv: -kv[1][1]["ms"])
+                        if any(t in k for t in ("hash2col", "col2hash", "gemm", "neighbour"))],
+        }
+        args.algo = save_algo
     if not args.no_cpu_baseline:
         v, cores, note = cpu_baseline(coords, offs, X0, W, u, b)
         out["cpu_baseline"] = {"value": round(v, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",

@@ -239,14 +239,16 @@ hch_status hch_relu_fwd(const float *x, float *y, int64_t n, void *stream);
 hch_status hch_relu_bwd(const float *y, const float *dy, float *dx, int64_t n, void *stream);
 
 /*
- * Optional per-kernel timing, for benchmarks.  Each kernel of the library has an id in
- * [0, hch_kernel_count()); hch_kernel_name gives the name of its __global__ function.
- * hch_profile_enable(mask): launches of kernel i are bracketed by two HIP events on their
- * stream while bit i of mask is set (0 = off, the default).  hch_profile_read blocks until the
- * bracketed launches so far have finished and returns, for one kernel, the number of timed
- * launches, the sum of their durations, and the sums of their ALGORITHMIC bytes and flops
- * (every operand moved once, as counted from the launch's shapes; not a hardware counter).
- * hch_profile_reset clears the sums.
+ * Optional per-kernel timing, for benchmarks.  A kernel gets an id in [0, hch_kernel_count())
+ * the first time it is launched; hch_kernel_name gives the name of its __global__ function,
+ * template arguments included, as a profiler prints it (the pointer is valid until the next
+ * call on the same thread).  hch_profile_enable(id, on): launches of that kernel are bracketed
+ * by two HIP events on their stream while on != 0; id = -1 switches every kernel, also ones
+ * that have not run yet.  Off by default.  hch_profile_read blocks until the bracketed launches
+ * so far have finished and returns, for one kernel, the number of timed launches, the sum of
+ * their durations, and the sums of their ALGORITHMIC bytes and flops (every operand moved
+ * once, as counted from the launch's shapes; not a hardware counter).  hch_profile_reset clears
+ * the sums.
  */
 typedef struct {
     int64_t launches;
@@ -257,7 +259,7 @@ typedef struct {
 
 int32_t hch_kernel_count(void);
 const char *hch_kernel_name(int32_t kernel_id);
-hch_status hch_profile_enable(uint64_t kernel_mask);
+hch_status hch_profile_enable(int32_t kernel_id, int32_t on);
 hch_status hch_profile_read(int32_t kernel_id, hch_kernel_stats *out);
 hch_status hch_profile_reset(void);
 

@@ -98,7 +98,7 @@ def load_library():
     L.hch_kernel_count.restype = i32
     L.hch_kernel_name.argtypes = [i32]
     L.hch_kernel_name.restype = C.c_char_p
-    L.hch_profile_enable.argtypes = [C.c_uint64]
+    L.hch_profile_enable.argtypes = [i32, i32]
     L.hch_profile_read.argtypes = [i32, C.POINTER(_KernelStats)]
     _lib = L
     return L
@@ -353,8 +353,8 @@ def hch_kernel_name(kernel_id):
     return load_library().hch_kernel_name(kernel_id).decode()
 
 
-def hch_profile_enable(mask):
-    _check(load_library().hch_profile_enable(int(mask)))
+def hch_profile_enable(kernel_id, on):
+    _check(load_library().hch_profile_enable(int(kernel_id), int(bool(on))))
 
 
 def hch_profile_read(kernel_id):

@@ -124,7 +124,7 @@ static hch_status launch_neighbours(const Level &L, hipStream_t s)
     {
         // per voxel: its position in, 27 indices out; the level's tables once
         const double bytes = (double)L.n_total * (12.0 + 108.0) + (double)L.m_total * 10.0 + (double)L.r_total * 3.0;
-        hch::LaunchTimer lt(hch::K_NEIGHBOUR, s, bytes, 0.0);
+        hch::LaunchTimer lt(HCH_KERNEL_ID("neighbour_kernel"), s, bytes, 0.0);
         hipLaunchKernelGGL(hch::neighbour_kernel, grid, dim3(256), 0, s, L.view(), L.dcoords, L.dnbr);
     }
     HCH_LAUNCH_CHECK("neighbour_kernel");
@@ -137,7 +137,7 @@ static hch_status launch_children(const Level &Lf, const Level &Lc, hipStream_t 
     dim3 grid(blocks_for(Lc.max_n), (unsigned)Lc.b);
     {
         const double bytes = (double)Lc.n_total * (12.0 + 32.0) + (double)Lf.m_total * 10.0 + (double)Lf.r_total * 3.0;
-        hch::LaunchTimer lt(hch::K_CHILD, s, bytes, 0.0);
+        hch::LaunchTimer lt(HCH_KERNEL_ID("child_kernel"), s, bytes, 0.0);
         hipLaunchKernelGGL(hch::child_kernel, grid, dim3(256), 0, s, Lf.view(), Lc.dcoords, Lc.dN(), Lc.dchild);
     }
     HCH_LAUNCH_CHECK("child_kernel");
@@ -409,11 +409,11 @@ static hch_status do_hash2col(const Level &L, hch_dtype dtype, const void *X, in
     const unsigned n_tiles = (unsigned)((rows + tv - 1) / tv);
     const unsigned grid = (n_tiles + hch::NUM_XCD - 1) / hch::NUM_XCD * hch::NUM_XCD;
     if (row_bytes % 16 == 0 && aligned16(X) && aligned16(col)) {
-        hch::LaunchTimer lt(hch::K_HASH2COL_VEC, s, bytes, 0.0);
+        hch::LaunchTimer lt(HCH_KERNEL_ID("hash2col_kernel<HIP_vector_type<unsigned int, 4u> >"), s, bytes, 0.0);
         hipLaunchKernelGGL(hch::hash2col_kernel<uint4>, dim3(grid), dim3(256), 0, s,
                            (const uint4 *)X, L.dnbr, (uint4 *)col, row_begin, rows, row_bytes / 16, tv, n_tiles);
     } else {
-        hch::LaunchTimer lt(hch::K_HASH2COL_ELEM, s, bytes, 0.0);
+        hch::LaunchTimer lt(dtype == HCH_F32 ? HCH_KERNEL_ID("hash2col_kernel<float>") : HCH_KERNEL_ID("hash2col_kernel<unsigned short>"), s, bytes, 0.0);
         if (dtype == HCH_F32)
             hipLaunchKernelGGL(hch::hash2col_kernel<float>, dim3(grid), dim3(256), 0, s,
                                (const float *)X, L.dnbr, (float *)col, row_begin, rows, c_in, tv, n_tiles);
@@ -444,8 +444,8 @@ static hch_status do_col2hash(const Level &L, const float *dcol, int c_in, float
     if (L.n_total == 0) return HCH_OK;
     // per voxel: 27 indices in, one c_in row per occupied neighbour in, one row out
     const double bytes = (double)L.n_total * (108.0 + 4.0 * c_in) + (double)L.nbr_valid * 4.0 * c_in;
-    hch::LaunchTimer lt(hch::K_COL2HASH, s, bytes, (double)L.nbr_valid * c_in);
     const bool vec = c_in % 4 == 0 && aligned16(dcol) && aligned16(dX);
+    hch::LaunchTimer lt((vec ? HCH_KERNEL_ID("col2hash_kernel<4>") : HCH_KERNEL_ID("col2hash_kernel<1>")), s, bytes, (double)L.nbr_valid * c_in);
     const int cu = vec ? c_in / 4 : c_in;
     const int tv = std::max(4, std::min(256, 256 / cu));
     const unsigned n_tiles = (unsigned)((L.n_total + tv - 1) / tv);
@@ -520,7 +520,7 @@ static GemmPlan plan_wgrad(int64_t n, int c_in, int c_out)
 }
 
 template <int AMODE, bool B_KC>
-static hch_status launch_gemm(int kernel_id, const GemmPlan &p, const float *A, const float *B, float *C,
+static hch_status launch_gemm(const GemmPlan &p, const float *A, const float *B, float *C,
                               const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
                               int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s)
 {
@@ -529,10 +529,23 @@ static hch_status launch_gemm(int kernel_id, const GemmPlan &p, const float *A, 
     const int vec_ok = (lda % 4 == 0) && (ldb % 4 == 0) && aligned16(A) && aligned16(B);
     const int c_vec_ok = (ldc % 4 == 0) && (c_split_stride % 4 == 0) && aligned16(C);
     const unsigned m_tiles = (unsigned)((M + p.bm - 1) / p.bm);
-    const unsigned gx = (m_tiles + hch::NUM_XCD - 1) / hch::NUM_XCD * hch::NUM_XCD;
+    // XCD-contiguous row tiles only where rows are voxels and there are enough tiles to keep
+    // every XCD busy (an exact multiple of 8 cannot be told apart from the plain order, so
+    // pad it by 8 as well)
+    const bool remap = (AMODE == hch::A_GATHER || AMODE == hch::A_ROWS) && m_tiles >= 256;
+    const unsigned gx = remap ? (m_tiles / hch::NUM_XCD + 1) * hch::NUM_XCD : m_tiles;
     const dim3 grid(gx, (unsigned)((N + p.bn - 1) / p.bn), (unsigned)p.splits);
     (void)gather;
-    hch::LaunchTimer lt(kernel_id, s, alg_bytes, 2.0 * M * (double)N * K);
+    // the kernel's name as a profiler prints it: gemm_f32_kernel<BM, BN, BK, WM, AMODE, B_KC>
+    static int ids[4] = {-1, -1, -1, -1};
+    const int cfg = p.bm == 64 ? 0 : (p.bn == 16 ? 1 : (p.bn == 32 ? 2 : 3));
+    if (ids[cfg] < 0) {
+        char nm[96];
+        snprintf(nm, sizeof nm, "gemm_f32_kernel<%d, %d, 32, %d, %d, %s>", p.bm, p.bm == 64 ? 64 : p.bn, p.wm,
+                 (int)AMODE, B_KC ? "true" : "false");
+        ids[cfg] = hch::Profiler::get().id_for(nm);
+    }
+    hch::LaunchTimer lt(ids[cfg], s, alg_bytes, 2.0 * M * (double)N * K);
 #define HCH_GEMM_CASE(BM_, BN_, BK_, WM_)                                                               \
     hipLaunchKernelGGL((hch::gemm_f32_kernel<BM_, BN_, BK_, WM_, AMODE, B_KC>), grid, dim3(256), 0, s, \
                        A, B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split, c_split_stride, vec_ok,     \
@@ -548,9 +561,17 @@ static hch_status launch_gemm(int kernel_id, const GemmPlan &p, const float *A, 
 
 static hch_status launch_reduce(const float *part, float *out, int64_t n, int splits, hipStream_t s)
 {
-    hch::LaunchTimer lt(hch::K_SPLITK_REDUCE, s, 4.0 * n * (splits + 1.0), (double)n * splits);
-    hipLaunchKernelGGL(hch::splitk_reduce_kernel, dim3((unsigned)((n + 15) / 16)), dim3(256), 0, s,
-                       part, out, n, splits, n);
+    const int kid = splits <= 16 ? HCH_KERNEL_ID("splitk_reduce_kernel<1>")
+                    : (n >= 65536 || splits <= 256 ? HCH_KERNEL_ID("splitk_reduce_kernel<16>") : HCH_KERNEL_ID("splitk_reduce_kernel<64>"));
+    hch::LaunchTimer lt(kid, s, 4.0 * n * (splits + 1.0), (double)n * splits);
+    // few slices: a thread per output; many slices: 16 or 64 lanes per output, so that even a
+    // small output (a 27 x 4 x 16 weight gradient) spreads over a few hundred workgroups
+    if (splits <= 16)
+        hipLaunchKernelGGL(hch::splitk_reduce_kernel<1>, dim3(blocks_for(n)), dim3(256), 0, s, part, out, n, splits, n);
+    else if (n >= 65536 || splits <= 256)
+        hipLaunchKernelGGL(hch::splitk_reduce_kernel<16>, dim3((unsigned)((n + 15) / 16)), dim3(256), 0, s, part, out, n, splits, n);
+    else
+        hipLaunchKernelGGL(hch::splitk_reduce_kernel<64>, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, s, part, out, n, splits, n);
     HCH_LAUNCH_CHECK("splitk_reduce_kernel");
     return HCH_OK;
 }
@@ -648,7 +669,7 @@ extern "C" hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_
         // Y = gathered columns . W, the column matrix never leaves the chip.  Per voxel: 27
         // indices and its feature row in, one output row out; the weights once.
         const double bytes = (double)n * (108.0 + 4.0 * c_in + 4.0 * c_out * p.splits) + 4.0 * Kc * c_out;
-        st = launch_gemm<hch::A_GATHER, false>(hch::K_GEMM_GATHER, p, (const float *)X, (const float *)W,
+        st = launch_gemm<hch::A_GATHER, false>(p, (const float *)X, (const float *)W,
                                                p.splits > 1 ? part : Y, L->dnbr, (int)n, c_out, Kc, c_in,
                                                c_out, c_out, n * c_out, bytes, s);
         if (st != HCH_OK) return st;
@@ -665,7 +686,7 @@ extern "C" hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_
         if (st != HCH_OK) return st;
         const double bytes = 4.0 * ((double)rows * Kc + (double)Kc * c_out + (double)rows * c_out * p.splits);
         // the split plan was made for all n rows; slices of a chunk land in the same places
-        st = launch_gemm<hch::A_ROWS, false>(hch::K_GEMM_ROWS, p, (const float *)workspace, (const float *)W,
+        st = launch_gemm<hch::A_ROWS, false>(p, (const float *)workspace, (const float *)W,
                                              p.splits > 1 ? part + r0 * c_out : Y + r0 * c_out, nullptr,
                                              (int)rows, c_out, Kc, Kc, c_out, c_out, n * c_out, bytes, s);
         if (st != HCH_OK) return st;
@@ -696,7 +717,7 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
         float *part = (float *)((char *)workspace + w.first_bytes);
         const int64_t wn = (int64_t)Kc * c_out;
         {
-            hch::LaunchTimer lt(hch::K_FLIP_WEIGHTS, s, 8.0 * wn, 0.0);
+            hch::LaunchTimer lt(HCH_KERNEL_ID("flip_transpose_weights_kernel"), s, 8.0 * wn, 0.0);
             hipLaunchKernelGGL(hch::flip_transpose_weights_kernel, dim3(blocks_for(wn)), dim3(256), 0, s,
                                (const float *)W, Wt, c_in, c_out);
         }
@@ -704,7 +725,7 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
         const int Kd = 27 * c_out;
         const GemmPlan p = plan_rows(n, c_in, Kd, true);
         const double bytes = (double)n * (108.0 + 4.0 * c_out + 4.0 * c_in * p.splits) + 4.0 * wn;
-        st = launch_gemm<hch::A_GATHER, false>(hch::K_GEMM_GATHER, p, (const float *)dY, Wt,
+        st = launch_gemm<hch::A_GATHER, false>(p, (const float *)dY, Wt,
                                                p.splits > 1 ? part : dX, L->dnbr, (int)n, c_in, Kd, c_out,
                                                c_in, c_in, n * c_in, bytes, s);
         if (st != HCH_OK) return st;
@@ -716,7 +737,7 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
     // dcol[N x Kc] = dY[N x c_out] . W^T   (W is [Kc x c_out]: its rows are B's columns)
     const GemmPlan p = plan_rows(n, Kc, c_out, false);
     const double bytes = 4.0 * ((double)n * c_out + (double)Kc * c_out + (double)n * Kc);
-    st = launch_gemm<hch::A_ROWS, true>(hch::K_GEMM_ROWS_BT, p, (const float *)dY, (const float *)W, dcol, nullptr,
+    st = launch_gemm<hch::A_ROWS, true>(p, (const float *)dY, (const float *)W, dcol, nullptr,
                                         (int)n, Kc, c_out, c_out, c_out, Kc, 0, bytes, s);
     if (st != HCH_OK) return st;
     return do_col2hash(*L, dcol, c_in, dX, s);
@@ -744,14 +765,14 @@ extern "C" hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t leve
     // dW[Kc x c_out] = col^T[Kc x N] . dY[N x c_out], reduction over the voxels split in slices
     if (algo == HCH_ALGO_FUSED) {
         const double bytes = (double)n * (108.0 + 4.0 * c_in + 4.0 * c_out) + 4.0 * wsize * p.splits;
-        st = launch_gemm<hch::A_GATHER_T, false>(hch::K_GEMM_GATHER_T, p, (const float *)X, (const float *)dY, dst,
+        st = launch_gemm<hch::A_GATHER_T, false>(p, (const float *)X, (const float *)dY, dst,
                                                  L->dnbr, Kc, c_out, (int)n, c_in, c_out, c_out, wsize, bytes, s);
     } else {
         float *col = (float *)workspace;
         st = do_hash2col(*L, dtype, X, c_in, 0, n, col, s);
         if (st != HCH_OK) return st;
         const double bytes = 4.0 * ((double)n * Kc + (double)n * c_out + (double)wsize * p.splits);
-        st = launch_gemm<hch::A_COLS, false>(hch::K_GEMM_COLS, p, col, (const float *)dY, dst, nullptr,
+        st = launch_gemm<hch::A_COLS, false>(p, col, (const float *)dY, dst, nullptr,
                                              Kc, c_out, (int)n, Kc, c_out, c_out, wsize, bytes, s);
     }
     if (st != HCH_OK) return st;
@@ -778,7 +799,7 @@ extern "C" hch_status hch_pool_fwd(const hch_levels *levels, int32_t level_in, c
         // per coarse voxel: 8 child indices, its children's rows in; value and switch rows out
         const Level &Lf = levels->lv[level_in];
         const double bytes = (double)Lc.n_total * (32.0 + 8.0 * c) + (double)Lf.n_total * 4.0 * c;
-        hch::LaunchTimer lt(hch::K_POOL_FWD, (hipStream_t)stream, bytes, 0.0);
+        hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("pool_fwd_kernel<4>") : HCH_KERNEL_ID("pool_fwd_kernel<1>"), (hipStream_t)stream, bytes, 0.0);
         if (vec)
             hipLaunchKernelGGL(hch::pool_fwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                                X, Lc.dchild, Y, argmax, Lc.n_total, c);
@@ -804,7 +825,7 @@ extern "C" hch_status hch_pool_bwd(const hch_levels *levels, int32_t level_in, c
     {
         const Level &Lf = levels->lv[level_in];
         const double bytes = (double)Lc.n_total * (32.0 + 8.0 * c) + (double)Lf.n_total * 4.0 * c;
-        hch::LaunchTimer lt(hch::K_POOL_BWD, (hipStream_t)stream, bytes, 0.0);
+        hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("pool_bwd_kernel<4>") : HCH_KERNEL_ID("pool_bwd_kernel<1>"), (hipStream_t)stream, bytes, 0.0);
         if (vec)
             hipLaunchKernelGGL(hch::pool_bwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                                dY, argmax, Lc.dchild, dX, Lc.n_total, c);
@@ -821,7 +842,7 @@ extern "C" hch_status hch_relu_fwd(const float *x, float *y, int64_t n, void *st
     if (!x || !y || n < 0) return fail(HCH_EINVAL, "hch_relu_fwd: bad argument");
     if (n == 0) return HCH_OK;
     {
-        hch::LaunchTimer lt(hch::K_RELU_FWD, (hipStream_t)stream, 8.0 * n, 0.0);
+        hch::LaunchTimer lt(HCH_KERNEL_ID("relu_fwd_kernel"), (hipStream_t)stream, 8.0 * n, 0.0);
         const int64_t n4 = (aligned16(x) && aligned16(y)) ? n / 4 : 0;
         hipLaunchKernelGGL(hch::relu_fwd_kernel, dim3(blocks_for(std::max(n4, n - 4 * n4))), dim3(256), 0,
                            (hipStream_t)stream, x, y, n, n4);
@@ -835,7 +856,7 @@ extern "C" hch_status hch_relu_bwd(const float *y, const float *dy, float *dx, i
     if (!y || !dy || !dx || n < 0) return fail(HCH_EINVAL, "hch_relu_bwd: bad argument");
     if (n == 0) return HCH_OK;
     {
-        hch::LaunchTimer lt(hch::K_RELU_BWD, (hipStream_t)stream, 12.0 * n, 0.0);
+        hch::LaunchTimer lt(HCH_KERNEL_ID("relu_bwd_kernel"), (hipStream_t)stream, 12.0 * n, 0.0);
         const int64_t n4 = (aligned16(y) && aligned16(dy) && aligned16(dx)) ? n / 4 : 0;
         hipLaunchKernelGGL(hch::relu_bwd_kernel, dim3(blocks_for(std::max(n4, n - 4 * n4))), dim3(256), 0,
                            (hipStream_t)stream, y, dy, dx, n, n4);
@@ -848,19 +869,26 @@ extern "C" hch_status hch_relu_bwd(const float *y, const float *dy, float *dx, i
 // per-kernel timing
 // ---------------------------------------------------------------------------------------
 
-extern "C" int32_t hch_kernel_count(void) { return hch::K_COUNT; }
+extern "C" int32_t hch_kernel_count(void) { return hch::Profiler::get().count(); }
 
-extern "C" const char *hch_kernel_name(int32_t id) { return hch::kernel_name(id); }
-
-extern "C" hch_status hch_profile_enable(uint64_t kernel_mask)
+extern "C" const char *hch_kernel_name(int32_t id)
 {
-    hch::Profiler::get().set_mask(kernel_mask);
+    thread_local std::string buf;
+    buf = hch::Profiler::get().name(id);
+    return buf.c_str();
+}
+
+extern "C" hch_status hch_profile_enable(int32_t kernel_id, int32_t on)
+{
+    if (kernel_id >= hch::Profiler::get().count()) return fail(HCH_EINVAL, "hch_profile_enable: unknown kernel id");
+    hch::Profiler::get().enable(kernel_id, on != 0);
     return HCH_OK;
 }
 
 extern "C" hch_status hch_profile_read(int32_t kernel_id, hch_kernel_stats *out)
 {
-    if (!out || kernel_id < 0 || kernel_id >= hch::K_COUNT) return fail(HCH_EINVAL, "hch_profile_read: bad argument");
+    if (!out || kernel_id < 0 || kernel_id >= hch::Profiler::get().count())
+        return fail(HCH_EINVAL, "hch_profile_read: bad argument");
     hch::Profiler::get().collect();
     const hch::KernelStats st = hch::Profiler::get().read(kernel_id);
     out->launches = st.launches; out->ms = st.ms; out->bytes = st.bytes; out->flops = st.flops;

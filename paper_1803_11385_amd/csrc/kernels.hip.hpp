@@ -257,8 +257,9 @@ __global__ __launch_bounds__(256) void col2hash_kernel(
 // its operands from LDS with 64/128-bit accesses.  blockIdx.z selects a slice of the reduction dimension (split-K):
 // slice z covers k in [z*k_per_split, (z+1)*k_per_split) and writes to C + z*c_split_stride.
 // The next tile's global loads are issued before the current tile's MFMAs.
-// Row tiles (blockIdx.x) are remapped so that each XCD owns a contiguous range of them:
-// gathered rows of neighbouring voxels then meet in one L2.
+// When the rows are voxels and there are many row tiles, the host launches a multiple of 8 of
+// them and blockIdx.x is remapped so that each XCD owns a contiguous range: gathered rows of
+// neighbouring voxels then meet in one L2.
 // ---------------------------------------------------------------------------------------
 constexpr int GEMM_BK = 32;   // granularity of reduction slices (split-K)
 enum { A_ROWS = 0, A_COLS = 1, A_GATHER = 2, A_GATHER_T = 3 };
@@ -302,9 +303,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
 
     __shared__ __attribute__((aligned(16))) float As[A_K_FAST ? BM * AS : BK * AS];
     __shared__ __attribute__((aligned(16))) float Bs[BK * BS];
-    __shared__ int32_t idx[AMODE == A_GATHER ? BM * 27 : 1];
 
-    const unsigned mtile = xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
+    // gridDim.x == m_tiles: plain order; gridDim.x > m_tiles (a multiple of 8): XCD-contiguous
+    const unsigned mtile = gridDim.x == m_tiles ? blockIdx.x : xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
     if (mtile >= m_tiles) return;
 
     const int tid = threadIdx.x;
@@ -315,13 +316,6 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     const int kend = min(K, kbeg + k_per_split);
     const int c = (int)lda;                           // channels per tap in the gather modes
     C += (int64_t)blockIdx.z * c_split_stride;
-
-    if (AMODE == A_GATHER) {
-        const int rows = min(BM, M - m0);
-        const int32_t *src = nbr + (int64_t)m0 * 27;
-        for (int t = tid; t < rows * 27; t += 256) idx[t] = src[t];
-        __syncthreads();
-    }
 
     f32x4 acc[MT][NT];
 #pragma unroll
@@ -349,57 +343,80 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     const int a_col = (tid % A_UPR) * 4;              // first of 4 elements along the fast axis
     const int a_row0 = tid / A_UPR;                   // unit uu sits in row a_row0 + uu*(256/A_UPR)
     constexpr int A_RSTEP = 256 / A_UPR;
+    constexpr bool GATHER = (AMODE == A_GATHER || AMODE == A_GATHER_T);
+    const bool fast_gather = GATHER && vec_ok;        // c % 4 == 0: a unit stays inside one tap
 
-    // fetch the tile starting at reduction index k0 into registers (zero outside the matrices)
-    auto fetch = [&](int k0) {
+    // Gather modes, stage 1: the index of the feature row behind each unit of the tile at k0
+    // (-1 = nothing to load).  Issued two tiles ahead of use so that the dependent row loads of
+    // stage 2 never wait for it.
+    auto fetch_idx = [&](int k0, int32_t *out) {
+        if (!fast_gather) return;
+        if (AMODE == A_GATHER) {
+            const int gk = k0 + a_col;
+            const int tap = gk / c;
+#pragma unroll
+            for (int uu = 0; uu < A_UNITS; ++uu) {
+                const int gi = m0 + a_row0 + uu * A_RSTEP;
+                out[uu] = (gi < M && gk < kend) ? nbr[(int64_t)gi * 27 + tap] : -1;
+            }
+        } else {
+            const int gi = m0 + a_col;
+            const int tap = gi / c;
+#pragma unroll
+            for (int uu = 0; uu < A_UNITS; ++uu) {
+                const int gk = k0 + a_row0 + uu * A_RSTEP;
+                out[uu] = (gk < kend && gi < M) ? nbr[(int64_t)gk * 27 + tap] : -1;
+            }
+        }
+    };
+
+    // stage 2: the tile starting at reduction index k0 into registers (zero outside the
+    // matrices); `rows` = the indices stage 1 produced for this tile
+    auto fetch = [&](int k0, const int32_t *rows) {
         if (A_K_FAST) {
             const int gk = k0 + a_col;
-            int tap = 0, cc = 0;
-            if (AMODE == A_GATHER) { tap = gk / c; cc = gk - tap * c; }
+            int cc = 0;
+            if (AMODE == A_GATHER) cc = gk % c;
 #pragma unroll
             for (int uu = 0; uu < A_UNITS; ++uu) {
                 const int i = a_row0 + uu * A_RSTEP;
                 const int gi = m0 + i;
                 f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (gi < M && gk < kend) {
-                    if (AMODE == A_ROWS) {
-                        v = load4(A + (int64_t)gi * lda + gk, kend - gk);
-                    } else if (vec_ok) {              // c % 4 == 0: the 4 elements share a tap
-                        const int32_t j = idx[i * 27 + tap];
-                        if (j >= 0) v = *reinterpret_cast<const f32x4 *>(A + (int64_t)j * c + cc);
-                    } else {
+                if (AMODE == A_ROWS) {
+                    if (gi < M && gk < kend) v = load4(A + (int64_t)gi * lda + gk, kend - gk);
+                } else if (fast_gather) {
+                    const int32_t j = rows[uu];
+                    if (j >= 0) v = *reinterpret_cast<const f32x4 *>(A + (int64_t)j * c + cc);
+                } else if (gi < M) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (gk + e < kend) {
-                                const int t2 = (gk + e) / c;
-                                v[e] = gather1(idx[i * 27 + t2], gk + e - t2 * c);
-                            }
-                    }
+                    for (int e = 0; e < 4; ++e)
+                        if (gk + e < kend) {
+                            const int t2 = (gk + e) / c;
+                            v[e] = gather1(nbr[(int64_t)gi * 27 + t2], gk + e - t2 * c);
+                        }
                 }
                 ra[uu] = v;
             }
         } else {
             const int gi = m0 + a_col;
-            int tap = 0, cc = 0;
-            if (AMODE == A_GATHER_T) { tap = gi / c; cc = gi - tap * c; }
+            int cc = 0;
+            if (AMODE == A_GATHER_T) cc = gi % c;
 #pragma unroll
             for (int uu = 0; uu < A_UNITS; ++uu) {
                 const int gk = k0 + a_row0 + uu * A_RSTEP;
                 f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (gk < kend && gi < M) {
-                    if (AMODE == A_COLS) {
-                        v = load4(A + (int64_t)gk * lda + gi, M - gi);
-                    } else if (vec_ok) {
-                        const int32_t j = nbr[(int64_t)gk * 27 + tap];
-                        if (j >= 0) v = *reinterpret_cast<const f32x4 *>(A + (int64_t)j * c + cc);
-                    } else {
+                if (AMODE == A_COLS) {
+                    if (gk < kend && gi < M) v = load4(A + (int64_t)gk * lda + gi, M - gi);
+                } else if (fast_gather) {
+                    const int32_t j = rows[uu];
+                    if (j >= 0) v = *reinterpret_cast<const f32x4 *>(A + (int64_t)j * c + cc);
+                } else if (gk < kend) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (gi + e < M) {
-                                const int t2 = (gi + e) / c;
-                                v[e] = gather1(nbr[(int64_t)gk * 27 + t2], gi + e - t2 * c);
-                            }
-                    }
+                    for (int e = 0; e < 4; ++e)
+                        if (gi + e < M) {
+                            const int t2 = (gi + e) / c;
+                            v[e] = gather1(nbr[(int64_t)gk * 27 + t2], gi + e - t2 * c);
+                        }
                 }
                 ra[uu] = v;
             }
@@ -446,11 +463,21 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
 
     const int li = lane & 15, lk = lane >> 4;
 
-    if (kbeg < kend) fetch(kbeg);
+    int32_t rcur[A_UNITS] = {}, rnext[A_UNITS] = {};  // feature-row indices: next tile, the one after
+    if (kbeg < kend) {
+        fetch_idx(kbeg, rcur);
+        fetch(kbeg, rcur);
+        fetch_idx(kbeg + BK, rcur);
+    }
     for (int k0 = kbeg; k0 < kend; k0 += BK) {
         stash();
         __syncthreads();
-        if (k0 + BK < kend) fetch(k0 + BK);
+        if (k0 + BK < kend) {
+            fetch_idx(k0 + 2 * BK, rnext);
+            fetch(k0 + BK, rcur);
+#pragma unroll
+            for (int uu = 0; uu < A_UNITS; ++uu) rcur[uu] = rnext[uu];
+        }
         if (A_K_FAST) {
 #pragma unroll
             for (int slab = 0; slab < BK / 16; ++slab) {
@@ -522,24 +549,30 @@ __global__ __launch_bounds__(256) void flip_transpose_weights_kernel(
     Wt[t] = W[((int64_t)(26 - k) * c_in + ci) * c_out + co];
 }
 
-// out[i] = sum_z part[z*stride + i].  A workgroup owns 16 outputs; 16 lanes per output each add
-// every 16th slice (z ascending), then the 16 partial sums are added in lane order: the same
-// order on every run.
+// out[i] = sum_z part[z*stride + i], the slices of a split reduction, always added in the same
+// order.  LANES lanes share one output: lane q adds slices q, q+LANES, ... (ascending), then the
+// LANES partial sums are added in lane order.  LANES = 1: one thread per output, plain loop.
+template <int LANES>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(
     const float *__restrict__ part, float *__restrict__ out, int64_t n, int splits, int64_t stride)
 {
-    __shared__ float sh[16][17];
-    const int ex = threadIdx.x & 15, zg = threadIdx.x >> 4;
-    const int64_t i = (int64_t)blockIdx.x * 16 + ex;
+    constexpr int OUTS = 256 / LANES;
+    __shared__ float sh[LANES == 1 ? 1 : LANES][OUTS + 1];
+    const int ex = threadIdx.x % OUTS, zg = threadIdx.x / OUTS;
+    const int64_t i = (int64_t)blockIdx.x * OUTS + ex;
     float s = 0.f;
     if (i < n)
-        for (int z = zg; z < splits; z += 16) s += part[(int64_t)z * stride + i];
+        for (int z = zg; z < splits; z += LANES) s += part[(int64_t)z * stride + i];
+    if (LANES == 1) {
+        if (i < n) out[i] = s;
+        return;
+    }
     sh[zg][ex] = s;
     __syncthreads();
     if (zg == 0 && i < n) {
         float t = sh[0][ex];
 #pragma unroll
-        for (int q = 1; q < 16; ++q) t += sh[q][ex];
+        for (int q = 1; q < LANES; ++q) t += sh[q][ex];
         out[i] = t;
     }
 }

@@ -1,36 +1,17 @@
 // Optional per-kernel timing with HIP events on the launch stream, plus the algorithmic
-// byte / flop counts of every launch.  Off by default; when a kernel's bit is set in the
-// mask each of its launches is bracketed by two events, which are resolved lazily when the
-// statistics are read.
+// byte / flop counts of every launch.  Off by default.  Kernels are registered by the name of
+// their __global__ function (template arguments included, spelled as a profiler prints them)
+// the first time they are launched; while timing is on for a kernel each of its launches is
+// bracketed by two events, which are resolved lazily when the statistics are read.
 #pragma once
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
 #include <mutex>
+#include <string>
 #include <vector>
 
 namespace hch {
-
-enum KernelId : int {
-    K_NEIGHBOUR = 0, K_CHILD,
-    K_HASH2COL_VEC, K_HASH2COL_ELEM,
-    K_COL2HASH,
-    K_GEMM_ROWS, K_GEMM_ROWS_BT, K_GEMM_COLS, K_GEMM_GATHER, K_GEMM_GATHER_T, K_FLIP_WEIGHTS,
-    K_SPLITK_REDUCE,
-    K_POOL_FWD, K_POOL_BWD, K_RELU_FWD, K_RELU_BWD,
-    K_COUNT
-};
-
-inline const char *kernel_name(int id)
-{
-    static const char *names[K_COUNT] = {
-        "neighbour_kernel", "child_kernel", "hash2col_kernel<uint4>", "hash2col_kernel<elem>", "col2hash_kernel",
-        "gemm_f32_kernel<A_ROWS,B_KC=0>", "gemm_f32_kernel<A_ROWS,B_KC=1>", "gemm_f32_kernel<A_COLS>",
-        "gemm_f32_kernel<A_GATHER>", "gemm_f32_kernel<A_GATHER_T>", "flip_transpose_weights_kernel",
-        "splitk_reduce_kernel", "pool_fwd_kernel", "pool_bwd_kernel", "relu_fwd_kernel",
-        "relu_bwd_kernel"};
-    return (id >= 0 && id < K_COUNT) ? names[id] : "";
-}
 
 struct KernelStats {
     int64_t launches = 0;
@@ -43,8 +24,27 @@ class Profiler {
 public:
     static Profiler &get() { static Profiler p; return p; }
 
-    void set_mask(uint64_t m) { std::lock_guard<std::mutex> g(mu_); mask_ = m; }
-    bool on(int id) const { return (mask_ >> id) & 1u; }
+    // id of a kernel name, registering it on first sight
+    int id_for(const std::string &name)
+    {
+        std::lock_guard<std::mutex> g(mu_);
+        for (size_t i = 0; i < names_.size(); ++i) if (names_[i] == name) return (int)i;
+        names_.push_back(name);
+        stats_.push_back(KernelStats());
+        on_.push_back(all_on_);
+        return (int)names_.size() - 1;
+    }
+    int count() { std::lock_guard<std::mutex> g(mu_); return (int)names_.size(); }
+    std::string name(int id) { std::lock_guard<std::mutex> g(mu_); return id >= 0 && id < (int)names_.size() ? names_[id] : std::string(); }
+
+    // id < 0: every kernel, including ones not launched yet
+    void enable(int id, bool on)
+    {
+        std::lock_guard<std::mutex> g(mu_);
+        if (id < 0) { all_on_ = on; for (size_t i = 0; i < on_.size(); ++i) on_[i] = on; }
+        else if (id < (int)on_.size()) on_[id] = on;
+    }
+    bool on(int id) { std::lock_guard<std::mutex> g(mu_); return id >= 0 && id < (int)on_.size() && on_[id]; }
 
     // called right before / after a launch of kernel `id` on stream s
     void before(int id, hipStream_t s, double bytes, double flops)
@@ -77,7 +77,7 @@ public:
         }
         pending_.clear();
     }
-    KernelStats read(int id) { std::lock_guard<std::mutex> g(mu_); return stats_[id]; }
+    KernelStats read(int id) { std::lock_guard<std::mutex> g(mu_); return id >= 0 && id < (int)stats_.size() ? stats_[id] : KernelStats(); }
     void reset() { std::lock_guard<std::mutex> g(mu_); for (auto &s : stats_) s = KernelStats(); }
 
 private:
@@ -90,13 +90,15 @@ private:
         return e;
     }
     std::mutex mu_;
-    uint64_t mask_ = 0;
+    bool all_on_ = false;
+    std::vector<std::string> names_;
+    std::vector<KernelStats> stats_;
+    std::vector<bool> on_;
     std::vector<Pending> pending_;
     std::vector<hipEvent_t> free_;
-    KernelStats stats_[K_COUNT];
 };
 
-// RAII bracket around one launch
+// RAII bracket around one launch.  `id` comes from Profiler::id_for, cached by the call site.
 struct LaunchTimer {
     hipStream_t s; bool active;
     LaunchTimer(int id, hipStream_t stream, double bytes, double flops) : s(stream), active(Profiler::get().on(id))
@@ -107,3 +109,6 @@ struct LaunchTimer {
 };
 
 }  // namespace hch
+
+// id of a kernel whose name is a literal, looked up once per call site
+#define HCH_KERNEL_ID(name_literal) ([]() { static const int id_ = hch::Profiler::get().id_for(name_literal); return id_; }())
