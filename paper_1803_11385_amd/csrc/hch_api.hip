@@ -519,14 +519,16 @@ static GemmPlan plan_wgrad(int64_t n, int c_in, int c_out)
     return p;
 }
 
-template <int AMODE, bool B_KC>
-static hch_status launch_gemm(const GemmPlan &p, const float *A, const float *B, float *C,
-                              const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
-                              int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s)
+template <typename TIN, int AMODE, bool B_KC>
+static hch_status launch_gemm_t(const GemmPlan &p, const void *A, const void *B, float *C,
+                                const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
+                                int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s)
 {
     if (M <= 0 || N <= 0) return HCH_OK;
-    const bool gather = (AMODE == hch::A_GATHER || AMODE == hch::A_GATHER_T);
-    const int vec_ok = (lda % 4 == 0) && (ldb % 4 == 0) && aligned16(A) && aligned16(B);
+    // vector loads move 4 elements: 16 bytes of float, 8 bytes of bf16
+    const uintptr_t amask = sizeof(TIN) * 4 - 1;
+    const int vec_ok = (lda % 4 == 0) && (ldb % 4 == 0) && !(reinterpret_cast<uintptr_t>(A) & amask) &&
+                       !(reinterpret_cast<uintptr_t>(B) & amask);
     const int c_vec_ok = (ldc % 4 == 0) && (c_split_stride % 4 == 0) && aligned16(C);
     const unsigned m_tiles = (unsigned)((M + p.bm - 1) / p.bm);
     // XCD-contiguous row tiles only where rows are voxels and there are enough tiles to keep
@@ -535,21 +537,21 @@ static hch_status launch_gemm(const GemmPlan &p, const float *A, const float *B,
     const bool remap = (AMODE == hch::A_GATHER || AMODE == hch::A_ROWS) && m_tiles >= 256;
     const unsigned gx = remap ? (m_tiles / hch::NUM_XCD + 1) * hch::NUM_XCD : m_tiles;
     const dim3 grid(gx, (unsigned)((N + p.bn - 1) / p.bn), (unsigned)p.splits);
-    (void)gather;
-    // the kernel's name as a profiler prints it: gemm_f32_kernel<BM, BN, BK, WM, AMODE, B_KC>
+    // the kernel's name as a profiler prints it: gemm_f32_kernel<TIN, BM, BN, BK, WM, AMODE, B_KC>
     static int ids[4] = {-1, -1, -1, -1};
     const int cfg = p.bm == 64 ? 0 : (p.bn == 16 ? 1 : (p.bn == 32 ? 2 : 3));
     if (ids[cfg] < 0) {
-        char nm[96];
-        snprintf(nm, sizeof nm, "gemm_f32_kernel<%d, %d, 32, %d, %d, %s>", p.bm, p.bm == 64 ? 64 : p.bn, p.wm,
+        char nm[112];
+        snprintf(nm, sizeof nm, "gemm_f32_kernel<%s, %d, %d, 32, %d, %d, %s>",
+                 sizeof(TIN) == 4 ? "float" : "unsigned short", p.bm, p.bm == 64 ? 64 : p.bn, p.wm,
                  (int)AMODE, B_KC ? "true" : "false");
         ids[cfg] = hch::Profiler::get().id_for(nm);
     }
     hch::LaunchTimer lt(ids[cfg], s, alg_bytes, 2.0 * M * (double)N * K);
-#define HCH_GEMM_CASE(BM_, BN_, BK_, WM_)                                                               \
-    hipLaunchKernelGGL((hch::gemm_f32_kernel<BM_, BN_, BK_, WM_, AMODE, B_KC>), grid, dim3(256), 0, s, \
-                       A, B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split, c_split_stride, vec_ok,     \
-                       c_vec_ok, m_tiles)
+#define HCH_GEMM_CASE(BM_, BN_, BK_, WM_)                                                                  \
+    hipLaunchKernelGGL((hch::gemm_f32_kernel<TIN, BM_, BN_, BK_, WM_, AMODE, B_KC>), grid, dim3(256), 0, s, \
+                       (const TIN *)A, (const TIN *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split,       \
+                       c_split_stride, vec_ok, c_vec_ok, m_tiles)
     if (p.bm == 64) HCH_GEMM_CASE(64, 64, 32, 2);
     else if (p.bn == 16) HCH_GEMM_CASE(128, 16, 32, 4);
     else if (p.bn == 32) HCH_GEMM_CASE(128, 32, 32, 4);
@@ -557,6 +559,16 @@ static hch_status launch_gemm(const GemmPlan &p, const float *A, const float *B,
 #undef HCH_GEMM_CASE
     HCH_LAUNCH_CHECK("gemm_f32_kernel");
     return HCH_OK;
+}
+
+template <int AMODE, bool B_KC>
+static hch_status launch_gemm(hch_dtype dtype, const GemmPlan &p, const void *A, const void *B, float *C,
+                              const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
+                              int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s)
+{
+    if (dtype == HCH_BF16)
+        return launch_gemm_t<uint16_t, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s);
+    return launch_gemm_t<float, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s);
 }
 
 static hch_status launch_reduce(const float *part, float *out, int64_t n, int splits, hipStream_t s)
@@ -593,7 +605,7 @@ static WsLayout ws_layout(const Level &L, int c_in, int c_out, hch_dtype dtype, 
         if (algo == HCH_ALGO_COLUMNS) w.first_bytes = round_up(n * Kc * 4, 256);
         else {
             const GemmPlan p = plan_rows(L.n_total, c_in, 27 * c_out, true);
-            w.first_bytes = round_up(Kc * c_out * 4, 256);
+            w.first_bytes = round_up(Kc * c_out * elem_size(dtype), 256);
             if (p.splits > 1) w.part_bytes = round_up((size_t)p.splits * n * c_in * 4, 256);
         }
     } else if (kind == HCH_WS_BWD_WEIGHT) {
@@ -639,8 +651,8 @@ static hch_status conv_args(const hch_levels *levels, int32_t level, hch_dtype d
         return fail(HCH_EINVAL, std::string(who) + ": weight tensor too large");
     if (algo != HCH_ALGO_COLUMNS && algo != HCH_ALGO_FUSED)
         return fail(HCH_EINVAL, std::string(who) + ": unknown algorithm");
-    if (dtype != HCH_F32)
-        return fail(HCH_EUNSUPPORTED, std::string(who) + ": only HCH_F32 is implemented");
+    if (dtype != HCH_F32 && dtype != HCH_BF16)
+        return fail(HCH_EINVAL, std::string(who) + ": unknown dtype");
     if (reinterpret_cast<uintptr_t>(ws) & 255u)
         return fail(HCH_EINVAL, std::string(who) + ": workspace must be 256-byte aligned");
     if ((*L)->n_total >= ((int64_t)1 << 31) / 64)
@@ -663,13 +675,14 @@ extern "C" hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_
     const int64_t n = L->n_total;
     const WsLayout w = ws_layout(*L, c_in, c_out, dtype, HCH_WS_FWD, algo);
     const GemmPlan p = plan_rows(n, c_out, Kc, true);
+    const double es = elem_size(dtype);               // bytes per input element
     float *part = (float *)((char *)workspace + ((ws_bytes - w.part_bytes) & ~(size_t)255));   // split-K area at the end
 
     if (algo == HCH_ALGO_FUSED) {
         // Y = gathered columns . W, the column matrix never leaves the chip.  Per voxel: 27
         // indices and its feature row in, one output row out; the weights once.
-        const double bytes = (double)n * (108.0 + 4.0 * c_in + 4.0 * c_out * p.splits) + 4.0 * Kc * c_out;
-        st = launch_gemm<hch::A_GATHER, false>(p, (const float *)X, (const float *)W,
+        const double bytes = (double)n * (108.0 + es * c_in + 4.0 * c_out * p.splits) + es * Kc * c_out;
+        st = launch_gemm<hch::A_GATHER, false>(dtype, p, X, W,
                                                p.splits > 1 ? part : Y, L->dnbr, (int)n, c_out, Kc, c_in,
                                                c_out, c_out, n * c_out, bytes, s);
         if (st != HCH_OK) return st;
@@ -678,15 +691,15 @@ extern "C" hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_
     }
 
     // as many rows of the column matrix as the workspace holds, in multiples of the GEMM tile
-    int64_t chunk = (int64_t)(((ws_bytes - w.part_bytes) & ~(size_t)255) / ((size_t)Kc * 4));
+    int64_t chunk = (int64_t)(((ws_bytes - w.part_bytes) & ~(size_t)255) / ((size_t)Kc * elem_size(dtype)));
     if (chunk < n) chunk = std::max<int64_t>(128, chunk / 128 * 128);
     for (int64_t r0 = 0; r0 < n; r0 += chunk) {
         const int64_t rows = std::min<int64_t>(chunk, n - r0);
         st = do_hash2col(*L, dtype, X, c_in, r0, rows, workspace, s);
         if (st != HCH_OK) return st;
-        const double bytes = 4.0 * ((double)rows * Kc + (double)Kc * c_out + (double)rows * c_out * p.splits);
+        const double bytes = es * ((double)rows * Kc + (double)Kc * c_out) + 4.0 * (double)rows * c_out * p.splits;
         // the split plan was made for all n rows; slices of a chunk land in the same places
-        st = launch_gemm<hch::A_ROWS, false>(p, (const float *)workspace, (const float *)W,
+        st = launch_gemm<hch::A_ROWS, false>(dtype, p, workspace, W,
                                              p.splits > 1 ? part + r0 * c_out : Y + r0 * c_out, nullptr,
                                              (int)rows, c_out, Kc, Kc, c_out, c_out, n * c_out, bytes, s);
         if (st != HCH_OK) return st;
@@ -708,24 +721,29 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
     hipStream_t s = (hipStream_t)stream;
     const int Kc = 27 * c_in;
     const int64_t n = L->n_total;
+    const double es = elem_size(dtype);
 
     if (algo == HCH_ALGO_FUSED) {
         // dX[q] = sum_k dY[neighbour 26-k of q] . W[k]^T: a gathered product over the output
         // gradients with the flipped, transposed weights; dcol is never formed.
         const WsLayout w = ws_layout(*L, c_in, c_out, dtype, HCH_WS_BWD_DATA, algo);
-        float *Wt = (float *)workspace;
+        void *Wt = workspace;
         float *part = (float *)((char *)workspace + w.first_bytes);
         const int64_t wn = (int64_t)Kc * c_out;
-        {
-            hch::LaunchTimer lt(HCH_KERNEL_ID("flip_transpose_weights_kernel"), s, 8.0 * wn, 0.0);
-            hipLaunchKernelGGL(hch::flip_transpose_weights_kernel, dim3(blocks_for(wn)), dim3(256), 0, s,
-                               (const float *)W, Wt, c_in, c_out);
+        if (dtype == HCH_F32) {
+            hch::LaunchTimer lt(HCH_KERNEL_ID("flip_transpose_weights_kernel<float>"), s, 8.0 * wn, 0.0);
+            hipLaunchKernelGGL(hch::flip_transpose_weights_kernel<float>, dim3(blocks_for(wn)), dim3(256), 0, s,
+                               (const float *)W, (float *)Wt, c_in, c_out);
+        } else {
+            hch::LaunchTimer lt(HCH_KERNEL_ID("flip_transpose_weights_kernel<unsigned short>"), s, 4.0 * wn, 0.0);
+            hipLaunchKernelGGL(hch::flip_transpose_weights_kernel<uint16_t>, dim3(blocks_for(wn)), dim3(256), 0, s,
+                               (const uint16_t *)W, (uint16_t *)Wt, c_in, c_out);
         }
         HCH_LAUNCH_CHECK("flip_transpose_weights_kernel");
         const int Kd = 27 * c_out;
         const GemmPlan p = plan_rows(n, c_in, Kd, true);
-        const double bytes = (double)n * (108.0 + 4.0 * c_out + 4.0 * c_in * p.splits) + 4.0 * wn;
-        st = launch_gemm<hch::A_GATHER, false>(p, (const float *)dY, Wt,
+        const double bytes = (double)n * (108.0 + es * c_out + 4.0 * c_in * p.splits) + es * wn;
+        st = launch_gemm<hch::A_GATHER, false>(dtype, p, dY, Wt,
                                                p.splits > 1 ? part : dX, L->dnbr, (int)n, c_in, Kd, c_out,
                                                c_in, c_in, n * c_in, bytes, s);
         if (st != HCH_OK) return st;
@@ -736,8 +754,8 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
     float *dcol = (float *)workspace;
     // dcol[N x Kc] = dY[N x c_out] . W^T   (W is [Kc x c_out]: its rows are B's columns)
     const GemmPlan p = plan_rows(n, Kc, c_out, false);
-    const double bytes = 4.0 * ((double)n * c_out + (double)Kc * c_out + (double)n * Kc);
-    st = launch_gemm<hch::A_ROWS, true>(p, (const float *)dY, (const float *)W, dcol, nullptr,
+    const double bytes = es * ((double)n * c_out + (double)Kc * c_out) + 4.0 * (double)n * Kc;
+    st = launch_gemm<hch::A_ROWS, true>(dtype, p, dY, W, dcol, nullptr,
                                         (int)n, Kc, c_out, c_out, c_out, Kc, 0, bytes, s);
     if (st != HCH_OK) return st;
     return do_col2hash(*L, dcol, c_in, dX, s);
@@ -756,6 +774,7 @@ extern "C" hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t leve
     hipStream_t s = (hipStream_t)stream;
     const int Kc = 27 * c_in;
     const int64_t n = L->n_total;
+    const double es = elem_size(dtype);
     const WsLayout w = ws_layout(*L, c_in, c_out, dtype, HCH_WS_BWD_WEIGHT, algo);
     const GemmPlan p = plan_wgrad(n, c_in, c_out);
     const int64_t wsize = (int64_t)Kc * c_out;
@@ -764,15 +783,15 @@ extern "C" hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t leve
 
     // dW[Kc x c_out] = col^T[Kc x N] . dY[N x c_out], reduction over the voxels split in slices
     if (algo == HCH_ALGO_FUSED) {
-        const double bytes = (double)n * (108.0 + 4.0 * c_in + 4.0 * c_out) + 4.0 * wsize * p.splits;
-        st = launch_gemm<hch::A_GATHER_T, false>(p, (const float *)X, (const float *)dY, dst,
+        const double bytes = (double)n * (108.0 + es * c_in + es * c_out) + 4.0 * wsize * p.splits;
+        st = launch_gemm<hch::A_GATHER_T, false>(dtype, p, X, dY, dst,
                                                  L->dnbr, Kc, c_out, (int)n, c_in, c_out, c_out, wsize, bytes, s);
     } else {
-        float *col = (float *)workspace;
+        void *col = workspace;
         st = do_hash2col(*L, dtype, X, c_in, 0, n, col, s);
         if (st != HCH_OK) return st;
-        const double bytes = 4.0 * ((double)n * Kc + (double)n * c_out + (double)wsize * p.splits);
-        st = launch_gemm<hch::A_COLS, false>(p, col, (const float *)dY, dst, nullptr,
+        const double bytes = es * ((double)n * Kc + (double)n * c_out) + 4.0 * (double)wsize * p.splits;
+        st = launch_gemm<hch::A_COLS, false>(dtype, p, col, dY, dst, nullptr,
                                              Kc, c_out, (int)n, Kc, c_out, c_out, wsize, bytes, s);
     }
     if (st != HCH_OK) return st;

@@ -242,6 +242,8 @@ __global__ __launch_bounds__(256) void col2hash_kernel(
 // ---------------------------------------------------------------------------------------
 // fp32 GEMM on the matrix cores:  C[M x N] (+split) = A[M x K] * B[K x N]
 //
+// A and B hold TIN elements (float, or bf16 bit patterns widened exactly to fp32 on load); all
+// arithmetic is fp32.
 // A operand (AMODE):
 //   A_ROWS    A(i,k) = A[i*lda + k]                       plain, k contiguous
 //   A_COLS    A(i,k) = A[k*lda + i]                       plain, i contiguous
@@ -264,6 +266,23 @@ __global__ __launch_bounds__(256) void col2hash_kernel(
 constexpr int GEMM_BK = 32;   // granularity of reduction slices (split-K)
 enum { A_ROWS = 0, A_COLS = 1, A_GATHER = 2, A_GATHER_T = 3 };
 
+// Input element types of the GEMM: float, or bfloat16 bit patterns (uint16_t) that are widened
+// to fp32 on load (exact), so that all products and sums are fp32.
+template <typename T> struct InElem;
+template <> struct InElem<float> {
+    static __device__ __forceinline__ float one(const float *p) { return *p; }
+    static __device__ __forceinline__ f32x4 four(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
+};
+template <> struct InElem<uint16_t> {
+    static __device__ __forceinline__ float one(const uint16_t *p) { return __uint_as_float((uint32_t)*p << 16); }
+    static __device__ __forceinline__ f32x4 four(const uint16_t *p)
+    {
+        const uint2 r = *reinterpret_cast<const uint2 *>(p);
+        return f32x4{__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u),
+                     __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xFFFF0000u)};
+    }
+};
+
 template <int N> struct FVec;
 template <> struct FVec<1> { typedef float type; };
 template <> struct FVec<2> { typedef float type __attribute__((ext_vector_type(2))); };
@@ -271,9 +290,9 @@ template <> struct FVec<4> { typedef float type __attribute__((ext_vector_type(4
 template <int N> __device__ __forceinline__ float vget(const typename FVec<N>::type &v, int i) { return v[i]; }
 template <> __device__ __forceinline__ float vget<1>(const float &v, int) { return v; }
 
-template <int BM, int BN, int BK, int WM, int AMODE, bool B_KC>
+template <typename TIN, int BM, int BN, int BK, int WM, int AMODE, bool B_KC>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(
-    const float *__restrict__ A, const float *__restrict__ B, float *__restrict__ C,
+    const TIN *__restrict__ A, const TIN *__restrict__ B, float *__restrict__ C,
     const int32_t *__restrict__ nbr, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
     int k_per_split, int64_t c_split_stride, int vec_ok, int c_vec_ok, unsigned m_tiles)
 {
@@ -326,18 +345,18 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     f32x4 ra[A_UNITS], rb[B_UNITS];
 
     // 4 consecutive elements starting at src; `left` = how many are inside the matrix
-    auto load4 = [&](const float *src, int left) {
+    auto load4 = [&](const TIN *src, int left) {
         f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (vec_ok && left >= 4) v = *reinterpret_cast<const f32x4 *>(src);
+        if (vec_ok && left >= 4) v = InElem<TIN>::four(src);
         else {
-            v[0] = src[0];
-            if (left > 1) v[1] = src[1];
-            if (left > 2) v[2] = src[2];
-            if (left > 3) v[3] = src[3];
+            v[0] = InElem<TIN>::one(src);
+            if (left > 1) v[1] = InElem<TIN>::one(src + 1);
+            if (left > 2) v[2] = InElem<TIN>::one(src + 2);
+            if (left > 3) v[3] = InElem<TIN>::one(src + 3);
         }
         return v;
     };
-    auto gather1 = [&](int32_t j, int cc) { return j >= 0 ? A[(int64_t)j * c + cc] : 0.f; };
+    auto gather1 = [&](int32_t j, int cc) { return j >= 0 ? InElem<TIN>::one(A + (int64_t)j * c + cc) : 0.f; };
 
     // position of this thread's units inside a tile: the same column of units in every row
     const int a_col = (tid % A_UPR) * 4;              // first of 4 elements along the fast axis
@@ -386,7 +405,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
                     if (gi < M && gk < kend) v = load4(A + (int64_t)gi * lda + gk, kend - gk);
                 } else if (fast_gather) {
                     const int32_t j = rows[uu];
-                    if (j >= 0) v = *reinterpret_cast<const f32x4 *>(A + (int64_t)j * c + cc);
+                    if (j >= 0) v = InElem<TIN>::four(A + (int64_t)j * c + cc);
                 } else if (gi < M) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
@@ -409,7 +428,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
                     if (gk < kend && gi < M) v = load4(A + (int64_t)gk * lda + gi, M - gi);
                 } else if (fast_gather) {
                     const int32_t j = rows[uu];
-                    if (j >= 0) v = *reinterpret_cast<const f32x4 *>(A + (int64_t)j * c + cc);
+                    if (j >= 0) v = InElem<TIN>::four(A + (int64_t)j * c + cc);
                 } else if (gk < kend) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
@@ -537,8 +556,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
 
 // Wt[k][co][ci] = W[26-k][ci][co]: the weights of the convolution that maps output gradients
 // back to the input (Eq.8 read through the symmetry of the 3x3x3 stride-1 neighbourhood)
+template <typename T>
 __global__ __launch_bounds__(256) void flip_transpose_weights_kernel(
-    const float *__restrict__ W, float *__restrict__ Wt, int c_in, int c_out)
+    const T *__restrict__ W, T *__restrict__ Wt, int c_in, int c_out)
 {
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t per = (int64_t)c_in * c_out;

@@ -293,3 +293,55 @@ def test_error_paths(case_sphere):
     with pytest.raises(hch.HchError) as ei:
         hch.hch_hash2col(case.glv, 0, hch.HCH_F32, X, 3, n - 5, 10, Y)
     assert ei.value.status == 1
+
+
+# --------------------------------------------------------------------------------------
+# bf16 inputs, fp32 accumulation
+# --------------------------------------------------------------------------------------
+
+TOL_BF16 = 2e-2     # stated bound for bf16-in / fp32-accumulate
+
+
+def dev_bf16(a_on_grid):
+    return dev(S.bf16_bits(a_on_grid).view(np.int16))
+
+
+@pytest.fixture(scope="module")
+def case_hires(oracle):
+    # the high-resolution workload scaled down: two-voxel shells of 2..6 primitives
+    coords, offs, _ = S.config_batch(5, batch=2, u=64)
+    return Case(oracle, coords, offs, 64, 2)
+
+
+@pytest.mark.parametrize("algo", ALGOS, ids=ALGO_IDS)
+@pytest.mark.parametrize("c_in,c_out", [(64, 64), (8, 24), (6, 5)])
+def test_conv_bf16(oracle, case_hires, c_in, c_out, algo):
+    """X, W, dY are bf16 (both sides start from the same bf16-representable numbers); products
+    are accumulated in fp32 on the GPU and in double in the oracle; outputs are fp32."""
+    case = case_hires
+    L = case.olv[0]
+    n = L.Ntot
+    X = S.to_bf16_grid(S.gaussian((n, c_in), 1.0, 51))
+    W = S.to_bf16_grid(S.he_weights(c_in, c_out, 52))
+    G = S.to_bf16_grid(S.gaussian((n, c_out), 1.0, 53))
+    Xp, Wp, Gp = oracle.to_paper_X(X), oracle.to_paper_W(W), oracle.to_paper_X(G)
+    B16 = hch.HCH_BF16
+
+    def ws(kind):
+        return workspace(hch.hch_conv_workspace_bytes(case.glv, 0, c_in, c_out, B16, kind, algo))
+
+    Y = torch.full((n, c_out), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_conv_fwd(case.glv, 0, B16, dev_bf16(X), dev_bf16(W), Y, c_in, c_out, ws(hch.HCH_WS_FWD), algo)
+    want = oracle.conv_fwd(L, Xp, Wp).T
+    assert_close(Y.cpu().numpy(), want, tol=TOL_BF16, what="bf16 fwd")
+    # exact products, fp32 sums: in fact as close as the fp32 path
+    assert_close(Y.cpu().numpy(), want, tol=TOL_F32, what="bf16 fwd (fp32-level)")
+
+    dX = torch.full((n, c_in), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_conv_bwd_data(case.glv, 0, B16, dev_bf16(G), dev_bf16(W), dX, c_in, c_out, ws(hch.HCH_WS_BWD_DATA), algo)
+    assert_close(dX.cpu().numpy(), oracle.conv_bwd_data(L, Gp, Wp, c_in).T, tol=TOL_BF16, what="bf16 bwd data")
+
+    dW = torch.full((27, c_in, c_out), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_conv_bwd_weight(case.glv, 0, B16, dev_bf16(X), dev_bf16(G), dW, c_in, c_out, ws(hch.HCH_WS_BWD_WEIGHT), algo)
+    assert_close(dW.cpu().numpy(), oracle.from_paper_W(oracle.conv_bwd_weight(L, Xp, Gp), c_in), tol=TOL_BF16,
+                 what="bf16 bwd weight")
