@@ -139,18 +139,27 @@ def main():
                 "algorithmic_bytes_per_launch": round(st["bytes"] / max(1, st["launches"])),
                 "flops_per_launch": round(st["flops"] / max(1, st["launches"]))}
 
-    traffic_db = {}
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic_db = json.load(open(tpath))
-        except Exception:
-            traffic_db = {}
+    def load_traffic(algo_name):
+        """kernel -> HBM bytes per launch, from the committed rocprofv3 --pmc summary of this
+        workload (FETCH_SIZE + WRITE_SIZE, calibrated on a copy kernel); the counters cannot be
+        read from inside this process."""
+        db = {}
+        path = os.path.join(ROOT, "profiles", f"hbm_traffic_encoder_{u}x{b}_{algo_name}.txt")
+        if os.path.exists(path):
+            for line in open(path):
+                parts = [x.strip() for x in line.split("|")]
+                if line.startswith("#") or len(parts) != 5:
+                    continue
+                try:
+                    db[parts[0]] = float(parts[4])
+                except ValueError:
+                    pass
+        return db
+
+    traffic_db = {a: load_traffic(a) for a in ("fused", "columns")}
 
     def traffic_of(name):
-        """HBM bytes per launch from the committed rocprofv3 --pmc summary, if it has this
-        kernel on this workload (the counters cannot be read from inside this process)."""
-        return traffic_db.get(f"{u}^3x{b}", {}).get(args.algo, {}).get(name)
+        return traffic_db.get(args.algo, {}).get(name)
 
     # warm-up; the first warm-up step times every kernel to find the dominant one
     hch.hch_profile_reset()
