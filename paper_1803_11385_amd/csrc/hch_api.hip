@@ -519,16 +519,23 @@ static GemmPlan plan_wgrad(int64_t n, int c_in, int c_out)
     return p;
 }
 
+static inline bool k_split_aligned(const GemmPlan &p) { return p.k_per_split % 4 == 0; }
+
 template <typename TIN, int AMODE, bool B_KC>
-static hch_status launch_gemm_t(const GemmPlan &p, const void *A, const void *B, float *C,
+static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void *B, float *C,
                                 const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
                                 int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s)
 {
     if (M <= 0 || N <= 0) return HCH_OK;
-    // vector loads move 4 elements: 16 bytes of float, 8 bytes of bf16
+    GemmPlan p = plan;
+    // vector path: every 4-element unit is aligned and wholly inside or outside its matrix
     const uintptr_t amask = sizeof(TIN) * 4 - 1;
-    const int vec_ok = (lda % 4 == 0) && (ldb % 4 == 0) && !(reinterpret_cast<uintptr_t>(A) & amask) &&
-                       !(reinterpret_cast<uintptr_t>(B) & amask);
+    const bool a_fast_ok = (AMODE == hch::A_COLS) ? (M % 4 == 0) : (K % 4 == 0 || AMODE == hch::A_GATHER_T);
+    const bool b_fast_ok = B_KC ? (K % 4 == 0) : (N % 4 == 0);
+    const bool vec = (lda % 4 == 0) && (ldb % 4 == 0) && a_fast_ok && b_fast_ok &&
+                     !(reinterpret_cast<uintptr_t>(A) & amask) && !(reinterpret_cast<uintptr_t>(B) & amask) &&
+                     (k_split_aligned(p));
+    if (!vec && p.bm == 64) { p.bm = 128; p.wm = 4; }   // the generic path has the 128-row tiles only
     const int c_vec_ok = (ldc % 4 == 0) && (c_split_stride % 4 == 0) && aligned16(C);
     const unsigned m_tiles = (unsigned)((M + p.bm - 1) / p.bm);
     // XCD-contiguous row tiles only where rows are voxels and there are enough tiles to keep
@@ -538,24 +545,32 @@ static hch_status launch_gemm_t(const GemmPlan &p, const void *A, const void *B,
     const unsigned gx = remap ? (m_tiles / hch::NUM_XCD + 1) * hch::NUM_XCD : m_tiles;
     const dim3 grid(gx, (unsigned)((N + p.bn - 1) / p.bn), (unsigned)p.splits);
     // the kernel's name as a profiler prints it: gemm_f32_kernel<TIN, BM, BN, BK, WM, AMODE, B_KC>
-    static int ids[4] = {-1, -1, -1, -1};
+    static int ids[2][4] = {{-1, -1, -1, -1}, {-1, -1, -1, -1}};
     const int cfg = p.bm == 64 ? 0 : (p.bn == 16 ? 1 : (p.bn == 32 ? 2 : 3));
-    if (ids[cfg] < 0) {
-        char nm[112];
-        snprintf(nm, sizeof nm, "gemm_f32_kernel<%s, %d, %d, 32, %d, %d, %s>",
+    const int v = vec ? 1 : 0;
+    if (ids[v][cfg] < 0) {
+        char nm[128];
+        snprintf(nm, sizeof nm, "gemm_f32_kernel<%s, %d, %d, 32, %d, %d, %s, %s>",
                  sizeof(TIN) == 4 ? "float" : "unsigned short", p.bm, p.bm == 64 ? 64 : p.bn, p.wm,
-                 (int)AMODE, B_KC ? "true" : "false");
-        ids[cfg] = hch::Profiler::get().id_for(nm);
+                 (int)AMODE, B_KC ? "true" : "false", v ? "true" : "false");
+        ids[v][cfg] = hch::Profiler::get().id_for(nm);
     }
-    hch::LaunchTimer lt(ids[cfg], s, alg_bytes, 2.0 * M * (double)N * K);
-#define HCH_GEMM_CASE(BM_, BN_, BK_, WM_)                                                                  \
-    hipLaunchKernelGGL((hch::gemm_f32_kernel<TIN, BM_, BN_, BK_, WM_, AMODE, B_KC>), grid, dim3(256), 0, s, \
-                       (const TIN *)A, (const TIN *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split,       \
-                       c_split_stride, vec_ok, c_vec_ok, m_tiles)
-    if (p.bm == 64) HCH_GEMM_CASE(64, 64, 32, 2);
-    else if (p.bn == 16) HCH_GEMM_CASE(128, 16, 32, 4);
-    else if (p.bn == 32) HCH_GEMM_CASE(128, 32, 32, 4);
-    else HCH_GEMM_CASE(128, 64, 32, 4);
+    hch::LaunchTimer lt(ids[v][cfg], s, alg_bytes, 2.0 * M * (double)N * K);
+#define HCH_GEMM_CASE(BM_, BN_, BK_, WM_, VEC_)                                                                \
+    hipLaunchKernelGGL((hch::gemm_f32_kernel<TIN, BM_, BN_, BK_, WM_, AMODE, B_KC, VEC_>), grid, dim3(256), 0, s, \
+                       (const TIN *)A, (const TIN *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split,            \
+                       c_split_stride, c_vec_ok, m_tiles)
+    if (vec) {
+        if (p.bm == 64) HCH_GEMM_CASE(64, 64, 32, 2, true);
+        else if (p.bn == 16) HCH_GEMM_CASE(128, 16, 32, 4, true);
+        else if (p.bn == 32) HCH_GEMM_CASE(128, 32, 32, 4, true);
+        else HCH_GEMM_CASE(128, 64, 32, 4, true);
+    } else {
+        // odd channel counts / unaligned operands: one generic shape is enough
+        if (p.bn == 16) HCH_GEMM_CASE(128, 16, 32, 4, false);
+        else if (p.bn == 32) HCH_GEMM_CASE(128, 32, 32, 4, false);
+        else HCH_GEMM_CASE(128, 64, 32, 4, false);
+    }
 #undef HCH_GEMM_CASE
     HCH_LAUNCH_CHECK("gemm_f32_kernel");
     return HCH_OK;

@@ -290,11 +290,11 @@ template <> struct FVec<4> { typedef float type __attribute__((ext_vector_type(4
 template <int N> __device__ __forceinline__ float vget(const typename FVec<N>::type &v, int i) { return v[i]; }
 template <> __device__ __forceinline__ float vget<1>(const float &v, int) { return v; }
 
-template <typename TIN, int BM, int BN, int BK, int WM, int AMODE, bool B_KC>
+template <typename TIN, int BM, int BN, int BK, int WM, int AMODE, bool B_KC, bool VEC>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(
     const TIN *__restrict__ A, const TIN *__restrict__ B, float *__restrict__ C,
     const int32_t *__restrict__ nbr, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
-    int k_per_split, int64_t c_split_stride, int vec_ok, int c_vec_ok, unsigned m_tiles)
+    int k_per_split, int64_t c_split_stride, int c_vec_ok, unsigned m_tiles)
 {
     constexpr int WN = 4 / WM;
     constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
@@ -303,6 +303,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     static_assert((MT == 1 || MT == 2 || MT == 4) && (NT == 1 || NT == 2 || NT == 4), "1, 2 or 4 tiles");
     static_assert(BK % 16 == 0, "BK must be a multiple of 16");
     constexpr bool A_K_FAST = (AMODE == A_ROWS || AMODE == A_GATHER);   // k contiguous in memory
+    constexpr bool GATHER = (AMODE == A_GATHER || AMODE == A_GATHER_T);
     // LDS layouts.  A with k fast in memory is kept row-major As[i][k] (a lane reads 4
     // consecutive k of its row at once); A with i fast is kept k-major As[k][i] and the MT MFMA
     // tiles of a wave take interleaved rows (tile mt: rows r*MT + mt) so that a lane reads its MT
@@ -314,8 +315,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     constexpr int A_TOTAL = BM * BK / 4;              // float4 units in an A tile
     constexpr int A_UNITS = A_TOTAL / 256;
     constexpr int A_UPR = A_ROWLEN / 4;               // units per LDS row
+    constexpr int A_RSTEP = 256 / A_UPR;              // unit uu sits in row a_row0 + uu*A_RSTEP
     constexpr int B_TOTAL = BK * BN / 4;
     constexpr int B_UNITS = (B_TOTAL + 255) / 256;
+    constexpr int B_UPR = B_KC ? BK / 4 : BN / 4;
     static_assert(A_TOTAL % 256 == 0 && 256 % A_UPR == 0, "A tile must split evenly over the threads");
     typedef typename FVec<MT>::type avec_t;
     typedef typename FVec<NT>::type bvec_t;
@@ -330,6 +333,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
+    const int li = lane & 15, lk = lane >> 4;
     const int m0 = (int)mtile * BM, n0 = blockIdx.y * BN;
     const int kbeg = blockIdx.z * k_per_split;
     const int kend = min(K, kbeg + k_per_split);
@@ -342,41 +346,32 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
 #pragma unroll
         for (int b = 0; b < NT; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    f32x4 ra[A_UNITS], rb[B_UNITS];
-
-    // 4 consecutive elements starting at src; `left` = how many are inside the matrix
-    auto load4 = [&](const TIN *src, int left) {
-        f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (vec_ok && left >= 4) v = InElem<TIN>::four(src);
-        else {
-            v[0] = InElem<TIN>::one(src);
-            if (left > 1) v[1] = InElem<TIN>::one(src + 1);
-            if (left > 2) v[2] = InElem<TIN>::one(src + 2);
-            if (left > 3) v[3] = InElem<TIN>::one(src + 3);
-        }
-        return v;
-    };
-    auto gather1 = [&](int32_t j, int cc) { return j >= 0 ? InElem<TIN>::one(A + (int64_t)j * c + cc) : 0.f; };
-
     // position of this thread's units inside a tile: the same column of units in every row
     const int a_col = (tid % A_UPR) * 4;              // first of 4 elements along the fast axis
-    const int a_row0 = tid / A_UPR;                   // unit uu sits in row a_row0 + uu*(256/A_UPR)
-    constexpr int A_RSTEP = 256 / A_UPR;
-    constexpr bool GATHER = (AMODE == A_GATHER || AMODE == A_GATHER_T);
-    const bool fast_gather = GATHER && vec_ok;        // c % 4 == 0: a unit stays inside one tap
+    const int a_row0 = tid / A_UPR;
+    const int b_col = (tid % B_UPR) * 4;
+    const int b_row0 = tid / B_UPR;
+    constexpr int B_RSTEP = 256 / B_UPR;
+    const f32x4 zero4 = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // ---- VEC: every unit is one aligned 4-element load that is either wholly inside its matrix
+    // or wholly outside (the host checks that the fast dimensions are multiples of 4).  Loads
+    // are unconditional -- an outside unit reads the operand's first elements and is replaced by
+    // zeros -- so that a tile's loads are issued back to back without branches.
 
     // Gather modes, stage 1: the index of the feature row behind each unit of the tile at k0
-    // (-1 = nothing to load).  Issued two tiles ahead of use so that the dependent row loads of
-    // stage 2 never wait for it.
+    // (-1 = nothing to load).  Issued ahead of the dependent row loads of stage 2.
     auto fetch_idx = [&](int k0, int32_t *out) {
-        if (!fast_gather) return;
+        if (!GATHER || !VEC) return;
         if (AMODE == A_GATHER) {
             const int gk = k0 + a_col;
             const int tap = gk / c;
 #pragma unroll
             for (int uu = 0; uu < A_UNITS; ++uu) {
                 const int gi = m0 + a_row0 + uu * A_RSTEP;
-                out[uu] = (gi < M && gk < kend) ? nbr[(int64_t)gi * 27 + tap] : -1;
+                const bool ok = gi < M && gk < kend;
+                const int32_t j = nbr[ok ? (int64_t)gi * 27 + tap : 0];
+                out[uu] = ok ? j : -1;
             }
         } else {
             const int gi = m0 + a_col;
@@ -384,119 +379,111 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
 #pragma unroll
             for (int uu = 0; uu < A_UNITS; ++uu) {
                 const int gk = k0 + a_row0 + uu * A_RSTEP;
-                out[uu] = (gk < kend && gi < M) ? nbr[(int64_t)gk * 27 + tap] : -1;
+                const bool ok = gk < kend && gi < M;
+                const int32_t j = nbr[ok ? (int64_t)gk * 27 + tap : 0];
+                out[uu] = ok ? j : -1;
             }
         }
     };
 
+    auto one = [&](const TIN *base, int64_t off, bool ok) { return ok ? InElem<TIN>::one(base + off) : 0.f; };
+
     // stage 2: the tile starting at reduction index k0 into registers (zero outside the
     // matrices); `rows` = the indices stage 1 produced for this tile
-    auto fetch = [&](int k0, const int32_t *rows) {
-        if (A_K_FAST) {
-            const int gk = k0 + a_col;
-            int cc = 0;
-            if (AMODE == A_GATHER) cc = gk % c;
+    auto fetch = [&](int k0, const int32_t *rows, f32x4 *ra, f32x4 *rb) {
+        if (VEC) {
+            if (A_K_FAST) {
+                const int gk = k0 + a_col;
+                const int cc = (AMODE == A_GATHER) ? gk % c : 0;
 #pragma unroll
-            for (int uu = 0; uu < A_UNITS; ++uu) {
-                const int i = a_row0 + uu * A_RSTEP;
-                const int gi = m0 + i;
-                f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (AMODE == A_ROWS) {
-                    if (gi < M && gk < kend) v = load4(A + (int64_t)gi * lda + gk, kend - gk);
-                } else if (fast_gather) {
-                    const int32_t j = rows[uu];
-                    if (j >= 0) v = InElem<TIN>::four(A + (int64_t)j * c + cc);
-                } else if (gi < M) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (gk + e < kend) {
-                            const int t2 = (gk + e) / c;
-                            v[e] = gather1(nbr[(int64_t)gi * 27 + t2], gk + e - t2 * c);
-                        }
+                for (int uu = 0; uu < A_UNITS; ++uu) {
+                    const int gi = m0 + a_row0 + uu * A_RSTEP;
+                    bool ok; int64_t off;
+                    if (AMODE == A_ROWS) { ok = gi < M && gk < kend; off = (int64_t)gi * lda + gk; }
+                    else { ok = rows[uu] >= 0; off = (int64_t)rows[uu] * c + cc; }
+                    const f32x4 v = InElem<TIN>::four(A + (ok ? off : 0));
+                    ra[uu] = ok ? v : zero4;
                 }
-                ra[uu] = v;
+            } else {
+                const int gi = m0 + a_col;
+                const int cc = (AMODE == A_GATHER_T) ? gi % c : 0;
+#pragma unroll
+                for (int uu = 0; uu < A_UNITS; ++uu) {
+                    const int gk = k0 + a_row0 + uu * A_RSTEP;
+                    bool ok; int64_t off;
+                    if (AMODE == A_COLS) { ok = gk < kend && gi < M; off = (int64_t)gk * lda + gi; }
+                    else { ok = rows[uu] >= 0; off = (int64_t)rows[uu] * c + cc; }
+                    const f32x4 v = InElem<TIN>::four(A + (ok ? off : 0));
+                    ra[uu] = ok ? v : zero4;
+                }
+            }
+#pragma unroll
+            for (int uu = 0; uu < B_UNITS; ++uu) {
+                const int r = b_row0 + uu * B_RSTEP;           // row of the unit inside the B tile
+                bool ok; int64_t off;
+                if (B_KC) { const int gj = n0 + r, gk = k0 + b_col; ok = r < BN && gj < N && gk < kend; off = (int64_t)gj * ldb + gk; }
+                else { const int gk = k0 + r, gj = n0 + b_col; ok = r < BK && gk < kend && gj < N; off = (int64_t)gk * ldb + gj; }
+                const f32x4 v = InElem<TIN>::four(B + (ok ? off : 0));
+                rb[uu] = ok ? v : zero4;
             }
         } else {
-            const int gi = m0 + a_col;
-            int cc = 0;
-            if (AMODE == A_GATHER_T) cc = gi % c;
+            // any shape and alignment: element by element with every guard
 #pragma unroll
             for (int uu = 0; uu < A_UNITS; ++uu) {
-                const int gk = k0 + a_row0 + uu * A_RSTEP;
-                f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (AMODE == A_COLS) {
-                    if (gk < kend && gi < M) v = load4(A + (int64_t)gk * lda + gi, M - gi);
-                } else if (fast_gather) {
-                    const int32_t j = rows[uu];
-                    if (j >= 0) v = InElem<TIN>::four(A + (int64_t)j * c + cc);
-                } else if (gk < kend) {
+                f32x4 v = zero4;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (gi + e < M) {
-                            const int t2 = (gi + e) / c;
-                            v[e] = gather1(nbr[(int64_t)gk * 27 + t2], gi + e - t2 * c);
-                        }
+                for (int e = 0; e < 4; ++e) {
+                    int gi, gk;
+                    if (A_K_FAST) { gi = m0 + a_row0 + uu * A_RSTEP; gk = k0 + a_col + e; }
+                    else { gk = k0 + a_row0 + uu * A_RSTEP; gi = m0 + a_col + e; }
+                    const bool in = gi < M && gk < kend;
+                    if (AMODE == A_ROWS) v[e] = one(A, (int64_t)gi * lda + gk, in);
+                    else if (AMODE == A_COLS) v[e] = one(A, (int64_t)gk * lda + gi, in);
+                    else if (in) {
+                        const int kk = (AMODE == A_GATHER) ? gk : gi;      // column-matrix column
+                        const int64_t vox = (AMODE == A_GATHER) ? gi : gk; // voxel
+                        const int tap = kk / c;
+                        const int32_t j = nbr[vox * 27 + tap];
+                        v[e] = one(A, (int64_t)j * c + (kk - tap * c), j >= 0);
+                    }
                 }
                 ra[uu] = v;
             }
-        }
 #pragma unroll
-        for (int uu = 0; uu < B_UNITS; ++uu) {
-            const int f = tid + 256 * uu;
-            f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (f < B_TOTAL) {
-                if (B_KC) {
-                    const int j = f / (BK / 4), kq = f % (BK / 4);
-                    const int gj = n0 + j, gk = k0 + kq * 4;
-                    if (gj < N && gk < kend) v = load4(B + (int64_t)gj * ldb + gk, kend - gk);
-                } else {
-                    const int k = f / (BN / 4), jq = f % (BN / 4);
-                    const int gk = k0 + k, gj = n0 + jq * 4;
-                    if (gk < kend && gj < N) v = load4(B + (int64_t)gk * ldb + gj, N - gj);
+            for (int uu = 0; uu < B_UNITS; ++uu) {
+                const int r = b_row0 + uu * B_RSTEP;
+                f32x4 v = zero4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (B_KC) { const int gj = n0 + r, gk = k0 + b_col + e; v[e] = one(B, (int64_t)gj * ldb + gk, r < BN && gj < N && gk < kend); }
+                    else { const int gk = k0 + r, gj = n0 + b_col + e; v[e] = one(B, (int64_t)gk * ldb + gj, r < BK && gk < kend && gj < N); }
                 }
+                rb[uu] = v;
             }
-            rb[uu] = v;
         }
     };
 
     // registers -> LDS
-    auto stash = [&]() {
+    auto stash = [&](const f32x4 *ra, const f32x4 *rb) {
 #pragma unroll
         for (int uu = 0; uu < A_UNITS; ++uu)
             *reinterpret_cast<f32x4 *>(&As[(a_row0 + uu * A_RSTEP) * AS + a_col]) = ra[uu];
 #pragma unroll
         for (int uu = 0; uu < B_UNITS; ++uu) {
-            const int f = tid + 256 * uu;
-            if (f < B_TOTAL) {
-                if (B_KC) {
-                    const int j = f / (BK / 4), kq = f % (BK / 4);
+            const int r = b_row0 + uu * B_RSTEP;
+            if (B_KC) {
+                if (r < BN) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) Bs[(kq * 4 + e) * BS + j] = rb[uu][e];
-                } else {
-                    const int k = f / (BN / 4), jq = f % (BN / 4);
-                    *reinterpret_cast<f32x4 *>(&Bs[k * BS + jq * 4]) = rb[uu];
+                    for (int e = 0; e < 4; ++e) Bs[(b_col + e) * BS + r] = rb[uu][e];
                 }
+            } else if (r < BK) {
+                *reinterpret_cast<f32x4 *>(&Bs[r * BS + b_col]) = rb[uu];
             }
         }
     };
 
-    const int li = lane & 15, lk = lane >> 4;
-
-    int32_t rcur[A_UNITS] = {}, rnext[A_UNITS] = {};  // feature-row indices: next tile, the one after
-    if (kbeg < kend) {
-        fetch_idx(kbeg, rcur);
-        fetch(kbeg, rcur);
-        fetch_idx(kbeg + BK, rcur);
-    }
-    for (int k0 = kbeg; k0 < kend; k0 += BK) {
-        stash();
-        __syncthreads();
-        if (k0 + BK < kend) {
-            fetch_idx(k0 + 2 * BK, rnext);
-            fetch(k0 + BK, rcur);
-#pragma unroll
-            for (int uu = 0; uu < A_UNITS; ++uu) rcur[uu] = rnext[uu];
-        }
+    // all MFMAs of the tile currently in LDS
+    auto multiply = [&]() {
         if (A_K_FAST) {
 #pragma unroll
             for (int slab = 0; slab < BK / 16; ++slab) {
@@ -526,6 +513,27 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
                         acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(vget<MT>(a, mt), vget<NT>(b, nt), acc[mt][nt], 0, 0, 0);
             }
         }
+    };
+
+    // Software pipeline over the tiles of this workgroup's reduction range:
+    //   iteration t:  LDS <- registers(t);  issue index loads of t+2, row loads of t+1;  MFMAs of t.
+    f32x4 ra[A_UNITS], rb[B_UNITS];
+    int32_t rcur[A_UNITS] = {}, rnext[A_UNITS] = {};  // feature-row indices of the next tile to fetch
+    if (kbeg < kend) {
+        fetch_idx(kbeg, rcur);
+        fetch(kbeg, rcur, ra, rb);
+        fetch_idx(kbeg + BK, rcur);
+    }
+    for (int k0 = kbeg; k0 < kend; k0 += BK) {
+        stash(ra, rb);
+        __syncthreads();
+        if (k0 + BK < kend) {
+            fetch_idx(k0 + 2 * BK, rnext);
+            fetch(k0 + BK, rcur, ra, rb);
+#pragma unroll
+            for (int uu = 0; uu < A_UNITS; ++uu) rcur[uu] = rnext[uu];
+        }
+        multiply();
         __syncthreads();
     }
 
