@@ -283,6 +283,12 @@ template <> struct InElem<uint16_t> {
     }
 };
 
+// Where a unit of a tile lies outside its matrix the kernels load from these constants instead
+// (16 bytes of zeros, an index of -1): no select has to wait for the load, so a tile's loads
+// stay in flight behind the MFMAs of the previous tile.
+__device__ __attribute__((aligned(16))) uint32_t g_zero16[4] = {0u, 0u, 0u, 0u};   // never written
+__device__ int32_t g_minus1 = -1;                                                   // never written
+
 template <int N> struct FVec;
 template <> struct FVec<1> { typedef float type; };
 template <> struct FVec<2> { typedef float type __attribute__((ext_vector_type(2))); };
@@ -353,79 +359,109 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     const int b_row0 = tid / B_UPR;
     constexpr int B_RSTEP = 256 / B_UPR;
     const f32x4 zero4 = f32x4{0.f, 0.f, 0.f, 0.f};
+    const TIN *zsrc = reinterpret_cast<const TIN *>(g_zero16);
 
     // ---- VEC: every unit is one aligned 4-element load that is either wholly inside its matrix
     // or wholly outside (the host checks that the fast dimensions are multiples of 4).  Loads
-    // are unconditional -- an outside unit reads the operand's first elements and is replaced by
-    // zeros -- so that a tile's loads are issued back to back without branches.
-
-    // Gather modes, stage 1: the index of the feature row behind each unit of the tile at k0
-    // (-1 = nothing to load).  Issued ahead of the dependent row loads of stage 2.
-    auto fetch_idx = [&](int k0, int32_t *out) {
-        if (!GATHER || !VEC) return;
+    // are unconditional -- an outside unit reads a constant block of zeros -- so that a tile's
+    // loads are issued back to back, without branches and without anything waiting on them.
+    // Addresses are carried from tile to tile (pointers advanced by one tile per fetch), so the
+    // loop has no multiplications or divisions.
+    //
+    // A side.  pa[uu]: where unit uu of the next tile starts (plain modes), or the position in
+    // the index rows its feature-row index is read from (gather modes).
+    const TIN *pa[A_UNITS];
+    const int32_t *pn[A_UNITS];
+    bool a_ok[A_UNITS];                               // the unit's row (k-fast) / column (i-fast) exists
+    int ka = kbeg;                                    // reduction index of the next tile's row loads
+    int kn = kbeg;                                    // ... of the next tile's index loads
+    // gather along k (A_GATHER): tap and channel of this thread's column, for both streams
+    int tap_n = 0, cc_n = 0, cc_a = 0;
+    int dtap = 0, dcc = 0;                            // one tile further along k: BK = dtap*c + dcc
+    if (VEC) {
         if (AMODE == A_GATHER) {
-            const int gk = k0 + a_col;
-            const int tap = gk / c;
+            const int gk = kbeg + a_col;
+            tap_n = gk / c; cc_n = gk - tap_n * c; cc_a = cc_n;
+            dtap = BK / c; dcc = BK - dtap * c;
+        }
 #pragma unroll
-            for (int uu = 0; uu < A_UNITS; ++uu) {
-                const int gi = m0 + a_row0 + uu * A_RSTEP;
-                const bool ok = gi < M && gk < kend;
-                const int32_t j = nbr[ok ? (int64_t)gi * 27 + tap : 0];
-                out[uu] = ok ? j : -1;
-            }
-        } else {
-            const int gi = m0 + a_col;
-            const int tap = gi / c;
-#pragma unroll
-            for (int uu = 0; uu < A_UNITS; ++uu) {
-                const int gk = k0 + a_row0 + uu * A_RSTEP;
-                const bool ok = gk < kend && gi < M;
-                const int32_t j = nbr[ok ? (int64_t)gk * 27 + tap : 0];
-                out[uu] = ok ? j : -1;
+        for (int uu = 0; uu < A_UNITS; ++uu) {
+            const int r = a_row0 + uu * A_RSTEP;
+            if (AMODE == A_ROWS) { a_ok[uu] = m0 + r < M; pa[uu] = A + (int64_t)(m0 + r) * lda + kbeg + a_col; }
+            if (AMODE == A_COLS) { a_ok[uu] = m0 + a_col < M; pa[uu] = A + (int64_t)(kbeg + r) * lda + m0 + a_col; }
+            if (AMODE == A_GATHER) { a_ok[uu] = m0 + r < M; pn[uu] = nbr + (int64_t)(m0 + r) * 27; }
+            if (AMODE == A_GATHER_T) {
+                const int gi = m0 + a_col;
+                const int tap = gi / c;
+                cc_a = gi - tap * c;
+                a_ok[uu] = gi < M; pn[uu] = nbr + (int64_t)(kbeg + r) * 27 + tap;
             }
         }
+    }
+    // B side
+    const TIN *pb[B_UNITS];
+    bool b_ok[B_UNITS];
+    int kb = kbeg;
+    if (VEC) {
+#pragma unroll
+        for (int uu = 0; uu < B_UNITS; ++uu) {
+            const int r = b_row0 + uu * B_RSTEP;
+            if (B_KC) { b_ok[uu] = r < BN && n0 + r < N; pb[uu] = B + (int64_t)(n0 + r) * ldb + kbeg + b_col; }
+            else { b_ok[uu] = r < BK && n0 + b_col < N; pb[uu] = B + (int64_t)(kbeg + r) * ldb + n0 + b_col; }
+        }
+    }
+
+    // Gather modes, stage 1: the index of the feature row behind each unit of the next tile
+    // (-1 = nothing to load).  Issued ahead of the dependent row loads of stage 2.
+    auto fetch_idx = [&](int32_t *out) {
+        if (!GATHER || !VEC) return;
+#pragma unroll
+        for (int uu = 0; uu < A_UNITS; ++uu) {
+            bool ok;
+            if (AMODE == A_GATHER) ok = a_ok[uu] && kn + a_col < kend;
+            else ok = a_ok[uu] && kn + a_row0 + uu * A_RSTEP < kend;
+            out[uu] = *(ok ? pn[uu] + (AMODE == A_GATHER ? tap_n : 0) : &g_minus1);
+            if (AMODE == A_GATHER_T) pn[uu] += BK * 27;
+        }
+        if (AMODE == A_GATHER) {
+            tap_n += dtap; cc_n += dcc;
+            if (cc_n >= c) { cc_n -= c; ++tap_n; }
+        }
+        kn += BK;
     };
 
     auto one = [&](const TIN *base, int64_t off, bool ok) { return ok ? InElem<TIN>::one(base + off) : 0.f; };
 
-    // stage 2: the tile starting at reduction index k0 into registers (zero outside the
-    // matrices); `rows` = the indices stage 1 produced for this tile
+    // stage 2: the next tile into registers (zero outside the matrices); `rows` = the indices
+    // stage 1 produced for this tile.  The generic path takes the tile's reduction index k0.
     auto fetch = [&](int k0, const int32_t *rows, f32x4 *ra, f32x4 *rb) {
         if (VEC) {
-            if (A_K_FAST) {
-                const int gk = k0 + a_col;
-                const int cc = (AMODE == A_GATHER) ? gk % c : 0;
 #pragma unroll
-                for (int uu = 0; uu < A_UNITS; ++uu) {
-                    const int gi = m0 + a_row0 + uu * A_RSTEP;
-                    bool ok; int64_t off;
-                    if (AMODE == A_ROWS) { ok = gi < M && gk < kend; off = (int64_t)gi * lda + gk; }
-                    else { ok = rows[uu] >= 0; off = (int64_t)rows[uu] * c + cc; }
-                    const f32x4 v = InElem<TIN>::four(A + (ok ? off : 0));
-                    ra[uu] = ok ? v : zero4;
-                }
-            } else {
-                const int gi = m0 + a_col;
-                const int cc = (AMODE == A_GATHER_T) ? gi % c : 0;
-#pragma unroll
-                for (int uu = 0; uu < A_UNITS; ++uu) {
-                    const int gk = k0 + a_row0 + uu * A_RSTEP;
-                    bool ok; int64_t off;
-                    if (AMODE == A_COLS) { ok = gk < kend && gi < M; off = (int64_t)gk * lda + gi; }
-                    else { ok = rows[uu] >= 0; off = (int64_t)rows[uu] * c + cc; }
-                    const f32x4 v = InElem<TIN>::four(A + (ok ? off : 0));
-                    ra[uu] = ok ? v : zero4;
+            for (int uu = 0; uu < A_UNITS; ++uu) {
+                if (AMODE == A_ROWS) {
+                    const bool ok = a_ok[uu] && ka + a_col < kend;
+                    ra[uu] = InElem<TIN>::four(ok ? pa[uu] : zsrc);
+                    pa[uu] += BK;
+                } else if (AMODE == A_COLS) {
+                    const bool ok = a_ok[uu] && ka + a_row0 + uu * A_RSTEP < kend;
+                    ra[uu] = InElem<TIN>::four(ok ? pa[uu] : zsrc);
+                    pa[uu] += (int64_t)BK * lda;
+                } else {
+                    const int32_t j = rows[uu];
+                    ra[uu] = InElem<TIN>::four(j >= 0 ? A + (uint32_t)(j * c + cc_a) : zsrc);
                 }
             }
+            if (AMODE == A_GATHER) { cc_a += dcc; if (cc_a >= c) cc_a -= c; }
+            ka += BK;
 #pragma unroll
             for (int uu = 0; uu < B_UNITS; ++uu) {
-                const int r = b_row0 + uu * B_RSTEP;           // row of the unit inside the B tile
-                bool ok; int64_t off;
-                if (B_KC) { const int gj = n0 + r, gk = k0 + b_col; ok = r < BN && gj < N && gk < kend; off = (int64_t)gj * ldb + gk; }
-                else { const int gk = k0 + r, gj = n0 + b_col; ok = r < BK && gk < kend && gj < N; off = (int64_t)gk * ldb + gj; }
-                const f32x4 v = InElem<TIN>::four(B + (ok ? off : 0));
-                rb[uu] = ok ? v : zero4;
+                bool ok;
+                if (B_KC) ok = b_ok[uu] && kb + b_col < kend;
+                else ok = b_ok[uu] && kb + b_row0 + uu * B_RSTEP < kend;
+                rb[uu] = InElem<TIN>::four(ok ? pb[uu] : zsrc);
+                pb[uu] += B_KC ? (int64_t)BK : (int64_t)BK * ldb;
             }
+            kb += BK;
         } else {
             // any shape and alignment: element by element with every guard
 #pragma unroll
@@ -517,24 +553,28 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
 
     // Software pipeline over the tiles of this workgroup's reduction range:
     //   iteration t:  LDS <- registers(t);  issue index loads of t+2, row loads of t+1;  MFMAs of t.
+    // The two index register sets alternate (no copies, so nothing waits on the index loads
+    // before the row loads of the following iteration need them).
     f32x4 ra[A_UNITS], rb[B_UNITS];
-    int32_t rcur[A_UNITS] = {}, rnext[A_UNITS] = {};  // feature-row indices of the next tile to fetch
-    if (kbeg < kend) {
-        fetch_idx(kbeg, rcur);
-        fetch(kbeg, rcur, ra, rb);
-        fetch_idx(kbeg + BK, rcur);
-    }
-    for (int k0 = kbeg; k0 < kend; k0 += BK) {
+    int32_t rx[A_UNITS] = {}, ry[A_UNITS] = {};
+    auto iteration = [&](int k0, int32_t *use, int32_t *load) {
         stash(ra, rb);
         __syncthreads();
         if (k0 + BK < kend) {
-            fetch_idx(k0 + 2 * BK, rnext);
-            fetch(k0 + BK, rcur, ra, rb);
-#pragma unroll
-            for (int uu = 0; uu < A_UNITS; ++uu) rcur[uu] = rnext[uu];
+            fetch_idx(load);
+            fetch(k0 + BK, use, ra, rb);
         }
         multiply();
         __syncthreads();
+    };
+    if (kbeg < kend) {
+        fetch_idx(ry);
+        fetch(kbeg, ry, ra, rb);
+        fetch_idx(rx);
+    }
+    for (int k0 = kbeg; k0 < kend; k0 += 2 * BK) {
+        iteration(k0, rx, ry);
+        if (k0 + BK < kend) iteration(k0 + BK, ry, rx);
     }
 
     // D layout of v_mfma_f32_16x16x4_f32: register e of lane l holds D[4*(l/16) + e][l%16].
