@@ -136,7 +136,8 @@ hch_status hch_level_info(const hch_levels *levels, int32_t level, hch_level_des
  * tag test of Section 3.1), the "pre-stored neighbour information" of Section 5.3:
  * nbr27 of `level`, and child8 of `level` (looked up in level-1's tables) when level > 0.
  * This is the index side of the traversal of Algorithm 1, done once per level and batch
- * instead of once per channel.  Asynchronous on `stream`.
+ * instead of once per channel.  level = -1 does every level (two launches in all).
+ * Asynchronous on `stream`.
  */
 hch_status hch_build_neighbours(hch_levels *levels, int32_t level, void *stream);
 

@@ -87,6 +87,11 @@ constexpr int64_t MAX_GRID_ITEMS = (int64_t)2147483647 * 256;   // grid.x limit 
 
 struct hch_levels {
     std::vector<Level> lv;
+    // one-launch index-list kernels: all levels as a kernel argument, and the tile prefix
+    // arrays (host copy + device) of the neighbour and child kernels
+    hch::LevelSet set{};
+    std::vector<int32_t> nbr_prefix, child_prefix;
+    int32_t *d_nbr_prefix = nullptr, *d_child_prefix = nullptr;
 };
 
 extern "C" const char *hch_last_error(void) { return g_err.c_str(); }
@@ -95,6 +100,8 @@ extern "C" void hch_free_levels(hch_levels *levels)
 {
     if (!levels) return;
     for (Level &L : levels->lv) free_level(L);
+    if (levels->d_nbr_prefix) (void)hipFree(levels->d_nbr_prefix);
+    if (levels->d_child_prefix) (void)hipFree(levels->d_child_prefix);
     delete levels;
 }
 
@@ -116,45 +123,49 @@ static hch_status upload(void **dst, const void *src, size_t bytes, hipStream_t 
     return HCH_OK;
 }
 
-// grid.x tiles of 256 voxels over the largest model, grid.y = model
-static hch_status launch_neighbours(const Level &L, hipStream_t s)
+// index lists of levels [l0, l1) in one launch each
+static hch_status launch_index_lists(const hch_levels *hl, int l0, int l1, hipStream_t s)
 {
-    if (L.max_n == 0) return HCH_OK;
-    dim3 grid(blocks_for(L.max_n), (unsigned)L.b);
+    const int b = hl->lv[0].b;
+    const int n_entries = (int)hl->lv.size() * b;
     {
-        // per voxel: its position in, 27 indices out; the level's tables once
-        const double bytes = (double)L.n_total * (12.0 + 108.0) + (double)L.m_total * 10.0 + (double)L.r_total * 3.0;
-        hch::LaunchTimer lt(HCH_KERNEL_ID("neighbour_kernel"), s, bytes, 0.0);
-        hipLaunchKernelGGL(hch::neighbour_kernel, grid, dim3(256), 0, s, L.view(), L.dcoords, L.dnbr);
+        const int first = hl->nbr_prefix[(size_t)l0 * b], last = hl->nbr_prefix[(size_t)l1 * b];
+        if (last > first) {
+            double bytes = 0.0;   // per voxel: its position in, 27 indices out; the level's tables once
+            for (int l = l0; l < l1; ++l)
+                bytes += (double)hl->lv[l].n_total * 120.0 + (double)hl->lv[l].m_total * 10.0 + (double)hl->lv[l].r_total * 3.0;
+            const unsigned n_tiles = (unsigned)(last - first);
+            const unsigned grid = (n_tiles + hch::NUM_XCD - 1) / hch::NUM_XCD * hch::NUM_XCD;
+            hch::LaunchTimer lt(HCH_KERNEL_ID("neighbour_kernel"), s, bytes, 0.0);
+            hipLaunchKernelGGL(hch::neighbour_kernel, dim3(grid), dim3(256), 0, s, hl->set, hl->d_nbr_prefix,
+                               n_entries, first, n_tiles);
+        }
+        HCH_LAUNCH_CHECK("neighbour_kernel");
     }
-    HCH_LAUNCH_CHECK("neighbour_kernel");
-    return HCH_OK;
-}
-
-static hch_status launch_children(const Level &Lf, const Level &Lc, hipStream_t s)
-{
-    if (Lc.max_n == 0) return HCH_OK;
-    dim3 grid(blocks_for(Lc.max_n), (unsigned)Lc.b);
     {
-        const double bytes = (double)Lc.n_total * (12.0 + 32.0) + (double)Lf.m_total * 10.0 + (double)Lf.r_total * 3.0;
-        hch::LaunchTimer lt(HCH_KERNEL_ID("child_kernel"), s, bytes, 0.0);
-        hipLaunchKernelGGL(hch::child_kernel, grid, dim3(256), 0, s, Lf.view(), Lc.dcoords, Lc.dN(), Lc.dchild);
+        const int first = hl->child_prefix[(size_t)l0 * b], last = hl->child_prefix[(size_t)l1 * b];
+        if (last > first) {
+            double bytes = 0.0;   // per coarse voxel: position in, 8 indices out; the finer tables once
+            for (int l = std::max(l0, 1); l < l1; ++l)
+                bytes += (double)hl->lv[l].n_total * 44.0 + (double)hl->lv[l - 1].m_total * 10.0 + (double)hl->lv[l - 1].r_total * 3.0;
+            const unsigned n_tiles = (unsigned)(last - first);
+            const unsigned grid = (n_tiles + hch::NUM_XCD - 1) / hch::NUM_XCD * hch::NUM_XCD;
+            hch::LaunchTimer lt(HCH_KERNEL_ID("child_kernel"), s, bytes, 0.0);
+            hipLaunchKernelGGL(hch::child_kernel, dim3(grid), dim3(256), 0, s, hl->set, hl->d_child_prefix,
+                               n_entries, first, n_tiles);
+        }
+        HCH_LAUNCH_CHECK("child_kernel");
     }
-    HCH_LAUNCH_CHECK("child_kernel");
     return HCH_OK;
 }
 
 extern "C" hch_status hch_build_neighbours(hch_levels *levels, int32_t level, void *stream)
 {
-    if (!levels || level < 0 || level >= (int32_t)levels->lv.size())
+    if (!levels || level < -1 || level >= (int32_t)levels->lv.size())
         return fail(HCH_EINVAL, "hch_build_neighbours: bad level");
-    hipStream_t s = (hipStream_t)stream;
-    Level &L = levels->lv[level];
-    if (!L.dnbr) return fail(HCH_EINVAL, "hch_build_neighbours: levels were built without device tables");
-    hch_status st = launch_neighbours(L, s);
-    if (st != HCH_OK) return st;
-    if (level > 0) st = launch_children(levels->lv[level - 1], L, s);
-    return st;
+    if (!levels->d_nbr_prefix) return fail(HCH_EINVAL, "hch_build_neighbours: levels were built without device tables");
+    if (level < 0) return launch_index_lists(levels, 0, (int)levels->lv.size(), (hipStream_t)stream);
+    return launch_index_lists(levels, level, level + 1, (hipStream_t)stream);
 }
 
 static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_offsets,
@@ -316,7 +327,30 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
             hipError_t e = hipStreamSynchronize(s);
             if (e != hipSuccess) { st = fail(HCH_EHIP, std::string("hipStreamSynchronize: ") + hipGetErrorString(e)); break; }
         }
-        for (int l = 0; l < n_levels && st == HCH_OK && with_device; ++l) st = hch_build_neighbours(hl, l, s);
+        if (st == HCH_OK && with_device) {
+            if (n_levels > hch::MAX_LEVELS) st = fail(HCH_EUNSUPPORTED, "hch_build_levels: too many levels");
+        }
+        if (st == HCH_OK && with_device) {
+            hl->set.batch = batch;
+            hl->nbr_prefix.assign((size_t)n_levels * batch + 1, 0);
+            hl->child_prefix.assign((size_t)n_levels * batch + 1, 0);
+            for (int l = 0; l < n_levels; ++l) {
+                Level &L = hl->lv[l];
+                hl->set.view[l] = L.view();
+                hl->set.coords[l] = L.dcoords;
+                hl->set.nbr[l] = L.dnbr;
+                hl->set.child[l] = L.dchild;
+                for (int v = 0; v < batch; ++v) {
+                    const int32_t tiles = (int32_t)((L.N[v + 1] - L.N[v] + 255) / 256);
+                    const size_t e = (size_t)l * batch + v;
+                    hl->nbr_prefix[e + 1] = hl->nbr_prefix[e] + tiles;
+                    hl->child_prefix[e + 1] = hl->child_prefix[e] + (l > 0 ? tiles : 0);
+                }
+            }
+            if ((st = upload((void **)&hl->d_nbr_prefix, hl->nbr_prefix.data(), hl->nbr_prefix.size() * 4, s)) == HCH_OK)
+                st = upload((void **)&hl->d_child_prefix, hl->child_prefix.data(), hl->child_prefix.size() * 4, s);
+            if (st == HCH_OK) st = hch_build_neighbours(hl, -1, s);
+        }
         if (st == HCH_OK && with_device) {
             hipError_t e = hipStreamSynchronize(s);
             if (e != hipSuccess) st = fail(HCH_EHIP, std::string("hipStreamSynchronize: ") + hipGetErrorString(e));

@@ -64,26 +64,54 @@ __device__ __forceinline__ int32_t psh_probe(const PshView &L, unsigned Mv, unsi
     return ((int32_t)h >= 0 && xy == (x | (y << 16)) && zz == z) ? (int32_t)h : -1;
 }
 
-// "Pre-stored neighbour information": for every voxel i of model v = blockIdx.y the global
-// data indices of its 27 neighbours p + (dx,dy,dz), tap k = (dx+1)*9 + (dy+1)*3 + (dz+1), or -1
-// (empty, or outside the grid: never hashed).  This is the index side of the stride-1
-// traversal of Algorithm 1.  One thread per voxel: the six residues are computed once and
-// stepped to the neighbours; the 256 x 27 tile goes through LDS so that the rows are written
-// coalesced.
+// All levels of a hierarchy, as one kernel argument: the index-list kernels cover every
+// (level, model) in a single launch.  Work is cut into tiles of 256 voxels of one model at one
+// level; tile_prefix[e] = number of tiles before entry e = level*batch + model (level-major),
+// so a workgroup finds its entry by a short binary search with wave-uniform loads.
+constexpr int MAX_LEVELS = 16;
+struct LevelSet {
+    PshView view[MAX_LEVELS];
+    const int32_t *coords[MAX_LEVELS];
+    int32_t *nbr[MAX_LEVELS];
+    int32_t *child[MAX_LEVELS];      // children (at level l-1) of level l's voxels; null for l = 0
+    int32_t batch;
+};
+
+__device__ __forceinline__ int find_entry(const int32_t *__restrict__ prefix, int n_entries, int tile)
+{
+    int lo = 0, hi = n_entries;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (prefix[mid] <= tile) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// "Pre-stored neighbour information": for every voxel the global data indices of its 27
+// neighbours p + (dx,dy,dz), tap k = (dx+1)*9 + (dy+1)*3 + (dz+1), or -1 (empty, or outside
+// the grid: never hashed).  This is the index side of the stride-1 traversal of Algorithm 1.
+// One thread per voxel: the six residues are computed once and stepped to the neighbours; the
+// 256 x 27 tile goes through LDS so that the rows are written coalesced.  Tiles
+// [tile_first, tile_first + n_tiles) are processed, numbered XCD-contiguously: the tiles of one
+// model (whose tables are a few hundred KB) then stay in one XCD's L2.
 __global__ __launch_bounds__(256) void neighbour_kernel(
-    PshView L, const int32_t *__restrict__ coords, int32_t *__restrict__ nbr)
+    LevelSet S, const int32_t *__restrict__ tile_prefix, int n_entries, int tile_first, unsigned n_tiles)
 {
     __shared__ int32_t tile[256 * 27];
-    const int v = blockIdx.y;
+    const unsigned t = xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
+    if (t >= n_tiles) return;
+    const int flat = tile_first + (int)t;
+    const int e = find_entry(tile_prefix, n_entries, flat);
+    const int lev = e / S.batch, v = e - lev * S.batch;
+    const PshView &L = S.view[lev];
     const int32_t base = L.N[v];
     const int32_t n = L.N[v + 1] - base;
-    const int32_t blk0 = blockIdx.x * 256;
-    if (blk0 >= n) return;
+    const int32_t blk0 = (flat - tile_prefix[e]) * 256;
     const int32_t i = blk0 + threadIdx.x;
     if (i < n) {
         const unsigned m = (unsigned)L.mbar[v], r = (unsigned)L.rbar[v];
         const unsigned Mv = (unsigned)L.M[v], Rv = (unsigned)L.R[v], u = (unsigned)L.ubar;
-        const int32_t *p = coords + 3 * (int64_t)(base + i);
+        const int32_t *p = S.coords[lev] + 3 * (int64_t)(base + i);
         const unsigned x = (unsigned)p[0], y = (unsigned)p[1], z = (unsigned)p[2];
         unsigned xm[3], ym[3], zm[3], xr[3], yr[3], zr[3];
         residues3(x % m, m, xm); residues3(y % m, m, ym); residues3(z % m, m, zm);
@@ -104,26 +132,32 @@ __global__ __launch_bounds__(256) void neighbour_kernel(
     }
     __syncthreads();
     const int32_t cnt = min(256, n - blk0) * 27;
-    int32_t *dst = nbr + (int64_t)(base + blk0) * 27;
-    for (int t = threadIdx.x; t < cnt; t += 256) dst[t] = tile[t];
+    int32_t *dst = S.nbr[lev] + (int64_t)(base + blk0) * 27;
+    for (int q = threadIdx.x; q < cnt; q += 256) dst[q] = tile[q];
 }
 
-// For every coarse voxel i of model v = blockIdx.y the global data indices, at the next finer
-// level, of its 8 children 2p + (dx,dy,dz), k = dx*4 + dy*2 + dz, or -1: the stride-2, F = 2,
-// no-padding traversal of Algorithm 1 (receptive field [2p, 2p+1]^3).  Lf = the FINE level.
+// For every coarse voxel the global data indices, at the next finer level, of its 8 children
+// 2p + (dx,dy,dz), k = dx*4 + dy*2 + dz, or -1: the stride-2, F = 2, no-padding traversal of
+// Algorithm 1 (receptive field [2p, 2p+1]^3).  Same tiling as above; entries of level 0 have no
+// tiles in this kernel's prefix.
 __global__ __launch_bounds__(256) void child_kernel(
-    PshView Lf, const int32_t *__restrict__ coarse_coords, const int32_t *__restrict__ Nc,
-    int32_t *__restrict__ child)
+    LevelSet S, const int32_t *__restrict__ tile_prefix, int n_entries, int tile_first, unsigned n_tiles)
 {
-    const int v = blockIdx.y;
+    const unsigned t = xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
+    if (t >= n_tiles) return;
+    const int flat = tile_first + (int)t;
+    const int e = find_entry(tile_prefix, n_entries, flat);
+    const int lev = e / S.batch, v = e - lev * S.batch;      // lev >= 1
+    const PshView &Lf = S.view[lev - 1];
+    const int32_t *Nc = S.view[lev].N;
     const int32_t cbase = Nc[v];
     const int32_t n = Nc[v + 1] - cbase;
-    const int32_t i = blockIdx.x * 256 + threadIdx.x;
+    const int32_t i = (flat - tile_prefix[e]) * 256 + threadIdx.x;
     if (i >= n) return;
     const unsigned m = (unsigned)Lf.mbar[v], r = (unsigned)Lf.rbar[v];
     const unsigned Mv = (unsigned)Lf.M[v], Rv = (unsigned)Lf.R[v];
     const int32_t fbase = Lf.N[v];
-    const int32_t *p = coarse_coords + 3 * (int64_t)(cbase + i);
+    const int32_t *p = S.coords[lev] + 3 * (int64_t)(cbase + i);
     const unsigned x = 2u * (unsigned)p[0], y = 2u * (unsigned)p[1], z = 2u * (unsigned)p[2];
     unsigned xm[2], ym[2], zm[2], xr[2], yr[2], zr[2];
     xm[0] = x % m; xm[1] = xm[0] + 1 == m ? 0 : xm[0] + 1;
@@ -144,7 +178,7 @@ __global__ __launch_bounds__(256) void child_kernel(
                                             x + a, y + b, z + c);
                 out[a * 4 + b * 2 + c] = h >= 0 ? fbase + h : -1;
             }
-    int4 *dst = reinterpret_cast<int4 *>(child + (int64_t)(cbase + i) * 8);
+    int4 *dst = reinterpret_cast<int4 *>(S.child[lev] + (int64_t)(cbase + i) * 8);
     dst[0] = make_int4(out[0], out[1], out[2], out[3]);
     dst[1] = make_int4(out[4], out[5], out[6], out[7]);
 }
@@ -326,7 +360,6 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     constexpr int B_UNITS = (B_TOTAL + 255) / 256;
     constexpr int B_UPR = B_KC ? BK / 4 : BN / 4;
     static_assert(A_TOTAL % 256 == 0 && 256 % A_UPR == 0, "A tile must split evenly over the threads");
-    typedef typename FVec<MT>::type avec_t;
     typedef typename FVec<NT>::type bvec_t;
 
     __shared__ __attribute__((aligned(16))) float As[A_K_FAST ? BM * AS : BK * AS];
@@ -518,41 +551,59 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
         }
     };
 
-    // all MFMAs of the tile currently in LDS
-    auto multiply = [&]() {
-        if (A_K_FAST) {
+    // The wave's operands of the tile in LDS, all of them, into registers: one LDS latency per
+    // tile instead of one per slab, and LDS is free again (second barrier) before the MFMAs run.
+    constexpr int A_REGS = A_K_FAST ? (BK / 16) * MT : BK / 4;
+    constexpr int B_REGS = A_K_FAST ? BK / 4 : BK / 4;
+    typedef typename FVec<A_K_FAST ? 4 : MT>::type areg_t;
+    areg_t oa[A_REGS];
+    bvec_t ob[B_REGS];
+    auto load_operands = [&]() {
+        if constexpr (A_K_FAST) {
 #pragma unroll
             for (int slab = 0; slab < BK / 16; ++slab) {
-                f32x4 a[MT];
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
-                    a[mt] = *reinterpret_cast<const f32x4 *>(&As[(wm * WTM + mt * 16 + li) * AS + slab * 16 + lk * 4]);
+                    oa[slab * MT + mt] = *reinterpret_cast<const areg_t *>(&As[(wm * WTM + mt * 16 + li) * AS + slab * 16 + lk * 4]);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const bvec_t b = *reinterpret_cast<const bvec_t *>(&Bs[(slab * 16 + lk * 4 + e) * BS + wn * WTN + li * NT]);
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt)
-                            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[mt][e], vget<NT>(b, nt), acc[mt][nt], 0, 0, 0);
-                }
+                for (int e = 0; e < 4; ++e)
+                    ob[slab * 4 + e] = *reinterpret_cast<const bvec_t *>(&Bs[(slab * 16 + lk * 4 + e) * BS + wn * WTN + li * NT]);
             }
         } else {
 #pragma unroll
             for (int kk = 0; kk < BK / 4; ++kk) {
-                const avec_t a = *reinterpret_cast<const avec_t *>(&As[(kk * 4 + lk) * AS + wm * WTM + li * MT]);
-                const bvec_t b = *reinterpret_cast<const bvec_t *>(&Bs[(kk * 4 + lk) * BS + wn * WTN + li * NT]);
+                oa[kk] = *reinterpret_cast<const areg_t *>(&As[(kk * 4 + lk) * AS + wm * WTM + li * MT]);
+                ob[kk] = *reinterpret_cast<const bvec_t *>(&Bs[(kk * 4 + lk) * BS + wn * WTN + li * NT]);
+            }
+        }
+    };
+    auto multiply = [&]() {
+        if constexpr (A_K_FAST) {
+#pragma unroll
+            for (int slab = 0; slab < BK / 16; ++slab)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt)
+                            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(
+                                vget<4>(oa[slab * MT + mt], e), vget<NT>(ob[slab * 4 + e], nt), acc[mt][nt], 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < BK / 4; ++kk)
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
-                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(vget<MT>(a, mt), vget<NT>(b, nt), acc[mt][nt], 0, 0, 0);
-            }
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(
+                            vget<A_K_FAST ? 4 : MT>(oa[kk], mt), vget<NT>(ob[kk], nt), acc[mt][nt], 0, 0, 0);
         }
     };
 
     // Software pipeline over the tiles of this workgroup's reduction range:
-    //   iteration t:  LDS <- registers(t);  issue index loads of t+2, row loads of t+1;  MFMAs of t.
+    //   iteration t:  LDS <- registers(t);  issue index loads of t+2, row loads of t+1;
+    //                 LDS -> operand registers;  MFMAs of t.
     // The two index register sets alternate (no copies, so nothing waits on the index loads
     // before the row loads of the following iteration need them).
     f32x4 ra[A_UNITS], rb[B_UNITS];
@@ -564,8 +615,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
             fetch_idx(load);
             fetch(k0 + BK, use, ra, rb);
         }
-        multiply();
+        load_operands();
         __syncthreads();
+        multiply();
     };
     if (kbeg < kend) {
         fetch_idx(ry);

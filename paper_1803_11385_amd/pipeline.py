@@ -47,8 +47,7 @@ class Encoder:
         return sum(3 * 2 * 27 * self.channels[l] * self.channels[l + 1] * self.n[l] for l in range(self.L))
 
     def build_indices(self):
-        for l in range(self.L + 1):
-            B.hch_build_neighbours(self.levels, l)
+        B.hch_build_neighbours(self.levels, -1)
 
     def forward(self):
         ch = self.channels
