@@ -47,21 +47,30 @@ __device__ __forceinline__ void residues3(unsigned q_mod, unsigned d, unsigned o
     out[2] = q_mod + 1 == d ? 0 : q_mod + 1;
 }
 
-// One probe: position (x,y,z) with residues (xm,ym,zm) mod m and (xr,yr,zr) mod r in the
-// tables of a model whose slots start at Mv and offset cells at Rv.  Returns the local data
-// index, or -1 on a redundant slot or a slot tagged with another position (Section 3.1).
-__device__ __forceinline__ int32_t psh_probe(const PshView &L, unsigned Mv, unsigned Rv, unsigned m,
-                                             unsigned r, unsigned xm, unsigned ym, unsigned zm,
-                                             unsigned xr, unsigned yr, unsigned zr,
-                                             unsigned x, unsigned y, unsigned z)
+// A probe in two steps, so that a thread can have the loads of many probes in flight at once.
+// Step 1: the offset cell of a position with residues (xr,yr,zr) mod r (Eq.4).
+__device__ __forceinline__ uint32_t psh_offset(const PshView &L, unsigned Rv, unsigned r,
+                                               unsigned xr, unsigned yr, unsigned zr)
 {
-    const uint32_t ph = L.phi4[Rv + (xr * r + yr) * r + zr];                 // Eq.4
-    unsigned hx = xm + (ph & 255u);         if (hx >= m) hx -= m;             // Eq.1
+    return L.phi4[Rv + (xr * r + yr) * r + zr];
+}
+// Step 2: the slot record of a position with residues (xm,ym,zm) mod m, given its offset cell
+// (Eq.1, Eq.5).
+__device__ __forceinline__ const uint32_t *psh_slot(const PshView &L, unsigned Mv, unsigned m, uint32_t ph,
+                                                    unsigned xm, unsigned ym, unsigned zm)
+{
+    unsigned hx = xm + (ph & 255u);         if (hx >= m) hx -= m;
     unsigned hy = ym + ((ph >> 8) & 255u);  if (hy >= m) hy -= m;
     unsigned hz = zm + ((ph >> 16) & 255u); if (hz >= m) hz -= m;
-    const uint32_t *rec = L.slot3 + 3u * (size_t)(Mv + (hx * m + hy) * m + hz);   // Eq.5
-    const uint32_t h = rec[0], xy = rec[1], zz = rec[2];
-    return ((int32_t)h >= 0 && xy == (x | (y << 16)) && zz == z) ? (int32_t)h : -1;
+    return L.slot3 + 3u * (size_t)(Mv + (hx * m + hy) * m + hz);
+}
+// Step 3: the local data index if the record is occupied and tagged with (x,y,z), else -1
+// (Section 3.1: redundant slot, or a slot that belongs to another position).
+__device__ __forceinline__ int32_t psh_match(uint32_t h, uint32_t xy, uint32_t zz,
+                                             unsigned x, unsigned y, unsigned z)
+{
+    const bool hit = ((int32_t)h >= 0) & (xy == (x | (y << 16))) & (zz == z);
+    return hit ? (int32_t)h : -1;
 }
 
 // All levels of a hierarchy, as one kernel argument: the index-list kernels cover every
@@ -117,18 +126,28 @@ __global__ __launch_bounds__(256) void neighbour_kernel(
         residues3(x % m, m, xm); residues3(y % m, m, ym); residues3(z % m, m, zm);
         residues3(x % r, r, xr); residues3(y % r, r, yr); residues3(z % r, r, zr);
         int32_t *row = tile + threadIdx.x * 27;
+        // one x-plane of 9 neighbours at a time: 9 offset loads, then 9 record loads, then the
+        // comparisons.  Positions outside the grid are probed too (their residues are valid
+        // table coordinates) and discarded afterwards, so there is no branch between the loads.
 #pragma unroll
-        for (int a = 0; a < 3; ++a)
+        for (int a = 0; a < 3; ++a) {
+            uint32_t ph[9];
 #pragma unroll
-            for (int b = 0; b < 3; ++b)
+            for (int q = 0; q < 9; ++q) ph[q] = psh_offset(L, Rv, r, xr[a], yr[q / 3], zr[q % 3]);
+            uint32_t rh[9], rxy[9], rz[9];
 #pragma unroll
-                for (int c = 0; c < 3; ++c) {
-                    const unsigned qx = x + a - 1, qy = y + b - 1, qz = z + c - 1;   // wraps below 0
-                    int32_t h = -1;
-                    if (qx < u && qy < u && qz < u)
-                        h = psh_probe(L, Mv, Rv, m, r, xm[a], ym[b], zm[c], xr[a], yr[b], zr[c], qx, qy, qz);
-                    row[a * 9 + b * 3 + c] = h >= 0 ? base + h : -1;                 // Eq.6
-                }
+            for (int q = 0; q < 9; ++q) {
+                const uint32_t *rec = psh_slot(L, Mv, m, ph[q], xm[a], ym[q / 3], zm[q % 3]);
+                rh[q] = rec[0]; rxy[q] = rec[1]; rz[q] = rec[2];
+            }
+#pragma unroll
+            for (int q = 0; q < 9; ++q) {
+                const unsigned qx = x + a - 1, qy = y + q / 3 - 1, qz = z + q % 3 - 1;   // wrap below 0
+                const int32_t h = psh_match(rh[q], rxy[q], rz[q], qx, qy, qz);
+                const bool inside = (qx < u) & (qy < u) & (qz < u);
+                row[a * 9 + q] = (inside & (h >= 0)) ? base + h : -1;                    // Eq.6
+            }
+        }
     }
     __syncthreads();
     const int32_t cnt = min(256, n - blk0) * 27;
@@ -167,17 +186,20 @@ __global__ __launch_bounds__(256) void child_kernel(
     yr[0] = y % r; yr[1] = yr[0] + 1 == r ? 0 : yr[0] + 1;
     zr[0] = z % r; zr[1] = zr[0] + 1 == r ? 0 : zr[0] + 1;
     int32_t out[8];
+    uint32_t ph[8], rh[8], rxy[8], rz[8];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int q = 0; q < 8; ++q) ph[q] = psh_offset(Lf, Rv, r, xr[q >> 2], yr[(q >> 1) & 1], zr[q & 1]);
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+    for (int q = 0; q < 8; ++q) {
+        const uint32_t *rec = psh_slot(Lf, Mv, m, ph[q], xm[q >> 2], ym[(q >> 1) & 1], zm[q & 1]);
+        rh[q] = rec[0]; rxy[q] = rec[1]; rz[q] = rec[2];
+    }
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                // 2p + 1 < 2 * (coarse side) = fine side: always inside the grid
-                const int32_t h = psh_probe(Lf, Mv, Rv, m, r, xm[a], ym[b], zm[c], xr[a], yr[b], zr[c],
-                                            x + a, y + b, z + c);
-                out[a * 4 + b * 2 + c] = h >= 0 ? fbase + h : -1;
-            }
+    for (int q = 0; q < 8; ++q) {
+        // 2p + 1 < 2 * (coarse side) = fine side: always inside the grid
+        const int32_t h = psh_match(rh[q], rxy[q], rz[q], x + (q >> 2), y + ((q >> 1) & 1), z + (q & 1));
+        out[q] = h >= 0 ? fbase + h : -1;
+    }
     int4 *dst = reinterpret_cast<int4 *>(S.child[lev] + (int64_t)(cbase + i) * 8);
     dst[0] = make_int4(out[0], out[1], out[2], out[3]);
     dst[1] = make_int4(out[4], out[5], out[6], out[7]);
