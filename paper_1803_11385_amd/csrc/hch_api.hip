@@ -443,9 +443,9 @@ static hch_status do_hash2col(const Level &L, hch_dtype dtype, const void *X, in
     const unsigned n_tiles = (unsigned)((rows + tv - 1) / tv);
     const unsigned grid = (n_tiles + hch::NUM_XCD - 1) / hch::NUM_XCD * hch::NUM_XCD;
     if (row_bytes % 16 == 0 && aligned16(X) && aligned16(col)) {
-        hch::LaunchTimer lt(HCH_KERNEL_ID("hash2col_kernel<HIP_vector_type<unsigned int, 4u> >"), s, bytes, 0.0);
-        hipLaunchKernelGGL(hch::hash2col_kernel<uint4>, dim3(grid), dim3(256), 0, s,
-                           (const uint4 *)X, L.dnbr, (uint4 *)col, row_begin, rows, row_bytes / 16, tv, n_tiles);
+        hch::LaunchTimer lt(HCH_KERNEL_ID("hash2col_kernel<unsigned int __vector(4)>"), s, bytes, 0.0);
+        hipLaunchKernelGGL(hch::hash2col_kernel<hch::u32x4>, dim3(grid), dim3(256), 0, s,
+                           (const hch::u32x4 *)X, L.dnbr, (hch::u32x4 *)col, row_begin, rows, row_bytes / 16, tv, n_tiles);
     } else {
         hch::LaunchTimer lt(dtype == HCH_F32 ? HCH_KERNEL_ID("hash2col_kernel<float>") : HCH_KERNEL_ID("hash2col_kernel<unsigned short>"), s, bytes, 0.0);
         if (dtype == HCH_F32)

@@ -9,6 +9,7 @@
 namespace hch {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte unit of anything
 
 // Workgroups are handed to the 8 XCDs (each with its own L2) round-robin.  Kernels whose
 // neighbouring tiles touch the same memory launch 8*per_xcd workgroups and use this mapping
@@ -18,6 +19,12 @@ __device__ __forceinline__ unsigned xcd_tile(unsigned bid, unsigned per_xcd)
 {
     return (bid % NUM_XCD) * per_xcd + bid / NUM_XCD;
 }
+
+// Where there is nothing to load (an empty neighbour, a unit of a tile outside its matrix) the
+// kernels load from these constants instead (16 bytes of zeros, an index of -1): loads stay
+// unconditional, so a thread issues all of them back to back and nothing waits on a branch.
+__device__ __attribute__((aligned(16))) uint32_t g_zero16[4] = {0u, 0u, 0u, 0u};   // never written
+__device__ int32_t g_minus1 = -1;                                                   // never written
 
 // ---------------------------------------------------------------------------------------
 // PSH lookup (paper Section 3.1, Eq.1; super tables Eq.4-6)
@@ -231,14 +238,20 @@ __global__ __launch_bounds__(256) void hash2col_kernel(
     const int grp = threadIdx.x / g, lane = threadIdx.x - grp * g;
     if (grp >= groups) return;
     U *dst = col + r0 * 27 * cu;
-    U zero;
-    __builtin_memset(&zero, 0, sizeof(U));
-    for (int q = grp; q < nv * 27; q += groups) {
-        const int32_t j = idx[q];
+    const U *zsrc = reinterpret_cast<const U *>(g_zero16);
+    // four (voxel, tap) pairs per pass: their loads are independent and issued together
+    const int total = nv * 27;
+    for (int q = grp; q < total; q += 4 * groups) {
+        int32_t j[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) j[t] = q + t * groups < total ? idx[q + t * groups] : -1;
         for (int u = lane; u < cu; u += g) {
-            U val = zero;
-            if (j >= 0) val = X[(int64_t)j * cu + u];
-            dst[(int64_t)q * cu + u] = val;
+            U v[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) v[t] = *(j[t] >= 0 ? X + (int64_t)j[t] * cu + u : zsrc);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (q + t * groups < total) __builtin_nontemporal_store(v[t], &dst[(int64_t)(q + t * groups) * cu + u]);
         }
     }
 }
@@ -271,11 +284,11 @@ __global__ __launch_bounds__(256) void col2hash_kernel(
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
         const int32_t *nb = idx + jl * 27;
+        const float *zsrc = reinterpret_cast<const float *>(g_zero16);
 #pragma unroll 9
         for (int k = 0; k < 27; ++k) {
             const int32_t i = nb[26 - k];
-            if (i < 0) continue;
-            const float *s = dcol + ((int64_t)i * 27 + k) * c + u * VEC;
+            const float *s = i >= 0 ? dcol + ((int64_t)i * 27 + k) * c + u * VEC : zsrc;
             if constexpr (VEC == 4) {
                 const f32x4 v = *reinterpret_cast<const f32x4 *>(s);
 #pragma unroll
@@ -338,12 +351,6 @@ template <> struct InElem<uint16_t> {
                      __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xFFFF0000u)};
     }
 };
-
-// Where a unit of a tile lies outside its matrix the kernels load from these constants instead
-// (16 bytes of zeros, an index of -1): no select has to wait for the load, so a tile's loads
-// stay in flight behind the MFMAs of the previous tile.
-__device__ __attribute__((aligned(16))) uint32_t g_zero16[4] = {0u, 0u, 0u, 0u};   // never written
-__device__ int32_t g_minus1 = -1;                                                   // never written
 
 template <int N> struct FVec;
 template <> struct FVec<1> { typedef float type; };
@@ -741,12 +748,12 @@ __global__ __launch_bounds__(256) void pool_fwd_kernel(
     int32_t arg[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { best[e] = 0.f; arg[e] = -1; }
+    const float *zsrc = reinterpret_cast<const float *>(g_zero16);
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
         const int32_t j = kids[k];
-        if (j < 0) continue;
         float v[VEC];
-        const float *s = X + (int64_t)j * c + u * VEC;
+        const float *s = j >= 0 ? X + (int64_t)j * c + u * VEC : zsrc;
         if constexpr (VEC == 4) {
             const f32x4 t = *reinterpret_cast<const f32x4 *>(s);
             v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
@@ -755,8 +762,11 @@ __global__ __launch_bounds__(256) void pool_fwd_kernel(
             for (int e = 0; e < VEC; ++e) v[e] = s[e];
         }
 #pragma unroll
-        for (int e = 0; e < VEC; ++e)
-            if (arg[e] < 0 || v[e] > best[e]) { best[e] = v[e]; arg[e] = j; }
+        for (int e = 0; e < VEC; ++e) {
+            const bool take = (j >= 0) & ((arg[e] < 0) | (v[e] > best[e]));
+            best[e] = take ? v[e] : best[e];
+            arg[e] = take ? j : arg[e];
+        }
     }
     float *dy = Y + o * c + u * VEC;
     int32_t *da = argmax + o * c + u * VEC;
