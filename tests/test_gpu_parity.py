@@ -345,3 +345,73 @@ def test_conv_bf16(oracle, case_hires, c_in, c_out, algo):
     hch.hch_conv_bwd_weight(case.glv, 0, B16, dev_bf16(X), dev_bf16(G), dW, c_in, c_out, ws(hch.HCH_WS_BWD_WEIGHT), algo)
     assert_close(dW.cpu().numpy(), oracle.from_paper_W(oracle.conv_bwd_weight(L, Xp, Gp), c_in), tol=TOL_BF16,
                  what="bf16 bwd weight")
+
+
+# --------------------------------------------------------------------------------------
+# degenerate and ragged cases
+# --------------------------------------------------------------------------------------
+
+@pytest.fixture(scope="module")
+def case_tiny(oracle):
+    """One-voxel models, a model in a grid corner and on the far faces (neighbours off the
+    grid), a two-voxel model whose voxels touch only diagonally; 5 levels down to 1^3."""
+    pts = [np.array([[7, 7, 7]]),
+           np.array([[0, 0, 0], [1, 1, 1]]),
+           np.array([[15, 15, 15], [15, 14, 15], [14, 15, 15], [15, 15, 14], [0, 15, 0]]),
+           np.array([[3, 3, 3]])]
+    coords = np.concatenate(pts).astype(np.int32)
+    offs = np.cumsum([0] + [len(p) for p in pts])
+    return Case(oracle, coords, offs, 16, 5)
+
+
+@pytest.mark.parametrize("algo", ALGOS, ids=ALGO_IDS)
+def test_tiny_models_all_levels(oracle, case_tiny, algo):
+    case = case_tiny
+    for l, L in enumerate(case.olv):
+        info = case.glv.info(l)
+        assert np.array_equal(info.device_nbr27(), oracle.neighbours(L))
+        if l > 0:
+            assert np.array_equal(info.device_child8(), oracle.children(case.olv[l - 1], L))
+    for level, (c_in, c_out) in ((0, (1, 1)), (0, (4, 8)), (2, (2, 3)), (4, (8, 4))):
+        L = case.olv[level]
+        n = L.Ntot
+        X = S.gaussian((n, c_in), 1.0, 61)
+        W = S.gaussian((27, c_in, c_out), 0.3, 62)
+        G = S.gaussian((n, c_out), 1.0, 63)
+        Xp, Wp, Gp = oracle.to_paper_X(X), oracle.to_paper_W(W), oracle.to_paper_X(G)
+        assert_close(_conv_fwd_gpu(case, level, X, W, algo=algo), oracle.conv_fwd(L, Xp, Wp).T, what="tiny fwd")
+        ws = workspace(hch.hch_conv_workspace_bytes(case.glv, level, c_in, c_out, hch.HCH_F32, hch.HCH_WS_BWD_DATA, algo))
+        dX = torch.full((n, c_in), float("nan"), dtype=torch.float32, device="cuda")
+        hch.hch_conv_bwd_data(case.glv, level, hch.HCH_F32, dev(G), dev(W), dX, c_in, c_out, ws, algo)
+        assert_close(dX.cpu().numpy(), oracle.conv_bwd_data(L, Gp, Wp, c_in).T, what="tiny bwd data")
+        ws = workspace(hch.hch_conv_workspace_bytes(case.glv, level, c_in, c_out, hch.HCH_F32, hch.HCH_WS_BWD_WEIGHT, algo))
+        dW = torch.full((27, c_in, c_out), float("nan"), dtype=torch.float32, device="cuda")
+        hch.hch_conv_bwd_weight(case.glv, level, hch.HCH_F32, dev(X), dev(G), dW, c_in, c_out, ws, algo)
+        assert_close(dW.cpu().numpy(), oracle.from_paper_W(oracle.conv_bwd_weight(L, Xp, Gp), c_in), what="tiny bwd weight")
+    # pooling over every level pair
+    for l in range(4):
+        lf, lc = case.olv[l], case.olv[l + 1]
+        X = S.gaussian((lf.Ntot, 3), 1.0, 64 + l)
+        Y = torch.empty((lc.Ntot, 3), dtype=torch.float32, device="cuda")
+        sw = torch.empty((lc.Ntot, 3), dtype=torch.int32, device="cuda")
+        hch.hch_pool_fwd(case.glv, l, dev(X), Y, sw, 3)
+        Yo, swo = oracle.pool_max_fwd(lf, lc, oracle.to_paper_X(X))
+        assert np.array_equal(sw.cpu().numpy(), swo.T) and np.array_equal(Y.cpu().numpy(), Yo.T.astype(np.float32))
+
+
+def test_pool_nan_and_negative_values(oracle, case_batch64):
+    """Empty children never enter the maximum (all-negative inputs keep a negative maximum) and a
+    NaN does not replace an earlier value."""
+    case = case_batch64
+    lf, lc = case.olv[0], case.olv[1]
+    X = -np.abs(S.gaussian((lf.Ntot, 4), 1.0, 71)) - 0.5
+    X[::97, 1] = np.nan
+    Y = torch.empty((lc.Ntot, 4), dtype=torch.float32, device="cuda")
+    sw = torch.empty((lc.Ntot, 4), dtype=torch.int32, device="cuda")
+    hch.hch_pool_fwd(case.glv, 0, dev(X), Y, sw, 4)
+    Yo, swo = oracle.pool_max_fwd(lf, lc, oracle.to_paper_X(X))
+    assert np.array_equal(sw.cpu().numpy(), swo.T)
+    got, want = Y.cpu().numpy(), Yo.T.astype(np.float32)
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    assert np.array_equal(got[~np.isnan(got)], want[~np.isnan(want)])
+    assert (got[~np.isnan(got)] < 0).all()
