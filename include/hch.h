@@ -234,6 +234,20 @@ hch_status hch_pool_fwd(const hch_levels *levels, int32_t level_in, const float 
 hch_status hch_pool_bwd(const hch_levels *levels, int32_t level_in, const float *dY,
                         const int32_t *argmax, float *dX, int32_t c, void *stream);
 
+/*
+ * The two steps that sit between a convolution and the next level in the paper's networks
+ * (Section 5.1: Convolution -> ReLU -> Pooling), fused into one pass each; results are
+ * identical to calling the separate functions.
+ *   hch_relu_pool_fwd:  A = max(Y, 0) (DEVICE [N_fine][c], written completely), then
+ *                       P, argmax = hch_pool_fwd(A).
+ *   hch_pool_relu_bwd:  dY = hch_relu_bwd(A, hch_pool_bwd(dP, argmax)), written completely.
+ */
+hch_status hch_relu_pool_fwd(const hch_levels *levels, int32_t level_in, const float *Y, float *A,
+                             float *P, int32_t *argmax, int32_t c, void *stream);
+hch_status hch_pool_relu_bwd(const hch_levels *levels, int32_t level_in, const float *dP,
+                             const int32_t *argmax, const float *A, float *dY, int32_t c,
+                             void *stream);
+
 /* Element-wise ReLU over a compact data array of n floats (Section 4, "other CNN
  * operations"): y = max(x, 0);  backward dx = (y > 0) ? dy : 0.  In-place use is allowed. */
 hch_status hch_relu_fwd(const float *x, float *y, int64_t n, void *stream);

@@ -14,8 +14,8 @@ __all__ = [
     "library_path", "load_library", "exported_symbols",
     "hch_build_levels", "hch_build_tables_host", "hch_build_neighbours", "hch_hash2col",
     "hch_col2hash", "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data",
-    "hch_conv_bwd_weight", "hch_pool_fwd", "hch_pool_bwd", "hch_relu_fwd", "hch_relu_bwd",
-    "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
+    "hch_conv_bwd_weight", "hch_pool_fwd", "hch_pool_bwd", "hch_relu_fwd", "hch_relu_bwd", "hch_relu_pool_fwd",
+    "hch_pool_relu_bwd", "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
     "hch_profile_reset",
 ]
 
@@ -31,8 +31,8 @@ exported_symbols = [
     "hch_last_error", "hch_build_levels", "hch_build_tables_host", "hch_free_levels",
     "hch_num_levels", "hch_level_info", "hch_build_neighbours", "hch_hash2col", "hch_col2hash",
     "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data", "hch_conv_bwd_weight",
-    "hch_pool_fwd", "hch_pool_bwd", "hch_relu_fwd", "hch_relu_bwd",
-    "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
+    "hch_pool_fwd", "hch_pool_bwd", "hch_relu_fwd", "hch_relu_bwd", "hch_relu_pool_fwd",
+    "hch_pool_relu_bwd", "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
     "hch_profile_reset",
 ]
 
@@ -93,6 +93,8 @@ def load_library():
         getattr(L, name).argtypes = [vp, i32, C.c_int, vp, vp, vp, i32, i32, vp, sz, C.c_int, vp]
     L.hch_pool_fwd.argtypes = [vp, i32, vp, vp, vp, i32, vp]
     L.hch_pool_bwd.argtypes = [vp, i32, vp, vp, vp, i32, vp]
+    L.hch_relu_pool_fwd.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
+    L.hch_pool_relu_bwd.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
     L.hch_relu_fwd.argtypes = [vp, vp, i64, vp]
     L.hch_relu_bwd.argtypes = [vp, vp, vp, i64, vp]
     L.hch_kernel_count.restype = i32
@@ -335,6 +337,16 @@ def hch_pool_fwd(levels, level_in, X, Y, argmax, c, stream=None):
 def hch_pool_bwd(levels, level_in, dY, argmax, dX, c, stream=None):
     _check(load_library().hch_pool_bwd(levels.handle, level_in, _dp(dY), _dp(argmax), _dp(dX), c,
                                        _stream(stream)))
+
+
+def hch_relu_pool_fwd(levels, level_in, Y, A, P, argmax, c, stream=None):
+    _check(load_library().hch_relu_pool_fwd(levels.handle, level_in, _dp(Y), _dp(A), _dp(P),
+                                            _dp(argmax), c, _stream(stream)))
+
+
+def hch_pool_relu_bwd(levels, level_in, dP, argmax, A, dY, c, stream=None):
+    _check(load_library().hch_pool_relu_bwd(levels.handle, level_in, _dp(dP), _dp(argmax), _dp(A),
+                                            _dp(dY), c, _stream(stream)))
 
 
 def hch_relu_fwd(x, y, n, stream=None):

@@ -905,6 +905,63 @@ extern "C" hch_status hch_pool_bwd(const hch_levels *levels, int32_t level_in, c
     return HCH_OK;
 }
 
+extern "C" hch_status hch_relu_pool_fwd(const hch_levels *levels, int32_t level_in, const float *Y,
+                                        float *A, float *P, int32_t *argmax, int32_t c, void *stream)
+{
+    if (!levels || level_in < 0 || level_in + 1 >= (int32_t)levels->lv.size())
+        return fail(HCH_EINVAL, "hch_relu_pool_fwd: level_in must have a coarser level");
+    if (!Y || !A || !P || !argmax || c <= 0) return fail(HCH_EINVAL, "hch_relu_pool_fwd: bad argument");
+    const Level &Lc = levels->lv[level_in + 1];
+    const Level &Lf = levels->lv[level_in];
+    if (!Lc.dchild) return fail(HCH_EINVAL, "hch_relu_pool_fwd: levels were built without device tables");
+    const bool vec = c % 4 == 0 && aligned16(Y) && aligned16(A) && aligned16(P) && aligned16(argmax);
+    const int64_t items = Lc.n_total * (vec ? c / 4 : c);
+    if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hch_relu_pool_fwd: too large");
+    {
+        // per fine voxel: its row in, its rectified row out; per coarse voxel: 8 indices in,
+        // value and switch rows out
+        const double bytes = (double)Lf.n_total * 8.0 * c + (double)Lc.n_total * (32.0 + 8.0 * c);
+        hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("relu_pool_fwd_kernel<4>") : HCH_KERNEL_ID("relu_pool_fwd_kernel<1>"),
+                            (hipStream_t)stream, bytes, 0.0);
+        if (vec)
+            hipLaunchKernelGGL(hch::relu_pool_fwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                               Y, Lc.dchild, A, P, argmax, Lc.n_total, c);
+        else
+            hipLaunchKernelGGL(hch::relu_pool_fwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                               Y, Lc.dchild, A, P, argmax, Lc.n_total, c);
+    }
+    HCH_LAUNCH_CHECK("relu_pool_fwd_kernel");
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_pool_relu_bwd(const hch_levels *levels, int32_t level_in, const float *dP,
+                                        const int32_t *argmax, const float *A, float *dY, int32_t c,
+                                        void *stream)
+{
+    if (!levels || level_in < 0 || level_in + 1 >= (int32_t)levels->lv.size())
+        return fail(HCH_EINVAL, "hch_pool_relu_bwd: level_in must have a coarser level");
+    if (!dP || !argmax || !A || !dY || c <= 0) return fail(HCH_EINVAL, "hch_pool_relu_bwd: bad argument");
+    const Level &Lc = levels->lv[level_in + 1];
+    const Level &Lf = levels->lv[level_in];
+    if (!Lc.dchild) return fail(HCH_EINVAL, "hch_pool_relu_bwd: levels were built without device tables");
+    const bool vec = c % 4 == 0 && aligned16(dP) && aligned16(argmax) && aligned16(A) && aligned16(dY);
+    const int64_t items = Lc.n_total * 8 * (vec ? c / 4 : c);
+    if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hch_pool_relu_bwd: too large");
+    {
+        const double bytes = (double)Lf.n_total * 8.0 * c + (double)Lc.n_total * (32.0 + 8.0 * c);
+        hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("pool_relu_bwd_kernel<4>") : HCH_KERNEL_ID("pool_relu_bwd_kernel<1>"),
+                            (hipStream_t)stream, bytes, 0.0);
+        if (vec)
+            hipLaunchKernelGGL(hch::pool_relu_bwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                               dP, argmax, Lc.dchild, A, dY, Lc.n_total, c);
+        else
+            hipLaunchKernelGGL(hch::pool_relu_bwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                               dP, argmax, Lc.dchild, A, dY, Lc.n_total, c);
+    }
+    HCH_LAUNCH_CHECK("pool_relu_bwd_kernel");
+    return HCH_OK;
+}
+
 extern "C" hch_status hch_relu_fwd(const float *x, float *y, int64_t n, void *stream)
 {
     if (!x || !y || n < 0) return fail(HCH_EINVAL, "hch_relu_fwd: bad argument");

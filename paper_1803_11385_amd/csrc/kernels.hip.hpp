@@ -808,6 +808,100 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(
     }
 }
 
+// ReLU followed by 2x2x2 max-pooling in one pass: A = max(Y, 0) is written for every child row
+// (each fine voxel is the child of exactly one coarse voxel, so all of A is covered), and the
+// maximum / switch are taken over the rectified values with the rules of pool_fwd_kernel.
+template <int VEC>
+__global__ __launch_bounds__(256) void relu_pool_fwd_kernel(
+    const float *__restrict__ Y, const int32_t *__restrict__ child8, float *__restrict__ A,
+    float *__restrict__ P, int32_t *__restrict__ argmax, int64_t n_coarse, int c)
+{
+    const int cu = c / VEC;
+    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (item >= n_coarse * cu) return;
+    const int64_t o = item / cu;
+    const int u = (int)(item - o * cu);
+    const int32_t *kids = child8 + o * 8;
+    float best[VEC];
+    int32_t arg[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { best[e] = 0.f; arg[e] = -1; }
+    const float *zsrc = reinterpret_cast<const float *>(g_zero16);
+    int32_t j[8];
+    float v[8][VEC];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) j[k] = kids[k];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const float *s = j[k] >= 0 ? Y + (int64_t)j[k] * c + u * VEC : zsrc;
+        if constexpr (VEC == 4) {
+            const f32x4 t = *reinterpret_cast<const f32x4 *>(s);
+            v[k][0] = t[0]; v[k][1] = t[1]; v[k][2] = t[2]; v[k][3] = t[3];
+        } else {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) v[k][e] = s[e];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            v[k][e] = v[k][e] > 0.f ? v[k][e] : 0.f;
+            const bool take = (j[k] >= 0) & ((arg[e] < 0) | (v[k][e] > best[e]));
+            best[e] = take ? v[k][e] : best[e];
+            arg[e] = take ? j[k] : arg[e];
+        }
+        if (j[k] >= 0) {
+            float *d = A + (int64_t)j[k] * c + u * VEC;
+            if constexpr (VEC == 4) *reinterpret_cast<f32x4 *>(d) = f32x4{v[k][0], v[k][1], v[k][2], v[k][3]};
+            else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) d[e] = v[k][e];
+            }
+        }
+    }
+    float *dy = P + o * c + u * VEC;
+    int32_t *da = argmax + o * c + u * VEC;
+    if constexpr (VEC == 4) {
+        *reinterpret_cast<f32x4 *>(dy) = f32x4{best[0], best[1], best[2], best[3]};
+        *reinterpret_cast<int4 *>(da) = make_int4(arg[0], arg[1], arg[2], arg[3]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { dy[e] = best[e]; da[e] = arg[e]; }
+    }
+}
+
+// Max-pool backward followed by ReLU backward in one pass:
+// dY[j][ch] = (argmax[o][ch] == j and A[j][ch] > 0) ? dP[o][ch] : 0 for child j of coarse voxel o.
+template <int VEC>
+__global__ __launch_bounds__(256) void pool_relu_bwd_kernel(
+    const float *__restrict__ dP, const int32_t *__restrict__ argmax, const int32_t *__restrict__ child8,
+    const float *__restrict__ A, float *__restrict__ dY, int64_t n_coarse, int c)
+{
+    const int cu = c / VEC;
+    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (item >= n_coarse * 8 * cu) return;
+    const int64_t ok = item / cu;            // coarse voxel * 8 + child
+    const int u = (int)(item - ok * cu);
+    const int32_t j = child8[ok];
+    if (j < 0) return;
+    const int64_t o = ok >> 3;
+    const float *g = dP + o * c + u * VEC;
+    const int32_t *a = argmax + o * c + u * VEC;
+    const float *act = A + (int64_t)j * c + u * VEC;
+    float *d = dY + (int64_t)j * c + u * VEC;
+    if constexpr (VEC == 4) {
+        const f32x4 gv = *reinterpret_cast<const f32x4 *>(g);
+        const int4 av = *reinterpret_cast<const int4 *>(a);
+        const f32x4 xv = *reinterpret_cast<const f32x4 *>(act);
+        *reinterpret_cast<f32x4 *>(d) = f32x4{((av.x == j) & (xv[0] > 0.f)) ? gv[0] : 0.f, ((av.y == j) & (xv[1] > 0.f)) ? gv[1] : 0.f,
+                                             ((av.z == j) & (xv[2] > 0.f)) ? gv[2] : 0.f, ((av.w == j) & (xv[3] > 0.f)) ? gv[3] : 0.f};
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) d[e] = ((a[e] == j) & (act[e] > 0.f)) ? g[e] : 0.f;
+    }
+}
+
 // element-wise ReLU; n4 = number of float4 units, the remaining n - 4*n4 floats are done one
 // per thread by the first threads (n4 = 0 when the pointers are not 16-byte aligned)
 __global__ __launch_bounds__(256) void relu_fwd_kernel(const float *__restrict__ x,

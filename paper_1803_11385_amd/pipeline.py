@@ -18,8 +18,9 @@ class Encoder:
     """channels = [c0, c1, ..., cL]: level l runs conv c_l -> c_{l+1}, ReLU, pool to level l+1.
     `levels` must hold L+1 levels.  All buffers are allocated once here."""
 
-    def __init__(self, levels, channels, algo=B.HCH_ALGO_COLUMNS, device="cuda"):
+    def __init__(self, levels, channels, algo=B.HCH_ALGO_COLUMNS, device="cuda", fuse_pointwise=True):
         self.levels, self.channels, self.algo = levels, list(channels), algo
+        self.fuse_pointwise = fuse_pointwise       # ReLU+pool (and their backward) as one call each
         self.L = len(channels) - 1
         assert levels.n_levels >= self.L + 1
         self.n = [levels.n(l) for l in range(self.L + 1)]
@@ -54,14 +55,20 @@ class Encoder:
         for l in range(self.L):
             B.hch_conv_fwd(self.levels, l, B.HCH_F32, self.X[l], self.W[l], self.Y[l], ch[l], ch[l + 1], self.ws,
                            self.algo)
-            B.hch_relu_fwd(self.Y[l], self.A[l], self.A[l].numel())
-            B.hch_pool_fwd(self.levels, l, self.A[l], self.X[l + 1], self.sw[l], ch[l + 1])
+            if self.fuse_pointwise:
+                B.hch_relu_pool_fwd(self.levels, l, self.Y[l], self.A[l], self.X[l + 1], self.sw[l], ch[l + 1])
+            else:
+                B.hch_relu_fwd(self.Y[l], self.A[l], self.A[l].numel())
+                B.hch_pool_fwd(self.levels, l, self.A[l], self.X[l + 1], self.sw[l], ch[l + 1])
 
     def backward(self):
         ch = self.channels
         for l in reversed(range(self.L)):
-            B.hch_pool_bwd(self.levels, l, self.dX[l + 1], self.sw[l], self.dA[l], ch[l + 1])
-            B.hch_relu_bwd(self.A[l], self.dA[l], self.dY[l], self.dY[l].numel())
+            if self.fuse_pointwise:
+                B.hch_pool_relu_bwd(self.levels, l, self.dX[l + 1], self.sw[l], self.A[l], self.dY[l], ch[l + 1])
+            else:
+                B.hch_pool_bwd(self.levels, l, self.dX[l + 1], self.sw[l], self.dA[l], ch[l + 1])
+                B.hch_relu_bwd(self.A[l], self.dA[l], self.dY[l], self.dY[l].numel())
             B.hch_conv_bwd_weight(self.levels, l, B.HCH_F32, self.X[l], self.dY[l], self.dW[l], ch[l], ch[l + 1], self.ws,
                                   self.algo)
             B.hch_conv_bwd_data(self.levels, l, B.HCH_F32, self.dY[l], self.W[l], self.dX[l], ch[l], ch[l + 1], self.ws,

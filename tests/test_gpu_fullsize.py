@@ -55,7 +55,9 @@ def test_full_size_tables_and_lists(oracle, full):
 def test_full_size_encoder_step(oracle, full, algo):
     from paper_1803_11385_amd.pipeline import Encoder
     olv, glv, W = full["olv"], full["glv"], full["W"]
-    enc = Encoder(glv, CHANNELS, algo)
+    # the fused algorithm is run with the fused ReLU/pool calls, the columns one with separate calls
+    fused_pw = algo == hch.HCH_ALGO_FUSED
+    enc = Encoder(glv, CHANNELS, algo, fuse_pointwise=fused_pw)
     enc.X[0].copy_(torch.from_numpy(full["X0"]))
     for l in range(5):
         enc.W[l].copy_(torch.from_numpy(W[l]))
@@ -83,7 +85,8 @@ def test_full_size_encoder_step(oracle, full, algo):
         # backward: pool and ReLU exact, the two conv gradients sampled
         dP = enc.dX[l + 1].cpu().numpy()
         dA = oracle.pool_max_bwd(L.Ntot, oracle.to_paper_X(dP), swo).T.astype(np.float32)
-        assert np.array_equal(enc.dA[l].cpu().numpy(), dA), f"pool bwd level {l}"
+        if not fused_pw:
+            assert np.array_equal(enc.dA[l].cpu().numpy(), dA), f"pool bwd level {l}"
         dYl = enc.dY[l].cpu().numpy()
         assert np.array_equal(dYl, np.where(Al > 0, dA, 0).astype(np.float32)), f"relu bwd level {l}"
         dYp = oracle.to_paper_X(dYl)

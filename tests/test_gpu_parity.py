@@ -260,6 +260,29 @@ def test_pool_fwd_bwd(oracle, case_batch64, c):
     assert np.array_equal(dX.cpu().numpy(), want.astype(np.float32))
 
 
+@pytest.mark.parametrize("c", [1, 16, 37])
+def test_fused_relu_pool(oracle, case_batch64, c):
+    """ReLU + pool in one call, and pool backward + ReLU backward in one call, against the oracle's
+    separate steps."""
+    case = case_batch64
+    lf, lc = case.olv[0], case.olv[1]
+    Yin = S.gaussian((lf.Ntot, c), 1.0, 34)
+    A = torch.full((lf.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
+    P = torch.full((lc.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
+    sw = torch.full((lc.Ntot, c), -7, dtype=torch.int32, device="cuda")
+    hch.hch_relu_pool_fwd(case.glv, 0, dev(Yin), A, P, sw, c)
+    Ao = np.maximum(Yin, 0)
+    Po, swo = oracle.pool_max_fwd(lf, lc, oracle.to_paper_X(Ao))
+    assert np.array_equal(A.cpu().numpy(), Ao)
+    assert np.array_equal(sw.cpu().numpy(), swo.T)
+    assert np.array_equal(P.cpu().numpy(), Po.T.astype(np.float32))
+    dP = S.gaussian((lc.Ntot, c), 1.0, 35)
+    dY = torch.full((lf.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_pool_relu_bwd(case.glv, 0, dev(dP), sw, A, dY, c)
+    dA = oracle.pool_max_bwd(lf.Ntot, oracle.to_paper_X(dP), swo).T
+    assert np.array_equal(dY.cpu().numpy(), np.where(Ao > 0, dA, 0).astype(np.float32))
+
+
 def test_relu():
     x = S.gaussian((100003,), 1.0, 41)
     y = torch.empty(x.size, dtype=torch.float32, device="cuda")
