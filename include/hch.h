@@ -235,6 +235,39 @@ hch_status hch_pool_bwd(const hch_levels *levels, int32_t level_in, const float 
                         const int32_t *argmax, float *dX, int32_t c, void *stream);
 
 /*
+ * Transposed convolution (Section 4: "flips the input and output of the forward convolution
+ * using a transposed kernel", i.e. Eq.8 followed by col2hash) and its two gradients.
+ *   W DEVICE [27][c_out][c_in] are the weights of the FORWARD convolution c_out -> c_in that is
+ *   being transposed;  X DEVICE [N_l][c_in];  Y DEVICE [N_l][c_out] float, overwritten.
+ *   hch_deconv_fwd        Y  = col2hash(X . W^T)
+ *   hch_deconv_bwd_data   dX = hash2col(dY) . W               (dX [N_l][c_in])
+ *   hch_deconv_bwd_weight dW = hash2col(dY)^T . X             (dW [27][c_out][c_in])
+ * Workspace: hch_conv_workspace_bytes with the channel counts exchanged (c_out, c_in) and the
+ * kinds HCH_WS_BWD_DATA, HCH_WS_FWD, HCH_WS_BWD_WEIGHT respectively.
+ */
+hch_status hch_deconv_fwd(const hch_levels *levels, int32_t level, hch_dtype dtype, const void *X,
+                          const void *W, float *Y, int32_t c_in, int32_t c_out, void *workspace,
+                          size_t ws_bytes, hch_algo algo, void *stream);
+hch_status hch_deconv_bwd_data(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                               const void *dY, const void *W, float *dX, int32_t c_in, int32_t c_out,
+                               void *workspace, size_t ws_bytes, hch_algo algo, void *stream);
+hch_status hch_deconv_bwd_weight(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                                 const void *X, const void *dY, float *dW, int32_t c_in,
+                                 int32_t c_out, void *workspace, size_t ws_bytes, hch_algo algo,
+                                 void *stream);
+
+/*
+ * Max-unpooling from level_out + 1 (coarse) to level_out (fine) (Section 4): the receptive field
+ * of every coarse voxel is zero except at its recorded switch, which receives the coarse value.
+ *   Xc DEVICE [N_coarse][c];  argmax as written by hch_pool_fwd;  Y DEVICE [N_fine][c], overwritten.
+ * Backward: dXc[o][ch] = dY[argmax[o][ch]][ch].
+ */
+hch_status hch_unpool_fwd(const hch_levels *levels, int32_t level_out, const float *Xc,
+                          const int32_t *argmax, float *Y, int32_t c, void *stream);
+hch_status hch_unpool_bwd(const hch_levels *levels, int32_t level_out, const float *dY,
+                          const int32_t *argmax, float *dXc, int32_t c, void *stream);
+
+/*
  * The two steps that sit between a convolution and the next level in the paper's networks
  * (Section 5.1: Convolution -> ReLU -> Pooling), fused into one pass each; results are
  * identical to calling the separate functions.

@@ -581,6 +581,38 @@ void orc_pool_max_bwd(int c, int64_t Ni, int64_t No, const double *dDout, const 
         }
 }
 
+/* ------------------------------------------------------------------------- */
+/* Transposed convolution and max-unpooling (Section 4, last paragraphs)       */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * Transposed convolution: D~_o = W^T * D_i, then col2hash -- "exactly how the error
+ * back-propagation is handled".  W: c_i x (c_o * F^3) is the weight matrix of the forward
+ * convolution c_o -> c_i that is being transposed; Din: c_i x N; Dout: c_o x N.
+ * Dt is scratch of (c_o*F^3) x N doubles.
+ */
+void orc_deconv_fwd(const orc_level *L, int c_i, int c_o, const double *Din, const double *W,
+                    int F, double *Dt, double *Dout)
+{
+    int64_t N = L->N[L->b];
+    orc_matmul(W, Din, Dt, (int64_t)c_o * F * F * F, c_i, N, 1, 0);
+    orc_col2hash(L, L, c_o, Dt, F, 1, 0, Dout);
+}
+
+/* Max-unpooling: the receptive field of every coarse voxel is zero except at the recorded
+ * switch, which receives the coarse value.  (Same routing as orc_pool_max_bwd.)
+ * Its backward reads the fine gradient back at the switches. */
+void orc_unpool_max_bwd(int c, int64_t Nf, int64_t Nc, const double *dDfine, const int32_t *sw,
+                        double *dDcoarse)
+{
+    int ic; int64_t j;
+    for (ic = 0; ic < c; ic++)
+        for (j = 0; j < Nc; j++) {
+            int32_t a = sw[(int64_t)ic * Nc + j];
+            dDcoarse[(int64_t)ic * Nc + j] = a >= 0 ? dDfine[(int64_t)ic * Nf + a] : 0.0;
+        }
+}
+
 /* number of OpenMP threads the parallel loops above will use */
 #ifdef _OPENMP
 #include <omp.h>

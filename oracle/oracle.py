@@ -346,3 +346,32 @@ def pool_max_bwd(Ni, dDout, sw):
     dD = np.empty((c, Ni), np.float64)
     lib().orc_pool_max_bwd(C.c_int(c), C.c_int64(Ni), C.c_int64(No), _p(dDout), _p(sw), _p(dD))
     return dD
+
+
+def deconv_fwd(L, Din, Wp):
+    """Transposed convolution (Section 4): col2hash(W^T * D_i).  Din c_i x N; Wp c_i x (c_o*27) is
+    the weight matrix of the forward convolution c_o -> c_i being transposed; returns c_o x N."""
+    Din = np.ascontiguousarray(Din, np.float64)
+    Wp = np.ascontiguousarray(Wp, np.float64)
+    c_i = Din.shape[0]
+    assert Wp.shape[0] == c_i and Wp.shape[1] % 27 == 0
+    c_o = Wp.shape[1] // 27
+    Dt = np.empty((c_o * 27, L.Ntot), np.float64)
+    Dout = np.empty((c_o, L.Ntot), np.float64)
+    lib().orc_deconv_fwd(L.ref, C.c_int(c_i), C.c_int(c_o), _p(Din), _p(Wp), C.c_int(3), _p(Dt), _p(Dout))
+    return Dout
+
+
+def unpool_max_fwd(Nfine, Dcoarse, sw):
+    """Max-unpooling (Section 4): zero everywhere except at the recorded switches."""
+    return pool_max_bwd(Nfine, Dcoarse, sw)
+
+
+def unpool_max_bwd(dDfine, sw):
+    dDfine = np.ascontiguousarray(dDfine, np.float64)
+    sw = np.ascontiguousarray(sw, np.int32)
+    c, Nf = dDfine.shape
+    Nc = sw.shape[1]
+    out = np.empty((c, Nc), np.float64)
+    lib().orc_unpool_max_bwd(C.c_int(c), C.c_int64(Nf), C.c_int64(Nc), _p(dDfine), _p(sw), _p(out))
+    return out

@@ -15,7 +15,8 @@ __all__ = [
     "hch_build_levels", "hch_build_tables_host", "hch_build_neighbours", "hch_hash2col",
     "hch_col2hash", "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data",
     "hch_conv_bwd_weight", "hch_pool_fwd", "hch_pool_bwd", "hch_relu_fwd", "hch_relu_bwd", "hch_relu_pool_fwd",
-    "hch_pool_relu_bwd", "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
+    "hch_pool_relu_bwd", "hch_deconv_fwd", "hch_deconv_bwd_data", "hch_deconv_bwd_weight",
+    "hch_unpool_fwd", "hch_unpool_bwd", "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
     "hch_profile_reset",
 ]
 
@@ -32,7 +33,8 @@ exported_symbols = [
     "hch_num_levels", "hch_level_info", "hch_build_neighbours", "hch_hash2col", "hch_col2hash",
     "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data", "hch_conv_bwd_weight",
     "hch_pool_fwd", "hch_pool_bwd", "hch_relu_fwd", "hch_relu_bwd", "hch_relu_pool_fwd",
-    "hch_pool_relu_bwd", "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
+    "hch_pool_relu_bwd", "hch_deconv_fwd", "hch_deconv_bwd_data", "hch_deconv_bwd_weight",
+    "hch_unpool_fwd", "hch_unpool_bwd", "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
     "hch_profile_reset",
 ]
 
@@ -89,7 +91,10 @@ def load_library():
     L.hch_col2hash.argtypes = [vp, i32, vp, i32, vp, vp]
     L.hch_conv_workspace_bytes.argtypes = [vp, i32, i32, i32, C.c_int, C.c_int, C.c_int]
     L.hch_conv_workspace_bytes.restype = sz
-    for name in ("hch_conv_fwd", "hch_conv_bwd_data", "hch_conv_bwd_weight"):
+    L.hch_unpool_fwd.argtypes = [vp, i32, vp, vp, vp, i32, vp]
+    L.hch_unpool_bwd.argtypes = [vp, i32, vp, vp, vp, i32, vp]
+    for name in ("hch_conv_fwd", "hch_conv_bwd_data", "hch_conv_bwd_weight",
+                 "hch_deconv_fwd", "hch_deconv_bwd_data", "hch_deconv_bwd_weight"):
         getattr(L, name).argtypes = [vp, i32, C.c_int, vp, vp, vp, i32, i32, vp, sz, C.c_int, vp]
     L.hch_pool_fwd.argtypes = [vp, i32, vp, vp, vp, i32, vp]
     L.hch_pool_bwd.argtypes = [vp, i32, vp, vp, vp, i32, vp]
@@ -327,6 +332,37 @@ def hch_conv_bwd_weight(levels, level, dtype, X, dY, dW, c_in, c_out, workspace,
                                               _dp(dW), c_in, c_out, _dp(workspace),
                                               workspace.numel() * workspace.element_size(), algo,
                                               _stream(stream)))
+
+
+def _conv_like(name, levels, level, dtype, a, b, out, c_in, c_out, workspace, algo, stream):
+    _check(getattr(load_library(), name)(levels.handle, level, dtype, _dp(a), _dp(b), _dp(out), c_in,
+                                         c_out, _dp(workspace),
+                                         workspace.numel() * workspace.element_size(), algo,
+                                         _stream(stream)))
+
+
+def hch_deconv_fwd(levels, level, dtype, X, W, Y, c_in, c_out, workspace, algo=HCH_ALGO_COLUMNS, stream=None):
+    _conv_like("hch_deconv_fwd", levels, level, dtype, X, W, Y, c_in, c_out, workspace, algo, stream)
+
+
+def hch_deconv_bwd_data(levels, level, dtype, dY, W, dX, c_in, c_out, workspace, algo=HCH_ALGO_COLUMNS,
+                        stream=None):
+    _conv_like("hch_deconv_bwd_data", levels, level, dtype, dY, W, dX, c_in, c_out, workspace, algo, stream)
+
+
+def hch_deconv_bwd_weight(levels, level, dtype, X, dY, dW, c_in, c_out, workspace, algo=HCH_ALGO_COLUMNS,
+                          stream=None):
+    _conv_like("hch_deconv_bwd_weight", levels, level, dtype, X, dY, dW, c_in, c_out, workspace, algo, stream)
+
+
+def hch_unpool_fwd(levels, level_out, Xc, argmax, Y, c, stream=None):
+    _check(load_library().hch_unpool_fwd(levels.handle, level_out, _dp(Xc), _dp(argmax), _dp(Y), c,
+                                         _stream(stream)))
+
+
+def hch_unpool_bwd(levels, level_out, dY, argmax, dXc, c, stream=None):
+    _check(load_library().hch_unpool_bwd(levels.handle, level_out, _dp(dY), _dp(argmax), _dp(dXc), c,
+                                         _stream(stream)))
 
 
 def hch_pool_fwd(levels, level_in, X, Y, argmax, c, stream=None):

@@ -905,6 +905,65 @@ extern "C" hch_status hch_pool_bwd(const hch_levels *levels, int32_t level_in, c
     return HCH_OK;
 }
 
+// ---------------------------------------------------------------------------------------
+// transposed convolution and max-unpooling (paper Section 4, last paragraphs): the same
+// products with the roles of input and output exchanged
+// ---------------------------------------------------------------------------------------
+
+extern "C" hch_status hch_deconv_fwd(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                                     const void *X, const void *W, float *Y, int32_t c_in,
+                                     int32_t c_out, void *workspace, size_t ws_bytes, hch_algo algo,
+                                     void *stream)
+{
+    // Y = col2hash(X . W^T): the data-gradient path of the convolution c_out -> c_in
+    return hch_conv_bwd_data(levels, level, dtype, X, W, Y, c_out, c_in, workspace, ws_bytes, algo, stream);
+}
+
+extern "C" hch_status hch_deconv_bwd_data(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                                          const void *dY, const void *W, float *dX, int32_t c_in,
+                                          int32_t c_out, void *workspace, size_t ws_bytes,
+                                          hch_algo algo, void *stream)
+{
+    // the adjoint of the above is the forward convolution c_out -> c_in
+    return hch_conv_fwd(levels, level, dtype, dY, W, dX, c_out, c_in, workspace, ws_bytes, algo, stream);
+}
+
+extern "C" hch_status hch_deconv_bwd_weight(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                                            const void *X, const void *dY, float *dW, int32_t c_in,
+                                            int32_t c_out, void *workspace, size_t ws_bytes,
+                                            hch_algo algo, void *stream)
+{
+    // dW[27][c_out][c_in] = hash2col(dY)^T . X: the weight gradient of the convolution c_out -> c_in
+    // whose input is dY and whose output gradient is X
+    return hch_conv_bwd_weight(levels, level, dtype, dY, X, dW, c_out, c_in, workspace, ws_bytes, algo, stream);
+}
+
+extern "C" hch_status hch_unpool_fwd(const hch_levels *levels, int32_t level_out, const float *Xc,
+                                     const int32_t *argmax, float *Y, int32_t c, void *stream)
+{
+    return hch_pool_bwd(levels, level_out, Xc, argmax, Y, c, stream);
+}
+
+extern "C" hch_status hch_unpool_bwd(const hch_levels *levels, int32_t level_out, const float *dY,
+                                     const int32_t *argmax, float *dXc, int32_t c, void *stream)
+{
+    if (!levels || level_out < 0 || level_out + 1 >= (int32_t)levels->lv.size())
+        return fail(HCH_EINVAL, "hch_unpool_bwd: level_out must have a coarser level");
+    if (!dY || !argmax || !dXc || c <= 0) return fail(HCH_EINVAL, "hch_unpool_bwd: bad argument");
+    const Level &Lc = levels->lv[level_out + 1];
+    if (!Lc.dchild) return fail(HCH_EINVAL, "hch_unpool_bwd: levels were built without device tables");
+    const int64_t items = Lc.n_total * c;
+    if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hch_unpool_bwd: too large");
+    if (items == 0) return HCH_OK;
+    {
+        hch::LaunchTimer lt(HCH_KERNEL_ID("unpool_bwd_kernel"), (hipStream_t)stream, 12.0 * items, 0.0);
+        hipLaunchKernelGGL(hch::unpool_bwd_kernel, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                           dY, argmax, dXc, Lc.n_total, c);
+    }
+    HCH_LAUNCH_CHECK("unpool_bwd_kernel");
+    return HCH_OK;
+}
+
 extern "C" hch_status hch_relu_pool_fwd(const hch_levels *levels, int32_t level_in, const float *Y,
                                         float *A, float *P, int32_t *argmax, int32_t c, void *stream)
 {

@@ -902,6 +902,19 @@ __global__ __launch_bounds__(256) void pool_relu_bwd_kernel(
     }
 }
 
+// backward of max-unpooling: the coarse gradient reads the fine gradient back at its switch,
+// dXc[o][ch] = dY[argmax[o][ch]][ch]
+__global__ __launch_bounds__(256) void unpool_bwd_kernel(
+    const float *__restrict__ dY, const int32_t *__restrict__ argmax, float *__restrict__ dXc,
+    int64_t n_coarse, int c)
+{
+    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (item >= n_coarse * c) return;
+    const int ch = (int)(item % c);
+    const int32_t j = argmax[item];
+    dXc[item] = j >= 0 ? dY[(int64_t)j * c + ch] : 0.f;
+}
+
 // element-wise ReLU; n4 = number of float4 units, the remaining n - 4*n4 floats are done one
 // per thread by the first threads (n4 = 0 when the pointers are not 16-byte aligned)
 __global__ __launch_bounds__(256) void relu_fwd_kernel(const float *__restrict__ x,

@@ -438,3 +438,51 @@ def test_pool_nan_and_negative_values(oracle, case_batch64):
     assert np.array_equal(np.isnan(got), np.isnan(want))
     assert np.array_equal(got[~np.isnan(got)], want[~np.isnan(want)])
     assert (got[~np.isnan(got)] < 0).all()
+
+
+# --------------------------------------------------------------------------------------
+# transposed convolution and max-unpooling
+# --------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("algo", ALGOS, ids=ALGO_IDS)
+@pytest.mark.parametrize("c_in,c_out", [(32, 16), (5, 3)])
+def test_deconv(oracle, case_small, c_in, c_out, algo):
+    case = case_small
+    L = case.olv[1]
+    n = L.Ntot
+    X = S.gaussian((n, c_in), 1.0, 81)
+    W = S.gaussian((27, c_out, c_in), 0.1, 82)         # forward conv c_out -> c_in, transposed here
+    G = S.gaussian((n, c_out), 1.0, 83)
+    Xp, Wp, Gp = oracle.to_paper_X(X), oracle.to_paper_W(W), oracle.to_paper_X(G)
+    F32 = hch.HCH_F32
+
+    def ws(kind):
+        return workspace(hch.hch_conv_workspace_bytes(case.glv, 1, c_out, c_in, F32, kind, algo))
+
+    Y = torch.full((n, c_out), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_deconv_fwd(case.glv, 1, F32, dev(X), dev(W), Y, c_in, c_out, ws(hch.HCH_WS_BWD_DATA), algo)
+    assert_close(Y.cpu().numpy(), oracle.deconv_fwd(L, Xp, Wp).T, what="deconv fwd")
+    dX = torch.full((n, c_in), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_deconv_bwd_data(case.glv, 1, F32, dev(G), dev(W), dX, c_in, c_out, ws(hch.HCH_WS_FWD), algo)
+    assert_close(dX.cpu().numpy(), oracle.conv_fwd(L, Gp, Wp).T, what="deconv bwd data")
+    dW = torch.full((27, c_out, c_in), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_deconv_bwd_weight(case.glv, 1, F32, dev(X), dev(G), dW, c_in, c_out, ws(hch.HCH_WS_BWD_WEIGHT), algo)
+    assert_close(dW.cpu().numpy(), oracle.from_paper_W(oracle.conv_bwd_weight(L, Gp, Xp), c_out), what="deconv bwd weight")
+
+
+def test_unpool(oracle, case_batch64):
+    case = case_batch64
+    lf, lc = case.olv[0], case.olv[1]
+    c = 6
+    X = S.gaussian((lf.Ntot, c), 1.0, 84)
+    P = torch.empty((lc.Ntot, c), dtype=torch.float32, device="cuda")
+    sw = torch.empty((lc.Ntot, c), dtype=torch.int32, device="cuda")
+    hch.hch_pool_fwd(case.glv, 0, dev(X), P, sw, c)
+    U = torch.full((lf.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_unpool_fwd(case.glv, 0, P, sw, U, c)
+    Po, swo = oracle.pool_max_fwd(lf, lc, oracle.to_paper_X(X))
+    assert np.array_equal(U.cpu().numpy(), oracle.unpool_max_fwd(lf.Ntot, Po, swo).T.astype(np.float32))
+    G = S.gaussian((lf.Ntot, c), 1.0, 85)
+    dP = torch.full((lc.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_unpool_bwd(case.glv, 0, dev(G), sw, dP, c)
+    assert np.array_equal(dP.cpu().numpy(), oracle.unpool_max_bwd(oracle.to_paper_X(G), swo).T.astype(np.float32))

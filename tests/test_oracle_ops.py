@@ -253,3 +253,49 @@ def test_strided_traversal_general_form(oracle):
                                2 * cc[:, 2] - 1 + fz + 1]
                     assert np.array_equal(fi[lc.N[v]:lc.N[v + 1], row], want)
                     row += 1
+
+
+def test_deconv_vs_dense_conv_transpose(oracle, small_batch):
+    """Transposed convolution against torch's dense float64 conv_transpose3d read back at the
+    occupied voxels, and as the adjoint of the forward convolution."""
+    coords, offs, normals, L = small_batch
+    rng = np.random.default_rng(11)
+    c_i, c_o, u = 4, 3, 32
+    X = rng.standard_normal((L.Ntot, c_i))
+    W = rng.standard_normal((27, c_o, c_i)) * 0.1        # forward conv c_o -> c_i
+    wt = torch.from_numpy(W.reshape(3, 3, 3, c_o, c_i).transpose(4, 3, 0, 1, 2).copy())   # [c_i, c_o, 3,3,3]
+    want = np.empty((L.Ntot, c_o))
+    for v in range(L.b):
+        c = coords[offs[v]:offs[v + 1]]
+        vol = torch.from_numpy(dense_scatter(c, X[offs[v]:offs[v + 1]], u))
+        # conv_transpose3d's weight is [in, out, k...] and it is the adjoint of conv3d with the
+        # same tensor read as [out_fwd = in, in_fwd = out]
+        y = torch.nn.functional.conv_transpose3d(vol[None], wt, padding=1)[0].numpy()
+        want[offs[v]:offs[v + 1]] = y[:, c[:, 0], c[:, 1], c[:, 2]].T
+    Wp = oracle.to_paper_W(W)                              # c_i x (c_o*27)
+    got = oracle.deconv_fwd(L, oracle.to_paper_X(X), Wp).T
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-11)
+    # adjoint of the forward convolution with the same weights
+    Z = rng.standard_normal((c_o, L.Ntot))
+    lhs = (oracle.conv_fwd(L, Z, Wp) * oracle.to_paper_X(X)).sum()
+    rhs = (Z * oracle.deconv_fwd(L, oracle.to_paper_X(X), Wp)).sum()
+    assert abs(lhs - rhs) < 1e-9 * abs(lhs)
+
+
+def test_unpool_restores_only_switches(oracle):
+    coords, offs, _ = S.config_batch(2, batch=2)
+    lf, lc = oracle.build_hierarchy(coords, offs, 64, 2)
+    rng = np.random.default_rng(12)
+    c = 3
+    X = rng.standard_normal((c, lf.Ntot))
+    P, sw = oracle.pool_max_fwd(lf, lc, X)
+    U = oracle.unpool_max_fwd(lf.Ntot, P, sw)
+    # unpool(pool(X)) keeps exactly the maxima: equal to X at the switches, zero elsewhere
+    mask = np.zeros_like(X, bool)
+    for ic in range(c):
+        mask[ic, sw[ic]] = True
+    assert np.array_equal(U[mask], X[mask]) and (U[~mask] == 0).all()
+    # backward of unpooling is the adjoint gather
+    G = rng.standard_normal((c, lf.Ntot))
+    dP = oracle.unpool_max_bwd(G, sw)
+    assert abs((U * G).sum() - (P * dP).sum()) < 1e-9
