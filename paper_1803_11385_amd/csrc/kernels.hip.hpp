@@ -391,8 +391,11 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     static_assert(A_TOTAL % 256 == 0 && 256 % A_UPR == 0, "A tile must split evenly over the threads");
     typedef typename FVec<NT>::type bvec_t;
 
-    __shared__ __attribute__((aligned(16))) float As[A_K_FAST ? BM * AS : BK * AS];
-    __shared__ __attribute__((aligned(16))) float Bs[BK * BS];
+    // two LDS stages: while the MFMAs read one, the next tile is written into the other
+    constexpr int A_LDS = A_K_FAST ? BM * AS : BK * AS;
+    constexpr int B_LDS = BK * BS;
+    __shared__ __attribute__((aligned(16))) float As2[2 * A_LDS];
+    __shared__ __attribute__((aligned(16))) float Bs2[2 * B_LDS];
 
     // gridDim.x == m_tiles: plain order; gridDim.x > m_tiles (a multiple of 8): XCD-contiguous
     const unsigned mtile = gridDim.x == m_tiles ? blockIdx.x : xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
@@ -562,7 +565,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     };
 
     // registers -> LDS
-    auto stash = [&](const f32x4 *ra, const f32x4 *rb) {
+    auto stash = [&](int stage, const f32x4 *ra, const f32x4 *rb) {
+        float *As = As2 + stage * A_LDS, *Bs = Bs2 + stage * B_LDS;
 #pragma unroll
         for (int uu = 0; uu < A_UNITS; ++uu)
             *reinterpret_cast<f32x4 *>(&As[(a_row0 + uu * A_RSTEP) * AS + a_col]) = ra[uu];
@@ -587,7 +591,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     typedef typename FVec<A_K_FAST ? 4 : MT>::type areg_t;
     areg_t oa[A_REGS];
     bvec_t ob[B_REGS];
-    auto load_operands = [&]() {
+    auto load_operands = [&](int stage) {
+        const float *As = As2 + stage * A_LDS, *Bs = Bs2 + stage * B_LDS;
         if constexpr (A_K_FAST) {
 #pragma unroll
             for (int slab = 0; slab < BK / 16; ++slab) {
@@ -630,32 +635,41 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
         }
     };
 
-    // Software pipeline over the tiles of this workgroup's reduction range:
-    //   iteration t:  LDS <- registers(t);  issue index loads of t+2, row loads of t+1;
-    //                 LDS -> operand registers;  MFMAs of t.
-    // The two index register sets alternate (no copies, so nothing waits on the index loads
-    // before the row loads of the following iteration need them).
+    // Software pipeline over the tiles t = 0, 1, ... of this workgroup's reduction range, one
+    // barrier per tile:
+    //   iteration t:  operands of t: LDS stage t%2 -> registers;  MFMAs of t;
+    //                 registers(t+1) -> LDS stage (t+1)%2;  issue index loads of t+3, row loads of t+2;
+    //                 barrier.
+    // The two index register sets alternate (no copies, so nothing waits on an index load before
+    // the row loads that need it).
     f32x4 ra[A_UNITS], rb[B_UNITS];
     int32_t rx[A_UNITS] = {}, ry[A_UNITS] = {};
-    auto iteration = [&](int k0, int32_t *use, int32_t *load) {
-        stash(ra, rb);
-        __syncthreads();
-        if (k0 + BK < kend) {
-            fetch_idx(load);
-            fetch(k0 + BK, use, ra, rb);
-        }
-        load_operands();
-        __syncthreads();
+    auto iteration = [&](int k0, int stage, int32_t *use, int32_t *load) {
+        load_operands(stage);
         multiply();
+        if (k0 + BK < kend) {
+            stash(stage ^ 1, ra, rb);
+            if (k0 + 2 * BK < kend) {
+                fetch_idx(load);
+                fetch(k0 + 2 * BK, use, ra, rb);
+            }
+        }
+        __syncthreads();
     };
     if (kbeg < kend) {
         fetch_idx(ry);
         fetch(kbeg, ry, ra, rb);
         fetch_idx(rx);
+        stash(0, ra, rb);
+        if (kbeg + BK < kend) {
+            fetch_idx(ry);
+            fetch(kbeg + BK, rx, ra, rb);
+        }
+        __syncthreads();
     }
     for (int k0 = kbeg; k0 < kend; k0 += 2 * BK) {
-        iteration(k0, rx, ry);
-        if (k0 + BK < kend) iteration(k0 + BK, ry, rx);
+        iteration(k0, 0, ry, rx);
+        if (k0 + BK < kend) iteration(k0 + BK, 1, rx, ry);
     }
 
     // D layout of v_mfma_f32_16x16x4_f32: register e of lane l holds D[4*(l/16) + e][l%16].
