@@ -87,6 +87,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-all", action="store_true", help="time every kernel (adds event overhead)")
     ap.add_argument("--no-other-algo", action="store_true", help="skip the second, fully timed pass")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="before the warm-up, run the library's ReLU kernel three times over 2^24 floats (reads "
+                         "64 MiB, writes 64 MiB): the known-size copy that scales the FETCH_SIZE / WRITE_SIZE "
+                         "counters of a rocprofv3 --pmc run")
     ap.add_argument("--algo", choices=["columns", "fused"], default="fused",
                     help="columns: hash2col -> GEMM -> col2hash through memory; fused: gathered GEMM operand")
     args = ap.parse_args()
@@ -160,6 +164,14 @@ def main():
 
     def traffic_of(name):
         return traffic_db.get(args.algo, {}).get(name)
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 24, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            hch.hch_relu_fwd(src, dst, src.numel())
+        torch.cuda.synchronize()
+        del src, dst
 
     # warm-up; the first warm-up step times every kernel to find the dominant one
     hch.hch_profile_reset()

@@ -272,8 +272,10 @@ hch_status hch_unpool_bwd(const hch_levels *levels, int32_t level_out, const flo
  * (Section 5.1: Convolution -> ReLU -> Pooling), fused into one pass each; results are
  * identical to calling the separate functions.
  *   hch_relu_pool_fwd:  A = max(Y, 0) (DEVICE [N_fine][c], written completely), then
- *                       P, argmax = hch_pool_fwd(A).
+ *                       P, argmax = hch_pool_fwd(A).  A may be NULL: the rectified rows are
+ *                       then not stored (a training step needs only their sign, which Y has).
  *   hch_pool_relu_bwd:  dY = hch_relu_bwd(A, hch_pool_bwd(dP, argmax)), written completely.
+ *                       Only the sign of A is read, so Y may be passed in its place.
  */
 hch_status hch_relu_pool_fwd(const hch_levels *levels, int32_t level_in, const float *Y, float *A,
                              float *P, int32_t *argmax, int32_t c, void *stream);

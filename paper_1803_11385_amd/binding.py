@@ -260,7 +260,7 @@ def _stream(stream):
 
 
 def _dp(t):
-    return C.c_void_p(t.data_ptr())
+    return C.c_void_p(t.data_ptr() if t is not None else None)
 
 
 def _host_inputs(coords, model_offsets):

@@ -969,17 +969,17 @@ extern "C" hch_status hch_relu_pool_fwd(const hch_levels *levels, int32_t level_
 {
     if (!levels || level_in < 0 || level_in + 1 >= (int32_t)levels->lv.size())
         return fail(HCH_EINVAL, "hch_relu_pool_fwd: level_in must have a coarser level");
-    if (!Y || !A || !P || !argmax || c <= 0) return fail(HCH_EINVAL, "hch_relu_pool_fwd: bad argument");
+    if (!Y || !P || !argmax || c <= 0) return fail(HCH_EINVAL, "hch_relu_pool_fwd: bad argument");
     const Level &Lc = levels->lv[level_in + 1];
     const Level &Lf = levels->lv[level_in];
     if (!Lc.dchild) return fail(HCH_EINVAL, "hch_relu_pool_fwd: levels were built without device tables");
-    const bool vec = c % 4 == 0 && aligned16(Y) && aligned16(A) && aligned16(P) && aligned16(argmax);
+    const bool vec = c % 4 == 0 && aligned16(Y) && (!A || aligned16(A)) && aligned16(P) && aligned16(argmax);
     const int64_t items = Lc.n_total * (vec ? c / 4 : c);
     if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hch_relu_pool_fwd: too large");
     {
-        // per fine voxel: its row in, its rectified row out; per coarse voxel: 8 indices in,
-        // value and switch rows out
-        const double bytes = (double)Lf.n_total * 8.0 * c + (double)Lc.n_total * (32.0 + 8.0 * c);
+        // per fine voxel: its row in (and its rectified row out when A is given); per coarse
+        // voxel: 8 indices in, value and switch rows out
+        const double bytes = (double)Lf.n_total * (A ? 8.0 : 4.0) * c + (double)Lc.n_total * (32.0 + 8.0 * c);
         hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("relu_pool_fwd_kernel<4>") : HCH_KERNEL_ID("relu_pool_fwd_kernel<1>"),
                             (hipStream_t)stream, bytes, 0.0);
         if (vec)
@@ -1004,7 +1004,7 @@ extern "C" hch_status hch_pool_relu_bwd(const hch_levels *levels, int32_t level_
     const Level &Lf = levels->lv[level_in];
     if (!Lc.dchild) return fail(HCH_EINVAL, "hch_pool_relu_bwd: levels were built without device tables");
     const bool vec = c % 4 == 0 && aligned16(dP) && aligned16(argmax) && aligned16(A) && aligned16(dY);
-    const int64_t items = Lc.n_total * 8 * (vec ? c / 4 : c);
+    const int64_t items = Lc.n_total * (vec ? c / 4 : c);
     if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hch_pool_relu_bwd: too large");
     {
         const double bytes = (double)Lf.n_total * 8.0 * c + (double)Lc.n_total * (32.0 + 8.0 * c);

@@ -823,8 +823,9 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(
 }
 
 // ReLU followed by 2x2x2 max-pooling in one pass: A = max(Y, 0) is written for every child row
-// (each fine voxel is the child of exactly one coarse voxel, so all of A is covered), and the
-// maximum / switch are taken over the rectified values with the rules of pool_fwd_kernel.
+// (each fine voxel is the child of exactly one coarse voxel, so all of A is covered) unless A is
+// null, and the maximum / switch are taken over the rectified values with the rules of
+// pool_fwd_kernel.
 template <int VEC>
 __global__ __launch_bounds__(256) void relu_pool_fwd_kernel(
     const float *__restrict__ Y, const int32_t *__restrict__ child8, float *__restrict__ A,
@@ -865,7 +866,7 @@ __global__ __launch_bounds__(256) void relu_pool_fwd_kernel(
             best[e] = take ? v[k][e] : best[e];
             arg[e] = take ? j[k] : arg[e];
         }
-        if (j[k] >= 0) {
+        if (A != nullptr && j[k] >= 0) {
             float *d = A + (int64_t)j[k] * c + u * VEC;
             if constexpr (VEC == 4) *reinterpret_cast<f32x4 *>(d) = f32x4{v[k][0], v[k][1], v[k][2], v[k][3]};
             else {
@@ -887,32 +888,58 @@ __global__ __launch_bounds__(256) void relu_pool_fwd_kernel(
 
 // Max-pool backward followed by ReLU backward in one pass:
 // dY[j][ch] = (argmax[o][ch] == j and A[j][ch] > 0) ? dP[o][ch] : 0 for child j of coarse voxel o.
+// Only the sign of A is used, so the values before the ReLU serve as well.
 template <int VEC>
 __global__ __launch_bounds__(256) void pool_relu_bwd_kernel(
     const float *__restrict__ dP, const int32_t *__restrict__ argmax, const int32_t *__restrict__ child8,
     const float *__restrict__ A, float *__restrict__ dY, int64_t n_coarse, int c)
 {
+    // one thread per (coarse voxel, channel unit): the coarse gradient and switches are read once
+    // and dealt to the up to 8 child rows
     const int cu = c / VEC;
     const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (item >= n_coarse * 8 * cu) return;
-    const int64_t ok = item / cu;            // coarse voxel * 8 + child
-    const int u = (int)(item - ok * cu);
-    const int32_t j = child8[ok];
-    if (j < 0) return;
-    const int64_t o = ok >> 3;
-    const float *g = dP + o * c + u * VEC;
-    const int32_t *a = argmax + o * c + u * VEC;
-    const float *act = A + (int64_t)j * c + u * VEC;
-    float *d = dY + (int64_t)j * c + u * VEC;
+    if (item >= n_coarse * cu) return;
+    const int64_t o = item / cu;
+    const int u = (int)(item - o * cu);
+    const int32_t *kids = child8 + o * 8;
+    const float *zsrc = reinterpret_cast<const float *>(g_zero16);
+    int32_t j[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) j[k] = kids[k];
+    float g[VEC], x[8][VEC];
+    int32_t a[VEC];
     if constexpr (VEC == 4) {
-        const f32x4 gv = *reinterpret_cast<const f32x4 *>(g);
-        const int4 av = *reinterpret_cast<const int4 *>(a);
-        const f32x4 xv = *reinterpret_cast<const f32x4 *>(act);
-        *reinterpret_cast<f32x4 *>(d) = f32x4{((av.x == j) & (xv[0] > 0.f)) ? gv[0] : 0.f, ((av.y == j) & (xv[1] > 0.f)) ? gv[1] : 0.f,
-                                             ((av.z == j) & (xv[2] > 0.f)) ? gv[2] : 0.f, ((av.w == j) & (xv[3] > 0.f)) ? gv[3] : 0.f};
+        const f32x4 gv = *reinterpret_cast<const f32x4 *>(dP + o * c + u * 4);
+        const int4 av = *reinterpret_cast<const int4 *>(argmax + o * c + u * 4);
+        g[0] = gv[0]; g[1] = gv[1]; g[2] = gv[2]; g[3] = gv[3];
+        a[0] = av.x; a[1] = av.y; a[2] = av.z; a[3] = av.w;
     } else {
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) d[e] = ((a[e] == j) & (act[e] > 0.f)) ? g[e] : 0.f;
+        for (int e = 0; e < VEC; ++e) { g[e] = dP[o * c + u * VEC + e]; a[e] = argmax[o * c + u * VEC + e]; }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const float *s = j[k] >= 0 ? A + (int64_t)j[k] * c + u * VEC : zsrc;
+        if constexpr (VEC == 4) {
+            const f32x4 t = *reinterpret_cast<const f32x4 *>(s);
+            x[k][0] = t[0]; x[k][1] = t[1]; x[k][2] = t[2]; x[k][3] = t[3];
+        } else {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) x[k][e] = s[e];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        if (j[k] < 0) continue;
+        float r[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) r[e] = ((a[e] == j[k]) & (x[k][e] > 0.f)) ? g[e] : 0.f;
+        float *d = dY + (int64_t)j[k] * c + u * VEC;
+        if constexpr (VEC == 4) *reinterpret_cast<f32x4 *>(d) = f32x4{r[0], r[1], r[2], r[3]};
+        else {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) d[e] = r[e];
+        }
     }
 }
 

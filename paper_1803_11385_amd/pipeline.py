@@ -28,13 +28,17 @@ class Encoder:
         ch = self.channels
         self.X = [torch.empty((self.n[l], ch[l]), **f32) for l in range(self.L + 1)]    # level inputs
         self.Y = [torch.empty((self.n[l], ch[l + 1]), **f32) for l in range(self.L)]    # conv outputs
-        self.A = [torch.empty((self.n[l], ch[l + 1]), **f32) for l in range(self.L)]    # after ReLU
+        # the rectified rows are kept only when ReLU and pooling run as separate calls: the
+        # fused calls take the sign for the backward pass from Y
+        self.A = [None if fuse_pointwise else torch.empty((self.n[l], ch[l + 1]), **f32)
+                  for l in range(self.L)]
         self.sw = [torch.empty((self.n[l + 1], ch[l + 1]), dtype=torch.int32, device=device)
                    for l in range(self.L)]
         self.W = [torch.empty((27, ch[l], ch[l + 1]), **f32) for l in range(self.L)]
         self.dW = [torch.empty((27, ch[l], ch[l + 1]), **f32) for l in range(self.L)]
         self.dX = [torch.empty((self.n[l], ch[l]), **f32) for l in range(self.L + 1)]   # dX[L] = upstream
-        self.dA = [torch.empty((self.n[l], ch[l + 1]), **f32) for l in range(self.L)]
+        self.dA = [None if fuse_pointwise else torch.empty((self.n[l], ch[l + 1]), **f32)
+                   for l in range(self.L)]
         self.dY = [torch.empty((self.n[l], ch[l + 1]), **f32) for l in range(self.L)]
         need = 256
         for l in range(self.L):
@@ -56,7 +60,7 @@ class Encoder:
             B.hch_conv_fwd(self.levels, l, B.HCH_F32, self.X[l], self.W[l], self.Y[l], ch[l], ch[l + 1], self.ws,
                            self.algo)
             if self.fuse_pointwise:
-                B.hch_relu_pool_fwd(self.levels, l, self.Y[l], self.A[l], self.X[l + 1], self.sw[l], ch[l + 1])
+                B.hch_relu_pool_fwd(self.levels, l, self.Y[l], None, self.X[l + 1], self.sw[l], ch[l + 1])
             else:
                 B.hch_relu_fwd(self.Y[l], self.A[l], self.A[l].numel())
                 B.hch_pool_fwd(self.levels, l, self.A[l], self.X[l + 1], self.sw[l], ch[l + 1])
@@ -65,7 +69,7 @@ class Encoder:
         ch = self.channels
         for l in reversed(range(self.L)):
             if self.fuse_pointwise:
-                B.hch_pool_relu_bwd(self.levels, l, self.dX[l + 1], self.sw[l], self.A[l], self.dY[l], ch[l + 1])
+                B.hch_pool_relu_bwd(self.levels, l, self.dX[l + 1], self.sw[l], self.Y[l], self.dY[l], ch[l + 1])
             else:
                 B.hch_pool_bwd(self.levels, l, self.dX[l + 1], self.sw[l], self.dA[l], ch[l + 1])
                 B.hch_relu_bwd(self.A[l], self.dA[l], self.dY[l], self.dY[l].numel())

@@ -71,7 +71,8 @@ def test_full_size_encoder_step(oracle, full, algo):
         ci, co = CHANNELS[l], CHANNELS[l + 1]
         Xl = enc.X[l].cpu().numpy()
         Yl = enc.Y[l].cpu().numpy()
-        Al = enc.A[l].cpu().numpy()
+        # the fused calls do not store the rectified rows
+        Al = np.maximum(Yl, 0) if fused_pw else enc.A[l].cpu().numpy()
         Xp, Wp = oracle.to_paper_X(Xl), oracle.to_paper_W(W[l])
         ns = 1500 if l < 2 else 400
         idx = np.sort(rng.choice(L.Ntot, min(ns, L.Ntot), replace=False))

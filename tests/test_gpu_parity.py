@@ -281,6 +281,15 @@ def test_fused_relu_pool(oracle, case_batch64, c):
     hch.hch_pool_relu_bwd(case.glv, 0, dev(dP), sw, A, dY, c)
     dA = oracle.pool_max_bwd(lf.Ntot, oracle.to_paper_X(dP), swo).T
     assert np.array_equal(dY.cpu().numpy(), np.where(Ao > 0, dA, 0).astype(np.float32))
+    # without storing the rectified rows: same pooled values and switches, and the backward
+    # pass takes the sign from the values before the ReLU
+    P2 = torch.full_like(P, float("nan"))
+    sw2 = torch.full_like(sw, -7)
+    hch.hch_relu_pool_fwd(case.glv, 0, dev(Yin), None, P2, sw2, c)
+    assert torch.equal(P2, P) and torch.equal(sw2, sw)
+    dY2 = torch.full_like(dY, float("nan"))
+    hch.hch_pool_relu_bwd(case.glv, 0, dev(dP), sw2, dev(Yin), dY2, c)
+    assert torch.equal(dY2, dY)
 
 
 def test_relu():
