@@ -1,0 +1,170 @@
+// Gathered products without a staging pass through LDS: every wavefront loads its matrix-core
+// operands from memory straight into registers and runs on its own, with no workgroup barrier.
+//
+// The MFMA 16x16x4 instruction takes, from lane l, one element of each operand for reduction
+// index l/16.  The reduction dimension of the gathered product (Eq.3 with the column matrix of
+// Algorithm 1 never formed) is cut into 16-byte units: unit u = tap*(c/4) + q holds channels
+// 4q..4q+3 of neighbour `tap`.  In reduction block j, lane group g = l/16 loads unit 4j+g of
+// its voxel (ONE 16-byte load: a quarter of a neighbour row when c = 16, the whole row of one
+// of four taps when c = 4) and the four instructions of the block take elements 0..3 of it, so
+// the reduction runs in a permuted order that costs nothing.
+#pragma once
+#include "kernels.hip.hpp"
+
+namespace hch {
+
+template <int NT> struct FragOf;
+template <> struct FragOf<1> { typedef float type; };
+template <> struct FragOf<2> { typedef float type __attribute__((ext_vector_type(2))); };
+template <> struct FragOf<4> { typedef f32x4 type; };
+
+template <int NT> __device__ __forceinline__ float frag_get(const typename FragOf<NT>::type &f, int i)
+{
+    if constexpr (NT == 1) return f; else return f[i];
+}
+
+// Y[i][n] (+ split slices) = sum over taps and channels of X[nbr[i][tap]][ch] * Wm[tap*c + ch][n]
+//   X    [M][c] rows, c % 4 == 0, 16-byte aligned
+//   nbr  [M][27]
+//   Wm   [27*c][N] row-major, 16-byte aligned, N % 4 == 0
+//   Y    [M][N] (slice z of a split reduction at Y + z*split_stride)
+// A wavefront owns 16*RT voxels and 16*NT output columns; a workgroup is four independent
+// wavefronts on consecutive voxel tiles.  Output column nb + NT*i + t belongs to column tile t
+// (row i of the instruction's weight operand), so a lane loads its NT weights of one reduction
+// row as one vector and ends up holding 4*NT consecutive outputs of one voxel.
+// S register sets form a ring: the loads of block j+S-1 are issued before the products of
+// block j.  CHECK: the last block may have units past the 27 taps (c % 16 != 0) or the column
+// group may reach past N; without it c % 16 == 0 and N % (16*NT) == 0.
+template <int RT, int NT, int S, bool CHECK>
+__global__ __launch_bounds__(256) void conv_direct_kernel(
+    const float *__restrict__ X, const int32_t *__restrict__ nbr, const float *__restrict__ Wm,
+    float *__restrict__ Y, int M, int c, int N, int J, int j_per_split, int upt, int step_t, int step_q,
+    unsigned wave_tiles, int64_t split_stride)
+{
+    typedef typename FragOf<NT>::type wfrag;
+    constexpr int ROWS = 16 * RT;
+    constexpr int IDX = ROWS * 27;
+    __shared__ int32_t sidx[4 * IDX];
+
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int r = lane & 15, g = lane >> 4;
+    const unsigned tile = xcd_tile(blockIdx.x, gridDim.x / NUM_XCD) * 4 + wv;
+    if (tile >= wave_tiles) return;                    // no barrier below: a wave may leave alone
+    const int nb = blockIdx.y * (16 * NT);
+    const int jb = blockIdx.z * j_per_split;
+    const int je = min(J, jb + j_per_split);
+
+    // this wave's 16*RT x 27 neighbour indices: one contiguous piece of the list, kept in LDS
+    // (written and read by this wave only)
+    int32_t *my = sidx + wv * IDX;
+    {
+        const int64_t pos0 = (int64_t)tile * IDX, lim = (int64_t)M * 27;
+        constexpr int PER = (IDX + 63) / 64;
+        int32_t v[PER];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {                 // all loads first, then all stores
+            const int64_t o = pos0 + i * 64 + lane;
+            v[i] = *(o < lim ? nbr + o : &g_minus1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if (IDX % 64 == 0 || i * 64 + lane < IDX) my[i * 64 + lane] = v[i];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    const float *zsrc = reinterpret_cast<const float *>(g_zero16);
+    // (t, q): tap and unit-in-tap of the block whose indices are read next, for this lane group
+    int jn = jb;
+    int t = (4 * jb + g) / upt;
+    int q = (4 * jb + g) - t * upt;
+    int32_t nidx[RT];
+    int cur_q4 = 0, cur_k = 0;
+    auto fetch_idx = [&]() {
+        const bool ok = (jn < je) & (t < 27);
+        const int tt = t < 27 ? t : 26;
+#pragma unroll
+        for (int i = 0; i < RT; ++i) {
+            const int32_t v = my[(16 * i + r) * 27 + tt];
+            nidx[i] = ok ? v : -1;
+        }
+        cur_q4 = 4 * q; cur_k = t * c + 4 * q;
+        t += step_t; q += step_q;
+        if (q >= upt) { q -= upt; ++t; }
+        ++jn;
+    };
+    // Weight loads never leave the matrix: past its last reduction row (blocks beyond this
+    // slice, units beyond the 27 taps) the row is clamped, which is harmless because the
+    // gathered operand is zero there; past its last column the column is clamped, and the
+    // outputs of such a lane are never stored.
+    const int wcol = CHECK ? min(nb + NT * r, N - NT) : nb + NT * r;
+    const int k_last = 27 * c - 4;
+    auto issue = [&](f32x4 (&a)[RT], wfrag (&b)[4]) {
+#pragma unroll
+        for (int i = 0; i < RT; ++i) {
+            const float *p = nidx[i] >= 0 ? X + (uint32_t)(nidx[i] * c + cur_q4) : zsrc;
+            a[i] = *reinterpret_cast<const f32x4 *>(p);
+        }
+        const float *wp = Wm + ((uint32_t)(min(cur_k, k_last) * N) + wcol);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) b[e] = *reinterpret_cast<const wfrag *>(wp + e * N);
+    };
+
+    f32x4 acc[RT][NT];
+#pragma unroll
+    for (int i = 0; i < RT; ++i)
+#pragma unroll
+        for (int n = 0; n < NT; ++n) acc[i][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto multiply = [&](const f32x4 (&a)[RT], const wfrag (&b)[4]) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int i = 0; i < RT; ++i)
+#pragma unroll
+                for (int n = 0; n < NT; ++n)
+                    acc[i][n] = __builtin_amdgcn_mfma_f32_16x16x4f32(frag_get<NT>(b[e], n), a[i][e], acc[i][n], 0, 0, 0);
+    };
+
+    f32x4 ra[S][RT];
+    wfrag rb[S][4];
+    fetch_idx();
+#pragma unroll
+    for (int s = 0; s < S - 1; ++s) { issue(ra[s], rb[s]); fetch_idx(); }
+    __builtin_amdgcn_sched_barrier(0);
+    for (int j0 = jb; j0 < je; j0 += S) {
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            // the scheduler must not sink these loads down to their use two steps later
+            issue(ra[(s + S - 1) % S], rb[(s + S - 1) % S]);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch_idx();
+            multiply(ra[s], rb[s]);      // blocks past je were gathered as zeros
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+
+    // accumulator register e of column tile n, lane (r, g): voxel r, output column
+    // nb + NT*(4g + e) + n, i.e. element NT*e + n of this lane's 4*NT consecutive columns
+    float *out = Y + (int64_t)blockIdx.z * split_stride;
+#pragma unroll
+    for (int i = 0; i < RT; ++i) {
+        const int64_t row = (int64_t)tile * ROWS + 16 * i + r;
+        if (row >= M) continue;
+#pragma unroll
+        for (int f = 0; f < NT; ++f) {
+            const int col = nb + 4 * NT * g + 4 * f;
+            if (CHECK && col >= N) continue;
+            f32x4 v;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int m = 4 * f + x;
+                v[x] = acc[i][m % NT][m / NT];
+            }
+            *reinterpret_cast<f32x4 *>(out + row * N + col) = v;
+        }
+    }
+}
+
+}  // namespace hch

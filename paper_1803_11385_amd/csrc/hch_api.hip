@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "kernels.hip.hpp"
+#include "direct.hip.hpp"
 #include "profile.hpp"
 #include "psh_build.hpp"
 
@@ -620,6 +621,65 @@ static hch_status launch_gemm(hch_dtype dtype, const GemmPlan &p, const void *A,
     return launch_gemm_t<float, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s);
 }
 
+// Register-direct gathered product (conv_direct_kernel): shape-only part of the plan, shared by
+// the workspace query and the launch.  Used for products with at most 16 output columns (the
+// first forward layer, data gradients into few channels): there a staged tile would be written
+// to LDS and read back exactly once, and this kernel measured faster; wider outputs go to the
+// LDS-tiled kernel, which measured faster there.
+struct DirectPlan {
+    bool ok;
+    int rt, nt, S;
+    bool check;
+    int J, upt, step_t, step_q;
+    int splits, j_per_split;
+    unsigned wave_tiles, n_groups;
+};
+
+static DirectPlan plan_direct(int64_t M, int c, int N)
+{
+    DirectPlan d{};
+    d.ok = M > 0 && c % 4 == 0 && N % 4 == 0 && N <= 16 && M * std::max(c, N) < ((int64_t)1 << 31) - 64 * std::max(c, N);
+    if (!d.ok) return d;
+    d.nt = 1; d.rt = 4; d.S = 4;
+    d.check = (c % 16 != 0) || (N % (16 * d.nt) != 0);
+    d.upt = c / 4;
+    d.J = (27 * d.upt + 3) / 4;
+    d.step_t = 4 / d.upt;
+    d.step_q = 4 % d.upt;
+    d.n_groups = (unsigned)((N + 16 * d.nt - 1) / (16 * d.nt));
+    d.wave_tiles = (unsigned)((M + 16 * d.rt - 1) / (16 * d.rt));
+    // small levels: slices of the reduction until every SIMD has a few waves
+    const int64_t waves = (int64_t)d.wave_tiles * d.n_groups;
+    int64_t want = waves >= 1536 ? 1 : std::max<int64_t>(1, std::min<int64_t>((2048 + waves - 1) / waves, d.J / (3 * d.S)));
+    int jps = (int)((d.J + want - 1) / want);
+    jps = (jps + d.S - 1) / d.S * d.S;
+    d.j_per_split = jps;
+    d.splits = (d.J + jps - 1) / jps;
+    return d;
+}
+
+static hch_status launch_direct(const DirectPlan &d, const float *X, const int32_t *nbr, const float *Wm,
+                                float *out, int64_t M, int c, int N, double alg_bytes, hipStream_t s)
+{
+    const unsigned blocks = (d.wave_tiles + 3) / 4;
+    const dim3 grid((blocks / hch::NUM_XCD + 1) * hch::NUM_XCD, d.n_groups, (unsigned)d.splits);
+    static int ids[2] = {-1, -1};
+    const int b = d.check ? 1 : 0;
+    if (ids[b] < 0) {
+        char nm[96];
+        snprintf(nm, sizeof nm, "conv_direct_kernel<%d, %d, %d, %s>", d.rt, d.nt, d.S, d.check ? "true" : "false");
+        ids[b] = hch::Profiler::get().id_for(nm);
+    }
+    hch::LaunchTimer lt(ids[b], s, alg_bytes, 2.0 * M * (double)N * 27.0 * c);
+#define HCH_DIRECT_CASE(RT_, NT_, S_, CHECK_)                                                                       \
+    hipLaunchKernelGGL((hch::conv_direct_kernel<RT_, NT_, S_, CHECK_>), grid, dim3(256), 0, s, X, nbr, Wm, out,  \
+                       (int)M, c, N, d.J, d.j_per_split, d.upt, d.step_t, d.step_q, d.wave_tiles, M * (int64_t)N)
+    if (d.check) HCH_DIRECT_CASE(4, 1, 4, true); else HCH_DIRECT_CASE(4, 1, 4, false);
+#undef HCH_DIRECT_CASE
+    HCH_LAUNCH_CHECK("conv_direct_kernel");
+    return HCH_OK;
+}
+
 static hch_status launch_reduce(const float *part, float *out, int64_t n, int splits, hipStream_t s)
 {
     const int kid = splits <= 16 ? HCH_KERNEL_ID("splitk_reduce_kernel<1>")
@@ -649,13 +709,17 @@ static WsLayout ws_layout(const Level &L, int c_in, int c_out, hch_dtype dtype, 
     if (kind == HCH_WS_FWD) {
         const GemmPlan p = plan_rows(L.n_total, c_out, (int)Kc, true);
         if (algo == HCH_ALGO_COLUMNS) w.first_bytes = round_up(n * Kc * elem_size(dtype), 256);
-        if (p.splits > 1) w.part_bytes = round_up((size_t)p.splits * n * c_out * 4, 256);
+        int splits = p.splits;
+        if (algo == HCH_ALGO_FUSED) { const DirectPlan d = plan_direct(L.n_total, c_in, c_out); if (d.ok) splits = std::max(splits, d.splits); }
+        if (splits > 1) w.part_bytes = round_up((size_t)splits * n * c_out * 4, 256);
     } else if (kind == HCH_WS_BWD_DATA) {
         if (algo == HCH_ALGO_COLUMNS) w.first_bytes = round_up(n * Kc * 4, 256);
         else {
             const GemmPlan p = plan_rows(L.n_total, c_in, 27 * c_out, true);
             w.first_bytes = round_up(Kc * c_out * elem_size(dtype), 256);
-            if (p.splits > 1) w.part_bytes = round_up((size_t)p.splits * n * c_in * 4, 256);
+            const DirectPlan d = plan_direct(L.n_total, c_out, c_in);
+            const int splits = d.ok ? std::max(p.splits, d.splits) : p.splits;
+            if (splits > 1) w.part_bytes = round_up((size_t)splits * n * c_in * 4, 256);
         }
     } else if (kind == HCH_WS_BWD_WEIGHT) {
         const GemmPlan p = plan_wgrad(L.n_total, c_in, c_out);
@@ -730,6 +794,14 @@ extern "C" hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_
     if (algo == HCH_ALGO_FUSED) {
         // Y = gathered columns . W, the column matrix never leaves the chip.  Per voxel: 27
         // indices and its feature row in, one output row out; the weights once.
+        const DirectPlan d = plan_direct(n, c_in, c_out);
+        if (d.ok && dtype == HCH_F32 && aligned16(X) && aligned16(W) && aligned16(Y)) {
+            const double bytes = (double)n * (108.0 + 4.0 * c_in + 4.0 * c_out * d.splits) + 4.0 * Kc * c_out;
+            st = launch_direct(d, (const float *)X, L->dnbr, (const float *)W, d.splits > 1 ? part : Y, n, c_in, c_out, bytes, s);
+            if (st != HCH_OK) return st;
+            if (d.splits > 1) st = launch_reduce(part, Y, n * c_out, d.splits, s);
+            return st;
+        }
         const double bytes = (double)n * (108.0 + es * c_in + 4.0 * c_out * p.splits) + es * Kc * c_out;
         st = launch_gemm<hch::A_GATHER, false>(dtype, p, X, W,
                                                p.splits > 1 ? part : Y, L->dnbr, (int)n, c_out, Kc, c_in,
@@ -790,6 +862,14 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
         }
         HCH_LAUNCH_CHECK("flip_transpose_weights_kernel");
         const int Kd = 27 * c_out;
+        const DirectPlan d = plan_direct(n, c_out, c_in);
+        if (d.ok && dtype == HCH_F32 && aligned16(dY) && aligned16(dX)) {
+            const double bytes = (double)n * (108.0 + 4.0 * c_out + 4.0 * c_in * d.splits) + 4.0 * wn;
+            st = launch_direct(d, (const float *)dY, L->dnbr, (const float *)Wt, d.splits > 1 ? part : dX, n, c_out, c_in, bytes, s);
+            if (st != HCH_OK) return st;
+            if (d.splits > 1) st = launch_reduce(part, dX, n * c_in, d.splits, s);
+            return st;
+        }
         const GemmPlan p = plan_rows(n, c_in, Kd, true);
         const double bytes = (double)n * (108.0 + es * c_out + 4.0 * c_in * p.splits) + es * wn;
         st = launch_gemm<hch::A_GATHER, false>(dtype, p, dY, Wt,
