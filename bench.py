@@ -91,6 +91,8 @@ def main():
                     help="before the warm-up, run the library's ReLU kernel three times over 2^24 floats (reads "
                          "64 MiB, writes 64 MiB): the known-size copy that scales the FETCH_SIZE / WRITE_SIZE "
                          "counters of a rocprofv3 --pmc run")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="run the weight gradients on the main stream instead of a second one")
     ap.add_argument("--algo", choices=["columns", "fused"], default="fused",
                     help="columns: hash2col -> GEMM -> col2hash through memory; fused: gathered GEMM operand")
     args = ap.parse_args()
@@ -113,7 +115,7 @@ def main():
     levels = hch.hch_build_levels(coords, offs, u, 6)
     t_build = time.perf_counter() - t0
     algo = hch.HCH_ALGO_FUSED if args.algo == "fused" else hch.HCH_ALGO_COLUMNS
-    enc = Encoder(levels, CHANNELS, algo)
+    enc = Encoder(levels, CHANNELS, algo, two_streams=not args.single_stream)
     enc.X[0].copy_(torch.from_numpy(X0))
     for l in range(5):
         enc.W[l].copy_(torch.from_numpy(W[l]))
@@ -220,7 +222,8 @@ def main():
         # the other algorithm on the same inputs, every kernel timed (event overhead included in
         # its step time): per-kernel rooflines of the gather, GEMM and scatter kernels
         other = "columns" if args.algo == "fused" else "fused"
-        enc2 = Encoder(levels, CHANNELS, hch.HCH_ALGO_COLUMNS if other == "columns" else hch.HCH_ALGO_FUSED)
+        enc2 = Encoder(levels, CHANNELS, hch.HCH_ALGO_COLUMNS if other == "columns" else hch.HCH_ALGO_FUSED,
+                       two_streams=not args.single_stream)
         enc2.X[0].copy_(enc.X[0]); enc2.dX[5].copy_(enc.dX[5])
         for l in range(5):
             enc2.W[l].copy_(enc.W[l])

@@ -141,6 +141,10 @@ hch_status hch_level_info(const hch_levels *levels, int32_t level, hch_level_des
  */
 hch_status hch_build_neighbours(hch_levels *levels, int32_t level, void *stream);
 
+/* The same for levels first .. first+count-1 (two launches for the whole range), so that a
+ * caller can build the finest level on one stream and the coarser ones beside it on another. */
+hch_status hch_build_neighbours_range(hch_levels *levels, int32_t first, int32_t count, void *stream);
+
 /*
  * hash2col (Algorithm 1), rows [row_begin, row_begin + row_count) of the column matrix:
  *   X    DEVICE [N_l][c_in]              (float or bf16 per dtype)

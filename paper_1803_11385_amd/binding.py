@@ -12,8 +12,8 @@ __all__ = [
     "HCH_WS_FWD", "HCH_WS_BWD_DATA", "HCH_WS_BWD_WEIGHT", "HCH_WS_MIN",
     "HCH_ALGO_COLUMNS", "HCH_ALGO_FUSED",
     "library_path", "load_library", "exported_symbols",
-    "hch_build_levels", "hch_build_tables_host", "hch_build_neighbours", "hch_hash2col",
-    "hch_col2hash", "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data",
+    "hch_build_levels", "hch_build_tables_host", "hch_build_neighbours", "hch_build_neighbours_range",
+    "hch_hash2col", "hch_col2hash", "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data",
     "hch_conv_bwd_weight", "hch_pool_fwd", "hch_pool_bwd", "hch_relu_fwd", "hch_relu_bwd", "hch_relu_pool_fwd",
     "hch_pool_relu_bwd", "hch_deconv_fwd", "hch_deconv_bwd_data", "hch_deconv_bwd_weight",
     "hch_unpool_fwd", "hch_unpool_bwd", "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
@@ -30,7 +30,8 @@ _LIBPATH = os.path.join(_HERE, "libhch.so")
 # every symbol include/hch.h declares
 exported_symbols = [
     "hch_last_error", "hch_build_levels", "hch_build_tables_host", "hch_free_levels",
-    "hch_num_levels", "hch_level_info", "hch_build_neighbours", "hch_hash2col", "hch_col2hash",
+    "hch_num_levels", "hch_level_info", "hch_build_neighbours", "hch_build_neighbours_range", "hch_hash2col",
+    "hch_col2hash",
     "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data", "hch_conv_bwd_weight",
     "hch_pool_fwd", "hch_pool_bwd", "hch_relu_fwd", "hch_relu_bwd", "hch_relu_pool_fwd",
     "hch_pool_relu_bwd", "hch_deconv_fwd", "hch_deconv_bwd_data", "hch_deconv_bwd_weight",
@@ -87,6 +88,7 @@ def load_library():
     L.hch_num_levels.restype = i32
     L.hch_level_info.argtypes = [vp, i32, C.POINTER(_Desc)]
     L.hch_build_neighbours.argtypes = [vp, i32, vp]
+    L.hch_build_neighbours_range.argtypes = [vp, i32, i32, vp]
     L.hch_hash2col.argtypes = [vp, i32, C.c_int, vp, i32, i64, i64, vp, vp]
     L.hch_col2hash.argtypes = [vp, i32, vp, i32, vp, vp]
     L.hch_conv_workspace_bytes.argtypes = [vp, i32, i32, i32, C.c_int, C.c_int, C.c_int]
@@ -293,6 +295,10 @@ def hch_build_tables_host(coords, model_offsets, resolution, n_levels):
 
 def hch_build_neighbours(levels, level, stream=None):
     _check(load_library().hch_build_neighbours(levels.handle, level, _stream(stream)))
+
+
+def hch_build_neighbours_range(levels, first, count, stream=None):
+    _check(load_library().hch_build_neighbours_range(levels.handle, first, count, _stream(stream)))
 
 
 def hch_hash2col(levels, level, dtype, X, c_in, row_begin, row_count, col, stream=None):

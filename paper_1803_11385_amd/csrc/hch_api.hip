@@ -169,6 +169,15 @@ extern "C" hch_status hch_build_neighbours(hch_levels *levels, int32_t level, vo
     return launch_index_lists(levels, level, level + 1, (hipStream_t)stream);
 }
 
+extern "C" hch_status hch_build_neighbours_range(hch_levels *levels, int32_t first, int32_t count, void *stream)
+{
+    if (!levels || first < 0 || count < 0 || (int64_t)first + count > (int64_t)levels->lv.size())
+        return fail(HCH_EINVAL, "hch_build_neighbours_range: bad level range");
+    if (!levels->d_nbr_prefix) return fail(HCH_EINVAL, "hch_build_neighbours_range: levels were built without device tables");
+    if (count == 0) return HCH_OK;
+    return launch_index_lists(levels, first, first + count, (hipStream_t)stream);
+}
+
 static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_offsets,
                              int32_t batch, int32_t resolution, int32_t n_levels,
                              void *stream, bool with_device, hch_levels **out)
