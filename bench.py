@@ -91,8 +91,10 @@ def main():
                     help="before the warm-up, run the library's ReLU kernel three times over 2^24 floats (reads "
                          "64 MiB, writes 64 MiB): the known-size copy that scales the FETCH_SIZE / WRITE_SIZE "
                          "counters of a rocprofv3 --pmc run")
-    ap.add_argument("--single-stream", action="store_true",
-                    help="run the weight gradients on the main stream instead of a second one")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="timed region with the weight gradients and the coarse index lists on a second "
+                         "stream (faster; kernels then share the chip, so per-kernel times are not clean)")
+    ap.add_argument("--no-overlap-pass", action="store_true", help="skip the extra two-stream pass")
     ap.add_argument("--algo", choices=["columns", "fused"], default="fused",
                     help="columns: hash2col -> GEMM -> col2hash through memory; fused: gathered GEMM operand")
     args = ap.parse_args()
@@ -115,7 +117,7 @@ def main():
     levels = hch.hch_build_levels(coords, offs, u, 6)
     t_build = time.perf_counter() - t0
     algo = hch.HCH_ALGO_FUSED if args.algo == "fused" else hch.HCH_ALGO_COLUMNS
-    enc = Encoder(levels, CHANNELS, algo, two_streams=not args.single_stream)
+    enc = Encoder(levels, CHANNELS, algo, two_streams=args.two_streams)
     enc.X[0].copy_(torch.from_numpy(X0))
     for l in range(5):
         enc.W[l].copy_(torch.from_numpy(W[l]))
@@ -218,12 +220,30 @@ def main():
         "kernels_ms_first_step": {k: round(v[1]["ms"], 4) for k, v in first.items()},
     }
 
+    if not args.two_streams and not args.no_overlap_pass:
+        # the same steps with the weight gradients and the coarse levels' index lists on a second
+        # stream: whole-step throughput when independent kernels share the chip
+        enc3 = Encoder(levels, CHANNELS, algo, two_streams=True)
+        enc3.X[0].copy_(enc.X[0]); enc3.dX[5].copy_(enc.dX[5])
+        for l in range(5):
+            enc3.W[l].copy_(enc.W[l])
+        for _ in range(max(1, args.warmup)):
+            enc3.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            enc3.step()
+        torch.cuda.synchronize()
+        dt3 = time.perf_counter() - t0
+        out["two_streams"] = {"ms_per_step": round(dt3 / args.steps * 1e3, 4),
+                              "value": round(flops / (dt3 / args.steps) / 1e12, 4), "unit": "TFLOP/s"}
+        del enc3
+
     if not args.no_other_algo:
         # the other algorithm on the same inputs, every kernel timed (event overhead included in
         # its step time): per-kernel rooflines of the gather, GEMM and scatter kernels
         other = "columns" if args.algo == "fused" else "fused"
-        enc2 = Encoder(levels, CHANNELS, hch.HCH_ALGO_COLUMNS if other == "columns" else hch.HCH_ALGO_FUSED,
-                       two_streams=not args.single_stream)
+        enc2 = Encoder(levels, CHANNELS, hch.HCH_ALGO_COLUMNS if other == "columns" else hch.HCH_ALGO_FUSED)
         enc2.X[0].copy_(enc.X[0]); enc2.dX[5].copy_(enc.dX[5])
         for l in range(5):
             enc2.W[l].copy_(enc.W[l])

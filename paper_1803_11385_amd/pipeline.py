@@ -19,7 +19,7 @@ class Encoder:
     `levels` must hold L+1 levels.  All buffers are allocated once here."""
 
     def __init__(self, levels, channels, algo=B.HCH_ALGO_COLUMNS, device="cuda", fuse_pointwise=True,
-                 two_streams=True):
+                 two_streams=False):
         self.levels, self.channels, self.algo = levels, list(channels), algo
         self.fuse_pointwise = fuse_pointwise       # ReLU+pool (and their backward) as one call each
         # backward: the weight gradient of a level runs on a second stream (default priority)

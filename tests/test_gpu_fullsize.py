@@ -51,19 +51,22 @@ def test_full_size_tables_and_lists(oracle, full):
             assert np.array_equal(info.device_child8(), oracle.children(olv[l - 1], L)), f"child8 level {l}"
 
 
-@pytest.mark.parametrize("algo", [hch.HCH_ALGO_FUSED, hch.HCH_ALGO_COLUMNS], ids=["fused", "columns"])
-def test_full_size_encoder_step(oracle, full, algo):
+@pytest.mark.parametrize("algo,two_streams", [(hch.HCH_ALGO_FUSED, False), (hch.HCH_ALGO_FUSED, True),
+                                              (hch.HCH_ALGO_COLUMNS, False)],
+                         ids=["fused", "fused-two-streams", "columns"])
+def test_full_size_encoder_step(oracle, full, algo, two_streams):
     from paper_1803_11385_amd.pipeline import Encoder
     olv, glv, W = full["olv"], full["glv"], full["W"]
     # the fused algorithm is run with the fused ReLU/pool calls, the columns one with separate calls
     fused_pw = algo == hch.HCH_ALGO_FUSED
-    enc = Encoder(glv, CHANNELS, algo, fuse_pointwise=fused_pw)
+    enc = Encoder(glv, CHANNELS, algo, fuse_pointwise=fused_pw, two_streams=two_streams)
     enc.X[0].copy_(torch.from_numpy(full["X0"]))
     for l in range(5):
         enc.W[l].copy_(torch.from_numpy(W[l]))
     G = S.gaussian((enc.n[5], CHANNELS[5]), 1.0, 4100)
     enc.dX[5].copy_(torch.from_numpy(G))
     enc.step()
+    enc.step()      # a second pass over the same buffers: stream hand-over between passes
     torch.cuda.synchronize()
     rng = np.random.default_rng(7)
     for l in range(5):

@@ -96,6 +96,10 @@ def test_neighbour_rebuild_is_idempotent(oracle, case_batch64):
     case = case_batch64
     for l in range(3):
         hch.hch_build_neighbours(case.glv, l)
+    hch.hch_build_neighbours_range(case.glv, 1, 2)
+    hch.hch_build_neighbours_range(case.glv, 0, 0)
+    with pytest.raises(hch.HchError):
+        hch.hch_build_neighbours_range(case.glv, 2, 2)
     torch.cuda.synchronize()
     assert np.array_equal(case.glv.info(1).device_nbr27(), oracle.neighbours(case.olv[1]))
     assert np.array_equal(case.glv.info(2).device_child8(), oracle.children(case.olv[1], case.olv[2]))
