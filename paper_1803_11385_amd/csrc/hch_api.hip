@@ -483,22 +483,30 @@ extern "C" hch_status hch_hash2col(const hch_levels *levels, int32_t level, hch_
     return do_hash2col(*L, dtype, X, c_in, row_begin, row_count, col, (hipStream_t)stream);
 }
 
-static hch_status do_col2hash(const Level &L, const float *dcol, int c_in, float *dX, hipStream_t s)
+// planes: dcol is stored tap-major, [27][n][c_in] (the library's own layout between the data
+// gradient product and this gather; needs c_in % 4 == 0), instead of [n][27*c_in]
+static hch_status do_col2hash(const Level &L, const float *dcol, int c_in, float *dX, bool planes, hipStream_t s)
 {
     if (L.n_total == 0) return HCH_OK;
     // per voxel: 27 indices in, one c_in row per occupied neighbour in, one row out
     const double bytes = (double)L.n_total * (108.0 + 4.0 * c_in) + (double)L.nbr_valid * 4.0 * c_in;
     const bool vec = c_in % 4 == 0 && aligned16(dcol) && aligned16(dX);
-    hch::LaunchTimer lt((vec ? HCH_KERNEL_ID("col2hash_kernel<4>") : HCH_KERNEL_ID("col2hash_kernel<1>")), s, bytes, (double)L.nbr_valid * c_in);
+    if (planes && !vec) return fail(HCH_EINVAL, "col2hash: tap-major layout needs aligned 4-channel units");
+    hch::LaunchTimer lt(planes ? HCH_KERNEL_ID("col2hash_kernel<4, true>")
+                               : (vec ? HCH_KERNEL_ID("col2hash_kernel<4, false>") : HCH_KERNEL_ID("col2hash_kernel<1, false>")),
+                        s, bytes, (double)L.nbr_valid * c_in);
     const int cu = vec ? c_in / 4 : c_in;
     const int tv = std::max(4, std::min(256, 256 / cu));
     const unsigned n_tiles = (unsigned)((L.n_total + tv - 1) / tv);
     const unsigned grid = (n_tiles + hch::NUM_XCD - 1) / hch::NUM_XCD * hch::NUM_XCD;
-    if (vec)
-        hipLaunchKernelGGL(hch::col2hash_kernel<4>, dim3(grid), dim3(256), 0, s, dcol, L.dnbr, dX,
+    if (planes)
+        hipLaunchKernelGGL((hch::col2hash_kernel<4, true>), dim3(grid), dim3(256), 0, s, dcol, L.dnbr, dX,
+                           L.n_total, c_in, tv, n_tiles);
+    else if (vec)
+        hipLaunchKernelGGL((hch::col2hash_kernel<4, false>), dim3(grid), dim3(256), 0, s, dcol, L.dnbr, dX,
                            L.n_total, c_in, tv, n_tiles);
     else
-        hipLaunchKernelGGL(hch::col2hash_kernel<1>, dim3(grid), dim3(256), 0, s, dcol, L.dnbr, dX,
+        hipLaunchKernelGGL((hch::col2hash_kernel<1, false>), dim3(grid), dim3(256), 0, s, dcol, L.dnbr, dX,
                            L.n_total, c_in, tv, n_tiles);
     HCH_LAUNCH_CHECK("col2hash");
     return HCH_OK;
@@ -511,7 +519,7 @@ extern "C" hch_status hch_col2hash(const hch_levels *levels, int32_t level, cons
     hch_status st = get_level(levels, level, &L, "hch_col2hash");
     if (st != HCH_OK) return st;
     if (!dcol || !dX || c_in <= 0) return fail(HCH_EINVAL, "hch_col2hash: bad argument");
-    return do_col2hash(*L, dcol, c_in, dX, (hipStream_t)stream);
+    return do_col2hash(*L, dcol, c_in, dX, false, (hipStream_t)stream);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -568,7 +576,8 @@ static inline bool k_split_aligned(const GemmPlan &p) { return p.k_per_split % 4
 template <typename TIN, int AMODE, bool B_KC>
 static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void *B, float *C,
                                 const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
-                                int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s)
+                                int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s,
+                                int c_planes = 0)
 {
     if (M <= 0 || N <= 0) return HCH_OK;
     GemmPlan p = plan;
@@ -580,7 +589,7 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
                      !(reinterpret_cast<uintptr_t>(A) & amask) && !(reinterpret_cast<uintptr_t>(B) & amask) &&
                      (k_split_aligned(p));
     if (!vec && p.bm == 64) { p.bm = 128; p.wm = 4; }   // the generic path has the 128-row tiles only
-    const int c_vec_ok = (ldc % 4 == 0) && (c_split_stride % 4 == 0) && aligned16(C);
+    const int c_vec_ok = (c_planes > 0 ? c_planes % 4 == 0 : ldc % 4 == 0) && (c_split_stride % 4 == 0) && aligned16(C);
     const unsigned m_tiles = (unsigned)((M + p.bm - 1) / p.bm);
     // XCD-contiguous row tiles only where rows are voxels and there are enough tiles to keep
     // every XCD busy (an exact multiple of 8 cannot be told apart from the plain order, so
@@ -589,31 +598,40 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
     const unsigned gx = remap ? (m_tiles / hch::NUM_XCD + 1) * hch::NUM_XCD : m_tiles;
     const dim3 grid(gx, (unsigned)((N + p.bn - 1) / p.bn), (unsigned)p.splits);
     // the kernel's name as a profiler prints it: gemm_f32_kernel<TIN, BM, BN, BK, WM, AMODE, B_KC>
-    static int ids[2][4] = {{-1, -1, -1, -1}, {-1, -1, -1, -1}};
+    static int ids[2][2][4] = {{{-1, -1, -1, -1}, {-1, -1, -1, -1}}, {{-1, -1, -1, -1}, {-1, -1, -1, -1}}};
     const int cfg = p.bm == 64 ? 0 : (p.bn == 16 ? 1 : (p.bn == 32 ? 2 : 3));
-    const int v = vec ? 1 : 0;
-    if (ids[v][cfg] < 0) {
+    const int v = vec ? 1 : 0, pl = c_planes > 0 ? 1 : 0;
+    if (pl && p.bn != 64) return fail(HCH_EINVAL, "gemm: plane-wise output needs the 64-column tile");
+    if (ids[pl][v][cfg] < 0) {
         char nm[128];
-        snprintf(nm, sizeof nm, "gemm_f32_kernel<%s, %d, %d, 32, %d, %d, %s, %s>",
+        snprintf(nm, sizeof nm, "gemm_f32_kernel<%s, %d, %d, 32, %d, %d, %s, %s, %s>",
                  sizeof(TIN) == 4 ? "float" : "unsigned short", p.bm, p.bm == 64 ? 64 : p.bn, p.wm,
-                 (int)AMODE, B_KC ? "true" : "false", v ? "true" : "false");
-        ids[v][cfg] = hch::Profiler::get().id_for(nm);
+                 (int)AMODE, B_KC ? "true" : "false", v ? "true" : "false", pl ? "true" : "false");
+        ids[pl][v][cfg] = hch::Profiler::get().id_for(nm);
     }
-    hch::LaunchTimer lt(ids[v][cfg], s, alg_bytes, 2.0 * M * (double)N * K);
-#define HCH_GEMM_CASE(BM_, BN_, BK_, WM_, VEC_)                                                                \
-    hipLaunchKernelGGL((hch::gemm_f32_kernel<TIN, BM_, BN_, BK_, WM_, AMODE, B_KC, VEC_>), grid, dim3(256), 0, s, \
+    hch::LaunchTimer lt(ids[pl][v][cfg], s, alg_bytes, 2.0 * M * (double)N * K);
+#define HCH_GEMM_CASE(BM_, BN_, BK_, WM_, VEC_, PL_)                                                                \
+    hipLaunchKernelGGL((hch::gemm_f32_kernel<TIN, BM_, BN_, BK_, WM_, AMODE, B_KC, VEC_, PL_>), grid, dim3(256), 0, s, \
                        (const TIN *)A, (const TIN *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split,            \
-                       c_split_stride, c_vec_ok, m_tiles)
+                       c_split_stride, c_vec_ok, m_tiles, c_planes)
+    if constexpr (AMODE == hch::A_ROWS && B_KC) {
+        if (pl) {
+            if (vec) { if (p.bm == 64) HCH_GEMM_CASE(64, 64, 32, 2, true, true); else HCH_GEMM_CASE(128, 64, 32, 4, true, true); }
+            else HCH_GEMM_CASE(128, 64, 32, 4, false, true);
+            HCH_LAUNCH_CHECK("gemm_f32_kernel");
+            return HCH_OK;
+        }
+    }
     if (vec) {
-        if (p.bm == 64) HCH_GEMM_CASE(64, 64, 32, 2, true);
-        else if (p.bn == 16) HCH_GEMM_CASE(128, 16, 32, 4, true);
-        else if (p.bn == 32) HCH_GEMM_CASE(128, 32, 32, 4, true);
-        else HCH_GEMM_CASE(128, 64, 32, 4, true);
+        if (p.bm == 64) HCH_GEMM_CASE(64, 64, 32, 2, true, false);
+        else if (p.bn == 16) HCH_GEMM_CASE(128, 16, 32, 4, true, false);
+        else if (p.bn == 32) HCH_GEMM_CASE(128, 32, 32, 4, true, false);
+        else HCH_GEMM_CASE(128, 64, 32, 4, true, false);
     } else {
         // odd channel counts / unaligned operands: one generic shape is enough
-        if (p.bn == 16) HCH_GEMM_CASE(128, 16, 32, 4, false);
-        else if (p.bn == 32) HCH_GEMM_CASE(128, 32, 32, 4, false);
-        else HCH_GEMM_CASE(128, 64, 32, 4, false);
+        if (p.bn == 16) HCH_GEMM_CASE(128, 16, 32, 4, false, false);
+        else if (p.bn == 32) HCH_GEMM_CASE(128, 32, 32, 4, false, false);
+        else HCH_GEMM_CASE(128, 64, 32, 4, false, false);
     }
 #undef HCH_GEMM_CASE
     HCH_LAUNCH_CHECK("gemm_f32_kernel");
@@ -623,11 +641,12 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
 template <int AMODE, bool B_KC>
 static hch_status launch_gemm(hch_dtype dtype, const GemmPlan &p, const void *A, const void *B, float *C,
                               const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
-                              int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s)
+                              int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s,
+                              int c_planes = 0)
 {
     if (dtype == HCH_BF16)
-        return launch_gemm_t<uint16_t, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s);
-    return launch_gemm_t<float, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s);
+        return launch_gemm_t<uint16_t, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes);
+    return launch_gemm_t<float, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes);
 }
 
 // Register-direct gathered product (conv_direct_kernel): shape-only part of the plan, shared by
@@ -893,10 +912,16 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
     // dcol[N x Kc] = dY[N x c_out] . W^T   (W is [Kc x c_out]: its rows are B's columns)
     const GemmPlan p = plan_rows(n, Kc, c_out, false);
     const double bytes = es * ((double)n * c_out + (double)Kc * c_out) + 4.0 * (double)n * Kc;
+    // with few input channels dcol is stored tap-major ([27][n][c_in]) between the two kernels:
+    // the gather then reads, tap by tap, 16- or 32-byte pieces of nearly consecutive rows that
+    // lie next to each other, instead of one such piece out of every 27*c_in-float row.  (With
+    // 16 channels or more a piece fills its own memory sectors and the row-major store of the
+    // product is the cheaper one: measured.)
+    const bool planes = c_in % 4 == 0 && c_in <= 8 && aligned16(dX);
     st = launch_gemm<hch::A_ROWS, true>(dtype, p, dY, W, dcol, nullptr,
-                                        (int)n, Kc, c_out, c_out, c_out, Kc, 0, bytes, s);
+                                        (int)n, Kc, c_out, c_out, c_out, Kc, 0, bytes, s, planes ? c_in : 0);
     if (st != HCH_OK) return st;
-    return do_col2hash(*L, dcol, c_in, dX, s);
+    return do_col2hash(*L, dcol, c_in, dX, planes, s);
 }
 
 extern "C" hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t level, hch_dtype dtype,

@@ -264,10 +264,10 @@ __global__ __launch_bounds__(256) void hash2col_kernel(
 // (voxel, VEC-float unit) pairs.  The sources of neighbouring destinations share cache lines
 // of dcol, hence the XCD-contiguous tile order.
 // ---------------------------------------------------------------------------------------
-template <int VEC>
+template <int VEC, bool PLANES>
 __global__ __launch_bounds__(256) void col2hash_kernel(
     const float *__restrict__ dcol, const int32_t *__restrict__ nbr, float *__restrict__ dX,
-    int64_t n, int c, int tv, unsigned n_tiles)
+    int64_t n, int c, int tv, unsigned n_tiles)   // PLANES: dcol is [27][n][c] instead of [n][27*c]
 {
     __shared__ int32_t idx[256 * 27];
     const unsigned tile = xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
@@ -288,7 +288,7 @@ __global__ __launch_bounds__(256) void col2hash_kernel(
 #pragma unroll 9
         for (int k = 0; k < 27; ++k) {
             const int32_t i = nb[26 - k];
-            const float *s = i >= 0 ? dcol + ((int64_t)i * 27 + k) * c + u * VEC : zsrc;
+            const float *s = i >= 0 ? dcol + (PLANES ? (int64_t)k * n + i : (int64_t)i * 27 + k) * c + u * VEC : zsrc;
             if constexpr (VEC == 4) {
                 const f32x4 v = *reinterpret_cast<const f32x4 *>(s);
 #pragma unroll
@@ -359,11 +359,11 @@ template <> struct FVec<4> { typedef float type __attribute__((ext_vector_type(4
 template <int N> __device__ __forceinline__ float vget(const typename FVec<N>::type &v, int i) { return v[i]; }
 template <> __device__ __forceinline__ float vget<1>(const float &v, int) { return v; }
 
-template <typename TIN, int BM, int BN, int BK, int WM, int AMODE, bool B_KC, bool VEC>
+template <typename TIN, int BM, int BN, int BK, int WM, int AMODE, bool B_KC, bool VEC, bool C_PLANES>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(
     const TIN *__restrict__ A, const TIN *__restrict__ B, float *__restrict__ C,
     const int32_t *__restrict__ nbr, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
-    int k_per_split, int64_t c_split_stride, int c_vec_ok, unsigned m_tiles)
+    int k_per_split, int64_t c_split_stride, int c_vec_ok, unsigned m_tiles, int c_planes)
 {
     constexpr int WN = 4 / WM;
     constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
@@ -675,6 +675,16 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     // D layout of v_mfma_f32_16x16x4_f32: register e of lane l holds D[4*(l/16) + e][l%16].
     // Lane li fed columns li*NT + nt of the wave's stretch to tile nt, so for one row it holds NT
     // neighbouring columns.  Rows: tile mt covers mt*16 + r (row-major A) or r*MT + mt (k-major A).
+    // C_PLANES: the output is stored plane by plane, C[j / c_planes][i][j % c_planes] (a
+    // lane's NT <= 4 columns start at a multiple of NT and c_planes is a multiple of 4, so they
+    // share a plane); else row-major with leading dimension ldc
+    const int gj = n0 + wn * WTN + li * NT;
+    int64_t row_stride = ldc, col_off = gj;
+    if constexpr (C_PLANES) {
+        const int pl = gj / c_planes;
+        row_stride = c_planes;
+        col_off = (int64_t)pl * M * c_planes + (gj - pl * c_planes);
+    }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -682,8 +692,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
             const int r = 4 * lk + e;
             const int gi = m0 + wm * WTM + (A_K_FAST ? mt * 16 + r : r * MT + mt);
             if (gi >= M) continue;
-            const int gj = n0 + wn * WTN + li * NT;
-            float *dst = C + (int64_t)gi * ldc + gj;
+            float *dst = C + (int64_t)gi * row_stride + col_off;
             if (NT == 4 && c_vec_ok && gj + 4 <= N) {
                 *reinterpret_cast<f32x4 *>(dst) = f32x4{acc[mt][0][e], acc[mt][1 % NT][e], acc[mt][2 % NT][e], acc[mt][3 % NT][e]};
             } else if (NT == 2 && c_vec_ok && gj + 2 <= N) {
