@@ -116,6 +116,23 @@ hch_status hch_build_levels(const int32_t *coords_xyz, const int64_t *model_offs
                             void *stream, hch_levels **out);
 
 /*
+ * The same object with the tables CONSTRUCTED ON THE DEVICE (Section 5.2 and the conclusion name
+ * GPU construction as future work).  Host work: argument checks and the occupancy of the coarser
+ * levels; then one set of launches builds every (level, model) pair: buckets of positions sharing
+ * p mod r are placed largest first, all buckets of one size in parallel, each claiming its slots
+ * with compare-and-swap and backing off to the next candidate offset on a conflict; pairs that
+ * fail are repeated with the next offset-table side.  Sizes (m, first r, growth of r), table
+ * formats and everything computed through the tables (neighbour and child lists, every
+ * convolution and pooling result) are the same as with hch_build_levels; the tables themselves
+ * are valid but differ from the host-built ones and from run to run (which of two racing buckets
+ * gets a slot depends on timing), and `attempts` / r may differ.  Same arguments, ownership and
+ * errors as hch_build_levels; BLOCKS.
+ */
+hch_status hch_build_levels_device(const int32_t *coords_xyz, const int64_t *model_offsets,
+                                   int32_t batch, int32_t resolution, int32_t n_levels,
+                                   void *stream, hch_levels **out);
+
+/*
  * The host half of hch_build_levels only: occupancy of every level, PSH construction and the
  * super tables, kept in host memory.  Touches no GPU.  The object serves hch_level_info (all
  * DEVICE pointers are NULL) and hch_free_levels; every other call rejects it with HCH_EINVAL.

@@ -12,8 +12,8 @@ __all__ = [
     "HCH_WS_FWD", "HCH_WS_BWD_DATA", "HCH_WS_BWD_WEIGHT", "HCH_WS_MIN",
     "HCH_ALGO_COLUMNS", "HCH_ALGO_FUSED",
     "library_path", "load_library", "exported_symbols",
-    "hch_build_levels", "hch_build_tables_host", "hch_build_neighbours", "hch_build_neighbours_range",
-    "hch_hash2col", "hch_col2hash", "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data",
+    "hch_build_levels", "hch_build_levels_device", "hch_build_tables_host", "hch_build_neighbours",
+    "hch_build_neighbours_range", "hch_hash2col", "hch_col2hash", "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data",
     "hch_conv_bwd_weight", "hch_pool_fwd", "hch_pool_bwd", "hch_relu_fwd", "hch_relu_bwd", "hch_relu_pool_fwd",
     "hch_pool_relu_bwd", "hch_deconv_fwd", "hch_deconv_bwd_data", "hch_deconv_bwd_weight",
     "hch_unpool_fwd", "hch_unpool_bwd", "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
@@ -29,7 +29,7 @@ _LIBPATH = os.path.join(_HERE, "libhch.so")
 
 # every symbol include/hch.h declares
 exported_symbols = [
-    "hch_last_error", "hch_build_levels", "hch_build_tables_host", "hch_free_levels",
+    "hch_last_error", "hch_build_levels", "hch_build_levels_device", "hch_build_tables_host", "hch_free_levels",
     "hch_num_levels", "hch_level_info", "hch_build_neighbours", "hch_build_neighbours_range", "hch_hash2col",
     "hch_col2hash",
     "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data", "hch_conv_bwd_weight",
@@ -81,6 +81,7 @@ def load_library():
     vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
     L.hch_last_error.restype = C.c_char_p
     L.hch_build_levels.argtypes = [vp, vp, i32, i32, i32, vp, C.POINTER(vp)]
+    L.hch_build_levels_device.argtypes = [vp, vp, i32, i32, i32, vp, C.POINTER(vp)]
     L.hch_build_tables_host.argtypes = [vp, vp, i32, i32, i32, C.POINTER(vp)]
     L.hch_free_levels.argtypes = [vp]
     L.hch_free_levels.restype = None
@@ -281,6 +282,15 @@ def hch_build_levels(coords, model_offsets, resolution, n_levels, stream=None):
     _check(load_library().hch_build_levels(coords.ctypes.data, offs.ctypes.data, offs.size - 1,
                                            int(resolution), int(n_levels), _stream(stream),
                                            C.byref(h)))
+    return Levels(h)
+
+
+def hch_build_levels_device(coords, model_offsets, resolution, n_levels, stream=None):
+    coords, offs = _host_inputs(coords, model_offsets)
+    h = C.c_void_p()
+    _check(load_library().hch_build_levels_device(coords.ctypes.data, offs.ctypes.data, offs.size - 1,
+                                                  int(resolution), int(n_levels), _stream(stream),
+                                                  C.byref(h)))
     return Levels(h)
 
 

@@ -14,6 +14,7 @@
 
 #include "kernels.hip.hpp"
 #include "direct.hip.hpp"
+#include "psh_device.hip.hpp"
 #include "profile.hpp"
 #include "psh_build.hpp"
 
@@ -178,9 +179,203 @@ extern "C" hch_status hch_build_neighbours_range(hch_levels *levels, int32_t fir
     return launch_index_lists(levels, first, first + count, (hipStream_t)stream);
 }
 
+// ---- PSH construction on the device (psh_device.hip.hpp) ----
+
+namespace {
+struct DeviceBlocks {            // device allocations that live until the end of the build call
+    std::vector<void *> ptrs;
+    ~DeviceBlocks() { for (void *p : ptrs) if (p) (void)hipFree(p); }
+    hch_status get(void **out, size_t bytes, int fill, hipStream_t s)
+    {
+        *out = nullptr;
+        hipError_t e = hipMalloc(out, bytes ? bytes : 16);
+        if (e != hipSuccess) { *out = nullptr; return fail(HCH_ENOMEM, std::string("hipMalloc: ") + hipGetErrorString(e)); }
+        ptrs.push_back(*out);
+        if (fill >= 0 && bytes) HCH_HIP(hipMemsetAsync(*out, fill, bytes, s));
+        return HCH_OK;
+    }
+};
+struct PairWork {
+    int l, v;
+    int32_t n, m, r, attempts;
+    const uint32_t *phi;         // offset words of the successful attempt (device)
+    bool done;
+};
+}  // namespace
+
+// Fills, for every level: mbar, rbar, attempts, M, R, m_total, r_total, the device tables dH, dT,
+// dV, dPhi, dslot3, dphi4, dcoords, dmeta and the host copies H, T, Phi, V.  Levels must have
+// ubar, b, coords, N, n_total.
+static hch_status device_construct(hch_levels *hl, hipStream_t s)
+{
+    const int n_levels = (int)hl->lv.size();
+    const int batch = hl->lv[0].b;
+    DeviceBlocks tmp;
+    std::vector<PairWork> work;
+    hch_status st;
+    for (int l = 0; l < n_levels; ++l) {
+        Level &L = hl->lv[l];
+        L.mbar.assign((size_t)batch, 0); L.rbar.assign((size_t)batch, 0); L.attempts.assign((size_t)batch, 0);
+        L.M.assign((size_t)batch + 1, 0); L.R.assign((size_t)batch + 1, 0);
+        for (int v = 0; v < batch; ++v) {
+            const int64_t n = L.N[v + 1] - L.N[v];
+            const int m = hch::hash_side(n);
+            if (m > 256) return fail(HCH_EUNSUPPORTED, "hch_build_levels_device: a model needs a hash table side above 256");
+            L.mbar[v] = m;
+            L.M[v + 1] = L.M[v] + (int64_t)m * m * m;
+            work.push_back(PairWork{l, v, (int32_t)n, m, hch::offset_side_first(n, m), 0, nullptr, false});
+        }
+        L.m_total = L.M[batch];
+        if (L.m_total >= ((int64_t)1 << 31)) return fail(HCH_EUNSUPPORTED, "hch_build_levels_device: super table exceeds 32-bit indexing");
+        HCH_HIP(hipMalloc((void **)&L.dH, (size_t)L.m_total * 4));
+        HCH_HIP(hipMalloc((void **)&L.dT, (size_t)L.m_total * 6));
+        HCH_HIP(hipMalloc((void **)&L.dV, (size_t)L.m_total * 4));
+        HCH_HIP(hipMemsetAsync(L.dH, 0xFF, (size_t)L.m_total * 4, s));     // -1 = free slot
+        HCH_HIP(hipMemsetAsync(L.dT, 0xFF, (size_t)L.m_total * 6, s));     // 0xFFFF = no position
+        if ((st = upload((void **)&L.dcoords, L.coords.data(), L.coords.size() * 4, s)) != HCH_OK) return st;
+    }
+    const int n_pairs = (int)work.size();
+    int32_t *d_fail = nullptr;
+    if ((st = tmp.get((void **)&d_fail, (size_t)n_pairs * 4, -1, s)) != HCH_OK) return st;
+    std::vector<int32_t> h_fail((size_t)n_pairs);
+
+    std::vector<int> active((size_t)n_pairs);
+    for (int i = 0; i < n_pairs; ++i) active[i] = i;
+    for (int round = 0; !active.empty(); ++round) {
+        if (round >= 24) return fail(HCH_EBUILD, "hch_build_levels_device: perfect hash construction failed");
+        const int na = (int)active.size();
+        std::vector<hch::PairDesc> desc((size_t)na);
+        int64_t cells = 0, vox = 0, slots = 0;
+        int32_t max_n = 0, max_r3 = 0, max_m3 = 0;
+        for (int a = 0; a < na; ++a) {
+            PairWork &w = work[active[a]];
+            Level &L = hl->lv[w.l];
+            if (w.r > 1024 || w.r > 2 * L.ubar + 1)   // beyond one cell per grid position nothing can improve
+                return fail(HCH_EBUILD, "hch_build_levels_device: perfect hash construction failed");
+            const int32_t r3 = w.r * w.r * w.r, m3 = w.m * w.m * w.m;
+            desc[a] = hch::PairDesc{L.dcoords + 3 * L.N[w.v], L.dH + L.M[w.v], L.dT + 3 * L.M[w.v], w.n, w.m, w.r,
+                                    (int32_t)cells, (int32_t)vox, (int32_t)slots, active[a]};
+            cells += r3; vox += w.n; slots += m3;
+            max_n = std::max(max_n, w.n); max_r3 = std::max(max_r3, r3); max_m3 = std::max(max_m3, m3);
+            ++w.attempts;
+        }
+        if (cells >= ((int64_t)1 << 31) / hch::PSH_CLASSES || vox >= ((int64_t)1 << 31) || slots >= ((int64_t)1 << 31))
+            return fail(HCH_EUNSUPPORTED, "hch_build_levels_device: offset tables exceed 32-bit indexing");
+        hch::PairDesc *d_desc = nullptr;
+        int32_t *d_cnt = nullptr, *d_first = nullptr, *d_fill = nullptr, *d_bucket = nullptr, *d_members = nullptr;
+        int32_t *d_counters = nullptr, *d_free = nullptr;
+        uint32_t *d_phi = nullptr, *d_res = nullptr;
+        int2 *d_cells = nullptr;
+        if ((st = tmp.get((void **)&d_desc, desc.size() * sizeof(hch::PairDesc), -1, s)) != HCH_OK) return st;
+        HCH_HIP(hipMemcpyAsync(d_desc, desc.data(), desc.size() * sizeof(hch::PairDesc), hipMemcpyHostToDevice, s));
+        if ((st = tmp.get((void **)&d_cnt, (size_t)cells * 4, 0, s)) != HCH_OK) return st;
+        if ((st = tmp.get((void **)&d_first, (size_t)cells * 4, -1, s)) != HCH_OK) return st;
+        if ((st = tmp.get((void **)&d_fill, (size_t)cells * 4, 0, s)) != HCH_OK) return st;
+        if ((st = tmp.get((void **)&d_phi, (size_t)cells * 4, 0, s)) != HCH_OK) return st;
+        if ((st = tmp.get((void **)&d_bucket, (size_t)vox * 4, -1, s)) != HCH_OK) return st;
+        if ((st = tmp.get((void **)&d_members, (size_t)vox * 4, -1, s)) != HCH_OK) return st;
+        if ((st = tmp.get((void **)&d_res, (size_t)vox * 4, -1, s)) != HCH_OK) return st;
+        if ((st = tmp.get((void **)&d_free, (size_t)slots * 4, -1, s)) != HCH_OK) return st;
+        if ((st = tmp.get((void **)&d_cells, (size_t)cells * hch::PSH_CLASSES * sizeof(int2), -1, s)) != HCH_OK) return st;
+        // counters: [0, CLASSES) buckets per class, then per active pair: free slots, singles placed
+        const size_t n_counters = (size_t)hch::PSH_CLASSES + 2 * (size_t)na;
+        if ((st = tmp.get((void **)&d_counters, n_counters * 4, 0, s)) != HCH_OK) return st;
+        int32_t *d_class_count = d_counters, *d_nfree = d_counters + hch::PSH_CLASSES, *d_rank = d_nfree + na;
+        HCH_HIP(hipMemsetAsync(d_fail, 0, (size_t)n_pairs * 4, s));
+
+        const dim3 gv((unsigned)((max_n + 255) / 256), (unsigned)na), gc((unsigned)((max_r3 + 255) / 256), (unsigned)na);
+        const dim3 gs((unsigned)((max_m3 + 255) / 256), (unsigned)na);
+        hipLaunchKernelGGL(hch::psh_count_kernel, gv, dim3(256), 0, s, d_desc, d_cnt, d_bucket);
+        hipLaunchKernelGGL(hch::psh_scan_kernel, dim3(1), dim3(1024), 0, s, d_cnt, d_first, (int)cells);
+        hipLaunchKernelGGL(hch::psh_fill_kernel, gv, dim3(256), 0, s, d_desc, d_bucket, d_first, d_fill, d_members, d_res);
+        hipLaunchKernelGGL(hch::psh_classify_kernel, gc, dim3(256), 0, s, d_desc, d_cnt, d_class_count, d_cells, cells);
+        HCH_LAUNCH_CHECK("psh construction");
+        int32_t class_count[hch::PSH_CLASSES];
+        HCH_HIP(hipMemcpyAsync(class_count, d_class_count, sizeof class_count, hipMemcpyDeviceToHost, s));
+        HCH_HIP(hipStreamSynchronize(s));
+        // largest buckets first: all of 9 voxels and more in one launch, then one size per launch
+        for (int k = hch::PSH_CLASSES - 1; k >= 2; --k) {
+            if (class_count[k] <= 0) continue;
+            HCH_HIP(hipMemsetAsync(d_nfree, 0, (size_t)na * 4, s));
+            hipLaunchKernelGGL(hch::psh_free_list_kernel, gs, dim3(256), 0, s, d_desc, d_nfree, d_free);
+            hipLaunchKernelGGL(hch::psh_place_kernel, dim3((unsigned)((class_count[k] + 3) / 4)), dim3(256), 0, s, d_desc,
+                               d_cells + (size_t)k * cells, class_count[k], d_cnt, d_first, d_members, d_res, d_nfree,
+                               d_free, d_phi, d_fail);
+        }
+        HCH_HIP(hipMemsetAsync(d_nfree, 0, (size_t)na * 4, s));
+        hipLaunchKernelGGL(hch::psh_free_list_kernel, gs, dim3(256), 0, s, d_desc, d_nfree, d_free);
+        hipLaunchKernelGGL(hch::psh_place_single_kernel, gc, dim3(256), 0, s, d_desc, d_cnt, d_first, d_members, d_res,
+                           d_nfree, d_free, d_rank, d_phi, d_fail);
+        HCH_LAUNCH_CHECK("psh construction");
+        HCH_HIP(hipMemcpyAsync(h_fail.data(), d_fail, (size_t)n_pairs * 4, hipMemcpyDeviceToHost, s));
+        HCH_HIP(hipStreamSynchronize(s));
+
+        std::vector<int> again;
+        for (int a = 0; a < na; ++a) {
+            PairWork &w = work[active[a]];
+            Level &L = hl->lv[w.l];
+            if (!h_fail[active[a]]) {
+                w.done = true;
+                w.phi = d_phi + desc[a].cell_base;
+                continue;
+            }
+            const size_t m3 = (size_t)w.m * w.m * w.m;
+            HCH_HIP(hipMemsetAsync(L.dH + L.M[w.v], 0xFF, m3 * 4, s));
+            HCH_HIP(hipMemsetAsync(L.dT + 3 * L.M[w.v], 0xFF, m3 * 6, s));
+            w.r = hch::offset_side_next(w.r, w.m);
+            again.push_back(active[a]);
+        }
+        active.swap(again);
+    }
+
+    // super tables of every level from the pairs' results
+    for (int l = 0; l < n_levels; ++l) {
+        Level &L = hl->lv[l];
+        std::vector<hch::PackDesc> pd((size_t)batch);
+        int32_t widest = 0;
+        for (int v = 0; v < batch; ++v) {
+            const PairWork &w = work[(size_t)l * batch + v];
+            L.rbar[v] = w.r; L.attempts[v] = w.attempts;
+            L.R[v + 1] = L.R[v] + (int64_t)w.r * w.r * w.r;
+        }
+        L.r_total = L.R[batch];
+        if (L.r_total >= ((int64_t)1 << 31) / 3) return fail(HCH_EUNSUPPORTED, "hch_build_levels_device: super table exceeds 32-bit indexing");
+        for (int v = 0; v < batch; ++v) {
+            const PairWork &w = work[(size_t)l * batch + v];
+            pd[v] = hch::PackDesc{w.phi, w.m * w.m * w.m, w.r * w.r * w.r, (int32_t)L.M[v], (int32_t)L.R[v]};
+            widest = std::max(widest, std::max(pd[v].m3, pd[v].r3));
+        }
+        hch::PackDesc *d_pd = nullptr;
+        if ((st = tmp.get((void **)&d_pd, pd.size() * sizeof(hch::PackDesc), -1, s)) != HCH_OK) return st;
+        HCH_HIP(hipMemcpyAsync(d_pd, pd.data(), pd.size() * sizeof(hch::PackDesc), hipMemcpyHostToDevice, s));
+        HCH_HIP(hipMalloc((void **)&L.dPhi, std::max<size_t>(16, (size_t)L.r_total * 3)));
+        HCH_HIP(hipMalloc((void **)&L.dphi4, std::max<size_t>(16, (size_t)L.r_total * 4)));
+        HCH_HIP(hipMalloc((void **)&L.dslot3, (size_t)L.m_total * 12));
+        hipLaunchKernelGGL(hch::psh_pack_kernel, dim3((unsigned)((widest + 255) / 256), (unsigned)batch), dim3(256), 0, s,
+                           d_pd, L.dH, L.dT, L.dslot3, L.dV, L.dphi4, L.dPhi);
+        HCH_LAUNCH_CHECK("psh_pack_kernel");
+        std::vector<int32_t> meta;
+        meta.insert(meta.end(), L.mbar.begin(), L.mbar.end());
+        meta.insert(meta.end(), L.rbar.begin(), L.rbar.end());
+        for (int64_t x : L.M) meta.push_back((int32_t)x);
+        for (int64_t x : L.R) meta.push_back((int32_t)x);
+        for (int64_t x : L.N) meta.push_back((int32_t)x);
+        if ((st = upload((void **)&L.dmeta, meta.data(), meta.size() * 4, s)) != HCH_OK) return st;
+        // host copies for hch_level_info
+        L.H.resize((size_t)L.m_total); L.V.resize((size_t)L.m_total);
+        L.T.resize((size_t)L.m_total * 3); L.Phi.resize((size_t)L.r_total * 3);
+        HCH_HIP(hipMemcpyAsync(L.H.data(), L.dH, L.H.size() * 4, hipMemcpyDeviceToHost, s));
+        HCH_HIP(hipMemcpyAsync(L.V.data(), L.dV, L.V.size() * 4, hipMemcpyDeviceToHost, s));
+        HCH_HIP(hipMemcpyAsync(L.T.data(), L.dT, L.T.size() * 2, hipMemcpyDeviceToHost, s));
+        if (L.r_total) HCH_HIP(hipMemcpyAsync(L.Phi.data(), L.dPhi, L.Phi.size(), hipMemcpyDeviceToHost, s));
+        HCH_HIP(hipStreamSynchronize(s));     // `meta` and `pd` die here
+    }
+    return HCH_OK;
+}
+
 static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_offsets,
                              int32_t batch, int32_t resolution, int32_t n_levels,
-                             void *stream, bool with_device, hch_levels **out)
+                             void *stream, bool with_device, bool device_tables, hch_levels **out)
 {
     if (out) *out = nullptr;
     if (!coords_xyz || !model_offsets || !out) return fail(HCH_EINVAL, "hch_build_levels: null pointer");
@@ -199,20 +394,34 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
     for (int64_t i = 0; i < 3 * n_total; ++i)
         if (coords_xyz[i] < 0 || coords_xyz[i] >= resolution)
             return fail(HCH_EINVAL, "hch_build_levels: coordinate outside [0, resolution)");
-    // duplicates inside a model
+    // duplicates inside a model (models in parallel on host threads)
     {
-        std::vector<int64_t> lin;
-        for (int v = 0; v < batch; ++v) {
-            const int64_t a = model_offsets[v], n = model_offsets[v + 1] - a;
-            lin.resize((size_t)n);
-            for (int64_t i = 0; i < n; ++i) {
-                const int32_t *p = coords_xyz + 3 * (a + i);
-                lin[i] = ((int64_t)p[0] * resolution + p[1]) * resolution + p[2];
+        std::atomic<int> next_model(0), dup(0);
+        auto check = [&]() {
+            std::vector<int64_t> lin;
+            for (;;) {
+                const int v = next_model.fetch_add(1);
+                if (v >= batch) break;
+                const int64_t a = model_offsets[v], n = model_offsets[v + 1] - a;
+                lin.resize((size_t)n);
+                for (int64_t i = 0; i < n; ++i) {
+                    const int32_t *p = coords_xyz + 3 * (a + i);
+                    lin[i] = ((int64_t)p[0] * resolution + p[1]) * resolution + p[2];
+                }
+                std::sort(lin.begin(), lin.end());
+                if (std::adjacent_find(lin.begin(), lin.end()) != lin.end()) dup = 1;
             }
-            std::sort(lin.begin(), lin.end());
-            if (std::adjacent_find(lin.begin(), lin.end()) != lin.end())
-                return fail(HCH_EINVAL, "hch_build_levels: duplicate voxel inside a model");
+        };
+        try {
+            const unsigned nthr = std::max(1u, std::min({std::thread::hardware_concurrency(), 16u, (unsigned)batch}));
+            std::vector<std::thread> pool;
+            for (unsigned i = 1; i < nthr; ++i) pool.emplace_back(check);
+            check();
+            for (auto &th : pool) th.join();
+        } catch (const std::bad_alloc &) {
+            return fail(HCH_ENOMEM, "hch_build_levels: out of host memory");
         }
+        if (dup) return fail(HCH_EINVAL, "hch_build_levels: duplicate voxel inside a model");
     }
 
     hch_levels *hl = new (std::nothrow) hch_levels;
@@ -233,11 +442,25 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
                 for (int v = 0; v <= batch; ++v) L.N[v] = model_offsets[v];
             } else {
                 const Level &Lf = hl->lv[l - 1];
-                std::vector<int32_t> tmp;
+                std::vector<std::vector<int32_t>> per_model((size_t)batch);
+                std::atomic<int> next_model(0);
+                auto coarsen = [&]() {
+                    for (;;) {
+                        const int v = next_model.fetch_add(1);
+                        if (v >= batch) break;
+                        hch::coarsen_model(Lf.coords.data() + 3 * Lf.N[v], Lf.N[v + 1] - Lf.N[v], Lf.ubar, per_model[v]);
+                    }
+                };
+                {
+                    const unsigned nthr = std::max(1u, std::min({std::thread::hardware_concurrency(), 16u, (unsigned)batch}));
+                    std::vector<std::thread> pool;
+                    for (unsigned i = 1; i < nthr; ++i) pool.emplace_back(coarsen);
+                    coarsen();
+                    for (auto &th : pool) th.join();
+                }
                 for (int v = 0; v < batch; ++v) {
-                    hch::coarsen_model(Lf.coords.data() + 3 * Lf.N[v], Lf.N[v + 1] - Lf.N[v], Lf.ubar, tmp);
-                    L.coords.insert(L.coords.end(), tmp.begin(), tmp.end());
-                    L.N[v + 1] = L.N[v] + (int64_t)tmp.size() / 3;
+                    L.coords.insert(L.coords.end(), per_model[v].begin(), per_model[v].end());
+                    L.N[v + 1] = L.N[v] + (int64_t)per_model[v].size() / 3;
                 }
             }
             L.n_total = L.N[batch];
@@ -245,10 +468,14 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
             for (int v = 0; v < batch; ++v) L.max_n = std::max<int32_t>(L.max_n, (int32_t)(L.N[v + 1] - L.N[v]));
         }
 
+        if (device_tables) {
+            if (n_levels > hch::MAX_LEVELS) st = fail(HCH_EUNSUPPORTED, "hch_build_levels: too many levels");
+            if (st == HCH_OK) st = device_construct(hl, s);
+        }
         // ---- PSH construction of every (level, model), spread over host threads ----
         std::vector<std::vector<hch::ModelTables>> tabs((size_t)n_levels);
         for (auto &t : tabs) t.resize((size_t)batch);
-        const int n_tasks = n_levels * batch;
+        const int n_tasks = device_tables ? 0 : n_levels * batch;
         std::vector<int> result((size_t)n_tasks, 0);
         std::atomic<int> next(0);
         auto worker = [&]() {
@@ -264,7 +491,7 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
         {
             unsigned nthr = std::thread::hardware_concurrency();
             nthr = std::max(1u, std::min(nthr, 16u));
-            nthr = std::min<unsigned>(nthr, (unsigned)n_tasks);
+            nthr = std::min<unsigned>(nthr, (unsigned)std::max(1, n_tasks));
             std::vector<std::thread> pool;
             for (unsigned i = 1; i < nthr; ++i) pool.emplace_back(worker);
             worker();
@@ -280,6 +507,15 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
         // ---- super tables (Section 3.2) and upload ----
         for (int l = 0; l < n_levels && st == HCH_OK; ++l) {
             Level &L = hl->lv[l];
+            if (device_tables) {      // tables are already resident; only the index lists are missing
+                if (hipMalloc((void **)&L.dnbr, (size_t)L.n_total * 27 * 4) != hipSuccess) {
+                    L.dnbr = nullptr; st = fail(HCH_ENOMEM, "hipMalloc(nbr27) failed"); break;
+                }
+                if (l > 0 && hipMalloc((void **)&L.dchild, (size_t)L.n_total * 8 * 4) != hipSuccess) {
+                    L.dchild = nullptr; st = fail(HCH_ENOMEM, "hipMalloc(child8) failed"); break;
+                }
+                continue;
+            }
             L.mbar.resize((size_t)batch); L.rbar.resize((size_t)batch); L.attempts.resize((size_t)batch);
             L.M.assign((size_t)batch + 1, 0); L.R.assign((size_t)batch + 1, 0);
             for (int v = 0; v < batch; ++v) {
@@ -366,14 +602,24 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
             if (e != hipSuccess) st = fail(HCH_EHIP, std::string("hipStreamSynchronize: ") + hipGetErrorString(e));
         }
         // occupied-neighbour count of every level (used only for reporting algorithmic traffic)
-        for (int l = 0; l < n_levels && st == HCH_OK && with_device; ++l) {
-            Level &L = hl->lv[l];
-            std::vector<int32_t> nb((size_t)L.n_total * 27);
-            hipError_t e = hipMemcpy(nb.data(), L.dnbr, nb.size() * 4, hipMemcpyDeviceToHost);
-            if (e != hipSuccess) { st = fail(HCH_EHIP, std::string("hipMemcpy(nbr27): ") + hipGetErrorString(e)); break; }
-            int64_t cnt = 0;
-            for (int32_t x : nb) cnt += (x >= 0);
-            L.nbr_valid = cnt;
+        if (st == HCH_OK && with_device) {
+            unsigned long long *d_cnt = nullptr;
+            std::vector<unsigned long long> h_cnt((size_t)n_levels, 0);
+            if (hipMalloc((void **)&d_cnt, (size_t)n_levels * 8) != hipSuccess) st = fail(HCH_ENOMEM, "hipMalloc failed");
+            if (st == HCH_OK) {
+                hipError_t e = hipMemsetAsync(d_cnt, 0, (size_t)n_levels * 8, s);
+                for (int l = 0; l < n_levels && e == hipSuccess; ++l) {
+                    const int64_t items = hl->lv[l].n_total * 27;
+                    const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(4096, (items + 255) / 256));
+                    hipLaunchKernelGGL(hch::count_valid_kernel, dim3(grid), dim3(256), 0, s, hl->lv[l].dnbr, items, d_cnt + l);
+                    e = hipGetLastError();
+                }
+                if (e == hipSuccess) e = hipMemcpyAsync(h_cnt.data(), d_cnt, (size_t)n_levels * 8, hipMemcpyDeviceToHost, s);
+                if (e == hipSuccess) e = hipStreamSynchronize(s);
+                if (e != hipSuccess) st = fail(HCH_EHIP, std::string("neighbour count: ") + hipGetErrorString(e));
+                for (int l = 0; l < n_levels; ++l) hl->lv[l].nbr_valid = (int64_t)h_cnt[l];
+            }
+            if (d_cnt) (void)hipFree(d_cnt);
         }
     } catch (const std::bad_alloc &) {
         st = fail(HCH_ENOMEM, "hch_build_levels: out of host memory");
@@ -388,14 +634,21 @@ extern "C" hch_status hch_build_levels(const int32_t *coords_xyz, const int64_t 
                                        int32_t batch, int32_t resolution, int32_t n_levels,
                                        void *stream, hch_levels **out)
 {
-    return build_impl(coords_xyz, model_offsets, batch, resolution, n_levels, stream, true, out);
+    return build_impl(coords_xyz, model_offsets, batch, resolution, n_levels, stream, true, false, out);
+}
+
+extern "C" hch_status hch_build_levels_device(const int32_t *coords_xyz, const int64_t *model_offsets,
+                                              int32_t batch, int32_t resolution, int32_t n_levels,
+                                              void *stream, hch_levels **out)
+{
+    return build_impl(coords_xyz, model_offsets, batch, resolution, n_levels, stream, true, true, out);
 }
 
 extern "C" hch_status hch_build_tables_host(const int32_t *coords_xyz, const int64_t *model_offsets,
                                             int32_t batch, int32_t resolution, int32_t n_levels,
                                             hch_levels **out)
 {
-    return build_impl(coords_xyz, model_offsets, batch, resolution, n_levels, nullptr, false, out);
+    return build_impl(coords_xyz, model_offsets, batch, resolution, n_levels, nullptr, false, false, out);
 }
 
 extern "C" hch_status hch_level_info(const hch_levels *levels, int32_t level, hch_level_desc *out)

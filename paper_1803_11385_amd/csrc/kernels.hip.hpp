@@ -749,6 +749,18 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(
     }
 }
 
+// number of entries >= 0 in an index list (the occupied neighbours of a level: the nnz of the
+// traffic model); count must be zero before the launch
+__global__ __launch_bounds__(256) void count_valid_kernel(const int32_t *__restrict__ idx, int64_t n,
+                                                          unsigned long long *__restrict__ count)
+{
+    int local = 0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) local += idx[i] >= 0;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) local += __shfl_xor(local, d);
+    if ((threadIdx.x & 63) == 0 && local) atomicAdd(count, (unsigned long long)local);
+}
+
 // ---------------------------------------------------------------------------------------
 // 2x2x2 max-pooling through the child index rows.  VEC channels per thread (4 when the
 // channel count allows 16-byte accesses).

@@ -101,3 +101,37 @@ def test_full_size_encoder_step(oracle, full, algo, two_streams):
         dWl = enc.dW[l].cpu().numpy()
         close(dWl[tr[:, 2], tr[:, 1], tr[:, 0]], oracle.conv_bwd_weight_at(L, Xp, dYp, tr),
               f"conv bwd weight level {l}", rms_of=dWl)
+
+
+def test_full_size_device_built_tables(oracle, full):
+    """The same batch with the tables constructed on the device: every table is a perfect hash of
+    its model (Eq.1 sends every voxel to the slot that holds its index and tag, all other slots
+    are empty), and all lookups through them (neighbour and child lists) equal the oracle's."""
+    olv = full["olv"]
+    coords0 = olv[0].coords
+    dlv = hch.hch_build_levels_device(coords0, olv[0].N, 256, 6)
+    torch.cuda.synchronize()
+    for l, L in enumerate(olv):
+        info = dlv.info(l)
+        assert np.array_equal(info.mbar, L.mbar) and np.array_equal(info.M, L.M) and np.array_equal(info.N, L.N)
+        H, T, Phi = info.device_H(), info.device_T(), info.device_Phi()
+        R = np.asarray(info.R)
+        coords = info.device_coords()
+        assert np.array_equal(coords, L.coords)
+        for v in range(L.b):
+            n, m, r = int(L.N[v + 1] - L.N[v]), int(info.mbar[v]), int(info.rbar[v])
+            h = H[L.M[v]:L.M[v + 1]]
+            occ = h >= 0
+            assert int(occ.sum()) == n and np.all(h[~occ] == -1)
+            p = coords[L.N[v]:L.N[v + 1]].astype(np.int64)
+            ph = Phi[R[v]:R[v + 1]].astype(np.int64)
+            cell = ((p[:, 0] % r) * r + p[:, 1] % r) * r + p[:, 2] % r
+            s = (p % m + ph[cell]) % m
+            slot = (s[:, 0] * m + s[:, 1]) * m + s[:, 2]
+            assert np.array_equal(h[slot], np.arange(n))
+            assert np.array_equal(T[L.M[v]:L.M[v + 1]][slot].astype(np.int64), p)
+        nb = info.device_nbr27()
+        assert np.array_equal(nb, oracle.neighbours(L)), f"nbr27 level {l}"
+        assert info.nbr_valid == int((nb >= 0).sum())
+        if l > 0:
+            assert np.array_equal(info.device_child8(), oracle.children(olv[l - 1], L)), f"child8 level {l}"

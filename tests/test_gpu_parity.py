@@ -499,3 +499,82 @@ def test_unpool(oracle, case_batch64):
     dP = torch.full((lc.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
     hch.hch_unpool_bwd(case.glv, 0, dev(G), sw, dP, c)
     assert np.array_equal(dP.cpu().numpy(), oracle.unpool_max_bwd(oracle.to_paper_X(G), swo).T.astype(np.float32))
+
+
+# --------------------------------------------------------------------------------------
+# tables constructed on the device: valid, and every lookup through them is the same
+# --------------------------------------------------------------------------------------
+
+def _check_device_built(oracle, olv, dlv):
+    for l, L in enumerate(olv):
+        info = dlv.info(l)
+        assert info.n_total == L.Ntot
+        assert np.array_equal(info.mbar, L.mbar), "hash table sides are fixed by n (Section 5.2)"
+        assert np.array_equal(info.M, L.M) and np.array_equal(info.N, L.N)
+        H, T, Phi, V = info.device_H(), info.device_T(), info.device_Phi(), info.device_V()
+        assert np.array_equal(info.H_host(), H) and np.array_equal(info.T_host(), T)
+        assert np.array_equal(info.Phi_host(), Phi)
+        coords = info.device_coords()
+        assert np.array_equal(coords, L.coords)
+        R = np.asarray(info.R)
+        for v in range(L.b):
+            n = int(L.N[v + 1] - L.N[v]); m = int(info.mbar[v]); r = int(info.rbar[v])
+            assert int(R[v + 1] - R[v]) == r ** 3 and np.gcd(r, m) == 1
+            h = H[L.M[v]:L.M[v + 1]]
+            occ = h >= 0
+            # a perfect hash: every data index exactly once, the other slots empty
+            assert int(occ.sum()) == n and np.array_equal(np.sort(h[occ]), np.arange(n))
+            assert np.all(h[~occ] == -1)
+            t = T[L.M[v]:L.M[v + 1]]
+            assert np.array_equal(t[occ].astype(np.int64), coords[L.N[v]:L.N[v + 1]][h[occ]])
+            assert np.all(t[~occ] == 0xFFFF)
+            assert np.all(V[L.M[v]:L.M[v + 1]] == v)
+            ph = Phi[R[v]:R[v + 1]].astype(np.int64)
+            assert ph.max(initial=0) < m
+            # Eq.1 with these tables sends every voxel to the slot that holds it
+            p = coords[L.N[v]:L.N[v + 1]].astype(np.int64)
+            cell = ((p[:, 0] % r) * r + p[:, 1] % r) * r + p[:, 2] % r
+            s = (p % m + ph[cell]) % m
+            slot = (s[:, 0] * m + s[:, 1]) * m + s[:, 2]
+            assert np.array_equal(h[slot], np.arange(n))
+        # lookups: occupied positions found, empty ones null, for all 27 / 8 probes of every voxel
+        assert np.array_equal(info.device_nbr27(), oracle.neighbours(L)), f"nbr27 level {l}"
+        if l > 0:
+            assert np.array_equal(info.device_child8(), oracle.children(olv[l - 1], L)), f"child8 level {l}"
+
+
+@pytest.mark.parametrize("name", ["case_sphere", "case_batch64", "case_small"])
+def test_device_built_tables(request, oracle, name):
+    case = request.getfixturevalue(name)
+    dlv = hch.hch_build_levels_device(case.coords, case.offs, case.u, len(case.olv))
+    torch.cuda.synchronize()
+    _check_device_built(oracle, case.olv, dlv)
+    # a convolution through them gives the same bits as through the host-built tables
+    L = case.olv[0]
+    X = S.gaussian((L.Ntot, 8), 1.0, 71)
+    W = S.gaussian((27, 8, 16), 0.1, 72)
+    outs = []
+    for lv in (case.glv, dlv):
+        Y = torch.full((L.Ntot, 16), float("nan"), dtype=torch.float32, device="cuda")
+        ws = workspace(hch.hch_conv_workspace_bytes(lv, 0, 8, 16, hch.HCH_F32, hch.HCH_WS_FWD, hch.HCH_ALGO_FUSED))
+        hch.hch_conv_fwd(lv, 0, hch.HCH_F32, dev(X), dev(W), Y, 8, 16, ws, hch.HCH_ALGO_FUSED)
+        outs.append(Y)
+    assert torch.equal(outs[0], outs[1])
+
+
+def test_device_build_tiny_and_errors():
+    # one voxel per model, a full 2^3 block, and the argument checks of the host entry point
+    coords = np.array([[0, 0, 0], [3, 3, 3]] + [[x, y, z] for x in (0, 1) for y in (0, 1) for z in (0, 1)], np.int32)
+    offs = np.array([0, 1, 2, 10], np.int64)
+    dlv = hch.hch_build_levels_device(coords, offs, 4, 3)
+    hlv = hch.hch_build_levels(coords, offs, 4, 3)
+    torch.cuda.synchronize()
+    for l in range(3):
+        a, b = dlv.info(l), hlv.info(l)
+        assert np.array_equal(a.device_nbr27(), b.device_nbr27())
+        if l > 0:
+            assert np.array_equal(a.device_child8(), b.device_child8())
+    with pytest.raises(hch.HchError):
+        hch.hch_build_levels_device(np.array([[0, 0, 0], [0, 0, 0]], np.int32), np.array([0, 2], np.int64), 4, 1)
+    with pytest.raises(hch.HchError):
+        hch.hch_build_levels_device(np.array([[0, 0, 5]], np.int32), np.array([0, 1], np.int64), 4, 1)
