@@ -95,6 +95,9 @@ def main():
                     help="timed region with the weight gradients and the coarse index lists on a second "
                          "stream (faster; kernels then share the chip, so per-kernel times are not clean)")
     ap.add_argument("--no-overlap-pass", action="store_true", help="skip the extra two-stream pass")
+    ap.add_argument("--build-bench", action="store_true",
+                    help="time only the construction of the hash tables of the workload, on the host "
+                         "(hch_build_levels) and on the device (hch_build_levels_device), and print that")
     ap.add_argument("--algo", choices=["columns", "fused"], default="fused",
                     help="columns: hash2col -> GEMM -> col2hash through memory; fused: gathered GEMM operand")
     args = ap.parse_args()
@@ -113,9 +116,30 @@ def main():
     t0 = time.perf_counter()
     coords, offs, X0, W = make_inputs(4, b, u)
     t_gen = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    levels = hch.hch_build_levels(coords, offs, u, 6)
-    t_build = time.perf_counter() - t0
+    def timed_build(fn):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        lv = fn(coords, offs, u, 6)
+        torch.cuda.synchronize()
+        return lv, time.perf_counter() - t0
+
+    if args.build_bench:
+        res = {"host": [], "device": []}
+        for _ in range(max(1, args.warmup // 2) + max(1, args.steps // 4)):
+            for name, fn in (("host", hch.hch_build_levels), ("device", hch.hch_build_levels_device)):
+                lv, dt = timed_build(fn)
+                res[name].append(dt)
+                del lv
+        skip = max(1, args.warmup // 2)
+        print(json.dumps({"metric": "construction of the 6-level hash tables, index lists included", "unit": "ms",
+                          "host_ms": round(1e3 * float(np.median(res["host"][skip:])), 2),
+                          "device_ms": round(1e3 * float(np.median(res["device"][skip:])), 2),
+                          "calls_timed": len(res["host"]) - skip, "higher_is_better": False,
+                          "config": {"workload": f"{u}^3 grid, batch {b}, random-primitive surfaces"}}))
+        return
+    levels, t_build = timed_build(hch.hch_build_levels)
+    lv_dev, t_build_dev = timed_build(hch.hch_build_levels_device)
+    del lv_dev
     algo = hch.HCH_ALGO_FUSED if args.algo == "fused" else hch.HCH_ALGO_COLUMNS
     enc = Encoder(levels, CHANNELS, algo, two_streams=args.two_streams)
     enc.X[0].copy_(torch.from_numpy(X0))
@@ -214,7 +238,7 @@ def main():
         "config": {"workload": f"5-level encoder fwd+bwd, {u}^3 grid, batch {b}, random-primitive surfaces, "
                                f"channels 4-16-32-64-128-256, N per level = {enc.n}",
                    "algo": args.algo, "flop_count": "paper-method 3 * 2*27*c_in*c_out*N_l per level",
-                   "gflop_per_step": round(flops / 1e9, 3), "psh_build_s": round(t_build, 2),
+                   "gflop_per_step": round(flops / 1e9, 3), "psh_build_s": round(t_build, 3), "psh_build_device_s": round(t_build_dev, 3),
                    "shape_gen_s": round(t_gen, 2)},
         "roofline": roofline,
         "kernels_ms_first_step": {k: round(v[1]["ms"], 4) for k, v in first.items()},

@@ -96,6 +96,20 @@ __global__ __launch_bounds__(256) void psh_fill_kernel(const PairDesc *__restric
     residues[pos] = (uint32_t)(p[0] % m) | ((uint32_t)(p[1] % m) << 8) | ((uint32_t)(p[2] % m) << 16);
 }
 
+// position of this lane among the lanes of its wavefront for which `flag` is set, after a
+// counter has been advanced once for all of them (one atomic per wavefront instead of per lane)
+__device__ __forceinline__ int psh_wave_append(bool flag, int32_t *counter)
+{
+    const unsigned long long mask = __ballot(flag);
+    if (mask == 0) return 0;
+    const int lane = threadIdx.x & 63;
+    const int leader = __builtin_ctzll(mask);
+    int base = 0;
+    if (lane == leader) base = atomicAdd(counter, __builtin_popcountll(mask));
+    base = __shfl(base, leader);
+    return base + __builtin_popcountll(mask & ((1ull << lane) - 1ull));
+}
+
 // the buckets of 2 and more voxels, listed by class: entry = (active pair, bucket number)
 __global__ __launch_bounds__(256) void psh_classify_kernel(const PairDesc *__restrict__ pairs,
                                                            const int32_t *__restrict__ cnt,
@@ -104,12 +118,13 @@ __global__ __launch_bounds__(256) void psh_classify_kernel(const PairDesc *__res
 {
     const PairDesc P = pairs[blockIdx.y];
     const int g = blockIdx.x * 256 + threadIdx.x;
-    if (g >= P.r * P.r * P.r) return;
-    const int c = cnt[P.cell_base + g];
-    if (c < 2) return;
-    const int k = c < PSH_CLASSES - 1 ? c : PSH_CLASSES - 1;
-    const int pos = atomicAdd(&class_count[k], 1);
-    class_cells[k * class_stride + pos] = make_int2((int)blockIdx.y, g);
+    const int c = g < P.r * P.r * P.r ? cnt[P.cell_base + g] : 0;
+    const int mine = c < 2 ? 0 : (c < PSH_CLASSES - 1 ? c : PSH_CLASSES - 1);
+#pragma unroll
+    for (int k = 2; k < PSH_CLASSES; ++k) {           // no lane leaves before the last ballot
+        const int pos = psh_wave_append(mine == k, &class_count[k]);
+        if (mine == k) class_cells[k * class_stride + pos] = make_int2((int)blockIdx.y, g);
+    }
 }
 
 // the free slots of every table (any order)
@@ -118,9 +133,9 @@ __global__ __launch_bounds__(256) void psh_free_list_kernel(const PairDesc *__re
 {
     const PairDesc P = pairs[blockIdx.y];
     const int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= P.m * P.m * P.m) return;
-    if (P.H[e] != -1) return;
-    free_list[P.slot_base + atomicAdd(&n_free[blockIdx.y], 1)] = e;
+    const bool is_free = e < P.m * P.m * P.m && P.H[e] == -1;
+    const int pos = psh_wave_append(is_free, &n_free[blockIdx.y]);
+    if (is_free) free_list[P.slot_base + pos] = e;
 }
 
 __device__ __forceinline__ int32_t psh_peek(const int32_t *p)
