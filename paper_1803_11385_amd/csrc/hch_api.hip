@@ -702,20 +702,21 @@ static hch_status do_hash2col(const Level &L, hch_dtype dtype, const void *X, in
     // per voxel: 27 indices and its own feature row in (neighbour re-reads are cache hits),
     // 27 rows out (zeros included: the GEMM operand needs them)
     const double bytes = (double)rows * (108.0 + 28.0 * row_bytes);
-    const int tv = tile_voxels(rows, 8, 256);
+    const int tv = tile_voxels(rows, 8, 128);
+    const size_t lds = (size_t)tv * 27 * 4;
     const unsigned n_tiles = (unsigned)((rows + tv - 1) / tv);
     const unsigned grid = (n_tiles + hch::NUM_XCD - 1) / hch::NUM_XCD * hch::NUM_XCD;
     if (row_bytes % 16 == 0 && aligned16(X) && aligned16(col)) {
         hch::LaunchTimer lt(HCH_KERNEL_ID("hash2col_kernel<unsigned int __vector(4)>"), s, bytes, 0.0);
-        hipLaunchKernelGGL(hch::hash2col_kernel<hch::u32x4>, dim3(grid), dim3(256), 0, s,
+        hipLaunchKernelGGL(hch::hash2col_kernel<hch::u32x4>, dim3(grid), dim3(256), lds, s,
                            (const hch::u32x4 *)X, L.dnbr, (hch::u32x4 *)col, row_begin, rows, row_bytes / 16, tv, n_tiles);
     } else {
         hch::LaunchTimer lt(dtype == HCH_F32 ? HCH_KERNEL_ID("hash2col_kernel<float>") : HCH_KERNEL_ID("hash2col_kernel<unsigned short>"), s, bytes, 0.0);
         if (dtype == HCH_F32)
-            hipLaunchKernelGGL(hch::hash2col_kernel<float>, dim3(grid), dim3(256), 0, s,
+            hipLaunchKernelGGL(hch::hash2col_kernel<float>, dim3(grid), dim3(256), lds, s,
                                (const float *)X, L.dnbr, (float *)col, row_begin, rows, c_in, tv, n_tiles);
         else
-            hipLaunchKernelGGL(hch::hash2col_kernel<uint16_t>, dim3(grid), dim3(256), 0, s,
+            hipLaunchKernelGGL(hch::hash2col_kernel<uint16_t>, dim3(grid), dim3(256), lds, s,
                                (const uint16_t *)X, L.dnbr, (uint16_t *)col, row_begin, rows, c_in, tv, n_tiles);
     }
     HCH_LAUNCH_CHECK("hash2col");
@@ -749,17 +750,18 @@ static hch_status do_col2hash(const Level &L, const float *dcol, int c_in, float
                                : (vec ? HCH_KERNEL_ID("col2hash_kernel<4, false>") : HCH_KERNEL_ID("col2hash_kernel<1, false>")),
                         s, bytes, (double)L.nbr_valid * c_in);
     const int cu = vec ? c_in / 4 : c_in;
-    const int tv = std::max(4, std::min(256, 256 / cu));
+    const int tv = std::max(4, std::min(128, 256 / cu));
+    const size_t lds = (size_t)tv * 27 * 4;
     const unsigned n_tiles = (unsigned)((L.n_total + tv - 1) / tv);
     const unsigned grid = (n_tiles + hch::NUM_XCD - 1) / hch::NUM_XCD * hch::NUM_XCD;
     if (planes)
-        hipLaunchKernelGGL((hch::col2hash_kernel<4, true>), dim3(grid), dim3(256), 0, s, dcol, L.dnbr, dX,
+        hipLaunchKernelGGL((hch::col2hash_kernel<4, true>), dim3(grid), dim3(256), lds, s, dcol, L.dnbr, dX,
                            L.n_total, c_in, tv, n_tiles);
     else if (vec)
-        hipLaunchKernelGGL((hch::col2hash_kernel<4, false>), dim3(grid), dim3(256), 0, s, dcol, L.dnbr, dX,
+        hipLaunchKernelGGL((hch::col2hash_kernel<4, false>), dim3(grid), dim3(256), lds, s, dcol, L.dnbr, dX,
                            L.n_total, c_in, tv, n_tiles);
     else
-        hipLaunchKernelGGL((hch::col2hash_kernel<1, false>), dim3(grid), dim3(256), 0, s, dcol, L.dnbr, dX,
+        hipLaunchKernelGGL((hch::col2hash_kernel<1, false>), dim3(grid), dim3(256), lds, s, dcol, L.dnbr, dX,
                            L.n_total, c_in, tv, n_tiles);
     HCH_LAUNCH_CHECK("col2hash");
     return HCH_OK;

@@ -216,7 +216,8 @@ __global__ __launch_bounds__(256) void child_kernel(
 // hash2col (Algorithm 1) through the pre-stored neighbour indices
 // ---------------------------------------------------------------------------------------
 
-// Tile of `tv` voxels per workgroup (tv * 27 <= 6912 indices staged in LDS).  A unit is `UB`
+// Tile of `tv` voxels per workgroup (tv * 27 indices staged in LDS, small enough for 8 workgroups
+// per CU).  A unit is `UB`
 // bytes (16: uint4, or one element); a voxel row has cu units.  Threads are split into groups
 // of g = min(cu, 256) lanes; group q moves the units of one (voxel, tap) pair per step, so a
 // step of the whole workgroup writes one contiguous stretch of col.
@@ -225,7 +226,7 @@ __global__ __launch_bounds__(256) void hash2col_kernel(
     const U *__restrict__ X, const int32_t *__restrict__ nbr, U *__restrict__ col,
     int64_t row_begin, int64_t rows, int cu, int tv, unsigned n_tiles)
 {
-    __shared__ int32_t idx[256 * 27];
+    extern __shared__ int32_t idx[];                  // tv * 27 indices (sized at launch)
     const unsigned tile = xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
     if (tile >= n_tiles) return;
     const int64_t r0 = (int64_t)tile * tv;
@@ -269,7 +270,7 @@ __global__ __launch_bounds__(256) void col2hash_kernel(
     const float *__restrict__ dcol, const int32_t *__restrict__ nbr, float *__restrict__ dX,
     int64_t n, int c, int tv, unsigned n_tiles)   // PLANES: dcol is [27][n][c] instead of [n][27*c]
 {
-    __shared__ int32_t idx[256 * 27];
+    extern __shared__ int32_t idx[];                  // tv * 27 indices (sized at launch)
     const unsigned tile = xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
     if (tile >= n_tiles) return;
     const int64_t j0 = (int64_t)tile * tv;
