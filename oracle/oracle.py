@@ -328,6 +328,63 @@ def conv_bwd_weight_at(L, Din, dDout, triples):
     return out
 
 
+# general kernel side F, stride Ss, padding Sp between an input level Li and an output level Lo
+# (Algorithm 1 / 2 as stated: field [p*Ss - Sp, p*Ss - Sp + F - 1]^3, centred when Ss = 1);
+# weights c_out x (c_in*F^3) with column index i_c*F^3 + row, row = (fx*F + fy)*F + fz
+
+def sconv_fwd(Li, Lo, Din, Wp, F, Ss, Sp):
+    Din = np.ascontiguousarray(Din, np.float64)
+    Wp = np.ascontiguousarray(Wp, np.float64)
+    c_in, c_out = Din.shape[0], Wp.shape[0]
+    assert Wp.shape[1] == c_in * F ** 3 and Din.shape[1] == Li.Ntot
+    Dt = np.zeros((c_in * F ** 3, Lo.Ntot), np.float64)
+    Dout = np.empty((c_out, Lo.Ntot), np.float64)
+    lib().orc_conv_fwd(Li.ref, Lo.ref, C.c_int(c_in), C.c_int(c_out), _p(Din), _p(Wp),
+                       C.c_int(F), C.c_int(Ss), C.c_int(Sp), _p(Dt), _p(Dout))
+    return Dout
+
+
+def sconv_bwd_weight(Li, Lo, Din, dDout, F, Ss, Sp):
+    Din = np.ascontiguousarray(Din, np.float64)
+    dDout = np.ascontiguousarray(dDout, np.float64)
+    c_in, c_out = Din.shape[0], dDout.shape[0]
+    assert Din.shape[1] == Li.Ntot and dDout.shape[1] == Lo.Ntot
+    Dt = np.zeros((c_in * F ** 3, Lo.Ntot), np.float64)
+    dW = np.empty((c_out, c_in * F ** 3), np.float64)
+    lib().orc_conv_bwd_weight(Li.ref, Lo.ref, C.c_int(c_in), C.c_int(c_out), _p(Din), _p(dDout),
+                              C.c_int(F), C.c_int(Ss), C.c_int(Sp), _p(Dt), _p(dW))
+    return dW
+
+
+def sconv_bwd_data(Li, Lo, dDout, Wp, c_in, F, Ss, Sp):
+    dDout = np.ascontiguousarray(dDout, np.float64)
+    Wp = np.ascontiguousarray(Wp, np.float64)
+    c_out = dDout.shape[0]
+    assert dDout.shape[1] == Lo.Ntot and Wp.shape == (c_out, c_in * F ** 3)
+    dDt = np.empty((c_in * F ** 3, Lo.Ntot), np.float64)
+    dD = np.empty((c_in, Li.Ntot), np.float64)
+    lib().orc_conv_bwd_data(Li.ref, Lo.ref, C.c_int(c_in), C.c_int(c_out), _p(dDout), _p(Wp),
+                            C.c_int(F), C.c_int(Ss), C.c_int(Sp), _p(dDt), _p(dD))
+    return dD
+
+
+def avgpool_fwd(Lfine, Lcoarse, Din, F=2, Ss=2, Sp=0):
+    """Average pooling (Section 4): the strided convolution whose weights all equal 1/F^3, applied
+    channel by channel: the mean of the column matrix over the F^3 field rows."""
+    Din = np.ascontiguousarray(Din, np.float64)
+    c = Din.shape[0]
+    Dt = hash2col(Lfine, Lcoarse, Din, F, Ss, Sp)
+    return Dt.reshape(c, F ** 3, Lcoarse.Ntot).sum(axis=1) / F ** 3
+
+
+def avgpool_bwd(Lfine, Lcoarse, dDout, F=2, Ss=2, Sp=0):
+    """Its adjoint = average-unpooling (Section 4): the coarse value spread evenly over the field."""
+    dDout = np.ascontiguousarray(dDout, np.float64)
+    c = dDout.shape[0]
+    dDt = np.repeat(dDout[:, None, :] / F ** 3, F ** 3, axis=1).reshape(c * F ** 3, Lcoarse.Ntot)
+    return col2hash(Lfine, Lcoarse, dDt, c, F, Ss, Sp)
+
+
 def pool_max_fwd(Lfine, Lcoarse, Din, F=2, Ss=2, Sp=0):
     Din = np.ascontiguousarray(Din, np.float64)
     c = Din.shape[0]

@@ -299,3 +299,90 @@ def test_unpool_restores_only_switches(oracle):
     G = rng.standard_normal((c, lf.Ntot))
     dP = oracle.unpool_max_bwd(G, sw)
     assert abs((U * G).sum() - (P * dP).sum()) < 1e-9
+
+
+# --------------------------------------------------------------------------------------
+# general kernel side / stride / padding across two levels, average pooling
+# --------------------------------------------------------------------------------------
+
+def _two_levels(oracle, u=32, batch=3, n_levels=2):
+    coords, offs, _ = S.config_batch(2, batch=batch, u=u)
+    return coords, offs, oracle.build_hierarchy(coords, offs, u, n_levels)
+
+
+def _dense_strided(Li, Lo, X, W, F, Ss, Sp, u, need_grad=False):
+    """dense zero-padded conv3d per model with torch (float64), read at the occupied output
+    voxels; returns the outputs and, for gradients, the torch tensors."""
+    c_in, c_out = W.shape[1], W.shape[2]
+    wt = torch.from_numpy(np.asarray(W, np.float64).reshape(F, F, F, c_in, c_out).transpose(4, 3, 0, 1, 2).copy())
+    wt.requires_grad_(need_grad)
+    pad = (F - 1) // 2 if Ss == 1 else Sp
+    outs, vols = [], []
+    for v in range(Li.b):
+        ci = Li.coords[Li.N[v]:Li.N[v + 1]]
+        co = Lo.coords[Lo.N[v]:Lo.N[v + 1]]
+        vol = torch.from_numpy(dense_scatter(ci, np.asarray(X[Li.N[v]:Li.N[v + 1]], np.float64), u))
+        vol.requires_grad_(need_grad)
+        y = torch.nn.functional.conv3d(vol[None], wt, stride=Ss, padding=pad)[0]
+        outs.append(y[:, co[:, 0], co[:, 1], co[:, 2]].T)
+        vols.append((vol, ci))
+    return torch.cat(outs, 0), wt, vols
+
+
+@pytest.mark.parametrize("F,Ss,Sp", [(3, 2, 1), (2, 2, 0), (5, 1, 2), (4, 2, 1), (3, 4, 1)])
+def test_general_conv_vs_dense(oracle, F, Ss, Sp):
+    """Forward and both gradients of the general traversal against dense strided conv3d and its
+    autograd, outputs taken at the occupied voxels of the output level."""
+    shift = {1: 0, 2: 1, 4: 2}[Ss]
+    coords, offs, lv = _two_levels(oracle, n_levels=shift + 1)
+    Li, Lo = lv[0], lv[shift]
+    c_in, c_out = 3, 4
+    X = S.gaussian((Li.Ntot, c_in), 1.0, 81)
+    W = S.gaussian((F ** 3, c_in, c_out), 0.2, 82)
+    G = S.gaussian((Lo.Ntot, c_out), 1.0, 83)
+    Wp = oracle.to_paper_W(W)
+    Y = oracle.sconv_fwd(Li, Lo, oracle.to_paper_X(X), Wp, F, Ss, Sp).T
+    want, wt, vols = _dense_strided(Li, Lo, X, W, F, Ss, Sp, 32, need_grad=True)
+    np.testing.assert_allclose(Y, want.detach().numpy(), rtol=0, atol=1e-11)
+    (want * torch.from_numpy(G)).sum().backward()
+    dW = oracle.sconv_bwd_weight(Li, Lo, oracle.to_paper_X(X), oracle.to_paper_X(G), F, Ss, Sp)
+    want_dW = wt.grad.numpy().transpose(2, 3, 4, 1, 0).reshape(F ** 3, c_in, c_out)     # [row][ci][co]
+    np.testing.assert_allclose(dW.reshape(c_out, c_in, F ** 3).transpose(2, 1, 0), want_dW, rtol=0, atol=1e-10)
+    dX = oracle.sconv_bwd_data(Li, Lo, oracle.to_paper_X(G), Wp, c_in, F, Ss, Sp).T
+    want_dX = np.concatenate([vol.grad.numpy()[:, ci[:, 0], ci[:, 1], ci[:, 2]].T for vol, ci in vols], 0)
+    np.testing.assert_allclose(dX, want_dX, rtol=0, atol=1e-11)
+
+
+def test_general_field_special_cases(oracle):
+    """F = 3, stride 1 is the neighbour list; F = 2, stride 2, no padding the child list; the
+    field of a stride-2 3^3 kernel contains the child list at its rows with all f >= 1."""
+    coords, offs, lv = _two_levels(oracle)
+    Li, Lo = lv[0], lv[1]
+    assert np.array_equal(oracle.field_indices(Li, Li, 3, 1, 0), oracle.neighbours(Li))
+    f3 = oracle.field_indices(Li, Lo, 3, 2, 1)
+    rows = [((fx * 3) + fy) * 3 + fz for fx in (1, 2) for fy in (1, 2) for fz in (1, 2)]
+    assert np.array_equal(f3[:, rows], oracle.children(Li, Lo))
+
+
+def test_avgpool_vs_dense(oracle):
+    """Average pooling = mean over the 2^3 field with empty voxels counted as zero (dense
+    avg_pool3d of the zero-filled grid), and its adjoint."""
+    coords, offs, lv = _two_levels(oracle)
+    Li, Lo = lv[0], lv[1]
+    c = 3
+    X = S.gaussian((Li.Ntot, c), 1.0, 91)
+    G = S.gaussian((Lo.Ntot, c), 1.0, 92)
+    Y = oracle.avgpool_fwd(Li, Lo, oracle.to_paper_X(X)).T
+    dX = oracle.avgpool_bwd(Li, Lo, oracle.to_paper_X(G)).T
+    for v in range(Li.b):
+        ci = Li.coords[Li.N[v]:Li.N[v + 1]]
+        co = Lo.coords[Lo.N[v]:Lo.N[v + 1]]
+        vol = torch.from_numpy(dense_scatter(ci, X[Li.N[v]:Li.N[v + 1]].astype(np.float64), 32))
+        y = torch.nn.functional.avg_pool3d(vol[None], 2)[0].numpy()
+        np.testing.assert_allclose(Y[Lo.N[v]:Lo.N[v + 1]], y[:, co[:, 0], co[:, 1], co[:, 2]].T, rtol=0, atol=1e-13)
+        # adjoint: every fine voxel receives an eighth of its parent's value
+        parent = {tuple(p): i for i, p in enumerate(co)}
+        want = np.stack([G[Lo.N[v] + parent[tuple(p // 2)]] / 8.0 for p in ci])
+        np.testing.assert_allclose(dX[Li.N[v]:Li.N[v + 1]], want, rtol=0, atol=1e-13)
+    # <avgpool(X), G> = <X, avgpool_bwd(G)>
+    assert abs((Y * G).sum() - (X * dX).sum()) < 1e-9
