@@ -289,6 +289,57 @@ hch_status hch_unpool_bwd(const hch_levels *levels, int32_t level_out, const flo
                           const int32_t *argmax, float *dXc, int32_t c, void *stream);
 
 /*
+ * Convolutions with a general kernel side F, stride and padding (Algorithm 1 and 2 as the paper
+ * states them, Section 3.3: receptive field [p*S - P, p*S - P + F - 1]^3 on the input level for
+ * output voxel p; [p - (F-1)/2, p + (F-1)/2]^3 when S = 1), and 2x2x2 average pooling (Section 4:
+ * a convolution whose weights all equal 1/F^3).  The levels of an hch_levels object halve the
+ * resolution, so stride S = 1, 2, 4, 8 reads level_in and writes level_in + log2(S); other
+ * resolution ratios are not supported.  F = 1..7; S = 1 needs odd F and P = (F-1)/2.
+ *
+ * hch_field_build fills the index rows of the traversal by hash lookups (the general form of
+ * the "pre-stored neighbour information"); both are caller-owned DEVICE buffers, either may be
+ * NULL:
+ *   field    [N_out][F^3]  input data index at row (fx*F + fy)*F + fz of output voxel o's field,
+ *                          or -1 (empty, or outside the grid)
+ *   field_t  [N_in][F^3]   data index of the output voxel whose field holds input voxel i at that
+ *                          row, or -1: Algorithm 2's scatter turned into a gather
+ * The products take them as arguments (W is [F^3][c_in][c_out], row as above):
+ *   hch_sconv_fwd         Y[N_out][c_out]  = gathered columns . W                (Eq.3)
+ *   hch_sconv_bwd_weight  dW               = gathered columns^T . dY             (Eq.7)
+ *   hch_sconv_bwd_data    dX[N_in][c_in]   = sum_rows dY[field_t[i][row]] . W[row]^T   (Eq.8 + Alg.2)
+ * X / dX live on level_in, Y / dY on the output level; dtype, outputs (fp32, overwritten),
+ * workspace rules (256-byte aligned, at least hch_sconv_workspace_bytes) and errors as for
+ * hch_conv_*.  With F = 3, S = 1, P = 1 `field` equals nbr27 and the results equal hch_conv_*'s.
+ */
+hch_status hch_field_build(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                           int32_t pad, int32_t *field, int32_t *field_t, void *stream);
+size_t hch_sconv_workspace_bytes(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                                 int32_t c_in, int32_t c_out, hch_dtype dtype, hch_ws_kind kind);
+hch_status hch_sconv_fwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                         hch_dtype dtype, const void *X, const void *W, float *Y, const int32_t *field,
+                         int32_t c_in, int32_t c_out, void *workspace, size_t ws_bytes, void *stream);
+hch_status hch_sconv_bwd_weight(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                                hch_dtype dtype, const void *X, const void *dY, float *dW,
+                                const int32_t *field, int32_t c_in, int32_t c_out, void *workspace,
+                                size_t ws_bytes, void *stream);
+hch_status hch_sconv_bwd_data(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                              hch_dtype dtype, const void *dY, const void *W, float *dX,
+                              const int32_t *field_t, int32_t c_in, int32_t c_out, void *workspace,
+                              size_t ws_bytes, void *stream);
+
+/*
+ * 2x2x2 average pooling from level_in to level_in + 1 and its adjoint (the average-unpooling of
+ * Section 4).  Y[o] = (sum over the occupied children of o of X[child]) / 8: an empty child
+ * counts as zero, as in a convolution with weights 1/8.  Backward: every occupied child of o
+ * receives dY[o] / 8; dX is written completely.
+ *   X, dX DEVICE [N_fine][c];  Y, dY DEVICE [N_coarse][c]
+ */
+hch_status hch_avgpool_fwd(const hch_levels *levels, int32_t level_in, const float *X, float *Y,
+                           int32_t c, void *stream);
+hch_status hch_avgpool_bwd(const hch_levels *levels, int32_t level_in, const float *dY, float *dX,
+                           int32_t c, void *stream);
+
+/*
  * The two steps that sit between a convolution and the next level in the paper's networks
  * (Section 5.1: Convolution -> ReLU -> Pooling), fused into one pass each; results are
  * identical to calling the separate functions.

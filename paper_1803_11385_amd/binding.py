@@ -17,7 +17,8 @@ __all__ = [
     "hch_conv_bwd_weight", "hch_pool_fwd", "hch_pool_bwd", "hch_relu_fwd", "hch_relu_bwd", "hch_relu_pool_fwd",
     "hch_pool_relu_bwd", "hch_deconv_fwd", "hch_deconv_bwd_data", "hch_deconv_bwd_weight",
     "hch_unpool_fwd", "hch_unpool_bwd", "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
-    "hch_profile_reset",
+    "hch_profile_reset", "hch_field_build", "hch_sconv_workspace_bytes", "hch_sconv_fwd", "hch_sconv_bwd_weight",
+    "hch_sconv_bwd_data", "hch_avgpool_fwd", "hch_avgpool_bwd",
 ]
 
 HCH_F32, HCH_BF16 = 0, 1
@@ -36,7 +37,8 @@ exported_symbols = [
     "hch_pool_fwd", "hch_pool_bwd", "hch_relu_fwd", "hch_relu_bwd", "hch_relu_pool_fwd",
     "hch_pool_relu_bwd", "hch_deconv_fwd", "hch_deconv_bwd_data", "hch_deconv_bwd_weight",
     "hch_unpool_fwd", "hch_unpool_bwd", "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
-    "hch_profile_reset",
+    "hch_profile_reset", "hch_field_build", "hch_sconv_workspace_bytes", "hch_sconv_fwd", "hch_sconv_bwd_weight",
+    "hch_sconv_bwd_data", "hch_avgpool_fwd", "hch_avgpool_bwd",
 ]
 
 
@@ -94,6 +96,13 @@ def load_library():
     L.hch_col2hash.argtypes = [vp, i32, vp, i32, vp, vp]
     L.hch_conv_workspace_bytes.argtypes = [vp, i32, i32, i32, C.c_int, C.c_int, C.c_int]
     L.hch_conv_workspace_bytes.restype = sz
+    L.hch_field_build.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
+    L.hch_sconv_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32, C.c_int, C.c_int]
+    L.hch_sconv_workspace_bytes.restype = sz
+    for name in ("hch_sconv_fwd", "hch_sconv_bwd_weight", "hch_sconv_bwd_data"):
+        getattr(L, name).argtypes = [vp, i32, i32, i32, C.c_int, vp, vp, vp, vp, i32, i32, vp, sz, vp]
+    L.hch_avgpool_fwd.argtypes = [vp, i32, vp, vp, i32, vp]
+    L.hch_avgpool_bwd.argtypes = [vp, i32, vp, vp, i32, vp]
     L.hch_unpool_fwd.argtypes = [vp, i32, vp, vp, vp, i32, vp]
     L.hch_unpool_bwd.argtypes = [vp, i32, vp, vp, vp, i32, vp]
     for name in ("hch_conv_fwd", "hch_conv_bwd_data", "hch_conv_bwd_weight",
@@ -399,6 +408,41 @@ def hch_relu_pool_fwd(levels, level_in, Y, A, P, argmax, c, stream=None):
 def hch_pool_relu_bwd(levels, level_in, dP, argmax, A, dY, c, stream=None):
     _check(load_library().hch_pool_relu_bwd(levels.handle, level_in, _dp(dP), _dp(argmax), _dp(A),
                                             _dp(dY), c, _stream(stream)))
+
+
+def hch_field_build(levels, level_in, F, stride, pad, field, field_t, stream=None):
+    _check(load_library().hch_field_build(levels.handle, level_in, F, stride, pad, _dp(field), _dp(field_t),
+                                          _stream(stream)))
+
+
+def hch_sconv_workspace_bytes(levels, level_in, F, stride, c_in, c_out, dtype, kind):
+    return int(load_library().hch_sconv_workspace_bytes(levels.handle, level_in, F, stride, c_in, c_out, dtype, kind))
+
+
+def _sconv(name, levels, level_in, F, stride, dtype, a, b, out, idx, c_in, c_out, workspace, stream):
+    _check(getattr(load_library(), name)(levels.handle, level_in, F, stride, dtype, _dp(a), _dp(b), _dp(out),
+                                         _dp(idx), c_in, c_out, _dp(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def hch_sconv_fwd(levels, level_in, F, stride, dtype, X, W, Y, field, c_in, c_out, workspace, stream=None):
+    _sconv("hch_sconv_fwd", levels, level_in, F, stride, dtype, X, W, Y, field, c_in, c_out, workspace, stream)
+
+
+def hch_sconv_bwd_weight(levels, level_in, F, stride, dtype, X, dY, dW, field, c_in, c_out, workspace, stream=None):
+    _sconv("hch_sconv_bwd_weight", levels, level_in, F, stride, dtype, X, dY, dW, field, c_in, c_out, workspace, stream)
+
+
+def hch_sconv_bwd_data(levels, level_in, F, stride, dtype, dY, W, dX, field_t, c_in, c_out, workspace, stream=None):
+    _sconv("hch_sconv_bwd_data", levels, level_in, F, stride, dtype, dY, W, dX, field_t, c_in, c_out, workspace, stream)
+
+
+def hch_avgpool_fwd(levels, level_in, X, Y, c, stream=None):
+    _check(load_library().hch_avgpool_fwd(levels.handle, level_in, _dp(X), _dp(Y), c, _stream(stream)))
+
+
+def hch_avgpool_bwd(levels, level_in, dY, dX, c, stream=None):
+    _check(load_library().hch_avgpool_bwd(levels.handle, level_in, _dp(dY), _dp(dX), c, _stream(stream)))
 
 
 def hch_relu_fwd(x, y, n, stream=None):

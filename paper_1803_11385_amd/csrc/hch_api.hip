@@ -810,10 +810,10 @@ static GemmPlan plan_rows(int64_t M, int N, int K, bool allow_split)
 }
 
 // weight-gradient product (M = 27*c_in, N = c_out, reduction over n voxels split in slices)
-static GemmPlan plan_wgrad(int64_t n, int c_in, int c_out)
+static GemmPlan plan_wgrad(int64_t n, int c_in, int c_out, int taps = 27)
 {
     GemmPlan p;
-    const int Kc = 27 * c_in;
+    const int Kc = taps * c_in;
     p.bn = c_out <= 16 ? 16 : (c_out <= 32 ? 32 : 64);
     p.bm = 128; p.wm = 4;
     const int64_t tiles = (int64_t)((Kc + 127) / 128) * ((c_out + p.bn - 1) / p.bn);
@@ -832,7 +832,7 @@ template <typename TIN, int AMODE, bool B_KC>
 static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void *B, float *C,
                                 const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
                                 int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s,
-                                int c_planes = 0)
+                                int c_planes = 0, int taps = 27)
 {
     if (M <= 0 || N <= 0) return HCH_OK;
     GemmPlan p = plan;
@@ -868,7 +868,7 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
 #define HCH_GEMM_CASE(BM_, BN_, BK_, WM_, VEC_, PL_)                                                                \
     hipLaunchKernelGGL((hch::gemm_f32_kernel<TIN, BM_, BN_, BK_, WM_, AMODE, B_KC, VEC_, PL_>), grid, dim3(256), 0, s, \
                        (const TIN *)A, (const TIN *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split,            \
-                       c_split_stride, c_vec_ok, m_tiles, c_planes)
+                       c_split_stride, c_vec_ok, m_tiles, c_planes, taps)
     if constexpr (AMODE == hch::A_ROWS && B_KC) {
         if (pl) {
             if (vec) { if (p.bm == 64) HCH_GEMM_CASE(64, 64, 32, 2, true, true); else HCH_GEMM_CASE(128, 64, 32, 4, true, true); }
@@ -897,11 +897,11 @@ template <int AMODE, bool B_KC>
 static hch_status launch_gemm(hch_dtype dtype, const GemmPlan &p, const void *A, const void *B, float *C,
                               const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
                               int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s,
-                              int c_planes = 0)
+                              int c_planes = 0, int taps = 27)
 {
     if (dtype == HCH_BF16)
-        return launch_gemm_t<uint16_t, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes);
-    return launch_gemm_t<float, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes);
+        return launch_gemm_t<uint16_t, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps);
+    return launch_gemm_t<float, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps);
 }
 
 // Register-direct gathered product (conv_direct_kernel): shape-only part of the plan, shared by
@@ -1137,11 +1137,11 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
         if (dtype == HCH_F32) {
             hch::LaunchTimer lt(HCH_KERNEL_ID("flip_transpose_weights_kernel<float>"), s, 8.0 * wn, 0.0);
             hipLaunchKernelGGL(hch::flip_transpose_weights_kernel<float>, dim3(blocks_for(wn)), dim3(256), 0, s,
-                               (const float *)W, (float *)Wt, c_in, c_out);
+                               (const float *)W, (float *)Wt, c_in, c_out, 27, 1);
         } else {
             hch::LaunchTimer lt(HCH_KERNEL_ID("flip_transpose_weights_kernel<unsigned short>"), s, 4.0 * wn, 0.0);
             hipLaunchKernelGGL(hch::flip_transpose_weights_kernel<uint16_t>, dim3(blocks_for(wn)), dim3(256), 0, s,
-                               (const uint16_t *)W, (uint16_t *)Wt, c_in, c_out);
+                               (const uint16_t *)W, (uint16_t *)Wt, c_in, c_out, 27, 1);
         }
         HCH_LAUNCH_CHECK("flip_transpose_weights_kernel");
         const int Kd = 27 * c_out;
@@ -1387,6 +1387,240 @@ extern "C" hch_status hch_pool_relu_bwd(const hch_levels *levels, int32_t level_
                                dP, argmax, Lc.dchild, A, dY, Lc.n_total, c);
     }
     HCH_LAUNCH_CHECK("pool_relu_bwd_kernel");
+    return HCH_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// general kernel side / stride / padding (Algorithm 1 and 2 as stated), average pooling
+// ---------------------------------------------------------------------------------------
+
+// level_out for a field of stride S read at level_in, or a failure
+static hch_status field_levels(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride, int32_t pad,
+                               const Level **Li, const Level **Lo, const char *who)
+{
+    if (!levels) return fail(HCH_EINVAL, std::string(who) + ": null levels");
+    if (F < 1 || F > 7) return fail(HCH_EINVAL, std::string(who) + ": kernel side must be 1..7");
+    int shift = 0;
+    while ((1 << shift) < stride) ++shift;
+    if (stride < 1 || stride > 8 || (1 << shift) != stride)
+        return fail(HCH_EINVAL, std::string(who) + ": stride must be 1, 2, 4 or 8 (the levels halve the resolution)");
+    if (stride == 1 && (F % 2 == 0 || pad != (F - 1) / 2))
+        return fail(HCH_EINVAL, std::string(who) + ": a stride-1 field is centred: odd kernel side, padding (F-1)/2");
+    if (pad < 0 || pad >= F) return fail(HCH_EINVAL, std::string(who) + ": padding must be in [0, F)");
+    if (level_in < 0 || level_in + shift >= (int32_t)levels->lv.size())
+        return fail(HCH_EINVAL, std::string(who) + ": level out of range");
+    *Li = &levels->lv[level_in];
+    *Lo = &levels->lv[level_in + shift];
+    if (!(*Li)->dslot3 || !(*Lo)->dslot3) return fail(HCH_EINVAL, std::string(who) + ": levels were built without device tables");
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_field_build(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                                      int32_t pad, int32_t *field, int32_t *field_t, void *stream)
+{
+    const Level *Li, *Lo;
+    hch_status st = field_levels(levels, level_in, F, stride, pad, &Li, &Lo, "hch_field_build");
+    if (st != HCH_OK) return st;
+    if (!field && !field_t) return fail(HCH_EINVAL, "hch_field_build: nothing to build");
+    const int F3 = F * F * F;
+    hipStream_t s = (hipStream_t)stream;
+    if (field) {
+        const int64_t items = (int64_t)Lo->max_n * F3;
+        hch::LaunchTimer lt(HCH_KERNEL_ID("field_kernel<false>"), s, (double)Lo->n_total * (12.0 + 4.0 * F3), 0.0);
+        hipLaunchKernelGGL(hch::field_kernel<false>, dim3(blocks_for(items), (unsigned)Lo->b), dim3(256), 0, s,
+                           Li->view(), Lo->dcoords, Lo->dN(), field, F, stride, pad);
+    }
+    if (field_t) {
+        const int64_t items = (int64_t)Li->max_n * F3;
+        hch::LaunchTimer lt(HCH_KERNEL_ID("field_kernel<true>"), s, (double)Li->n_total * (12.0 + 4.0 * F3), 0.0);
+        hipLaunchKernelGGL(hch::field_kernel<true>, dim3(blocks_for(items), (unsigned)Li->b), dim3(256), 0, s,
+                           Lo->view(), Li->dcoords, Li->dN(), field_t, F, stride, pad);
+    }
+    HCH_LAUNCH_CHECK("field_kernel");
+    return HCH_OK;
+}
+
+// workspace of the three products of a general convolution: [ transposed weights (bwd_data) |
+// split partial sums ]
+static WsLayout sconv_layout(const Level &Li, const Level &Lo, int taps, int c_in, int c_out, hch_dtype dtype, hch_ws_kind kind)
+{
+    WsLayout w{0, 0};
+    if (kind == HCH_WS_FWD) {
+        const GemmPlan p = plan_rows(Lo.n_total, c_out, taps * c_in, true);
+        if (p.splits > 1) w.part_bytes = round_up((size_t)p.splits * Lo.n_total * c_out * 4, 256);
+    } else if (kind == HCH_WS_BWD_DATA) {
+        const GemmPlan p = plan_rows(Li.n_total, c_in, taps * c_out, true);
+        w.first_bytes = round_up((size_t)taps * c_in * c_out * elem_size(dtype), 256);
+        if (p.splits > 1) w.part_bytes = round_up((size_t)p.splits * Li.n_total * c_in * 4, 256);
+    } else {
+        const GemmPlan p = plan_wgrad(Lo.n_total, c_in, c_out, taps);
+        if (p.splits > 1) w.part_bytes = round_up((size_t)p.splits * taps * c_in * c_out * 4, 256);
+    }
+    return w;
+}
+
+extern "C" size_t hch_sconv_workspace_bytes(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                                            int32_t c_in, int32_t c_out, hch_dtype dtype, hch_ws_kind kind)
+{
+    const Level *Li, *Lo;
+    if (c_in <= 0 || c_out <= 0 || (kind != HCH_WS_FWD && kind != HCH_WS_BWD_DATA && kind != HCH_WS_BWD_WEIGHT)) return 0;
+    if (field_levels(levels, level_in, F, stride, stride == 1 ? (F - 1) / 2 : 0, &Li, &Lo, "hch_sconv_workspace_bytes") != HCH_OK) return 0;
+    const WsLayout w = sconv_layout(*Li, *Lo, F * F * F, c_in, c_out, dtype, kind);
+    return std::max<size_t>(256, w.first_bytes + w.part_bytes);
+}
+
+static hch_status sconv_args(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride, hch_dtype dtype,
+                             const void *a, const void *b, const void *c, const void *idx, int32_t c_in, int32_t c_out,
+                             const void *ws, size_t ws_bytes, hch_ws_kind kind, const Level **Li, const Level **Lo,
+                             const char *who)
+{
+    hch_status st = field_levels(levels, level_in, F, stride, stride == 1 ? (F - 1) / 2 : 0, Li, Lo, who);
+    if (st != HCH_OK) return st;
+    if (!a || !b || !c || !idx || !ws || c_in <= 0 || c_out <= 0)
+        return fail(HCH_EINVAL, std::string(who) + ": null pointer or non-positive channel count");
+    if ((int64_t)F * F * F * c_in * c_out >= ((int64_t)1 << 31)) return fail(HCH_EINVAL, std::string(who) + ": weight tensor too large");
+    if (dtype != HCH_F32 && dtype != HCH_BF16) return fail(HCH_EINVAL, std::string(who) + ": unknown dtype");
+    if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(HCH_EINVAL, std::string(who) + ": workspace must be 256-byte aligned");
+    if (std::max((*Li)->n_total, (*Lo)->n_total) >= ((int64_t)1 << 31) / 512)
+        return fail(HCH_EUNSUPPORTED, std::string(who) + ": too many voxels");
+    if (ws_bytes < hch_sconv_workspace_bytes(levels, level_in, F, stride, c_in, c_out, dtype, kind))
+        return fail(HCH_EWORKSPACE, std::string(who) + ": workspace too small");
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_sconv_fwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                                    hch_dtype dtype, const void *X, const void *W, float *Y, const int32_t *field,
+                                    int32_t c_in, int32_t c_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    const Level *Li, *Lo;
+    hch_status st = sconv_args(levels, level_in, F, stride, dtype, X, W, Y, field, c_in, c_out, workspace, ws_bytes,
+                               HCH_WS_FWD, &Li, &Lo, "hch_sconv_fwd");
+    if (st != HCH_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    const int taps = F * F * F, K = taps * c_in;
+    const int64_t n = Lo->n_total;
+    const double es = elem_size(dtype);
+    const GemmPlan p = plan_rows(n, c_out, K, true);
+    float *part = (float *)workspace;
+    const double bytes = (double)n * (4.0 * taps + 4.0 * c_out * p.splits) + es * (double)Li->n_total * c_in + es * K * c_out;
+    st = launch_gemm<hch::A_GATHER, false>(dtype, p, X, W, p.splits > 1 ? part : Y, field, (int)n, c_out, K, c_in,
+                                           c_out, c_out, n * c_out, bytes, s, 0, taps);
+    if (st != HCH_OK) return st;
+    if (p.splits > 1) st = launch_reduce(part, Y, n * c_out, p.splits, s);
+    return st;
+}
+
+extern "C" hch_status hch_sconv_bwd_weight(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                                           hch_dtype dtype, const void *X, const void *dY, float *dW,
+                                           const int32_t *field, int32_t c_in, int32_t c_out, void *workspace,
+                                           size_t ws_bytes, void *stream)
+{
+    const Level *Li, *Lo;
+    hch_status st = sconv_args(levels, level_in, F, stride, dtype, X, dY, dW, field, c_in, c_out, workspace, ws_bytes,
+                               HCH_WS_BWD_WEIGHT, &Li, &Lo, "hch_sconv_bwd_weight");
+    if (st != HCH_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    const int taps = F * F * F, K = taps * c_in;
+    const int64_t n = Lo->n_total, wsize = (int64_t)K * c_out;
+    const double es = elem_size(dtype);
+    const GemmPlan p = plan_wgrad(n, c_in, c_out, taps);
+    float *part = (float *)workspace;
+    const double bytes = (double)n * (4.0 * taps + es * c_out) + es * (double)Li->n_total * c_in + 4.0 * wsize * p.splits;
+    st = launch_gemm<hch::A_GATHER_T, false>(dtype, p, X, dY, p.splits == 1 ? dW : part, field, K, c_out, (int)n, c_in,
+                                             c_out, c_out, wsize, bytes, s, 0, taps);
+    if (st != HCH_OK) return st;
+    if (p.splits > 1) st = launch_reduce(part, dW, wsize, p.splits, s);
+    return st;
+}
+
+extern "C" hch_status hch_sconv_bwd_data(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                                         hch_dtype dtype, const void *dY, const void *W, float *dX,
+                                         const int32_t *field_t, int32_t c_in, int32_t c_out, void *workspace,
+                                         size_t ws_bytes, void *stream)
+{
+    const Level *Li, *Lo;
+    hch_status st = sconv_args(levels, level_in, F, stride, dtype, dY, W, dX, field_t, c_in, c_out, workspace, ws_bytes,
+                               HCH_WS_BWD_DATA, &Li, &Lo, "hch_sconv_bwd_data");
+    if (st != HCH_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    const int taps = F * F * F, Kd = taps * c_out;
+    const int64_t n = Li->n_total, wn = (int64_t)taps * c_in * c_out;
+    const double es = elem_size(dtype);
+    const WsLayout w = sconv_layout(*Li, *Lo, taps, c_in, c_out, dtype, HCH_WS_BWD_DATA);
+    void *Wt = workspace;
+    float *part = (float *)((char *)workspace + w.first_bytes);
+    // dX[i] = sum over rows of dY[field_t[i][row]] . W[row]^T: a gathered product over the output
+    // gradients through the transposed index rows, weights transposed per tap (not flipped)
+    if (dtype == HCH_F32) {
+        hch::LaunchTimer lt(HCH_KERNEL_ID("flip_transpose_weights_kernel<float>"), s, 8.0 * wn, 0.0);
+        hipLaunchKernelGGL(hch::flip_transpose_weights_kernel<float>, dim3(blocks_for(wn)), dim3(256), 0, s,
+                           (const float *)W, (float *)Wt, c_in, c_out, taps, 0);
+    } else {
+        hch::LaunchTimer lt(HCH_KERNEL_ID("flip_transpose_weights_kernel<unsigned short>"), s, 4.0 * wn, 0.0);
+        hipLaunchKernelGGL(hch::flip_transpose_weights_kernel<uint16_t>, dim3(blocks_for(wn)), dim3(256), 0, s,
+                           (const uint16_t *)W, (uint16_t *)Wt, c_in, c_out, taps, 0);
+    }
+    HCH_LAUNCH_CHECK("flip_transpose_weights_kernel");
+    const GemmPlan p = plan_rows(n, c_in, Kd, true);
+    const double bytes = (double)n * (4.0 * taps + 4.0 * c_in * p.splits) + es * (double)Lo->n_total * c_out + es * wn;
+    st = launch_gemm<hch::A_GATHER, false>(dtype, p, dY, Wt, p.splits > 1 ? part : dX, field_t, (int)n, c_in, Kd, c_out,
+                                           c_in, c_in, n * c_in, bytes, s, 0, taps);
+    if (st != HCH_OK) return st;
+    if (p.splits > 1) st = launch_reduce(part, dX, n * c_in, p.splits, s);
+    return st;
+}
+
+extern "C" hch_status hch_avgpool_fwd(const hch_levels *levels, int32_t level_in, const float *X, float *Y,
+                                      int32_t c, void *stream)
+{
+    if (!levels || level_in < 0 || level_in + 1 >= (int32_t)levels->lv.size())
+        return fail(HCH_EINVAL, "hch_avgpool_fwd: level_in must have a coarser level");
+    if (!X || !Y || c <= 0) return fail(HCH_EINVAL, "hch_avgpool_fwd: bad argument");
+    const Level &Lc = levels->lv[level_in + 1];
+    const Level &Lf = levels->lv[level_in];
+    if (!Lc.dchild) return fail(HCH_EINVAL, "hch_avgpool_fwd: levels were built without device tables");
+    const bool vec = c % 4 == 0 && aligned16(X) && aligned16(Y);
+    const int64_t items = Lc.n_total * (vec ? c / 4 : c);
+    if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hch_avgpool_fwd: too large");
+    {
+        const double bytes = (double)Lf.n_total * 4.0 * c + (double)Lc.n_total * (32.0 + 4.0 * c);
+        hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("avgpool_fwd_kernel<4>") : HCH_KERNEL_ID("avgpool_fwd_kernel<1>"),
+                            (hipStream_t)stream, bytes, 8.0 * Lc.n_total * c);
+        if (vec)
+            hipLaunchKernelGGL(hch::avgpool_fwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                               X, Lc.dchild, Y, Lc.n_total, c);
+        else
+            hipLaunchKernelGGL(hch::avgpool_fwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                               X, Lc.dchild, Y, Lc.n_total, c);
+    }
+    HCH_LAUNCH_CHECK("avgpool_fwd_kernel");
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_avgpool_bwd(const hch_levels *levels, int32_t level_in, const float *dY, float *dX,
+                                      int32_t c, void *stream)
+{
+    if (!levels || level_in < 0 || level_in + 1 >= (int32_t)levels->lv.size())
+        return fail(HCH_EINVAL, "hch_avgpool_bwd: level_in must have a coarser level");
+    if (!dY || !dX || c <= 0) return fail(HCH_EINVAL, "hch_avgpool_bwd: bad argument");
+    const Level &Lc = levels->lv[level_in + 1];
+    const Level &Lf = levels->lv[level_in];
+    if (!Lc.dchild) return fail(HCH_EINVAL, "hch_avgpool_bwd: levels were built without device tables");
+    const bool vec = c % 4 == 0 && aligned16(dY) && aligned16(dX);
+    const int64_t items = Lc.n_total * (vec ? c / 4 : c);
+    if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hch_avgpool_bwd: too large");
+    {
+        const double bytes = (double)Lf.n_total * 4.0 * c + (double)Lc.n_total * (32.0 + 4.0 * c);
+        hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("avgpool_bwd_kernel<4>") : HCH_KERNEL_ID("avgpool_bwd_kernel<1>"),
+                            (hipStream_t)stream, bytes, 0.0);
+        if (vec)
+            hipLaunchKernelGGL(hch::avgpool_bwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                               dY, Lc.dchild, dX, Lc.n_total, c);
+        else
+            hipLaunchKernelGGL(hch::avgpool_bwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                               dY, Lc.dchild, dX, Lc.n_total, c);
+    }
+    HCH_LAUNCH_CHECK("avgpool_bwd_kernel");
     return HCH_OK;
 }
 

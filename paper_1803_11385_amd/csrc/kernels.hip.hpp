@@ -212,6 +212,58 @@ __global__ __launch_bounds__(256) void child_kernel(
     dst[1] = make_int4(out[4], out[5], out[6], out[7]);
 }
 
+// One probe at an arbitrary position (Eq.1, Eq.4-6 and the tag test): global data index or -1.
+// The position must be inside the grid.
+__device__ __forceinline__ int32_t psh_lookup(const PshView &L, int v, unsigned x, unsigned y, unsigned z)
+{
+    const unsigned m = (unsigned)L.mbar[v], r = (unsigned)L.rbar[v];
+    const uint32_t ph = psh_offset(L, (unsigned)L.R[v], r, x % r, y % r, z % r);
+    const uint32_t *rec = psh_slot(L, (unsigned)L.M[v], m, ph, x % m, y % m, z % m);
+    const int32_t h = psh_match(rec[0], rec[1], rec[2], x, y, z);
+    return h >= 0 ? L.N[v] + h : -1;
+}
+
+// Receptive fields of the general traversal of Algorithm 1 (kernel side F, stride S, padding P)
+// between an input level and an output level S times coarser (the same level when S = 1):
+// output voxel p covers the input positions lo(p) + (fx,fy,fz), 0 <= f < F, with lo(p) =
+// p - (F-1)/2 per axis when S = 1 and p*S - P otherwise; row = (fx*F + fy)*F + fz.
+//   TRANSPOSED = false:  out[o][row] = input data index at that position, or -1
+//                        (rows owned by the output voxels; probes go to the input level's tables)
+//   TRANSPOSED = true :  out[i][row] = data index of the output voxel o whose field holds input
+//                        voxel i at this row, or -1 (rows owned by the input voxels; probes go to
+//                        the output level's tables): the index rows of Algorithm 2 turned into
+//                        a gather.
+// One thread per (voxel, row); grid.y = model.  `owner` = coordinates and N* prefix of the level
+// that owns the rows, `probe` = tables of the other level.
+template <bool TRANSPOSED>
+__global__ __launch_bounds__(256) void field_kernel(
+    PshView probe, const int32_t *__restrict__ owner_coords, const int32_t *__restrict__ owner_N,
+    int32_t *__restrict__ out, int F, int S, int P)
+{
+    const int v = blockIdx.y;
+    const int F3 = F * F * F;
+    const int32_t base = owner_N[v], n = owner_N[v + 1] - base;
+    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (item >= (int64_t)n * F3) return;
+    const int i = (int)(item / F3), row = (int)(item - (int64_t)i * F3);
+    const int f[3] = {row / (F * F), (row / F) % F, row % F};
+    const int32_t *p = owner_coords + 3 * (int64_t)(base + i);
+    int q[3];
+    bool ok = true;
+#pragma unroll
+    for (int a = 0; a < 3; ++a) {
+        if (!TRANSPOSED) q[a] = (S == 1 ? p[a] - (F - 1) / 2 : p[a] * S - P) + f[a];
+        else if (S == 1) q[a] = p[a] - f[a] + (F - 1) / 2;
+        else {
+            const int t = p[a] + P - f[a];
+            ok &= t >= 0 && t % S == 0;
+            q[a] = t / S;
+        }
+        ok &= q[a] >= 0 && q[a] < probe.ubar;
+    }
+    out[(int64_t)(base + i) * F3 + row] = ok ? psh_lookup(probe, v, (unsigned)q[0], (unsigned)q[1], (unsigned)q[2]) : -1;
+}
+
 // ---------------------------------------------------------------------------------------
 // hash2col (Algorithm 1) through the pre-stored neighbour indices
 // ---------------------------------------------------------------------------------------
@@ -317,7 +369,7 @@ __global__ __launch_bounds__(256) void col2hash_kernel(
 // A operand (AMODE):
 //   A_ROWS    A(i,k) = A[i*lda + k]                       plain, k contiguous
 //   A_COLS    A(i,k) = A[k*lda + i]                       plain, i contiguous
-//   A_GATHER  A(i,k) = X[nbr[i][k / c]][k % c] or 0       row i of the column matrix of
+//   A_GATHER  A(i,k) = X[nbr[i][k / c]][k % c] or 0       (nbr rows of `taps` entries) row i of the column matrix of
 //             hash2col (Algorithm 1) read straight from the feature rows: i = voxel,
 //             k = tap*c + channel.  `A` = X, `lda` = c, `nbr` = the level's index rows.
 //   A_GATHER_T  A(i,k) = X[nbr[k][i / c]][i % c] or 0     the transpose of the above:
@@ -364,7 +416,7 @@ template <typename TIN, int BM, int BN, int BK, int WM, int AMODE, bool B_KC, bo
 __global__ __launch_bounds__(256) void gemm_f32_kernel(
     const TIN *__restrict__ A, const TIN *__restrict__ B, float *__restrict__ C,
     const int32_t *__restrict__ nbr, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
-    int k_per_split, int64_t c_split_stride, int c_vec_ok, unsigned m_tiles, int c_planes)
+    int k_per_split, int64_t c_split_stride, int c_vec_ok, unsigned m_tiles, int c_planes, int taps)
 {
     constexpr int WN = 4 / WM;
     constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
@@ -455,12 +507,12 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
             const int r = a_row0 + uu * A_RSTEP;
             if (AMODE == A_ROWS) { a_ok[uu] = m0 + r < M; pa[uu] = A + (int64_t)(m0 + r) * lda + kbeg + a_col; }
             if (AMODE == A_COLS) { a_ok[uu] = m0 + a_col < M; pa[uu] = A + (int64_t)(kbeg + r) * lda + m0 + a_col; }
-            if (AMODE == A_GATHER) { a_ok[uu] = m0 + r < M; pn[uu] = nbr + (int64_t)(m0 + r) * 27; }
+            if (AMODE == A_GATHER) { a_ok[uu] = m0 + r < M; pn[uu] = nbr + (int64_t)(m0 + r) * taps; }
             if (AMODE == A_GATHER_T) {
                 const int gi = m0 + a_col;
                 const int tap = gi / c;
                 cc_a = gi - tap * c;
-                a_ok[uu] = gi < M; pn[uu] = nbr + (int64_t)(kbeg + r) * 27 + tap;
+                a_ok[uu] = gi < M; pn[uu] = nbr + (int64_t)(kbeg + r) * taps + tap;
             }
         }
     }
@@ -487,7 +539,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
             if (AMODE == A_GATHER) ok = a_ok[uu] && kn + a_col < kend;
             else ok = a_ok[uu] && kn + a_row0 + uu * A_RSTEP < kend;
             out[uu] = *(ok ? pn[uu] + (AMODE == A_GATHER ? tap_n : 0) : &g_minus1);
-            if (AMODE == A_GATHER_T) pn[uu] += BK * 27;
+            if (AMODE == A_GATHER_T) pn[uu] += BK * taps;
         }
         if (AMODE == A_GATHER) {
             tap_n += dtap; cc_n += dcc;
@@ -545,7 +597,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
                         const int kk = (AMODE == A_GATHER) ? gk : gi;      // column-matrix column
                         const int64_t vox = (AMODE == A_GATHER) ? gi : gk; // voxel
                         const int tap = kk / c;
-                        const int32_t j = nbr[vox * 27 + tap];
+                        const int32_t j = nbr[vox * taps + tap];
                         v[e] = one(A, (int64_t)j * c + (kk - tap * c), j >= 0);
                     }
                 }
@@ -707,19 +759,21 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
         }
 }
 
-// Wt[k][co][ci] = W[26-k][ci][co]: the weights of the convolution that maps output gradients
-// back to the input (Eq.8 read through the symmetry of the 3x3x3 stride-1 neighbourhood)
+// Wt[k][co][ci] = W[flip ? taps-1-k : k][ci][co]: the weights of the convolution that maps
+// output gradients back to the input (Eq.8).  For the 3x3x3 stride-1 neighbourhood, which is
+// symmetric, the gradient is gathered through the same index rows with the taps flipped; a
+// general receptive field uses its transposed index rows and the taps as they are.
 template <typename T>
 __global__ __launch_bounds__(256) void flip_transpose_weights_kernel(
-    const T *__restrict__ W, T *__restrict__ Wt, int c_in, int c_out)
+    const T *__restrict__ W, T *__restrict__ Wt, int c_in, int c_out, int taps, int flip)
 {
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t per = (int64_t)c_in * c_out;
-    if (t >= 27 * per) return;
+    if (t >= taps * per) return;
     const int k = (int)(t / per);
     const int r = (int)(t - k * per);
     const int co = r / c_in, ci = r - co * c_in;
-    Wt[t] = W[((int64_t)(26 - k) * c_in + ci) * c_out + co];
+    Wt[t] = W[((int64_t)(flip ? taps - 1 - k : k) * c_in + ci) * c_out + co];
 }
 
 // out[i] = sum_z part[z*stride + i], the slices of a split reduction, always added in the same
@@ -962,6 +1016,56 @@ __global__ __launch_bounds__(256) void pool_relu_bwd_kernel(
 #pragma unroll
             for (int e = 0; e < VEC; ++e) d[e] = r[e];
         }
+    }
+}
+
+// 2x2x2 average pooling as the paper defines it (Section 4): a stride-2 convolution whose
+// weights all equal 1/F^3, so an empty child counts as zero and the divisor is always 8.
+// One thread per (coarse voxel, channel unit).
+template <int VEC>
+__global__ __launch_bounds__(256) void avgpool_fwd_kernel(
+    const float *__restrict__ X, const int32_t *__restrict__ child8, float *__restrict__ Y, int64_t n_coarse, int c)
+{
+    const int cu = c / VEC;
+    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (item >= n_coarse * cu) return;
+    const int64_t o = item / cu;
+    const int u = (int)(item - o * cu);
+    const float *zsrc = reinterpret_cast<const float *>(g_zero16);
+    float acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int32_t j = child8[o * 8 + k];
+        const float *s = j >= 0 ? X + (int64_t)j * c + u * VEC : zsrc;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] += s[e];
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) Y[o * c + u * VEC + e] = acc[e] * 0.125f;
+}
+
+// its adjoint, the average-unpooling of Section 4: every occupied child receives an eighth of
+// the coarse value; all fine rows are written (each has exactly one parent)
+template <int VEC>
+__global__ __launch_bounds__(256) void avgpool_bwd_kernel(
+    const float *__restrict__ dY, const int32_t *__restrict__ child8, float *__restrict__ dX, int64_t n_coarse, int c)
+{
+    const int cu = c / VEC;
+    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (item >= n_coarse * cu) return;
+    const int64_t o = item / cu;
+    const int u = (int)(item - o * cu);
+    float g[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) g[e] = dY[o * c + u * VEC + e] * 0.125f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int32_t j = child8[o * 8 + k];
+        if (j < 0) continue;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) dX[(int64_t)j * c + u * VEC + e] = g[e];
     }
 }
 

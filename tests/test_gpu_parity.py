@@ -578,3 +578,101 @@ def test_device_build_tiny_and_errors():
         hch.hch_build_levels_device(np.array([[0, 0, 0], [0, 0, 0]], np.int32), np.array([0, 2], np.int64), 4, 1)
     with pytest.raises(hch.HchError):
         hch.hch_build_levels_device(np.array([[0, 0, 5]], np.int32), np.array([0, 1], np.int64), 4, 1)
+
+
+# --------------------------------------------------------------------------------------
+# general kernel side / stride / padding across two levels, average pooling
+# --------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("F,stride,pad", [(3, 1, 1), (5, 1, 2), (3, 2, 1), (2, 2, 0), (4, 2, 1), (3, 4, 1)])
+def test_field_lists_bit_exact(oracle, case_batch64, F, stride, pad):
+    case = case_batch64
+    shift = {1: 0, 2: 1, 4: 2}[stride]
+    Li, Lo = case.olv[0], case.olv[shift]
+    field = torch.full((Lo.Ntot, F ** 3), -7, dtype=torch.int32, device="cuda")
+    field_t = torch.full((Li.Ntot, F ** 3), -7, dtype=torch.int32, device="cuda")
+    hch.hch_field_build(case.glv, 0, F, stride, pad, field, field_t)
+    want = oracle.field_indices(Li, Lo, F, stride, pad)
+    got = field.cpu().numpy()
+    assert np.array_equal(got, want)
+    # the transposed rows are the inverse relation: field_t[i][row] = o  <=>  field[o][row] = i
+    want_t = np.full((Li.Ntot, F ** 3), -1, np.int32)
+    o, row = np.nonzero(want >= 0)
+    want_t[want[o, row], row] = o
+    assert np.array_equal(field_t.cpu().numpy(), want_t)
+    if F == 3 and stride == 1:
+        assert np.array_equal(got, case.glv.info(0).device_nbr27())
+
+
+@pytest.mark.parametrize("F,stride,pad,c_in,c_out", [(3, 2, 1, 8, 16), (2, 2, 0, 4, 8), (5, 1, 2, 4, 8),
+                                                     (3, 2, 1, 3, 5), (3, 4, 1, 8, 8)])
+def test_general_conv(oracle, case_small, F, stride, pad, c_in, c_out):
+    """Forward, weight gradient and data gradient of a strided / larger convolution between two
+    levels against the oracle's Algorithm 1 / 2."""
+    case = case_small
+    shift = {1: 0, 2: 1, 4: 2}[stride]
+    Li, Lo = case.olv[0], case.olv[shift]
+    F3 = F ** 3
+    X = S.gaussian((Li.Ntot, c_in), 1.0, 101)
+    W = S.gaussian((F3, c_in, c_out), 0.1, 102)
+    G = S.gaussian((Lo.Ntot, c_out), 1.0, 103)
+    field = torch.empty((Lo.Ntot, F3), dtype=torch.int32, device="cuda")
+    field_t = torch.empty((Li.Ntot, F3), dtype=torch.int32, device="cuda")
+    hch.hch_field_build(case.glv, 0, F, stride, pad, field, field_t)
+    F32 = hch.HCH_F32
+    ws = workspace(max(hch.hch_sconv_workspace_bytes(case.glv, 0, F, stride, c_in, c_out, F32, k)
+                       for k in (hch.HCH_WS_FWD, hch.HCH_WS_BWD_DATA, hch.HCH_WS_BWD_WEIGHT)))
+    Xp, Wp, Gp = oracle.to_paper_X(X), oracle.to_paper_W(W), oracle.to_paper_X(G)
+    Y = torch.full((Lo.Ntot, c_out), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_sconv_fwd(case.glv, 0, F, stride, F32, dev(X), dev(W), Y, field, c_in, c_out, ws)
+    assert_close(Y.cpu().numpy(), oracle.sconv_fwd(Li, Lo, Xp, Wp, F, stride, pad).T, what="general fwd")
+    dW = torch.full((F3, c_in, c_out), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_sconv_bwd_weight(case.glv, 0, F, stride, F32, dev(X), dev(G), dW, field, c_in, c_out, ws)
+    want_dW = oracle.sconv_bwd_weight(Li, Lo, Xp, Gp, F, stride, pad).reshape(c_out, c_in, F3).transpose(2, 1, 0)
+    assert_close(dW.cpu().numpy(), want_dW, what="general bwd weight")
+    dX = torch.full((Li.Ntot, c_in), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_sconv_bwd_data(case.glv, 0, F, stride, F32, dev(G), dev(W), dX, field_t, c_in, c_out, ws)
+    assert_close(dX.cpu().numpy(), oracle.sconv_bwd_data(Li, Lo, Gp, Wp, c_in, F, stride, pad).T, what="general bwd data")
+
+
+def test_general_conv_equals_3x3x3(case_small):
+    """F = 3, stride 1 through the general entry points gives the bits of hch_conv_fwd (fused)."""
+    case = case_small
+    n = case.olv[0].Ntot
+    X, W = dev(S.gaussian((n, 32), 1.0, 111)), dev(S.gaussian((27, 32, 64), 0.1, 112))
+    field = torch.empty((n, 27), dtype=torch.int32, device="cuda")
+    hch.hch_field_build(case.glv, 0, 3, 1, 1, field, None)
+    F32, FU = hch.HCH_F32, hch.HCH_ALGO_FUSED
+    Y1 = torch.empty((n, 64), dtype=torch.float32, device="cuda")
+    Y2 = torch.empty_like(Y1)
+    hch.hch_sconv_fwd(case.glv, 0, 3, 1, F32, X, W, Y1, field, 32, 64,
+                      workspace(hch.hch_sconv_workspace_bytes(case.glv, 0, 3, 1, 32, 64, F32, hch.HCH_WS_FWD)))
+    hch.hch_conv_fwd(case.glv, 0, F32, X, W, Y2, 32, 64,
+                     workspace(hch.hch_conv_workspace_bytes(case.glv, 0, 32, 64, F32, hch.HCH_WS_FWD, FU)), FU)
+    assert torch.equal(Y1, Y2)
+
+
+@pytest.mark.parametrize("c", [1, 16, 37])
+def test_avgpool(oracle, case_batch64, c):
+    case = case_batch64
+    lf, lc = case.olv[0], case.olv[1]
+    X = S.gaussian((lf.Ntot, c), 1.0, 121)
+    G = S.gaussian((lc.Ntot, c), 1.0, 122)
+    Y = torch.full((lc.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_avgpool_fwd(case.glv, 0, dev(X), Y, c)
+    assert_close(Y.cpu().numpy(), oracle.avgpool_fwd(lf, lc, oracle.to_paper_X(X)).T, what="avgpool fwd")
+    dX = torch.full((lf.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_avgpool_bwd(case.glv, 0, dev(G), dX, c)
+    want = oracle.avgpool_bwd(lf, lc, oracle.to_paper_X(G)).T
+    assert np.array_equal(dX.cpu().numpy(), want.astype(np.float32))      # one exact scaling per element
+
+
+def test_general_conv_errors(case_batch64):
+    case = case_batch64
+    n = case.olv[0].Ntot
+    f = torch.empty((n, 27), dtype=torch.int32, device="cuda")
+    for F, stride, pad, level in ((4, 1, 1, 0), (3, 3, 1, 0), (3, 1, 0, 0), (3, 2, 3, 0), (3, 2, 1, 2), (8, 2, 1, 0)):
+        with pytest.raises(hch.HchError):
+            hch.hch_field_build(case.glv, level, F, stride, pad, f, None)
+    with pytest.raises(hch.HchError):
+        hch.hch_field_build(case.glv, 0, 3, 1, 1, None, None)
