@@ -799,7 +799,10 @@ static GemmPlan plan_rows(int64_t M, int N, int K, bool allow_split)
     if (p.bn == 64 && blocks < 1024) { p.bm = 64; p.wm = 2; blocks = (M + 63) / 64 * n_tiles; }
     p.splits = 1; p.k_per_split = K + hch::GEMM_BK;
     if (allow_split && blocks < 512 && K >= 512) {
-        int64_t want = std::min<int64_t>((768 + blocks - 1) / blocks, K / 256);
+        // as many slices as fit the chip in one round of workgroups (4 per CU with the 64-row
+        // tile, 3 with the 128-row ones): a second, nearly empty round costs as much as a full one
+        const int64_t resident = p.bm == 64 ? 1024 : 768;
+        int64_t want = std::min<int64_t>(resident / blocks, K / 256);
         want = std::max<int64_t>(1, want);
         int64_t kps = (K + want - 1) / want;
         kps = (kps + hch::GEMM_BK - 1) / hch::GEMM_BK * hch::GEMM_BK;
@@ -817,7 +820,7 @@ static GemmPlan plan_wgrad(int64_t n, int c_in, int c_out, int taps = 27)
     p.bn = c_out <= 16 ? 16 : (c_out <= 32 ? 32 : 64);
     p.bm = 128; p.wm = 4;
     const int64_t tiles = (int64_t)((Kc + 127) / 128) * ((c_out + p.bn - 1) / p.bn);
-    int64_t want = std::max<int64_t>(1, 1024 / tiles);
+    int64_t want = std::max<int64_t>(1, 768 / tiles);   // one round of workgroups, 3 per CU
     want = std::min<int64_t>(want, std::max<int64_t>(1, (n + 255) / 256));
     int64_t rows = (n + want - 1) / want;
     rows = std::max<int64_t>(hch::GEMM_BK, (rows + hch::GEMM_BK - 1) / hch::GEMM_BK * hch::GEMM_BK);
