@@ -168,3 +168,123 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(
 }
 
 }  // namespace hch
+
+namespace hch {
+
+// Gathered product into FOUR output columns (the data gradient of a first layer with 4 input
+// channels):  Y[i][0..3] = sum over taps t and channels ch of X[nbr[i][t]][ch] * Wm[t*C + ch][0..3],
+// C = 16*CC.  With 4 columns a 16x16x4 instruction would carry 12 rows of padding, so this kernel
+// uses v_mfma_f32_4x4x1 (16 independent 4x4 outer products per instruction): the 16 blocks take
+// 16 different reduction indices and the 4 rows of a block 4 voxels,
+//   lane l = 4*b + i,  b = 4*tq + cq:  tap 4*T + tq of voxel i, channels 4*cq .. 4*cq+3 of the
+//   current 16-channel chunk (ONE 16-byte load feeds four instructions, element e = channel
+//   4*cq + e); the same lane holds, as j = l % 4, the weights of output column j for those
+//   reduction indices (kept in registers for the whole kernel).
+// A block's accumulator is D[b][i][j] in register i of lane 4*b + j; the 16 blocks are summed
+// through LDS once per group of 4 voxels.  A wavefront owns 64 voxels (their 27 indices each in
+// LDS, as in conv_direct_kernel) and works on 16 of them at a time: all 28*1 loads of a chunk
+// are issued before its 112 instructions.
+//   X [M][C] rows, nbr [M][27], Wm [27*C][4], Y [M][4]; all 16-byte aligned.
+template <int CC>
+__global__ __launch_bounds__(256) void conv_narrow4_kernel(
+    const float *__restrict__ X, const int32_t *__restrict__ nbr, const float *__restrict__ Wm,
+    float *__restrict__ Y, int M, unsigned wave_tiles)
+{
+    constexpr int C = 16 * CC;
+    constexpr int IDX = 64 * 27;
+    __shared__ int32_t sidx[4 * IDX];
+    __shared__ float sred[4 * 1024];
+
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const unsigned tile = xcd_tile(blockIdx.x, gridDim.x / NUM_XCD) * 4 + wv;
+    if (tile >= wave_tiles) return;                    // no workgroup barrier below
+    const int i = lane & 3, b = lane >> 2, tq = b >> 2, cq = b & 3, j = i;
+
+    int32_t *my = sidx + wv * IDX;
+    float *red = sred + wv * 1024;
+    {
+        const int64_t pos0 = (int64_t)tile * IDX, lim = (int64_t)M * 27;
+        int32_t v[27];
+#pragma unroll
+        for (int q = 0; q < 27; ++q) {
+            const int64_t o = pos0 + q * 64 + lane;
+            v[q] = *(o < lim ? nbr + o : &g_minus1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < 27; ++q) my[q * 64 + lane] = v[q];
+    }
+    // this lane's weights: reduction row (4T + tq)*C + 16*cc + 4*cq + e, column j
+    float w[7][CC][4];
+#pragma unroll
+    for (int T = 0; T < 7; ++T)
+#pragma unroll
+        for (int cc = 0; cc < CC; ++cc)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int t = 4 * T + tq;
+                const float *src = t < 27 ? Wm + ((t * C + 16 * cc + 4 * cq + e) * 4 + j)
+                                          : reinterpret_cast<const float *>(g_zero16);
+                w[T][cc][e] = *src;
+            }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    const float *zsrc = reinterpret_cast<const float *>(g_zero16);
+    for (int it = 0; it < 4; ++it) {                   // 16 voxels = 4 groups of 4 per pass
+        f32x4 acc[4];
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) acc[gq] = f32x4{0.f, 0.f, 0.f, 0.f};
+        int32_t idx[7][4];
+#pragma unroll
+        for (int T = 0; T < 7; ++T)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int t = 4 * T + tq;
+                const int32_t v = my[(16 * it + 4 * gq + i) * 27 + (t < 27 ? t : 26)];
+                idx[T][gq] = t < 27 ? v : -1;
+            }
+#pragma unroll
+        for (int cc = 0; cc < CC; ++cc) {
+            f32x4 a[7][4];
+#pragma unroll
+            for (int T = 0; T < 7; ++T)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const float *p = idx[T][gq] >= 0 ? X + (uint32_t)(idx[T][gq] * C + 16 * cc + 4 * cq) : zsrc;
+                    a[T][gq] = *reinterpret_cast<const f32x4 *>(p);
+                }
+            __builtin_amdgcn_sched_barrier(0);         // all loads of the chunk before its products
+#pragma unroll
+            for (int T = 0; T < 7; ++T)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int gq = 0; gq < 4; ++gq)
+                        acc[gq] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[T][gq][e], w[T][cc][e], acc[gq], 0, 0, 0);
+        }
+        // sum of the 16 blocks: red[((gq*4 + i)*4 + j)*16 + b], then lane (gq, i, j) adds its 16
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) red[((gq * 4 + r) * 4 + j) * 16 + b] = acc[gq][r];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        float s = 0.f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 v = *reinterpret_cast<const f32x4 *>(red + lane * 16 + 4 * q);
+            s += (v[0] + v[1]) + (v[2] + v[3]);
+        }
+        // lane = (gq*4 + i)*4 + j: voxel 16*it + lane/4 of the tile, column lane%4
+        const int64_t row = (int64_t)tile * 64 + 16 * it + (lane >> 2);
+        if (row < M) Y[row * 4 + (lane & 3)] = s;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();               // red is reused by the next pass
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
+
+}  // namespace hch

@@ -966,6 +966,30 @@ static hch_status launch_direct(const DirectPlan &d, const float *X, const int32
     return HCH_OK;
 }
 
+// gathered product into exactly 4 output columns (conv_narrow4_kernel)
+static bool narrow4_ok(int64_t M, int c, int N)
+{
+    return N == 4 && (c == 16 || c == 32 || c == 64) && M > 0 && M * (int64_t)c < ((int64_t)1 << 31) - 64 * c;
+}
+
+static hch_status launch_narrow4(const float *X, const int32_t *nbr, const float *Wm, float *out, int64_t M, int c,
+                                 double alg_bytes, hipStream_t s)
+{
+    const unsigned wave_tiles = (unsigned)((M + 63) / 64);
+    const unsigned blocks = (wave_tiles + 3) / 4;
+    const dim3 grid((blocks / hch::NUM_XCD + 1) * hch::NUM_XCD);
+    const int cc = c / 16;
+    hch::LaunchTimer lt(cc == 1 ? HCH_KERNEL_ID("conv_narrow4_kernel<1>")
+                                : (cc == 2 ? HCH_KERNEL_ID("conv_narrow4_kernel<2>") : HCH_KERNEL_ID("conv_narrow4_kernel<4>")),
+                        s, alg_bytes, 2.0 * M * 4.0 * 27.0 * c);
+    if (cc == 1) hipLaunchKernelGGL(hch::conv_narrow4_kernel<1>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles);
+    else if (cc == 2) hipLaunchKernelGGL(hch::conv_narrow4_kernel<2>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles);
+    else if (cc == 4) hipLaunchKernelGGL(hch::conv_narrow4_kernel<4>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles);
+    else return fail(HCH_EINVAL, "conv_narrow4: channel count");
+    HCH_LAUNCH_CHECK("conv_narrow4_kernel");
+    return HCH_OK;
+}
+
 static hch_status launch_reduce(const float *part, float *out, int64_t n, int splits, hipStream_t s)
 {
     const int kid = splits <= 16 ? HCH_KERNEL_ID("splitk_reduce_kernel<1>")
@@ -1080,6 +1104,10 @@ extern "C" hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_
     if (algo == HCH_ALGO_FUSED) {
         // Y = gathered columns . W, the column matrix never leaves the chip.  Per voxel: 27
         // indices and its feature row in, one output row out; the weights once.
+        if (narrow4_ok(n, c_in, c_out) && dtype == HCH_F32 && aligned16(X) && aligned16(W) && aligned16(Y)) {
+            const double bytes = (double)n * (108.0 + 4.0 * c_in + 4.0 * c_out) + 4.0 * Kc * c_out;
+            return launch_narrow4((const float *)X, L->dnbr, (const float *)W, Y, n, c_in, bytes, s);
+        }
         const DirectPlan d = plan_direct(n, c_in, c_out);
         if (d.ok && dtype == HCH_F32 && aligned16(X) && aligned16(W) && aligned16(Y)) {
             const double bytes = (double)n * (108.0 + 4.0 * c_in + 4.0 * c_out * d.splits) + 4.0 * Kc * c_out;
@@ -1148,6 +1176,10 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
         }
         HCH_LAUNCH_CHECK("flip_transpose_weights_kernel");
         const int Kd = 27 * c_out;
+        if (narrow4_ok(n, c_out, c_in) && dtype == HCH_F32 && aligned16(dY) && aligned16(dX)) {
+            const double bytes = (double)n * (108.0 + 4.0 * c_out + 4.0 * c_in) + 4.0 * wn;
+            return launch_narrow4((const float *)dY, L->dnbr, (const float *)Wt, dX, n, c_out, bytes, s);
+        }
         const DirectPlan d = plan_direct(n, c_out, c_in);
         if (d.ok && dtype == HCH_F32 && aligned16(dY) && aligned16(dX)) {
             const double bytes = (double)n * (108.0 + 4.0 * c_out + 4.0 * c_in * d.splits) + 4.0 * wn;

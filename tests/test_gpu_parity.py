@@ -214,7 +214,8 @@ def test_conv_fwd_batch64_4_to_32(oracle, case_batch64, algo):
 
 @pytest.mark.parametrize("algo", ALGOS, ids=ALGO_IDS)
 @pytest.mark.parametrize("c_in,c_out,level", [(32, 64, 0), (16, 32, 1), (5, 7, 1), (64, 128, 2), (8, 80, 2),
-                                              (128, 256, 2), (4, 16, 0)])
+                                              (128, 256, 2), (4, 16, 0), (4, 32, 0), (4, 64, 1), (16, 4, 1),
+                                              (32, 16, 1)])
 def test_conv_fwd_and_gradients(oracle, case_small, c_in, c_out, level, algo):
     case = case_small
     L = case.olv[level]
