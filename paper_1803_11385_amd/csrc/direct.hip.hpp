@@ -26,7 +26,9 @@ template <int NT> __device__ __forceinline__ float frag_get(const typename FragO
 // Y[i][n] (+ split slices) = sum over taps and channels of X[nbr[i][tap]][ch] * Wm[tap*c + ch][n]
 //   X    [M][c] rows, c % 4 == 0, 16-byte aligned
 //   nbr  [M][27]
-//   Wm   [27*c][N] row-major, 16-byte aligned, N % 4 == 0
+//   Wm   [27*c][N] row-major, 16-byte aligned, N % 4 == 0; or, with `flipped` (NT = 1 only), the
+//        weights W[27][N][c] of the convolution whose data gradient this is, read as
+//        Wm[t*c + ch][n] = W[26-t][n][ch] (Eq.8 through the symmetry of the 3x3x3 neighbourhood)
 //   Y    [M][N] (slice z of a split reduction at Y + z*split_stride)
 // A wavefront owns 16*RT voxels and 16*NT output columns; a workgroup is four independent
 // wavefronts on consecutive voxel tiles.  Output column nb + NT*i + t belongs to column tile t
@@ -39,7 +41,7 @@ template <int RT, int NT, int S, bool CHECK>
 __global__ __launch_bounds__(256) void conv_direct_kernel(
     const float *__restrict__ X, const int32_t *__restrict__ nbr, const float *__restrict__ Wm,
     float *__restrict__ Y, int M, int c, int N, int J, int j_per_split, int upt, int step_t, int step_q,
-    unsigned wave_tiles, int64_t split_stride)
+    unsigned wave_tiles, int64_t split_stride, int flipped)
 {
     typedef typename FragOf<NT>::type wfrag;
     constexpr int ROWS = 16 * RT;
@@ -81,7 +83,7 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(
     int t = (4 * jb + g) / upt;
     int q = (4 * jb + g) - t * upt;
     int32_t nidx[RT];
-    int cur_q4 = 0, cur_k = 0;
+    int cur_q4 = 0, cur_k = 0, cur_t = 0;
     auto fetch_idx = [&]() {
         const bool ok = (jn < je) & (t < 27);
         const int tt = t < 27 ? t : 26;
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(
             const int32_t v = my[(16 * i + r) * 27 + tt];
             nidx[i] = ok ? v : -1;
         }
-        cur_q4 = 4 * q; cur_k = t * c + 4 * q;
+        cur_q4 = 4 * q; cur_k = t * c + 4 * q; cur_t = tt;
         t += step_t; q += step_q;
         if (q >= upt) { q -= upt; ++t; }
         ++jn;
@@ -107,9 +109,21 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(
             const float *p = nidx[i] >= 0 ? X + (uint32_t)(nidx[i] * c + cur_q4) : zsrc;
             a[i] = *reinterpret_cast<const f32x4 *>(p);
         }
-        const float *wp = Wm + ((uint32_t)(min(cur_k, k_last) * N) + wcol);
+        bool plain = true;
+        if constexpr (NT == 1) {
+            if (flipped) {
+                // the four reduction rows of this unit are four neighbouring channels of one weight row
+                const f32x4 v = *reinterpret_cast<const f32x4 *>(Wm + ((uint32_t)(((26 - cur_t) * N + wcol) * c) + cur_q4));
 #pragma unroll
-        for (int e = 0; e < 4; ++e) b[e] = *reinterpret_cast<const wfrag *>(wp + e * N);
+                for (int e = 0; e < 4; ++e) b[e] = v[e];
+                plain = false;
+            }
+        }
+        if (plain) {
+            const float *wp = Wm + ((uint32_t)(min(cur_k, k_last) * N) + wcol);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) b[e] = *reinterpret_cast<const wfrag *>(wp + e * N);
+        }
     };
 
     f32x4 acc[RT][NT];
@@ -184,11 +198,13 @@ namespace hch {
 // through LDS once per group of 4 voxels.  A wavefront owns 64 voxels (their 27 indices each in
 // LDS, as in conv_direct_kernel) and works on 16 of them at a time: all 28*1 loads of a chunk
 // are issued before its 112 instructions.
-//   X [M][C] rows, nbr [M][27], Wm [27*C][4], Y [M][4]; all 16-byte aligned.
+//   X [M][C] rows, nbr [M][27], Wm [27*C][4], Y [M][4]; all 16-byte aligned.  With `flipped`, Wm is
+//   the weight tensor W[27][4][C] of the convolution whose data gradient this is:
+//   Wm[t*C + ch][j] = W[26-t][j][ch].
 template <int CC>
 __global__ __launch_bounds__(256) void conv_narrow4_kernel(
     const float *__restrict__ X, const int32_t *__restrict__ nbr, const float *__restrict__ Wm,
-    float *__restrict__ Y, int M, unsigned wave_tiles)
+    float *__restrict__ Y, int M, unsigned wave_tiles, int flipped)
 {
     constexpr int C = 16 * CC;
     constexpr int IDX = 64 * 27;
@@ -223,8 +239,9 @@ __global__ __launch_bounds__(256) void conv_narrow4_kernel(
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int t = 4 * T + tq;
-                const float *src = t < 27 ? Wm + ((t * C + 16 * cc + 4 * cq + e) * 4 + j)
-                                          : reinterpret_cast<const float *>(g_zero16);
+                const int ch = 16 * cc + 4 * cq + e;
+                const float *src = t >= 27 ? reinterpret_cast<const float *>(g_zero16)
+                                           : (flipped ? Wm + (((26 - t) * 4 + j) * C + ch) : Wm + ((t * C + ch) * 4 + j));
                 w[T][cc][e] = *src;
             }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");

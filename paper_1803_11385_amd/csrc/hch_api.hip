@@ -945,7 +945,7 @@ static DirectPlan plan_direct(int64_t M, int c, int N)
 }
 
 static hch_status launch_direct(const DirectPlan &d, const float *X, const int32_t *nbr, const float *Wm,
-                                float *out, int64_t M, int c, int N, double alg_bytes, hipStream_t s)
+                                float *out, int64_t M, int c, int N, double alg_bytes, hipStream_t s, int flipped = 0)
 {
     const unsigned blocks = (d.wave_tiles + 3) / 4;
     const dim3 grid((blocks / hch::NUM_XCD + 1) * hch::NUM_XCD, d.n_groups, (unsigned)d.splits);
@@ -959,7 +959,7 @@ static hch_status launch_direct(const DirectPlan &d, const float *X, const int32
     hch::LaunchTimer lt(ids[b], s, alg_bytes, 2.0 * M * (double)N * 27.0 * c);
 #define HCH_DIRECT_CASE(RT_, NT_, S_, CHECK_)                                                                       \
     hipLaunchKernelGGL((hch::conv_direct_kernel<RT_, NT_, S_, CHECK_>), grid, dim3(256), 0, s, X, nbr, Wm, out,  \
-                       (int)M, c, N, d.J, d.j_per_split, d.upt, d.step_t, d.step_q, d.wave_tiles, M * (int64_t)N)
+                       (int)M, c, N, d.J, d.j_per_split, d.upt, d.step_t, d.step_q, d.wave_tiles, M * (int64_t)N, flipped)
     if (d.check) HCH_DIRECT_CASE(4, 1, 4, true); else HCH_DIRECT_CASE(4, 1, 4, false);
 #undef HCH_DIRECT_CASE
     HCH_LAUNCH_CHECK("conv_direct_kernel");
@@ -973,7 +973,7 @@ static bool narrow4_ok(int64_t M, int c, int N)
 }
 
 static hch_status launch_narrow4(const float *X, const int32_t *nbr, const float *Wm, float *out, int64_t M, int c,
-                                 double alg_bytes, hipStream_t s)
+                                 double alg_bytes, hipStream_t s, int flipped = 0)
 {
     const unsigned wave_tiles = (unsigned)((M + 63) / 64);
     const unsigned blocks = (wave_tiles + 3) / 4;
@@ -982,9 +982,9 @@ static hch_status launch_narrow4(const float *X, const int32_t *nbr, const float
     hch::LaunchTimer lt(cc == 1 ? HCH_KERNEL_ID("conv_narrow4_kernel<1>")
                                 : (cc == 2 ? HCH_KERNEL_ID("conv_narrow4_kernel<2>") : HCH_KERNEL_ID("conv_narrow4_kernel<4>")),
                         s, alg_bytes, 2.0 * M * 4.0 * 27.0 * c);
-    if (cc == 1) hipLaunchKernelGGL(hch::conv_narrow4_kernel<1>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles);
-    else if (cc == 2) hipLaunchKernelGGL(hch::conv_narrow4_kernel<2>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles);
-    else if (cc == 4) hipLaunchKernelGGL(hch::conv_narrow4_kernel<4>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles);
+    if (cc == 1) hipLaunchKernelGGL(hch::conv_narrow4_kernel<1>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles, flipped);
+    else if (cc == 2) hipLaunchKernelGGL(hch::conv_narrow4_kernel<2>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles, flipped);
+    else if (cc == 4) hipLaunchKernelGGL(hch::conv_narrow4_kernel<4>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles, flipped);
     else return fail(HCH_EINVAL, "conv_narrow4: channel count");
     HCH_LAUNCH_CHECK("conv_narrow4_kernel");
     return HCH_OK;
@@ -1165,6 +1165,20 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
         void *Wt = workspace;
         float *part = (float *)((char *)workspace + w.first_bytes);
         const int64_t wn = (int64_t)Kc * c_out;
+        const int Kd = 27 * c_out;
+        // narrow outputs: kernels that read the weights in place (flipped and transposed on the fly)
+        if (narrow4_ok(n, c_out, c_in) && dtype == HCH_F32 && aligned16(dY) && aligned16(dX) && aligned16(W)) {
+            const double bytes = (double)n * (108.0 + 4.0 * c_out + 4.0 * c_in) + 4.0 * wn;
+            return launch_narrow4((const float *)dY, L->dnbr, (const float *)W, dX, n, c_out, bytes, s, 1);
+        }
+        const DirectPlan d = plan_direct(n, c_out, c_in);
+        if (d.ok && dtype == HCH_F32 && aligned16(dY) && aligned16(dX) && aligned16(W)) {
+            const double bytes = (double)n * (108.0 + 4.0 * c_out + 4.0 * c_in * d.splits) + 4.0 * wn;
+            st = launch_direct(d, (const float *)dY, L->dnbr, (const float *)W, d.splits > 1 ? part : dX, n, c_out, c_in, bytes, s, 1);
+            if (st != HCH_OK) return st;
+            if (d.splits > 1) st = launch_reduce(part, dX, n * c_in, d.splits, s);
+            return st;
+        }
         if (dtype == HCH_F32) {
             hch::LaunchTimer lt(HCH_KERNEL_ID("flip_transpose_weights_kernel<float>"), s, 8.0 * wn, 0.0);
             hipLaunchKernelGGL(hch::flip_transpose_weights_kernel<float>, dim3(blocks_for(wn)), dim3(256), 0, s,
@@ -1175,19 +1189,6 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
                                (const uint16_t *)W, (uint16_t *)Wt, c_in, c_out, 27, 1);
         }
         HCH_LAUNCH_CHECK("flip_transpose_weights_kernel");
-        const int Kd = 27 * c_out;
-        if (narrow4_ok(n, c_out, c_in) && dtype == HCH_F32 && aligned16(dY) && aligned16(dX)) {
-            const double bytes = (double)n * (108.0 + 4.0 * c_out + 4.0 * c_in) + 4.0 * wn;
-            return launch_narrow4((const float *)dY, L->dnbr, (const float *)Wt, dX, n, c_out, bytes, s);
-        }
-        const DirectPlan d = plan_direct(n, c_out, c_in);
-        if (d.ok && dtype == HCH_F32 && aligned16(dY) && aligned16(dX)) {
-            const double bytes = (double)n * (108.0 + 4.0 * c_out + 4.0 * c_in * d.splits) + 4.0 * wn;
-            st = launch_direct(d, (const float *)dY, L->dnbr, (const float *)Wt, d.splits > 1 ? part : dX, n, c_out, c_in, bytes, s);
-            if (st != HCH_OK) return st;
-            if (d.splits > 1) st = launch_reduce(part, dX, n * c_in, d.splits, s);
-            return st;
-        }
         const GemmPlan p = plan_rows(n, c_in, Kd, true);
         const double bytes = (double)n * (108.0 + es * c_out + 4.0 * c_in * p.splits) + es * wn;
         st = launch_gemm<hch::A_GATHER, false>(dtype, p, dY, Wt,
