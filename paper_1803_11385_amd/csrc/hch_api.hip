@@ -835,7 +835,7 @@ template <typename TIN, int AMODE, bool B_KC>
 static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void *B, float *C,
                                 const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
                                 int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s,
-                                int c_planes = 0, int taps = 27)
+                                int c_planes = 0, int taps = 27, int b_wrap = 0, int64_t b_tap_stride = 0)
 {
     if (M <= 0 || N <= 0) return HCH_OK;
     GemmPlan p = plan;
@@ -846,6 +846,7 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
     const bool vec = (lda % 4 == 0) && (ldb % 4 == 0) && a_fast_ok && b_fast_ok &&
                      !(reinterpret_cast<uintptr_t>(A) & amask) && !(reinterpret_cast<uintptr_t>(B) & amask) &&
                      (k_split_aligned(p));
+    if (b_wrap && !vec) return fail(HCH_EINVAL, "gemm: in-place weight reading needs aligned operands");
     if (!vec && p.bm == 64) { p.bm = 128; p.wm = 4; }   // the generic path has the 128-row tiles only
     const int c_vec_ok = (c_planes > 0 ? c_planes % 4 == 0 : ldc % 4 == 0) && (c_split_stride % 4 == 0) && aligned16(C);
     const unsigned m_tiles = (unsigned)((M + p.bm - 1) / p.bm);
@@ -871,7 +872,7 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
 #define HCH_GEMM_CASE(BM_, BN_, BK_, WM_, VEC_, PL_)                                                                \
     hipLaunchKernelGGL((hch::gemm_f32_kernel<TIN, BM_, BN_, BK_, WM_, AMODE, B_KC, VEC_, PL_>), grid, dim3(256), 0, s, \
                        (const TIN *)A, (const TIN *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split,            \
-                       c_split_stride, c_vec_ok, m_tiles, c_planes, taps)
+                       c_split_stride, c_vec_ok, m_tiles, c_planes, taps, b_wrap, b_tap_stride)
     if constexpr (AMODE == hch::A_ROWS && B_KC) {
         if (pl) {
             if (vec) { if (p.bm == 64) HCH_GEMM_CASE(64, 64, 32, 2, true, true); else HCH_GEMM_CASE(128, 64, 32, 4, true, true); }
@@ -900,11 +901,11 @@ template <int AMODE, bool B_KC>
 static hch_status launch_gemm(hch_dtype dtype, const GemmPlan &p, const void *A, const void *B, float *C,
                               const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
                               int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s,
-                              int c_planes = 0, int taps = 27)
+                              int c_planes = 0, int taps = 27, int b_wrap = 0, int64_t b_tap_stride = 0)
 {
     if (dtype == HCH_BF16)
-        return launch_gemm_t<uint16_t, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps);
-    return launch_gemm_t<float, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps);
+        return launch_gemm_t<uint16_t, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps, b_wrap, b_tap_stride);
+    return launch_gemm_t<float, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps, b_wrap, b_tap_stride);
 }
 
 // Register-direct gathered product (conv_direct_kernel): shape-only part of the plan, shared by
@@ -1179,6 +1180,19 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
             if (d.splits > 1) st = launch_reduce(part, dX, n * c_in, d.splits, s);
             return st;
         }
+        const GemmPlan p = plan_rows(n, c_in, Kd, true);
+        if (c_out % hch::GEMM_BK == 0 && c_in % 4 == 0 && aligned16(dY) && aligned16(W)) {
+            // the LDS-tiled kernel reads W[27][c_in][c_out] in place as the flipped, transposed
+            // matrix: tap 26 - t of the weights for rows t*c_out .. (t+1)*c_out - 1
+            const int64_t per_tap = (int64_t)c_in * c_out;
+            const char *Wlast = (const char *)W + 26 * per_tap * elem_size(dtype);
+            const double bytes = (double)n * (108.0 + es * c_out + 4.0 * c_in * p.splits) + es * wn;
+            st = launch_gemm<hch::A_GATHER, true>(dtype, p, dY, Wlast, p.splits > 1 ? part : dX, L->dnbr, (int)n, c_in, Kd,
+                                                  c_out, c_out, c_in, n * c_in, bytes, s, 0, 27, c_out, -per_tap);
+            if (st != HCH_OK) return st;
+            if (p.splits > 1) st = launch_reduce(part, dX, n * c_in, p.splits, s);
+            return st;
+        }
         if (dtype == HCH_F32) {
             hch::LaunchTimer lt(HCH_KERNEL_ID("flip_transpose_weights_kernel<float>"), s, 8.0 * wn, 0.0);
             hipLaunchKernelGGL(hch::flip_transpose_weights_kernel<float>, dim3(blocks_for(wn)), dim3(256), 0, s,
@@ -1189,7 +1203,6 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
                                (const uint16_t *)W, (uint16_t *)Wt, c_in, c_out, 27, 1);
         }
         HCH_LAUNCH_CHECK("flip_transpose_weights_kernel");
-        const GemmPlan p = plan_rows(n, c_in, Kd, true);
         const double bytes = (double)n * (108.0 + es * c_out + 4.0 * c_in * p.splits) + es * wn;
         st = launch_gemm<hch::A_GATHER, false>(dtype, p, dY, Wt,
                                                p.splits > 1 ? part : dX, L->dnbr, (int)n, c_in, Kd, c_out,

@@ -416,7 +416,8 @@ template <typename TIN, int BM, int BN, int BK, int WM, int AMODE, bool B_KC, bo
 __global__ __launch_bounds__(256) void gemm_f32_kernel(
     const TIN *__restrict__ A, const TIN *__restrict__ B, float *__restrict__ C,
     const int32_t *__restrict__ nbr, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
-    int k_per_split, int64_t c_split_stride, int c_vec_ok, unsigned m_tiles, int c_planes, int taps)
+    int k_per_split, int64_t c_split_stride, int c_vec_ok, unsigned m_tiles, int c_planes, int taps,
+    int b_wrap, int64_t b_tap_stride)
 {
     constexpr int WN = 4 / WM;
     constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
@@ -517,14 +518,23 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
         }
     }
     // B side
+    // b_wrap > 0 (B_KC only): the reduction axis of B is cut into runs of b_wrap elements (a
+    // multiple of BK) that lie b_tap_stride apart instead of back to back: B(k, j) =
+    // B[(k / b_wrap)*b_tap_stride + j*ldb + k % b_wrap].  This reads the weight tensor
+    // W[27][c_in][c_out] of a convolution as the flipped, transposed matrix of its data gradient.
     const TIN *pb[B_UNITS];
     bool b_ok[B_UNITS];
     int kb = kbeg;
+    int b_pos = b_wrap ? kbeg % b_wrap : 0;
     if (VEC) {
 #pragma unroll
         for (int uu = 0; uu < B_UNITS; ++uu) {
             const int r = b_row0 + uu * B_RSTEP;
-            if (B_KC) { b_ok[uu] = r < BN && n0 + r < N; pb[uu] = B + (int64_t)(n0 + r) * ldb + kbeg + b_col; }
+            if (B_KC) {
+                b_ok[uu] = r < BN && n0 + r < N;
+                pb[uu] = B + (int64_t)(n0 + r) * ldb + b_col +
+                         (b_wrap ? (int64_t)(kbeg / b_wrap) * b_tap_stride + kbeg % b_wrap : (int64_t)kbeg);
+            }
             else { b_ok[uu] = r < BK && n0 + b_col < N; pb[uu] = B + (int64_t)(kbeg + r) * ldb + n0 + b_col; }
         }
     }
@@ -578,6 +588,14 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
                 else ok = b_ok[uu] && kb + b_row0 + uu * B_RSTEP < kend;
                 rb[uu] = InElem<TIN>::four(ok ? pb[uu] : zsrc);
                 pb[uu] += B_KC ? (int64_t)BK : (int64_t)BK * ldb;
+            }
+            if (B_KC && b_wrap) {
+                b_pos += BK;
+                if (b_pos >= b_wrap) {
+                    b_pos -= b_wrap;
+#pragma unroll
+                    for (int uu = 0; uu < B_UNITS; ++uu) pb[uu] += b_tap_stride - b_wrap;
+                }
             }
             kb += BK;
         } else {
