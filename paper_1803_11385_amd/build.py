@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhch.so")
 SOURCES = ["hch_api.hip", "psh_build.cpp"]
-HEADERS = ["kernels.hip.hpp", "direct.hip.hpp", "psh_device.hip.hpp", "psh_build.hpp", "profile.hpp", os.path.join("..", "..", "include", "hch.h")]
+HEADERS = ["kernels.hip.hpp", "direct.hip.hpp", "gemm_bf16.hip.hpp", "psh_device.hip.hpp", "psh_build.hpp", "profile.hpp", os.path.join("..", "..", "include", "hch.h")]
 
 
 def hipcc():

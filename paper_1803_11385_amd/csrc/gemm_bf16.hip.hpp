@@ -1,0 +1,302 @@
+// Matrix products of the convolution (Eq.2/3, Eq.7, Eq.8) for bfloat16 inputs on the bf16 matrix
+// instruction of gfx950 (v_mfma_f32_16x16x32_bf16: products exact, sums in fp32).  Same roles and
+// operand modes as gemm_f32_kernel; the difference is what sits in LDS: bf16 bit patterns, with
+// the reduction index fastest for BOTH operands, because a lane feeds the instruction 8
+// consecutive reduction indices of its row (A) or column (B) as one 16-byte read.  Operands whose
+// reduction index is the slow one in memory (the weights in the forward product, both operands
+// of the weight gradient) are transposed on their way from registers to LDS.
+//
+// Included by hch_api.hip after kernels.hip.hpp.
+#pragma once
+
+namespace hch {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int BF16_BK = 64;   // reduction indices per tile = granularity of split reductions
+
+// C[M x N] (+ slices) = A[M x K] . B[K x N], fp32 out.
+//   AMODE  A_ROWS      A(i,k) = A[i*lda + k]
+//          A_COLS      A(i,k) = A[k*lda + i]
+//          A_GATHER    A(i,k) = X[nbr[i*taps + k/c]][k%c]      (c = lda; rows of X have c elements)
+//          A_GATHER_T  A(i,k) = X[nbr[k*taps + i/c]][i%c]
+//   B_KC   true: B(k,j) = B[j*ldb + k] (optionally cut into runs, see gemm_f32_kernel);
+//          false: B(k,j) = B[k*ldb + j]
+// Requirements, checked by the host: every 8-element unit along an operand's fast axis is
+// 16-byte aligned and wholly inside or outside its matrix (lda, ldb, c multiples of 8; K, M or N
+// multiples of 8 where they bound a fast axis); k_per_split and b_wrap multiples of 64.
+// Units outside read a constant block of zeros; an absent neighbour (-1) likewise.
+template <int BM, int BN, int WM, int AMODE, bool B_KC>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(
+    const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, float *__restrict__ C,
+    const int32_t *__restrict__ nbr, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
+    int k_per_split, int64_t c_split_stride, int c_vec_ok, unsigned m_tiles, int taps,
+    int b_wrap, int64_t b_tap_stride)
+{
+    constexpr int BK = BF16_BK;
+    constexpr int LS = BK + 8;                        // LDS row: 144 bytes, rows shift by 4 banks
+    constexpr int WN = 4 / WM;
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int MT = WTM / 16, NT = WTN / 16;
+    static_assert(WTM % 16 == 0 && WTN % 16 == 0, "wave tile must be a multiple of 16x16");
+    static_assert((MT == 1 || MT == 2 || MT == 4) && (NT == 1 || NT == 2 || NT == 4), "1, 2 or 4 tiles");
+    constexpr bool A_K_FAST = (AMODE == A_ROWS || AMODE == A_GATHER);
+    constexpr bool GATHER = (AMODE == A_GATHER || AMODE == A_GATHER_T);
+    static_assert(A_K_FAST || BM == 128, "transposed A: 128-row tiles only");
+    constexpr int A_UNITS = BM / 32;                  // 16-byte units of an A tile per thread
+    constexpr int B_UNITS = B_KC ? (BN >= 32 ? BN / 32 : 1) : 2;
+
+    __shared__ __attribute__((aligned(16))) uint16_t As2[2 * BM * LS];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs2[2 * BN * LS];
+
+    const unsigned mtile = gridDim.x == m_tiles ? blockIdx.x : xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
+    if (mtile >= m_tiles) return;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WM, wn = wave / WM;
+    const int li = lane & 15, lk = lane >> 4;
+    const int m0 = (int)mtile * BM, n0 = blockIdx.y * BN;
+    const int kbeg = blockIdx.z * k_per_split;
+    const int kend = min(K, kbeg + k_per_split);
+    const int c = (int)lda;
+    C += (int64_t)blockIdx.z * c_split_stride;
+
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int a = 0; a < MT; ++a)
+#pragma unroll
+        for (int b = 0; b < NT; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const uint16_t *zsrc = reinterpret_cast<const uint16_t *>(g_zero16);
+
+    // ---- A: which units of a tile this thread moves.
+    // k fast in memory: unit uu = row a_r + 32*uu, reduction offsets a_c .. a_c+7.
+    // i fast in memory: rows (i) a_c .. a_c+7 at A_UNITS consecutive reduction offsets
+    // a_r .. a_r + A_UNITS-1, which leave for LDS together as one write per row.  Lanes of a
+    // wave take consecutive a_r, so that those writes fall on consecutive banks.
+    const int a_c = A_K_FAST ? (tid % 8) * 8 : (tid / 16) * 8;
+    const int a_r = A_K_FAST ? tid / 8 : (tid % 16) * A_UNITS;
+    const uint16_t *pa[A_UNITS];
+    const int32_t *pn[A_UNITS];
+    bool a_ok[A_UNITS];
+    int ka = kbeg, kn = kbeg;
+    int tap_n = 0, cc_n = 0, cc_a = 0, dtap = 0, dcc = 0;
+    if (AMODE == A_GATHER) {
+        const int gk = kbeg + a_c;
+        tap_n = gk / c; cc_n = gk - tap_n * c; cc_a = cc_n;
+        dtap = BK / c; dcc = BK - dtap * c;
+    }
+#pragma unroll
+    for (int uu = 0; uu < A_UNITS; ++uu) {
+        pa[uu] = nullptr; pn[uu] = nullptr;
+        if (AMODE == A_ROWS) { const int r = a_r + 32 * uu; a_ok[uu] = m0 + r < M; pa[uu] = A + (int64_t)(m0 + r) * lda + kbeg + a_c; }
+        if (AMODE == A_COLS) { a_ok[uu] = m0 + a_c < M; pa[uu] = A + (int64_t)(kbeg + a_r + uu) * lda + m0 + a_c; }
+        if (AMODE == A_GATHER) { const int r = a_r + 32 * uu; a_ok[uu] = m0 + r < M; pn[uu] = nbr + (int64_t)(m0 + r) * taps; }
+        if (AMODE == A_GATHER_T) {
+            const int gi = m0 + a_c;
+            const int tap = gi / c;
+            cc_a = gi - tap * c;
+            a_ok[uu] = gi < M; pn[uu] = nbr + (int64_t)(kbeg + a_r + uu) * taps + tap;
+        }
+    }
+
+    // ---- B.  k fast in memory: unit uu = column b_r + 32*uu, reduction offsets b_c .. b_c+7.
+    // j fast: columns b_c .. b_c+7 at the two reduction offsets b_r, b_r+1.
+    const int b_c = B_KC ? (tid % 8) * 8 : (tid / 32) * 8;
+    const int b_r = B_KC ? tid / 8 : (tid % 32) * 2;
+    const uint16_t *pb[B_UNITS];
+    bool b_ok[B_UNITS];
+    int kb = kbeg;
+    int b_pos = b_wrap ? kbeg % b_wrap : 0;
+#pragma unroll
+    for (int uu = 0; uu < B_UNITS; ++uu) {
+        if (B_KC) {
+            const int r = b_r + 32 * uu;
+            b_ok[uu] = r < BN && n0 + r < N;
+            pb[uu] = B + (int64_t)(n0 + r) * ldb + b_c +
+                     (b_wrap ? (int64_t)(kbeg / b_wrap) * b_tap_stride + kbeg % b_wrap : (int64_t)kbeg);
+        } else {
+            b_ok[uu] = b_c < BN && n0 + b_c < N;
+            pb[uu] = B + (int64_t)(kbeg + b_r + uu) * ldb + n0 + b_c;
+        }
+    }
+    // LDS row of column j of the tile: the NT MFMA tiles of a wave take interleaved columns
+    // (tile nt: columns li*NT + nt of the wave's stretch, so that a lane ends up with NT
+    // neighbouring outputs), stored tile after tile so that 16 lanes read 16 consecutive rows
+    auto b_lds_row = [&](int j) {
+        const int w = j / WTN, q = j - w * WTN;
+        return w * WTN + (q % NT) * 16 + q / NT;
+    };
+
+    auto fetch_idx = [&](int32_t *out) {
+        if (!GATHER) return;
+#pragma unroll
+        for (int uu = 0; uu < A_UNITS; ++uu) {
+            bool ok;
+            if (AMODE == A_GATHER) ok = a_ok[uu] && kn + a_c < kend;
+            else ok = a_ok[uu] && kn + a_r + uu < kend;
+            out[uu] = *(ok ? pn[uu] + (AMODE == A_GATHER ? tap_n : 0) : &g_minus1);
+            if (AMODE == A_GATHER_T) pn[uu] += BK * taps;
+        }
+        if (AMODE == A_GATHER) {
+            tap_n += dtap; cc_n += dcc;
+            if (cc_n >= c) { cc_n -= c; ++tap_n; }
+        }
+        kn += BK;
+    };
+
+    auto fetch = [&](const int32_t *rows, u32x4 *ra, u32x4 *rb) {
+#pragma unroll
+        for (int uu = 0; uu < A_UNITS; ++uu) {
+            const uint16_t *src;
+            if (AMODE == A_ROWS) {
+                src = (a_ok[uu] && ka + a_c < kend) ? pa[uu] : zsrc;
+                pa[uu] += BK;
+            } else if (AMODE == A_COLS) {
+                src = (a_ok[uu] && ka + a_r + uu < kend) ? pa[uu] : zsrc;
+                pa[uu] += (int64_t)BK * lda;
+            } else {
+                const int32_t j = rows[uu];
+                src = j >= 0 ? A + (uint32_t)(j * c + cc_a) : zsrc;
+            }
+            ra[uu] = *reinterpret_cast<const u32x4 *>(src);
+        }
+        if (AMODE == A_GATHER) { cc_a += dcc; if (cc_a >= c) cc_a -= c; }
+        ka += BK;
+#pragma unroll
+        for (int uu = 0; uu < B_UNITS; ++uu) {
+            bool ok;
+            if (B_KC) ok = b_ok[uu] && kb + b_c < kend;
+            else ok = b_ok[uu] && kb + b_r + uu < kend;
+            rb[uu] = *reinterpret_cast<const u32x4 *>(ok ? pb[uu] : zsrc);
+            pb[uu] += B_KC ? (int64_t)BK : (int64_t)BK * ldb;
+        }
+        if (B_KC && b_wrap) {
+            b_pos += BK;
+            if (b_pos >= b_wrap) {
+                b_pos -= b_wrap;
+#pragma unroll
+                for (int uu = 0; uu < B_UNITS; ++uu) pb[uu] += b_tap_stride - b_wrap;
+            }
+        }
+        kb += BK;
+    };
+
+    // registers -> LDS (both tiles end up with the reduction index fastest)
+    auto stash = [&](int stage, const u32x4 *ra, const u32x4 *rb) {
+        uint16_t *As = As2 + stage * BM * LS, *Bs = Bs2 + stage * BN * LS;
+        if constexpr (A_K_FAST) {
+#pragma unroll
+            for (int uu = 0; uu < A_UNITS; ++uu)
+                *reinterpret_cast<u32x4 *>(&As[(a_r + 32 * uu) * LS + a_c]) = ra[uu];
+        } else {
+            // 4 reduction offsets x 8 rows in registers -> per row its 4 values, 8 bytes
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const u32x2 lo = {(ra[0][q] & 0xFFFFu) | (ra[1][q] << 16), (ra[2][q] & 0xFFFFu) | (ra[3][q] << 16)};
+                const u32x2 hi = {(ra[0][q] >> 16) | (ra[1][q] & 0xFFFF0000u), (ra[2][q] >> 16) | (ra[3][q] & 0xFFFF0000u)};
+                *reinterpret_cast<u32x2 *>(&As[(a_c + 2 * q) * LS + a_r]) = lo;
+                *reinterpret_cast<u32x2 *>(&As[(a_c + 2 * q + 1) * LS + a_r]) = hi;
+            }
+        }
+        if constexpr (B_KC) {
+#pragma unroll
+            for (int uu = 0; uu < B_UNITS; ++uu) {
+                const int r = b_r + 32 * uu;
+                if (r < BN) *reinterpret_cast<u32x4 *>(&Bs[b_lds_row(r) * LS + b_c]) = rb[uu];
+            }
+        } else if (b_c < BN) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                *reinterpret_cast<uint32_t *>(&Bs[b_lds_row(b_c + 2 * q) * LS + b_r]) = (rb[0][q] & 0xFFFFu) | (rb[1][q] << 16);
+                *reinterpret_cast<uint32_t *>(&Bs[b_lds_row(b_c + 2 * q + 1) * LS + b_r]) = (rb[0][q] >> 16) | (rb[1][q] & 0xFFFF0000u);
+            }
+        }
+    };
+
+    // A lane's operands of one instruction: 8 consecutive reduction offsets (32*ks + 8*lk ...) of
+    // row li of an A tile and of column li of a B tile.  Both sides use the same offsets, which
+    // is all the sum over the reduction index needs.
+    u32x4 oa[2][MT], ob[2][NT];
+    auto load_operands = [&](int stage) {
+        const uint16_t *As = As2 + stage * BM * LS, *Bs = Bs2 + stage * BN * LS;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                oa[ks][mt] = *reinterpret_cast<const u32x4 *>(&As[(wm * WTM + mt * 16 + li) * LS + ks * 32 + lk * 8]);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                ob[ks][nt] = *reinterpret_cast<const u32x4 *>(&Bs[(wn * WTN + nt * 16 + li) * LS + ks * 32 + lk * 8]);
+        }
+    };
+    auto multiply = [&]() {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8, oa[ks][mt]), __builtin_bit_cast(bf16x8, ob[ks][nt]), acc[mt][nt], 0, 0, 0);
+    };
+
+    // software pipeline as in gemm_f32_kernel: one barrier per tile, registers one tile ahead of
+    // LDS, index loads one tile ahead of the row loads that need them
+    u32x4 ra[A_UNITS], rb[B_UNITS];
+    int32_t rx[A_UNITS] = {}, ry[A_UNITS] = {};
+    auto iteration = [&](int k0, int stage, int32_t *use, int32_t *load) {
+        load_operands(stage);
+        multiply();
+        if (k0 + BK < kend) {
+            stash(stage ^ 1, ra, rb);
+            if (k0 + 2 * BK < kend) {
+                fetch_idx(load);
+                fetch(use, ra, rb);
+            }
+        }
+        __syncthreads();
+    };
+    if (kbeg < kend) {
+        fetch_idx(ry);
+        fetch(ry, ra, rb);
+        fetch_idx(rx);
+        stash(0, ra, rb);
+        if (kbeg + BK < kend) {
+            fetch_idx(ry);
+            fetch(rx, ra, rb);
+        }
+        __syncthreads();
+    }
+    for (int k0 = kbeg; k0 < kend; k0 += 2 * BK) {
+        iteration(k0, 0, ry, rx);
+        if (k0 + BK < kend) iteration(k0 + BK, 1, rx, ry);
+    }
+
+    // D layout (as for every 16x16 fp32 result): register e of lane l holds D[4*(l/16) + e][l%16];
+    // column l%16 of tile nt is column li*NT + nt of the wave's stretch
+    const int gj = n0 + wn * WTN + li * NT;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int gi = m0 + wm * WTM + mt * 16 + 4 * lk + e;
+            if (gi >= M) continue;
+            float *dst = C + (int64_t)gi * ldc + gj;
+            if (NT == 4 && c_vec_ok && gj + 4 <= N) {
+                *reinterpret_cast<f32x4 *>(dst) = f32x4{acc[mt][0][e], acc[mt][1 % NT][e], acc[mt][2 % NT][e], acc[mt][3 % NT][e]};
+            } else if (NT == 2 && c_vec_ok && gj + 2 <= N) {
+                typedef float f32x2 __attribute__((ext_vector_type(2)));
+                *reinterpret_cast<f32x2 *>(dst) = f32x2{acc[mt][0][e], acc[mt][1 % NT][e]};
+            } else {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    if (gj + nt < N) dst[nt] = acc[mt][nt][e];
+            }
+        }
+}
+
+}  // namespace hch

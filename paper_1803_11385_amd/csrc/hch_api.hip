@@ -14,6 +14,7 @@
 
 #include "kernels.hip.hpp"
 #include "direct.hip.hpp"
+#include "gemm_bf16.hip.hpp"
 #include "psh_device.hip.hpp"
 #include "profile.hpp"
 #include "psh_build.hpp"
@@ -781,6 +782,9 @@ extern "C" hch_status hch_col2hash(const hch_levels *levels, int32_t level, cons
 // GEMM launches
 // ---------------------------------------------------------------------------------------
 
+// slices of a split reduction are multiples of the reduction length of one tile
+static inline int k_gran(hch_dtype dtype) { return dtype == HCH_BF16 ? hch::BF16_BK : hch::GEMM_BK; }
+
 // tile shape and split of one product
 struct GemmPlan {
     int bm, bn, wm;
@@ -789,7 +793,7 @@ struct GemmPlan {
 
 // fwd-like products (M = voxels): wide tiles when there are many row tiles, 64-row tiles and a
 // split of the reduction when the level is too small to fill the chip
-static GemmPlan plan_rows(int64_t M, int N, int K, bool allow_split)
+static GemmPlan plan_rows(int64_t M, int N, int K, bool allow_split, int gran = hch::GEMM_BK)
 {
     GemmPlan p;
     p.bn = N <= 16 ? 16 : (N <= 32 ? 32 : 64);
@@ -805,7 +809,7 @@ static GemmPlan plan_rows(int64_t M, int N, int K, bool allow_split)
         int64_t want = std::min<int64_t>(resident / blocks, K / 256);
         want = std::max<int64_t>(1, want);
         int64_t kps = (K + want - 1) / want;
-        kps = (kps + hch::GEMM_BK - 1) / hch::GEMM_BK * hch::GEMM_BK;
+        kps = (kps + gran - 1) / gran * gran;
         p.k_per_split = (int)kps;
         p.splits = (int)((K + kps - 1) / kps);
     }
@@ -813,7 +817,7 @@ static GemmPlan plan_rows(int64_t M, int N, int K, bool allow_split)
 }
 
 // weight-gradient product (M = 27*c_in, N = c_out, reduction over n voxels split in slices)
-static GemmPlan plan_wgrad(int64_t n, int c_in, int c_out, int taps = 27)
+static GemmPlan plan_wgrad(int64_t n, int c_in, int c_out, int taps = 27, int gran = hch::GEMM_BK)
 {
     GemmPlan p;
     const int Kc = taps * c_in;
@@ -823,7 +827,7 @@ static GemmPlan plan_wgrad(int64_t n, int c_in, int c_out, int taps = 27)
     int64_t want = std::max<int64_t>(1, 768 / tiles);   // one round of workgroups, 3 per CU
     want = std::min<int64_t>(want, std::max<int64_t>(1, (n + 255) / 256));
     int64_t rows = (n + want - 1) / want;
-    rows = std::max<int64_t>(hch::GEMM_BK, (rows + hch::GEMM_BK - 1) / hch::GEMM_BK * hch::GEMM_BK);
+    rows = std::max<int64_t>(gran, (rows + gran - 1) / gran * gran);
     p.k_per_split = (int)rows;
     p.splits = (int)std::max<int64_t>(1, (n + rows - 1) / rows);
     return p;
@@ -897,12 +901,66 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
     return HCH_OK;
 }
 
+// bf16 operands on the bf16 matrix instruction (gemm_bf16_kernel): whether the operands meet its
+// alignment rules; products that do not go to the kernel that widens to fp32 on load
+template <int AMODE, bool B_KC>
+static bool bf16_mfma_ok(const GemmPlan &p, const void *A, const void *B, int M, int N, int K, int64_t lda,
+                         int64_t ldb, int c_planes, int b_wrap)
+{
+    constexpr bool a_k_fast = (AMODE == hch::A_ROWS || AMODE == hch::A_GATHER);
+    if (c_planes > 0 || lda % 8 != 0 || ldb % 8 != 0 || !aligned16(A) || !aligned16(B)) return false;
+    if (p.splits > 1 && p.k_per_split % hch::BF16_BK != 0) return false;
+    if (b_wrap % hch::BF16_BK != 0) return false;
+    if (a_k_fast ? (K % 8 != 0) : (M % 8 != 0 || p.bm != 128)) return false;
+    if (B_KC ? (K % 8 != 0) : (N % 8 != 0)) return false;
+    return true;
+}
+
+template <int AMODE, bool B_KC>
+static hch_status launch_gemm_bf16(const GemmPlan &p, const void *A, const void *B, float *C,
+                                   const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
+                                   int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s,
+                                   int taps, int b_wrap, int64_t b_tap_stride)
+{
+    if (M <= 0 || N <= 0) return HCH_OK;
+    const int c_vec_ok = (ldc % 4 == 0) && (c_split_stride % 4 == 0) && aligned16(C);
+    const unsigned m_tiles = (unsigned)((M + p.bm - 1) / p.bm);
+    const bool remap = (AMODE == hch::A_GATHER || AMODE == hch::A_ROWS) && m_tiles >= 256;
+    const unsigned gx = remap ? (m_tiles / hch::NUM_XCD + 1) * hch::NUM_XCD : m_tiles;
+    const dim3 grid(gx, (unsigned)((N + p.bn - 1) / p.bn), (unsigned)p.splits);
+    static int ids[4] = {-1, -1, -1, -1};
+    const int cfg = p.bm == 64 ? 0 : (p.bn == 16 ? 1 : (p.bn == 32 ? 2 : 3));
+    if (ids[cfg] < 0) {
+        char nm[128];
+        snprintf(nm, sizeof nm, "gemm_bf16_kernel<%d, %d, %d, %d, %s>", p.bm, p.bm == 64 ? 64 : p.bn, p.wm,
+                 (int)AMODE, B_KC ? "true" : "false");
+        ids[cfg] = hch::Profiler::get().id_for(nm);
+    }
+    hch::LaunchTimer lt(ids[cfg], s, alg_bytes, 2.0 * M * (double)N * K);
+#define HCH_BF16_CASE(BM_, BN_, WM_)                                                                                 \
+    hipLaunchKernelGGL((hch::gemm_bf16_kernel<BM_, BN_, WM_, AMODE, B_KC>), grid, dim3(256), 0, s,                  \
+                       (const uint16_t *)A, (const uint16_t *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split,     \
+                       c_split_stride, c_vec_ok, m_tiles, taps, b_wrap, b_tap_stride)
+    if (p.bm == 64) {
+        if constexpr (AMODE == hch::A_ROWS || AMODE == hch::A_GATHER) HCH_BF16_CASE(64, 64, 2);
+        else return fail(HCH_EINVAL, "gemm_bf16: 64-row tiles with a transposed A");
+    }
+    else if (p.bn == 16) HCH_BF16_CASE(128, 16, 4);
+    else if (p.bn == 32) HCH_BF16_CASE(128, 32, 4);
+    else HCH_BF16_CASE(128, 64, 4);
+#undef HCH_BF16_CASE
+    HCH_LAUNCH_CHECK("gemm_bf16_kernel");
+    return HCH_OK;
+}
+
 template <int AMODE, bool B_KC>
 static hch_status launch_gemm(hch_dtype dtype, const GemmPlan &p, const void *A, const void *B, float *C,
                               const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
                               int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s,
                               int c_planes = 0, int taps = 27, int b_wrap = 0, int64_t b_tap_stride = 0)
 {
+    if (dtype == HCH_BF16 && bf16_mfma_ok<AMODE, B_KC>(p, A, B, M, N, K, lda, ldb, c_planes, b_wrap))
+        return launch_gemm_bf16<AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, taps, b_wrap, b_tap_stride);
     if (dtype == HCH_BF16)
         return launch_gemm_t<uint16_t, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps, b_wrap, b_tap_stride);
     return launch_gemm_t<float, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps, b_wrap, b_tap_stride);
@@ -1018,7 +1076,7 @@ static WsLayout ws_layout(const Level &L, int c_in, int c_out, hch_dtype dtype, 
     const size_t Kc = (size_t)27 * c_in, n = (size_t)L.n_total;
     WsLayout w{0, 0};
     if (kind == HCH_WS_FWD) {
-        const GemmPlan p = plan_rows(L.n_total, c_out, (int)Kc, true);
+        const GemmPlan p = plan_rows(L.n_total, c_out, (int)Kc, true, k_gran(dtype));
         if (algo == HCH_ALGO_COLUMNS) w.first_bytes = round_up(n * Kc * elem_size(dtype), 256);
         int splits = p.splits;
         if (algo == HCH_ALGO_FUSED) { const DirectPlan d = plan_direct(L.n_total, c_in, c_out); if (d.ok) splits = std::max(splits, d.splits); }
@@ -1026,14 +1084,14 @@ static WsLayout ws_layout(const Level &L, int c_in, int c_out, hch_dtype dtype, 
     } else if (kind == HCH_WS_BWD_DATA) {
         if (algo == HCH_ALGO_COLUMNS) w.first_bytes = round_up(n * Kc * 4, 256);
         else {
-            const GemmPlan p = plan_rows(L.n_total, c_in, 27 * c_out, true);
+            const GemmPlan p = plan_rows(L.n_total, c_in, 27 * c_out, true, k_gran(dtype));
             w.first_bytes = round_up(Kc * c_out * elem_size(dtype), 256);
             const DirectPlan d = plan_direct(L.n_total, c_out, c_in);
             const int splits = d.ok ? std::max(p.splits, d.splits) : p.splits;
             if (splits > 1) w.part_bytes = round_up((size_t)splits * n * c_in * 4, 256);
         }
     } else if (kind == HCH_WS_BWD_WEIGHT) {
-        const GemmPlan p = plan_wgrad(L.n_total, c_in, c_out);
+        const GemmPlan p = plan_wgrad(L.n_total, c_in, c_out, 27, k_gran(dtype));
         if (algo == HCH_ALGO_COLUMNS) w.first_bytes = round_up(n * Kc * elem_size(dtype), 256);
         if (p.splits > 1) w.part_bytes = round_up((size_t)p.splits * Kc * c_out * 4, 256);
     }
@@ -1098,7 +1156,7 @@ extern "C" hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_
     const int Kc = 27 * c_in;
     const int64_t n = L->n_total;
     const WsLayout w = ws_layout(*L, c_in, c_out, dtype, HCH_WS_FWD, algo);
-    const GemmPlan p = plan_rows(n, c_out, Kc, true);
+    const GemmPlan p = plan_rows(n, c_out, Kc, true, k_gran(dtype));
     const double es = elem_size(dtype);               // bytes per input element
     float *part = (float *)((char *)workspace + ((ws_bytes - w.part_bytes) & ~(size_t)255));   // split-K area at the end
 
@@ -1180,8 +1238,8 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
             if (d.splits > 1) st = launch_reduce(part, dX, n * c_in, d.splits, s);
             return st;
         }
-        const GemmPlan p = plan_rows(n, c_in, Kd, true);
-        if (c_out % hch::GEMM_BK == 0 && c_in % 4 == 0 && aligned16(dY) && aligned16(W)) {
+        const GemmPlan p = plan_rows(n, c_in, Kd, true, k_gran(dtype));
+        if (c_out % k_gran(dtype) == 0 && c_in % 4 == 0 && aligned16(dY) && aligned16(W)) {
             // the LDS-tiled kernel reads W[27][c_in][c_out] in place as the flipped, transposed
             // matrix: tap 26 - t of the weights for rows t*c_out .. (t+1)*c_out - 1
             const int64_t per_tap = (int64_t)c_in * c_out;
@@ -1214,7 +1272,7 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
 
     float *dcol = (float *)workspace;
     // dcol[N x Kc] = dY[N x c_out] . W^T   (W is [Kc x c_out]: its rows are B's columns)
-    const GemmPlan p = plan_rows(n, Kc, c_out, false);
+    const GemmPlan p = plan_rows(n, Kc, c_out, false, k_gran(dtype));
     const double bytes = es * ((double)n * c_out + (double)Kc * c_out) + 4.0 * (double)n * Kc;
     // with few input channels dcol is stored tap-major ([27][n][c_in]) between the two kernels:
     // the gather then reads, tap by tap, 16- or 32-byte pieces of nearly consecutive rows that
@@ -1243,7 +1301,7 @@ extern "C" hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t leve
     const int64_t n = L->n_total;
     const double es = elem_size(dtype);
     const WsLayout w = ws_layout(*L, c_in, c_out, dtype, HCH_WS_BWD_WEIGHT, algo);
-    const GemmPlan p = plan_wgrad(n, c_in, c_out);
+    const GemmPlan p = plan_wgrad(n, c_in, c_out, 27, k_gran(dtype));
     const int64_t wsize = (int64_t)Kc * c_out;
     float *part = (float *)((char *)workspace + w.first_bytes);
     float *dst = (p.splits == 1) ? dW : part;
@@ -1495,14 +1553,14 @@ static WsLayout sconv_layout(const Level &Li, const Level &Lo, int taps, int c_i
 {
     WsLayout w{0, 0};
     if (kind == HCH_WS_FWD) {
-        const GemmPlan p = plan_rows(Lo.n_total, c_out, taps * c_in, true);
+        const GemmPlan p = plan_rows(Lo.n_total, c_out, taps * c_in, true, k_gran(dtype));
         if (p.splits > 1) w.part_bytes = round_up((size_t)p.splits * Lo.n_total * c_out * 4, 256);
     } else if (kind == HCH_WS_BWD_DATA) {
-        const GemmPlan p = plan_rows(Li.n_total, c_in, taps * c_out, true);
+        const GemmPlan p = plan_rows(Li.n_total, c_in, taps * c_out, true, k_gran(dtype));
         w.first_bytes = round_up((size_t)taps * c_in * c_out * elem_size(dtype), 256);
         if (p.splits > 1) w.part_bytes = round_up((size_t)p.splits * Li.n_total * c_in * 4, 256);
     } else {
-        const GemmPlan p = plan_wgrad(Lo.n_total, c_in, c_out, taps);
+        const GemmPlan p = plan_wgrad(Lo.n_total, c_in, c_out, taps, k_gran(dtype));
         if (p.splits > 1) w.part_bytes = round_up((size_t)p.splits * taps * c_in * c_out * 4, 256);
     }
     return w;
@@ -1549,7 +1607,7 @@ extern "C" hch_status hch_sconv_fwd(const hch_levels *levels, int32_t level_in, 
     const int taps = F * F * F, K = taps * c_in;
     const int64_t n = Lo->n_total;
     const double es = elem_size(dtype);
-    const GemmPlan p = plan_rows(n, c_out, K, true);
+    const GemmPlan p = plan_rows(n, c_out, K, true, k_gran(dtype));
     float *part = (float *)workspace;
     const double bytes = (double)n * (4.0 * taps + 4.0 * c_out * p.splits) + es * (double)Li->n_total * c_in + es * K * c_out;
     st = launch_gemm<hch::A_GATHER, false>(dtype, p, X, W, p.splits > 1 ? part : Y, field, (int)n, c_out, K, c_in,
@@ -1572,7 +1630,7 @@ extern "C" hch_status hch_sconv_bwd_weight(const hch_levels *levels, int32_t lev
     const int taps = F * F * F, K = taps * c_in;
     const int64_t n = Lo->n_total, wsize = (int64_t)K * c_out;
     const double es = elem_size(dtype);
-    const GemmPlan p = plan_wgrad(n, c_in, c_out, taps);
+    const GemmPlan p = plan_wgrad(n, c_in, c_out, taps, k_gran(dtype));
     float *part = (float *)workspace;
     const double bytes = (double)n * (4.0 * taps + es * c_out) + es * (double)Li->n_total * c_in + 4.0 * wsize * p.splits;
     st = launch_gemm<hch::A_GATHER_T, false>(dtype, p, X, dY, p.splits == 1 ? dW : part, field, K, c_out, (int)n, c_in,
@@ -1610,7 +1668,7 @@ extern "C" hch_status hch_sconv_bwd_data(const hch_levels *levels, int32_t level
                            (const uint16_t *)W, (uint16_t *)Wt, c_in, c_out, taps, 0);
     }
     HCH_LAUNCH_CHECK("flip_transpose_weights_kernel");
-    const GemmPlan p = plan_rows(n, c_in, Kd, true);
+    const GemmPlan p = plan_rows(n, c_in, Kd, true, k_gran(dtype));
     const double bytes = (double)n * (4.0 * taps + 4.0 * c_in * p.splits) + es * (double)Lo->n_total * c_out + es * wn;
     st = launch_gemm<hch::A_GATHER, false>(dtype, p, dY, Wt, p.splits > 1 ? part : dX, field_t, (int)n, c_in, Kd, c_out,
                                            c_in, c_in, n * c_in, bytes, s, 0, taps);

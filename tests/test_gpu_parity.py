@@ -351,7 +351,7 @@ def case_hires(oracle):
 
 
 @pytest.mark.parametrize("algo", ALGOS, ids=ALGO_IDS)
-@pytest.mark.parametrize("c_in,c_out", [(64, 64), (8, 24), (6, 5)])
+@pytest.mark.parametrize("c_in,c_out", [(64, 64), (8, 24), (6, 5), (16, 32), (32, 16), (24, 40), (128, 64), (64, 8)])
 def test_conv_bf16(oracle, case_hires, c_in, c_out, algo):
     """X, W, dY are bf16 (both sides start from the same bf16-representable numbers); products
     are accumulated in fp32 on the GPU and in double in the oracle; outputs are fp32."""
