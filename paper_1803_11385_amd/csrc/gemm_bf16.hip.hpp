@@ -36,7 +36,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     int b_wrap, int64_t b_tap_stride)
 {
     constexpr int BK = BF16_BK;
-    constexpr int LS = BK + 8;                        // LDS row: 144 bytes, rows shift by 4 banks
+    // An LDS row holds the 64 reduction offsets of one row (A) or column (B) of the tile: 128
+    // bytes, no padding.  Its eight 16-byte pieces are stored permuted, piece p of row r at
+    // position p ^ (r % 8), so that the 8 lanes that read or write the same piece of 8
+    // consecutive rows at once touch 8 different groups of banks.
+    constexpr int LS = BK;
+    auto lds_at = [](int row, int k) { return row * LS + ((((k >> 3) ^ (row & 7))) << 3) + (k & 7); };
     constexpr int WN = 4 / WM;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int MT = WTM / 16, NT = WTN / 16;
@@ -191,28 +196,28 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
         if constexpr (A_K_FAST) {
 #pragma unroll
             for (int uu = 0; uu < A_UNITS; ++uu)
-                *reinterpret_cast<u32x4 *>(&As[(a_r + 32 * uu) * LS + a_c]) = ra[uu];
+                *reinterpret_cast<u32x4 *>(&As[lds_at(a_r + 32 * uu, a_c)]) = ra[uu];
         } else {
             // 4 reduction offsets x 8 rows in registers -> per row its 4 values, 8 bytes
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const u32x2 lo = {(ra[0][q] & 0xFFFFu) | (ra[1][q] << 16), (ra[2][q] & 0xFFFFu) | (ra[3][q] << 16)};
                 const u32x2 hi = {(ra[0][q] >> 16) | (ra[1][q] & 0xFFFF0000u), (ra[2][q] >> 16) | (ra[3][q] & 0xFFFF0000u)};
-                *reinterpret_cast<u32x2 *>(&As[(a_c + 2 * q) * LS + a_r]) = lo;
-                *reinterpret_cast<u32x2 *>(&As[(a_c + 2 * q + 1) * LS + a_r]) = hi;
+                *reinterpret_cast<u32x2 *>(&As[lds_at(a_c + 2 * q, a_r)]) = lo;
+                *reinterpret_cast<u32x2 *>(&As[lds_at(a_c + 2 * q + 1, a_r)]) = hi;
             }
         }
         if constexpr (B_KC) {
 #pragma unroll
             for (int uu = 0; uu < B_UNITS; ++uu) {
                 const int r = b_r + 32 * uu;
-                if (r < BN) *reinterpret_cast<u32x4 *>(&Bs[b_lds_row(r) * LS + b_c]) = rb[uu];
+                if (r < BN) *reinterpret_cast<u32x4 *>(&Bs[lds_at(b_lds_row(r), b_c)]) = rb[uu];
             }
         } else if (b_c < BN) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                *reinterpret_cast<uint32_t *>(&Bs[b_lds_row(b_c + 2 * q) * LS + b_r]) = (rb[0][q] & 0xFFFFu) | (rb[1][q] << 16);
-                *reinterpret_cast<uint32_t *>(&Bs[b_lds_row(b_c + 2 * q + 1) * LS + b_r]) = (rb[0][q] >> 16) | (rb[1][q] & 0xFFFF0000u);
+                *reinterpret_cast<uint32_t *>(&Bs[lds_at(b_lds_row(b_c + 2 * q), b_r)]) = (rb[0][q] & 0xFFFFu) | (rb[1][q] << 16);
+                *reinterpret_cast<uint32_t *>(&Bs[lds_at(b_lds_row(b_c + 2 * q + 1), b_r)]) = (rb[0][q] >> 16) | (rb[1][q] & 0xFFFF0000u);
             }
         }
     };
@@ -227,10 +232,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
         for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-                oa[ks][mt] = *reinterpret_cast<const u32x4 *>(&As[(wm * WTM + mt * 16 + li) * LS + ks * 32 + lk * 8]);
+                oa[ks][mt] = *reinterpret_cast<const u32x4 *>(&As[lds_at(wm * WTM + mt * 16 + li, ks * 32 + lk * 8)]);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
-                ob[ks][nt] = *reinterpret_cast<const u32x4 *>(&Bs[(wn * WTN + nt * 16 + li) * LS + ks * 32 + lk * 8]);
+                ob[ks][nt] = *reinterpret_cast<const u32x4 *>(&Bs[lds_at(wn * WTN + nt * 16 + li, ks * 32 + lk * 8)]);
         }
     };
     auto multiply = [&]() {
