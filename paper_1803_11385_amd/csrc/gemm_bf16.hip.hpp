@@ -39,9 +39,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     // An LDS row holds the 64 reduction offsets of one row (A) or column (B) of the tile: 128
     // bytes, no padding.  Its eight 16-byte pieces are stored permuted, piece p of row r at
     // position p ^ (r % 8), so that the 8 lanes that read or write the same piece of 8
-    // consecutive rows at once touch 8 different groups of banks.
+    // consecutive rows at once touch 8 different groups of banks.  (Permuting by r/8 as well,
+    // which would also separate rows that lie 8 apart in the transposing writes, measured
+    // slower: the operand reads are what counts.)
     constexpr int LS = BK;
-    auto lds_at = [](int row, int k) { return row * LS + ((((k >> 3) ^ (row & 7))) << 3) + (k & 7); };
+    auto lds_at = [](int row, int k) { return row * LS + ((((k >> 3) ^ row) & 7) << 3) + (k & 7); };
     constexpr int WN = 4 / WM;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int MT = WTM / 16, NT = WTN / 16;
@@ -109,9 +111,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     }
 
     // ---- B.  k fast in memory: unit uu = column b_r + 32*uu, reduction offsets b_c .. b_c+7.
-    // j fast: columns b_c .. b_c+7 at the two reduction offsets b_r, b_r+1.
-    const int b_c = B_KC ? (tid % 8) * 8 : (tid / 32) * 8;
-    const int b_r = B_KC ? tid / 8 : (tid % 32) * 2;
+    // j fast: columns b_c .. b_c+7 at the two reduction offsets b_r, b_r+1 (8 lanes side by side
+    // along a row of B in memory).
+    const int b_c = (tid % 8) * 8;
+    const int b_r = B_KC ? tid / 8 : (tid / 8) * 2;
     const uint16_t *pb[B_UNITS];
     bool b_ok[B_UNITS];
     int kb = kbeg;
@@ -303,5 +306,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
             }
         }
 }
+
 
 }  // namespace hch
