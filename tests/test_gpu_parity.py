@@ -605,11 +605,12 @@ def test_field_lists_bit_exact(oracle, case_batch64, F, stride, pad):
         assert np.array_equal(got, case.glv.info(0).device_nbr27())
 
 
-@pytest.mark.parametrize("F,stride,pad,c_in,c_out", [(3, 2, 1, 8, 16), (2, 2, 0, 4, 8), (5, 1, 2, 4, 8),
-                                                     (3, 2, 1, 3, 5), (3, 4, 1, 8, 8)])
-def test_general_conv(oracle, case_small, F, stride, pad, c_in, c_out):
+@pytest.mark.parametrize("F,stride,pad,c_in,c_out,bf16", [
+    (3, 2, 1, 8, 16, False), (2, 2, 0, 4, 8, False), (5, 1, 2, 4, 8, False), (3, 2, 1, 3, 5, False), (3, 4, 1, 8, 8, False),
+    (3, 2, 1, 16, 32, True), (2, 2, 0, 64, 64, True), (5, 1, 2, 8, 8, True), (3, 2, 1, 6, 5, True)])
+def test_general_conv(oracle, case_small, F, stride, pad, c_in, c_out, bf16):
     """Forward, weight gradient and data gradient of a strided / larger convolution between two
-    levels against the oracle's Algorithm 1 / 2."""
+    levels against the oracle's Algorithm 1 / 2, in fp32 and with bf16 inputs."""
     case = case_small
     shift = {1: 0, 2: 1, 4: 2}[stride]
     Li, Lo = case.olv[0], case.olv[shift]
@@ -617,23 +618,27 @@ def test_general_conv(oracle, case_small, F, stride, pad, c_in, c_out):
     X = S.gaussian((Li.Ntot, c_in), 1.0, 101)
     W = S.gaussian((F3, c_in, c_out), 0.1, 102)
     G = S.gaussian((Lo.Ntot, c_out), 1.0, 103)
+    if bf16:
+        X, W, G = S.to_bf16_grid(X), S.to_bf16_grid(W), S.to_bf16_grid(G)
+    put = dev_bf16 if bf16 else dev
+    tol = TOL_BF16 if bf16 else TOL_F32
     field = torch.empty((Lo.Ntot, F3), dtype=torch.int32, device="cuda")
     field_t = torch.empty((Li.Ntot, F3), dtype=torch.int32, device="cuda")
     hch.hch_field_build(case.glv, 0, F, stride, pad, field, field_t)
-    F32 = hch.HCH_F32
-    ws = workspace(max(hch.hch_sconv_workspace_bytes(case.glv, 0, F, stride, c_in, c_out, F32, k)
+    DT = hch.HCH_BF16 if bf16 else hch.HCH_F32
+    ws = workspace(max(hch.hch_sconv_workspace_bytes(case.glv, 0, F, stride, c_in, c_out, DT, k)
                        for k in (hch.HCH_WS_FWD, hch.HCH_WS_BWD_DATA, hch.HCH_WS_BWD_WEIGHT)))
     Xp, Wp, Gp = oracle.to_paper_X(X), oracle.to_paper_W(W), oracle.to_paper_X(G)
     Y = torch.full((Lo.Ntot, c_out), float("nan"), dtype=torch.float32, device="cuda")
-    hch.hch_sconv_fwd(case.glv, 0, F, stride, F32, dev(X), dev(W), Y, field, c_in, c_out, ws)
-    assert_close(Y.cpu().numpy(), oracle.sconv_fwd(Li, Lo, Xp, Wp, F, stride, pad).T, what="general fwd")
+    hch.hch_sconv_fwd(case.glv, 0, F, stride, DT, put(X), put(W), Y, field, c_in, c_out, ws)
+    assert_close(Y.cpu().numpy(), oracle.sconv_fwd(Li, Lo, Xp, Wp, F, stride, pad).T, tol=tol, what="general fwd")
     dW = torch.full((F3, c_in, c_out), float("nan"), dtype=torch.float32, device="cuda")
-    hch.hch_sconv_bwd_weight(case.glv, 0, F, stride, F32, dev(X), dev(G), dW, field, c_in, c_out, ws)
+    hch.hch_sconv_bwd_weight(case.glv, 0, F, stride, DT, put(X), put(G), dW, field, c_in, c_out, ws)
     want_dW = oracle.sconv_bwd_weight(Li, Lo, Xp, Gp, F, stride, pad).reshape(c_out, c_in, F3).transpose(2, 1, 0)
-    assert_close(dW.cpu().numpy(), want_dW, what="general bwd weight")
+    assert_close(dW.cpu().numpy(), want_dW, tol=tol, what="general bwd weight")
     dX = torch.full((Li.Ntot, c_in), float("nan"), dtype=torch.float32, device="cuda")
-    hch.hch_sconv_bwd_data(case.glv, 0, F, stride, F32, dev(G), dev(W), dX, field_t, c_in, c_out, ws)
-    assert_close(dX.cpu().numpy(), oracle.sconv_bwd_data(Li, Lo, Gp, Wp, c_in, F, stride, pad).T, what="general bwd data")
+    hch.hch_sconv_bwd_data(case.glv, 0, F, stride, DT, put(G), put(W), dX, field_t, c_in, c_out, ws)
+    assert_close(dX.cpu().numpy(), oracle.sconv_bwd_data(Li, Lo, Gp, Wp, c_in, F, stride, pad).T, tol=tol, what="general bwd data")
 
 
 def test_general_conv_equals_3x3x3(case_small):
