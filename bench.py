@@ -77,6 +77,51 @@ def cpu_baseline(coords, offs, X0, W, u, max_shapes, budget_s=24.0):
             f"first {ns} of {len(offs) - 1} shapes, {passes} fwd+bwd passes, {total_t:.1f} s")
 
 
+def bf16_conv_bench(args, torch, hch, S):
+    """Forward, data gradient and weight gradient of a 64 -> 64 convolution, bf16 inputs, fp32
+    sums and outputs, on level 0 of the 512^3 / batch 4 workload (tables built on the device)."""
+    coords, offs, _ = S.config_batch(5)
+    lv = hch.hch_build_levels_device(coords, offs, 512, 1)
+    n, ci, co = lv.n(0), 64, 64
+    algo = hch.HCH_ALGO_FUSED if args.algo == "fused" else hch.HCH_ALGO_COLUMNS
+    B16 = hch.HCH_BF16
+
+    def bf16(a):
+        return torch.from_numpy(S.bf16_bits(S.to_bf16_grid(a)).view(np.int16)).to("cuda")
+
+    X, G = bf16(S.gaussian((n, ci), 1.0, 5001)), bf16(S.gaussian((n, co), 1.0, 5003))
+    W = bf16(S.he_weights(ci, co, 5002))
+    Y = torch.empty((n, co), dtype=torch.float32, device="cuda")
+    dX = torch.empty((n, ci), dtype=torch.float32, device="cuda")
+    dW = torch.empty((27, ci, co), dtype=torch.float32, device="cuda")
+    need = max(hch.hch_conv_workspace_bytes(lv, 0, ci, co, B16, k, algo)
+               for k in (hch.HCH_WS_FWD, hch.HCH_WS_BWD_DATA, hch.HCH_WS_BWD_WEIGHT))
+    buf = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+    off = (-buf.data_ptr()) % 256
+    ws = buf[off: off + need]
+    calls = (("forward", lambda: hch.hch_conv_fwd(lv, 0, B16, X, W, Y, ci, co, ws, algo)),
+             ("data_gradient", lambda: hch.hch_conv_bwd_data(lv, 0, B16, G, W, dX, ci, co, ws, algo)),
+             ("weight_gradient", lambda: hch.hch_conv_bwd_weight(lv, 0, B16, X, G, dW, ci, co, ws, algo)))
+    flop = 2.0 * n * 27 * ci * co
+    out = {}
+    for name, fn in calls:
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        out[name] = {"ms": round(ms, 4), "tflops": round(flop / ms / 1e9, 1)}
+    print(json.dumps({"metric": "one 3x3x3 convolution 64 -> 64, bf16 inputs, fp32 sums: time per product", "unit": "ms",
+                      "products": out, "calls_timed": args.steps, "higher_is_better": False, "dtype": "bf16",
+                      "data": "synthetic", "algo": args.algo,
+                      "config": {"workload": f"512^3 grid, batch 4, two-voxel shells of 2-6 primitives, {n} voxels"}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -98,6 +143,9 @@ def main():
     ap.add_argument("--build-bench", action="store_true",
                     help="time only the construction of the hash tables of the workload, on the host "
                          "(hch_build_levels) and on the device (hch_build_levels_device), and print that")
+    ap.add_argument("--bf16-conv-bench", action="store_true",
+                    help="time only the three products of one 64 -> 64 convolution with bf16 inputs on the "
+                         "finest level of the high-resolution workload (512^3 grid, batch 4), and print that")
     ap.add_argument("--algo", choices=["columns", "fused"], default="fused",
                     help="columns: hash2col -> GEMM -> col2hash through memory; fused: gathered GEMM operand")
     args = ap.parse_args()
@@ -112,6 +160,9 @@ def main():
     import synth_shapes as S
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.bf16_conv_bench:
+        bf16_conv_bench(args, torch, hch, S)
+        return
     u, b = args.resolution, args.batch
     t0 = time.perf_counter()
     coords, offs, X0, W = make_inputs(4, b, u)

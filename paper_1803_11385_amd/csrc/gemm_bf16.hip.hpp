@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, float *__restrict__ C,
     const int32_t *__restrict__ nbr, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
     int k_per_split, int64_t c_split_stride, int c_vec_ok, unsigned m_tiles, int taps,
-    int b_wrap, int64_t b_tap_stride)
+    int b_wrap, int64_t b_tap_stride, int flat_slices)
 {
     constexpr int BK = BF16_BK;
     // An LDS row holds the 64 reduction offsets of one row (A) or column (B) of the tile: 128
@@ -58,18 +58,35 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     __shared__ __attribute__((aligned(16))) uint16_t As2[2 * BM * LS];
     __shared__ __attribute__((aligned(16))) uint16_t Bs2[2 * BN * LS];
 
-    const unsigned mtile = gridDim.x == m_tiles ? blockIdx.x : xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
-    if (mtile >= m_tiles) return;
+    // Which tile and which slice of the reduction this workgroup computes.
+    // Grid (x, y, z) = (row tiles, column tiles, slices); with more row tiles than gridDim.x ==
+    // m_tiles says, x is remapped so that each XCD owns a contiguous range of row tiles.
+    // flat_slices > 0 (a multiple of 8): a one-dimensional grid in which workgroup b belongs to
+    // XCD b % 8 (workgroups are handed to the XCDs in turn) and slice s is computed, all tiles of
+    // it, by XCD s % 8.  The tiles of a slice of the weight gradient walk through the same voxels
+    // at the same time -- each gathers them for its own taps -- and so meet the rows in one L2
+    // instead of fetching them from memory once per tile.
+    unsigned mtile, ntile, slice;
+    if (flat_slices > 0) {
+        const unsigned n_tiles = (unsigned)((N + BN - 1) / BN), tiles = m_tiles * n_tiles;
+        const unsigned q = blockIdx.x / NUM_XCD, t = q % tiles;
+        slice = (q / tiles) * NUM_XCD + blockIdx.x % NUM_XCD;
+        mtile = t % m_tiles; ntile = t / m_tiles;
+    } else {
+        mtile = gridDim.x == m_tiles ? blockIdx.x : xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
+        if (mtile >= m_tiles) return;
+        ntile = blockIdx.y; slice = blockIdx.z;
+    }
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
     const int li = lane & 15, lk = lane >> 4;
-    const int m0 = (int)mtile * BM, n0 = blockIdx.y * BN;
-    const int kbeg = blockIdx.z * k_per_split;
+    const int m0 = (int)mtile * BM, n0 = (int)ntile * BN;
+    const int kbeg = (int)slice * k_per_split;
     const int kend = min(K, kbeg + k_per_split);
     const int c = (int)lda;
-    C += (int64_t)blockIdx.z * c_split_stride;
+    C += (int64_t)slice * c_split_stride;
 
     f32x4 acc[MT][NT];
 #pragma unroll
@@ -82,10 +99,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     // ---- A: which units of a tile this thread moves.
     // k fast in memory: unit uu = row a_r + 32*uu, reduction offsets a_c .. a_c+7.
     // i fast in memory: rows (i) a_c .. a_c+7 at A_UNITS consecutive reduction offsets
-    // a_r .. a_r + A_UNITS-1, which leave for LDS together as one write per row.  Lanes of a
-    // wave take consecutive a_r, so that those writes fall on consecutive banks.
-    const int a_c = A_K_FAST ? (tid % 8) * 8 : (tid / 16) * 8;
-    const int a_r = A_K_FAST ? tid / 8 : (tid % 16) * A_UNITS;
+    // a_r .. a_r + A_UNITS-1, which leave for LDS together as one write per row.  Four
+    // neighbouring lanes take 64 contiguous bytes of one row of the operand in memory (the
+    // address unit merges accesses of neighbouring lanes only; with the lanes of a row 16 apart
+    // every lane cost its own cache access and the kernel was bound by their number).
+    const int a_c = A_K_FAST ? (tid % 8) * 8 : ((tid & 3) + 4 * (tid >> 6)) * 8;
+    const int a_r = A_K_FAST ? tid / 8 : ((tid >> 2) & 15) * A_UNITS;
     const uint16_t *pa[A_UNITS];
     const int32_t *pn[A_UNITS];
     bool a_ok[A_UNITS];

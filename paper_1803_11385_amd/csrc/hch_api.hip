@@ -825,6 +825,9 @@ static GemmPlan plan_wgrad(int64_t n, int c_in, int c_out, int taps = 27, int gr
     p.bm = 128; p.wm = 4;
     const int64_t tiles = (int64_t)((Kc + 127) / 128) * ((c_out + p.bn - 1) / p.bn);
     int64_t want = std::max<int64_t>(1, 768 / tiles);   // one round of workgroups, 3 per CU
+    // bf16 kernel: a multiple of 8 slices, each XCD (32 CUs, 96 workgroups at a time) taking
+    // whole slices, if that still fills most of the chip
+    if (gran == hch::BF16_BK && tiles <= 96 && (96 / tiles) * tiles >= 64) want = 8 * (96 / tiles);
     want = std::min<int64_t>(want, std::max<int64_t>(1, (n + 255) / 256));
     int64_t rows = (n + want - 1) / want;
     rows = std::max<int64_t>(gran, (rows + gran - 1) / gran * gran);
@@ -927,7 +930,10 @@ static hch_status launch_gemm_bf16(const GemmPlan &p, const void *A, const void 
     const unsigned m_tiles = (unsigned)((M + p.bm - 1) / p.bm);
     const bool remap = (AMODE == hch::A_GATHER || AMODE == hch::A_ROWS) && m_tiles >= 256;
     const unsigned gx = remap ? (m_tiles / hch::NUM_XCD + 1) * hch::NUM_XCD : m_tiles;
-    const dim3 grid(gx, (unsigned)((N + p.bn - 1) / p.bn), (unsigned)p.splits);
+    const unsigned n_tiles = (unsigned)((N + p.bn - 1) / p.bn);
+    // reductions over the voxels cut into a multiple of 8 slices: one XCD per slice
+    const int flat = ((AMODE == hch::A_GATHER_T || AMODE == hch::A_COLS) && p.splits % (int)hch::NUM_XCD == 0) ? p.splits : 0;
+    const dim3 grid = flat ? dim3((unsigned)p.splits * m_tiles * n_tiles) : dim3(gx, n_tiles, (unsigned)p.splits);
     static int ids[4] = {-1, -1, -1, -1};
     const int cfg = p.bm == 64 ? 0 : (p.bn == 16 ? 1 : (p.bn == 32 ? 2 : 3));
     if (ids[cfg] < 0) {
@@ -940,7 +946,7 @@ static hch_status launch_gemm_bf16(const GemmPlan &p, const void *A, const void 
 #define HCH_BF16_CASE(BM_, BN_, WM_)                                                                                 \
     hipLaunchKernelGGL((hch::gemm_bf16_kernel<BM_, BN_, WM_, AMODE, B_KC>), grid, dim3(256), 0, s,                  \
                        (const uint16_t *)A, (const uint16_t *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split,     \
-                       c_split_stride, c_vec_ok, m_tiles, taps, b_wrap, b_tap_stride)
+                       c_split_stride, c_vec_ok, m_tiles, taps, b_wrap, b_tap_stride, flat)
     if (p.bm == 64) {
         if constexpr (AMODE == hch::A_ROWS || AMODE == hch::A_GATHER) HCH_BF16_CASE(64, 64, 2);
         else return fail(HCH_EINVAL, "gemm_bf16: 64-row tiles with a transposed A");
