@@ -77,31 +77,37 @@ def cpu_baseline(coords, offs, X0, W, u, max_shapes, budget_s=24.0):
             f"first {ns} of {len(offs) - 1} shapes, {passes} fwd+bwd passes, {total_t:.1f} s")
 
 
-def bf16_conv_bench(args, torch, hch, S):
-    """Forward, data gradient and weight gradient of a 64 -> 64 convolution, bf16 inputs, fp32
-    sums and outputs, on level 0 of the 512^3 / batch 4 workload (tables built on the device)."""
-    coords, offs, _ = S.config_batch(5)
-    lv = hch.hch_build_levels_device(coords, offs, 512, 1)
-    n, ci, co = lv.n(0), 64, 64
+def conv_bench(args, torch, hch, S):
+    """The three products of ONE convolution on the finest level of a per-kernel workload:
+    3 = 128^3 grid, batch 16, 32 -> 64, fp32; 5 = 512^3 grid, batch 4, 64 -> 64, bf16 inputs with
+    fp32 sums and outputs.  Tables built on the device; time per product from HIP events."""
+    cfg = args.conv_bench
+    u, ci, co, bf = {3: (128, 32, 64, False), 5: (512, 64, 64, True)}[cfg]
+    coords, offs, _ = S.config_batch(cfg)
+    lv = hch.hch_build_levels_device(coords, offs, u, 1)
+    n = lv.n(0)
     algo = hch.HCH_ALGO_FUSED if args.algo == "fused" else hch.HCH_ALGO_COLUMNS
-    B16 = hch.HCH_BF16
+    DT = hch.HCH_BF16 if bf else hch.HCH_F32
 
-    def bf16(a):
-        return torch.from_numpy(S.bf16_bits(S.to_bf16_grid(a)).view(np.int16)).to("cuda")
+    def put(a):
+        if bf:
+            return torch.from_numpy(S.bf16_bits(S.to_bf16_grid(a)).view(np.int16)).to("cuda")
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda")
 
-    X, G = bf16(S.gaussian((n, ci), 1.0, 5001)), bf16(S.gaussian((n, co), 1.0, 5003))
-    W = bf16(S.he_weights(ci, co, 5002))
+    seed = 1000 * cfg
+    X, G = put(S.gaussian((n, ci), 1.0, seed + 1)), put(S.gaussian((n, co), 1.0, seed + 3))
+    W = put(S.he_weights(ci, co, seed + 2))
     Y = torch.empty((n, co), dtype=torch.float32, device="cuda")
     dX = torch.empty((n, ci), dtype=torch.float32, device="cuda")
     dW = torch.empty((27, ci, co), dtype=torch.float32, device="cuda")
-    need = max(hch.hch_conv_workspace_bytes(lv, 0, ci, co, B16, k, algo)
+    need = max(hch.hch_conv_workspace_bytes(lv, 0, ci, co, DT, k, algo)
                for k in (hch.HCH_WS_FWD, hch.HCH_WS_BWD_DATA, hch.HCH_WS_BWD_WEIGHT))
     buf = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
     off = (-buf.data_ptr()) % 256
     ws = buf[off: off + need]
-    calls = (("forward", lambda: hch.hch_conv_fwd(lv, 0, B16, X, W, Y, ci, co, ws, algo)),
-             ("data_gradient", lambda: hch.hch_conv_bwd_data(lv, 0, B16, G, W, dX, ci, co, ws, algo)),
-             ("weight_gradient", lambda: hch.hch_conv_bwd_weight(lv, 0, B16, X, G, dW, ci, co, ws, algo)))
+    calls = (("forward", lambda: hch.hch_conv_fwd(lv, 0, DT, X, W, Y, ci, co, ws, algo)),
+             ("data_gradient", lambda: hch.hch_conv_bwd_data(lv, 0, DT, G, W, dX, ci, co, ws, algo)),
+             ("weight_gradient", lambda: hch.hch_conv_bwd_weight(lv, 0, DT, X, G, dW, ci, co, ws, algo)))
     flop = 2.0 * n * 27 * ci * co
     out = {}
     for name, fn in calls:
@@ -116,10 +122,10 @@ def bf16_conv_bench(args, torch, hch, S):
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / args.steps
         out[name] = {"ms": round(ms, 4), "tflops": round(flop / ms / 1e9, 1)}
-    print(json.dumps({"metric": "one 3x3x3 convolution 64 -> 64, bf16 inputs, fp32 sums: time per product", "unit": "ms",
-                      "products": out, "calls_timed": args.steps, "higher_is_better": False, "dtype": "bf16",
-                      "data": "synthetic", "algo": args.algo,
-                      "config": {"workload": f"512^3 grid, batch 4, two-voxel shells of 2-6 primitives, {n} voxels"}}))
+    print(json.dumps({"metric": f"one 3x3x3 convolution {ci} -> {co}: time per product", "unit": "ms",
+                      "products": out, "calls_timed": args.steps, "higher_is_better": False,
+                      "dtype": "bf16" if bf else "f32", "data": "synthetic", "algo": args.algo,
+                      "config": {"workload": f"{u}^3 grid, batch {len(offs) - 1}, random-primitive surfaces, {n} voxels"}}))
 
 
 def main():
@@ -143,9 +149,9 @@ def main():
     ap.add_argument("--build-bench", action="store_true",
                     help="time only the construction of the hash tables of the workload, on the host "
                          "(hch_build_levels) and on the device (hch_build_levels_device), and print that")
-    ap.add_argument("--bf16-conv-bench", action="store_true",
-                    help="time only the three products of one 64 -> 64 convolution with bf16 inputs on the "
-                         "finest level of the high-resolution workload (512^3 grid, batch 4), and print that")
+    ap.add_argument("--conv-bench", type=int, choices=[3, 5], default=0,
+                    help="time only the three products of one convolution on a per-kernel workload and print "
+                         "that: 3 = 128^3 grid, batch 16, 32 -> 64, fp32; 5 = 512^3 grid, batch 4, 64 -> 64, bf16")
     ap.add_argument("--algo", choices=["columns", "fused"], default="fused",
                     help="columns: hash2col -> GEMM -> col2hash through memory; fused: gathered GEMM operand")
     args = ap.parse_args()
@@ -160,8 +166,8 @@ def main():
     import synth_shapes as S
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    if args.bf16_conv_bench:
-        bf16_conv_bench(args, torch, hch, S)
+    if args.conv_bench:
+        conv_bench(args, torch, hch, S)
         return
     u, b = args.resolution, args.batch
     t0 = time.perf_counter()
