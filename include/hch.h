@@ -133,6 +133,23 @@ hch_status hch_build_levels_device(const int32_t *coords_xyz, const int64_t *mod
                                    void *stream, hch_levels **out);
 
 /*
+ * Level sets whose resolutions are in ratios other than 2 (Section 4: unlike an octree, a PSH can
+ * be generated on a grid of arbitrary resolution, which is what allows any stride):
+ *   resolution  grid side of the finest level, any integer 2 .. 32768
+ *   ratios      HOST [n_levels - 1], ratios[l] >= 2: level l+1 has side ceil(side_l / ratios[l]) and
+ *               holds the voxels floor(p / ratios[l]) of level l's voxels p (occupied iff one of the
+ *               ratios[l]^3 positions below it is), ordered by linear position per model
+ *   device_tables  0: tables constructed on the host as in hch_build_levels; else on the device
+ * Everything else as hch_build_levels.  child8 exists only between levels in ratio 2, and only
+ * there hch_pool_*, hch_relu_pool_*, hch_avgpool_*, hch_unpool_* apply (HCH_EUNSUPPORTED
+ * elsewhere); between any two levels use hch_field_build with hch_sconv_* and hch_spool_*.
+ */
+hch_status hch_build_levels_ratios(const int32_t *coords_xyz, const int64_t *model_offsets,
+                                   int32_t batch, int32_t resolution, int32_t n_levels,
+                                   const int32_t *ratios, int32_t device_tables,
+                                   void *stream, hch_levels **out);
+
+/*
  * The host half of hch_build_levels only: occupancy of every level, PSH construction and the
  * super tables, kept in host memory.  Touches no GPU.  The object serves hch_level_info (all
  * DEVICE pointers are NULL) and hch_free_levels; every other call rejects it with HCH_EINVAL.
@@ -292,9 +309,11 @@ hch_status hch_unpool_bwd(const hch_levels *levels, int32_t level_out, const flo
  * Convolutions with a general kernel side F, stride and padding (Algorithm 1 and 2 as the paper
  * states them, Section 3.3: receptive field [p*S - P, p*S - P + F - 1]^3 on the input level for
  * output voxel p; [p - (F-1)/2, p + (F-1)/2]^3 when S = 1), and 2x2x2 average pooling (Section 4:
- * a convolution whose weights all equal 1/F^3).  The levels of an hch_levels object halve the
- * resolution, so stride S = 1, 2, 4, 8 reads level_in and writes level_in + log2(S); other
- * resolution ratios are not supported.  F = 1..7; S = 1 needs odd F and P = (F-1)/2.
+ * a convolution whose weights all equal 1/F^3).  Stride S reads level_in and writes the level
+ * of the same hch_levels object whose grid is S times coarser: level_in + log2(S) when the levels
+ * halve the resolution (hch_build_levels), or wherever the ratios given to
+ * hch_build_levels_ratios multiply up to S; HCH_EINVAL if there is no such level.  F = 1..7;
+ * S = 1 needs odd F and P = (F-1)/2.
  *
  * hch_field_build fills the index rows of the traversal by hash lookups (the general form of
  * the "pre-stored neighbour information"); both are caller-owned DEVICE buffers, either may be
@@ -326,6 +345,33 @@ hch_status hch_sconv_bwd_data(const hch_levels *levels, int32_t level_in, int32_
                               hch_dtype dtype, const void *dY, const void *W, float *dX,
                               const int32_t *field_t, int32_t c_in, int32_t c_out, void *workspace,
                               size_t ws_bytes, void *stream);
+
+/*
+ * Pooling over general receptive fields (Section 4: pooling is a convolution-like traversal with
+ * stride S > 1, and "any stride sizes" are possible because a PSH can be built on a grid of any
+ * resolution), between level_in and the level S times coarser, through the index rows of
+ * hch_field_build(levels, level_in, F, S, pad, field, field_t):
+ *   hch_spool_max_fwd  Y[o][ch] = maximum of X over the occupied entries of field[o][:], argmax the
+ *                      entry's data index; rules as for hch_pool_fwd (first maximum in row order,
+ *                      NaN never replaces, empty field: 0 and -1)
+ *   hch_spool_max_bwd  dX[q][ch] = sum of dY[o][ch] over the outputs o = field_t[q][:] whose switch
+ *                      for ch is q (at most one when fields do not overlap, F <= S); dX is
+ *                      written completely
+ *   hch_spool_avg_fwd  Y[o] = (sum of the occupied entries' rows) / F^3     (weights 1/F^3)
+ *   hch_spool_avg_bwd  dX[q] = (sum of dY[o] over o = field_t[q][:]) / F^3
+ * X, dX DEVICE [N_in][c] float;  Y, dY DEVICE [N_out][c] float;  argmax DEVICE [N_out][c] int32.
+ * With F = 2, S = 2, pad = 0 on levels in ratio 2 the results equal hch_pool_* / hch_avgpool_*.
+ */
+hch_status hch_spool_max_fwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                             const float *X, const int32_t *field, float *Y, int32_t *argmax,
+                             int32_t c, void *stream);
+hch_status hch_spool_max_bwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                             const float *dY, const int32_t *argmax, const int32_t *field_t,
+                             float *dX, int32_t c, void *stream);
+hch_status hch_spool_avg_fwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                             const float *X, const int32_t *field, float *Y, int32_t c, void *stream);
+hch_status hch_spool_avg_bwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                             const float *dY, const int32_t *field_t, float *dX, int32_t c, void *stream);
 
 /*
  * 2x2x2 average pooling from level_in to level_in + 1 and its adjoint (the average-unpooling of

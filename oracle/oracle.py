@@ -153,14 +153,16 @@ class Level:
         return int(lib().orc_hash_slot(self.ref, int(v), int(p[0]), int(p[1]), int(p[2])))
 
 
-def coarsen(coords, model_offsets, ubar):
-    """Next coarser level of the hierarchy (Section 5.1: each level halves the
-    resolution): a coarse voxel is occupied iff one of its 8 children is; per model
-    the coarse voxels are ordered by their linear index (x*u+y)*u+z, ascending."""
-    uc = ubar // 2
+def coarsen(coords, model_offsets, ubar, ratio=2):
+    """Next coarser level of the hierarchy.  Section 5.1: each level halves the resolution
+    (ratio 2); Section 4: a PSH can be generated on a grid of arbitrary resolution, so any
+    integer ratio is possible: the grid has side ceil(ubar / ratio), a coarse voxel is occupied
+    iff one of the ratio^3 positions below it is; per model the coarse voxels are ordered by
+    their linear index (x*u+y)*u+z, ascending."""
+    uc = -(-ubar // ratio)
     out, offs = [], [0]
     for i in range(len(model_offsets) - 1):
-        c = coords[model_offsets[i]: model_offsets[i + 1]].astype(np.int64) // 2
+        c = coords[model_offsets[i]: model_offsets[i + 1]].astype(np.int64) // ratio
         lin = np.unique((c[:, 0] * uc + c[:, 1]) * uc + c[:, 2])
         cc = np.stack([lin // (uc * uc), (lin // uc) % uc, lin % uc], axis=1).astype(np.int32)
         out.append(cc)
@@ -168,14 +170,15 @@ def coarsen(coords, model_offsets, ubar):
     return np.concatenate(out, axis=0), np.asarray(offs, np.int64), uc
 
 
-def build_hierarchy(coords, model_offsets, ubar, n_levels):
-    """Level 0 = finest (caller's voxel order), level l has resolution ubar / 2^l."""
+def build_hierarchy(coords, model_offsets, ubar, n_levels, ratios=None):
+    """Level 0 = finest (caller's voxel order); level l+1 is ratios[l] times coarser than level l
+    (2 everywhere when ratios is None: resolution ubar / 2^l)."""
     levels = []
     c, o, u = np.ascontiguousarray(coords, np.int32), np.asarray(model_offsets, np.int64), ubar
     for l in range(n_levels):
         levels.append(Level(c, o, u))
         if l + 1 < n_levels:
-            c, o, u = coarsen(c, o, u)
+            c, o, u = coarsen(c, o, u, 2 if ratios is None else int(ratios[l]))
     return levels
 
 

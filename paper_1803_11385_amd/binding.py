@@ -18,7 +18,8 @@ __all__ = [
     "hch_pool_relu_bwd", "hch_deconv_fwd", "hch_deconv_bwd_data", "hch_deconv_bwd_weight",
     "hch_unpool_fwd", "hch_unpool_bwd", "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
     "hch_profile_reset", "hch_field_build", "hch_sconv_workspace_bytes", "hch_sconv_fwd", "hch_sconv_bwd_weight",
-    "hch_sconv_bwd_data", "hch_avgpool_fwd", "hch_avgpool_bwd",
+    "hch_sconv_bwd_data", "hch_avgpool_fwd", "hch_avgpool_bwd", "hch_build_levels_ratios",
+    "hch_spool_max_fwd", "hch_spool_max_bwd", "hch_spool_avg_fwd", "hch_spool_avg_bwd",
 ]
 
 HCH_F32, HCH_BF16 = 0, 1
@@ -38,7 +39,8 @@ exported_symbols = [
     "hch_pool_relu_bwd", "hch_deconv_fwd", "hch_deconv_bwd_data", "hch_deconv_bwd_weight",
     "hch_unpool_fwd", "hch_unpool_bwd", "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
     "hch_profile_reset", "hch_field_build", "hch_sconv_workspace_bytes", "hch_sconv_fwd", "hch_sconv_bwd_weight",
-    "hch_sconv_bwd_data", "hch_avgpool_fwd", "hch_avgpool_bwd",
+    "hch_sconv_bwd_data", "hch_avgpool_fwd", "hch_avgpool_bwd", "hch_build_levels_ratios",
+    "hch_spool_max_fwd", "hch_spool_max_bwd", "hch_spool_avg_fwd", "hch_spool_avg_bwd",
 ]
 
 
@@ -85,6 +87,11 @@ def load_library():
     L.hch_build_levels.argtypes = [vp, vp, i32, i32, i32, vp, C.POINTER(vp)]
     L.hch_build_levels_device.argtypes = [vp, vp, i32, i32, i32, vp, C.POINTER(vp)]
     L.hch_build_tables_host.argtypes = [vp, vp, i32, i32, i32, C.POINTER(vp)]
+    L.hch_build_levels_ratios.argtypes = [vp, vp, i32, i32, i32, vp, i32, vp, C.POINTER(vp)]
+    L.hch_spool_max_fwd.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp]
+    L.hch_spool_max_bwd.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp]
+    L.hch_spool_avg_fwd.argtypes = [vp, i32, i32, i32, vp, vp, vp, i32, vp]
+    L.hch_spool_avg_bwd.argtypes = [vp, i32, i32, i32, vp, vp, vp, i32, vp]
     L.hch_free_levels.argtypes = [vp]
     L.hch_free_levels.restype = None
     L.hch_num_levels.argtypes = [vp]
@@ -303,6 +310,18 @@ def hch_build_levels_device(coords, model_offsets, resolution, n_levels, stream=
     return Levels(h)
 
 
+def hch_build_levels_ratios(coords, model_offsets, resolution, ratios, device_tables=False, stream=None):
+    """Levels 0 .. len(ratios): level l+1 is ratios[l] times coarser than level l."""
+    coords, offs = _host_inputs(coords, model_offsets)
+    r = np.ascontiguousarray(np.asarray(ratios, dtype=np.int32).reshape(-1))
+    h = C.c_void_p()
+    _check(load_library().hch_build_levels_ratios(coords.ctypes.data, offs.ctypes.data, offs.size - 1,
+                                                  int(resolution), int(r.size) + 1,
+                                                  r.ctypes.data if r.size else None,
+                                                  1 if device_tables else 0, _stream(stream), C.byref(h)))
+    return Levels(h)
+
+
 def hch_build_tables_host(coords, model_offsets, resolution, n_levels):
     coords, offs = _host_inputs(coords, model_offsets)
     h = C.c_void_p()
@@ -443,6 +462,26 @@ def hch_avgpool_fwd(levels, level_in, X, Y, c, stream=None):
 
 def hch_avgpool_bwd(levels, level_in, dY, dX, c, stream=None):
     _check(load_library().hch_avgpool_bwd(levels.handle, level_in, _dp(dY), _dp(dX), c, _stream(stream)))
+
+
+def hch_spool_max_fwd(levels, level_in, F, stride, X, field, Y, argmax, c, stream=None):
+    _check(load_library().hch_spool_max_fwd(levels.handle, level_in, F, stride, _dp(X), _dp(field), _dp(Y),
+                                            _dp(argmax), c, _stream(stream)))
+
+
+def hch_spool_max_bwd(levels, level_in, F, stride, dY, argmax, field_t, dX, c, stream=None):
+    _check(load_library().hch_spool_max_bwd(levels.handle, level_in, F, stride, _dp(dY), _dp(argmax),
+                                            _dp(field_t), _dp(dX), c, _stream(stream)))
+
+
+def hch_spool_avg_fwd(levels, level_in, F, stride, X, field, Y, c, stream=None):
+    _check(load_library().hch_spool_avg_fwd(levels.handle, level_in, F, stride, _dp(X), _dp(field), _dp(Y), c,
+                                            _stream(stream)))
+
+
+def hch_spool_avg_bwd(levels, level_in, F, stride, dY, field_t, dX, c, stream=None):
+    _check(load_library().hch_spool_avg_bwd(levels.handle, level_in, F, stride, _dp(dY), _dp(field_t), _dp(dX), c,
+                                            _stream(stream)))
 
 
 def hch_relu_fwd(x, y, n, stream=None):

@@ -46,6 +46,7 @@ hch_status fail(hch_status st, const std::string &msg)
 // One level of the super-PSH, host and device side.
 struct Level {
     int32_t ubar = 0, b = 0;
+    int32_t ratio = 1;                         // side of the next finer level / side of this one (1 at level 0)
     int64_t n_total = 0, m_total = 0, r_total = 0;
     int32_t max_n = 0;                         // largest model of the level
     int64_t nbr_valid = 0;                     // occupied entries of nbr27 (incl. the centre)
@@ -150,7 +151,7 @@ static hch_status launch_index_lists(const hch_levels *hl, int l0, int l1, hipSt
         if (last > first) {
             double bytes = 0.0;   // per coarse voxel: position in, 8 indices out; the finer tables once
             for (int l = std::max(l0, 1); l < l1; ++l)
-                bytes += (double)hl->lv[l].n_total * 44.0 + (double)hl->lv[l - 1].m_total * 10.0 + (double)hl->lv[l - 1].r_total * 3.0;
+                if (hl->lv[l].ratio == 2) bytes += (double)hl->lv[l].n_total * 44.0 + (double)hl->lv[l - 1].m_total * 10.0 + (double)hl->lv[l - 1].r_total * 3.0;
             const unsigned n_tiles = (unsigned)(last - first);
             const unsigned grid = (n_tiles + hch::NUM_XCD - 1) / hch::NUM_XCD * hch::NUM_XCD;
             hch::LaunchTimer lt(HCH_KERNEL_ID("child_kernel"), s, bytes, 0.0);
@@ -374,17 +375,33 @@ static hch_status device_construct(hch_levels *hl, hipStream_t s)
     return HCH_OK;
 }
 
+// ratios == nullptr: every level halves the resolution (a power of two); else ratios[l] >= 2 is
+// the ratio between level l and level l+1, whose side is ceil(side_l / ratios[l])
 static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_offsets,
-                             int32_t batch, int32_t resolution, int32_t n_levels,
+                             int32_t batch, int32_t resolution, int32_t n_levels, const int32_t *ratios,
                              void *stream, bool with_device, bool device_tables, hch_levels **out)
 {
     if (out) *out = nullptr;
     if (!coords_xyz || !model_offsets || !out) return fail(HCH_EINVAL, "hch_build_levels: null pointer");
     if (batch <= 0 || batch > 65535) return fail(HCH_EINVAL, "hch_build_levels: batch must be 1..65535");
-    if (resolution < 2 || resolution > 32768 || (resolution & (resolution - 1)))
-        return fail(HCH_EINVAL, "hch_build_levels: resolution must be a power of two in 2..32768");
-    if (n_levels < 1 || (resolution >> (n_levels - 1)) < 1)
-        return fail(HCH_EINVAL, "hch_build_levels: n_levels out of range for this resolution");
+    std::vector<int32_t> side((size_t)std::max(n_levels, 1), resolution), ratio_of((size_t)std::max(n_levels, 1), 1);
+    if (!ratios) {
+        if (resolution < 2 || resolution > 32768 || (resolution & (resolution - 1)))
+            return fail(HCH_EINVAL, "hch_build_levels: resolution must be a power of two in 2..32768");
+        if (n_levels < 1 || (resolution >> (n_levels - 1)) < 1)
+            return fail(HCH_EINVAL, "hch_build_levels: n_levels out of range for this resolution");
+        for (int l = 1; l < n_levels; ++l) { side[l] = resolution >> l; ratio_of[l] = 2; }
+    } else {
+        if (resolution < 2 || resolution > 32768)
+            return fail(HCH_EINVAL, "hch_build_levels_ratios: resolution must be in 2..32768");
+        if (n_levels < 1) return fail(HCH_EINVAL, "hch_build_levels_ratios: n_levels must be at least 1");
+        for (int l = 1; l < n_levels; ++l) {
+            if (ratios[l - 1] < 2 || side[l - 1] < 2)
+                return fail(HCH_EINVAL, "hch_build_levels_ratios: every ratio must be >= 2 and every level but the last have side >= 2");
+            ratio_of[l] = ratios[l - 1];
+            side[l] = (side[l - 1] + ratios[l - 1] - 1) / ratios[l - 1];
+        }
+    }
     if (model_offsets[0] != 0) return fail(HCH_EINVAL, "hch_build_levels: model_offsets[0] must be 0");
     for (int v = 0; v < batch; ++v)
         if (model_offsets[v + 1] <= model_offsets[v])
@@ -435,7 +452,8 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
         // ---- occupancy of every level (host) ----
         for (int l = 0; l < n_levels; ++l) {
             Level &L = hl->lv[l];
-            L.ubar = resolution >> l;
+            L.ubar = side[l];
+            L.ratio = ratio_of[l];
             L.b = batch;
             L.N.assign((size_t)batch + 1, 0);
             if (l == 0) {
@@ -449,7 +467,7 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
                     for (;;) {
                         const int v = next_model.fetch_add(1);
                         if (v >= batch) break;
-                        hch::coarsen_model(Lf.coords.data() + 3 * Lf.N[v], Lf.N[v + 1] - Lf.N[v], Lf.ubar, per_model[v]);
+                        hch::coarsen_model(Lf.coords.data() + 3 * Lf.N[v], Lf.N[v + 1] - Lf.N[v], Lf.ubar, L.ratio, per_model[v]);
                     }
                 };
                 {
@@ -512,7 +530,7 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
                 if (hipMalloc((void **)&L.dnbr, (size_t)L.n_total * 27 * 4) != hipSuccess) {
                     L.dnbr = nullptr; st = fail(HCH_ENOMEM, "hipMalloc(nbr27) failed"); break;
                 }
-                if (l > 0 && hipMalloc((void **)&L.dchild, (size_t)L.n_total * 8 * 4) != hipSuccess) {
+                if (l > 0 && L.ratio == 2 && hipMalloc((void **)&L.dchild, (size_t)L.n_total * 8 * 4) != hipSuccess) {
                     L.dchild = nullptr; st = fail(HCH_ENOMEM, "hipMalloc(child8) failed"); break;
                 }
                 continue;
@@ -567,7 +585,7 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
             if (hipMalloc((void **)&L.dnbr, (size_t)L.n_total * 27 * 4) != hipSuccess) {
                 L.dnbr = nullptr; st = fail(HCH_ENOMEM, "hipMalloc(nbr27) failed"); break;
             }
-            if (l > 0 && hipMalloc((void **)&L.dchild, (size_t)L.n_total * 8 * 4) != hipSuccess) {
+            if (l > 0 && L.ratio == 2 && hipMalloc((void **)&L.dchild, (size_t)L.n_total * 8 * 4) != hipSuccess) {
                 L.dchild = nullptr; st = fail(HCH_ENOMEM, "hipMalloc(child8) failed"); break;
             }
             // the staging vectors die at the end of this iteration: finish the copies first
@@ -591,7 +609,7 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
                     const int32_t tiles = (int32_t)((L.N[v + 1] - L.N[v] + 255) / 256);
                     const size_t e = (size_t)l * batch + v;
                     hl->nbr_prefix[e + 1] = hl->nbr_prefix[e] + tiles;
-                    hl->child_prefix[e + 1] = hl->child_prefix[e] + (l > 0 ? tiles : 0);
+                    hl->child_prefix[e + 1] = hl->child_prefix[e] + (l > 0 && L.ratio == 2 ? tiles : 0);
                 }
             }
             if ((st = upload((void **)&hl->d_nbr_prefix, hl->nbr_prefix.data(), hl->nbr_prefix.size() * 4, s)) == HCH_OK)
@@ -635,21 +653,35 @@ extern "C" hch_status hch_build_levels(const int32_t *coords_xyz, const int64_t 
                                        int32_t batch, int32_t resolution, int32_t n_levels,
                                        void *stream, hch_levels **out)
 {
-    return build_impl(coords_xyz, model_offsets, batch, resolution, n_levels, stream, true, false, out);
+    return build_impl(coords_xyz, model_offsets, batch, resolution, n_levels, nullptr, stream, true, false, out);
 }
 
 extern "C" hch_status hch_build_levels_device(const int32_t *coords_xyz, const int64_t *model_offsets,
                                               int32_t batch, int32_t resolution, int32_t n_levels,
                                               void *stream, hch_levels **out)
 {
-    return build_impl(coords_xyz, model_offsets, batch, resolution, n_levels, stream, true, true, out);
+    return build_impl(coords_xyz, model_offsets, batch, resolution, n_levels, nullptr, stream, true, true, out);
+}
+
+extern "C" hch_status hch_build_levels_ratios(const int32_t *coords_xyz, const int64_t *model_offsets,
+                                              int32_t batch, int32_t resolution, int32_t n_levels,
+                                              const int32_t *ratios, int32_t device_tables,
+                                              void *stream, hch_levels **out)
+{
+    if (n_levels > 1 && !ratios) {
+        if (out) *out = nullptr;
+        return fail(HCH_EINVAL, "hch_build_levels_ratios: null ratios");
+    }
+    static const int32_t none[1] = {2};
+    return build_impl(coords_xyz, model_offsets, batch, resolution, n_levels, ratios ? ratios : none, stream, true,
+                      device_tables != 0, out);
 }
 
 extern "C" hch_status hch_build_tables_host(const int32_t *coords_xyz, const int64_t *model_offsets,
                                             int32_t batch, int32_t resolution, int32_t n_levels,
                                             hch_levels **out)
 {
-    return build_impl(coords_xyz, model_offsets, batch, resolution, n_levels, nullptr, false, false, out);
+    return build_impl(coords_xyz, model_offsets, batch, resolution, n_levels, nullptr, nullptr, false, false, out);
 }
 
 extern "C" hch_status hch_level_info(const hch_levels *levels, int32_t level, hch_level_desc *out)
@@ -1341,6 +1373,7 @@ extern "C" hch_status hch_pool_fwd(const hch_levels *levels, int32_t level_in, c
         return fail(HCH_EINVAL, "hch_pool_fwd: level_in must have a coarser level");
     if (!X || !Y || !argmax || c <= 0) return fail(HCH_EINVAL, "hch_pool_fwd: bad argument");
     const Level &Lc = levels->lv[level_in + 1];
+    if (Lc.ratio != 2) return fail(HCH_EUNSUPPORTED, "hch_pool_fwd: these two levels are not in ratio 2; use hch_field_build with hch_spool_* / hch_sconv_*");
     if (!Lc.dchild) return fail(HCH_EINVAL, "hch_pool_fwd: levels were built without device tables");
     const bool vec = c % 4 == 0 && aligned16(X) && aligned16(Y) && aligned16(argmax);
     const int64_t items = Lc.n_total * (vec ? c / 4 : c);
@@ -1368,6 +1401,7 @@ extern "C" hch_status hch_pool_bwd(const hch_levels *levels, int32_t level_in, c
         return fail(HCH_EINVAL, "hch_pool_bwd: level_in must have a coarser level");
     if (!dY || !argmax || !dX || c <= 0) return fail(HCH_EINVAL, "hch_pool_bwd: bad argument");
     const Level &Lc = levels->lv[level_in + 1];
+    if (Lc.ratio != 2) return fail(HCH_EUNSUPPORTED, "hch_pool_bwd: these two levels are not in ratio 2; use hch_field_build with hch_spool_* / hch_sconv_*");
     if (!Lc.dchild) return fail(HCH_EINVAL, "hch_pool_bwd: levels were built without device tables");
     const bool vec = c % 4 == 0 && aligned16(dY) && aligned16(dX) && aligned16(argmax);
     const int64_t items = Lc.n_total * 8 * (vec ? c / 4 : c);
@@ -1433,6 +1467,7 @@ extern "C" hch_status hch_unpool_bwd(const hch_levels *levels, int32_t level_out
         return fail(HCH_EINVAL, "hch_unpool_bwd: level_out must have a coarser level");
     if (!dY || !argmax || !dXc || c <= 0) return fail(HCH_EINVAL, "hch_unpool_bwd: bad argument");
     const Level &Lc = levels->lv[level_out + 1];
+    if (Lc.ratio != 2) return fail(HCH_EUNSUPPORTED, "hch_unpool_bwd: these two levels are not in ratio 2; use hch_field_build with hch_spool_* / hch_sconv_*");
     if (!Lc.dchild) return fail(HCH_EINVAL, "hch_unpool_bwd: levels were built without device tables");
     const int64_t items = Lc.n_total * c;
     if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hch_unpool_bwd: too large");
@@ -1454,6 +1489,7 @@ extern "C" hch_status hch_relu_pool_fwd(const hch_levels *levels, int32_t level_
     if (!Y || !P || !argmax || c <= 0) return fail(HCH_EINVAL, "hch_relu_pool_fwd: bad argument");
     const Level &Lc = levels->lv[level_in + 1];
     const Level &Lf = levels->lv[level_in];
+    if (Lc.ratio != 2) return fail(HCH_EUNSUPPORTED, "hch_relu_pool_fwd: these two levels are not in ratio 2; use hch_field_build with hch_spool_* / hch_sconv_*");
     if (!Lc.dchild) return fail(HCH_EINVAL, "hch_relu_pool_fwd: levels were built without device tables");
     const bool vec = c % 4 == 0 && aligned16(Y) && (!A || aligned16(A)) && aligned16(P) && aligned16(argmax);
     const int64_t items = Lc.n_total * (vec ? c / 4 : c);
@@ -1484,6 +1520,7 @@ extern "C" hch_status hch_pool_relu_bwd(const hch_levels *levels, int32_t level_
     if (!dP || !argmax || !A || !dY || c <= 0) return fail(HCH_EINVAL, "hch_pool_relu_bwd: bad argument");
     const Level &Lc = levels->lv[level_in + 1];
     const Level &Lf = levels->lv[level_in];
+    if (Lc.ratio != 2) return fail(HCH_EUNSUPPORTED, "hch_pool_relu_bwd: these two levels are not in ratio 2; use hch_field_build with hch_spool_* / hch_sconv_*");
     if (!Lc.dchild) return fail(HCH_EINVAL, "hch_pool_relu_bwd: levels were built without device tables");
     const bool vec = c % 4 == 0 && aligned16(dP) && aligned16(argmax) && aligned16(A) && aligned16(dY);
     const int64_t items = Lc.n_total * (vec ? c / 4 : c);
@@ -1513,15 +1550,21 @@ static hch_status field_levels(const hch_levels *levels, int32_t level_in, int32
 {
     if (!levels) return fail(HCH_EINVAL, std::string(who) + ": null levels");
     if (F < 1 || F > 7) return fail(HCH_EINVAL, std::string(who) + ": kernel side must be 1..7");
-    int shift = 0;
-    while ((1 << shift) < stride) ++shift;
-    if (stride < 1 || stride > 8 || (1 << shift) != stride)
-        return fail(HCH_EINVAL, std::string(who) + ": stride must be 1, 2, 4 or 8 (the levels halve the resolution)");
+    if (stride < 1) return fail(HCH_EINVAL, std::string(who) + ": stride must be positive");
     if (stride == 1 && (F % 2 == 0 || pad != (F - 1) / 2))
         return fail(HCH_EINVAL, std::string(who) + ": a stride-1 field is centred: odd kernel side, padding (F-1)/2");
     if (pad < 0 || pad >= F) return fail(HCH_EINVAL, std::string(who) + ": padding must be in [0, F)");
-    if (level_in < 0 || level_in + shift >= (int32_t)levels->lv.size())
+    if (level_in < 0 || level_in >= (int32_t)levels->lv.size())
         return fail(HCH_EINVAL, std::string(who) + ": level out of range");
+    // the output level: the one whose side relates to level_in's by exactly `stride`
+    int shift = 0;
+    int64_t prod = 1;
+    while (prod < stride && level_in + shift + 1 < (int32_t)levels->lv.size()) {
+        ++shift;
+        prod *= levels->lv[level_in + shift].ratio;
+    }
+    if (prod != stride)
+        return fail(HCH_EINVAL, std::string(who) + ": no level of this set is `stride` times coarser than level_in");
     *Li = &levels->lv[level_in];
     *Lo = &levels->lv[level_in + shift];
     if (!(*Li)->dslot3 || !(*Lo)->dslot3) return fail(HCH_EINVAL, std::string(who) + ": levels were built without device tables");
@@ -1683,6 +1726,98 @@ extern "C" hch_status hch_sconv_bwd_data(const hch_levels *levels, int32_t level
     return st;
 }
 
+// pooling over general receptive fields between level_in and the level `stride` times coarser
+static hch_status spool_args(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride, const void *a,
+                             const void *b, const void *idx, int32_t c, const Level **Li, const Level **Lo, const char *who)
+{
+    hch_status st = field_levels(levels, level_in, F, stride, stride == 1 ? (F - 1) / 2 : 0, Li, Lo, who);
+    if (st != HCH_OK) return st;
+    if (!a || !b || !idx || c <= 0) return fail(HCH_EINVAL, std::string(who) + ": null pointer or non-positive channel count");
+    if (std::max((*Li)->n_total, (*Lo)->n_total) * (int64_t)c > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, std::string(who) + ": too large");
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_spool_max_fwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                                        const float *X, const int32_t *field, float *Y, int32_t *argmax,
+                                        int32_t c, void *stream)
+{
+    const Level *Li, *Lo;
+    hch_status st = spool_args(levels, level_in, F, stride, X, Y, field, c, &Li, &Lo, "hch_spool_max_fwd");
+    if (st != HCH_OK) return st;
+    if (!argmax) return fail(HCH_EINVAL, "hch_spool_max_fwd: null argmax");
+    const int taps = F * F * F;
+    const bool vec = c % 4 == 0 && aligned16(X) && aligned16(Y) && aligned16(argmax);
+    const int64_t items = Lo->n_total * (vec ? c / 4 : c);
+    const double bytes = (double)Lo->n_total * (4.0 * taps + 8.0 * c) + (double)Li->n_total * 4.0 * c;
+    hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("field_pool_fwd_kernel<4>") : HCH_KERNEL_ID("field_pool_fwd_kernel<1>"),
+                        (hipStream_t)stream, bytes, 0.0);
+    if (vec)
+        hipLaunchKernelGGL(hch::field_pool_fwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                           X, field, Y, argmax, Lo->n_total, taps, c);
+    else
+        hipLaunchKernelGGL(hch::field_pool_fwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                           X, field, Y, argmax, Lo->n_total, taps, c);
+    HCH_LAUNCH_CHECK("field_pool_fwd_kernel");
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_spool_max_bwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                                        const float *dY, const int32_t *argmax, const int32_t *field_t,
+                                        float *dX, int32_t c, void *stream)
+{
+    const Level *Li, *Lo;
+    hch_status st = spool_args(levels, level_in, F, stride, dY, dX, field_t, c, &Li, &Lo, "hch_spool_max_bwd");
+    if (st != HCH_OK) return st;
+    if (!argmax) return fail(HCH_EINVAL, "hch_spool_max_bwd: null argmax");
+    const int taps = F * F * F;
+    const bool vec = c % 4 == 0 && aligned16(dY) && aligned16(dX) && aligned16(argmax);
+    const int64_t items = Li->n_total * (vec ? c / 4 : c);
+    const double bytes = (double)Li->n_total * (4.0 * taps + 4.0 * c) + (double)Lo->n_total * 8.0 * c;
+    hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("field_pool_bwd_kernel<4>") : HCH_KERNEL_ID("field_pool_bwd_kernel<1>"),
+                        (hipStream_t)stream, bytes, 0.0);
+    if (vec)
+        hipLaunchKernelGGL(hch::field_pool_bwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                           dY, argmax, field_t, dX, Li->n_total, taps, c);
+    else
+        hipLaunchKernelGGL(hch::field_pool_bwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+                           dY, argmax, field_t, dX, Li->n_total, taps, c);
+    HCH_LAUNCH_CHECK("field_pool_bwd_kernel");
+    return HCH_OK;
+}
+
+static hch_status launch_field_avg(const float *src, const int32_t *idx, float *dst, int64_t n_dst, int64_t n_src,
+                                   int taps, int c, hipStream_t s)
+{
+    const bool vec = c % 4 == 0 && aligned16(src) && aligned16(dst);
+    const int64_t items = n_dst * (vec ? c / 4 : c);
+    const double bytes = (double)n_dst * (4.0 * taps + 4.0 * c) + (double)n_src * 4.0 * c;
+    hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("field_avg_kernel<4>") : HCH_KERNEL_ID("field_avg_kernel<1>"), s, bytes, 0.0);
+    if (vec)
+        hipLaunchKernelGGL(hch::field_avg_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, s, src, idx, dst, n_dst, taps, c, 1.0f / taps);
+    else
+        hipLaunchKernelGGL(hch::field_avg_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, s, src, idx, dst, n_dst, taps, c, 1.0f / taps);
+    HCH_LAUNCH_CHECK("field_avg_kernel");
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_spool_avg_fwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                                        const float *X, const int32_t *field, float *Y, int32_t c, void *stream)
+{
+    const Level *Li, *Lo;
+    hch_status st = spool_args(levels, level_in, F, stride, X, Y, field, c, &Li, &Lo, "hch_spool_avg_fwd");
+    if (st != HCH_OK) return st;
+    return launch_field_avg(X, field, Y, Lo->n_total, Li->n_total, F * F * F, c, (hipStream_t)stream);
+}
+
+extern "C" hch_status hch_spool_avg_bwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
+                                        const float *dY, const int32_t *field_t, float *dX, int32_t c, void *stream)
+{
+    const Level *Li, *Lo;
+    hch_status st = spool_args(levels, level_in, F, stride, dY, dX, field_t, c, &Li, &Lo, "hch_spool_avg_bwd");
+    if (st != HCH_OK) return st;
+    return launch_field_avg(dY, field_t, dX, Li->n_total, Lo->n_total, F * F * F, c, (hipStream_t)stream);
+}
+
 extern "C" hch_status hch_avgpool_fwd(const hch_levels *levels, int32_t level_in, const float *X, float *Y,
                                       int32_t c, void *stream)
 {
@@ -1691,6 +1826,7 @@ extern "C" hch_status hch_avgpool_fwd(const hch_levels *levels, int32_t level_in
     if (!X || !Y || c <= 0) return fail(HCH_EINVAL, "hch_avgpool_fwd: bad argument");
     const Level &Lc = levels->lv[level_in + 1];
     const Level &Lf = levels->lv[level_in];
+    if (Lc.ratio != 2) return fail(HCH_EUNSUPPORTED, "hch_avgpool_fwd: these two levels are not in ratio 2; use hch_field_build with hch_spool_* / hch_sconv_*");
     if (!Lc.dchild) return fail(HCH_EINVAL, "hch_avgpool_fwd: levels were built without device tables");
     const bool vec = c % 4 == 0 && aligned16(X) && aligned16(Y);
     const int64_t items = Lc.n_total * (vec ? c / 4 : c);
@@ -1718,6 +1854,7 @@ extern "C" hch_status hch_avgpool_bwd(const hch_levels *levels, int32_t level_in
     if (!dY || !dX || c <= 0) return fail(HCH_EINVAL, "hch_avgpool_bwd: bad argument");
     const Level &Lc = levels->lv[level_in + 1];
     const Level &Lf = levels->lv[level_in];
+    if (Lc.ratio != 2) return fail(HCH_EUNSUPPORTED, "hch_avgpool_bwd: these two levels are not in ratio 2; use hch_field_build with hch_spool_* / hch_sconv_*");
     if (!Lc.dchild) return fail(HCH_EINVAL, "hch_avgpool_bwd: levels were built without device tables");
     const bool vec = c % 4 == 0 && aligned16(dY) && aligned16(dX);
     const int64_t items = Lc.n_total * (vec ? c / 4 : c);

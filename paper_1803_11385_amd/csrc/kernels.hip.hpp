@@ -916,6 +916,122 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(
     }
 }
 
+// Max-pooling over general receptive fields (Section 4: pooling is the strided traversal of
+// Algorithm 1 with the maximum taken instead of the inner product): field[o][0..taps) holds the
+// input indices of output voxel o's field in traversal order (-1 = empty).  Same rules as
+// pool_fwd_kernel: the first occupied entry seeds the maximum, a later one replaces it only
+// when strictly greater; an output voxel whose field is empty gets 0 and the switch -1.
+template <int VEC>
+__global__ __launch_bounds__(256) void field_pool_fwd_kernel(
+    const float *__restrict__ X, const int32_t *__restrict__ field, float *__restrict__ Y,
+    int32_t *__restrict__ argmax, int64_t n_out, int taps, int c)
+{
+    const int cu = c / VEC;
+    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (item >= n_out * cu) return;
+    const int64_t o = item / cu;
+    const int u = (int)(item - o * cu);
+    const int32_t *rows = field + o * taps;
+    float best[VEC];
+    int32_t arg[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { best[e] = 0.f; arg[e] = -1; }
+    const float *zsrc = reinterpret_cast<const float *>(g_zero16);
+    for (int k = 0; k < taps; ++k) {
+        const int32_t j = rows[k];
+        float v[VEC];
+        const float *s = j >= 0 ? X + (int64_t)j * c + u * VEC : zsrc;
+        if constexpr (VEC == 4) {
+            const f32x4 t = *reinterpret_cast<const f32x4 *>(s);
+            v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+        } else {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) v[e] = s[e];
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const bool take = (j >= 0) & ((arg[e] < 0) | (v[e] > best[e]));
+            best[e] = take ? v[e] : best[e];
+            arg[e] = take ? j : arg[e];
+        }
+    }
+    float *dy = Y + o * c + u * VEC;
+    int32_t *da = argmax + o * c + u * VEC;
+    if constexpr (VEC == 4) {
+        *reinterpret_cast<f32x4 *>(dy) = f32x4{best[0], best[1], best[2], best[3]};
+        *reinterpret_cast<int4 *>(da) = make_int4(arg[0], arg[1], arg[2], arg[3]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { dy[e] = best[e]; da[e] = arg[e]; }
+    }
+}
+
+// Its backward pass as a gather: field_t[q][0..taps) holds, per field row, the output voxel
+// whose field contains input voxel q at that row (-1 = none).  dX[q][ch] = sum of dY[o][ch]
+// over those o whose switch for channel ch is q, added in row order (with fields that do not
+// overlap there is at most one such o).  Every element of dX is written.
+template <int VEC>
+__global__ __launch_bounds__(256) void field_pool_bwd_kernel(
+    const float *__restrict__ dY, const int32_t *__restrict__ argmax, const int32_t *__restrict__ field_t,
+    float *__restrict__ dX, int64_t n_in, int taps, int c)
+{
+    const int cu = c / VEC;
+    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (item >= n_in * cu) return;
+    const int64_t q = item / cu;
+    const int u = (int)(item - q * cu);
+    const int32_t *rows = field_t + q * taps;
+    float acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+    for (int k = 0; k < taps; ++k) {
+        const int32_t o = rows[k];
+        if (o < 0) continue;
+        const float *g = dY + (int64_t)o * c + u * VEC;
+        const int32_t *a = argmax + (int64_t)o * c + u * VEC;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] += (a[e] == (int32_t)q) ? g[e] : 0.f;
+    }
+    float *d = dX + q * c + u * VEC;
+    if constexpr (VEC == 4) {
+        *reinterpret_cast<f32x4 *>(d) = f32x4{acc[0], acc[1], acc[2], acc[3]};
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) d[e] = acc[e];
+    }
+}
+
+// Average pooling over general receptive fields (Section 4: the convolution whose weights all
+// equal 1/F^3, channel by channel; empty entries add nothing): Y[o] = sum of the occupied
+// entries' rows, in row order, times `scale` = 1/taps.  TRANSPOSED = false: idx = field (rows of
+// the outputs, gathering X); true: idx = field_t (rows of the inputs, gathering dY) -- the
+// backward pass spreads scale * dY[o] over o's field, here summed per input voxel.
+template <int VEC>
+__global__ __launch_bounds__(256) void field_avg_kernel(
+    const float *__restrict__ src, const int32_t *__restrict__ idx, float *__restrict__ dst,
+    int64_t n_dst, int taps, int c, float scale)
+{
+    const int cu = c / VEC;
+    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (item >= n_dst * cu) return;
+    const int64_t o = item / cu;
+    const int u = (int)(item - o * cu);
+    const int32_t *rows = idx + o * taps;
+    float acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+    for (int k = 0; k < taps; ++k) {
+        const int32_t j = rows[k];
+        if (j < 0) continue;
+        const float *p = src + (int64_t)j * c + u * VEC;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] += p[e];
+    }
+    float *d = dst + o * c + u * VEC;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) d[e] = acc[e] * scale;
+}
+
 // ReLU followed by 2x2x2 max-pooling in one pass: A = max(Y, 0) is written for every child row
 // (each fine voxel is the child of exactly one coarse voxel, so all of A is covered) unless A is
 // null, and the maximum / switch are taken over the rectified values with the rules of

@@ -172,12 +172,12 @@ BuildResult build_model_tables(const int32_t *xyz, int64_t n, int ubar, ModelTab
     return BUILD_OK;
 }
 
-void coarsen_model(const int32_t *xyz, int64_t n, int ubar_fine, std::vector<int32_t> &out_xyz)
+void coarsen_model(const int32_t *xyz, int64_t n, int ubar_fine, int ratio, std::vector<int32_t> &out_xyz)
 {
-    const int64_t uc = ubar_fine / 2;
+    const int64_t uc = (ubar_fine + ratio - 1) / ratio;
     std::vector<int64_t> lin((size_t)n);
     for (int64_t i = 0; i < n; ++i)
-        lin[i] = ((int64_t)(xyz[3 * i] >> 1) * uc + (xyz[3 * i + 1] >> 1)) * uc + (xyz[3 * i + 2] >> 1);
+        lin[i] = ((int64_t)(xyz[3 * i] / ratio) * uc + (xyz[3 * i + 1] / ratio)) * uc + (xyz[3 * i + 2] / ratio);
     std::sort(lin.begin(), lin.end());
     lin.erase(std::unique(lin.begin(), lin.end()), lin.end());
     out_xyz.resize(lin.size() * 3);

@@ -25,7 +25,8 @@ int offset_side_next(int r, int m);       // smallest larger r with >= 2x the ce
 // xyz: n x 3 positions in [0, ubar); data index = row number.  Input is assumed validated.
 BuildResult build_model_tables(const int32_t *xyz, int64_t n, int ubar, ModelTables &out);
 
-// Parents of a model's voxels at half the resolution, unique, ordered by linear position.
-void coarsen_model(const int32_t *xyz, int64_t n, int ubar_fine, std::vector<int32_t> &out_xyz);
+// Parents floor(p / ratio) of a model's voxels on the grid of side ceil(ubar_fine / ratio), unique,
+// ordered by linear position.
+void coarsen_model(const int32_t *xyz, int64_t n, int ubar_fine, int ratio, std::vector<int32_t> &out_xyz);
 
 }  // namespace hch

@@ -386,3 +386,89 @@ def test_avgpool_vs_dense(oracle):
         np.testing.assert_allclose(dX[Li.N[v]:Li.N[v + 1]], want, rtol=0, atol=1e-13)
     # <avgpool(X), G> = <X, avgpool_bwd(G)>
     assert abs((Y * G).sum() - (X * dX).sum()) < 1e-9
+
+
+# --------------------------------------------------------------------------------------
+# levels in ratios other than 2 (Section 4: a PSH on a grid of any resolution allows any stride)
+# --------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("u,ratio", [(30, 3), (32, 3), (35, 5)])
+def test_ratio_levels_occupancy_and_max_pool(oracle, u, ratio):
+    """The coarse level of ratio r is the dense occupancy max-pooled with window r (ceil mode for
+    a side that r does not divide); max-pooling with F = S = r equals dense max_pool3d with
+    -inf at the empty voxels, the switches point at an occupied voxel below the right parent,
+    and the backward pass moves each gradient to its switch."""
+    coords, offs, _ = S.config_batch(2, batch=2, u=u)
+    lv = oracle.build_hierarchy(coords, offs, u, 2, ratios=[ratio])
+    Li, Lo = lv[0], lv[1]
+    uc = -(-u // ratio)
+    assert Lo.ubar == uc
+    c = 3
+    X = S.gaussian((Li.Ntot, c), 1.0, 131)
+    P, sw = oracle.pool_max_fwd(Li, Lo, oracle.to_paper_X(X), ratio, ratio, 0)
+    for v in range(Li.b):
+        ci = Li.coords[Li.N[v]:Li.N[v + 1]]
+        co = Lo.coords[Lo.N[v]:Lo.N[v + 1]]
+        occ = torch.zeros((1, u, u, u), dtype=torch.float64)
+        occ[0, ci[:, 0], ci[:, 1], ci[:, 2]] = 1.0
+        pooled = torch.nn.functional.max_pool3d(occ, ratio, ceil_mode=True)[0].numpy()
+        want_c = np.argwhere(pooled > 0)
+        assert np.array_equal(co, want_c)           # argwhere is in linear-index order too
+        vol = torch.full((c, u, u, u), -np.inf, dtype=torch.float64)
+        vol[:, ci[:, 0], ci[:, 1], ci[:, 2]] = torch.from_numpy(X[Li.N[v]:Li.N[v + 1]].astype(np.float64).T)
+        want = torch.nn.functional.max_pool3d(vol[None], ratio, ceil_mode=True)[0].numpy()
+        np.testing.assert_array_equal(P[:, Lo.N[v]:Lo.N[v + 1]], want[:, co[:, 0], co[:, 1], co[:, 2]])
+        s = sw[:, Lo.N[v]:Lo.N[v + 1]]
+        assert (s >= Li.N[v]).all() and (s < Li.N[v + 1]).all()
+        assert np.array_equal(Li.coords[s] // ratio, np.broadcast_to(co, (c,) + co.shape))
+    G = S.gaussian((Lo.Ntot, c), 1.0, 132)
+    dX = oracle.pool_max_bwd(Li.Ntot, oracle.to_paper_X(G), sw)
+    assert abs(dX.sum() - G.astype(np.float64).sum()) < 1e-9 and (dX != 0).sum() == G.size
+    assert np.array_equal(dX[np.arange(c)[:, None], sw], oracle.to_paper_X(G))
+
+
+@pytest.mark.parametrize("u,F,Ss,Sp", [(30, 3, 3, 0), (32, 5, 3, 1), (35, 5, 5, 0)])
+def test_ratio_levels_conv_vs_dense(oracle, u, F, Ss, Sp):
+    """Strided convolution and its gradients between levels in ratio 3 and 5 against dense
+    conv3d with that stride (a side the stride does not divide is zero-padded at the far end,
+    which is what an out-of-grid lookup returns), and average pooling against avg_pool3d."""
+    coords, offs, _ = S.config_batch(2, batch=2, u=u)
+    lv = oracle.build_hierarchy(coords, offs, u, 2, ratios=[Ss])
+    Li, Lo = lv[0], lv[1]
+    c_in, c_out = 2, 3
+    X = S.gaussian((Li.Ntot, c_in), 1.0, 141)
+    W = S.gaussian((F ** 3, c_in, c_out), 0.2, 142)
+    G = S.gaussian((Lo.Ntot, c_out), 1.0, 143)
+    Wp = oracle.to_paper_W(W)
+    up = Lo.ubar * Ss + F                   # padded side: every field of every output voxel inside
+    wt = torch.from_numpy(np.asarray(W, np.float64).reshape(F, F, F, c_in, c_out).transpose(4, 3, 0, 1, 2).copy())
+    wt.requires_grad_(True)
+    outs, vols = [], []
+    for v in range(Li.b):
+        ci = Li.coords[Li.N[v]:Li.N[v + 1]]
+        co = Lo.coords[Lo.N[v]:Lo.N[v + 1]]
+        vol = torch.zeros((c_in, up, up, up), dtype=torch.float64)
+        vol[:, ci[:, 0] + Sp, ci[:, 1] + Sp, ci[:, 2] + Sp] = torch.from_numpy(X[Li.N[v]:Li.N[v + 1]].astype(np.float64).T)
+        vol.requires_grad_(True)
+        y = torch.nn.functional.conv3d(vol[None], wt, stride=Ss)[0]
+        outs.append(y[:, co[:, 0], co[:, 1], co[:, 2]].T)
+        vols.append((vol, ci))
+    want = torch.cat(outs, 0)
+    Y = oracle.sconv_fwd(Li, Lo, oracle.to_paper_X(X), Wp, F, Ss, Sp).T
+    np.testing.assert_allclose(Y, want.detach().numpy(), rtol=0, atol=1e-11)
+    (want * torch.from_numpy(G)).sum().backward()
+    dW = oracle.sconv_bwd_weight(Li, Lo, oracle.to_paper_X(X), oracle.to_paper_X(G), F, Ss, Sp)
+    want_dW = wt.grad.numpy().transpose(2, 3, 4, 1, 0).reshape(F ** 3, c_in, c_out)
+    np.testing.assert_allclose(dW.reshape(c_out, c_in, F ** 3).transpose(2, 1, 0), want_dW, rtol=0, atol=1e-10)
+    dX = oracle.sconv_bwd_data(Li, Lo, oracle.to_paper_X(G), Wp, c_in, F, Ss, Sp).T
+    want_dX = np.concatenate([vol.grad.numpy()[:, ci[:, 0] + Sp, ci[:, 1] + Sp, ci[:, 2] + Sp].T for vol, ci in vols], 0)
+    np.testing.assert_allclose(dX, want_dX, rtol=0, atol=1e-11)
+    if F == Ss and Sp == 0:
+        A = oracle.avgpool_fwd(Li, Lo, oracle.to_paper_X(X), F, Ss, Sp).T
+        for v in range(Li.b):
+            vol, ci = vols[v]
+            co = Lo.coords[Lo.N[v]:Lo.N[v + 1]]
+            a = torch.nn.functional.avg_pool3d(vol.detach()[None], F)[0].numpy()
+            np.testing.assert_allclose(A[Lo.N[v]:Lo.N[v + 1]], a[:, co[:, 0], co[:, 1], co[:, 2]].T, rtol=0, atol=1e-13)
+        dA = oracle.avgpool_bwd(Li, Lo, oracle.to_paper_X(G[:, :c_in]), F, Ss, Sp).T
+        assert abs((A * G[:, :c_in]).sum() - (X * dA).sum()) < 1e-9
