@@ -1596,14 +1596,17 @@ extern "C" hch_status hch_field_build(const hch_levels *levels, int32_t level_in
     return HCH_OK;
 }
 
-// workspace of the three products of a general convolution: [ transposed weights (bwd_data) |
-// split partial sums ]
+// workspace of the three products of a general convolution: [ transposed weights (bwd_data on one
+// level) or the column-matrix gradient (bwd_data between two levels) | split partial sums ]
 static WsLayout sconv_layout(const Level &Li, const Level &Lo, int taps, int c_in, int c_out, hch_dtype dtype, hch_ws_kind kind)
 {
     WsLayout w{0, 0};
     if (kind == HCH_WS_FWD) {
         const GemmPlan p = plan_rows(Lo.n_total, c_out, taps * c_in, true, k_gran(dtype));
         if (p.splits > 1) w.part_bytes = round_up((size_t)p.splits * Lo.n_total * c_out * 4, 256);
+    } else if (kind == HCH_WS_BWD_DATA && &Li != &Lo) {
+        // between two levels: the gradient of the column matrix, [N_out][taps*c_in] floats
+        w.first_bytes = round_up((size_t)Lo.n_total * taps * c_in * 4, 256);
     } else if (kind == HCH_WS_BWD_DATA) {
         const GemmPlan p = plan_rows(Li.n_total, c_in, taps * c_out, true, k_gran(dtype));
         w.first_bytes = round_up((size_t)taps * c_in * c_out * elem_size(dtype), 256);
@@ -1703,6 +1706,31 @@ extern "C" hch_status hch_sconv_bwd_data(const hch_levels *levels, int32_t level
     const int64_t n = Li->n_total, wn = (int64_t)taps * c_in * c_out;
     const double es = elem_size(dtype);
     const WsLayout w = sconv_layout(*Li, *Lo, taps, c_in, c_out, dtype, HCH_WS_BWD_DATA);
+    if (Li != Lo) {
+        // Between two levels only about one field row in stride^3 of an input voxel has an owner,
+        // so the gathered product below would multiply mostly zeros.  Here the paper's own order
+        // is the cheaper one: dcol[N_out][taps*c_in] = dY . W^T (Eq.8), then col2hash (Algorithm
+        // 2) as a gather through field_t.
+        float *dcol = (float *)workspace;
+        const int Kc = taps * c_in;
+        const int64_t no = Lo->n_total;
+        const GemmPlan pc = plan_rows(no, Kc, c_out, false, k_gran(dtype));
+        const double gbytes = es * ((double)no * c_out + (double)wn) + 4.0 * (double)no * Kc;
+        st = launch_gemm<hch::A_ROWS, true>(dtype, pc, dY, W, dcol, nullptr, (int)no, Kc, c_out, c_out, c_out, Kc, 0, gbytes, s);
+        if (st != HCH_OK) return st;
+        const bool vec = c_in % 4 == 0 && aligned16(dX);
+        const int64_t items = n * (vec ? c_in / 4 : c_in);
+        if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hch_sconv_bwd_data: too large");
+        // per input voxel: its index row, one piece of dcol per owner (about taps / stride^3), its row out
+        const double cbytes = (double)n * (4.0 * taps + 4.0 * c_in + 4.0 * c_in * taps / ((double)stride * stride * stride));
+        hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("field_col2hash_kernel<4>") : HCH_KERNEL_ID("field_col2hash_kernel<1>"), s, cbytes, 0.0);
+        if (vec)
+            hipLaunchKernelGGL(hch::field_col2hash_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, s, dcol, field_t, dX, n, taps, c_in);
+        else
+            hipLaunchKernelGGL(hch::field_col2hash_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, s, dcol, field_t, dX, n, taps, c_in);
+        HCH_LAUNCH_CHECK("field_col2hash_kernel");
+        return HCH_OK;
+    }
     void *Wt = workspace;
     float *part = (float *)((char *)workspace + w.first_bytes);
     // dX[i] = sum over rows of dY[field_t[i][row]] . W[row]^T: a gathered product over the output

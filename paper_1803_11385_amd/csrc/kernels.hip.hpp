@@ -1001,6 +1001,57 @@ __global__ __launch_bounds__(256) void field_pool_bwd_kernel(
     }
 }
 
+// col2hash for a general receptive field (Algorithm 2), as a gather: dX[q][:] = sum over the
+// field rows r with o = field_t[q][r] >= 0 of dcol[o][r*c + :], added in row order (no atomics,
+// reproducible).  dcol is [N_out][taps*c]; every element of dX is written.
+template <int VEC>
+__global__ __launch_bounds__(256) void field_col2hash_kernel(
+    const float *__restrict__ dcol, const int32_t *__restrict__ field_t, float *__restrict__ dX,
+    int64_t n_in, int taps, int c)
+{
+    const int cu = c / VEC;
+    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (item >= n_in * cu) return;
+    const int64_t q = item / cu;
+    const int u = (int)(item - q * cu);
+    const int32_t *rows = field_t + q * taps;
+    const int64_t ld = (int64_t)taps * c;
+    float acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+    const float *zsrc = reinterpret_cast<const float *>(g_zero16);
+    // nine rows at a time: their indices, then their pieces (a constant block of zeros where a
+    // row has no owner), with no branch between the loads
+    for (int r0 = 0; r0 < taps; r0 += 9) {
+        int32_t o[9];
+#pragma unroll
+        for (int j = 0; j < 9; ++j) o[j] = *(r0 + j < taps ? rows + r0 + j : &g_minus1);
+        float v[9][VEC];
+#pragma unroll
+        for (int j = 0; j < 9; ++j) {
+            const float *p = o[j] >= 0 ? dcol + o[j] * ld + (r0 + j) * c + u * VEC : zsrc;
+            if constexpr (VEC == 4) {
+                const f32x4 t = *reinterpret_cast<const f32x4 *>(p);
+                v[j][0] = t[0]; v[j][1] = t[1]; v[j][2] = t[2]; v[j][3] = t[3];
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) v[j][e] = p[e];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 9; ++j)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] += v[j][e];
+    }
+    float *d = dX + q * c + u * VEC;
+    if constexpr (VEC == 4) {
+        *reinterpret_cast<f32x4 *>(d) = f32x4{acc[0], acc[1], acc[2], acc[3]};
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) d[e] = acc[e];
+    }
+}
+
 // Average pooling over general receptive fields (Section 4: the convolution whose weights all
 // equal 1/F^3, channel by channel; empty entries add nothing): Y[o] = sum of the occupied
 // entries' rows, in row order, times `scale` = 1/taps.  TRANSPOSED = false: idx = field (rows of
