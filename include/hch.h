@@ -203,8 +203,14 @@ hch_status hch_col2hash(const hch_levels *levels, int32_t level, const float *dc
  *   HCH_ALGO_COLUMNS  the paper's three steps: hash2col writes the column matrix to the
  *                     workspace, a dense GEMM consumes it, col2hash folds gradients back.
  *   HCH_ALGO_FUSED    the same products with the column matrix gathered through the index rows
- *                     straight into the GEMM's operand tile, so it never goes to memory.  */
-typedef enum { HCH_ALGO_COLUMNS = 0, HCH_ALGO_FUSED = 1 } hch_algo;
+ *                     straight into the GEMM's operand tile, so it never goes to memory.
+ *   HCH_ALGO_COLUMNS_RESIDENT  hch_conv_bwd_weight only: as HCH_ALGO_COLUMNS, but the workspace
+ *                     still holds the column matrix of X that hch_conv_fwd(HCH_ALGO_COLUMNS) left
+ *                     at its start (same level, c_in, dtype and X; a workspace of at least the
+ *                     HCH_WS_FWD size, so that the forward pass ran in one piece, and not used by
+ *                     another call since), so hash2col is not run again.  The caller vouches for
+ *                     the contents; sizes as for HCH_ALGO_COLUMNS.  */
+typedef enum { HCH_ALGO_COLUMNS = 0, HCH_ALGO_FUSED = 1, HCH_ALGO_COLUMNS_RESIDENT = 2 } hch_algo;
 
 typedef enum {
     HCH_WS_FWD = 0,         /* hch_conv_fwd: everything in one pass                            */

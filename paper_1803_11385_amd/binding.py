@@ -10,7 +10,7 @@ import numpy as np
 __all__ = [
     "HchError", "Levels", "LevelInfo", "HCH_F32", "HCH_BF16",
     "HCH_WS_FWD", "HCH_WS_BWD_DATA", "HCH_WS_BWD_WEIGHT", "HCH_WS_MIN",
-    "HCH_ALGO_COLUMNS", "HCH_ALGO_FUSED",
+    "HCH_ALGO_COLUMNS", "HCH_ALGO_FUSED", "HCH_ALGO_COLUMNS_RESIDENT",
     "library_path", "load_library", "exported_symbols",
     "hch_build_levels", "hch_build_levels_device", "hch_build_tables_host", "hch_build_neighbours",
     "hch_build_neighbours_range", "hch_hash2col", "hch_col2hash", "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data",
@@ -24,7 +24,7 @@ __all__ = [
 
 HCH_F32, HCH_BF16 = 0, 1
 HCH_WS_FWD, HCH_WS_BWD_DATA, HCH_WS_BWD_WEIGHT, HCH_WS_MIN = 0, 1, 2, 3
-HCH_ALGO_COLUMNS, HCH_ALGO_FUSED = 0, 1
+HCH_ALGO_COLUMNS, HCH_ALGO_FUSED, HCH_ALGO_COLUMNS_RESIDENT = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIBPATH = os.path.join(_HERE, "libhch.so")

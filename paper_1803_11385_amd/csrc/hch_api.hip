@@ -1140,6 +1140,7 @@ extern "C" size_t hch_conv_workspace_bytes(const hch_levels *levels, int32_t lev
                                            int32_t c_out, hch_dtype dtype, hch_ws_kind kind, hch_algo algo)
 {
     if (!levels || level < 0 || level >= (int32_t)levels->lv.size() || c_in <= 0 || c_out <= 0) return 0;
+    if (algo == HCH_ALGO_COLUMNS_RESIDENT) algo = HCH_ALGO_COLUMNS;
     if (algo != HCH_ALGO_COLUMNS && algo != HCH_ALGO_FUSED) return 0;
     const Level &L = levels->lv[level];
     if (kind == HCH_WS_MIN) {
@@ -1330,6 +1331,8 @@ extern "C" hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t leve
                                           void *stream)
 {
     const Level *L;
+    const bool resident = algo == HCH_ALGO_COLUMNS_RESIDENT;     // the column matrix is in the workspace already
+    if (resident) algo = HCH_ALGO_COLUMNS;
     hch_status st = conv_args(levels, level, dtype, X, dY, dW, c_in, c_out, workspace, algo, &L, "hch_conv_bwd_weight");
     if (st != HCH_OK) return st;
     if (ws_bytes < hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, HCH_WS_BWD_WEIGHT, algo))
@@ -1351,8 +1354,10 @@ extern "C" hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t leve
                                                  L->dnbr, Kc, c_out, (int)n, c_in, c_out, c_out, wsize, bytes, s);
     } else {
         void *col = workspace;
-        st = do_hash2col(*L, dtype, X, c_in, 0, n, col, s);
-        if (st != HCH_OK) return st;
+        if (!resident) {
+            st = do_hash2col(*L, dtype, X, c_in, 0, n, col, s);
+            if (st != HCH_OK) return st;
+        }
         const double bytes = es * ((double)n * Kc + (double)n * c_out) + 4.0 * (double)wsize * p.splits;
         st = launch_gemm<hch::A_COLS, false>(dtype, p, col, dY, dst, nullptr,
                                              Kc, c_out, (int)n, Kc, c_out, c_out, wsize, bytes, s);

@@ -19,8 +19,11 @@ class Encoder:
     `levels` must hold L+1 levels.  All buffers are allocated once here."""
 
     def __init__(self, levels, channels, algo=B.HCH_ALGO_COLUMNS, device="cuda", fuse_pointwise=True,
-                 two_streams=False):
+                 two_streams=False, keep_columns=True):
         self.levels, self.channels, self.algo = levels, list(channels), algo
+        # columns algorithm: every level keeps the column matrix of its forward pass (1 GB in all
+        # for the 256^3 x 8 workload) and the weight gradient reads it instead of gathering again
+        self.keep_columns = keep_columns and algo == B.HCH_ALGO_COLUMNS
         self.fuse_pointwise = fuse_pointwise       # ReLU+pool (and their backward) as one call each
         # backward: the weight gradient of a level runs on a second stream (default priority)
         # beside the data gradient; both only read dY of that level
@@ -49,6 +52,11 @@ class Encoder:
             for kind in (B.HCH_WS_FWD, B.HCH_WS_BWD_DATA, B.HCH_WS_BWD_WEIGHT):
                 need = max(need, B.hch_conv_workspace_bytes(levels, l, ch[l], ch[l + 1], B.HCH_F32, kind, algo))
         self.ws = _aligned_bytes(need, device)
+        self.ws_col = None
+        if self.keep_columns:
+            self.ws_col = [_aligned_bytes(max(B.hch_conv_workspace_bytes(levels, l, ch[l], ch[l + 1], B.HCH_F32, k, algo)
+                                              for k in (B.HCH_WS_FWD, B.HCH_WS_BWD_WEIGHT)), device)
+                           for l in range(self.L)]
         if two_streams:
             need_w = max(B.hch_conv_workspace_bytes(levels, l, ch[l], ch[l + 1], B.HCH_F32, B.HCH_WS_BWD_WEIGHT, algo)
                          for l in range(self.L))
@@ -78,8 +86,8 @@ class Encoder:
     def forward(self):
         ch = self.channels
         for l in range(self.L):
-            B.hch_conv_fwd(self.levels, l, B.HCH_F32, self.X[l], self.W[l], self.Y[l], ch[l], ch[l + 1], self.ws,
-                           self.algo)
+            B.hch_conv_fwd(self.levels, l, B.HCH_F32, self.X[l], self.W[l], self.Y[l], ch[l], ch[l + 1],
+                           self.ws_col[l] if self.keep_columns else self.ws, self.algo)
             if l == 0 and self.two_streams:
                 torch.cuda.current_stream().wait_event(self.coarse_ready)
             if self.fuse_pointwise:
@@ -97,14 +105,16 @@ class Encoder:
             else:
                 B.hch_pool_bwd(self.levels, l, self.dX[l + 1], self.sw[l], self.dA[l], ch[l + 1])
                 B.hch_relu_bwd(self.A[l], self.dA[l], self.dY[l], self.dY[l].numel())
+            walgo = B.HCH_ALGO_COLUMNS_RESIDENT if self.keep_columns else self.algo
             if self.two_streams:
                 self.ready[l].record(main)
                 self.side.wait_event(self.ready[l])
                 B.hch_conv_bwd_weight(self.levels, l, B.HCH_F32, self.X[l], self.dY[l], self.dW[l], ch[l], ch[l + 1],
-                                      self.ws_side, self.algo, stream=self.side.cuda_stream)
+                                      self.ws_col[l] if self.keep_columns else self.ws_side, walgo,
+                                      stream=self.side.cuda_stream)
             else:
                 B.hch_conv_bwd_weight(self.levels, l, B.HCH_F32, self.X[l], self.dY[l], self.dW[l], ch[l], ch[l + 1],
-                                      self.ws, self.algo)
+                                      self.ws_col[l] if self.keep_columns else self.ws, walgo)
             B.hch_conv_bwd_data(self.levels, l, B.HCH_F32, self.dY[l], self.W[l], self.dX[l], ch[l], ch[l + 1], self.ws,
                                 self.algo)
         if self.two_streams:

@@ -332,6 +332,29 @@ def test_error_paths(case_sphere):
     assert ei.value.status == 1
 
 
+def test_weight_gradient_from_resident_columns(case_small):
+    """The weight gradient computed from the column matrix that the forward pass left in the
+    workspace equals, bit for bit, the one that gathers the columns again; the option is
+    refused by the other calls."""
+    case = case_small
+    n, ci, co = case.olv[0].Ntot, 16, 32
+    F32, CO, RES = hch.HCH_F32, hch.HCH_ALGO_COLUMNS, hch.HCH_ALGO_COLUMNS_RESIDENT
+    X, W, G = dev(S.gaussian((n, ci), 1.0, 61)), dev(S.gaussian((27, ci, co), 0.1, 62)), dev(S.gaussian((n, co), 1.0, 63))
+    ws = workspace(max(hch.hch_conv_workspace_bytes(case.glv, 0, ci, co, F32, k, a)
+                       for k in (hch.HCH_WS_FWD, hch.HCH_WS_BWD_WEIGHT) for a in (CO, RES)))
+    Y = torch.empty((n, co), dtype=torch.float32, device="cuda")
+    hch.hch_conv_fwd(case.glv, 0, F32, X, W, Y, ci, co, ws, CO)
+    d1 = torch.full((27, ci, co), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_conv_bwd_weight(case.glv, 0, F32, X, G, d1, ci, co, ws, RES)
+    d2 = torch.full((27, ci, co), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_conv_bwd_weight(case.glv, 0, F32, X, G, d2, ci, co, ws, CO)
+    assert torch.equal(d1, d2)
+    for fn, args in ((hch.hch_conv_fwd, (X, W, Y)), (hch.hch_conv_bwd_data, (G, W, torch.empty((n, ci), dtype=torch.float32, device="cuda")))):
+        with pytest.raises(hch.HchError) as ei:
+            fn(case.glv, 0, F32, *args, ci, co, ws, RES)
+        assert ei.value.status == 1
+
+
 # --------------------------------------------------------------------------------------
 # bf16 inputs, fp32 accumulation
 # --------------------------------------------------------------------------------------
