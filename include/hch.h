@@ -233,6 +233,11 @@ size_t hch_conv_workspace_bytes(const hch_levels *levels, int32_t level, int32_t
  * Convolution forward (Eq.2 = Eq.3):  Y = hash2col(X) . W
  *   X  DEVICE [N_l][c_in], W DEVICE [27][c_in][c_out]  (dtype);  Y DEVICE [N_l][c_out] float,
  *   overwritten.  workspace DEVICE, ws_bytes as above, 256-byte aligned.  No bias.
+ * Errors of the three convolution calls: HCH_EINVAL (null pointer, channel count <= 0, level,
+ * dtype or algorithm unknown, workspace misaligned, 27*c_in*c_out >= 2^31), HCH_EWORKSPACE
+ * (ws_bytes below the required size), HCH_EUNSUPPORTED (N_l >= 2^31/64, or a feature matrix of
+ * 2^31 elements or more, N_l * max(c_in, c_out): rows are indexed with 32 bits), HCH_EHIP (a
+ * launch failed).  Nothing is written on error.
  */
 hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_dtype dtype,
                         const void *X, const void *W, float *Y, int32_t c_in, int32_t c_out,

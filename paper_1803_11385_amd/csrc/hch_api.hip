@@ -1178,6 +1178,9 @@ static hch_status conv_args(const hch_levels *levels, int32_t level, hch_dtype d
         return fail(HCH_EINVAL, std::string(who) + ": workspace must be 256-byte aligned");
     if ((*L)->n_total >= ((int64_t)1 << 31) / 64)
         return fail(HCH_EUNSUPPORTED, std::string(who) + ": too many voxels");
+    // the kernels index feature rows with 32 bits: voxel * channels + channel
+    if ((*L)->n_total * (int64_t)std::max(c_in, c_out) >= ((int64_t)1 << 31))
+        return fail(HCH_EUNSUPPORTED, std::string(who) + ": a feature matrix of more than 2^31 elements");
     return HCH_OK;
 }
 
@@ -1647,6 +1650,8 @@ static hch_status sconv_args(const hch_levels *levels, int32_t level_in, int32_t
     if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(HCH_EINVAL, std::string(who) + ": workspace must be 256-byte aligned");
     if (std::max((*Li)->n_total, (*Lo)->n_total) >= ((int64_t)1 << 31) / 512)
         return fail(HCH_EUNSUPPORTED, std::string(who) + ": too many voxels");
+    if (std::max((*Li)->n_total, (*Lo)->n_total) * (int64_t)std::max(c_in, c_out) >= ((int64_t)1 << 31))
+        return fail(HCH_EUNSUPPORTED, std::string(who) + ": a feature matrix of more than 2^31 elements");
     if (ws_bytes < hch_sconv_workspace_bytes(levels, level_in, F, stride, c_in, c_out, dtype, kind))
         return fail(HCH_EWORKSPACE, std::string(who) + ": workspace too small");
     return HCH_OK;
