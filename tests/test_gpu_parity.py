@@ -482,29 +482,33 @@ def test_pool_nan_and_negative_values(oracle, case_batch64):
 # --------------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("algo", ALGOS, ids=ALGO_IDS)
-@pytest.mark.parametrize("c_in,c_out", [(32, 16), (5, 3)])
-def test_deconv(oracle, case_small, c_in, c_out, algo):
+@pytest.mark.parametrize("c_in,c_out,bf16", [(32, 16, False), (5, 3, False), (64, 32, True), (16, 64, True)])
+def test_deconv(oracle, case_small, c_in, c_out, bf16, algo):
     case = case_small
     L = case.olv[1]
     n = L.Ntot
     X = S.gaussian((n, c_in), 1.0, 81)
     W = S.gaussian((27, c_out, c_in), 0.1, 82)         # forward conv c_out -> c_in, transposed here
     G = S.gaussian((n, c_out), 1.0, 83)
+    if bf16:
+        X, W, G = S.to_bf16_grid(X), S.to_bf16_grid(W), S.to_bf16_grid(G)
     Xp, Wp, Gp = oracle.to_paper_X(X), oracle.to_paper_W(W), oracle.to_paper_X(G)
-    F32 = hch.HCH_F32
+    DT = hch.HCH_BF16 if bf16 else hch.HCH_F32
+    put = (lambda a: dev(S.bf16_bits(a).view(np.int16))) if bf16 else dev
+    tol = 2e-2 if bf16 else TOL_F32
 
     def ws(kind):
-        return workspace(hch.hch_conv_workspace_bytes(case.glv, 1, c_out, c_in, F32, kind, algo))
+        return workspace(hch.hch_conv_workspace_bytes(case.glv, 1, c_out, c_in, DT, kind, algo))
 
     Y = torch.full((n, c_out), float("nan"), dtype=torch.float32, device="cuda")
-    hch.hch_deconv_fwd(case.glv, 1, F32, dev(X), dev(W), Y, c_in, c_out, ws(hch.HCH_WS_BWD_DATA), algo)
-    assert_close(Y.cpu().numpy(), oracle.deconv_fwd(L, Xp, Wp).T, what="deconv fwd")
+    hch.hch_deconv_fwd(case.glv, 1, DT, put(X), put(W), Y, c_in, c_out, ws(hch.HCH_WS_BWD_DATA), algo)
+    assert_close(Y.cpu().numpy(), oracle.deconv_fwd(L, Xp, Wp).T, tol=tol, what="deconv fwd")
     dX = torch.full((n, c_in), float("nan"), dtype=torch.float32, device="cuda")
-    hch.hch_deconv_bwd_data(case.glv, 1, F32, dev(G), dev(W), dX, c_in, c_out, ws(hch.HCH_WS_FWD), algo)
-    assert_close(dX.cpu().numpy(), oracle.conv_fwd(L, Gp, Wp).T, what="deconv bwd data")
+    hch.hch_deconv_bwd_data(case.glv, 1, DT, put(G), put(W), dX, c_in, c_out, ws(hch.HCH_WS_FWD), algo)
+    assert_close(dX.cpu().numpy(), oracle.conv_fwd(L, Gp, Wp).T, tol=tol, what="deconv bwd data")
     dW = torch.full((27, c_out, c_in), float("nan"), dtype=torch.float32, device="cuda")
-    hch.hch_deconv_bwd_weight(case.glv, 1, F32, dev(X), dev(G), dW, c_in, c_out, ws(hch.HCH_WS_BWD_WEIGHT), algo)
-    assert_close(dW.cpu().numpy(), oracle.from_paper_W(oracle.conv_bwd_weight(L, Gp, Xp), c_out), what="deconv bwd weight")
+    hch.hch_deconv_bwd_weight(case.glv, 1, DT, put(X), put(G), dW, c_in, c_out, ws(hch.HCH_WS_BWD_WEIGHT), algo)
+    assert_close(dW.cpu().numpy(), oracle.from_paper_W(oracle.conv_bwd_weight(L, Gp, Xp), c_out), tol=tol, what="deconv bwd weight")
 
 
 def test_unpool(oracle, case_batch64):
