@@ -370,6 +370,9 @@ hch_status hch_sconv_bwd_data(const hch_levels *levels, int32_t level_in, int32_
  *                      written completely
  *   hch_spool_avg_fwd  Y[o] = (sum of the occupied entries' rows) / F^3     (weights 1/F^3)
  *   hch_spool_avg_bwd  dX[q] = (sum of dY[o] over o = field_t[q][:]) / F^3
+ * The two backward calls take `field` and `field_t`, either of which may be NULL: when F = S the
+ * fields partition the input level and, given `field`, each output voxel writes the rows of its
+ * own field (faster than the gather through `field_t`, same result); otherwise `field_t` is needed.
  * X, dX DEVICE [N_in][c] float;  Y, dY DEVICE [N_out][c] float;  argmax DEVICE [N_out][c] int32.
  * With F = 2, S = 2, pad = 0 on levels in ratio 2 the results equal hch_pool_* / hch_avgpool_*.
  */
@@ -377,12 +380,13 @@ hch_status hch_spool_max_fwd(const hch_levels *levels, int32_t level_in, int32_t
                              const float *X, const int32_t *field, float *Y, int32_t *argmax,
                              int32_t c, void *stream);
 hch_status hch_spool_max_bwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
-                             const float *dY, const int32_t *argmax, const int32_t *field_t,
-                             float *dX, int32_t c, void *stream);
+                             const float *dY, const int32_t *argmax, const int32_t *field,
+                             const int32_t *field_t, float *dX, int32_t c, void *stream);
 hch_status hch_spool_avg_fwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
                              const float *X, const int32_t *field, float *Y, int32_t c, void *stream);
 hch_status hch_spool_avg_bwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
-                             const float *dY, const int32_t *field_t, float *dX, int32_t c, void *stream);
+                             const float *dY, const int32_t *field, const int32_t *field_t, float *dX,
+                             int32_t c, void *stream);
 
 /*
  * 2x2x2 average pooling from level_in to level_in + 1 and its adjoint (the average-unpooling of

@@ -89,9 +89,9 @@ def load_library():
     L.hch_build_tables_host.argtypes = [vp, vp, i32, i32, i32, C.POINTER(vp)]
     L.hch_build_levels_ratios.argtypes = [vp, vp, i32, i32, i32, vp, i32, vp, C.POINTER(vp)]
     L.hch_spool_max_fwd.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp]
-    L.hch_spool_max_bwd.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp]
+    L.hch_spool_max_bwd.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp]
     L.hch_spool_avg_fwd.argtypes = [vp, i32, i32, i32, vp, vp, vp, i32, vp]
-    L.hch_spool_avg_bwd.argtypes = [vp, i32, i32, i32, vp, vp, vp, i32, vp]
+    L.hch_spool_avg_bwd.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp]
     L.hch_free_levels.argtypes = [vp]
     L.hch_free_levels.restype = None
     L.hch_num_levels.argtypes = [vp]
@@ -469,9 +469,9 @@ def hch_spool_max_fwd(levels, level_in, F, stride, X, field, Y, argmax, c, strea
                                             _dp(argmax), c, _stream(stream)))
 
 
-def hch_spool_max_bwd(levels, level_in, F, stride, dY, argmax, field_t, dX, c, stream=None):
+def hch_spool_max_bwd(levels, level_in, F, stride, dY, argmax, field, field_t, dX, c, stream=None):
     _check(load_library().hch_spool_max_bwd(levels.handle, level_in, F, stride, _dp(dY), _dp(argmax),
-                                            _dp(field_t), _dp(dX), c, _stream(stream)))
+                                            _dp(field), _dp(field_t), _dp(dX), c, _stream(stream)))
 
 
 def hch_spool_avg_fwd(levels, level_in, F, stride, X, field, Y, c, stream=None):
@@ -479,9 +479,9 @@ def hch_spool_avg_fwd(levels, level_in, F, stride, X, field, Y, c, stream=None):
                                             _stream(stream)))
 
 
-def hch_spool_avg_bwd(levels, level_in, F, stride, dY, field_t, dX, c, stream=None):
-    _check(load_library().hch_spool_avg_bwd(levels.handle, level_in, F, stride, _dp(dY), _dp(field_t), _dp(dX), c,
-                                            _stream(stream)))
+def hch_spool_avg_bwd(levels, level_in, F, stride, dY, field, field_t, dX, c, stream=None):
+    _check(load_library().hch_spool_avg_bwd(levels.handle, level_in, F, stride, _dp(dY), _dp(field), _dp(field_t),
+                                            _dp(dX), c, _stream(stream)))
 
 
 def hch_relu_fwd(x, y, n, stream=None):

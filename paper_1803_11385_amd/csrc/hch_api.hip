@@ -1799,15 +1799,39 @@ extern "C" hch_status hch_spool_max_fwd(const hch_levels *levels, int32_t level_
     return HCH_OK;
 }
 
+// backward of pooling where the fields partition the input level (F = stride): through the forward rows
+template <bool MAXPOOL>
+static hch_status launch_field_unpool(const float *dY, const int32_t *argmax, const int32_t *field, float *dX,
+                                      int64_t n_out, int64_t n_in, int taps, int c, hipStream_t s)
+{
+    const bool vec = c % 4 == 0 && aligned16(dY) && aligned16(dX) && (!MAXPOOL || aligned16(argmax));
+    const int64_t items = n_out * taps * (vec ? c / 4 : c);
+    if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "field pooling backward: too large");
+    const double bytes = (double)n_out * (4.0 * taps + (MAXPOOL ? 8.0 : 4.0) * c) + (double)n_in * 4.0 * c;
+    const int kid = MAXPOOL ? (vec ? HCH_KERNEL_ID("field_unpool_kernel<4, true>") : HCH_KERNEL_ID("field_unpool_kernel<1, true>"))
+                            : (vec ? HCH_KERNEL_ID("field_unpool_kernel<4, false>") : HCH_KERNEL_ID("field_unpool_kernel<1, false>"));
+    hch::LaunchTimer lt(kid, s, bytes, 0.0);
+    if (vec)
+        hipLaunchKernelGGL((hch::field_unpool_kernel<4, MAXPOOL>), dim3(blocks_for(items)), dim3(256), 0, s,
+                           dY, argmax, field, dX, n_out, taps, c, 1.0f / taps);
+    else
+        hipLaunchKernelGGL((hch::field_unpool_kernel<1, MAXPOOL>), dim3(blocks_for(items)), dim3(256), 0, s,
+                           dY, argmax, field, dX, n_out, taps, c, 1.0f / taps);
+    HCH_LAUNCH_CHECK("field_unpool_kernel");
+    return HCH_OK;
+}
+
 extern "C" hch_status hch_spool_max_bwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
-                                        const float *dY, const int32_t *argmax, const int32_t *field_t,
-                                        float *dX, int32_t c, void *stream)
+                                        const float *dY, const int32_t *argmax, const int32_t *field,
+                                        const int32_t *field_t, float *dX, int32_t c, void *stream)
 {
     const Level *Li, *Lo;
-    hch_status st = spool_args(levels, level_in, F, stride, dY, dX, field_t, c, &Li, &Lo, "hch_spool_max_bwd");
+    const bool partition = field && F == stride && stride > 1;
+    hch_status st = spool_args(levels, level_in, F, stride, dY, dX, partition ? field : field_t, c, &Li, &Lo, "hch_spool_max_bwd");
     if (st != HCH_OK) return st;
     if (!argmax) return fail(HCH_EINVAL, "hch_spool_max_bwd: null argmax");
     const int taps = F * F * F;
+    if (partition) return launch_field_unpool<true>(dY, argmax, field, dX, Lo->n_total, Li->n_total, taps, c, (hipStream_t)stream);
     const bool vec = c % 4 == 0 && aligned16(dY) && aligned16(dX) && aligned16(argmax);
     const int64_t items = Li->n_total * (vec ? c / 4 : c);
     const double bytes = (double)Li->n_total * (4.0 * taps + 4.0 * c) + (double)Lo->n_total * 8.0 * c;
@@ -1848,11 +1872,14 @@ extern "C" hch_status hch_spool_avg_fwd(const hch_levels *levels, int32_t level_
 }
 
 extern "C" hch_status hch_spool_avg_bwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
-                                        const float *dY, const int32_t *field_t, float *dX, int32_t c, void *stream)
+                                        const float *dY, const int32_t *field, const int32_t *field_t, float *dX,
+                                        int32_t c, void *stream)
 {
     const Level *Li, *Lo;
-    hch_status st = spool_args(levels, level_in, F, stride, dY, dX, field_t, c, &Li, &Lo, "hch_spool_avg_bwd");
+    const bool partition = field && F == stride && stride > 1;
+    hch_status st = spool_args(levels, level_in, F, stride, dY, dX, partition ? field : field_t, c, &Li, &Lo, "hch_spool_avg_bwd");
     if (st != HCH_OK) return st;
+    if (partition) return launch_field_unpool<false>(dY, nullptr, field, dX, Lo->n_total, Li->n_total, F * F * F, c, (hipStream_t)stream);
     return launch_field_avg(dY, field_t, dX, Li->n_total, Lo->n_total, F * F * F, c, (hipStream_t)stream);
 }
 

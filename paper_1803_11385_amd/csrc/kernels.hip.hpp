@@ -984,13 +984,31 @@ __global__ __launch_bounds__(256) void field_pool_bwd_kernel(
     float acc[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
-    for (int k = 0; k < taps; ++k) {
-        const int32_t o = rows[k];
-        if (o < 0) continue;
-        const float *g = dY + (int64_t)o * c + u * VEC;
-        const int32_t *a = argmax + (int64_t)o * c + u * VEC;
+    // nine rows at a time: their owners, then the owners' switches and gradients (row 0 stands in
+    // where a row has no owner; its values are not used), with no branch between the loads
+    for (int r0 = 0; r0 < taps; r0 += 9) {
+        int32_t o[9];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] += (a[e] == (int32_t)q) ? g[e] : 0.f;
+        for (int j = 0; j < 9; ++j) o[j] = *(r0 + j < taps ? rows + r0 + j : &g_minus1);
+        float g[9][VEC];
+        int32_t a[9][VEC];
+#pragma unroll
+        for (int j = 0; j < 9; ++j) {
+            const int64_t at = (int64_t)max(o[j], 0) * c + u * VEC;
+            if constexpr (VEC == 4) {
+                const f32x4 gv = *reinterpret_cast<const f32x4 *>(dY + at);
+                const int4 av = *reinterpret_cast<const int4 *>(argmax + at);
+                g[j][0] = gv[0]; g[j][1] = gv[1]; g[j][2] = gv[2]; g[j][3] = gv[3];
+                a[j][0] = av.x; a[j][1] = av.y; a[j][2] = av.z; a[j][3] = av.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) { g[j][e] = dY[at + e]; a[j][e] = argmax[at + e]; }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 9; ++j)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] += (o[j] >= 0 && a[j][e] == (int32_t)q) ? g[j][e] : 0.f;
     }
     float *d = dX + q * c + u * VEC;
     if constexpr (VEC == 4) {
@@ -998,6 +1016,45 @@ __global__ __launch_bounds__(256) void field_pool_bwd_kernel(
     } else {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) d[e] = acc[e];
+    }
+}
+
+// The backward passes of pooling when the fields PARTITION the input level (kernel side =
+// stride, no padding: every input voxel lies in exactly one field): one thread per (output
+// voxel, field row, channel unit) writes the row of the input voxel at that place, so all of
+// dX is written exactly once.  MAXPOOL: the gradient where the switch points here, else 0;
+// otherwise the average's scale * dY.
+template <int VEC, bool MAXPOOL>
+__global__ __launch_bounds__(256) void field_unpool_kernel(
+    const float *__restrict__ dY, const int32_t *__restrict__ argmax, const int32_t *__restrict__ field,
+    float *__restrict__ dX, int64_t n_out, int taps, int c, float scale)
+{
+    const int cu = c / VEC;
+    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (item >= n_out * taps * cu) return;
+    const int64_t ok = item / cu;            // output voxel * taps + row
+    const int u = (int)(item - ok * cu);
+    const int32_t j = field[ok];
+    if (j < 0) return;
+    const int64_t o = ok / taps;
+    const float *g = dY + o * c + u * VEC;
+    float *d = dX + (int64_t)j * c + u * VEC;
+    float v[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) v[e] = g[e];
+    if constexpr (MAXPOOL) {
+        const int32_t *a = argmax + o * c + u * VEC;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[e] = (a[e] == j) ? v[e] : 0.f;
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[e] *= scale;
+    }
+    if constexpr (VEC == 4) {
+        *reinterpret_cast<f32x4 *>(d) = f32x4{v[0], v[1], v[2], v[3]};
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) d[e] = v[e];
     }
 }
 
@@ -1071,12 +1128,27 @@ __global__ __launch_bounds__(256) void field_avg_kernel(
     float acc[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
-    for (int k = 0; k < taps; ++k) {
-        const int32_t j = rows[k];
-        if (j < 0) continue;
-        const float *p = src + (int64_t)j * c + u * VEC;
+    const float *zsrc = reinterpret_cast<const float *>(g_zero16);
+    for (int r0 = 0; r0 < taps; r0 += 9) {          // nine rows at a time, no branch between the loads
+        int32_t jj[9];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] += p[e];
+        for (int j = 0; j < 9; ++j) jj[j] = *(r0 + j < taps ? rows + r0 + j : &g_minus1);
+        float v[9][VEC];
+#pragma unroll
+        for (int j = 0; j < 9; ++j) {
+            const float *p = jj[j] >= 0 ? src + (int64_t)jj[j] * c + u * VEC : zsrc;
+            if constexpr (VEC == 4) {
+                const f32x4 t = *reinterpret_cast<const f32x4 *>(p);
+                v[j][0] = t[0]; v[j][1] = t[1]; v[j][2] = t[2]; v[j][3] = t[3];
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) v[j][e] = p[e];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 9; ++j)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] += v[j][e];
     }
     float *d = dst + o * c + u * VEC;
 #pragma unroll

@@ -150,8 +150,12 @@ def test_ratio_conv_and_pooling(oracle, ratio_case):
             hch.hch_spool_avg_fwd(d["glv"], level_in, F, stride, dev(Xc), field, A, c)
             assert_close(A.cpu().numpy(), oracle.avgpool_fwd(Li, Lo, oracle.to_paper_X(Xc), F, stride, pad).T, what="avg fwd")
             dA = torch.full((Li.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
-            hch.hch_spool_avg_bwd(d["glv"], level_in, F, stride, dev(Gc), field_t, dA, c)
+            hch.hch_spool_avg_bwd(d["glv"], level_in, F, stride, dev(Gc), None, field_t, dA, c)
             assert_close(dA.cpu().numpy(), oracle.avgpool_bwd(Li, Lo, oracle.to_paper_X(Gc), F, stride, pad).T, what="avg bwd")
+            if F == stride:         # the fields partition the input level: the form that writes through `field`
+                dA2 = torch.full((Li.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
+                hch.hch_spool_avg_bwd(d["glv"], level_in, F, stride, dev(Gc), field, None, dA2, c)
+                assert torch.equal(dA, dA2)
             if F > stride:
                 continue        # overlapping fields: the oracle's switch routing is defined for disjoint ones
             P = torch.full((Lo.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
@@ -161,9 +165,13 @@ def test_ratio_conv_and_pooling(oracle, ratio_case):
             assert np.array_equal(sw.cpu().numpy(), swo.T)
             assert np.array_equal(P.cpu().numpy(), Po.T.astype(np.float32))
             dP = torch.full((Li.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
-            hch.hch_spool_max_bwd(d["glv"], level_in, F, stride, dev(Gc), sw, field_t, dP, c)
+            hch.hch_spool_max_bwd(d["glv"], level_in, F, stride, dev(Gc), sw, None, field_t, dP, c)
             want = oracle.pool_max_bwd(Li.Ntot, oracle.to_paper_X(Gc), swo).T
             assert np.array_equal(dP.cpu().numpy(), want.astype(np.float32))
+            if F == stride:
+                dP2 = torch.full((Li.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
+                hch.hch_spool_max_bwd(d["glv"], level_in, F, stride, dev(Gc), sw, field, None, dP2, c)
+                assert torch.equal(dP, dP2)
 
 
 def test_field_pooling_equals_child_pooling(oracle):
@@ -184,13 +192,19 @@ def test_field_pooling_equals_child_pooling(oracle):
         assert torch.equal(P1, P2) and torch.equal(s1, s2)
         d1, d2 = (torch.empty((nf, c), dtype=torch.float32, device="cuda") for _ in range(2))
         hch.hch_pool_bwd(glv, 0, G, s1, d1, c)
-        hch.hch_spool_max_bwd(glv, 0, 2, 2, G, s2, field_t, d2, c)
+        hch.hch_spool_max_bwd(glv, 0, 2, 2, G, s2, None, field_t, d2, c)
+        assert torch.equal(d1, d2)
+        d2.fill_(float("nan"))
+        hch.hch_spool_max_bwd(glv, 0, 2, 2, G, s2, field, None, d2, c)
         assert torch.equal(d1, d2)
         hch.hch_avgpool_fwd(glv, 0, X, P1, c)
         hch.hch_spool_avg_fwd(glv, 0, 2, 2, X, field, P2, c)
         assert torch.equal(P1, P2)
         hch.hch_avgpool_bwd(glv, 0, G, d1, c)
-        hch.hch_spool_avg_bwd(glv, 0, 2, 2, G, field_t, d2, c)
+        hch.hch_spool_avg_bwd(glv, 0, 2, 2, G, None, field_t, d2, c)
+        assert torch.equal(d1, d2)
+        d2.fill_(float("nan"))
+        hch.hch_spool_avg_bwd(glv, 0, 2, 2, G, field, None, d2, c)
         assert torch.equal(d1, d2)
 
 
