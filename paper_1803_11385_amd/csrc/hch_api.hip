@@ -2,6 +2,7 @@
 #include "../../include/hch.h"
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <atomic>
@@ -18,6 +19,15 @@
 #include "psh_device.hip.hpp"
 #include "profile.hpp"
 #include "psh_build.hpp"
+
+// Every kernel launch of the library: carries the two timing events of the enclosing LaunchTimer,
+// if there is one and timing is on (null events make this an ordinary launch).
+#define HCH_LAUNCH(kernel, grid, block, lds, stream, ...)                                          \
+    do {                                                                                           \
+        hipEvent_t ev_a_ = hch::tls_start_event, ev_b_ = hch::tls_stop_event;                      \
+        hch::tls_start_event = hch::tls_stop_event = nullptr;                                      \
+        hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, ev_a_, ev_b_, 0, __VA_ARGS__);     \
+    } while (0)
 
 namespace {
 
@@ -141,7 +151,7 @@ static hch_status launch_index_lists(const hch_levels *hl, int l0, int l1, hipSt
             const unsigned n_tiles = (unsigned)(last - first);
             const unsigned grid = (n_tiles + hch::NUM_XCD - 1) / hch::NUM_XCD * hch::NUM_XCD;
             hch::LaunchTimer lt(HCH_KERNEL_ID("neighbour_kernel"), s, bytes, 0.0);
-            hipLaunchKernelGGL(hch::neighbour_kernel, dim3(grid), dim3(256), 0, s, hl->set, hl->d_nbr_prefix,
+            HCH_LAUNCH(hch::neighbour_kernel, dim3(grid), dim3(256), 0, s, hl->set, hl->d_nbr_prefix,
                                n_entries, first, n_tiles);
         }
         HCH_LAUNCH_CHECK("neighbour_kernel");
@@ -155,7 +165,7 @@ static hch_status launch_index_lists(const hch_levels *hl, int l0, int l1, hipSt
             const unsigned n_tiles = (unsigned)(last - first);
             const unsigned grid = (n_tiles + hch::NUM_XCD - 1) / hch::NUM_XCD * hch::NUM_XCD;
             hch::LaunchTimer lt(HCH_KERNEL_ID("child_kernel"), s, bytes, 0.0);
-            hipLaunchKernelGGL(hch::child_kernel, dim3(grid), dim3(256), 0, s, hl->set, hl->d_child_prefix,
+            HCH_LAUNCH(hch::child_kernel, dim3(grid), dim3(256), 0, s, hl->set, hl->d_child_prefix,
                                n_entries, first, n_tiles);
         }
         HCH_LAUNCH_CHECK("child_kernel");
@@ -287,10 +297,10 @@ static hch_status device_construct(hch_levels *hl, hipStream_t s)
 
         const dim3 gv((unsigned)((max_n + 255) / 256), (unsigned)na), gc((unsigned)((max_r3 + 255) / 256), (unsigned)na);
         const dim3 gs((unsigned)((max_m3 + 255) / 256), (unsigned)na);
-        hipLaunchKernelGGL(hch::psh_count_kernel, gv, dim3(256), 0, s, d_desc, d_cnt, d_bucket);
-        hipLaunchKernelGGL(hch::psh_scan_kernel, dim3(1), dim3(1024), 0, s, d_cnt, d_first, (int)cells);
-        hipLaunchKernelGGL(hch::psh_fill_kernel, gv, dim3(256), 0, s, d_desc, d_bucket, d_first, d_fill, d_members, d_res);
-        hipLaunchKernelGGL(hch::psh_classify_kernel, gc, dim3(256), 0, s, d_desc, d_cnt, d_class_count, d_cells, cells);
+        HCH_LAUNCH(hch::psh_count_kernel, gv, dim3(256), 0, s, d_desc, d_cnt, d_bucket);
+        HCH_LAUNCH(hch::psh_scan_kernel, dim3(1), dim3(1024), 0, s, d_cnt, d_first, (int)cells);
+        HCH_LAUNCH(hch::psh_fill_kernel, gv, dim3(256), 0, s, d_desc, d_bucket, d_first, d_fill, d_members, d_res);
+        HCH_LAUNCH(hch::psh_classify_kernel, gc, dim3(256), 0, s, d_desc, d_cnt, d_class_count, d_cells, cells);
         HCH_LAUNCH_CHECK("psh construction");
         int32_t class_count[hch::PSH_CLASSES];
         HCH_HIP(hipMemcpyAsync(class_count, d_class_count, sizeof class_count, hipMemcpyDeviceToHost, s));
@@ -299,14 +309,14 @@ static hch_status device_construct(hch_levels *hl, hipStream_t s)
         for (int k = hch::PSH_CLASSES - 1; k >= 2; --k) {
             if (class_count[k] <= 0) continue;
             HCH_HIP(hipMemsetAsync(d_nfree, 0, (size_t)na * 4, s));
-            hipLaunchKernelGGL(hch::psh_free_list_kernel, gs, dim3(256), 0, s, d_desc, d_nfree, d_free);
-            hipLaunchKernelGGL(hch::psh_place_kernel, dim3((unsigned)((class_count[k] + 3) / 4)), dim3(256), 0, s, d_desc,
+            HCH_LAUNCH(hch::psh_free_list_kernel, gs, dim3(256), 0, s, d_desc, d_nfree, d_free);
+            HCH_LAUNCH(hch::psh_place_kernel, dim3((unsigned)((class_count[k] + 3) / 4)), dim3(256), 0, s, d_desc,
                                d_cells + (size_t)k * cells, class_count[k], d_cnt, d_first, d_members, d_res, d_nfree,
                                d_free, d_phi, d_fail);
         }
         HCH_HIP(hipMemsetAsync(d_nfree, 0, (size_t)na * 4, s));
-        hipLaunchKernelGGL(hch::psh_free_list_kernel, gs, dim3(256), 0, s, d_desc, d_nfree, d_free);
-        hipLaunchKernelGGL(hch::psh_place_single_kernel, gc, dim3(256), 0, s, d_desc, d_cnt, d_first, d_members, d_res,
+        HCH_LAUNCH(hch::psh_free_list_kernel, gs, dim3(256), 0, s, d_desc, d_nfree, d_free);
+        HCH_LAUNCH(hch::psh_place_single_kernel, gc, dim3(256), 0, s, d_desc, d_cnt, d_first, d_members, d_res,
                            d_nfree, d_free, d_rank, d_phi, d_fail);
         HCH_LAUNCH_CHECK("psh construction");
         HCH_HIP(hipMemcpyAsync(h_fail.data(), d_fail, (size_t)n_pairs * 4, hipMemcpyDeviceToHost, s));
@@ -353,7 +363,7 @@ static hch_status device_construct(hch_levels *hl, hipStream_t s)
         HCH_HIP(hipMalloc((void **)&L.dPhi, std::max<size_t>(16, (size_t)L.r_total * 3)));
         HCH_HIP(hipMalloc((void **)&L.dphi4, std::max<size_t>(16, (size_t)L.r_total * 4)));
         HCH_HIP(hipMalloc((void **)&L.dslot3, (size_t)L.m_total * 12));
-        hipLaunchKernelGGL(hch::psh_pack_kernel, dim3((unsigned)((widest + 255) / 256), (unsigned)batch), dim3(256), 0, s,
+        HCH_LAUNCH(hch::psh_pack_kernel, dim3((unsigned)((widest + 255) / 256), (unsigned)batch), dim3(256), 0, s,
                            d_pd, L.dH, L.dT, L.dslot3, L.dV, L.dphi4, L.dPhi);
         HCH_LAUNCH_CHECK("psh_pack_kernel");
         std::vector<int32_t> meta;
@@ -630,7 +640,7 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
                 for (int l = 0; l < n_levels && e == hipSuccess; ++l) {
                     const int64_t items = hl->lv[l].n_total * 27;
                     const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>(4096, (items + 255) / 256));
-                    hipLaunchKernelGGL(hch::count_valid_kernel, dim3(grid), dim3(256), 0, s, hl->lv[l].dnbr, items, d_cnt + l);
+                    HCH_LAUNCH(hch::count_valid_kernel, dim3(grid), dim3(256), 0, s, hl->lv[l].dnbr, items, d_cnt + l);
                     e = hipGetLastError();
                 }
                 if (e == hipSuccess) e = hipMemcpyAsync(h_cnt.data(), d_cnt, (size_t)n_levels * 8, hipMemcpyDeviceToHost, s);
@@ -741,15 +751,15 @@ static hch_status do_hash2col(const Level &L, hch_dtype dtype, const void *X, in
     const unsigned grid = (n_tiles + hch::NUM_XCD - 1) / hch::NUM_XCD * hch::NUM_XCD;
     if (row_bytes % 16 == 0 && aligned16(X) && aligned16(col)) {
         hch::LaunchTimer lt(HCH_KERNEL_ID("hash2col_kernel<unsigned int __vector(4)>"), s, bytes, 0.0);
-        hipLaunchKernelGGL(hch::hash2col_kernel<hch::u32x4>, dim3(grid), dim3(256), lds, s,
+        HCH_LAUNCH(hch::hash2col_kernel<hch::u32x4>, dim3(grid), dim3(256), lds, s,
                            (const hch::u32x4 *)X, L.dnbr, (hch::u32x4 *)col, row_begin, rows, row_bytes / 16, tv, n_tiles);
     } else {
         hch::LaunchTimer lt(dtype == HCH_F32 ? HCH_KERNEL_ID("hash2col_kernel<float>") : HCH_KERNEL_ID("hash2col_kernel<unsigned short>"), s, bytes, 0.0);
         if (dtype == HCH_F32)
-            hipLaunchKernelGGL(hch::hash2col_kernel<float>, dim3(grid), dim3(256), lds, s,
+            HCH_LAUNCH(hch::hash2col_kernel<float>, dim3(grid), dim3(256), lds, s,
                                (const float *)X, L.dnbr, (float *)col, row_begin, rows, c_in, tv, n_tiles);
         else
-            hipLaunchKernelGGL(hch::hash2col_kernel<uint16_t>, dim3(grid), dim3(256), lds, s,
+            HCH_LAUNCH(hch::hash2col_kernel<uint16_t>, dim3(grid), dim3(256), lds, s,
                                (const uint16_t *)X, L.dnbr, (uint16_t *)col, row_begin, rows, c_in, tv, n_tiles);
     }
     HCH_LAUNCH_CHECK("hash2col");
@@ -788,13 +798,13 @@ static hch_status do_col2hash(const Level &L, const float *dcol, int c_in, float
     const unsigned n_tiles = (unsigned)((L.n_total + tv - 1) / tv);
     const unsigned grid = (n_tiles + hch::NUM_XCD - 1) / hch::NUM_XCD * hch::NUM_XCD;
     if (planes)
-        hipLaunchKernelGGL((hch::col2hash_kernel<4, true>), dim3(grid), dim3(256), lds, s, dcol, L.dnbr, dX,
+        HCH_LAUNCH((hch::col2hash_kernel<4, true>), dim3(grid), dim3(256), lds, s, dcol, L.dnbr, dX,
                            L.n_total, c_in, tv, n_tiles);
     else if (vec)
-        hipLaunchKernelGGL((hch::col2hash_kernel<4, false>), dim3(grid), dim3(256), lds, s, dcol, L.dnbr, dX,
+        HCH_LAUNCH((hch::col2hash_kernel<4, false>), dim3(grid), dim3(256), lds, s, dcol, L.dnbr, dX,
                            L.n_total, c_in, tv, n_tiles);
     else
-        hipLaunchKernelGGL((hch::col2hash_kernel<1, false>), dim3(grid), dim3(256), lds, s, dcol, L.dnbr, dX,
+        HCH_LAUNCH((hch::col2hash_kernel<1, false>), dim3(grid), dim3(256), lds, s, dcol, L.dnbr, dX,
                            L.n_total, c_in, tv, n_tiles);
     HCH_LAUNCH_CHECK("col2hash");
     return HCH_OK;
@@ -909,7 +919,7 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
     }
     hch::LaunchTimer lt(ids[pl][v][cfg], s, alg_bytes, 2.0 * M * (double)N * K);
 #define HCH_GEMM_CASE(BM_, BN_, BK_, WM_, VEC_, PL_)                                                                \
-    hipLaunchKernelGGL((hch::gemm_f32_kernel<TIN, BM_, BN_, BK_, WM_, AMODE, B_KC, VEC_, PL_>), grid, dim3(256), 0, s, \
+    HCH_LAUNCH((hch::gemm_f32_kernel<TIN, BM_, BN_, BK_, WM_, AMODE, B_KC, VEC_, PL_>), grid, dim3(256), 0, s, \
                        (const TIN *)A, (const TIN *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split,            \
                        c_split_stride, c_vec_ok, m_tiles, c_planes, taps, b_wrap, b_tap_stride)
     if constexpr (AMODE == hch::A_ROWS && B_KC) {
@@ -976,7 +986,7 @@ static hch_status launch_gemm_bf16(const GemmPlan &p, const void *A, const void 
     }
     hch::LaunchTimer lt(ids[cfg], s, alg_bytes, 2.0 * M * (double)N * K);
 #define HCH_BF16_CASE(BM_, BN_, WM_)                                                                                 \
-    hipLaunchKernelGGL((hch::gemm_bf16_kernel<BM_, BN_, WM_, AMODE, B_KC>), grid, dim3(256), 0, s,                  \
+    HCH_LAUNCH((hch::gemm_bf16_kernel<BM_, BN_, WM_, AMODE, B_KC>), grid, dim3(256), 0, s,                  \
                        (const uint16_t *)A, (const uint16_t *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split,     \
                        c_split_stride, c_vec_ok, m_tiles, taps, b_wrap, b_tap_stride, flat)
     if (p.bm == 64) {
@@ -1055,7 +1065,7 @@ static hch_status launch_direct(const DirectPlan &d, const float *X, const int32
     }
     hch::LaunchTimer lt(ids[b], s, alg_bytes, 2.0 * M * (double)N * 27.0 * c);
 #define HCH_DIRECT_CASE(RT_, NT_, S_, CHECK_)                                                                       \
-    hipLaunchKernelGGL((hch::conv_direct_kernel<RT_, NT_, S_, CHECK_>), grid, dim3(256), 0, s, X, nbr, Wm, out,  \
+    HCH_LAUNCH((hch::conv_direct_kernel<RT_, NT_, S_, CHECK_>), grid, dim3(256), 0, s, X, nbr, Wm, out,  \
                        (int)M, c, N, d.J, d.j_per_split, d.upt, d.step_t, d.step_q, d.wave_tiles, M * (int64_t)N, flipped)
     if (d.check) HCH_DIRECT_CASE(4, 1, 4, true); else HCH_DIRECT_CASE(4, 1, 4, false);
 #undef HCH_DIRECT_CASE
@@ -1079,9 +1089,9 @@ static hch_status launch_narrow4(const float *X, const int32_t *nbr, const float
     hch::LaunchTimer lt(cc == 1 ? HCH_KERNEL_ID("conv_narrow4_kernel<1>")
                                 : (cc == 2 ? HCH_KERNEL_ID("conv_narrow4_kernel<2>") : HCH_KERNEL_ID("conv_narrow4_kernel<4>")),
                         s, alg_bytes, 2.0 * M * 4.0 * 27.0 * c);
-    if (cc == 1) hipLaunchKernelGGL(hch::conv_narrow4_kernel<1>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles, flipped);
-    else if (cc == 2) hipLaunchKernelGGL(hch::conv_narrow4_kernel<2>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles, flipped);
-    else if (cc == 4) hipLaunchKernelGGL(hch::conv_narrow4_kernel<4>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles, flipped);
+    if (cc == 1) HCH_LAUNCH(hch::conv_narrow4_kernel<1>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles, flipped);
+    else if (cc == 2) HCH_LAUNCH(hch::conv_narrow4_kernel<2>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles, flipped);
+    else if (cc == 4) HCH_LAUNCH(hch::conv_narrow4_kernel<4>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles, flipped);
     else return fail(HCH_EINVAL, "conv_narrow4: channel count");
     HCH_LAUNCH_CHECK("conv_narrow4_kernel");
     return HCH_OK;
@@ -1095,11 +1105,11 @@ static hch_status launch_reduce(const float *part, float *out, int64_t n, int sp
     // few slices: a thread per output; many slices: 16 or 64 lanes per output, so that even a
     // small output (a 27 x 4 x 16 weight gradient) spreads over a few hundred workgroups
     if (splits <= 16)
-        hipLaunchKernelGGL(hch::splitk_reduce_kernel<1>, dim3(blocks_for(n)), dim3(256), 0, s, part, out, n, splits, n);
+        HCH_LAUNCH(hch::splitk_reduce_kernel<1>, dim3(blocks_for(n)), dim3(256), 0, s, part, out, n, splits, n);
     else if (n >= 65536 || splits <= 256)
-        hipLaunchKernelGGL(hch::splitk_reduce_kernel<16>, dim3((unsigned)((n + 15) / 16)), dim3(256), 0, s, part, out, n, splits, n);
+        HCH_LAUNCH(hch::splitk_reduce_kernel<16>, dim3((unsigned)((n + 15) / 16)), dim3(256), 0, s, part, out, n, splits, n);
     else
-        hipLaunchKernelGGL(hch::splitk_reduce_kernel<64>, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, s, part, out, n, splits, n);
+        HCH_LAUNCH(hch::splitk_reduce_kernel<64>, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, s, part, out, n, splits, n);
     HCH_LAUNCH_CHECK("splitk_reduce_kernel");
     return HCH_OK;
 }
@@ -1295,11 +1305,11 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
         }
         if (dtype == HCH_F32) {
             hch::LaunchTimer lt(HCH_KERNEL_ID("flip_transpose_weights_kernel<float>"), s, 8.0 * wn, 0.0);
-            hipLaunchKernelGGL(hch::flip_transpose_weights_kernel<float>, dim3(blocks_for(wn)), dim3(256), 0, s,
+            HCH_LAUNCH(hch::flip_transpose_weights_kernel<float>, dim3(blocks_for(wn)), dim3(256), 0, s,
                                (const float *)W, (float *)Wt, c_in, c_out, 27, 1);
         } else {
             hch::LaunchTimer lt(HCH_KERNEL_ID("flip_transpose_weights_kernel<unsigned short>"), s, 4.0 * wn, 0.0);
-            hipLaunchKernelGGL(hch::flip_transpose_weights_kernel<uint16_t>, dim3(blocks_for(wn)), dim3(256), 0, s,
+            HCH_LAUNCH(hch::flip_transpose_weights_kernel<uint16_t>, dim3(blocks_for(wn)), dim3(256), 0, s,
                                (const uint16_t *)W, (uint16_t *)Wt, c_in, c_out, 27, 1);
         }
         HCH_LAUNCH_CHECK("flip_transpose_weights_kernel");
@@ -1392,10 +1402,10 @@ extern "C" hch_status hch_pool_fwd(const hch_levels *levels, int32_t level_in, c
         const double bytes = (double)Lc.n_total * (32.0 + 8.0 * c) + (double)Lf.n_total * 4.0 * c;
         hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("pool_fwd_kernel<4>") : HCH_KERNEL_ID("pool_fwd_kernel<1>"), (hipStream_t)stream, bytes, 0.0);
         if (vec)
-            hipLaunchKernelGGL(hch::pool_fwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+            HCH_LAUNCH(hch::pool_fwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                                X, Lc.dchild, Y, argmax, Lc.n_total, c);
         else
-            hipLaunchKernelGGL(hch::pool_fwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+            HCH_LAUNCH(hch::pool_fwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                                X, Lc.dchild, Y, argmax, Lc.n_total, c);
     }
     HCH_LAUNCH_CHECK("pool_fwd_kernel");
@@ -1419,10 +1429,10 @@ extern "C" hch_status hch_pool_bwd(const hch_levels *levels, int32_t level_in, c
         const double bytes = (double)Lc.n_total * (32.0 + 8.0 * c) + (double)Lf.n_total * 4.0 * c;
         hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("pool_bwd_kernel<4>") : HCH_KERNEL_ID("pool_bwd_kernel<1>"), (hipStream_t)stream, bytes, 0.0);
         if (vec)
-            hipLaunchKernelGGL(hch::pool_bwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+            HCH_LAUNCH(hch::pool_bwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                                dY, argmax, Lc.dchild, dX, Lc.n_total, c);
         else
-            hipLaunchKernelGGL(hch::pool_bwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+            HCH_LAUNCH(hch::pool_bwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                                dY, argmax, Lc.dchild, dX, Lc.n_total, c);
     }
     HCH_LAUNCH_CHECK("pool_bwd_kernel");
@@ -1482,7 +1492,7 @@ extern "C" hch_status hch_unpool_bwd(const hch_levels *levels, int32_t level_out
     if (items == 0) return HCH_OK;
     {
         hch::LaunchTimer lt(HCH_KERNEL_ID("unpool_bwd_kernel"), (hipStream_t)stream, 12.0 * items, 0.0);
-        hipLaunchKernelGGL(hch::unpool_bwd_kernel, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+        HCH_LAUNCH(hch::unpool_bwd_kernel, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                            dY, argmax, dXc, Lc.n_total, c);
     }
     HCH_LAUNCH_CHECK("unpool_bwd_kernel");
@@ -1509,10 +1519,10 @@ extern "C" hch_status hch_relu_pool_fwd(const hch_levels *levels, int32_t level_
         hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("relu_pool_fwd_kernel<4>") : HCH_KERNEL_ID("relu_pool_fwd_kernel<1>"),
                             (hipStream_t)stream, bytes, 0.0);
         if (vec)
-            hipLaunchKernelGGL(hch::relu_pool_fwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+            HCH_LAUNCH(hch::relu_pool_fwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                                Y, Lc.dchild, A, P, argmax, Lc.n_total, c);
         else
-            hipLaunchKernelGGL(hch::relu_pool_fwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+            HCH_LAUNCH(hch::relu_pool_fwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                                Y, Lc.dchild, A, P, argmax, Lc.n_total, c);
     }
     HCH_LAUNCH_CHECK("relu_pool_fwd_kernel");
@@ -1538,10 +1548,10 @@ extern "C" hch_status hch_pool_relu_bwd(const hch_levels *levels, int32_t level_
         hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("pool_relu_bwd_kernel<4>") : HCH_KERNEL_ID("pool_relu_bwd_kernel<1>"),
                             (hipStream_t)stream, bytes, 0.0);
         if (vec)
-            hipLaunchKernelGGL(hch::pool_relu_bwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+            HCH_LAUNCH(hch::pool_relu_bwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                                dP, argmax, Lc.dchild, A, dY, Lc.n_total, c);
         else
-            hipLaunchKernelGGL(hch::pool_relu_bwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+            HCH_LAUNCH(hch::pool_relu_bwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                                dP, argmax, Lc.dchild, A, dY, Lc.n_total, c);
     }
     HCH_LAUNCH_CHECK("pool_relu_bwd_kernel");
@@ -1591,13 +1601,13 @@ extern "C" hch_status hch_field_build(const hch_levels *levels, int32_t level_in
     if (field) {
         const int64_t items = (int64_t)Lo->max_n * F3;
         hch::LaunchTimer lt(HCH_KERNEL_ID("field_kernel<false>"), s, (double)Lo->n_total * (12.0 + 4.0 * F3), 0.0);
-        hipLaunchKernelGGL(hch::field_kernel<false>, dim3(blocks_for(items), (unsigned)Lo->b), dim3(256), 0, s,
+        HCH_LAUNCH(hch::field_kernel<false>, dim3(blocks_for(items), (unsigned)Lo->b), dim3(256), 0, s,
                            Li->view(), Lo->dcoords, Lo->dN(), field, F, stride, pad);
     }
     if (field_t) {
         const int64_t items = (int64_t)Li->max_n * F3;
         hch::LaunchTimer lt(HCH_KERNEL_ID("field_kernel<true>"), s, (double)Li->n_total * (12.0 + 4.0 * F3), 0.0);
-        hipLaunchKernelGGL(hch::field_kernel<true>, dim3(blocks_for(items), (unsigned)Li->b), dim3(256), 0, s,
+        HCH_LAUNCH(hch::field_kernel<true>, dim3(blocks_for(items), (unsigned)Li->b), dim3(256), 0, s,
                            Lo->view(), Li->dcoords, Li->dN(), field_t, F, stride, pad);
     }
     HCH_LAUNCH_CHECK("field_kernel");
@@ -1735,9 +1745,9 @@ extern "C" hch_status hch_sconv_bwd_data(const hch_levels *levels, int32_t level
         const double cbytes = (double)n * (4.0 * taps + 4.0 * c_in + 4.0 * c_in * taps / ((double)stride * stride * stride));
         hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("field_col2hash_kernel<4>") : HCH_KERNEL_ID("field_col2hash_kernel<1>"), s, cbytes, 0.0);
         if (vec)
-            hipLaunchKernelGGL(hch::field_col2hash_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, s, dcol, field_t, dX, n, taps, c_in);
+            HCH_LAUNCH(hch::field_col2hash_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, s, dcol, field_t, dX, n, taps, c_in);
         else
-            hipLaunchKernelGGL(hch::field_col2hash_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, s, dcol, field_t, dX, n, taps, c_in);
+            HCH_LAUNCH(hch::field_col2hash_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, s, dcol, field_t, dX, n, taps, c_in);
         HCH_LAUNCH_CHECK("field_col2hash_kernel");
         return HCH_OK;
     }
@@ -1747,11 +1757,11 @@ extern "C" hch_status hch_sconv_bwd_data(const hch_levels *levels, int32_t level
     // gradients through the transposed index rows, weights transposed per tap (not flipped)
     if (dtype == HCH_F32) {
         hch::LaunchTimer lt(HCH_KERNEL_ID("flip_transpose_weights_kernel<float>"), s, 8.0 * wn, 0.0);
-        hipLaunchKernelGGL(hch::flip_transpose_weights_kernel<float>, dim3(blocks_for(wn)), dim3(256), 0, s,
+        HCH_LAUNCH(hch::flip_transpose_weights_kernel<float>, dim3(blocks_for(wn)), dim3(256), 0, s,
                            (const float *)W, (float *)Wt, c_in, c_out, taps, 0);
     } else {
         hch::LaunchTimer lt(HCH_KERNEL_ID("flip_transpose_weights_kernel<unsigned short>"), s, 4.0 * wn, 0.0);
-        hipLaunchKernelGGL(hch::flip_transpose_weights_kernel<uint16_t>, dim3(blocks_for(wn)), dim3(256), 0, s,
+        HCH_LAUNCH(hch::flip_transpose_weights_kernel<uint16_t>, dim3(blocks_for(wn)), dim3(256), 0, s,
                            (const uint16_t *)W, (uint16_t *)Wt, c_in, c_out, taps, 0);
     }
     HCH_LAUNCH_CHECK("flip_transpose_weights_kernel");
@@ -1790,10 +1800,10 @@ extern "C" hch_status hch_spool_max_fwd(const hch_levels *levels, int32_t level_
     hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("field_pool_fwd_kernel<4>") : HCH_KERNEL_ID("field_pool_fwd_kernel<1>"),
                         (hipStream_t)stream, bytes, 0.0);
     if (vec)
-        hipLaunchKernelGGL(hch::field_pool_fwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+        HCH_LAUNCH(hch::field_pool_fwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                            X, field, Y, argmax, Lo->n_total, taps, c);
     else
-        hipLaunchKernelGGL(hch::field_pool_fwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+        HCH_LAUNCH(hch::field_pool_fwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                            X, field, Y, argmax, Lo->n_total, taps, c);
     HCH_LAUNCH_CHECK("field_pool_fwd_kernel");
     return HCH_OK;
@@ -1812,10 +1822,10 @@ static hch_status launch_field_unpool(const float *dY, const int32_t *argmax, co
                             : (vec ? HCH_KERNEL_ID("field_unpool_kernel<4, false>") : HCH_KERNEL_ID("field_unpool_kernel<1, false>"));
     hch::LaunchTimer lt(kid, s, bytes, 0.0);
     if (vec)
-        hipLaunchKernelGGL((hch::field_unpool_kernel<4, MAXPOOL>), dim3(blocks_for(items)), dim3(256), 0, s,
+        HCH_LAUNCH((hch::field_unpool_kernel<4, MAXPOOL>), dim3(blocks_for(items)), dim3(256), 0, s,
                            dY, argmax, field, dX, n_out, taps, c, 1.0f / taps);
     else
-        hipLaunchKernelGGL((hch::field_unpool_kernel<1, MAXPOOL>), dim3(blocks_for(items)), dim3(256), 0, s,
+        HCH_LAUNCH((hch::field_unpool_kernel<1, MAXPOOL>), dim3(blocks_for(items)), dim3(256), 0, s,
                            dY, argmax, field, dX, n_out, taps, c, 1.0f / taps);
     HCH_LAUNCH_CHECK("field_unpool_kernel");
     return HCH_OK;
@@ -1838,10 +1848,10 @@ extern "C" hch_status hch_spool_max_bwd(const hch_levels *levels, int32_t level_
     hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("field_pool_bwd_kernel<4>") : HCH_KERNEL_ID("field_pool_bwd_kernel<1>"),
                         (hipStream_t)stream, bytes, 0.0);
     if (vec)
-        hipLaunchKernelGGL(hch::field_pool_bwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+        HCH_LAUNCH(hch::field_pool_bwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                            dY, argmax, field_t, dX, Li->n_total, taps, c);
     else
-        hipLaunchKernelGGL(hch::field_pool_bwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+        HCH_LAUNCH(hch::field_pool_bwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                            dY, argmax, field_t, dX, Li->n_total, taps, c);
     HCH_LAUNCH_CHECK("field_pool_bwd_kernel");
     return HCH_OK;
@@ -1855,9 +1865,9 @@ static hch_status launch_field_avg(const float *src, const int32_t *idx, float *
     const double bytes = (double)n_dst * (4.0 * taps + 4.0 * c) + (double)n_src * 4.0 * c;
     hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("field_avg_kernel<4>") : HCH_KERNEL_ID("field_avg_kernel<1>"), s, bytes, 0.0);
     if (vec)
-        hipLaunchKernelGGL(hch::field_avg_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, s, src, idx, dst, n_dst, taps, c, 1.0f / taps);
+        HCH_LAUNCH(hch::field_avg_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, s, src, idx, dst, n_dst, taps, c, 1.0f / taps);
     else
-        hipLaunchKernelGGL(hch::field_avg_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, s, src, idx, dst, n_dst, taps, c, 1.0f / taps);
+        HCH_LAUNCH(hch::field_avg_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, s, src, idx, dst, n_dst, taps, c, 1.0f / taps);
     HCH_LAUNCH_CHECK("field_avg_kernel");
     return HCH_OK;
 }
@@ -1901,10 +1911,10 @@ extern "C" hch_status hch_avgpool_fwd(const hch_levels *levels, int32_t level_in
         hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("avgpool_fwd_kernel<4>") : HCH_KERNEL_ID("avgpool_fwd_kernel<1>"),
                             (hipStream_t)stream, bytes, 8.0 * Lc.n_total * c);
         if (vec)
-            hipLaunchKernelGGL(hch::avgpool_fwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+            HCH_LAUNCH(hch::avgpool_fwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                                X, Lc.dchild, Y, Lc.n_total, c);
         else
-            hipLaunchKernelGGL(hch::avgpool_fwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+            HCH_LAUNCH(hch::avgpool_fwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                                X, Lc.dchild, Y, Lc.n_total, c);
     }
     HCH_LAUNCH_CHECK("avgpool_fwd_kernel");
@@ -1929,10 +1939,10 @@ extern "C" hch_status hch_avgpool_bwd(const hch_levels *levels, int32_t level_in
         hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("avgpool_bwd_kernel<4>") : HCH_KERNEL_ID("avgpool_bwd_kernel<1>"),
                             (hipStream_t)stream, bytes, 0.0);
         if (vec)
-            hipLaunchKernelGGL(hch::avgpool_bwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+            HCH_LAUNCH(hch::avgpool_bwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                                dY, Lc.dchild, dX, Lc.n_total, c);
         else
-            hipLaunchKernelGGL(hch::avgpool_bwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
+            HCH_LAUNCH(hch::avgpool_bwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
                                dY, Lc.dchild, dX, Lc.n_total, c);
     }
     HCH_LAUNCH_CHECK("avgpool_bwd_kernel");
@@ -1946,7 +1956,7 @@ extern "C" hch_status hch_relu_fwd(const float *x, float *y, int64_t n, void *st
     {
         hch::LaunchTimer lt(HCH_KERNEL_ID("relu_fwd_kernel"), (hipStream_t)stream, 8.0 * n, 0.0);
         const int64_t n4 = (aligned16(x) && aligned16(y)) ? n / 4 : 0;
-        hipLaunchKernelGGL(hch::relu_fwd_kernel, dim3(blocks_for(std::max(n4, n - 4 * n4))), dim3(256), 0,
+        HCH_LAUNCH(hch::relu_fwd_kernel, dim3(blocks_for(std::max(n4, n - 4 * n4))), dim3(256), 0,
                            (hipStream_t)stream, x, y, n, n4);
     }
     HCH_LAUNCH_CHECK("relu_fwd_kernel");
@@ -1960,7 +1970,7 @@ extern "C" hch_status hch_relu_bwd(const float *y, const float *dy, float *dx, i
     {
         hch::LaunchTimer lt(HCH_KERNEL_ID("relu_bwd_kernel"), (hipStream_t)stream, 12.0 * n, 0.0);
         const int64_t n4 = (aligned16(y) && aligned16(dy) && aligned16(dx)) ? n / 4 : 0;
-        hipLaunchKernelGGL(hch::relu_bwd_kernel, dim3(blocks_for(std::max(n4, n - 4 * n4))), dim3(256), 0,
+        HCH_LAUNCH(hch::relu_bwd_kernel, dim3(blocks_for(std::max(n4, n - 4 * n4))), dim3(256), 0,
                            (hipStream_t)stream, y, dy, dx, n, n4);
     }
     HCH_LAUNCH_CHECK("relu_bwd_kernel");

@@ -1,8 +1,11 @@
 // Optional per-kernel timing with HIP events on the launch stream, plus the algorithmic
 // byte / flop counts of every launch.  Off by default.  Kernels are registered by the name of
 // their __global__ function (template arguments included, spelled as a profiler prints them)
-// the first time they are launched; while timing is on for a kernel each of its launches is
-// bracketed by two events, which are resolved lazily when the statistics are read.
+// the first time they are launched; while timing is on for a kernel each of its launches
+// carries two events that take the start and the end of the dispatch itself (the launch goes
+// through hipExtLaunchKernelGGL, which attaches them to the kernel: no command-processor time
+// between an event and the kernel is counted); they are resolved lazily when the statistics
+// are read.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -12,6 +15,10 @@
 #include <vector>
 
 namespace hch {
+
+// the events the next launch on this thread carries (null: none); set by LaunchTimer, taken by
+// the launch macro
+inline thread_local hipEvent_t tls_start_event = nullptr, tls_stop_event = nullptr;
 
 struct KernelStats {
     int64_t launches = 0;
@@ -54,13 +61,13 @@ public:
         p.id = id; p.bytes = bytes; p.flops = flops;
         p.a = take(); p.b = take();
         if (!p.a || !p.b) return;
-        (void)hipEventRecord(p.a, s);
+        (void)s;
+        tls_start_event = p.a; tls_stop_event = p.b;
         pending_.push_back(p);
     }
-    void after(hipStream_t s)
+    void after(hipStream_t)
     {
-        std::lock_guard<std::mutex> g(mu_);
-        if (!pending_.empty()) (void)hipEventRecord(pending_.back().b, s);
+        tls_start_event = tls_stop_event = nullptr;     // a scope without a launch times nothing
     }
 
     // resolve all pending event pairs (blocks until those launches finished)
