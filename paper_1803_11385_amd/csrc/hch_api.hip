@@ -21,12 +21,13 @@
 #include "psh_build.hpp"
 
 // Every kernel launch of the library: carries the two timing events of the enclosing LaunchTimer,
-// if there is one and timing is on (null events make this an ordinary launch).
+// if there is one and timing is on; an ordinary launch otherwise.
 #define HCH_LAUNCH(kernel, grid, block, lds, stream, ...)                                          \
     do {                                                                                           \
         hipEvent_t ev_a_ = hch::tls_start_event, ev_b_ = hch::tls_stop_event;                      \
         hch::tls_start_event = hch::tls_stop_event = nullptr;                                      \
-        hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, ev_a_, ev_b_, 0, __VA_ARGS__);     \
+        if (ev_a_) hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, ev_a_, ev_b_, 0, __VA_ARGS__); \
+        else hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                    \
     } while (0)
 
 namespace {
