@@ -88,6 +88,8 @@ def conv_bench(args, torch, hch, S):
     n = lv.n(0)
     algo = hch.HCH_ALGO_FUSED if args.algo == "fused" else hch.HCH_ALGO_COLUMNS
     DT = hch.HCH_BF16 if bf else hch.HCH_F32
+    if bf and not args.no_tap_major:
+        hch.hch_build_tap_major(lv, 0)        # the bf16 gathers read their indices tap by tap
 
     def put(a):
         if bf:
@@ -152,6 +154,7 @@ def main():
     ap.add_argument("--conv-bench", type=int, choices=[3, 5], default=0,
                     help="time only the three products of one convolution on a per-kernel workload and print "
                          "that: 3 = 128^3 grid, batch 16, 32 -> 64, fp32; 5 = 512^3 grid, batch 4, 64 -> 64, bf16")
+    ap.add_argument("--no-tap-major", action="store_true", help="--conv-bench 5 without the tap-major index copy")
     ap.add_argument("--algo", choices=["columns", "fused"], default="fused",
                     help="columns: hash2col -> GEMM -> col2hash through memory; fused: gathered GEMM operand")
     args = ap.parse_args()

@@ -180,6 +180,17 @@ hch_status hch_build_neighbours(hch_levels *levels, int32_t level, void *stream)
 hch_status hch_build_neighbours_range(hch_levels *levels, int32_t first, int32_t count, void *stream);
 
 /*
+ * Optional tap-major copy of nbr27, [27][N_l] instead of [N_l][27], of `level` (-1: every level).
+ * The products with bf16 inputs are bound by the number of cache accesses of their gathers, and
+ * the 27 indices of a voxel one tap at a time cost one access per voxel; from the copy the
+ * indices that a tile of voxels needs for a tap are consecutive.  The first call on a level
+ * allocates N_l * 108 bytes (owned by `levels`); the copy is refreshed by this call and by every
+ * later hch_build_neighbours* on that level, and used by hch_conv_* (bf16) when present.
+ * Results do not depend on it.  Asynchronous on `stream` apart from the allocation.
+ */
+hch_status hch_build_tap_major(hch_levels *levels, int32_t level, void *stream);
+
+/*
  * hash2col (Algorithm 1), rows [row_begin, row_begin + row_count) of the column matrix:
  *   X    DEVICE [N_l][c_in]              (float or bf16 per dtype)
  *   col  DEVICE [row_count][27*c_in]     same element type as X; written completely

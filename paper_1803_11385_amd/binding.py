@@ -19,7 +19,7 @@ __all__ = [
     "hch_unpool_fwd", "hch_unpool_bwd", "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
     "hch_profile_reset", "hch_field_build", "hch_sconv_workspace_bytes", "hch_sconv_fwd", "hch_sconv_bwd_weight",
     "hch_sconv_bwd_data", "hch_avgpool_fwd", "hch_avgpool_bwd", "hch_build_levels_ratios",
-    "hch_spool_max_fwd", "hch_spool_max_bwd", "hch_spool_avg_fwd", "hch_spool_avg_bwd",
+    "hch_spool_max_fwd", "hch_spool_max_bwd", "hch_spool_avg_fwd", "hch_spool_avg_bwd", "hch_build_tap_major",
 ]
 
 HCH_F32, HCH_BF16 = 0, 1
@@ -40,7 +40,7 @@ exported_symbols = [
     "hch_unpool_fwd", "hch_unpool_bwd", "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
     "hch_profile_reset", "hch_field_build", "hch_sconv_workspace_bytes", "hch_sconv_fwd", "hch_sconv_bwd_weight",
     "hch_sconv_bwd_data", "hch_avgpool_fwd", "hch_avgpool_bwd", "hch_build_levels_ratios",
-    "hch_spool_max_fwd", "hch_spool_max_bwd", "hch_spool_avg_fwd", "hch_spool_avg_bwd",
+    "hch_spool_max_fwd", "hch_spool_max_bwd", "hch_spool_avg_fwd", "hch_spool_avg_bwd", "hch_build_tap_major",
 ]
 
 
@@ -99,6 +99,7 @@ def load_library():
     L.hch_level_info.argtypes = [vp, i32, C.POINTER(_Desc)]
     L.hch_build_neighbours.argtypes = [vp, i32, vp]
     L.hch_build_neighbours_range.argtypes = [vp, i32, i32, vp]
+    L.hch_build_tap_major.argtypes = [vp, i32, vp]
     L.hch_hash2col.argtypes = [vp, i32, C.c_int, vp, i32, i64, i64, vp, vp]
     L.hch_col2hash.argtypes = [vp, i32, vp, i32, vp, vp]
     L.hch_conv_workspace_bytes.argtypes = [vp, i32, i32, i32, C.c_int, C.c_int, C.c_int]
@@ -333,6 +334,10 @@ def hch_build_tables_host(coords, model_offsets, resolution, n_levels):
 
 def hch_build_neighbours(levels, level, stream=None):
     _check(load_library().hch_build_neighbours(levels.handle, level, _stream(stream)))
+
+
+def hch_build_tap_major(levels, level=-1, stream=None):
+    _check(load_library().hch_build_tap_major(levels.handle, level, _stream(stream)))
 
 
 def hch_build_neighbours_range(levels, first, count, stream=None):

@@ -20,8 +20,12 @@ constexpr int BF16_BK = 64;   // reduction indices per tile = granularity of spl
 // C[M x N] (+ slices) = A[M x K] . B[K x N], fp32 out.
 //   AMODE  A_ROWS      A(i,k) = A[i*lda + k]
 //          A_COLS      A(i,k) = A[k*lda + i]
-//          A_GATHER    A(i,k) = X[nbr[i*taps + k/c]][k%c]      (c = lda; rows of X have c elements)
-//          A_GATHER_T  A(i,k) = X[nbr[k*taps + i/c]][i%c]
+//          A_GATHER    A(i,k) = X[idx(i, k/c)][k%c]      (c = lda; rows of X have c elements)
+//          A_GATHER_T  A(i,k) = X[idx(k, i/c)][i%c]
+//          with idx(voxel, tap) = nbr[voxel*idx_row_stride + tap*idx_tap_stride]: strides (taps, 1)
+//          for index rows [voxel][tap], (1, number of voxels) for the tap-major copy [tap][voxel],
+//          in which the indices a tile needs for one tap lie side by side (a few cache accesses
+//          instead of one per voxel)
 //   B_KC   true: B(k,j) = B[j*ldb + k] (optionally cut into runs, see gemm_f32_kernel);
 //          false: B(k,j) = B[k*ldb + j]
 // Requirements, checked by the host: every 8-element unit along an operand's fast axis is
@@ -32,8 +36,8 @@ template <int BM, int BN, int WM, int AMODE, bool B_KC>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, float *__restrict__ C,
     const int32_t *__restrict__ nbr, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
-    int k_per_split, int64_t c_split_stride, int c_vec_ok, unsigned m_tiles, int taps,
-    int b_wrap, int64_t b_tap_stride, int flat_slices)
+    int k_per_split, int64_t c_split_stride, int c_vec_ok, unsigned m_tiles,
+    int64_t idx_row_stride, int64_t idx_tap_stride, int b_wrap, int64_t b_tap_stride, int flat_slices)
 {
     constexpr int BK = BF16_BK;
     // An LDS row holds the 64 reduction offsets of one row (A) or column (B) of the tile: 128
@@ -120,12 +124,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
         pa[uu] = nullptr; pn[uu] = nullptr;
         if (AMODE == A_ROWS) { const int r = a_r + 32 * uu; a_ok[uu] = m0 + r < M; pa[uu] = A + (int64_t)(m0 + r) * lda + kbeg + a_c; }
         if (AMODE == A_COLS) { a_ok[uu] = m0 + a_c < M; pa[uu] = A + (int64_t)(kbeg + a_r + uu) * lda + m0 + a_c; }
-        if (AMODE == A_GATHER) { const int r = a_r + 32 * uu; a_ok[uu] = m0 + r < M; pn[uu] = nbr + (int64_t)(m0 + r) * taps; }
+        if (AMODE == A_GATHER) { const int r = a_r + 32 * uu; a_ok[uu] = m0 + r < M; pn[uu] = nbr + (int64_t)(m0 + r) * idx_row_stride; }
         if (AMODE == A_GATHER_T) {
             const int gi = m0 + a_c;
             const int tap = gi / c;
             cc_a = gi - tap * c;
-            a_ok[uu] = gi < M; pn[uu] = nbr + (int64_t)(kbeg + a_r + uu) * taps + tap;
+            a_ok[uu] = gi < M; pn[uu] = nbr + (int64_t)(kbeg + a_r + uu) * idx_row_stride + tap * idx_tap_stride;
         }
     }
 
@@ -165,8 +169,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
             bool ok;
             if (AMODE == A_GATHER) ok = a_ok[uu] && kn + a_c < kend;
             else ok = a_ok[uu] && kn + a_r + uu < kend;
-            out[uu] = *(ok ? pn[uu] + (AMODE == A_GATHER ? tap_n : 0) : &g_minus1);
-            if (AMODE == A_GATHER_T) pn[uu] += BK * taps;
+            out[uu] = *(ok ? pn[uu] + (AMODE == A_GATHER ? tap_n * idx_tap_stride : 0) : &g_minus1);
+            if (AMODE == A_GATHER_T) pn[uu] += BK * idx_row_stride;
         }
         if (AMODE == A_GATHER) {
             tap_n += dtap; cc_n += dcc;

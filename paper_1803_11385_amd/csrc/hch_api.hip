@@ -68,6 +68,7 @@ struct Level {
     std::vector<uint8_t> Phi;
     // device
     int32_t *dH = nullptr, *dV = nullptr, *dcoords = nullptr, *dnbr = nullptr, *dchild = nullptr;
+    int32_t *dnbr_t = nullptr;                 // tap-major copy of dnbr ([27][n_total]), built on request
     uint16_t *dT = nullptr;
     uint8_t *dPhi = nullptr;
     uint32_t *dslot3 = nullptr, *dphi4 = nullptr;   // packed copies of H*,T* and Phi* for the lookups
@@ -86,9 +87,9 @@ struct Level {
 
 void free_level(Level &L)
 {
-    void *ptrs[] = {L.dH, L.dV, L.dcoords, L.dnbr, L.dchild, L.dT, L.dPhi, L.dmeta, L.dslot3, L.dphi4};
+    void *ptrs[] = {L.dH, L.dV, L.dcoords, L.dnbr, L.dchild, L.dT, L.dPhi, L.dmeta, L.dslot3, L.dphi4, L.dnbr_t};
     for (void *p : ptrs) if (p) (void)hipFree(p);
-    L.dH = L.dV = L.dcoords = L.dnbr = L.dchild = L.dmeta = nullptr;
+    L.dH = L.dV = L.dcoords = L.dnbr = L.dchild = L.dmeta = L.dnbr_t = nullptr;
     L.dT = nullptr; L.dPhi = nullptr; L.dslot3 = L.dphi4 = nullptr;
 }
 
@@ -138,6 +139,16 @@ static hch_status upload(void **dst, const void *src, size_t bytes, hipStream_t 
     return HCH_OK;
 }
 
+// dnbr_t[t][i] = dnbr[i][t], if the level has the copy
+static hch_status transpose_neighbours(const Level &L, hipStream_t s)
+{
+    if (!L.dnbr_t || L.n_total == 0) return HCH_OK;
+    hch::LaunchTimer lt(HCH_KERNEL_ID("index_transpose_kernel"), s, 216.0 * (double)L.n_total, 0.0);
+    HCH_LAUNCH(hch::index_transpose_kernel, dim3(blocks_for(L.n_total)), dim3(256), 0, s, L.dnbr, L.dnbr_t, L.n_total, 27);
+    HCH_LAUNCH_CHECK("index_transpose_kernel");
+    return HCH_OK;
+}
+
 // index lists of levels [l0, l1) in one launch each
 static hch_status launch_index_lists(const hch_levels *hl, int l0, int l1, hipStream_t s)
 {
@@ -156,6 +167,10 @@ static hch_status launch_index_lists(const hch_levels *hl, int l0, int l1, hipSt
                                n_entries, first, n_tiles);
         }
         HCH_LAUNCH_CHECK("neighbour_kernel");
+        for (int l = l0; l < l1; ++l) {            // keep the tap-major copies in step
+            hch_status st = transpose_neighbours(hl->lv[l], s);
+            if (st != HCH_OK) return st;
+        }
     }
     {
         const int first = hl->child_prefix[(size_t)l0 * b], last = hl->child_prefix[(size_t)l1 * b];
@@ -181,6 +196,24 @@ extern "C" hch_status hch_build_neighbours(hch_levels *levels, int32_t level, vo
     if (!levels->d_nbr_prefix) return fail(HCH_EINVAL, "hch_build_neighbours: levels were built without device tables");
     if (level < 0) return launch_index_lists(levels, 0, (int)levels->lv.size(), (hipStream_t)stream);
     return launch_index_lists(levels, level, level + 1, (hipStream_t)stream);
+}
+
+extern "C" hch_status hch_build_tap_major(hch_levels *levels, int32_t level, void *stream)
+{
+    if (!levels || level < -1 || level >= (int32_t)levels->lv.size())
+        return fail(HCH_EINVAL, "hch_build_tap_major: bad level");
+    if (!levels->d_nbr_prefix) return fail(HCH_EINVAL, "hch_build_tap_major: levels were built without device tables");
+    const int l0 = level < 0 ? 0 : level, l1 = level < 0 ? (int)levels->lv.size() : level + 1;
+    for (int l = l0; l < l1; ++l) {
+        Level &L = levels->lv[l];
+        if (!L.dnbr_t && L.n_total > 0 && hipMalloc((void **)&L.dnbr_t, (size_t)L.n_total * 27 * 4) != hipSuccess) {
+            L.dnbr_t = nullptr;
+            return fail(HCH_ENOMEM, "hch_build_tap_major: hipMalloc failed");
+        }
+        hch_status st = transpose_neighbours(L, (hipStream_t)stream);
+        if (st != HCH_OK) return st;
+    }
+    return HCH_OK;
 }
 
 extern "C" hch_status hch_build_neighbours_range(hch_levels *levels, int32_t first, int32_t count, void *stream)
@@ -966,9 +999,14 @@ template <int AMODE, bool B_KC>
 static hch_status launch_gemm_bf16(const GemmPlan &p, const void *A, const void *B, float *C,
                                    const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
                                    int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s,
-                                   int taps, int b_wrap, int64_t b_tap_stride)
+                                   int taps, int b_wrap, int64_t b_tap_stride, const int32_t *nbr_t)
 {
     if (M <= 0 || N <= 0) return HCH_OK;
+    // index rows [voxel][tap], or their tap-major copy [tap][voxel] (voxels = rows of the output
+    // when gathering along the reduction axis, the reduction length when gathering along the rows)
+    const int64_t idx_row_stride = nbr_t ? 1 : taps;
+    const int64_t idx_tap_stride = nbr_t ? (AMODE == hch::A_GATHER_T ? K : M) : 1;
+    if (nbr_t) nbr = nbr_t;
     const int c_vec_ok = (ldc % 4 == 0) && (c_split_stride % 4 == 0) && aligned16(C);
     const unsigned m_tiles = (unsigned)((M + p.bm - 1) / p.bm);
     const bool remap = (AMODE == hch::A_GATHER || AMODE == hch::A_ROWS) && m_tiles >= 256;
@@ -989,7 +1027,7 @@ static hch_status launch_gemm_bf16(const GemmPlan &p, const void *A, const void 
 #define HCH_BF16_CASE(BM_, BN_, WM_)                                                                                 \
     HCH_LAUNCH((hch::gemm_bf16_kernel<BM_, BN_, WM_, AMODE, B_KC>), grid, dim3(256), 0, s,                  \
                        (const uint16_t *)A, (const uint16_t *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split,     \
-                       c_split_stride, c_vec_ok, m_tiles, taps, b_wrap, b_tap_stride, flat)
+                       c_split_stride, c_vec_ok, m_tiles, idx_row_stride, idx_tap_stride, b_wrap, b_tap_stride, flat)
     if (p.bm == 64) {
         if constexpr (AMODE == hch::A_ROWS || AMODE == hch::A_GATHER) HCH_BF16_CASE(64, 64, 2);
         else return fail(HCH_EINVAL, "gemm_bf16: 64-row tiles with a transposed A");
@@ -1006,10 +1044,11 @@ template <int AMODE, bool B_KC>
 static hch_status launch_gemm(hch_dtype dtype, const GemmPlan &p, const void *A, const void *B, float *C,
                               const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
                               int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s,
-                              int c_planes = 0, int taps = 27, int b_wrap = 0, int64_t b_tap_stride = 0)
+                              int c_planes = 0, int taps = 27, int b_wrap = 0, int64_t b_tap_stride = 0,
+                              const int32_t *nbr_t = nullptr)
 {
     if (dtype == HCH_BF16 && bf16_mfma_ok<AMODE, B_KC>(p, A, B, M, N, K, lda, ldb, c_planes, b_wrap))
-        return launch_gemm_bf16<AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, taps, b_wrap, b_tap_stride);
+        return launch_gemm_bf16<AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, taps, b_wrap, b_tap_stride, nbr_t);
     if (dtype == HCH_BF16)
         return launch_gemm_t<uint16_t, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps, b_wrap, b_tap_stride);
     return launch_gemm_t<float, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps, b_wrap, b_tap_stride);
@@ -1231,7 +1270,7 @@ extern "C" hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_
         const double bytes = (double)n * (108.0 + es * c_in + 4.0 * c_out * p.splits) + es * Kc * c_out;
         st = launch_gemm<hch::A_GATHER, false>(dtype, p, X, W,
                                                p.splits > 1 ? part : Y, L->dnbr, (int)n, c_out, Kc, c_in,
-                                               c_out, c_out, n * c_out, bytes, s);
+                                               c_out, c_out, n * c_out, bytes, s, 0, 27, 0, 0, L->dnbr_t);
         if (st != HCH_OK) return st;
         if (p.splits > 1) st = launch_reduce(part, Y, n * c_out, p.splits, s);
         return st;
@@ -1299,7 +1338,7 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
             const char *Wlast = (const char *)W + 26 * per_tap * elem_size(dtype);
             const double bytes = (double)n * (108.0 + es * c_out + 4.0 * c_in * p.splits) + es * wn;
             st = launch_gemm<hch::A_GATHER, true>(dtype, p, dY, Wlast, p.splits > 1 ? part : dX, L->dnbr, (int)n, c_in, Kd,
-                                                  c_out, c_out, c_in, n * c_in, bytes, s, 0, 27, c_out, -per_tap);
+                                                  c_out, c_out, c_in, n * c_in, bytes, s, 0, 27, c_out, -per_tap, L->dnbr_t);
             if (st != HCH_OK) return st;
             if (p.splits > 1) st = launch_reduce(part, dX, n * c_in, p.splits, s);
             return st;
@@ -1317,7 +1356,7 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
         const double bytes = (double)n * (108.0 + es * c_out + 4.0 * c_in * p.splits) + es * wn;
         st = launch_gemm<hch::A_GATHER, false>(dtype, p, dY, Wt,
                                                p.splits > 1 ? part : dX, L->dnbr, (int)n, c_in, Kd, c_out,
-                                               c_in, c_in, n * c_in, bytes, s);
+                                               c_in, c_in, n * c_in, bytes, s, 0, 27, 0, 0, L->dnbr_t);
         if (st != HCH_OK) return st;
         if (p.splits > 1) st = launch_reduce(part, dX, n * c_in, p.splits, s);
         return st;
@@ -1365,7 +1404,7 @@ extern "C" hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t leve
     if (algo == HCH_ALGO_FUSED) {
         const double bytes = (double)n * (108.0 + es * c_in + es * c_out) + 4.0 * wsize * p.splits;
         st = launch_gemm<hch::A_GATHER_T, false>(dtype, p, X, dY, dst,
-                                                 L->dnbr, Kc, c_out, (int)n, c_in, c_out, c_out, wsize, bytes, s);
+                                                 L->dnbr, Kc, c_out, (int)n, c_in, c_out, c_out, wsize, bytes, s, 0, 27, 0, 0, L->dnbr_t);
     } else {
         void *col = workspace;
         if (!resident) {

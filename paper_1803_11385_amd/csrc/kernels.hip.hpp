@@ -162,6 +162,20 @@ __global__ __launch_bounds__(256) void neighbour_kernel(
     for (int q = threadIdx.x; q < cnt; q += 256) dst[q] = tile[q];
 }
 
+// dst[t][i] = src[i][t] for an index list src[n][taps] (taps <= 27 here): the tap-major copy of
+// the neighbour lists.  256 rows per workgroup through LDS, both sides coalesced.
+__global__ __launch_bounds__(256) void index_transpose_kernel(
+    const int32_t *__restrict__ src, int32_t *__restrict__ dst, int64_t n, int taps)
+{
+    __shared__ int32_t tile[256 * 27];
+    const int64_t r0 = (int64_t)blockIdx.x * 256;
+    const int rows = (int)min((int64_t)256, n - r0);
+    for (int q = threadIdx.x; q < rows * taps; q += 256) tile[q] = src[r0 * taps + q];
+    __syncthreads();
+    if ((int)threadIdx.x < rows)
+        for (int t = 0; t < taps; ++t) dst[(int64_t)t * n + r0 + threadIdx.x] = tile[threadIdx.x * taps + t];
+}
+
 // For every coarse voxel the global data indices, at the next finer level, of its 8 children
 // 2p + (dx,dy,dz), k = dx*4 + dy*2 + dz, or -1: the stride-2, F = 2, no-padding traversal of
 // Algorithm 1 (receptive field [2p, 2p+1]^3).  Same tiling as above; entries of level 0 have no

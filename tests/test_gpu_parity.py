@@ -406,6 +406,17 @@ def test_conv_bf16(oracle, case_hires, c_in, c_out, algo):
     assert_close(dW.cpu().numpy(), oracle.from_paper_W(oracle.conv_bwd_weight(L, Xp, Gp), c_in), tol=TOL_BF16,
                  what="bf16 bwd weight")
 
+    # with the tap-major copy of the index lists (another lay-out of the same indices): same bits
+    tlv = hch.hch_build_levels(case.coords, case.offs, case.u, 1)
+    hch.hch_build_tap_major(tlv, 0)
+    hch.hch_build_neighbours(tlv, 0)          # a rebuild refreshes the copy
+    for fn, a, b, ref, shape, kind in ((hch.hch_conv_fwd, X, W, Y, (n, c_out), hch.HCH_WS_FWD),
+                                       (hch.hch_conv_bwd_data, G, W, dX, (n, c_in), hch.HCH_WS_BWD_DATA),
+                                       (hch.hch_conv_bwd_weight, X, G, dW, (27, c_in, c_out), hch.HCH_WS_BWD_WEIGHT)):
+        out = torch.full(shape, float("nan"), dtype=torch.float32, device="cuda")
+        fn(tlv, 0, B16, dev_bf16(a), dev_bf16(b), out, c_in, c_out, ws(kind), algo)
+        assert torch.equal(out, ref), fn.__name__
+
 
 # --------------------------------------------------------------------------------------
 # degenerate and ragged cases
