@@ -329,7 +329,7 @@ hch_status hch_unpool_bwd(const hch_levels *levels, int32_t level_out, const flo
 
 /*
  * Convolutions with a general kernel side F, stride and padding (Algorithm 1 and 2 as the paper
- * states them, Section 3.3: receptive field [p*S - P, p*S - P + F - 1]^3 on the input level for
+ * states them, Section 4: receptive field [p*S - P, p*S - P + F - 1]^3 on the input level for
  * output voxel p; [p - (F-1)/2, p + (F-1)/2]^3 when S = 1), and 2x2x2 average pooling (Section 4:
  * a convolution whose weights all equal 1/F^3).  Stride S reads level_in and writes the level
  * of the same hch_levels object whose grid is S times coarser: level_in + log2(S) when the levels
@@ -381,9 +381,13 @@ hch_status hch_sconv_bwd_data(const hch_levels *levels, int32_t level_in, int32_
  *                      written completely
  *   hch_spool_avg_fwd  Y[o] = (sum of the occupied entries' rows) / F^3     (weights 1/F^3)
  *   hch_spool_avg_bwd  dX[q] = (sum of dY[o] over o = field_t[q][:]) / F^3
- * The two backward calls take `field` and `field_t`, either of which may be NULL: when F = S the
- * fields partition the input level and, given `field`, each output voxel writes the rows of its
- * own field (faster than the gather through `field_t`, same result); otherwise `field_t` is needed.
+ * The two backward calls take `pad` (the padding the index rows were built with) and both `field`
+ * and `field_t`, either of which may be NULL: when F = S > 1 and pad = 0 the fields partition the
+ * input level and every input voxel lies in the field of an occupied output voxel, so, given
+ * `field`, each output voxel writes the rows of its own field (faster than the gather through
+ * `field_t`, same result); in every other case `field_t` is needed (HCH_EINVAL without it) and
+ * `field` is ignored: with padding an input voxel can fall into the field of an unoccupied
+ * position, which no forward row reaches.
  * X, dX DEVICE [N_in][c] float;  Y, dY DEVICE [N_out][c] float;  argmax DEVICE [N_out][c] int32.
  * With F = 2, S = 2, pad = 0 on levels in ratio 2 the results equal hch_pool_* / hch_avgpool_*.
  */
@@ -391,13 +395,13 @@ hch_status hch_spool_max_fwd(const hch_levels *levels, int32_t level_in, int32_t
                              const float *X, const int32_t *field, float *Y, int32_t *argmax,
                              int32_t c, void *stream);
 hch_status hch_spool_max_bwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
-                             const float *dY, const int32_t *argmax, const int32_t *field,
+                             int32_t pad, const float *dY, const int32_t *argmax, const int32_t *field,
                              const int32_t *field_t, float *dX, int32_t c, void *stream);
 hch_status hch_spool_avg_fwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
                              const float *X, const int32_t *field, float *Y, int32_t c, void *stream);
 hch_status hch_spool_avg_bwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
-                             const float *dY, const int32_t *field, const int32_t *field_t, float *dX,
-                             int32_t c, void *stream);
+                             int32_t pad, const float *dY, const int32_t *field, const int32_t *field_t,
+                             float *dX, int32_t c, void *stream);
 
 /*
  * 2x2x2 average pooling from level_in to level_in + 1 and its adjoint (the average-unpooling of

@@ -18,17 +18,20 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "hch_oracle.c")
-_LIB = os.path.join(_HERE, "liboracle.so")
+# HCH_ORACLE_LIB names another build of the same source (the sanitizer run of the test suite)
+_LIB = os.environ.get("HCH_ORACLE_LIB") or os.path.join(_HERE, "liboracle.so")
 
 ORC_OK, ORC_EINVAL, ORC_ECAP, ORC_EBUILD, ORC_EUNSUPPORTED = 0, 1, 2, 3, 5
 
 
-def build(force=False):
-    """Compile the oracle with gcc (plain C, OpenMP on the outer loops)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99",
-                               "-Wall", "-o", _LIB, _SRC, "-lm"])
-    return _LIB
+def build(force=False, out=None, extra_flags=("-O2",)):
+    """Compile the oracle with gcc (plain C, OpenMP on the outer loops).  No -march=native: the
+    library is built in one container and also run on another machine."""
+    out = out or _LIB
+    if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", *extra_flags, "-fopenmp", "-fPIC", "-shared", "-std=c99",
+                               "-Wall", "-o", out, _SRC, "-lm"])
+    return out
 
 
 class _Level(C.Structure):

@@ -89,9 +89,9 @@ def load_library():
     L.hch_build_tables_host.argtypes = [vp, vp, i32, i32, i32, C.POINTER(vp)]
     L.hch_build_levels_ratios.argtypes = [vp, vp, i32, i32, i32, vp, i32, vp, C.POINTER(vp)]
     L.hch_spool_max_fwd.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp]
-    L.hch_spool_max_bwd.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp]
+    L.hch_spool_max_bwd.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32, vp]
     L.hch_spool_avg_fwd.argtypes = [vp, i32, i32, i32, vp, vp, vp, i32, vp]
-    L.hch_spool_avg_bwd.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp]
+    L.hch_spool_avg_bwd.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, i32, vp]
     L.hch_free_levels.argtypes = [vp]
     L.hch_free_levels.restype = None
     L.hch_num_levels.argtypes = [vp]
@@ -241,6 +241,7 @@ class Levels:
 
     def __init__(self, handle):
         self._h = handle
+        self._n = {}
 
     @property
     def handle(self):
@@ -258,7 +259,10 @@ class Levels:
         return LevelInfo(d)
 
     def n(self, level):
-        return self.info(level).n_total
+        """N_l, the number of voxels (rows of every feature tensor) of `level`."""
+        if level not in self._n:
+            self._n[level] = int(self.info(level).n_total)
+        return self._n[level]
 
     def free(self):
         if self._h:
@@ -279,8 +283,64 @@ def _stream(stream):
     return C.c_void_p(int(stream))
 
 
-def _dp(t):
-    return C.c_void_p(t.data_ptr() if t is not None else None)
+# Every DEVICE argument is checked here, on the host, before its address goes to the library: a
+# CPU tensor, a wrong element type, a non-contiguous view or a buffer shorter than the call will
+# read or write would otherwise become an out-of-bounds access on the GPU instead of an error.
+_F32, _I32 = "f32", "i32"
+
+
+def _dp(t, what="tensor", kind=None, numel=0):
+    """Address of a DEVICE tensor (None -> NULL).  kind: _F32, _I32, an hch_dtype (HCH_F32 / HCH_BF16:
+    float32, or any 2-byte element type holding bfloat16 bit patterns), or None (bytes)."""
+    if t is None:
+        return C.c_void_p(None)
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise HchError(1, f"{what}: must be a torch tensor in GPU memory")
+    if not t.is_contiguous():
+        raise HchError(1, f"{what}: must be contiguous")
+    if kind == _F32 or kind == HCH_F32:
+        ok = t.dtype == torch.float32
+    elif kind == _I32:
+        ok = t.dtype == torch.int32
+    elif kind == HCH_BF16:
+        ok = t.element_size() == 2
+    else:
+        ok = True
+    if not ok:
+        raise HchError(1, f"{what}: wrong element type {t.dtype}")
+    if t.numel() < numel:
+        raise HchError(1, f"{what}: {t.numel()} elements, the call needs {int(numel)}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _nbytes(ws):
+    return ws.numel() * ws.element_size() if ws is not None else 0
+
+
+def _in_dtype(dtype):
+    if dtype not in (HCH_F32, HCH_BF16):
+        raise HchError(1, "unknown dtype")
+    return dtype
+
+
+def _level_n(levels, level, what="level"):
+    if not isinstance(level, int) or level < 0 or level >= levels.n_levels:
+        raise HchError(1, f"{what} out of range")
+    return levels.n(level)
+
+
+def _out_level(levels, level_in, stride):
+    """Rows of the level a field of this stride writes, for the argument checks only; the library
+    decides (and rejects a stride that no level matches)."""
+    n_in = _level_n(levels, level_in, "level_in")
+    if stride == 1:
+        return n_in, n_in
+    u = levels.info(level_in).ubar
+    for l in range(level_in + 1, levels.n_levels):
+        if levels.info(l).ubar * stride >= u > (levels.info(l).ubar - 1) * stride:
+            return n_in, levels.n(l)
+    raise HchError(1, "no level of this set is `stride` times coarser than level_in")
 
 
 def _host_inputs(coords, model_offsets):
@@ -345,13 +405,15 @@ def hch_build_neighbours_range(levels, first, count, stream=None):
 
 
 def hch_hash2col(levels, level, dtype, X, c_in, row_begin, row_count, col, stream=None):
-    _check(load_library().hch_hash2col(levels.handle, level, dtype, _dp(X), c_in, row_begin,
-                                       row_count, _dp(col), _stream(stream)))
+    n, dt = _level_n(levels, level), _in_dtype(dtype)
+    _check(load_library().hch_hash2col(levels.handle, level, dtype, _dp(X, "X", dt, n * c_in), c_in, row_begin,
+                                       row_count, _dp(col, "col", dt, max(0, row_count) * 27 * c_in), _stream(stream)))
 
 
 def hch_col2hash(levels, level, dcol, c_in, dX, stream=None):
-    _check(load_library().hch_col2hash(levels.handle, level, _dp(dcol), c_in, _dp(dX),
-                                       _stream(stream)))
+    n = _level_n(levels, level)
+    _check(load_library().hch_col2hash(levels.handle, level, _dp(dcol, "dcol", _F32, n * 27 * c_in), c_in,
+                                       _dp(dX, "dX", _F32, n * c_in), _stream(stream)))
 
 
 def hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, kind, algo=HCH_ALGO_COLUMNS):
@@ -359,142 +421,178 @@ def hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, kind, algo=HCH_A
                                                        kind, algo))
 
 
-def hch_conv_fwd(levels, level, dtype, X, W, Y, c_in, c_out, workspace,
-                 algo=HCH_ALGO_COLUMNS, stream=None):
-    _check(load_library().hch_conv_fwd(levels.handle, level, dtype, _dp(X), _dp(W), _dp(Y), c_in,
-                                       c_out, _dp(workspace),
-                                       workspace.numel() * workspace.element_size(), algo,
-                                       _stream(stream)))
-
-
-def hch_conv_bwd_data(levels, level, dtype, dY, W, dX, c_in, c_out, workspace,
-                      algo=HCH_ALGO_COLUMNS, stream=None):
-    _check(load_library().hch_conv_bwd_data(levels.handle, level, dtype, _dp(dY), _dp(W), _dp(dX),
-                                            c_in, c_out, _dp(workspace),
-                                            workspace.numel() * workspace.element_size(), algo,
-                                            _stream(stream)))
-
-
-def hch_conv_bwd_weight(levels, level, dtype, X, dY, dW, c_in, c_out, workspace,
-                        algo=HCH_ALGO_COLUMNS, stream=None):
-    _check(load_library().hch_conv_bwd_weight(levels.handle, level, dtype, _dp(X), _dp(dY),
-                                              _dp(dW), c_in, c_out, _dp(workspace),
-                                              workspace.numel() * workspace.element_size(), algo,
-                                              _stream(stream)))
-
-
-def _conv_like(name, levels, level, dtype, a, b, out, c_in, c_out, workspace, algo, stream):
-    _check(getattr(load_library(), name)(levels.handle, level, dtype, _dp(a), _dp(b), _dp(out), c_in,
-                                         c_out, _dp(workspace),
-                                         workspace.numel() * workspace.element_size(), algo,
+def _conv_like(name, levels, level, dtype, a, a_c, b, b_c, out, out_c, c_in, c_out, workspace, algo, stream):
+    """a, b: inputs of `dtype`; out: float32.  *_c: channels per voxel row, or None for a weight
+    tensor of 27 * c_in * c_out elements."""
+    n, dt = _level_n(levels, level), _in_dtype(dtype)
+    wn = 27 * c_in * c_out
+    size = lambda c: wn if c is None else n * c
+    _check(getattr(load_library(), name)(levels.handle, level, dtype, _dp(a, "first input", dt, size(a_c)),
+                                         _dp(b, "second input", dt, size(b_c)), _dp(out, "output", _F32, size(out_c)),
+                                         c_in, c_out, _dp(workspace, "workspace"), _nbytes(workspace), algo,
                                          _stream(stream)))
 
 
+def hch_conv_fwd(levels, level, dtype, X, W, Y, c_in, c_out, workspace, algo=HCH_ALGO_COLUMNS, stream=None):
+    _conv_like("hch_conv_fwd", levels, level, dtype, X, c_in, W, None, Y, c_out, c_in, c_out, workspace, algo, stream)
+
+
+def hch_conv_bwd_data(levels, level, dtype, dY, W, dX, c_in, c_out, workspace, algo=HCH_ALGO_COLUMNS, stream=None):
+    _conv_like("hch_conv_bwd_data", levels, level, dtype, dY, c_out, W, None, dX, c_in, c_in, c_out, workspace, algo, stream)
+
+
+def hch_conv_bwd_weight(levels, level, dtype, X, dY, dW, c_in, c_out, workspace, algo=HCH_ALGO_COLUMNS, stream=None):
+    _conv_like("hch_conv_bwd_weight", levels, level, dtype, X, c_in, dY, c_out, dW, None, c_in, c_out, workspace, algo, stream)
+
+
 def hch_deconv_fwd(levels, level, dtype, X, W, Y, c_in, c_out, workspace, algo=HCH_ALGO_COLUMNS, stream=None):
-    _conv_like("hch_deconv_fwd", levels, level, dtype, X, W, Y, c_in, c_out, workspace, algo, stream)
+    _conv_like("hch_deconv_fwd", levels, level, dtype, X, c_in, W, None, Y, c_out, c_in, c_out, workspace, algo, stream)
 
 
 def hch_deconv_bwd_data(levels, level, dtype, dY, W, dX, c_in, c_out, workspace, algo=HCH_ALGO_COLUMNS,
                         stream=None):
-    _conv_like("hch_deconv_bwd_data", levels, level, dtype, dY, W, dX, c_in, c_out, workspace, algo, stream)
+    _conv_like("hch_deconv_bwd_data", levels, level, dtype, dY, c_out, W, None, dX, c_in, c_in, c_out, workspace, algo, stream)
 
 
 def hch_deconv_bwd_weight(levels, level, dtype, X, dY, dW, c_in, c_out, workspace, algo=HCH_ALGO_COLUMNS,
                           stream=None):
-    _conv_like("hch_deconv_bwd_weight", levels, level, dtype, X, dY, dW, c_in, c_out, workspace, algo, stream)
+    _conv_like("hch_deconv_bwd_weight", levels, level, dtype, X, c_in, dY, c_out, dW, None, c_in, c_out, workspace, algo, stream)
+
+
+def _pool_rows(levels, level_in):
+    """(N_fine, N_coarse) of a pooling between level_in and level_in + 1."""
+    return _level_n(levels, level_in, "level_in"), _level_n(levels, level_in + 1, "level_in + 1")
 
 
 def hch_unpool_fwd(levels, level_out, Xc, argmax, Y, c, stream=None):
-    _check(load_library().hch_unpool_fwd(levels.handle, level_out, _dp(Xc), _dp(argmax), _dp(Y), c,
+    nf, nc = _pool_rows(levels, level_out)
+    _check(load_library().hch_unpool_fwd(levels.handle, level_out, _dp(Xc, "Xc", _F32, nc * c),
+                                         _dp(argmax, "argmax", _I32, nc * c), _dp(Y, "Y", _F32, nf * c), c,
                                          _stream(stream)))
 
 
 def hch_unpool_bwd(levels, level_out, dY, argmax, dXc, c, stream=None):
-    _check(load_library().hch_unpool_bwd(levels.handle, level_out, _dp(dY), _dp(argmax), _dp(dXc), c,
+    nf, nc = _pool_rows(levels, level_out)
+    _check(load_library().hch_unpool_bwd(levels.handle, level_out, _dp(dY, "dY", _F32, nf * c),
+                                         _dp(argmax, "argmax", _I32, nc * c), _dp(dXc, "dXc", _F32, nc * c), c,
                                          _stream(stream)))
 
 
 def hch_pool_fwd(levels, level_in, X, Y, argmax, c, stream=None):
-    _check(load_library().hch_pool_fwd(levels.handle, level_in, _dp(X), _dp(Y), _dp(argmax), c,
-                                       _stream(stream)))
+    nf, nc = _pool_rows(levels, level_in)
+    _check(load_library().hch_pool_fwd(levels.handle, level_in, _dp(X, "X", _F32, nf * c), _dp(Y, "Y", _F32, nc * c),
+                                       _dp(argmax, "argmax", _I32, nc * c), c, _stream(stream)))
 
 
 def hch_pool_bwd(levels, level_in, dY, argmax, dX, c, stream=None):
-    _check(load_library().hch_pool_bwd(levels.handle, level_in, _dp(dY), _dp(argmax), _dp(dX), c,
+    nf, nc = _pool_rows(levels, level_in)
+    _check(load_library().hch_pool_bwd(levels.handle, level_in, _dp(dY, "dY", _F32, nc * c),
+                                       _dp(argmax, "argmax", _I32, nc * c), _dp(dX, "dX", _F32, nf * c), c,
                                        _stream(stream)))
 
 
 def hch_relu_pool_fwd(levels, level_in, Y, A, P, argmax, c, stream=None):
-    _check(load_library().hch_relu_pool_fwd(levels.handle, level_in, _dp(Y), _dp(A), _dp(P),
-                                            _dp(argmax), c, _stream(stream)))
+    nf, nc = _pool_rows(levels, level_in)
+    _check(load_library().hch_relu_pool_fwd(levels.handle, level_in, _dp(Y, "Y", _F32, nf * c), _dp(A, "A", _F32, nf * c),
+                                            _dp(P, "P", _F32, nc * c), _dp(argmax, "argmax", _I32, nc * c), c,
+                                            _stream(stream)))
 
 
 def hch_pool_relu_bwd(levels, level_in, dP, argmax, A, dY, c, stream=None):
-    _check(load_library().hch_pool_relu_bwd(levels.handle, level_in, _dp(dP), _dp(argmax), _dp(A),
-                                            _dp(dY), c, _stream(stream)))
+    nf, nc = _pool_rows(levels, level_in)
+    _check(load_library().hch_pool_relu_bwd(levels.handle, level_in, _dp(dP, "dP", _F32, nc * c),
+                                            _dp(argmax, "argmax", _I32, nc * c), _dp(A, "A", _F32, nf * c),
+                                            _dp(dY, "dY", _F32, nf * c), c, _stream(stream)))
 
 
 def hch_field_build(levels, level_in, F, stride, pad, field, field_t, stream=None):
-    _check(load_library().hch_field_build(levels.handle, level_in, F, stride, pad, _dp(field), _dp(field_t),
-                                          _stream(stream)))
+    n_in, n_out = _out_level(levels, level_in, stride)
+    _check(load_library().hch_field_build(levels.handle, level_in, F, stride, pad,
+                                          _dp(field, "field", _I32, n_out * F ** 3),
+                                          _dp(field_t, "field_t", _I32, n_in * F ** 3), _stream(stream)))
 
 
 def hch_sconv_workspace_bytes(levels, level_in, F, stride, c_in, c_out, dtype, kind):
     return int(load_library().hch_sconv_workspace_bytes(levels.handle, level_in, F, stride, c_in, c_out, dtype, kind))
 
 
-def _sconv(name, levels, level_in, F, stride, dtype, a, b, out, idx, c_in, c_out, workspace, stream):
-    _check(getattr(load_library(), name)(levels.handle, level_in, F, stride, dtype, _dp(a), _dp(b), _dp(out),
-                                         _dp(idx), c_in, c_out, _dp(workspace),
-                                         workspace.numel() * workspace.element_size(), _stream(stream)))
+def _sconv(name, levels, level_in, F, stride, dtype, a, a_n, b, b_n, out, out_n, idx, idx_n, c_in, c_out, workspace,
+           stream):
+    dt = _in_dtype(dtype)
+    _check(getattr(load_library(), name)(levels.handle, level_in, F, stride, dtype, _dp(a, "first input", dt, a_n),
+                                         _dp(b, "second input", dt, b_n), _dp(out, "output", _F32, out_n),
+                                         _dp(idx, "index rows", _I32, idx_n), c_in, c_out, _dp(workspace, "workspace"),
+                                         _nbytes(workspace), _stream(stream)))
 
 
 def hch_sconv_fwd(levels, level_in, F, stride, dtype, X, W, Y, field, c_in, c_out, workspace, stream=None):
-    _sconv("hch_sconv_fwd", levels, level_in, F, stride, dtype, X, W, Y, field, c_in, c_out, workspace, stream)
+    n_in, n_out = _out_level(levels, level_in, stride)
+    _sconv("hch_sconv_fwd", levels, level_in, F, stride, dtype, X, n_in * c_in, W, F ** 3 * c_in * c_out, Y,
+           n_out * c_out, field, n_out * F ** 3, c_in, c_out, workspace, stream)
 
 
 def hch_sconv_bwd_weight(levels, level_in, F, stride, dtype, X, dY, dW, field, c_in, c_out, workspace, stream=None):
-    _sconv("hch_sconv_bwd_weight", levels, level_in, F, stride, dtype, X, dY, dW, field, c_in, c_out, workspace, stream)
+    n_in, n_out = _out_level(levels, level_in, stride)
+    _sconv("hch_sconv_bwd_weight", levels, level_in, F, stride, dtype, X, n_in * c_in, dY, n_out * c_out, dW,
+           F ** 3 * c_in * c_out, field, n_out * F ** 3, c_in, c_out, workspace, stream)
 
 
 def hch_sconv_bwd_data(levels, level_in, F, stride, dtype, dY, W, dX, field_t, c_in, c_out, workspace, stream=None):
-    _sconv("hch_sconv_bwd_data", levels, level_in, F, stride, dtype, dY, W, dX, field_t, c_in, c_out, workspace, stream)
+    n_in, n_out = _out_level(levels, level_in, stride)
+    _sconv("hch_sconv_bwd_data", levels, level_in, F, stride, dtype, dY, n_out * c_out, W, F ** 3 * c_in * c_out, dX,
+           n_in * c_in, field_t, n_in * F ** 3, c_in, c_out, workspace, stream)
 
 
 def hch_avgpool_fwd(levels, level_in, X, Y, c, stream=None):
-    _check(load_library().hch_avgpool_fwd(levels.handle, level_in, _dp(X), _dp(Y), c, _stream(stream)))
+    nf, nc = _pool_rows(levels, level_in)
+    _check(load_library().hch_avgpool_fwd(levels.handle, level_in, _dp(X, "X", _F32, nf * c), _dp(Y, "Y", _F32, nc * c),
+                                          c, _stream(stream)))
 
 
 def hch_avgpool_bwd(levels, level_in, dY, dX, c, stream=None):
-    _check(load_library().hch_avgpool_bwd(levels.handle, level_in, _dp(dY), _dp(dX), c, _stream(stream)))
+    nf, nc = _pool_rows(levels, level_in)
+    _check(load_library().hch_avgpool_bwd(levels.handle, level_in, _dp(dY, "dY", _F32, nc * c),
+                                          _dp(dX, "dX", _F32, nf * c), c, _stream(stream)))
 
 
 def hch_spool_max_fwd(levels, level_in, F, stride, X, field, Y, argmax, c, stream=None):
-    _check(load_library().hch_spool_max_fwd(levels.handle, level_in, F, stride, _dp(X), _dp(field), _dp(Y),
-                                            _dp(argmax), c, _stream(stream)))
+    n_in, n_out = _out_level(levels, level_in, stride)
+    _check(load_library().hch_spool_max_fwd(levels.handle, level_in, F, stride, _dp(X, "X", _F32, n_in * c),
+                                            _dp(field, "field", _I32, n_out * F ** 3), _dp(Y, "Y", _F32, n_out * c),
+                                            _dp(argmax, "argmax", _I32, n_out * c), c, _stream(stream)))
 
 
-def hch_spool_max_bwd(levels, level_in, F, stride, dY, argmax, field, field_t, dX, c, stream=None):
-    _check(load_library().hch_spool_max_bwd(levels.handle, level_in, F, stride, _dp(dY), _dp(argmax),
-                                            _dp(field), _dp(field_t), _dp(dX), c, _stream(stream)))
+def hch_spool_max_bwd(levels, level_in, F, stride, pad, dY, argmax, field, field_t, dX, c, stream=None):
+    n_in, n_out = _out_level(levels, level_in, stride)
+    _check(load_library().hch_spool_max_bwd(levels.handle, level_in, F, stride, pad, _dp(dY, "dY", _F32, n_out * c),
+                                            _dp(argmax, "argmax", _I32, n_out * c),
+                                            _dp(field, "field", _I32, n_out * F ** 3),
+                                            _dp(field_t, "field_t", _I32, n_in * F ** 3), _dp(dX, "dX", _F32, n_in * c),
+                                            c, _stream(stream)))
 
 
 def hch_spool_avg_fwd(levels, level_in, F, stride, X, field, Y, c, stream=None):
-    _check(load_library().hch_spool_avg_fwd(levels.handle, level_in, F, stride, _dp(X), _dp(field), _dp(Y), c,
+    n_in, n_out = _out_level(levels, level_in, stride)
+    _check(load_library().hch_spool_avg_fwd(levels.handle, level_in, F, stride, _dp(X, "X", _F32, n_in * c),
+                                            _dp(field, "field", _I32, n_out * F ** 3), _dp(Y, "Y", _F32, n_out * c), c,
                                             _stream(stream)))
 
 
-def hch_spool_avg_bwd(levels, level_in, F, stride, dY, field, field_t, dX, c, stream=None):
-    _check(load_library().hch_spool_avg_bwd(levels.handle, level_in, F, stride, _dp(dY), _dp(field), _dp(field_t),
-                                            _dp(dX), c, _stream(stream)))
+def hch_spool_avg_bwd(levels, level_in, F, stride, pad, dY, field, field_t, dX, c, stream=None):
+    n_in, n_out = _out_level(levels, level_in, stride)
+    _check(load_library().hch_spool_avg_bwd(levels.handle, level_in, F, stride, pad, _dp(dY, "dY", _F32, n_out * c),
+                                            _dp(field, "field", _I32, n_out * F ** 3),
+                                            _dp(field_t, "field_t", _I32, n_in * F ** 3), _dp(dX, "dX", _F32, n_in * c),
+                                            c, _stream(stream)))
 
 
 def hch_relu_fwd(x, y, n, stream=None):
-    _check(load_library().hch_relu_fwd(_dp(x), _dp(y), n, _stream(stream)))
+    _check(load_library().hch_relu_fwd(_dp(x, "x", _F32, n), _dp(y, "y", _F32, n), n, _stream(stream)))
 
 
 def hch_relu_bwd(y, dy, dx, n, stream=None):
-    _check(load_library().hch_relu_bwd(_dp(y), _dp(dy), _dp(dx), n, _stream(stream)))
+    _check(load_library().hch_relu_bwd(_dp(y, "y", _F32, n), _dp(dy, "dy", _F32, n), _dp(dx, "dx", _F32, n), n,
+                                       _stream(stream)))
 
 
 def hch_kernel_count():

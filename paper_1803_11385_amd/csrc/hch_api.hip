@@ -421,6 +421,33 @@ static hch_status device_construct(hch_levels *hl, hipStream_t s)
 
 // ratios == nullptr: every level halves the resolution (a power of two); else ratios[l] >= 2 is
 // the ratio between level l and level l+1, whose side is ceil(side_l / ratios[l])
+// Run `fn` on up to `nthr` host threads (the caller's included) and wait for all of them.  An
+// exception inside a worker (std::bad_alloc from its vectors, std::system_error) must not leave
+// the thread function: it is caught there and reported as false.  Threads that were started are
+// always joined, also when starting a further one fails.
+template <typename Fn>
+static bool run_on_threads(unsigned nthr, Fn fn)
+{
+    std::atomic<int> failed(0);
+    auto guarded = [&]() {
+        try { fn(); } catch (...) { failed = 1; }
+    };
+    std::vector<std::thread> pool;
+    struct Joiner {
+        std::vector<std::thread> &p;
+        ~Joiner() { for (auto &th : p) if (th.joinable()) th.join(); }
+    } joiner{pool};
+    try {
+        pool.reserve(nthr);
+        for (unsigned i = 1; i < nthr; ++i) pool.emplace_back(guarded);
+    } catch (...) {
+        failed = 1;             // fewer threads than wanted: the work is still done below
+    }
+    guarded();
+    for (auto &th : pool) th.join();
+    return failed == 0;
+}
+
 static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_offsets,
                              int32_t batch, int32_t resolution, int32_t n_levels, const int32_t *ratios,
                              void *stream, bool with_device, bool device_tables, hch_levels **out)
@@ -474,15 +501,8 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
                 if (std::adjacent_find(lin.begin(), lin.end()) != lin.end()) dup = 1;
             }
         };
-        try {
-            const unsigned nthr = std::max(1u, std::min({std::thread::hardware_concurrency(), 16u, (unsigned)batch}));
-            std::vector<std::thread> pool;
-            for (unsigned i = 1; i < nthr; ++i) pool.emplace_back(check);
-            check();
-            for (auto &th : pool) th.join();
-        } catch (const std::bad_alloc &) {
-            return fail(HCH_ENOMEM, "hch_build_levels: out of host memory");
-        }
+        const unsigned nthr = std::max(1u, std::min({std::thread::hardware_concurrency(), 16u, (unsigned)batch}));
+        if (!run_on_threads(nthr, check)) return fail(HCH_ENOMEM, "hch_build_levels: out of host memory");
         if (dup) return fail(HCH_EINVAL, "hch_build_levels: duplicate voxel inside a model");
     }
 
@@ -516,10 +536,7 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
                 };
                 {
                     const unsigned nthr = std::max(1u, std::min({std::thread::hardware_concurrency(), 16u, (unsigned)batch}));
-                    std::vector<std::thread> pool;
-                    for (unsigned i = 1; i < nthr; ++i) pool.emplace_back(coarsen);
-                    coarsen();
-                    for (auto &th : pool) th.join();
+                    if (!run_on_threads(nthr, coarsen)) throw std::bad_alloc();
                 }
                 for (int v = 0; v < batch; ++v) {
                     L.coords.insert(L.coords.end(), per_model[v].begin(), per_model[v].end());
@@ -555,10 +572,7 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
             unsigned nthr = std::thread::hardware_concurrency();
             nthr = std::max(1u, std::min(nthr, 16u));
             nthr = std::min<unsigned>(nthr, (unsigned)std::max(1, n_tasks));
-            std::vector<std::thread> pool;
-            for (unsigned i = 1; i < nthr; ++i) pool.emplace_back(worker);
-            worker();
-            for (auto &th : pool) th.join();
+            if (!run_on_threads(nthr, worker)) throw std::bad_alloc();
         }
         for (int t = 0; t < n_tasks && st == HCH_OK; ++t) {
             if (result[t] == hch::BUILD_UNSUPPORTED)
@@ -1871,12 +1885,21 @@ static hch_status launch_field_unpool(const float *dY, const int32_t *argmax, co
     return HCH_OK;
 }
 
+// The fields of a pooling with F = stride > 1 and NO padding partition the input level, and every
+// input voxel lies in the field of an occupied output voxel (its parent): only then may the
+// backward pass write dX through the forward rows.  With padding an input voxel can fall into the
+// field of a position that is not occupied on the output level, and no forward row reaches it.
+static inline bool fields_partition(int32_t F, int32_t stride, int32_t pad) { return F == stride && stride > 1 && pad == 0; }
+
 extern "C" hch_status hch_spool_max_bwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
-                                        const float *dY, const int32_t *argmax, const int32_t *field,
+                                        int32_t pad, const float *dY, const int32_t *argmax, const int32_t *field,
                                         const int32_t *field_t, float *dX, int32_t c, void *stream)
 {
     const Level *Li, *Lo;
-    const bool partition = field && F == stride && stride > 1;
+    const bool partition = field && fields_partition(F, stride, pad);
+    if (pad < 0 || pad >= F) return fail(HCH_EINVAL, "hch_spool_max_bwd: padding must be in [0, F)");
+    if (!partition && !field_t)
+        return fail(HCH_EINVAL, "hch_spool_max_bwd: field_t is needed unless F = stride > 1, pad = 0 and field is given");
     hch_status st = spool_args(levels, level_in, F, stride, dY, dX, partition ? field : field_t, c, &Li, &Lo, "hch_spool_max_bwd");
     if (st != HCH_OK) return st;
     if (!argmax) return fail(HCH_EINVAL, "hch_spool_max_bwd: null argmax");
@@ -1922,11 +1945,14 @@ extern "C" hch_status hch_spool_avg_fwd(const hch_levels *levels, int32_t level_
 }
 
 extern "C" hch_status hch_spool_avg_bwd(const hch_levels *levels, int32_t level_in, int32_t F, int32_t stride,
-                                        const float *dY, const int32_t *field, const int32_t *field_t, float *dX,
-                                        int32_t c, void *stream)
+                                        int32_t pad, const float *dY, const int32_t *field, const int32_t *field_t,
+                                        float *dX, int32_t c, void *stream)
 {
     const Level *Li, *Lo;
-    const bool partition = field && F == stride && stride > 1;
+    const bool partition = field && fields_partition(F, stride, pad);
+    if (pad < 0 || pad >= F) return fail(HCH_EINVAL, "hch_spool_avg_bwd: padding must be in [0, F)");
+    if (!partition && !field_t)
+        return fail(HCH_EINVAL, "hch_spool_avg_bwd: field_t is needed unless F = stride > 1, pad = 0 and field is given");
     hch_status st = spool_args(levels, level_in, F, stride, dY, dX, partition ? field : field_t, c, &Li, &Lo, "hch_spool_avg_bwd");
     if (st != HCH_OK) return st;
     if (partition) return launch_field_unpool<false>(dY, nullptr, field, dX, Lo->n_total, Li->n_total, F * F * F, c, (hipStream_t)stream);

@@ -167,6 +167,9 @@ BuildResult build_model_tables(const int32_t *xyz, int64_t n, int ubar, ModelTab
         if (attempt(xyz, n, out.m, r, out)) break;
         if (r >= ubar) return BUILD_FAILED;      // singleton buckets cannot fail
         r = offset_side_next(r, out.m);
+        // an offset table beyond what the super tables can index (32 bits, 3 bytes per cell) is
+        // refused before anything of that size is allocated
+        if ((int64_t)r * r * r >= ((int64_t)1 << 31) / 3) return BUILD_UNSUPPORTED;
     }
     out.r = r;
     return BUILD_OK;

@@ -243,6 +243,75 @@ def test_conv_fwd_and_gradients(oracle, case_small, c_in, c_out, level, algo):
 
 
 # --------------------------------------------------------------------------------------
+# caller order is the contract: the finest level's data index is the order of the caller's
+# coordinates, whatever it is
+# --------------------------------------------------------------------------------------
+
+@pytest.fixture(scope="module")
+def case_permuted(oracle):
+    """The 64^3 / batch 32 workload with the voxels of every model in a seeded random order (the
+    generator hands them out sorted by linear position)."""
+    coords, offs, normals = S.config_batch(2, with_normals=True)
+    rng = np.random.default_rng(2718)
+    perm = np.concatenate([offs[v] + rng.permutation(int(offs[v + 1] - offs[v])) for v in range(len(offs) - 1)])
+    c = Case(oracle, np.ascontiguousarray(coords[perm]), offs, 64, 3)
+    c.normals = np.ascontiguousarray(normals[perm])
+    c.perm = perm
+    return c
+
+
+def test_permuted_input_tables_and_lists(oracle, case_permuted, case_batch64):
+    case = case_permuted
+    for l, L in enumerate(case.olv):
+        info = case.glv.info(l)
+        assert np.array_equal(info.mbar, L.mbar) and np.array_equal(info.rbar, L.rbar)
+        assert np.array_equal(info.M, L.M) and np.array_equal(info.R, L.R) and np.array_equal(info.N, L.N)
+        assert np.array_equal(info.device_H(), L.H) and np.array_equal(info.device_T(), L.T)
+        assert np.array_equal(info.device_Phi(), L.Phi) and np.array_equal(info.device_V(), L.V)
+        assert np.array_equal(info.device_coords(), L.coords)
+        nb = info.device_nbr27()
+        assert np.array_equal(nb, oracle.neighbours(L)), f"nbr27 level {l}"
+        if l > 0:
+            assert np.array_equal(info.device_child8(), oracle.children(case.olv[l - 1], L)), f"child8 level {l}"
+    # the finest level really is in the caller's order, and its lists are the sorted case's
+    # lists with rows and entries renamed by the permutation
+    assert np.array_equal(case.glv.info(0).device_coords(), case.coords)
+    inv = np.empty_like(case.perm)
+    inv[case.perm] = np.arange(case.perm.size)
+    nb_sorted = case_batch64.glv.info(0).device_nbr27()[case.perm]
+    assert np.array_equal(case.glv.info(0).device_nbr27(), np.where(nb_sorted >= 0, inv[np.maximum(nb_sorted, 0)], -1))
+
+
+@pytest.mark.parametrize("algo", ALGOS, ids=ALGO_IDS)
+@pytest.mark.parametrize("c_in,c_out", [(4, 32), (16, 4), (32, 64)])
+def test_permuted_input_conv_and_pool(oracle, case_permuted, c_in, c_out, algo):
+    case = case_permuted
+    L = case.olv[0]
+    n = L.Ntot
+    X = S.normals_plus_one(case.normals) if c_in == 4 else S.gaussian((n, c_in), 1.0, 61)
+    W = S.he_weights(c_in, c_out, 62)
+    G = S.gaussian((n, c_out), 1.0, 63)
+    Xp, Wp, Gp = oracle.to_paper_X(X), oracle.to_paper_W(W), oracle.to_paper_X(G)
+    Y = _conv_fwd_gpu(case, 0, X, W, algo=algo)
+    assert_close(Y, oracle.conv_fwd(L, Xp, Wp).T, what="fwd")
+    ws = workspace(max(hch.hch_conv_workspace_bytes(case.glv, 0, c_in, c_out, hch.HCH_F32, k, algo)
+                       for k in (hch.HCH_WS_BWD_DATA, hch.HCH_WS_BWD_WEIGHT)))
+    dX = torch.full((n, c_in), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_conv_bwd_data(case.glv, 0, hch.HCH_F32, dev(G), dev(W), dX, c_in, c_out, ws, algo)
+    assert_close(dX.cpu().numpy(), oracle.conv_bwd_data(L, Gp, Wp, c_in).T, what="bwd data")
+    dW = torch.full((27, c_in, c_out), float("nan"), dtype=torch.float32, device="cuda")
+    hch.hch_conv_bwd_weight(case.glv, 0, hch.HCH_F32, dev(X), dev(G), dW, c_in, c_out, ws, algo)
+    assert_close(dW.cpu().numpy(), oracle.from_paper_W(oracle.conv_bwd_weight(L, Xp, Gp), c_in), what="bwd weight")
+    # pooling of the GPU's own output from the permuted level to the (sorted) coarser one
+    n1 = case.olv[1].Ntot
+    P = torch.empty((n1, c_out), dtype=torch.float32, device="cuda")
+    sw = torch.empty((n1, c_out), dtype=torch.int32, device="cuda")
+    hch.hch_pool_fwd(case.glv, 0, dev(Y), P, sw, c_out)
+    Po, swo = oracle.pool_max_fwd(L, case.olv[1], oracle.to_paper_X(Y))
+    assert np.array_equal(sw.cpu().numpy(), swo.T) and np.array_equal(P.cpu().numpy(), Po.T.astype(np.float32))
+
+
+# --------------------------------------------------------------------------------------
 # pooling, ReLU
 # --------------------------------------------------------------------------------------
 

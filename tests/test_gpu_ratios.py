@@ -150,11 +150,11 @@ def test_ratio_conv_and_pooling(oracle, ratio_case):
             hch.hch_spool_avg_fwd(d["glv"], level_in, F, stride, dev(Xc), field, A, c)
             assert_close(A.cpu().numpy(), oracle.avgpool_fwd(Li, Lo, oracle.to_paper_X(Xc), F, stride, pad).T, what="avg fwd")
             dA = torch.full((Li.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
-            hch.hch_spool_avg_bwd(d["glv"], level_in, F, stride, dev(Gc), None, field_t, dA, c)
+            hch.hch_spool_avg_bwd(d["glv"], level_in, F, stride, pad, dev(Gc), None, field_t, dA, c)
             assert_close(dA.cpu().numpy(), oracle.avgpool_bwd(Li, Lo, oracle.to_paper_X(Gc), F, stride, pad).T, what="avg bwd")
-            if F == stride:         # the fields partition the input level: the form that writes through `field`
+            if F == stride and pad == 0:   # the fields partition the input level: the form that writes through `field`
                 dA2 = torch.full((Li.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
-                hch.hch_spool_avg_bwd(d["glv"], level_in, F, stride, dev(Gc), field, None, dA2, c)
+                hch.hch_spool_avg_bwd(d["glv"], level_in, F, stride, pad, dev(Gc), field, None, dA2, c)
                 assert torch.equal(dA, dA2)
             if F > stride:
                 continue        # overlapping fields: the oracle's switch routing is defined for disjoint ones
@@ -165,12 +165,12 @@ def test_ratio_conv_and_pooling(oracle, ratio_case):
             assert np.array_equal(sw.cpu().numpy(), swo.T)
             assert np.array_equal(P.cpu().numpy(), Po.T.astype(np.float32))
             dP = torch.full((Li.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
-            hch.hch_spool_max_bwd(d["glv"], level_in, F, stride, dev(Gc), sw, None, field_t, dP, c)
+            hch.hch_spool_max_bwd(d["glv"], level_in, F, stride, pad, dev(Gc), sw, None, field_t, dP, c)
             want = oracle.pool_max_bwd(Li.Ntot, oracle.to_paper_X(Gc), swo).T
             assert np.array_equal(dP.cpu().numpy(), want.astype(np.float32))
-            if F == stride:
+            if F == stride and pad == 0:
                 dP2 = torch.full((Li.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
-                hch.hch_spool_max_bwd(d["glv"], level_in, F, stride, dev(Gc), sw, field, None, dP2, c)
+                hch.hch_spool_max_bwd(d["glv"], level_in, F, stride, pad, dev(Gc), sw, field, None, dP2, c)
                 assert torch.equal(dP, dP2)
 
 
@@ -192,20 +192,65 @@ def test_field_pooling_equals_child_pooling(oracle):
         assert torch.equal(P1, P2) and torch.equal(s1, s2)
         d1, d2 = (torch.empty((nf, c), dtype=torch.float32, device="cuda") for _ in range(2))
         hch.hch_pool_bwd(glv, 0, G, s1, d1, c)
-        hch.hch_spool_max_bwd(glv, 0, 2, 2, G, s2, None, field_t, d2, c)
+        hch.hch_spool_max_bwd(glv, 0, 2, 2, 0, G, s2, None, field_t, d2, c)
         assert torch.equal(d1, d2)
         d2.fill_(float("nan"))
-        hch.hch_spool_max_bwd(glv, 0, 2, 2, G, s2, field, None, d2, c)
+        hch.hch_spool_max_bwd(glv, 0, 2, 2, 0, G, s2, field, None, d2, c)
         assert torch.equal(d1, d2)
         hch.hch_avgpool_fwd(glv, 0, X, P1, c)
         hch.hch_spool_avg_fwd(glv, 0, 2, 2, X, field, P2, c)
         assert torch.equal(P1, P2)
         hch.hch_avgpool_bwd(glv, 0, G, d1, c)
-        hch.hch_spool_avg_bwd(glv, 0, 2, 2, G, None, field_t, d2, c)
+        hch.hch_spool_avg_bwd(glv, 0, 2, 2, 0, G, None, field_t, d2, c)
         assert torch.equal(d1, d2)
         d2.fill_(float("nan"))
-        hch.hch_spool_avg_bwd(glv, 0, 2, 2, G, field, None, d2, c)
+        hch.hch_spool_avg_bwd(glv, 0, 2, 2, 0, G, field, None, d2, c)
         assert torch.equal(d1, d2)
+
+
+def test_padded_partition_pooling_backward(oracle):
+    """F = stride with padding: the fields still tile the grid, but an input voxel can lie in the
+    field of a position that is unoccupied on the output level, where no forward row reaches it.
+    Its gradient is zero; dX is prefilled with NaN to show that every row is written.  With
+    padding the backward calls must go through field_t, whether or not `field` is passed."""
+    coords, offs, _ = S.config_batch(2, batch=3, u=64)
+    olv = oracle.build_hierarchy(coords, offs, 64, 2)
+    glv = hch.hch_build_levels(coords, offs, 64, 2)
+    Li, Lo = olv[0], olv[1]
+    F, stride, pad = 2, 2, 1
+    field = torch.empty((Lo.Ntot, 8), dtype=torch.int32, device="cuda")
+    field_t = torch.empty((Li.Ntot, 8), dtype=torch.int32, device="cuda")
+    hch.hch_field_build(glv, 0, F, stride, pad, field, field_t)
+    want_field = oracle.field_indices(Li, Lo, F, stride, pad)
+    assert np.array_equal(field.cpu().numpy(), want_field)
+    covered = np.zeros(Li.Ntot, bool)
+    covered[want_field[want_field >= 0]] = True
+    assert not covered.all(), "the case must contain input voxels that no occupied output's field holds"
+    for c in (8, 5):
+        Xc, Gc = S.gaussian((Li.Ntot, c), 1.0, 181), S.gaussian((Lo.Ntot, c), 1.0, 182)
+        want_avg = oracle.avgpool_bwd(Li, Lo, oracle.to_paper_X(Gc), F, stride, pad).T
+        assert np.all(want_avg[~covered] == 0)
+        for f in (field, None):
+            dA = torch.full((Li.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
+            hch.hch_spool_avg_bwd(glv, 0, F, stride, pad, dev(Gc), f, field_t, dA, c)
+            assert_close(dA.cpu().numpy(), want_avg, what="avg bwd, padded partition")
+        P = torch.full((Lo.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
+        sw = torch.full((Lo.Ntot, c), -9, dtype=torch.int32, device="cuda")
+        hch.hch_spool_max_fwd(glv, 0, F, stride, dev(Xc), field, P, sw, c)
+        Po, swo = oracle.pool_max_fwd(Li, Lo, oracle.to_paper_X(Xc), F, stride, pad)
+        assert np.array_equal(sw.cpu().numpy(), swo.T) and np.array_equal(P.cpu().numpy(), Po.T.astype(np.float32))
+        # an output voxel whose padded field is empty has the switch -1 and routes nothing
+        want_max = oracle.pool_max_bwd(Li.Ntot, oracle.to_paper_X(Gc), swo)
+        for f in (field, None):
+            dP = torch.full((Li.Ntot, c), float("nan"), dtype=torch.float32, device="cuda")
+            hch.hch_spool_max_bwd(glv, 0, F, stride, pad, dev(Gc), sw, f, field_t, dP, c)
+            assert np.array_equal(dP.cpu().numpy(), want_max.T.astype(np.float32))
+        with pytest.raises(hch.HchError) as ei:        # the forward rows alone cannot serve a padded field
+            hch.hch_spool_max_bwd(glv, 0, F, stride, pad, dev(Gc), sw, field, None, dP, c)
+        assert ei.value.status == 1
+        with pytest.raises(hch.HchError) as ei:
+            hch.hch_spool_avg_bwd(glv, 0, F, stride, pad, dev(Gc), field, None, dA, c)
+        assert ei.value.status == 1
 
 
 def test_ratio_errors(oracle, ratio_case):
