@@ -277,6 +277,29 @@ hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t level, hch_dtyp
                                void *stream);
 
 /*
+ * hch_conv_bwd_weight with HCH_ALGO_FUSED for callers that can neither allocate device memory nor
+ * hand over a workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The call itself allocates nothing (no hipMalloc / hipFree, no allocating library
+ * routine): the partial sums of its split reduction go to an array of HCH_NOALLOC_SCRATCH_BYTES
+ * bytes that is part of the library's device image, so every GPU the library runs on holds that
+ * much memory until the process ends.  Same arguments (minus workspace and algorithm), same
+ * kernels, same bits in dW as hch_conv_bwd_weight(..., HCH_ALGO_FUSED).
+ * Errors: as hch_conv_bwd_weight, and HCH_EWORKSPACE when the product's partial sums,
+ * hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, HCH_WS_BWD_WEIGHT, HCH_ALGO_FUSED),
+ * exceed HCH_NOALLOC_SCRATCH_BYTES (nothing is launched then; the library's split planning fills
+ * one round of workgroups, which keeps those sums below 24 MiB for every level and channel count,
+ * so this only guards against a change of that planning).
+ * All calls on one GPU share the one array: calls that may overlap on a GPU (different streams,
+ * different host threads) race on it and must be serialised by the caller; calls on the same
+ * stream are ordered.  The array keeps the last call's partial sums; every call overwrites all the
+ * entries it later reads, so nothing needs clearing in between.
+ */
+#define HCH_NOALLOC_SCRATCH_BYTES (32u << 20)
+hch_status hch_conv_bwd_weight_noalloc(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                                       const void *X, const void *dY, float *dW, int32_t c_in,
+                                       int32_t c_out, void *stream);
+
+/*
  * 2x2x2 stride-2 max-pooling from level_in (fine) to level_in + 1 (coarse) (Section 4,
  * pooling): per coarse voxel and channel the maximum over the OCCUPIED children, and the
  * switch = global data index (at level_in) of the child holding it; the first child in

@@ -20,6 +20,7 @@ __all__ = [
     "hch_profile_reset", "hch_field_build", "hch_sconv_workspace_bytes", "hch_sconv_fwd", "hch_sconv_bwd_weight",
     "hch_sconv_bwd_data", "hch_avgpool_fwd", "hch_avgpool_bwd", "hch_build_levels_ratios",
     "hch_spool_max_fwd", "hch_spool_max_bwd", "hch_spool_avg_fwd", "hch_spool_avg_bwd", "hch_build_tap_major",
+    "hch_conv_bwd_weight_noalloc", "HCH_NOALLOC_SCRATCH_BYTES",
 ]
 
 HCH_F32, HCH_BF16 = 0, 1
@@ -41,6 +42,8 @@ exported_symbols = [
     "hch_profile_reset", "hch_field_build", "hch_sconv_workspace_bytes", "hch_sconv_fwd", "hch_sconv_bwd_weight",
     "hch_sconv_bwd_data", "hch_avgpool_fwd", "hch_avgpool_bwd", "hch_build_levels_ratios",
     "hch_spool_max_fwd", "hch_spool_max_bwd", "hch_spool_avg_fwd", "hch_spool_avg_bwd", "hch_build_tap_major",
+    "hch_conv_bwd_weight_noalloc",
+    "hch_conv_bwd_weight_noalloc",
 ]
 
 
@@ -116,6 +119,7 @@ def load_library():
     for name in ("hch_conv_fwd", "hch_conv_bwd_data", "hch_conv_bwd_weight",
                  "hch_deconv_fwd", "hch_deconv_bwd_data", "hch_deconv_bwd_weight"):
         getattr(L, name).argtypes = [vp, i32, C.c_int, vp, vp, vp, i32, i32, vp, sz, C.c_int, vp]
+    L.hch_conv_bwd_weight_noalloc.argtypes = [vp, i32, C.c_int, vp, vp, vp, i32, i32, vp]
     L.hch_pool_fwd.argtypes = [vp, i32, vp, vp, vp, i32, vp]
     L.hch_pool_bwd.argtypes = [vp, i32, vp, vp, vp, i32, vp]
     L.hch_relu_pool_fwd.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
@@ -443,6 +447,17 @@ def hch_conv_bwd_data(levels, level, dtype, dY, W, dX, c_in, c_out, workspace, a
 
 def hch_conv_bwd_weight(levels, level, dtype, X, dY, dW, c_in, c_out, workspace, algo=HCH_ALGO_COLUMNS, stream=None):
     _conv_like("hch_conv_bwd_weight", levels, level, dtype, X, c_in, dY, c_out, dW, None, c_in, c_out, workspace, algo, stream)
+
+
+HCH_NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def hch_conv_bwd_weight_noalloc(levels, level, dtype, X, dY, dW, c_in, c_out, stream=None):
+    n, dt = _level_n(levels, level), _in_dtype(dtype)
+    _check(load_library().hch_conv_bwd_weight_noalloc(levels.handle, level, dtype, _dp(X, "X", dt, n * c_in),
+                                                      _dp(dY, "dY", dt, n * c_out),
+                                                      _dp(dW, "dW", _F32, 27 * c_in * c_out), c_in, c_out,
+                                                      _stream(stream)))
 
 
 def hch_deconv_fwd(levels, level, dtype, X, W, Y, c_in, c_out, workspace, algo=HCH_ALGO_COLUMNS, stream=None):

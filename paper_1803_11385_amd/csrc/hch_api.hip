@@ -1392,18 +1392,18 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
     return do_col2hash(*L, dcol, c_in, dX, planes, s);
 }
 
-extern "C" hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t level, hch_dtype dtype,
-                                          const void *X, const void *dY, float *dW, int32_t c_in,
-                                          int32_t c_out, void *workspace, size_t ws_bytes, hch_algo algo,
-                                          void *stream)
+static hch_status conv_bwd_weight_impl(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                                       const void *X, const void *dY, float *dW, int32_t c_in,
+                                       int32_t c_out, void *workspace, size_t ws_bytes, hch_algo algo,
+                                       void *stream, const char *who)
 {
     const Level *L;
     const bool resident = algo == HCH_ALGO_COLUMNS_RESIDENT;     // the column matrix is in the workspace already
     if (resident) algo = HCH_ALGO_COLUMNS;
-    hch_status st = conv_args(levels, level, dtype, X, dY, dW, c_in, c_out, workspace, algo, &L, "hch_conv_bwd_weight");
+    hch_status st = conv_args(levels, level, dtype, X, dY, dW, c_in, c_out, workspace, algo, &L, who);
     if (st != HCH_OK) return st;
     if (ws_bytes < hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, HCH_WS_BWD_WEIGHT, algo))
-        return fail(HCH_EWORKSPACE, "hch_conv_bwd_weight: workspace too small");
+        return fail(HCH_EWORKSPACE, std::string(who) + ": workspace too small");
     hipStream_t s = (hipStream_t)stream;
     const int Kc = 27 * c_in;
     const int64_t n = L->n_total;
@@ -1432,6 +1432,73 @@ extern "C" hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t leve
     if (st != HCH_OK) return st;
     if (p.splits > 1) st = launch_reduce(part, dW, wsize, p.splits, s);
     return st;
+}
+
+extern "C" hch_status hch_conv_bwd_weight(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                                          const void *X, const void *dY, float *dW, int32_t c_in,
+                                          int32_t c_out, void *workspace, size_t ws_bytes, hch_algo algo,
+                                          void *stream)
+{
+    return conv_bwd_weight_impl(levels, level, dtype, X, dY, dW, c_in, c_out, workspace, ws_bytes, algo, stream,
+                                "hch_conv_bwd_weight");
+}
+
+// ---------------------------------------------------------------------------------------
+// The weight gradient for callers that cannot allocate and bring no workspace: the partial sums of
+// the split reduction live in a fixed array in device memory that every GPU the library runs on
+// holds until the process ends.
+// ---------------------------------------------------------------------------------------
+
+// The array's name is only a host-side handle of the symbol; the device address is asked for
+// once per device (each GPU has its own copy at its own address) and only that pointer is
+// handed to kernels.
+static __device__ __align__(256) unsigned char scratch[HCH_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::atomic<void *> g_scratch_ptr[MAX_DEVICES];
+}
+
+static hch_status scratch_address(void **out)
+{
+    int dev = -1;
+    HCH_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(HCH_EUNSUPPORTED, "hch_conv_bwd_weight_noalloc: device ordinal above 63");
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        // two threads may both ask; they get the same answer
+        HCH_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || (reinterpret_cast<uintptr_t>(p) & 255u))
+            return fail(HCH_EHIP, "hch_conv_bwd_weight_noalloc: no usable address for the scratch array");
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return HCH_OK;
+}
+
+extern "C" hch_status hch_conv_bwd_weight_noalloc(const hch_levels *levels, int32_t level, hch_dtype dtype,
+                                                  const void *X, const void *dY, float *dW, int32_t c_in,
+                                                  int32_t c_out, void *stream)
+{
+    if (!levels || level < 0 || level >= (int32_t)levels->lv.size() || c_in <= 0 || c_out <= 0)
+        return fail(HCH_EINVAL, "hch_conv_bwd_weight_noalloc: bad level or channel count");
+    if (dtype != HCH_F32 && dtype != HCH_BF16) return fail(HCH_EINVAL, "hch_conv_bwd_weight_noalloc: unknown dtype");
+    if ((int64_t)27 * c_in * c_out >= ((int64_t)1 << 31))
+        return fail(HCH_EINVAL, "hch_conv_bwd_weight_noalloc: weight tensor too large");
+    const size_t need = hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, HCH_WS_BWD_WEIGHT, HCH_ALGO_FUSED);
+    if (need == 0 || need > (size_t)HCH_NOALLOC_SCRATCH_BYTES)
+        return fail(HCH_EWORKSPACE, "hch_conv_bwd_weight_noalloc: the partial sums of this product need " +
+                                        std::to_string(need) + " bytes, the built-in scratch array holds " +
+                                        std::to_string((size_t)HCH_NOALLOC_SCRATCH_BYTES) +
+                                        "; use hch_conv_bwd_weight with a workspace");
+    void *ptr = nullptr;
+    hch_status st = scratch_address(&ptr);
+    if (st != HCH_OK) return st;
+    // every slice of the split reduction writes all of its 27*c_in*c_out partial sums (zeros where
+    // its range of voxels is empty) before the reduction kernel reads them: nothing has to be
+    // cleared between calls
+    return conv_bwd_weight_impl(levels, level, dtype, X, dY, dW, c_in, c_out, ptr, (size_t)HCH_NOALLOC_SCRATCH_BYTES,
+                                HCH_ALGO_FUSED, stream, "hch_conv_bwd_weight_noalloc");
 }
 
 // ---------------------------------------------------------------------------------------
