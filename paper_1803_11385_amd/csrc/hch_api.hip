@@ -396,7 +396,7 @@ static hch_status device_construct(hch_levels *hl, hipStream_t s)
         HCH_HIP(hipMemcpyAsync(d_pd, pd.data(), pd.size() * sizeof(hch::PackDesc), hipMemcpyHostToDevice, s));
         HCH_HIP(hipMalloc((void **)&L.dPhi, std::max<size_t>(16, (size_t)L.r_total * 3)));
         HCH_HIP(hipMalloc((void **)&L.dphi4, std::max<size_t>(16, (size_t)L.r_total * 4)));
-        HCH_HIP(hipMalloc((void **)&L.dslot3, (size_t)L.m_total * 12));
+        HCH_HIP(hipMalloc((void **)&L.dslot3, (size_t)L.m_total * 4 * hch::SLOT_WORDS));
         HCH_LAUNCH(hch::psh_pack_kernel, dim3((unsigned)((widest + 255) / 256), (unsigned)batch), dim3(256), 0, s,
                            d_pd, L.dH, L.dT, L.dslot3, L.dV, L.dphi4, L.dPhi);
         HCH_LAUNCH_CHECK("psh_pack_kernel");
@@ -630,11 +630,12 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
             if ((st = upload((void **)&L.dPhi, L.Phi.data(), L.Phi.size(), s)) != HCH_OK) break;
             if ((st = upload((void **)&L.dcoords, L.coords.data(), L.coords.size() * 4, s)) != HCH_OK) break;
             if ((st = upload((void **)&L.dmeta, meta.data(), meta.size() * 4, s)) != HCH_OK) break;
-            std::vector<uint32_t> slot3((size_t)L.m_total * 3), phi4((size_t)L.r_total);
+            constexpr int SW = hch::SLOT_WORDS;
+            std::vector<uint32_t> slot3((size_t)L.m_total * SW, 0u), phi4((size_t)L.r_total);
             for (int64_t q = 0; q < L.m_total; ++q) {
-                slot3[3 * q + 0] = (uint32_t)L.H[q];
-                slot3[3 * q + 1] = (uint32_t)L.T[3 * q] | ((uint32_t)L.T[3 * q + 1] << 16);
-                slot3[3 * q + 2] = (uint32_t)L.T[3 * q + 2];
+                slot3[SW * q + 0] = (uint32_t)L.H[q];
+                slot3[SW * q + 1] = (uint32_t)L.T[3 * q] | ((uint32_t)L.T[3 * q + 1] << 16);
+                slot3[SW * q + 2] = (uint32_t)L.T[3 * q + 2];
             }
             for (int64_t q = 0; q < L.r_total; ++q)
                 phi4[q] = (uint32_t)L.Phi[3 * q] | ((uint32_t)L.Phi[3 * q + 1] << 8) | ((uint32_t)L.Phi[3 * q + 2] << 16);

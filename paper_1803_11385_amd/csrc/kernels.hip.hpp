@@ -31,12 +31,14 @@ __device__ int32_t g_minus1 = -1;                                               
 // ---------------------------------------------------------------------------------------
 
 // Device view of one level of the mini-batch super-PSH.  The lookup kernels read packed
-// copies of the paper's tables: one 12-byte record per hash slot
-//   slot3[3s] = H*[s],  slot3[3s+1] = T*[s].x | T*[s].y << 16,  slot3[3s+2] = T*[s].z
+// copies of the paper's tables: one 16-byte record per hash slot (a record never straddles a
+// cache line, so a probe is exactly one cache access)
+//   slot3[4s] = H*[s],  slot3[4s+1] = T*[s].x | T*[s].y << 16,  slot3[4s+2] = T*[s].z,  slot3[4s+3] = 0
 // and one 32-bit word per offset cell, phi4[c] = Phi*[c].x | .y << 8 | .z << 16.
 // Prefix arrays are 32-bit on the device (the host checks that they fit).
+constexpr int SLOT_WORDS = 4;
 struct PshView {
-    const uint32_t *slot3;  // [M_total][3]
+    const uint32_t *slot3;  // [M_total][SLOT_WORDS]
     const uint32_t *phi4;   // [R_total]
     const int32_t *mbar;    // [b]
     const int32_t *rbar;    // [b]
@@ -69,8 +71,10 @@ __device__ __forceinline__ const uint32_t *psh_slot(const PshView &L, unsigned M
     unsigned hx = xm + (ph & 255u);         if (hx >= m) hx -= m;
     unsigned hy = ym + ((ph >> 8) & 255u);  if (hy >= m) hy -= m;
     unsigned hz = zm + ((ph >> 16) & 255u); if (hz >= m) hz -= m;
-    return L.slot3 + 3u * (size_t)(Mv + (hx * m + hy) * m + hz);
+    return L.slot3 + (size_t)SLOT_WORDS * (size_t)(Mv + (hx * m + hy) * m + hz);
 }
+// the record itself: one aligned 16-byte load
+__device__ __forceinline__ u32x4 psh_record(const uint32_t *rec) { return *reinterpret_cast<const u32x4 *>(rec); }
 // Step 3: the local data index if the record is occupied and tagged with (x,y,z), else -1
 // (Section 3.1: redundant slot, or a slot that belongs to another position).
 __device__ __forceinline__ int32_t psh_match(uint32_t h, uint32_t xy, uint32_t zz,
@@ -106,14 +110,25 @@ __device__ __forceinline__ int find_entry(const int32_t *__restrict__ prefix, in
 // "Pre-stored neighbour information": for every voxel the global data indices of its 27
 // neighbours p + (dx,dy,dz), tap k = (dx+1)*9 + (dy+1)*3 + (dz+1), or -1 (empty, or outside
 // the grid: never hashed).  This is the index side of the stride-1 traversal of Algorithm 1.
-// One thread per voxel: the six residues are computed once and stepped to the neighbours; the
-// 256 x 27 tile goes through LDS so that the rows are written coalesced.  Tiles
+// One thread per voxel: the six residues are computed once and stepped to the neighbours.  Tiles
 // [tile_first, tile_first + n_tiles) are processed, numbered XCD-contiguously: the tiles of one
 // model (whose tables are a few hundred KB) then stay in one XCD's L2.
+//
+// A probe is two dependent loads, the offset cell (Eq.4) and the slot record (Eq.5), and the
+// kernel is bound by the number of such cache accesses, not by bytes.  The offset cells a tile
+// needs are the planes x' mod r of Phi for x' in [xmin - 1, xmax + 1] over the tile's voxels; when
+// these fit (a tile of voxels that lie close together in x: always the case for data ordered by
+// position, and for small tables) they are copied to LDS once, with coalesced loads, and the 26
+// offset reads of every voxel come from there; otherwise the cells are read from memory as the
+// slot records are.  The centre tap is the voxel itself.  Results are kept in registers until
+// all probes of the workgroup are done, then go through the same LDS space so that the rows are
+// written coalesced.
+constexpr int NBR_LDS_WORDS = 256 * 27;
 __global__ __launch_bounds__(256) void neighbour_kernel(
     LevelSet S, const int32_t *__restrict__ tile_prefix, int n_entries, int tile_first, unsigned n_tiles)
 {
-    __shared__ int32_t tile[256 * 27];
+    __shared__ uint32_t lds[NBR_LDS_WORDS];          // offset planes first, the 256 x 27 result tile afterwards
+    __shared__ int32_t xrange[8];
     const unsigned t = xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
     if (t >= n_tiles) return;
     const int flat = tile_first + (int)t;
@@ -124,41 +139,88 @@ __global__ __launch_bounds__(256) void neighbour_kernel(
     const int32_t n = L.N[v + 1] - base;
     const int32_t blk0 = (flat - tile_prefix[e]) * 256;
     const int32_t i = blk0 + threadIdx.x;
-    if (i < n) {
-        const unsigned m = (unsigned)L.mbar[v], r = (unsigned)L.rbar[v];
-        const unsigned Mv = (unsigned)L.M[v], Rv = (unsigned)L.R[v], u = (unsigned)L.ubar;
+    const bool live = i < n;
+    const unsigned m = (unsigned)L.mbar[v], r = (unsigned)L.rbar[v];
+    const unsigned Mv = (unsigned)L.M[v], Rv = (unsigned)L.R[v], u = (unsigned)L.ubar;
+    unsigned x = 0, y = 0, z = 0;
+    if (live) {
         const int32_t *p = S.coords[lev] + 3 * (int64_t)(base + i);
-        const unsigned x = (unsigned)p[0], y = (unsigned)p[1], z = (unsigned)p[2];
+        x = (unsigned)p[0]; y = (unsigned)p[1]; z = (unsigned)p[2];
+    }
+    // smallest and largest x of the tile
+    int xlo = live ? (int)x : 0x7fffffff, xhi = live ? (int)x : -1;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        xlo = min(xlo, __shfl_xor(xlo, d));
+        xhi = max(xhi, __shfl_xor(xhi, d));
+    }
+    if ((threadIdx.x & 63) == 0) { xrange[threadIdx.x >> 6] = xlo; xrange[4 + (threadIdx.x >> 6)] = xhi; }
+    __syncthreads();
+    xlo = min(min(xrange[0], xrange[1]), min(xrange[2], xrange[3]));
+    xhi = max(max(xrange[4], xrange[5]), max(xrange[6], xrange[7]));
+    // planes of Phi to stage: residues res0, res0 + 1, ... (mod r) of x' = xlo - 1 .. xhi + 1
+    const unsigned r2 = r * r;
+    const unsigned planes = min((unsigned)(xhi - xlo + 3), r);
+    const bool staged = planes * r2 <= (unsigned)NBR_LDS_WORDS;
+    const unsigned xlo_r = (unsigned)xlo % r;
+    const unsigned res0 = xlo_r == 0 ? r - 1 : xlo_r - 1;
+    if (staged) {
+        unsigned res = res0;
+        for (unsigned pl = 0; pl < planes; ++pl) {
+            const uint32_t *src = L.phi4 + Rv + res * r2;
+            for (unsigned q = threadIdx.x; q < r2; q += 256) lds[pl * r2 + q] = src[q];
+            if (++res == r) res = 0;
+        }
+    }
+    __syncthreads();
+
+    int32_t out[27];
+    if (live) {
         unsigned xm[3], ym[3], zm[3], xr[3], yr[3], zr[3];
         residues3(x % m, m, xm); residues3(y % m, m, ym); residues3(z % m, m, zm);
         residues3(x % r, r, xr); residues3(y % r, r, yr); residues3(z % r, r, zr);
-        int32_t *row = tile + threadIdx.x * 27;
-        // one x-plane of 9 neighbours at a time: 9 offset loads, then 9 record loads, then the
+        // one x-plane of 9 neighbours at a time: 9 offset reads, then 9 record loads, then the
         // comparisons.  Positions outside the grid are probed too (their residues are valid
         // table coordinates) and discarded afterwards, so there is no branch between the loads.
 #pragma unroll
         for (int a = 0; a < 3; ++a) {
             uint32_t ph[9];
+            if (staged) {
+                unsigned pl = xr[a] >= res0 ? xr[a] - res0 : xr[a] + r - res0;
+                const uint32_t *plane = lds + pl * r2;
 #pragma unroll
-            for (int q = 0; q < 9; ++q) ph[q] = psh_offset(L, Rv, r, xr[a], yr[q / 3], zr[q % 3]);
+                for (int q = 0; q < 9; ++q) ph[q] = plane[yr[q / 3] * r + zr[q % 3]];
+            } else {
+#pragma unroll
+                for (int q = 0; q < 9; ++q) ph[q] = psh_offset(L, Rv, r, xr[a], yr[q / 3], zr[q % 3]);
+            }
             uint32_t rh[9], rxy[9], rz[9];
 #pragma unroll
             for (int q = 0; q < 9; ++q) {
-                const uint32_t *rec = psh_slot(L, Mv, m, ph[q], xm[a], ym[q / 3], zm[q % 3]);
+                if (a == 1 && q == 4) continue;          // the voxel itself
+                const u32x4 rec = psh_record(psh_slot(L, Mv, m, ph[q], xm[a], ym[q / 3], zm[q % 3]));
                 rh[q] = rec[0]; rxy[q] = rec[1]; rz[q] = rec[2];
             }
 #pragma unroll
             for (int q = 0; q < 9; ++q) {
+                if (a == 1 && q == 4) { out[13] = base + i; continue; }
                 const unsigned qx = x + a - 1, qy = y + q / 3 - 1, qz = z + q % 3 - 1;   // wrap below 0
                 const int32_t h = psh_match(rh[q], rxy[q], rz[q], qx, qy, qz);
                 const bool inside = (qx < u) & (qy < u) & (qz < u);
-                row[a * 9 + q] = (inside & (h >= 0)) ? base + h : -1;                    // Eq.6
+                out[a * 9 + q] = (inside & (h >= 0)) ? base + h : -1;                    // Eq.6
             }
         }
+    }
+    __syncthreads();                                  // every thread is done with the offset planes
+    if (live) {
+        int32_t *row = reinterpret_cast<int32_t *>(lds) + threadIdx.x * 27;
+#pragma unroll
+        for (int k = 0; k < 27; ++k) row[k] = out[k];
     }
     __syncthreads();
     const int32_t cnt = min(256, n - blk0) * 27;
     int32_t *dst = S.nbr[lev] + (int64_t)(base + blk0) * 27;
+    const int32_t *tile = reinterpret_cast<const int32_t *>(lds);
     for (int q = threadIdx.x; q < cnt; q += 256) dst[q] = tile[q];
 }
 
@@ -212,7 +274,7 @@ __global__ __launch_bounds__(256) void child_kernel(
     for (int q = 0; q < 8; ++q) ph[q] = psh_offset(Lf, Rv, r, xr[q >> 2], yr[(q >> 1) & 1], zr[q & 1]);
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-        const uint32_t *rec = psh_slot(Lf, Mv, m, ph[q], xm[q >> 2], ym[(q >> 1) & 1], zm[q & 1]);
+        const u32x4 rec = psh_record(psh_slot(Lf, Mv, m, ph[q], xm[q >> 2], ym[(q >> 1) & 1], zm[q & 1]));
         rh[q] = rec[0]; rxy[q] = rec[1]; rz[q] = rec[2];
     }
 #pragma unroll
@@ -232,7 +294,7 @@ __device__ __forceinline__ int32_t psh_lookup(const PshView &L, int v, unsigned 
 {
     const unsigned m = (unsigned)L.mbar[v], r = (unsigned)L.rbar[v];
     const uint32_t ph = psh_offset(L, (unsigned)L.R[v], r, x % r, y % r, z % r);
-    const uint32_t *rec = psh_slot(L, (unsigned)L.M[v], m, ph, x % m, y % m, z % m);
+    const u32x4 rec = psh_record(psh_slot(L, (unsigned)L.M[v], m, ph, x % m, y % m, z % m));
     const int32_t h = psh_match(rec[0], rec[1], rec[2], x, y, z);
     return h >= 0 ? L.N[v] + h : -1;
 }

@@ -271,9 +271,10 @@ __global__ __launch_bounds__(256) void psh_pack_kernel(const PackDesc *__restric
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i < D.m3) {
         const int64_t q = (int64_t)D.M + i;
-        slot3[3 * q + 0] = (uint32_t)H[q];
-        slot3[3 * q + 1] = (uint32_t)T[3 * q] | ((uint32_t)T[3 * q + 1] << 16);
-        slot3[3 * q + 2] = (uint32_t)T[3 * q + 2];
+        slot3[SLOT_WORDS * q + 0] = (uint32_t)H[q];
+        slot3[SLOT_WORDS * q + 1] = (uint32_t)T[3 * q] | ((uint32_t)T[3 * q + 1] << 16);
+        slot3[SLOT_WORDS * q + 2] = (uint32_t)T[3 * q + 2];
+        if (SLOT_WORDS > 3) slot3[SLOT_WORDS * q + 3] = 0u;
         V[q] = (int32_t)blockIdx.y;
     }
     if (i < D.r3) {
