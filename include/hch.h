@@ -85,6 +85,14 @@ typedef struct {
     const int32_t *nbr27;    /* [n_total][27] global data index of neighbour k, or -1           */
     const int32_t *child8;   /* [n_total][8]  global data index AT THE NEXT FINER LEVEL of child
                                 k = dx*4 + dy*2 + dz at 2p + (dx,dy,dz), or -1; NULL at level 0  */
+    const int32_t *row_order;/* [n_total]     the level's data indices in "pattern order": sorted
+                                (stably) by a 6-bit key, one bit per pair of opposite edge-adjacent
+                                neighbours (taps k and 26-k, k = 1, 3, .., 11; first pair = most
+                                significant bit): set if either exists.  Consecutive entries have
+                                similar sets of neighbours.  NULL for host-only level sets        */
+    const uint32_t *tile_taps;/* [ceil(n_total/64)] bit k of entry b: some voxel among
+                                row_order[64b .. 64b+63] has neighbour k.  The fused products
+                                work on such tiles and leave out the taps a tile lacks            */
 } hch_level_desc;
 
 const char *hch_last_error(void);
@@ -220,8 +228,12 @@ hch_status hch_col2hash(const hch_levels *levels, int32_t level, const float *dc
  *                     at its start (same level, c_in, dtype and X; a workspace of at least the
  *                     HCH_WS_FWD size, so that the forward pass ran in one piece, and not used by
  *                     another call since), so hash2col is not run again.  The caller vouches for
- *                     the contents; sizes as for HCH_ALGO_COLUMNS.  */
-typedef enum { HCH_ALGO_COLUMNS = 0, HCH_ALGO_FUSED = 1, HCH_ALGO_COLUMNS_RESIDENT = 2 } hch_algo;
+ *                     the contents; sizes as for HCH_ALGO_COLUMNS.
+ *   HCH_ALGO_FUSED_DENSE  HCH_ALGO_FUSED without its tap compaction: where the fused algorithm
+ *                     would compact, tap by tap, the voxels whose neighbour exists and multiply
+ *                     only those rows, this one multiplies whole rows of the column matrix, zeros
+ *                     included (what the paper's dense GEMM does).  For measurement.  */
+typedef enum { HCH_ALGO_COLUMNS = 0, HCH_ALGO_FUSED = 1, HCH_ALGO_COLUMNS_RESIDENT = 2, HCH_ALGO_FUSED_DENSE = 3 } hch_algo;
 
 typedef enum {
     HCH_WS_FWD = 0,         /* hch_conv_fwd: everything in one pass                            */

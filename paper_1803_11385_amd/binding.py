@@ -10,7 +10,7 @@ import numpy as np
 __all__ = [
     "HchError", "Levels", "LevelInfo", "HCH_F32", "HCH_BF16",
     "HCH_WS_FWD", "HCH_WS_BWD_DATA", "HCH_WS_BWD_WEIGHT", "HCH_WS_MIN",
-    "HCH_ALGO_COLUMNS", "HCH_ALGO_FUSED", "HCH_ALGO_COLUMNS_RESIDENT",
+    "HCH_ALGO_COLUMNS", "HCH_ALGO_FUSED", "HCH_ALGO_COLUMNS_RESIDENT", "HCH_ALGO_FUSED_DENSE",
     "library_path", "load_library", "exported_symbols",
     "hch_build_levels", "hch_build_levels_device", "hch_build_tables_host", "hch_build_neighbours",
     "hch_build_neighbours_range", "hch_hash2col", "hch_col2hash", "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data",
@@ -25,7 +25,7 @@ __all__ = [
 
 HCH_F32, HCH_BF16 = 0, 1
 HCH_WS_FWD, HCH_WS_BWD_DATA, HCH_WS_BWD_WEIGHT, HCH_WS_MIN = 0, 1, 2, 3
-HCH_ALGO_COLUMNS, HCH_ALGO_FUSED, HCH_ALGO_COLUMNS_RESIDENT = 0, 1, 2
+HCH_ALGO_COLUMNS, HCH_ALGO_FUSED, HCH_ALGO_COLUMNS_RESIDENT, HCH_ALGO_FUSED_DENSE = 0, 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIBPATH = os.path.join(_HERE, "libhch.so")
@@ -61,7 +61,8 @@ class _Desc(C.Structure):
                 ("coords_host", C.c_void_p), ("H_host", C.c_void_p), ("T_host", C.c_void_p),
                 ("Phi_host", C.c_void_p), ("V_host", C.c_void_p),
                 ("H", C.c_void_p), ("T", C.c_void_p), ("Phi", C.c_void_p), ("V", C.c_void_p),
-                ("coords", C.c_void_p), ("nbr27", C.c_void_p), ("child8", C.c_void_p)]
+                ("coords", C.c_void_p), ("nbr27", C.c_void_p), ("child8", C.c_void_p),
+                ("row_order", C.c_void_p), ("tile_taps", C.c_void_p)]
 
 
 class _KernelStats(C.Structure):
@@ -220,6 +221,12 @@ class LevelInfo:
 
     def device_child8(self):
         return self._dev(self._d.child8, (self.n_total, 8), np.int32)
+
+    def device_row_order(self):
+        return self._dev(self._d.row_order, (self.n_total,), np.int32)
+
+    def device_tile_taps(self):
+        return self._dev(self._d.tile_taps, ((self.n_total + 63) // 64,), np.uint32)
 
 
 _hiplib = None

@@ -27,7 +27,7 @@ def build_library(force=True, verbose=False):
            # keep the compiler from forming packed-fp32 instructions
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wall", "-Wno-unused-function", "-pthread",
-           "-o", LIB] + [os.path.join(CSRC, f) for f in SOURCES]
+           "-o", LIB] + os.environ.get("HCH_EXTRA_HIPCC_FLAGS", "").split() + [os.path.join(CSRC, f) for f in SOURCES]
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)

@@ -69,6 +69,9 @@ struct Level {
     // device
     int32_t *dH = nullptr, *dV = nullptr, *dcoords = nullptr, *dnbr = nullptr, *dchild = nullptr;
     int32_t *dnbr_t = nullptr;                 // tap-major copy of dnbr ([27][n_total]), built on request
+    uint32_t *dmask27 = nullptr;               // [n_total] bit k: neighbour k exists
+    uint32_t *dtilemask = nullptr;             // [ceil(n_total/64)] taps present in each tile of the pattern order
+    const int32_t *dorder = nullptr;           // [n_total] the level's voxels in pattern order (into hch_levels' sort output)
     uint16_t *dT = nullptr;
     uint8_t *dPhi = nullptr;
     uint32_t *dslot3 = nullptr, *dphi4 = nullptr;   // packed copies of H*,T* and Phi* for the lookups
@@ -87,9 +90,10 @@ struct Level {
 
 void free_level(Level &L)
 {
-    void *ptrs[] = {L.dH, L.dV, L.dcoords, L.dnbr, L.dchild, L.dT, L.dPhi, L.dmeta, L.dslot3, L.dphi4, L.dnbr_t};
+    void *ptrs[] = {L.dH, L.dV, L.dcoords, L.dnbr, L.dchild, L.dT, L.dPhi, L.dmeta, L.dslot3, L.dphi4, L.dnbr_t, L.dmask27, L.dtilemask};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     L.dH = L.dV = L.dcoords = L.dnbr = L.dchild = L.dmeta = L.dnbr_t = nullptr;
+    L.dmask27 = L.dtilemask = nullptr; L.dorder = nullptr;
     L.dT = nullptr; L.dPhi = nullptr; L.dslot3 = L.dphi4 = nullptr;
 }
 
@@ -108,6 +112,11 @@ struct hch_levels {
     hch::LevelSet set{};
     std::vector<int32_t> nbr_prefix, child_prefix;
     int32_t *d_nbr_prefix = nullptr, *d_child_prefix = nullptr;
+    // pattern order of every level's voxels (level l at sort_off[l]): keys and tile histograms
+    // written by the neighbour kernel, the sorted data indices
+    std::vector<int32_t> sort_off;
+    uint8_t *d_sort_key = nullptr;
+    int32_t *d_tile_hist = nullptr, *d_key_total = nullptr, *d_order = nullptr;
 };
 
 extern "C" const char *hch_last_error(void) { return g_err.c_str(); }
@@ -118,6 +127,8 @@ extern "C" void hch_free_levels(hch_levels *levels)
     for (Level &L : levels->lv) free_level(L);
     if (levels->d_nbr_prefix) (void)hipFree(levels->d_nbr_prefix);
     if (levels->d_child_prefix) (void)hipFree(levels->d_child_prefix);
+    void *sort_ptrs[] = {levels->d_sort_key, levels->d_tile_hist, levels->d_key_total, levels->d_order};
+    for (void *p : sort_ptrs) if (p) (void)hipFree(p);
     delete levels;
 }
 
@@ -170,6 +181,36 @@ static hch_status launch_index_lists(const hch_levels *hl, int l0, int l1, hipSt
         for (int l = l0; l < l1; ++l) {            // keep the tap-major copies in step
             hch_status st = transpose_neighbours(hl->lv[l], s);
             if (st != HCH_OK) return st;
+        }
+        // pattern order of the levels' voxels (stable counting sort by pattern key), then the tap
+        // masks of its 64-row tiles
+        const int64_t cnt = (int64_t)hl->sort_off[l1] - hl->sort_off[l0];
+        if (cnt > 0) {
+            {
+                hch::LaunchTimer lt(HCH_KERNEL_ID("pattern_scan_kernel"), s, 8.0 * 64.0 * (double)(last - first), 0.0);
+                HCH_LAUNCH(hch::pattern_scan_kernel, dim3(hch::PATTERN_BINS, (unsigned)(l1 - l0)), dim3(256), 0, s, hl->set,
+                           hl->d_key_total, l0);
+            }
+            HCH_LAUNCH_CHECK("pattern_scan_kernel");
+            {
+                hch::LaunchTimer lt(HCH_KERNEL_ID("pattern_scatter_kernel"), s, 5.0 * (double)cnt, 0.0);
+                HCH_LAUNCH(hch::pattern_scatter_kernel, dim3((unsigned)(last - first)), dim3(256), 0, s, hl->set,
+                           hl->d_nbr_prefix, n_entries, first, (unsigned)(last - first), hl->d_key_total, hl->d_order);
+            }
+            HCH_LAUNCH_CHECK("pattern_scatter_kernel");
+            hch::TileMaskArgs A{};
+            A.n_levels = l1 - l0;
+            A.tile_prefix[0] = 0;
+            for (int l = l0; l < l1; ++l) {
+                const Level &L = hl->lv[l];
+                A.mask27[l - l0] = L.dmask27; A.tile_mask[l - l0] = L.dtilemask; A.order[l - l0] = L.dorder;
+                A.n[l - l0] = (int32_t)L.n_total;
+                A.tile_prefix[l - l0 + 1] = A.tile_prefix[l - l0] + (int32_t)((L.n_total + hch::PATTERN_TILE - 1) / hch::PATTERN_TILE);
+            }
+            const int tiles = A.tile_prefix[A.n_levels];
+            hch::LaunchTimer lt(HCH_KERNEL_ID("tile_mask_kernel"), s, 8.0 * (double)cnt, 0.0);
+            HCH_LAUNCH(hch::tile_mask_kernel, dim3((unsigned)((tiles + 3) / 4)), dim3(256), 0, s, A);
+            HCH_LAUNCH_CHECK("tile_mask_kernel");
         }
     }
     {
@@ -655,6 +696,26 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
             if (n_levels > hch::MAX_LEVELS) st = fail(HCH_EUNSUPPORTED, "hch_build_levels: too many levels");
         }
         if (st == HCH_OK && with_device) {
+            // buffers of the pattern order (see launch_index_lists)
+            hl->sort_off.assign((size_t)n_levels + 1, 0);
+            for (int l = 0; l < n_levels; ++l) hl->sort_off[l + 1] = hl->sort_off[l] + (int32_t)hl->lv[l].n_total;
+            const size_t n_all = (size_t)hl->sort_off[n_levels];
+            int64_t nbr_tiles = 0;
+            for (int l = 0; l < n_levels; ++l)
+                for (int v = 0; v < batch; ++v) nbr_tiles += (hl->lv[l].N[v + 1] - hl->lv[l].N[v] + 255) / 256;
+            if (hipMalloc((void **)&hl->d_sort_key, std::max<size_t>(n_all, 64)) != hipSuccess) { hl->d_sort_key = nullptr; st = fail(HCH_ENOMEM, "hipMalloc(pattern keys) failed"); }
+            if (st == HCH_OK && hipMalloc((void **)&hl->d_order, std::max<size_t>(n_all, 64) * 4) != hipSuccess) { hl->d_order = nullptr; st = fail(HCH_ENOMEM, "hipMalloc(pattern order) failed"); }
+            if (st == HCH_OK && hipMalloc((void **)&hl->d_tile_hist, (size_t)std::max<int64_t>(nbr_tiles, 1) * hch::PATTERN_BINS * 4) != hipSuccess) { hl->d_tile_hist = nullptr; st = fail(HCH_ENOMEM, "hipMalloc(tile histograms) failed"); }
+            if (st == HCH_OK && hipMalloc((void **)&hl->d_key_total, (size_t)hch::MAX_LEVELS * hch::PATTERN_BINS * 4) != hipSuccess) { hl->d_key_total = nullptr; st = fail(HCH_ENOMEM, "hipMalloc(key totals) failed"); }
+            for (int l = 0; l < n_levels && st == HCH_OK; ++l) {
+                Level &L = hl->lv[l];
+                const size_t tiles = (size_t)((L.n_total + hch::PATTERN_TILE - 1) / hch::PATTERN_TILE);
+                if (hipMalloc((void **)&L.dmask27, std::max<size_t>((size_t)L.n_total, 64) * 4) != hipSuccess) { L.dmask27 = nullptr; st = fail(HCH_ENOMEM, "hipMalloc(mask27) failed"); break; }
+                if (hipMalloc((void **)&L.dtilemask, std::max<size_t>(tiles, 64) * 4) != hipSuccess) { L.dtilemask = nullptr; st = fail(HCH_ENOMEM, "hipMalloc(tile masks) failed"); break; }
+                L.dorder = hl->d_order + hl->sort_off[l];
+            }
+        }
+        if (st == HCH_OK && with_device) {
             hl->set.batch = batch;
             hl->nbr_prefix.assign((size_t)n_levels * batch + 1, 0);
             hl->child_prefix.assign((size_t)n_levels * batch + 1, 0);
@@ -664,12 +725,22 @@ static hch_status build_impl(const int32_t *coords_xyz, const int64_t *model_off
                 hl->set.coords[l] = L.dcoords;
                 hl->set.nbr[l] = L.dnbr;
                 hl->set.child[l] = L.dchild;
+                hl->set.mask27[l] = L.dmask27;
+                hl->set.sort_off[l] = hl->sort_off[l];
+                hl->set.level_tile0[l] = hl->nbr_prefix[(size_t)l * batch];
                 for (int v = 0; v < batch; ++v) {
                     const int32_t tiles = (int32_t)((L.N[v + 1] - L.N[v] + 255) / 256);
                     const size_t e = (size_t)l * batch + v;
                     hl->nbr_prefix[e + 1] = hl->nbr_prefix[e] + tiles;
                     hl->child_prefix[e + 1] = hl->child_prefix[e] + (l > 0 && L.ratio == 2 ? tiles : 0);
                 }
+            }
+            hl->set.sort_key = hl->d_sort_key;
+            hl->set.tile_hist = hl->d_tile_hist;
+            for (int l = 0; l < n_levels; ++l) {
+                hl->set.level_tile0[l] = hl->nbr_prefix[(size_t)l * batch];
+                hl->set.level_tiles[l] = hl->nbr_prefix[(size_t)(l + 1) * batch] - hl->nbr_prefix[(size_t)l * batch];
+                hl->set.hist_off[l] = hl->set.level_tile0[l] * hch::PATTERN_BINS;
             }
             if ((st = upload((void **)&hl->d_nbr_prefix, hl->nbr_prefix.data(), hl->nbr_prefix.size() * 4, s)) == HCH_OK)
                 st = upload((void **)&hl->d_child_prefix, hl->child_prefix.data(), hl->child_prefix.size() * 4, s);
@@ -758,6 +829,7 @@ extern "C" hch_status hch_level_info(const hch_levels *levels, int32_t level, hc
     out->V_host = L.V.data();
     out->H = L.dH; out->T = L.dT; out->Phi = L.dPhi; out->V = L.dV; out->coords = L.dcoords;
     out->nbr27 = L.dnbr; out->child8 = L.dchild;
+    out->row_order = L.dorder; out->tile_taps = L.dtilemask;
     return HCH_OK;
 }
 
@@ -1206,6 +1278,7 @@ extern "C" size_t hch_conv_workspace_bytes(const hch_levels *levels, int32_t lev
 {
     if (!levels || level < 0 || level >= (int32_t)levels->lv.size() || c_in <= 0 || c_out <= 0) return 0;
     if (algo == HCH_ALGO_COLUMNS_RESIDENT) algo = HCH_ALGO_COLUMNS;
+    if (algo == HCH_ALGO_FUSED_DENSE) algo = HCH_ALGO_FUSED;     // same workspace as the fused algorithm
     if (algo != HCH_ALGO_COLUMNS && algo != HCH_ALGO_FUSED) return 0;
     const Level &L = levels->lv[level];
     if (kind == HCH_WS_MIN) {
@@ -1255,6 +1328,8 @@ extern "C" hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_
                                    void *stream)
 {
     const Level *L;
+    const bool skip = algo == HCH_ALGO_FUSED;                    // absent taps may be skipped
+    if (algo == HCH_ALGO_FUSED_DENSE) algo = HCH_ALGO_FUSED;
     hch_status st = conv_args(levels, level, dtype, X, W, Y, c_in, c_out, workspace, algo, &L, "hch_conv_fwd");
     if (st != HCH_OK) return st;
     if (ws_bytes < hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, HCH_WS_MIN, algo))
@@ -1315,6 +1390,8 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
                                         void *stream)
 {
     const Level *L;
+    const bool skip = algo == HCH_ALGO_FUSED;
+    if (algo == HCH_ALGO_FUSED_DENSE) algo = HCH_ALGO_FUSED;
     hch_status st = conv_args(levels, level, dtype, dY, W, dX, c_in, c_out, workspace, algo, &L, "hch_conv_bwd_data");
     if (st != HCH_OK) return st;
     if (ws_bytes < hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, HCH_WS_BWD_DATA, algo))
@@ -1401,6 +1478,8 @@ static hch_status conv_bwd_weight_impl(const hch_levels *levels, int32_t level, 
     const Level *L;
     const bool resident = algo == HCH_ALGO_COLUMNS_RESIDENT;     // the column matrix is in the workspace already
     if (resident) algo = HCH_ALGO_COLUMNS;
+    const bool skip = algo == HCH_ALGO_FUSED;
+    if (algo == HCH_ALGO_FUSED_DENSE) algo = HCH_ALGO_FUSED;
     hch_status st = conv_args(levels, level, dtype, X, dY, dW, c_in, c_out, workspace, algo, &L, who);
     if (st != HCH_OK) return st;
     if (ws_bytes < hch_conv_workspace_bytes(levels, level, c_in, c_out, dtype, HCH_WS_BWD_WEIGHT, algo))

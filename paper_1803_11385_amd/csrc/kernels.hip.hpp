@@ -94,8 +94,33 @@ struct LevelSet {
     const int32_t *coords[MAX_LEVELS];
     int32_t *nbr[MAX_LEVELS];
     int32_t *child[MAX_LEVELS];      // children (at level l-1) of level l's voxels; null for l = 0
+    uint32_t *mask27[MAX_LEVELS];    // per voxel: bit k set iff neighbour k exists
+    // inputs of the counting sort that puts every level's voxels into pattern order (see
+    // pattern_key): one key per voxel (level l's voxels at sort_off[l] ...) and one histogram of
+    // the keys per 256-voxel tile of the index-list kernels
+    uint8_t *sort_key;
+    int32_t *tile_hist;              // level l at hist_off[l]: [PATTERN_BINS][tiles of the level], key-major
+    int32_t sort_off[MAX_LEVELS];
+    int32_t hist_off[MAX_LEVELS];
+    int32_t level_tiles[MAX_LEVELS]; // 256-voxel tiles of the index-list kernels at level l
+    int32_t level_tile0[MAX_LEVELS]; // flat number of the level's first tile
     int32_t batch;
 };
+
+// Which neighbours a surface voxel has depends on the local orientation of the surface.  The key
+// has one bit for each of the 6 pairs of opposite edge-adjacent neighbours (two coordinates
+// differ; taps k and 26-k): set if either of the pair exists.  Voxels ordered by this key come in
+// runs with similar neighbour patterns, and a tile of consecutive rows of that order lacks most
+// of the taps its voxels lack: the fused products work on such tiles and skip those taps.
+constexpr int PATTERN_BINS = 64;
+__device__ __forceinline__ uint32_t pattern_key(uint32_t mask27)
+{
+    uint32_t key = 0;
+    // edge-adjacent taps below the centre: 1, 3, 5, 7, 9, 11
+#pragma unroll
+    for (int k = 1; k < 13; k += 2) key = (key << 1) | (((mask27 >> k) | (mask27 >> (26 - k))) & 1u);
+    return key;
+}
 
 __device__ __forceinline__ int find_entry(const int32_t *__restrict__ prefix, int n_entries, int tile)
 {
@@ -129,6 +154,7 @@ __global__ __launch_bounds__(256) void neighbour_kernel(
 {
     __shared__ uint32_t lds[NBR_LDS_WORDS];          // offset planes first, the 256 x 27 result tile afterwards
     __shared__ int32_t xrange[8];
+    __shared__ int32_t hist[PATTERN_BINS];
     const unsigned t = xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
     if (t >= n_tiles) return;
     const int flat = tile_first + (int)t;
@@ -155,6 +181,7 @@ __global__ __launch_bounds__(256) void neighbour_kernel(
         xhi = max(xhi, __shfl_xor(xhi, d));
     }
     if ((threadIdx.x & 63) == 0) { xrange[threadIdx.x >> 6] = xlo; xrange[4 + (threadIdx.x >> 6)] = xhi; }
+    if (threadIdx.x < PATTERN_BINS) hist[threadIdx.x] = 0;
     __syncthreads();
     xlo = min(min(xrange[0], xrange[1]), min(xrange[2], xrange[3]));
     xhi = max(max(xrange[4], xrange[5]), max(xrange[6], xrange[7]));
@@ -214,15 +241,110 @@ __global__ __launch_bounds__(256) void neighbour_kernel(
     __syncthreads();                                  // every thread is done with the offset planes
     if (live) {
         int32_t *row = reinterpret_cast<int32_t *>(lds) + threadIdx.x * 27;
+        uint32_t mask = 0;
 #pragma unroll
-        for (int k = 0; k < 27; ++k) row[k] = out[k];
+        for (int k = 0; k < 27; ++k) { row[k] = out[k]; mask |= (uint32_t)(out[k] >= 0) << k; }
+        S.mask27[lev][base + i] = mask;
+        const uint32_t key = pattern_key(mask);
+        S.sort_key[S.sort_off[lev] + base + i] = (uint8_t)key;
+        atomicAdd(&hist[key], 1);
     }
     __syncthreads();
     const int32_t cnt = min(256, n - blk0) * 27;
     int32_t *dst = S.nbr[lev] + (int64_t)(base + blk0) * 27;
     const int32_t *tile = reinterpret_cast<const int32_t *>(lds);
     for (int q = threadIdx.x; q < cnt; q += 256) dst[q] = tile[q];
+    if (threadIdx.x < PATTERN_BINS)
+        S.tile_hist[S.hist_off[lev] + (int64_t)threadIdx.x * S.level_tiles[lev] + (flat - S.level_tile0[lev])] = hist[threadIdx.x];
 }
+
+// Counting sort of every level's voxels by pattern key, stable (voxels with equal keys keep
+// their data order, so the order is the same from run to run), in two steps after the
+// index-list kernel has left one key per voxel and one histogram per tile.
+//
+// Step 1, one workgroup per (key, level): turns the tile histograms into offsets.  Sorted position
+// of a voxel = sort_off[level] + (voxels of the level with a smaller key) + (voxels with the same
+// key in earlier tiles) + (voxels with the same key earlier in its tile).  The histograms are
+// stored key-major, so the third term is an exclusive prefix sum along one row, which this
+// kernel computes in place; the row's total goes to key_total[level][key], from which step 2
+// takes the second term.
+__global__ __launch_bounds__(256) void pattern_scan_kernel(LevelSet S, int32_t *__restrict__ key_total, int level_first)
+{
+    __shared__ int32_t sums[256];
+    const int lev = level_first + blockIdx.y, key = blockIdx.x;
+    const int T = S.level_tiles[lev];
+    int32_t *row = S.tile_hist + S.hist_off[lev] + (int64_t)key * T;
+    const int per = (T + 255) / 256;
+    const int a = min(T, (int)threadIdx.x * per), b = min(T, a + per);
+    int32_t sum = 0;
+    for (int t = a; t < b; ++t) sum += row[t];
+    sums[threadIdx.x] = sum;
+    __syncthreads();
+    // exclusive prefix of the 256 stretch sums (Hillis-Steele in LDS)
+    for (int o = 1; o < 256; o <<= 1) {
+        const int32_t add = (int)threadIdx.x >= o ? sums[threadIdx.x - o] : 0;
+        __syncthreads();
+        sums[threadIdx.x] += add;
+        __syncthreads();
+    }
+    int32_t run = sums[threadIdx.x] - sum;
+    for (int t = a; t < b; ++t) {
+        const int32_t c = row[t];
+        row[t] = run;
+        run += c;
+    }
+    if (threadIdx.x == 255) key_total[lev * PATTERN_BINS + key] = sums[255];
+}
+
+// Step 2, one workgroup per tile of the index-list kernels: every voxel finds its rank among the
+// voxels of its tile with the same key (lanes with the same key through six ballots, earlier
+// wavefronts through LDS) and writes its data index to its sorted position.
+__global__ __launch_bounds__(256) void pattern_scatter_kernel(
+    LevelSet S, const int32_t *__restrict__ tile_prefix, int n_entries, int tile_first, unsigned n_tiles,
+    const int32_t *__restrict__ key_total, int32_t *__restrict__ order)
+{
+    __shared__ int32_t wcnt[4][PATTERN_BINS];
+    __shared__ int32_t below[PATTERN_BINS];
+    const unsigned t = blockIdx.x;
+    if (t >= n_tiles) return;
+    const int flat = tile_first + (int)t;
+    const int e = find_entry(tile_prefix, n_entries, flat);
+    const int lev = e / S.batch, v = e - lev * S.batch;
+    const int32_t base = S.view[lev].N[v];
+    const int32_t n = S.view[lev].N[v + 1] - base;
+    const int32_t i = (flat - tile_prefix[e]) * 256 + threadIdx.x;
+    const bool live = i < n;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t key = live ? S.sort_key[S.sort_off[lev] + base + i] : 0u;
+    wcnt[wave][lane] = 0;
+    if (wave == 0) {                       // voxels of the level with a smaller key
+        const int32_t total = key_total[lev * PATTERN_BINS + lane];
+        int32_t incl = total;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int32_t up = __shfl_up(incl, o);
+            if (lane >= o) incl += up;
+        }
+        below[lane] = incl - total;
+    }
+    // lanes of this wavefront with the same key (dead lanes match nobody)
+    unsigned long long same = __ballot(live);
+#pragma unroll
+    for (int b = 0; b < 6; ++b) {
+        const unsigned long long bal = __ballot((key >> b) & 1u);
+        same &= ((key >> b) & 1u) ? bal : ~bal;
+    }
+    const int before = __builtin_amdgcn_mbcnt_hi((unsigned)(same >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)same, 0u));
+    if (live && before == 0) wcnt[wave][key] = __popcll(same);        // one lane per key present
+    __syncthreads();
+    if (live) {
+        int32_t pos = S.sort_off[lev] + below[key] + before +
+                      S.tile_hist[S.hist_off[lev] + (int64_t)key * S.level_tiles[lev] + (flat - S.level_tile0[lev])];
+        for (int w = 0; w < wave; ++w) pos += wcnt[w][key];
+        order[pos] = base + i;
+    }
+}
+
 
 // dst[t][i] = src[i][t] for an index list src[n][taps] (taps <= 27 here): the tap-major copy of
 // the neighbour lists.  256 rows per workgroup through LDS, both sides coalesced.
@@ -236,6 +358,33 @@ __global__ __launch_bounds__(256) void index_transpose_kernel(
     __syncthreads();
     if ((int)threadIdx.x < rows)
         for (int t = 0; t < taps; ++t) dst[(int64_t)t * n + r0 + threadIdx.x] = tile[threadIdx.x * taps + t];
+}
+
+// Tap masks of the tiles of the pattern order: tile b of level l covers rows 64b .. 64b+63 of the
+// level's sorted voxel list `order`, and bit k of its mask says whether any of them has
+// neighbour k.  One wavefront per tile; tiles of all levels of the range in one launch
+// (tile_prefix[l - l0] = tiles before level l).
+struct TileMaskArgs {
+    const uint32_t *mask27[MAX_LEVELS];
+    uint32_t *tile_mask[MAX_LEVELS];
+    const int32_t *order[MAX_LEVELS];
+    int32_t n[MAX_LEVELS];
+    int32_t tile_prefix[MAX_LEVELS + 1];
+    int32_t n_levels;
+};
+constexpr int PATTERN_TILE = 64;
+__global__ __launch_bounds__(256) void tile_mask_kernel(TileMaskArgs A)
+{
+    const int flat = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (flat >= A.tile_prefix[A.n_levels]) return;
+    int l = 0;
+    while (l + 1 < A.n_levels && A.tile_prefix[l + 1] <= flat) ++l;
+    const int b = flat - A.tile_prefix[l];
+    const int r = b * PATTERN_TILE + lane;
+    uint32_t m = r < A.n[l] ? A.mask27[l][A.order[l][r]] : 0u;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) m |= (uint32_t)__shfl_xor((int)m, d);
+    if (lane == 0) A.tile_mask[l][b] = m;
 }
 
 // For every coarse voxel the global data indices, at the next finer level, of its 8 children

@@ -92,6 +92,28 @@ def test_tables_and_index_lists_bit_exact(request, oracle, name):
             assert np.array_equal(info.device_child8(), oracle.children(case.olv[l - 1], L)), f"child8 level {l}"
 
 
+@pytest.mark.parametrize("name", ["case_sphere", "case_batch64", "case_small"])
+def test_pattern_order_and_tile_taps(request, oracle, name):
+    """The order in which the fused products walk a level and the taps each of its 64-row tiles
+    has: a permutation of the level's voxels, sorted stably by a 6-bit key (one bit per pair of
+    opposite edge-adjacent neighbours, taps k and 26-k for k = 1, 3, .., 11: set if either
+    exists), and per tile exactly the union of its voxels' neighbour sets, all derived from the
+    oracle's neighbour lists."""
+    case = request.getfixturevalue(name)
+    for l, L in enumerate(case.olv):
+        info = case.glv.info(l)
+        valid = oracle.neighbours(L) >= 0
+        key = np.zeros(L.Ntot, np.int64)
+        for k in range(1, 13, 2):
+            key = key * 2 + (valid[:, k] | valid[:, 26 - k])
+        order = info.device_row_order()
+        assert np.array_equal(order, np.argsort(key, kind="stable")), f"level {l}"
+        mask = valid.astype(np.int64) @ (1 << np.arange(27, dtype=np.int64))
+        pad = np.zeros(-(-L.Ntot // 64) * 64, np.int64)
+        pad[:L.Ntot] = mask[order]
+        assert np.array_equal(info.device_tile_taps().astype(np.int64), np.bitwise_or.reduce(pad.reshape(-1, 64), axis=1)), f"level {l}"
+
+
 def test_neighbour_rebuild_is_idempotent(oracle, case_batch64):
     case = case_batch64
     for l in range(3):
