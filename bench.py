@@ -86,7 +86,7 @@ def conv_bench(args, torch, hch, S):
     coords, offs, _ = S.config_batch(cfg)
     lv = hch.hch_build_levels_device(coords, offs, u, 1)
     n = lv.n(0)
-    algo = hch.HCH_ALGO_FUSED if args.algo == "fused" else hch.HCH_ALGO_COLUMNS
+    algo = {"fused": hch.HCH_ALGO_FUSED, "fused_dense": hch.HCH_ALGO_FUSED_DENSE, "columns": hch.HCH_ALGO_COLUMNS}[args.algo]
     DT = hch.HCH_BF16 if bf else hch.HCH_F32
     if bf and not args.no_tap_major:
         hch.hch_build_tap_major(lv, 0)        # the bf16 gathers read their indices tap by tap
@@ -155,8 +155,9 @@ def main():
                     help="time only the three products of one convolution on a per-kernel workload and print "
                          "that: 3 = 128^3 grid, batch 16, 32 -> 64, fp32; 5 = 512^3 grid, batch 4, 64 -> 64, bf16")
     ap.add_argument("--no-tap-major", action="store_true", help="--conv-bench 5 without the tap-major index copy")
-    ap.add_argument("--algo", choices=["columns", "fused"], default="fused",
-                    help="columns: hash2col -> GEMM -> col2hash through memory; fused: gathered GEMM operand")
+    ap.add_argument("--algo", choices=["columns", "fused", "fused_dense"], default="fused",
+                    help="columns: hash2col -> GEMM -> col2hash through memory; fused: gathered GEMM operand, taps "
+                         "that a tile of voxels lacks left out; fused_dense: the same without leaving taps out")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -200,7 +201,7 @@ def main():
     levels, t_build = timed_build(hch.hch_build_levels)
     lv_dev, t_build_dev = timed_build(hch.hch_build_levels_device)
     del lv_dev
-    algo = hch.HCH_ALGO_FUSED if args.algo == "fused" else hch.HCH_ALGO_COLUMNS
+    algo = {"fused": hch.HCH_ALGO_FUSED, "fused_dense": hch.HCH_ALGO_FUSED_DENSE, "columns": hch.HCH_ALGO_COLUMNS}[args.algo]
     enc = Encoder(levels, CHANNELS, algo, two_streams=args.two_streams)
     enc.X[0].copy_(torch.from_numpy(X0))
     for l in range(5):

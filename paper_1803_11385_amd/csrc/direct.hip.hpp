@@ -37,24 +37,49 @@ template <int NT> __device__ __forceinline__ float frag_get(const typename FragO
 // S register sets form a ring: the loads of block j+S-1 are issued before the products of
 // block j.  CHECK: the last block may have units past the 27 taps (c % 16 != 0) or the column
 // group may reach past N; without it c % 16 == 0 and N % (16*NT) == 0.
-template <int RT, int NT, int S, bool CHECK>
+// SKIP (RT = 4: a wavefront's 64 voxels are one tile of the pattern order): row i of the
+// wavefront is voxel rowmap[tile*64 + i] and tilemask[tile] has the taps those voxels have; the
+// reduction runs over the units of the present taps only (tap t' of the compacted list is tap
+// tmap[t']), tiles are dealt round-robin (neighbouring tiles have the same amount of work).
+template <int RT, int NT, int S, bool CHECK, bool SKIP = false>
 __global__ __launch_bounds__(256) void conv_direct_kernel(
     const float *__restrict__ X, const int32_t *__restrict__ nbr, const float *__restrict__ Wm,
     float *__restrict__ Y, int M, int c, int N, int J, int j_per_split, int upt, int step_t, int step_q,
-    unsigned wave_tiles, int64_t split_stride, int flipped)
+    unsigned wave_tiles, int64_t split_stride, int flipped, const int32_t *__restrict__ rowmap,
+    const uint32_t *__restrict__ tilemask)
 {
     typedef typename FragOf<NT>::type wfrag;
     constexpr int ROWS = 16 * RT;
     constexpr int IDX = ROWS * 27;
+    static_assert(!SKIP || ROWS == PATTERN_TILE, "a wavefront's rows are one tile of the pattern order");
     __shared__ int32_t sidx[4 * IDX];
+    __shared__ int32_t srow[SKIP ? 4 * ROWS : 1];
+    __shared__ uint8_t stap[SKIP ? 4 * 32 : 1];
 
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int r = lane & 15, g = lane >> 4;
-    const unsigned tile = xcd_tile(blockIdx.x, gridDim.x / NUM_XCD) * 4 + wv;
+    const unsigned tile = (SKIP ? blockIdx.x : xcd_tile(blockIdx.x, gridDim.x / NUM_XCD)) * 4 + wv;
     if (tile >= wave_tiles) return;                    // no barrier below: a wave may leave alone
     const int nb = blockIdx.y * (16 * NT);
-    const int jb = blockIdx.z * j_per_split;
-    const int je = min(J, jb + j_per_split);
+    int jb = blockIdx.z * j_per_split;
+    int je = min(J, jb + j_per_split);
+    int n_taps = 27;                                   // taps of the reduction (present ones with SKIP)
+    int32_t *rv = srow + (SKIP ? wv * ROWS : 0);
+    uint8_t *tmap = stap + (SKIP ? wv * 32 : 0);
+    if constexpr (SKIP) {
+        const uint32_t present = tilemask[tile];
+        n_taps = __popc(present);
+        if (lane < 27 && ((present >> lane) & 1u)) tmap[__popc(present & ((1u << lane) - 1u))] = (uint8_t)lane;
+        const int64_t row = (int64_t)tile * ROWS + lane;
+        rv[lane] = row < M ? rowmap[row] : -1;
+        const int Jp = (n_taps * upt + 3) / 4;
+        const int per = ((Jp + (int)gridDim.z - 1) / (int)gridDim.z + S - 1) / S * S;
+        jb = blockIdx.z * per;
+        je = min(Jp, jb + per);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
 
     // this wave's 16*RT x 27 neighbour indices: one contiguous piece of the list, kept in LDS
     // (written and read by this wave only)
@@ -65,8 +90,14 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(
         int32_t v[PER];
 #pragma unroll
         for (int i = 0; i < PER; ++i) {                 // all loads first, then all stores
-            const int64_t o = pos0 + i * 64 + lane;
-            v[i] = *(o < lim ? nbr + o : &g_minus1);
+            if constexpr (SKIP) {
+                // element e of the tile: column e % 27 of the index row of voxel rv[e / 27]
+                const int e = i * 64 + lane, row = e / 27, vox = rv[min(row, ROWS - 1)];
+                v[i] = *((e < IDX && vox >= 0) ? nbr + ((int64_t)vox * 27 + (e - row * 27)) : &g_minus1);
+            } else {
+                const int64_t o = pos0 + i * 64 + lane;
+                v[i] = *(o < lim ? nbr + o : &g_minus1);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -85,14 +116,15 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(
     int32_t nidx[RT];
     int cur_q4 = 0, cur_k = 0, cur_t = 0;
     auto fetch_idx = [&]() {
-        const bool ok = (jn < je) & (t < 27);
-        const int tt = t < 27 ? t : 26;
+        const bool ok = (jn < je) & (t < n_taps);
+        int tt = t < 27 ? t : 26;
+        if constexpr (SKIP) tt = tmap[min(t, 31)] % 27;     // the tap behind entry t of the compacted list
 #pragma unroll
         for (int i = 0; i < RT; ++i) {
             const int32_t v = my[(16 * i + r) * 27 + tt];
             nidx[i] = ok ? v : -1;
         }
-        cur_q4 = 4 * q; cur_k = t * c + 4 * q; cur_t = tt;
+        cur_q4 = 4 * q; cur_k = tt * c + 4 * q; cur_t = tt;
         t += step_t; q += step_q;
         if (q >= upt) { q -= upt; ++t; }
         ++jn;
@@ -164,8 +196,9 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(
     float *out = Y + (int64_t)blockIdx.z * split_stride;
 #pragma unroll
     for (int i = 0; i < RT; ++i) {
-        const int64_t row = (int64_t)tile * ROWS + 16 * i + r;
+        int64_t row = (int64_t)tile * ROWS + 16 * i + r;
         if (row >= M) continue;
+        if constexpr (SKIP) row = rv[16 * i + r];
 #pragma unroll
         for (int f = 0; f < NT; ++f) {
             const int col = nb + 4 * NT * g + 4 * f;
@@ -201,72 +234,57 @@ namespace hch {
 //   X [M][C] rows, nbr [M][27], Wm [27*C][4], Y [M][4]; all 16-byte aligned.  With `flipped`, Wm is
 //   the weight tensor W[27][4][C] of the convolution whose data gradient this is:
 //   Wm[t*C + ch][j] = W[26-t][j][ch].
-template <int CC>
-__global__ __launch_bounds__(256) void conv_narrow4_kernel(
-    const float *__restrict__ X, const int32_t *__restrict__ nbr, const float *__restrict__ Wm,
-    float *__restrict__ Y, int M, unsigned wave_tiles, int flipped)
+// SKIP: as in conv_direct_kernel: the wavefront's 64 voxels are tile `tile` of the pattern order
+// (voxel rowmap[tile*64 + i]), and only the taps of tilemask[tile] are multiplied, four at a
+// time: TA = ceil(present taps / 4) groups instead of 7 (one instantiation of the loop body per
+// TA, so that the loads of a chunk stay in one straight run).
+template <int CC, int TA>
+__device__ __forceinline__ void narrow4_tile(const float *__restrict__ X, const float *__restrict__ Wm,
+                                             float *__restrict__ Y, const int32_t *my, float *red,
+                                             const int32_t *rv, const uint8_t *tmap, int n_taps, int M,
+                                             unsigned tile, int lane, int flipped, bool skip)
 {
     constexpr int C = 16 * CC;
-    constexpr int IDX = 64 * 27;
-    __shared__ int32_t sidx[4 * IDX];
-    __shared__ float sred[4 * 1024];
-
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const unsigned tile = xcd_tile(blockIdx.x, gridDim.x / NUM_XCD) * 4 + wv;
-    if (tile >= wave_tiles) return;                    // no workgroup barrier below
     const int i = lane & 3, b = lane >> 2, tq = b >> 2, cq = b & 3, j = i;
-
-    int32_t *my = sidx + wv * IDX;
-    float *red = sred + wv * 1024;
-    {
-        const int64_t pos0 = (int64_t)tile * IDX, lim = (int64_t)M * 27;
-        int32_t v[27];
+    // this lane's taps: entry 4T + tq of the (compacted) tap list
+    int tap[TA];
 #pragma unroll
-        for (int q = 0; q < 27; ++q) {
-            const int64_t o = pos0 + q * 64 + lane;
-            v[q] = *(o < lim ? nbr + o : &g_minus1);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int q = 0; q < 27; ++q) my[q * 64 + lane] = v[q];
+    for (int T = 0; T < TA; ++T) {
+        const int t = 4 * T + tq;
+        tap[T] = t < n_taps ? (skip ? (int)tmap[t] : t) : -1;
     }
-    // this lane's weights: reduction row (4T + tq)*C + 16*cc + 4*cq + e, column j
-    float w[7][CC][4];
+    // this lane's weights: reduction row tap*C + 16*cc + 4*cq + e, column j
+    float w[TA][CC][4];
 #pragma unroll
-    for (int T = 0; T < 7; ++T)
+    for (int T = 0; T < TA; ++T)
 #pragma unroll
         for (int cc = 0; cc < CC; ++cc)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int t = 4 * T + tq;
+                const int t = tap[T];
                 const int ch = 16 * cc + 4 * cq + e;
-                const float *src = t >= 27 ? reinterpret_cast<const float *>(g_zero16)
-                                           : (flipped ? Wm + (((26 - t) * 4 + j) * C + ch) : Wm + ((t * C + ch) * 4 + j));
+                const float *src = t < 0 ? reinterpret_cast<const float *>(g_zero16)
+                                         : (flipped ? Wm + (((26 - t) * 4 + j) * C + ch) : Wm + ((t * C + ch) * 4 + j));
                 w[T][cc][e] = *src;
             }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
     const float *zsrc = reinterpret_cast<const float *>(g_zero16);
     for (int it = 0; it < 4; ++it) {                   // 16 voxels = 4 groups of 4 per pass
         f32x4 acc[4];
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) acc[gq] = f32x4{0.f, 0.f, 0.f, 0.f};
-        int32_t idx[7][4];
+        int32_t idx[TA][4];
 #pragma unroll
-        for (int T = 0; T < 7; ++T)
+        for (int T = 0; T < TA; ++T)
 #pragma unroll
             for (int gq = 0; gq < 4; ++gq) {
-                const int t = 4 * T + tq;
-                const int32_t v = my[(16 * it + 4 * gq + i) * 27 + (t < 27 ? t : 26)];
-                idx[T][gq] = t < 27 ? v : -1;
+                const int32_t v = my[(16 * it + 4 * gq + i) * 27 + max(tap[T], 0)];
+                idx[T][gq] = tap[T] >= 0 ? v : -1;
             }
 #pragma unroll
         for (int cc = 0; cc < CC; ++cc) {
-            f32x4 a[7][4];
+            f32x4 a[TA][4];
 #pragma unroll
-            for (int T = 0; T < 7; ++T)
+            for (int T = 0; T < TA; ++T)
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
                     const float *p = idx[T][gq] >= 0 ? X + (uint32_t)(idx[T][gq] * C + 16 * cc + 4 * cq) : zsrc;
@@ -274,7 +292,7 @@ __global__ __launch_bounds__(256) void conv_narrow4_kernel(
                 }
             __builtin_amdgcn_sched_barrier(0);         // all loads of the chunk before its products
 #pragma unroll
-            for (int T = 0; T < 7; ++T)
+            for (int T = 0; T < TA; ++T)
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
@@ -296,11 +314,82 @@ __global__ __launch_bounds__(256) void conv_narrow4_kernel(
             s += (v[0] + v[1]) + (v[2] + v[3]);
         }
         // lane = (gq*4 + i)*4 + j: voxel 16*it + lane/4 of the tile, column lane%4
-        const int64_t row = (int64_t)tile * 64 + 16 * it + (lane >> 2);
-        if (row < M) Y[row * 4 + (lane & 3)] = s;
+        const int local = 16 * it + (lane >> 2);
+        int64_t row = (int64_t)tile * 64 + local;
+        if (row < M) {
+            if (skip) row = rv[local];
+            Y[row * 4 + (lane & 3)] = s;
+        }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();               // red is reused by the next pass
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
+
+template <int CC, bool SKIP = false>
+__global__ __launch_bounds__(256) void conv_narrow4_kernel(
+    const float *__restrict__ X, const int32_t *__restrict__ nbr, const float *__restrict__ Wm,
+    float *__restrict__ Y, int M, unsigned wave_tiles, int flipped, const int32_t *__restrict__ rowmap,
+    const uint32_t *__restrict__ tilemask)
+{
+    constexpr int IDX = 64 * 27;
+    __shared__ int32_t sidx[4 * IDX];
+    __shared__ float sred[4 * 1024];
+    __shared__ int32_t srow[SKIP ? 4 * 64 : 1];
+    __shared__ uint8_t stap[SKIP ? 4 * 32 : 1];
+
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const unsigned tile = (SKIP ? blockIdx.x : xcd_tile(blockIdx.x, gridDim.x / NUM_XCD)) * 4 + wv;
+    if (tile >= wave_tiles) return;                    // no workgroup barrier below
+
+    int32_t *my = sidx + wv * IDX;
+    float *red = sred + wv * 1024;
+    int32_t *rv = srow + (SKIP ? wv * 64 : 0);
+    uint8_t *tmap = stap + (SKIP ? wv * 32 : 0);
+    int n_taps = 27;
+    if constexpr (SKIP) {
+        const uint32_t present = tilemask[tile];
+        n_taps = __popc(present);
+        if (lane < 27 && ((present >> lane) & 1u)) tmap[__popc(present & ((1u << lane) - 1u))] = (uint8_t)lane;
+        const int64_t row = (int64_t)tile * 64 + lane;
+        rv[lane] = row < M ? rowmap[row] : -1;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    {
+        const int64_t pos0 = (int64_t)tile * IDX, lim = (int64_t)M * 27;
+        int32_t v[27];
+#pragma unroll
+        for (int q = 0; q < 27; ++q) {
+            if constexpr (SKIP) {
+                const int e = q * 64 + lane, row = e / 27, vox = rv[row];
+                v[q] = *(vox >= 0 ? nbr + ((int64_t)vox * 27 + (e - row * 27)) : &g_minus1);
+            } else {
+                const int64_t o = pos0 + q * 64 + lane;
+                v[q] = *(o < lim ? nbr + o : &g_minus1);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < 27; ++q) my[q * 64 + lane] = v[q];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    if constexpr (SKIP) {
+        switch ((n_taps + 3) / 4) {
+        case 1: narrow4_tile<CC, 1>(X, Wm, Y, my, red, rv, tmap, n_taps, M, tile, lane, flipped, true); break;
+        case 2: narrow4_tile<CC, 2>(X, Wm, Y, my, red, rv, tmap, n_taps, M, tile, lane, flipped, true); break;
+        case 3: narrow4_tile<CC, 3>(X, Wm, Y, my, red, rv, tmap, n_taps, M, tile, lane, flipped, true); break;
+        case 4: narrow4_tile<CC, 4>(X, Wm, Y, my, red, rv, tmap, n_taps, M, tile, lane, flipped, true); break;
+        case 5: narrow4_tile<CC, 5>(X, Wm, Y, my, red, rv, tmap, n_taps, M, tile, lane, flipped, true); break;
+        case 6: narrow4_tile<CC, 6>(X, Wm, Y, my, red, rv, tmap, n_taps, M, tile, lane, flipped, true); break;
+        default: narrow4_tile<CC, 7>(X, Wm, Y, my, red, rv, tmap, n_taps, M, tile, lane, flipped, true); break;
+        }
+    } else {
+        narrow4_tile<CC, 7>(X, Wm, Y, my, red, rv, tmap, 27, M, tile, lane, flipped, false);
     }
 }
 

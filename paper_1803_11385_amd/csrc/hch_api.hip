@@ -1005,7 +1005,8 @@ template <typename TIN, int AMODE, bool B_KC>
 static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void *B, float *C,
                                 const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
                                 int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s,
-                                int c_planes = 0, int taps = 27, int b_wrap = 0, int64_t b_tap_stride = 0)
+                                int c_planes = 0, int taps = 27, int b_wrap = 0, int64_t b_tap_stride = 0,
+                                const int32_t *rowmap = nullptr, const uint32_t *tilemask = nullptr)
 {
     if (M <= 0 || N <= 0) return HCH_OK;
     GemmPlan p = plan;
@@ -1017,36 +1018,52 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
                      !(reinterpret_cast<uintptr_t>(A) & amask) && !(reinterpret_cast<uintptr_t>(B) & amask) &&
                      (k_split_aligned(p));
     if (b_wrap && !vec) return fail(HCH_EINVAL, "gemm: in-place weight reading needs aligned operands");
+    if (!vec || AMODE != hch::A_GATHER || taps != 27) rowmap = nullptr;     // rows in pattern order and tap skipping:
+    if (!rowmap) tilemask = nullptr;                                        // the vector path of the 3x3x3 gather only
     if (!vec && p.bm == 64) { p.bm = 128; p.wm = 4; }   // the generic path has the 128-row tiles only
     const int c_vec_ok = (c_planes > 0 ? c_planes % 4 == 0 : ldc % 4 == 0) && (c_split_stride % 4 == 0) && aligned16(C);
     const unsigned m_tiles = (unsigned)((M + p.bm - 1) / p.bm);
     // XCD-contiguous row tiles only where rows are voxels and there are enough tiles to keep
     // every XCD busy (an exact multiple of 8 cannot be told apart from the plain order, so
     // pad it by 8 as well)
-    const bool remap = (AMODE == hch::A_GATHER || AMODE == hch::A_ROWS) && m_tiles >= 256;
+    // (not in pattern order: neighbouring tiles then have the same amount of work, and dealing them
+    // round-robin is what spreads the work evenly over the XCDs)
+    const bool remap = (AMODE == hch::A_GATHER || AMODE == hch::A_ROWS) && m_tiles >= 256 && !tilemask;
     const unsigned gx = remap ? (m_tiles / hch::NUM_XCD + 1) * hch::NUM_XCD : m_tiles;
     const dim3 grid(gx, (unsigned)((N + p.bn - 1) / p.bn), (unsigned)p.splits);
     // the kernel's name as a profiler prints it: gemm_f32_kernel<TIN, BM, BN, BK, WM, AMODE, B_KC>
-    static int ids[2][2][4] = {{{-1, -1, -1, -1}, {-1, -1, -1, -1}}, {{-1, -1, -1, -1}, {-1, -1, -1, -1}}};
+    static int ids[3][2][4] = {{{-1, -1, -1, -1}, {-1, -1, -1, -1}}, {{-1, -1, -1, -1}, {-1, -1, -1, -1}}, {{-1, -1, -1, -1}, {-1, -1, -1, -1}}};
     const int cfg = p.bm == 64 ? 0 : (p.bn == 16 ? 1 : (p.bn == 32 ? 2 : 3));
-    const int v = vec ? 1 : 0, pl = c_planes > 0 ? 1 : 0;
-    if (pl && p.bn != 64) return fail(HCH_EINVAL, "gemm: plane-wise output needs the 64-column tile");
+    const int v = vec ? 1 : 0, pl = c_planes > 0 ? 1 : (tilemask ? 2 : 0);
+    if (pl == 1 && p.bn != 64) return fail(HCH_EINVAL, "gemm: plane-wise output needs the 64-column tile");
     if (ids[pl][v][cfg] < 0) {
         char nm[128];
-        snprintf(nm, sizeof nm, "gemm_f32_kernel<%s, %d, %d, 32, %d, %d, %s, %s, %s>",
+        snprintf(nm, sizeof nm, "gemm_f32_kernel<%s, %d, %d, 32, %d, %d, %s, %s, %s%s>",
                  sizeof(TIN) == 4 ? "float" : "unsigned short", p.bm, p.bm == 64 ? 64 : p.bn, p.wm,
-                 (int)AMODE, B_KC ? "true" : "false", v ? "true" : "false", pl ? "true" : "false");
+                 (int)AMODE, B_KC ? "true" : "false", v ? "true" : "false", pl == 1 ? "true" : "false", pl == 2 ? ", true" : "");
         ids[pl][v][cfg] = hch::Profiler::get().id_for(nm);
     }
     hch::LaunchTimer lt(ids[pl][v][cfg], s, alg_bytes, 2.0 * M * (double)N * K);
+#define HCH_GEMM_ARGS (const TIN *)A, (const TIN *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split, c_split_stride, c_vec_ok, \
+                      m_tiles, c_planes, taps, b_wrap, b_tap_stride, rowmap, tilemask
 #define HCH_GEMM_CASE(BM_, BN_, BK_, WM_, VEC_, PL_)                                                                \
-    HCH_LAUNCH((hch::gemm_f32_kernel<TIN, BM_, BN_, BK_, WM_, AMODE, B_KC, VEC_, PL_>), grid, dim3(256), 0, s, \
-                       (const TIN *)A, (const TIN *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split,            \
-                       c_split_stride, c_vec_ok, m_tiles, c_planes, taps, b_wrap, b_tap_stride)
+    HCH_LAUNCH((hch::gemm_f32_kernel<TIN, BM_, BN_, BK_, WM_, AMODE, B_KC, VEC_, PL_>), grid, dim3(256), 0, s, HCH_GEMM_ARGS)
+#define HCH_GEMM_SKIP_CASE(BM_, BN_, WM_)                                                                           \
+    HCH_LAUNCH((hch::gemm_f32_kernel<TIN, BM_, BN_, 32, WM_, hch::A_GATHER, B_KC, true, false, true>), grid, dim3(256), 0, s, HCH_GEMM_ARGS)
     if constexpr (AMODE == hch::A_ROWS && B_KC) {
-        if (pl) {
+        if (pl == 1) {
             if (vec) { if (p.bm == 64) HCH_GEMM_CASE(64, 64, 32, 2, true, true); else HCH_GEMM_CASE(128, 64, 32, 4, true, true); }
             else HCH_GEMM_CASE(128, 64, 32, 4, false, true);
+            HCH_LAUNCH_CHECK("gemm_f32_kernel");
+            return HCH_OK;
+        }
+    }
+    if constexpr (AMODE == hch::A_GATHER) {
+        if (vec && tilemask) {      // rows in pattern order, absent taps left out
+            if (p.bm == 64) HCH_GEMM_SKIP_CASE(64, 64, 2);
+            else if (p.bn == 16) HCH_GEMM_SKIP_CASE(128, 16, 4);
+            else if (p.bn == 32) HCH_GEMM_SKIP_CASE(128, 32, 4);
+            else HCH_GEMM_SKIP_CASE(128, 64, 4);
             HCH_LAUNCH_CHECK("gemm_f32_kernel");
             return HCH_OK;
         }
@@ -1063,6 +1080,8 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
         else HCH_GEMM_CASE(128, 64, 32, 4, false, false);
     }
 #undef HCH_GEMM_CASE
+#undef HCH_GEMM_SKIP_CASE
+#undef HCH_GEMM_ARGS
     HCH_LAUNCH_CHECK("gemm_f32_kernel");
     return HCH_OK;
 }
@@ -1132,13 +1151,14 @@ static hch_status launch_gemm(hch_dtype dtype, const GemmPlan &p, const void *A,
                               const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
                               int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s,
                               int c_planes = 0, int taps = 27, int b_wrap = 0, int64_t b_tap_stride = 0,
-                              const int32_t *nbr_t = nullptr)
+                              const int32_t *nbr_t = nullptr, const int32_t *rowmap = nullptr, const uint32_t *tilemask = nullptr)
 {
     if (dtype == HCH_BF16 && bf16_mfma_ok<AMODE, B_KC>(p, A, B, M, N, K, lda, ldb, c_planes, b_wrap))
         return launch_gemm_bf16<AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, taps, b_wrap, b_tap_stride, nbr_t);
     if (dtype == HCH_BF16)
         return launch_gemm_t<uint16_t, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps, b_wrap, b_tap_stride);
-    return launch_gemm_t<float, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps, b_wrap, b_tap_stride);
+    return launch_gemm_t<float, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps, b_wrap, b_tap_stride,
+                                             rowmap, tilemask);
 }
 
 // Register-direct gathered product (conv_direct_kernel): shape-only part of the plan, shared by
@@ -1179,22 +1199,26 @@ static DirectPlan plan_direct(int64_t M, int c, int N)
 }
 
 static hch_status launch_direct(const DirectPlan &d, const float *X, const int32_t *nbr, const float *Wm,
-                                float *out, int64_t M, int c, int N, double alg_bytes, hipStream_t s, int flipped = 0)
+                                float *out, int64_t M, int c, int N, double alg_bytes, hipStream_t s, int flipped = 0,
+                                const int32_t *rowmap = nullptr, const uint32_t *tilemask = nullptr)
 {
     const unsigned blocks = (d.wave_tiles + 3) / 4;
-    const dim3 grid((blocks / hch::NUM_XCD + 1) * hch::NUM_XCD, d.n_groups, (unsigned)d.splits);
-    static int ids[2] = {-1, -1};
-    const int b = d.check ? 1 : 0;
-    if (ids[b] < 0) {
+    const bool skip = rowmap && tilemask;        // rows in pattern order, absent taps left out, tiles dealt round-robin
+    const dim3 grid(skip ? blocks : (blocks / hch::NUM_XCD + 1) * hch::NUM_XCD, d.n_groups, (unsigned)d.splits);
+    static int ids[2][2] = {{-1, -1}, {-1, -1}};
+    const int b = d.check ? 1 : 0, k = skip ? 1 : 0;
+    if (ids[k][b] < 0) {
         char nm[96];
-        snprintf(nm, sizeof nm, "conv_direct_kernel<%d, %d, %d, %s>", d.rt, d.nt, d.S, d.check ? "true" : "false");
-        ids[b] = hch::Profiler::get().id_for(nm);
+        snprintf(nm, sizeof nm, "conv_direct_kernel<%d, %d, %d, %s%s>", d.rt, d.nt, d.S, d.check ? "true" : "false", skip ? ", true" : "");
+        ids[k][b] = hch::Profiler::get().id_for(nm);
     }
-    hch::LaunchTimer lt(ids[b], s, alg_bytes, 2.0 * M * (double)N * 27.0 * c);
-#define HCH_DIRECT_CASE(RT_, NT_, S_, CHECK_)                                                                       \
-    HCH_LAUNCH((hch::conv_direct_kernel<RT_, NT_, S_, CHECK_>), grid, dim3(256), 0, s, X, nbr, Wm, out,  \
-                       (int)M, c, N, d.J, d.j_per_split, d.upt, d.step_t, d.step_q, d.wave_tiles, M * (int64_t)N, flipped)
-    if (d.check) HCH_DIRECT_CASE(4, 1, 4, true); else HCH_DIRECT_CASE(4, 1, 4, false);
+    hch::LaunchTimer lt(ids[k][b], s, alg_bytes, 2.0 * M * (double)N * 27.0 * c);
+#define HCH_DIRECT_CASE(RT_, NT_, S_, CHECK_, SKIP_)                                                                \
+    HCH_LAUNCH((hch::conv_direct_kernel<RT_, NT_, S_, CHECK_, SKIP_>), grid, dim3(256), 0, s, X, nbr, Wm, out,  \
+                       (int)M, c, N, d.J, d.j_per_split, d.upt, d.step_t, d.step_q, d.wave_tiles, M * (int64_t)N, flipped, \
+                       rowmap, tilemask)
+    if (skip) { if (d.check) HCH_DIRECT_CASE(4, 1, 4, true, true); else HCH_DIRECT_CASE(4, 1, 4, false, true); }
+    else { if (d.check) HCH_DIRECT_CASE(4, 1, 4, true, false); else HCH_DIRECT_CASE(4, 1, 4, false, false); }
 #undef HCH_DIRECT_CASE
     HCH_LAUNCH_CHECK("conv_direct_kernel");
     return HCH_OK;
@@ -1207,19 +1231,28 @@ static bool narrow4_ok(int64_t M, int c, int N)
 }
 
 static hch_status launch_narrow4(const float *X, const int32_t *nbr, const float *Wm, float *out, int64_t M, int c,
-                                 double alg_bytes, hipStream_t s, int flipped = 0)
+                                 double alg_bytes, hipStream_t s, int flipped = 0,
+                                 const int32_t *rowmap = nullptr, const uint32_t *tilemask = nullptr)
 {
     const unsigned wave_tiles = (unsigned)((M + 63) / 64);
     const unsigned blocks = (wave_tiles + 3) / 4;
-    const dim3 grid((blocks / hch::NUM_XCD + 1) * hch::NUM_XCD);
+    const bool skip = rowmap && tilemask;
+    const dim3 grid(skip ? blocks : (blocks / hch::NUM_XCD + 1) * hch::NUM_XCD);
     const int cc = c / 16;
-    hch::LaunchTimer lt(cc == 1 ? HCH_KERNEL_ID("conv_narrow4_kernel<1>")
-                                : (cc == 2 ? HCH_KERNEL_ID("conv_narrow4_kernel<2>") : HCH_KERNEL_ID("conv_narrow4_kernel<4>")),
-                        s, alg_bytes, 2.0 * M * 4.0 * 27.0 * c);
-    if (cc == 1) HCH_LAUNCH(hch::conv_narrow4_kernel<1>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles, flipped);
-    else if (cc == 2) HCH_LAUNCH(hch::conv_narrow4_kernel<2>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles, flipped);
-    else if (cc == 4) HCH_LAUNCH(hch::conv_narrow4_kernel<4>, grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles, flipped);
+    int kid;
+    if (skip) kid = cc == 1 ? HCH_KERNEL_ID("conv_narrow4_kernel<1, true>") : (cc == 2 ? HCH_KERNEL_ID("conv_narrow4_kernel<2, true>") : HCH_KERNEL_ID("conv_narrow4_kernel<4, true>"));
+    else kid = cc == 1 ? HCH_KERNEL_ID("conv_narrow4_kernel<1>") : (cc == 2 ? HCH_KERNEL_ID("conv_narrow4_kernel<2>") : HCH_KERNEL_ID("conv_narrow4_kernel<4>"));
+    hch::LaunchTimer lt(kid, s, alg_bytes, 2.0 * M * 4.0 * 27.0 * c);
+#define HCH_NARROW_CASE(CC_)                                                                                          \
+    do {                                                                                                                \
+        if (skip) HCH_LAUNCH((hch::conv_narrow4_kernel<CC_, true>), grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles, flipped, rowmap, tilemask); \
+        else HCH_LAUNCH((hch::conv_narrow4_kernel<CC_, false>), grid, dim3(256), 0, s, X, nbr, Wm, out, (int)M, wave_tiles, flipped, rowmap, tilemask);     \
+    } while (0)
+    if (cc == 1) HCH_NARROW_CASE(1);
+    else if (cc == 2) HCH_NARROW_CASE(2);
+    else if (cc == 4) HCH_NARROW_CASE(4);
     else return fail(HCH_EINVAL, "conv_narrow4: channel count");
+#undef HCH_NARROW_CASE
     HCH_LAUNCH_CHECK("conv_narrow4_kernel");
     return HCH_OK;
 }
@@ -1347,12 +1380,14 @@ extern "C" hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_
         // indices and its feature row in, one output row out; the weights once.
         if (narrow4_ok(n, c_in, c_out) && dtype == HCH_F32 && aligned16(X) && aligned16(W) && aligned16(Y)) {
             const double bytes = (double)n * (108.0 + 4.0 * c_in + 4.0 * c_out) + 4.0 * Kc * c_out;
-            return launch_narrow4((const float *)X, L->dnbr, (const float *)W, Y, n, c_in, bytes, s);
+            return launch_narrow4((const float *)X, L->dnbr, (const float *)W, Y, n, c_in, bytes, s, 0,
+                                  skip ? L->dorder : nullptr, skip ? L->dtilemask : nullptr);
         }
         const DirectPlan d = plan_direct(n, c_in, c_out);
         if (d.ok && dtype == HCH_F32 && aligned16(X) && aligned16(W) && aligned16(Y)) {
             const double bytes = (double)n * (108.0 + 4.0 * c_in + 4.0 * c_out * d.splits) + 4.0 * Kc * c_out;
-            st = launch_direct(d, (const float *)X, L->dnbr, (const float *)W, d.splits > 1 ? part : Y, n, c_in, c_out, bytes, s);
+            st = launch_direct(d, (const float *)X, L->dnbr, (const float *)W, d.splits > 1 ? part : Y, n, c_in, c_out, bytes, s, 0,
+                               skip ? L->dorder : nullptr, skip ? L->dtilemask : nullptr);
             if (st != HCH_OK) return st;
             if (d.splits > 1) st = launch_reduce(part, Y, n * c_out, d.splits, s);
             return st;
@@ -1360,7 +1395,8 @@ extern "C" hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_
         const double bytes = (double)n * (108.0 + es * c_in + 4.0 * c_out * p.splits) + es * Kc * c_out;
         st = launch_gemm<hch::A_GATHER, false>(dtype, p, X, W,
                                                p.splits > 1 ? part : Y, L->dnbr, (int)n, c_out, Kc, c_in,
-                                               c_out, c_out, n * c_out, bytes, s, 0, 27, 0, 0, L->dnbr_t);
+                                               c_out, c_out, n * c_out, bytes, s, 0, 27, 0, 0, L->dnbr_t,
+                                               skip ? L->dorder : nullptr, skip ? L->dtilemask : nullptr);
         if (st != HCH_OK) return st;
         if (p.splits > 1) st = launch_reduce(part, Y, n * c_out, p.splits, s);
         return st;
@@ -1412,12 +1448,14 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
         // narrow outputs: kernels that read the weights in place (flipped and transposed on the fly)
         if (narrow4_ok(n, c_out, c_in) && dtype == HCH_F32 && aligned16(dY) && aligned16(dX) && aligned16(W)) {
             const double bytes = (double)n * (108.0 + 4.0 * c_out + 4.0 * c_in) + 4.0 * wn;
-            return launch_narrow4((const float *)dY, L->dnbr, (const float *)W, dX, n, c_out, bytes, s, 1);
+            return launch_narrow4((const float *)dY, L->dnbr, (const float *)W, dX, n, c_out, bytes, s, 1,
+                                  skip ? L->dorder : nullptr, skip ? L->dtilemask : nullptr);
         }
         const DirectPlan d = plan_direct(n, c_out, c_in);
         if (d.ok && dtype == HCH_F32 && aligned16(dY) && aligned16(dX) && aligned16(W)) {
             const double bytes = (double)n * (108.0 + 4.0 * c_out + 4.0 * c_in * d.splits) + 4.0 * wn;
-            st = launch_direct(d, (const float *)dY, L->dnbr, (const float *)W, d.splits > 1 ? part : dX, n, c_out, c_in, bytes, s, 1);
+            st = launch_direct(d, (const float *)dY, L->dnbr, (const float *)W, d.splits > 1 ? part : dX, n, c_out, c_in, bytes, s, 1,
+                               skip ? L->dorder : nullptr, skip ? L->dtilemask : nullptr);
             if (st != HCH_OK) return st;
             if (d.splits > 1) st = launch_reduce(part, dX, n * c_in, d.splits, s);
             return st;
@@ -1430,7 +1468,8 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
             const char *Wlast = (const char *)W + 26 * per_tap * elem_size(dtype);
             const double bytes = (double)n * (108.0 + es * c_out + 4.0 * c_in * p.splits) + es * wn;
             st = launch_gemm<hch::A_GATHER, true>(dtype, p, dY, Wlast, p.splits > 1 ? part : dX, L->dnbr, (int)n, c_in, Kd,
-                                                  c_out, c_out, c_in, n * c_in, bytes, s, 0, 27, c_out, -per_tap, L->dnbr_t);
+                                                  c_out, c_out, c_in, n * c_in, bytes, s, 0, 27, c_out, -per_tap, L->dnbr_t,
+                                                  skip ? L->dorder : nullptr, skip ? L->dtilemask : nullptr);
             if (st != HCH_OK) return st;
             if (p.splits > 1) st = launch_reduce(part, dX, n * c_in, p.splits, s);
             return st;
@@ -1448,7 +1487,8 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
         const double bytes = (double)n * (108.0 + es * c_out + 4.0 * c_in * p.splits) + es * wn;
         st = launch_gemm<hch::A_GATHER, false>(dtype, p, dY, Wt,
                                                p.splits > 1 ? part : dX, L->dnbr, (int)n, c_in, Kd, c_out,
-                                               c_in, c_in, n * c_in, bytes, s, 0, 27, 0, 0, L->dnbr_t);
+                                               c_in, c_in, n * c_in, bytes, s, 0, 27, 0, 0, L->dnbr_t,
+                                               skip ? L->dorder : nullptr, skip ? L->dtilemask : nullptr);
         if (st != HCH_OK) return st;
         if (p.splits > 1) st = launch_reduce(part, dX, n * c_in, p.splits, s);
         return st;

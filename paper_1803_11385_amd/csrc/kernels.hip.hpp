@@ -637,12 +637,12 @@ template <> struct FVec<4> { typedef float type __attribute__((ext_vector_type(4
 template <int N> __device__ __forceinline__ float vget(const typename FVec<N>::type &v, int i) { return v[i]; }
 template <> __device__ __forceinline__ float vget<1>(const float &v, int) { return v; }
 
-template <typename TIN, int BM, int BN, int BK, int WM, int AMODE, bool B_KC, bool VEC, bool C_PLANES>
+template <typename TIN, int BM, int BN, int BK, int WM, int AMODE, bool B_KC, bool VEC, bool C_PLANES, bool SKIP = false>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(
     const TIN *__restrict__ A, const TIN *__restrict__ B, float *__restrict__ C,
     const int32_t *__restrict__ nbr, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
     int k_per_split, int64_t c_split_stride, int c_vec_ok, unsigned m_tiles, int c_planes, int taps,
-    int b_wrap, int64_t b_tap_stride)
+    int b_wrap, int64_t b_tap_stride, const int32_t *__restrict__ rowmap, const uint32_t *__restrict__ tilemask)
 {
     constexpr int WN = 4 / WM;
     constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
@@ -685,9 +685,31 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     const int wm = wave % WM, wn = wave / WM;
     const int li = lane & 15, lk = lane >> 4;
     const int m0 = (int)mtile * BM, n0 = blockIdx.y * BN;
-    const int kbeg = blockIdx.z * k_per_split;
-    const int kend = min(K, kbeg + k_per_split);
     const int c = (int)lda;                           // channels per tap in the gather modes
+    // Tap skipping (gather along k, rows in pattern order): `rowmap` gives the voxel behind each
+    // row of this product and `tilemask` the taps that the voxels of each 64-row tile have.  The
+    // reduction then runs over the present taps only, k' = position in the compacted list of taps
+    // * c + channel, and tapmap translates back wherever the real tap is needed: the column of the
+    // index rows and the rows of the weights.
+    // (SKIP: instantiated for the vector path of the gather along k only.)
+    static_assert(!SKIP || (AMODE == A_GATHER && VEC), "tap skipping belongs to the gathered, vectorised product");
+    constexpr bool skipping = SKIP;
+    __shared__ uint8_t tapmap[SKIP ? 32 : 1];
+    __shared__ int32_t rowtile[SKIP ? BM : 1];        // the voxels behind this tile's rows
+    int kbeg = blockIdx.z * k_per_split;
+    int kend = min(K, kbeg + k_per_split);
+    if constexpr (SKIP) {
+        const unsigned t64 = mtile * (BM / 64), n64 = (unsigned)((M + 63) / 64);
+        uint32_t present = tilemask[t64];
+        if (BM == 128 && t64 + 1 < n64) present |= tilemask[t64 + 1];
+        if (tid < 27 && ((present >> tid) & 1u)) tapmap[__popc(present & ((1u << tid) - 1u))] = (uint8_t)tid;
+        if (tid < BM) rowtile[tid] = m0 + tid < M ? rowmap[m0 + tid] : 0;
+        const int Kp = __popc(present) * c;
+        const int per = ((Kp + (int)gridDim.z - 1) / (int)gridDim.z + BK - 1) / BK * BK;
+        kbeg = blockIdx.z * per;
+        kend = min(Kp, kbeg + per);
+        __syncthreads();
+    }
     C += (int64_t)blockIdx.z * c_split_stride;
 
     f32x4 acc[MT][NT];
@@ -733,7 +755,12 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
             const int r = a_row0 + uu * A_RSTEP;
             if (AMODE == A_ROWS) { a_ok[uu] = m0 + r < M; pa[uu] = A + (int64_t)(m0 + r) * lda + kbeg + a_col; }
             if (AMODE == A_COLS) { a_ok[uu] = m0 + a_col < M; pa[uu] = A + (int64_t)(kbeg + r) * lda + m0 + a_col; }
-            if (AMODE == A_GATHER) { a_ok[uu] = m0 + r < M; pn[uu] = nbr + (int64_t)(m0 + r) * taps; }
+            if (AMODE == A_GATHER) {
+                a_ok[uu] = m0 + r < M;
+                int64_t vox = m0 + r;
+                if constexpr (SKIP) vox = rowtile[r];
+                pn[uu] = nbr + vox * taps;
+            }
             if (AMODE == A_GATHER_T) {
                 const int gi = m0 + a_col;
                 const int tap = gi / c;
@@ -751,16 +778,26 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     bool b_ok[B_UNITS];
     int kb = kbeg;
     int b_pos = b_wrap ? kbeg % b_wrap : 0;
+    // with tap skipping the weights' rows are addressed anew for every tile: B_KC: this unit's
+    // column start (pb0) plus the tap's offset; else per unit the (compacted tap, channel) of its row
+    const TIN *pb0[B_UNITS];
+    int b_tap = b_wrap ? kbeg / b_wrap : 0;
+    int tapb[B_UNITS], ccb[B_UNITS];
     if (VEC) {
 #pragma unroll
         for (int uu = 0; uu < B_UNITS; ++uu) {
             const int r = b_row0 + uu * B_RSTEP;
             if (B_KC) {
                 b_ok[uu] = r < BN && n0 + r < N;
-                pb[uu] = B + (int64_t)(n0 + r) * ldb + b_col +
-                         (b_wrap ? (int64_t)(kbeg / b_wrap) * b_tap_stride + kbeg % b_wrap : (int64_t)kbeg);
+                pb0[uu] = B + (int64_t)(n0 + r) * ldb + b_col;
+                pb[uu] = pb0[uu] + (b_wrap ? (int64_t)(kbeg / b_wrap) * b_tap_stride + kbeg % b_wrap : (int64_t)kbeg);
             }
-            else { b_ok[uu] = r < BK && n0 + b_col < N; pb[uu] = B + (int64_t)(kbeg + r) * ldb + n0 + b_col; }
+            else {
+                b_ok[uu] = r < BK && n0 + b_col < N;
+                pb0[uu] = B + n0 + b_col;
+                pb[uu] = B + (int64_t)(kbeg + r) * ldb + n0 + b_col;
+                tapb[uu] = (kbeg + r) / c; ccb[uu] = (kbeg + r) - tapb[uu] * c;
+            }
         }
     }
 
@@ -773,7 +810,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
             bool ok;
             if (AMODE == A_GATHER) ok = a_ok[uu] && kn + a_col < kend;
             else ok = a_ok[uu] && kn + a_row0 + uu * A_RSTEP < kend;
-            out[uu] = *(ok ? pn[uu] + (AMODE == A_GATHER ? tap_n : 0) : &g_minus1);
+            int tap_col = AMODE == A_GATHER ? tap_n : 0;
+            if constexpr (SKIP) tap_col = tapmap[min(tap_n, 31)];
+            out[uu] = *(ok ? pn[uu] + tap_col : &g_minus1);
             if (AMODE == A_GATHER_T) pn[uu] += BK * taps;
         }
         if (AMODE == A_GATHER) {
@@ -806,20 +845,39 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
             }
             if (AMODE == A_GATHER) { cc_a += dcc; if (cc_a >= c) cc_a -= c; }
             ka += BK;
+            if constexpr (skipping) {
 #pragma unroll
-            for (int uu = 0; uu < B_UNITS; ++uu) {
-                bool ok;
-                if (B_KC) ok = b_ok[uu] && kb + b_col < kend;
-                else ok = b_ok[uu] && kb + b_row0 + uu * B_RSTEP < kend;
-                rb[uu] = InElem<TIN>::four(ok ? pb[uu] : zsrc);
-                pb[uu] += B_KC ? (int64_t)BK : (int64_t)BK * ldb;
-            }
-            if (B_KC && b_wrap) {
-                b_pos += BK;
-                if (b_pos >= b_wrap) {
-                    b_pos -= b_wrap;
+                for (int uu = 0; uu < B_UNITS; ++uu) {
+                    bool ok;
+                    const TIN *src;
+                    if (B_KC) {
+                        ok = b_ok[uu] && kb + b_col < kend;
+                        src = pb0[uu] + ((int64_t)tapmap[min(b_tap, 31)] * b_tap_stride + b_pos);
+                    } else {
+                        ok = b_ok[uu] && kb + b_row0 + uu * B_RSTEP < kend;
+                        src = pb0[uu] + (int64_t)((int)tapmap[min(tapb[uu], 31)] * c + ccb[uu]) * ldb;
+                        tapb[uu] += dtap; ccb[uu] += dcc;
+                        if (ccb[uu] >= c) { ccb[uu] -= c; ++tapb[uu]; }
+                    }
+                    rb[uu] = InElem<TIN>::four(ok ? src : zsrc);
+                }
+                if (B_KC) { b_pos += BK; if (b_pos >= b_wrap) { b_pos -= b_wrap; ++b_tap; } }
+            } else {
 #pragma unroll
-                    for (int uu = 0; uu < B_UNITS; ++uu) pb[uu] += b_tap_stride - b_wrap;
+                for (int uu = 0; uu < B_UNITS; ++uu) {
+                    bool ok;
+                    if (B_KC) ok = b_ok[uu] && kb + b_col < kend;
+                    else ok = b_ok[uu] && kb + b_row0 + uu * B_RSTEP < kend;
+                    rb[uu] = InElem<TIN>::four(ok ? pb[uu] : zsrc);
+                    pb[uu] += B_KC ? (int64_t)BK : (int64_t)BK * ldb;
+                }
+                if (B_KC && b_wrap) {
+                    b_pos += BK;
+                    if (b_pos >= b_wrap) {
+                        b_pos -= b_wrap;
+#pragma unroll
+                        for (int uu = 0; uu < B_UNITS; ++uu) pb[uu] += b_tap_stride - b_wrap;
+                    }
                 }
             }
             kb += BK;
@@ -988,7 +1046,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
             const int r = 4 * lk + e;
             const int gi = m0 + wm * WTM + (A_K_FAST ? mt * 16 + r : r * MT + mt);
             if (gi >= M) continue;
-            float *dst = C + (int64_t)gi * row_stride + col_off;
+            int64_t orow = gi;
+            if constexpr (SKIP) orow = rowtile[gi - m0];
+            float *dst = C + orow * row_stride + col_off;
             if (NT == 4 && c_vec_ok && gj + 4 <= N) {
                 *reinterpret_cast<f32x4 *>(dst) = f32x4{acc[mt][0][e], acc[mt][1 % NT][e], acc[mt][2 % NT][e], acc[mt][3 % NT][e]};
             } else if (NT == 2 && c_vec_ok && gj + 2 <= N) {

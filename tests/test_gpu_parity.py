@@ -186,8 +186,8 @@ def test_col2hash(oracle, case_small, c_in):
 # convolution forward and backward
 # --------------------------------------------------------------------------------------
 
-ALGOS = [hch.HCH_ALGO_COLUMNS, hch.HCH_ALGO_FUSED]
-ALGO_IDS = ["columns", "fused"]
+ALGOS = [hch.HCH_ALGO_COLUMNS, hch.HCH_ALGO_FUSED, hch.HCH_ALGO_FUSED_DENSE]
+ALGO_IDS = ["columns", "fused", "fused-dense"]
 
 
 def _conv_fwd_gpu(case, level, X, W, ws_bytes=None, algo=hch.HCH_ALGO_COLUMNS):
@@ -227,7 +227,7 @@ def test_conv_fwd_batch64_4_to_32(oracle, case_batch64, algo):
     W = S.gaussian((27, 4, 32), 0.05, 2000)
     want = oracle.conv_fwd(L, oracle.to_paper_X(X), oracle.to_paper_W(W)).T
     assert_close(_conv_fwd_gpu(case, 0, X, W, algo=algo), want, what="conv fwd 4->32")
-    if algo == hch.HCH_ALGO_FUSED:
+    if algo != hch.HCH_ALGO_COLUMNS:
         return
     # the same through a workspace that forces several chunks
     small = hch.hch_conv_workspace_bytes(case.glv, 0, 4, 32, hch.HCH_F32, hch.HCH_WS_MIN)
@@ -771,20 +771,26 @@ def test_general_conv(oracle, case_small, F, stride, pad, c_in, c_out, bf16):
 
 
 def test_general_conv_equals_3x3x3(case_small):
-    """F = 3, stride 1 through the general entry points gives the bits of hch_conv_fwd (fused)."""
+    """F = 3, stride 1 through the general entry points gives the bits of hch_conv_fwd with the fused
+    algorithm that multiplies every tap (HCH_ALGO_FUSED_DENSE); the default fused algorithm leaves
+    out the taps a tile of voxels lacks, which changes where a split reduction is cut and hence
+    the rounding, not the sums."""
     case = case_small
     n = case.olv[0].Ntot
     X, W = dev(S.gaussian((n, 32), 1.0, 111)), dev(S.gaussian((27, 32, 64), 0.1, 112))
     field = torch.empty((n, 27), dtype=torch.int32, device="cuda")
     hch.hch_field_build(case.glv, 0, 3, 1, 1, field, None)
-    F32, FU = hch.HCH_F32, hch.HCH_ALGO_FUSED
+    F32, FU, FD = hch.HCH_F32, hch.HCH_ALGO_FUSED, hch.HCH_ALGO_FUSED_DENSE
     Y1 = torch.empty((n, 64), dtype=torch.float32, device="cuda")
-    Y2 = torch.empty_like(Y1)
+    Y2, Y3 = torch.empty_like(Y1), torch.empty_like(Y1)
     hch.hch_sconv_fwd(case.glv, 0, 3, 1, F32, X, W, Y1, field, 32, 64,
                       workspace(hch.hch_sconv_workspace_bytes(case.glv, 0, 3, 1, 32, 64, F32, hch.HCH_WS_FWD)))
     hch.hch_conv_fwd(case.glv, 0, F32, X, W, Y2, 32, 64,
-                     workspace(hch.hch_conv_workspace_bytes(case.glv, 0, 32, 64, F32, hch.HCH_WS_FWD, FU)), FU)
+                     workspace(hch.hch_conv_workspace_bytes(case.glv, 0, 32, 64, F32, hch.HCH_WS_FWD, FD)), FD)
     assert torch.equal(Y1, Y2)
+    hch.hch_conv_fwd(case.glv, 0, F32, X, W, Y3, 32, 64,
+                     workspace(hch.hch_conv_workspace_bytes(case.glv, 0, 32, 64, F32, hch.HCH_WS_FWD, FU)), FU)
+    assert_close(Y3.cpu().numpy(), Y2.cpu().numpy(), what="fused vs fused without tap skipping")
 
 
 @pytest.mark.parametrize("c", [1, 16, 37])
