@@ -992,10 +992,16 @@ static GemmPlan plan_wgrad(int64_t n, int c_in, int c_out, int taps = 27, int gr
     // whole slices, if that still fills most of the chip
     if (gran == hch::BF16_BK && tiles <= 96 && (96 / tiles) * tiles >= 64) want = 8 * (96 / tiles);
     want = std::min<int64_t>(want, std::max<int64_t>(1, (n + 255) / 256));
+    // fp32 kernel: a multiple of 8 slices as well (each XCD takes whole slices and gathers their
+    // voxels once for all its tiles) where that costs at most an eighth of the slices
+    if (gran != hch::BF16_BK && want >= 8) want = want / 8 * 8;
     int64_t rows = (n + want - 1) / want;
     rows = std::max<int64_t>(gran, (rows + gran - 1) / gran * gran);
     p.k_per_split = (int)rows;
     p.splits = (int)std::max<int64_t>(1, (n + rows - 1) / rows);
+    // keep the count a multiple of 8 (rounding the slice length up may have dropped a few slices;
+    // the extra ones are empty and write zeros)
+    if (want >= 8 && want % 8 == 0 && p.splits <= want) p.splits = (int)((p.splits + 7) / 8 * 8);
     return p;
 }
 
@@ -1030,7 +1036,10 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
     // round-robin is what spreads the work evenly over the XCDs)
     const bool remap = (AMODE == hch::A_GATHER || AMODE == hch::A_ROWS) && m_tiles >= 256 && !tilemask;
     const unsigned gx = remap ? (m_tiles / hch::NUM_XCD + 1) * hch::NUM_XCD : m_tiles;
-    const dim3 grid(gx, (unsigned)((N + p.bn - 1) / p.bn), (unsigned)p.splits);
+    const unsigned n_tiles = (unsigned)((N + p.bn - 1) / p.bn);
+    // reductions over the voxels cut into a multiple of 8 slices: one XCD per slice
+    const int flat = ((AMODE == hch::A_GATHER_T || AMODE == hch::A_COLS) && p.splits >= 8 && p.splits % (int)hch::NUM_XCD == 0) ? p.splits : 0;
+    const dim3 grid = flat ? dim3((unsigned)p.splits * m_tiles * n_tiles) : dim3(gx, n_tiles, (unsigned)p.splits);
     // the kernel's name as a profiler prints it: gemm_f32_kernel<TIN, BM, BN, BK, WM, AMODE, B_KC>
     static int ids[3][2][4] = {{{-1, -1, -1, -1}, {-1, -1, -1, -1}}, {{-1, -1, -1, -1}, {-1, -1, -1, -1}}, {{-1, -1, -1, -1}, {-1, -1, -1, -1}}};
     const int cfg = p.bm == 64 ? 0 : (p.bn == 16 ? 1 : (p.bn == 32 ? 2 : 3));
@@ -1045,7 +1054,7 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
     }
     hch::LaunchTimer lt(ids[pl][v][cfg], s, alg_bytes, 2.0 * M * (double)N * K);
 #define HCH_GEMM_ARGS (const TIN *)A, (const TIN *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split, c_split_stride, c_vec_ok, \
-                      m_tiles, c_planes, taps, b_wrap, b_tap_stride, rowmap, tilemask
+                      m_tiles, c_planes, taps, b_wrap, b_tap_stride, rowmap, tilemask, flat
 #define HCH_GEMM_CASE(BM_, BN_, BK_, WM_, VEC_, PL_)                                                                \
     HCH_LAUNCH((hch::gemm_f32_kernel<TIN, BM_, BN_, BK_, WM_, AMODE, B_KC, VEC_, PL_>), grid, dim3(256), 0, s, HCH_GEMM_ARGS)
 #define HCH_GEMM_SKIP_CASE(BM_, BN_, WM_)                                                                           \

@@ -642,7 +642,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     const TIN *__restrict__ A, const TIN *__restrict__ B, float *__restrict__ C,
     const int32_t *__restrict__ nbr, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
     int k_per_split, int64_t c_split_stride, int c_vec_ok, unsigned m_tiles, int c_planes, int taps,
-    int b_wrap, int64_t b_tap_stride, const int32_t *__restrict__ rowmap, const uint32_t *__restrict__ tilemask)
+    int b_wrap, int64_t b_tap_stride, const int32_t *__restrict__ rowmap, const uint32_t *__restrict__ tilemask,
+    int flat_slices)
 {
     constexpr int WN = 4 / WM;
     constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
@@ -676,15 +677,29 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     __shared__ __attribute__((aligned(16))) float As2[2 * A_LDS];
     __shared__ __attribute__((aligned(16))) float Bs2[2 * B_LDS];
 
-    // gridDim.x == m_tiles: plain order; gridDim.x > m_tiles (a multiple of 8): XCD-contiguous
-    const unsigned mtile = gridDim.x == m_tiles ? blockIdx.x : xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
-    if (mtile >= m_tiles) return;
+    // gridDim.x == m_tiles: plain order; gridDim.x > m_tiles (a multiple of 8): XCD-contiguous.
+    // flat_slices > 0 (a multiple of 8): a one-dimensional grid in which workgroup b belongs to XCD
+    // b % 8 (workgroups are handed to the XCDs in turn) and slice s of the reduction is computed,
+    // all tiles of it, by XCD s % 8.  The tiles of a slice of the weight gradient walk through the
+    // same voxels at the same time -- each gathers them for its own taps -- and so meet the rows
+    // in one L2 instead of fetching them from memory once per tile.
+    unsigned mtile, ntile = blockIdx.y, slice = blockIdx.z, n_slices = gridDim.z;
+    if (flat_slices > 0) {
+        const unsigned n_tiles = (unsigned)((N + BN - 1) / BN), tiles = m_tiles * n_tiles;
+        const unsigned q = blockIdx.x / NUM_XCD, t = q % tiles;
+        slice = (q / tiles) * NUM_XCD + blockIdx.x % NUM_XCD;
+        mtile = t % m_tiles; ntile = t / m_tiles;
+        n_slices = (unsigned)flat_slices;
+    } else {
+        mtile = gridDim.x == m_tiles ? blockIdx.x : xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
+        if (mtile >= m_tiles) return;
+    }
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
     const int li = lane & 15, lk = lane >> 4;
-    const int m0 = (int)mtile * BM, n0 = blockIdx.y * BN;
+    const int m0 = (int)mtile * BM, n0 = (int)ntile * BN;
     const int c = (int)lda;                           // channels per tap in the gather modes
     // Tap skipping (gather along k, rows in pattern order): `rowmap` gives the voxel behind each
     // row of this product and `tilemask` the taps that the voxels of each 64-row tile have.  The
@@ -696,7 +711,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     constexpr bool skipping = SKIP;
     __shared__ uint8_t tapmap[SKIP ? 32 : 1];
     __shared__ int32_t rowtile[SKIP ? BM : 1];        // the voxels behind this tile's rows
-    int kbeg = blockIdx.z * k_per_split;
+    int kbeg = (int)slice * k_per_split;
     int kend = min(K, kbeg + k_per_split);
     if constexpr (SKIP) {
         const unsigned t64 = mtile * (BM / 64), n64 = (unsigned)((M + 63) / 64);
@@ -705,12 +720,12 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
         if (tid < 27 && ((present >> tid) & 1u)) tapmap[__popc(present & ((1u << tid) - 1u))] = (uint8_t)tid;
         if (tid < BM) rowtile[tid] = m0 + tid < M ? rowmap[m0 + tid] : 0;
         const int Kp = __popc(present) * c;
-        const int per = ((Kp + (int)gridDim.z - 1) / (int)gridDim.z + BK - 1) / BK * BK;
-        kbeg = blockIdx.z * per;
+        const int per = ((Kp + (int)n_slices - 1) / (int)n_slices + BK - 1) / BK * BK;
+        kbeg = (int)slice * per;
         kend = min(Kp, kbeg + per);
         __syncthreads();
     }
-    C += (int64_t)blockIdx.z * c_split_stride;
+    C += (int64_t)slice * c_split_stride;
 
     f32x4 acc[MT][NT];
 #pragma unroll
