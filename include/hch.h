@@ -472,6 +472,16 @@ hch_status hch_relu_fwd(const float *x, float *y, int64_t n, void *stream);
 hch_status hch_relu_bwd(const float *y, const float *dy, float *dx, int64_t n, void *stream);
 
 /*
+ * Measurement aid: a kernel that does nothing but matrix instructions, so that a benchmark can
+ * state the rate the chip's matrix pipes actually reach next to the rates of the products above.
+ * `workgroups` workgroups of 4 wavefronts each run `iters` iterations of 8 independent
+ * instructions (HCH_F32: v_mfma_f32_16x16x4_f32, 2048 flops each; HCH_BF16:
+ * v_mfma_f32_16x16x32_bf16, 16384 flops each), i.e. workgroups * 4 * iters * 8 instructions.
+ *   sink  DEVICE [workgroups * 256] float, overwritten.  Asynchronous on `stream`.
+ */
+hch_status hch_probe_mfma(hch_dtype dtype, int32_t iters, int32_t workgroups, float *sink, void *stream);
+
+/*
  * Optional per-kernel timing, for benchmarks.  A kernel gets an id in [0, hch_kernel_count())
  * the first time it is launched; hch_kernel_name gives the name of its __global__ function,
  * template arguments included, as a profiler prints it (the pointer is valid until the next

@@ -617,6 +617,9 @@ void orc_unpool_max_bwd(int c, int64_t Nf, int64_t Nc, const double *dDfine, con
 #ifdef _OPENMP
 #include <omp.h>
 int orc_threads(void) { return omp_get_max_threads(); }
+/* number of threads the loops above use from now on (for timing the oracle at 1 thread) */
+void orc_set_threads(int n) { if (n >= 1) omp_set_num_threads(n); }
 #else
 int orc_threads(void) { return 1; }
+void orc_set_threads(int n) { (void)n; }
 #endif

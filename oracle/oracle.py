@@ -85,6 +85,11 @@ def threads():
     return lib().orc_threads()
 
 
+def set_threads(n):
+    """Threads of the oracle's OpenMP loops from now on (timing only; results do not depend on it)."""
+    lib().orc_set_threads(C.c_int(int(n)))
+
+
 def psh_build(coords, ubar):
     """PSH of one model (Section 3.1, 5.2).  Returns dict(m, r, H, T, Phi, attempts)."""
     coords = np.ascontiguousarray(coords, dtype=np.int32)

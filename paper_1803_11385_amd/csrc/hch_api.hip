@@ -2243,6 +2243,20 @@ extern "C" hch_status hch_relu_bwd(const float *y, const float *dy, float *dx, i
 // per-kernel timing
 // ---------------------------------------------------------------------------------------
 
+extern "C" hch_status hch_probe_mfma(hch_dtype dtype, int32_t iters, int32_t workgroups, float *sink, void *stream)
+{
+    if (!sink || iters <= 0 || workgroups <= 0 || (dtype != HCH_F32 && dtype != HCH_BF16))
+        return fail(HCH_EINVAL, "hch_probe_mfma: bad argument");
+    hipStream_t s = (hipStream_t)stream;
+    const double waves = 4.0 * workgroups, per = dtype == HCH_BF16 ? 16384.0 : 2048.0;
+    hch::LaunchTimer lt(dtype == HCH_BF16 ? HCH_KERNEL_ID("mfma_probe_kernel<true>") : HCH_KERNEL_ID("mfma_probe_kernel<false>"),
+                        s, 0.0, waves * iters * 8.0 * per);
+    if (dtype == HCH_BF16) HCH_LAUNCH(hch::mfma_probe_kernel<true>, dim3((unsigned)workgroups), dim3(256), 0, s, sink, iters);
+    else HCH_LAUNCH(hch::mfma_probe_kernel<false>, dim3((unsigned)workgroups), dim3(256), 0, s, sink, iters);
+    HCH_LAUNCH_CHECK("mfma_probe_kernel");
+    return HCH_OK;
+}
+
 extern "C" int32_t hch_kernel_count(void) { return hch::Profiler::get().count(); }
 
 extern "C" const char *hch_kernel_name(int32_t id)

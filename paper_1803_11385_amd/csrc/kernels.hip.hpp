@@ -1122,6 +1122,37 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(
     }
 }
 
+// A loop of independent matrix instructions with nothing else in it: what the matrix pipes of
+// the chip deliver at their best, measured next to the kernels that use them.  BF16 = false:
+// v_mfma_f32_16x16x4_f32 (2048 flops each), true: v_mfma_f32_16x16x32_bf16 (16384 flops each);
+// 8 instructions per iteration and wavefront.
+typedef __bf16 bf16x8_probe __attribute__((ext_vector_type(8)));
+template <bool BF16>
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ sink, int iters)
+{
+    f32x4 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const float a = threadIdx.x * 1e-3f, b = threadIdx.x * 2e-3f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if constexpr (BF16) {
+                bf16x8_probe va, vb;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { va[e] = (__bf16)a; vb[e] = (__bf16)b; }
+                acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, vb, acc[i], 0, 0, 0);
+            } else {
+                acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[i], 0, 0, 0);
+            }
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+    sink[(int64_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 // number of entries >= 0 in an index list (the occupied neighbours of a level: the nnz of the
 // traffic model); count must be zero before the launch
 __global__ __launch_bounds__(256) void count_valid_kernel(const int32_t *__restrict__ idx, int64_t n,
