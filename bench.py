@@ -11,7 +11,6 @@ Prints ONE JSON line; README.md lists its fields.
 from __future__ import annotations
 
 import argparse
-import hashlib
 import json
 import os
 import sys
@@ -36,18 +35,6 @@ def make_inputs(config, batch, u):
     X0 = S.normals_plus_one(normals)
     W = [S.he_weights(CHANNELS[l], CHANNELS[l + 1], 4000 + l) for l in range(5)]
     return coords, offs, X0, W
-
-
-def source_digest():
-    """sha256 over the library's sources: ties a committed counter summary under profiles/ to the
-    code it was measured on (each summary names the digest of the sources it ran)."""
-    h = hashlib.sha256()
-    base = os.path.join(ROOT, "paper_1803_11385_amd", "csrc")
-    for name in sorted(os.listdir(base)):
-        with open(os.path.join(base, name), "rb") as f:
-            h.update(name.encode())
-            h.update(f.read())
-    return h.hexdigest()[:16]
 
 
 def cpu_baseline(coords, offs, X0, W, u, max_shapes, budget_s=16.0):
@@ -284,6 +271,7 @@ def main():
                 out[hch.hch_kernel_name(i)] = (i, st)
         return out
 
+    from paper_1803_11385_amd.build import source_digest
     digest = source_digest()
 
     def load_traffic(algo_name):

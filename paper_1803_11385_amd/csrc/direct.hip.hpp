@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(
 
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int r = lane & 15, g = lane >> 4;
-    const unsigned tile = (SKIP ? blockIdx.x : xcd_tile(blockIdx.x, gridDim.x / NUM_XCD)) * 4 + wv;
+    const unsigned tile = (SKIP ? xcd_chunk_tile(blockIdx.x, skip_chunk(wave_tiles, 4)) : xcd_tile(blockIdx.x, gridDim.x / NUM_XCD)) * 4 + wv;
     if (tile >= wave_tiles) return;                    // no barrier below: a wave may leave alone
     const int nb = blockIdx.y * (16 * NT);
     int jb = blockIdx.z * j_per_split;
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(256) void conv_narrow4_kernel(
     __shared__ uint8_t stap[SKIP ? 4 * 32 : 1];
 
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const unsigned tile = (SKIP ? blockIdx.x : xcd_tile(blockIdx.x, gridDim.x / NUM_XCD)) * 4 + wv;
+    const unsigned tile = (SKIP ? xcd_chunk_tile(blockIdx.x, skip_chunk(wave_tiles, 4)) : xcd_tile(blockIdx.x, gridDim.x / NUM_XCD)) * 4 + wv;
     if (tile >= wave_tiles) return;                    // no workgroup barrier below
 
     int32_t *my = sidx + wv * IDX;

@@ -1032,10 +1032,11 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
     // XCD-contiguous row tiles only where rows are voxels and there are enough tiles to keep
     // every XCD busy (an exact multiple of 8 cannot be told apart from the plain order, so
     // pad it by 8 as well)
-    // (not in pattern order: neighbouring tiles then have the same amount of work, and dealing them
-    // round-robin is what spreads the work evenly over the XCDs)
+    // (in pattern order neighbouring tiles have the same amount of work: chunks of tiles go to the
+    // XCDs in turn, see xcd_chunk_tile, and the grid is a whole number of rounds of chunks)
     const bool remap = (AMODE == hch::A_GATHER || AMODE == hch::A_ROWS) && m_tiles >= 256 && !tilemask;
-    const unsigned gx = remap ? (m_tiles / hch::NUM_XCD + 1) * hch::NUM_XCD : m_tiles;
+    const unsigned gx = tilemask ? hch::skip_grid(m_tiles, hch::skip_chunk(m_tiles * (unsigned)(p.bm / 64), (unsigned)(p.bm / 64)))
+                                 : (remap ? (m_tiles / hch::NUM_XCD + 1) * hch::NUM_XCD : m_tiles);
     const unsigned n_tiles = (unsigned)((N + p.bn - 1) / p.bn);
     // reductions over the voxels cut into a multiple of 8 slices: one XCD per slice
     const int flat = ((AMODE == hch::A_GATHER_T || AMODE == hch::A_COLS) && p.splits >= 8 && p.splits % (int)hch::NUM_XCD == 0) ? p.splits : 0;
@@ -1212,8 +1213,8 @@ static hch_status launch_direct(const DirectPlan &d, const float *X, const int32
                                 const int32_t *rowmap = nullptr, const uint32_t *tilemask = nullptr)
 {
     const unsigned blocks = (d.wave_tiles + 3) / 4;
-    const bool skip = rowmap && tilemask;        // rows in pattern order, absent taps left out, tiles dealt round-robin
-    const dim3 grid(skip ? blocks : (blocks / hch::NUM_XCD + 1) * hch::NUM_XCD, d.n_groups, (unsigned)d.splits);
+    const bool skip = rowmap && tilemask;        // rows in pattern order, absent taps left out, chunks of tiles per XCD
+    const dim3 grid(skip ? hch::skip_grid(blocks, hch::skip_chunk(d.wave_tiles, 4)) : (blocks / hch::NUM_XCD + 1) * hch::NUM_XCD, d.n_groups, (unsigned)d.splits);
     static int ids[2][2] = {{-1, -1}, {-1, -1}};
     const int b = d.check ? 1 : 0, k = skip ? 1 : 0;
     if (ids[k][b] < 0) {
@@ -1246,7 +1247,7 @@ static hch_status launch_narrow4(const float *X, const int32_t *nbr, const float
     const unsigned wave_tiles = (unsigned)((M + 63) / 64);
     const unsigned blocks = (wave_tiles + 3) / 4;
     const bool skip = rowmap && tilemask;
-    const dim3 grid(skip ? blocks : (blocks / hch::NUM_XCD + 1) * hch::NUM_XCD);
+    const dim3 grid(skip ? hch::skip_grid(blocks, hch::skip_chunk(wave_tiles, 4)) : (blocks / hch::NUM_XCD + 1) * hch::NUM_XCD);
     const int cc = c / 16;
     int kid;
     if (skip) kid = cc == 1 ? HCH_KERNEL_ID("conv_narrow4_kernel<1, true>") : (cc == 2 ? HCH_KERNEL_ID("conv_narrow4_kernel<2, true>") : HCH_KERNEL_ID("conv_narrow4_kernel<4, true>"));

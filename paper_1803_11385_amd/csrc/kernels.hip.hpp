@@ -20,6 +20,31 @@ __device__ __forceinline__ unsigned xcd_tile(unsigned bid, unsigned per_xcd)
     return (bid % NUM_XCD) * per_xcd + bid / NUM_XCD;
 }
 
+// Kernels that leave out taps walk the tiles of the pattern order, in which equal neighbour
+// patterns lie together: contiguous ranges per XCD would give one XCD all the dense patterns, plain
+// round-robin makes every XCD fetch every row.  In between: chunks of `chunk` consecutive tiles
+// (neighbours in space as far as the order allows) go to the XCDs in turn.  The grid holds a
+// multiple of 8*chunk workgroups; tiles past the last one are skipped by the caller.
+__device__ __forceinline__ unsigned xcd_chunk_tile(unsigned bid, unsigned chunk)
+{
+    const unsigned x = bid % NUM_XCD, q = bid / NUM_XCD;
+    return ((q / chunk) * NUM_XCD + x) * chunk + q % chunk;
+}
+// Tiles per chunk when a workgroup computes `group` of `tiles64` 64-row tiles: 16 tiles' worth of
+// rows; on small levels 1, which is plain round-robin (few chunks per XCD would leave some XCDs
+// with a chunk more than others).  Host and kernels derive the chunk, and the host the grid from
+// it, with this one function.
+__host__ __device__ __forceinline__ unsigned skip_chunk(unsigned tiles64, unsigned group)
+{
+    return tiles64 >= 512u ? 16u / group : 1u;
+}
+// workgroups to launch for `blocks` workgroups' worth of tiles: whole rounds of chunks
+__host__ __device__ __forceinline__ unsigned skip_grid(unsigned blocks, unsigned chunk)
+{
+    const unsigned round = NUM_XCD * chunk;
+    return chunk > 1u ? (blocks + round - 1) / round * round : blocks;
+}
+
 // Where there is nothing to load (an empty neighbour, a unit of a tile outside its matrix) the
 // kernels load from these constants instead (16 bytes of zeros, an index of -1): loads stay
 // unconditional, so a thread issues all of them back to back and nothing waits on a branch.
@@ -691,7 +716,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
         mtile = t % m_tiles; ntile = t / m_tiles;
         n_slices = (unsigned)flat_slices;
     } else {
-        mtile = gridDim.x == m_tiles ? blockIdx.x : xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
+        if constexpr (SKIP) mtile = xcd_chunk_tile(blockIdx.x, skip_chunk(m_tiles * (BM / 64), BM / 64));
+        else mtile = gridDim.x == m_tiles ? blockIdx.x : xcd_tile(blockIdx.x, gridDim.x / NUM_XCD);
         if (mtile >= m_tiles) return;
     }
 
