@@ -1012,7 +1012,7 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
                                 const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
                                 int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s,
                                 int c_planes = 0, int taps = 27, int b_wrap = 0, int64_t b_tap_stride = 0,
-                                const int32_t *rowmap = nullptr, const uint32_t *tilemask = nullptr)
+                                const int32_t *rowmap = nullptr, const uint32_t *tilemask = nullptr, int64_t a_rows = 0)
 {
     if (M <= 0 || N <= 0) return HCH_OK;
     GemmPlan p = plan;
@@ -1042,18 +1042,39 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
     const int flat = ((AMODE == hch::A_GATHER_T || AMODE == hch::A_COLS) && p.splits >= 8 && p.splits % (int)hch::NUM_XCD == 0) ? p.splits : 0;
     const dim3 grid = flat ? dim3((unsigned)p.splits * m_tiles * n_tiles) : dim3(gx, n_tiles, (unsigned)p.splits);
     // the kernel's name as a profiler prints it: gemm_f32_kernel<TIN, BM, BN, BK, WM, AMODE, B_KC>
-    static int ids[3][2][4] = {{{-1, -1, -1, -1}, {-1, -1, -1, -1}}, {{-1, -1, -1, -1}, {-1, -1, -1, -1}}, {{-1, -1, -1, -1}, {-1, -1, -1, -1}}};
+    static int ids[2][3][2][4];                        // [lean][planes / skipping][vector path][tile shape]
+    static const bool ids_ready = [] { memset(ids, 0xFF, sizeof ids); return true; }();
+    (void)ids_ready;
     const int cfg = p.bm == 64 ? 0 : (p.bn == 16 ? 1 : (p.bn == 32 ? 2 : 3));
     const int v = vec ? 1 : 0, pl = c_planes > 0 ? 1 : (tilemask ? 2 : 0);
     if (pl == 1 && p.bn != 64) return fail(HCH_EINVAL, "gemm: plane-wise output needs the 64-column tile");
-    if (ids[pl][v][cfg] < 0) {
+    // The lean loop (buffer loads, scalar offsets): float gathers of a 3x3x3 neighbourhood whose
+    // operands stay below 2 GiB each, so that 32-bit byte offsets reach everything and a negative
+    // offset is out of range; row indices must fit the 24-bit multiply.  Gathering along the
+    // reduction axis a tile must lie within one tap (rows of a multiple of 32 channels).
+    constexpr bool lean_mode = (AMODE == hch::A_GATHER || (AMODE == hch::A_GATHER_T && !B_KC)) && sizeof(TIN) == 4;
+    bool lean = false;
+    if constexpr (lean_mode) {
+        const int64_t lim = (int64_t)1 << 31;
+        const int64_t idx_rows = AMODE == hch::A_GATHER ? M : K;
+        int64_t b_bytes;
+        if (AMODE == hch::A_GATHER_T) b_bytes = (int64_t)K * ldb * 4;
+        else if (B_KC) b_bytes = ((int64_t)(taps - 1) * (b_tap_stride < 0 ? -b_tap_stride : b_tap_stride) + (int64_t)N * ldb) * 4;
+        else b_bytes = (int64_t)taps * lda * ldb * 4;
+        lean = vec && c_planes == 0 && taps == 27 && nbr && a_rows > 0 && a_rows < ((int64_t)1 << 23) && lda * 4 < ((int64_t)1 << 23) &&
+               a_rows * lda * 4 < lim && idx_rows * taps * 4 < lim && b_bytes < lim &&
+               (AMODE == hch::A_GATHER_T || (lda % 32 == 0 && (B_KC ? b_wrap == (int)lda : b_wrap == 0)));
+    }
+    const int ln = lean ? 1 : 0;
+    if (ids[ln][pl][v][cfg] < 0) {
         char nm[128];
         snprintf(nm, sizeof nm, "gemm_f32_kernel<%s, %d, %d, 32, %d, %d, %s, %s, %s%s>",
                  sizeof(TIN) == 4 ? "float" : "unsigned short", p.bm, p.bm == 64 ? 64 : p.bn, p.wm,
-                 (int)AMODE, B_KC ? "true" : "false", v ? "true" : "false", pl == 1 ? "true" : "false", pl == 2 ? ", true" : "");
-        ids[pl][v][cfg] = hch::Profiler::get().id_for(nm);
+                 (int)AMODE, B_KC ? "true" : "false", v ? "true" : "false", pl == 1 ? "true" : "false",
+                 lean ? (pl == 2 ? ", true, true" : ", false, true") : (pl == 2 ? ", true" : ""));
+        ids[ln][pl][v][cfg] = hch::Profiler::get().id_for(nm);
     }
-    hch::LaunchTimer lt(ids[pl][v][cfg], s, alg_bytes, 2.0 * M * (double)N * K);
+    hch::LaunchTimer lt(ids[ln][pl][v][cfg], s, alg_bytes, 2.0 * M * (double)N * K);
 #define HCH_GEMM_ARGS (const TIN *)A, (const TIN *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split, c_split_stride, c_vec_ok, \
                       m_tiles, c_planes, taps, b_wrap, b_tap_stride, rowmap, tilemask, flat
 #define HCH_GEMM_CASE(BM_, BN_, BK_, WM_, VEC_, PL_)                                                                \
@@ -1068,6 +1089,29 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
             return HCH_OK;
         }
     }
+#define HCH_GEMM_LEAN_CASE(BM_, BN_, WM_, SKIP_)                                                                     \
+    HCH_LAUNCH((hch::gemm_f32_kernel<TIN, BM_, BN_, 32, WM_, AMODE, B_KC, true, false, SKIP_, true>), grid, dim3(256), 0, s, HCH_GEMM_ARGS)
+    if constexpr (lean_mode) {
+        if (lean) {
+            if constexpr (AMODE == hch::A_GATHER) {
+                if (tilemask) {
+                    if (p.bm == 64) HCH_GEMM_LEAN_CASE(64, 64, 2, true);
+                    else if (p.bn == 16) HCH_GEMM_LEAN_CASE(128, 16, 4, true);
+                    else if (p.bn == 32) HCH_GEMM_LEAN_CASE(128, 32, 4, true);
+                    else HCH_GEMM_LEAN_CASE(128, 64, 4, true);
+                    HCH_LAUNCH_CHECK("gemm_f32_kernel");
+                    return HCH_OK;
+                }
+            }
+            if (p.bm == 64) HCH_GEMM_LEAN_CASE(64, 64, 2, false);
+            else if (p.bn == 16) HCH_GEMM_LEAN_CASE(128, 16, 4, false);
+            else if (p.bn == 32) HCH_GEMM_LEAN_CASE(128, 32, 4, false);
+            else HCH_GEMM_LEAN_CASE(128, 64, 4, false);
+            HCH_LAUNCH_CHECK("gemm_f32_kernel");
+            return HCH_OK;
+        }
+    }
+#undef HCH_GEMM_LEAN_CASE
     if constexpr (AMODE == hch::A_GATHER) {
         if (vec && tilemask) {      // rows in pattern order, absent taps left out
             if (p.bm == 64) HCH_GEMM_SKIP_CASE(64, 64, 2);
@@ -1161,14 +1205,15 @@ static hch_status launch_gemm(hch_dtype dtype, const GemmPlan &p, const void *A,
                               const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
                               int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s,
                               int c_planes = 0, int taps = 27, int b_wrap = 0, int64_t b_tap_stride = 0,
-                              const int32_t *nbr_t = nullptr, const int32_t *rowmap = nullptr, const uint32_t *tilemask = nullptr)
+                              const int32_t *nbr_t = nullptr, const int32_t *rowmap = nullptr, const uint32_t *tilemask = nullptr,
+                              int64_t a_rows = 0 /* rows of the gathered matrix; 0: not known, no lean loop */)
 {
     if (dtype == HCH_BF16 && bf16_mfma_ok<AMODE, B_KC>(p, A, B, M, N, K, lda, ldb, c_planes, b_wrap))
         return launch_gemm_bf16<AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, taps, b_wrap, b_tap_stride, nbr_t);
     if (dtype == HCH_BF16)
         return launch_gemm_t<uint16_t, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps, b_wrap, b_tap_stride);
     return launch_gemm_t<float, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps, b_wrap, b_tap_stride,
-                                             rowmap, tilemask);
+                                             rowmap, tilemask, a_rows);
 }
 
 // Register-direct gathered product (conv_direct_kernel): shape-only part of the plan, shared by
@@ -1406,7 +1451,7 @@ extern "C" hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_
         st = launch_gemm<hch::A_GATHER, false>(dtype, p, X, W,
                                                p.splits > 1 ? part : Y, L->dnbr, (int)n, c_out, Kc, c_in,
                                                c_out, c_out, n * c_out, bytes, s, 0, 27, 0, 0, L->dnbr_t,
-                                               skip ? L->dorder : nullptr, skip ? L->dtilemask : nullptr);
+                                               skip ? L->dorder : nullptr, skip ? L->dtilemask : nullptr, n);
         if (st != HCH_OK) return st;
         if (p.splits > 1) st = launch_reduce(part, Y, n * c_out, p.splits, s);
         return st;
@@ -1479,7 +1524,7 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
             const double bytes = (double)n * (108.0 + es * c_out + 4.0 * c_in * p.splits) + es * wn;
             st = launch_gemm<hch::A_GATHER, true>(dtype, p, dY, Wlast, p.splits > 1 ? part : dX, L->dnbr, (int)n, c_in, Kd,
                                                   c_out, c_out, c_in, n * c_in, bytes, s, 0, 27, c_out, -per_tap, L->dnbr_t,
-                                                  skip ? L->dorder : nullptr, skip ? L->dtilemask : nullptr);
+                                                  skip ? L->dorder : nullptr, skip ? L->dtilemask : nullptr, n);
             if (st != HCH_OK) return st;
             if (p.splits > 1) st = launch_reduce(part, dX, n * c_in, p.splits, s);
             return st;
@@ -1498,7 +1543,7 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
         st = launch_gemm<hch::A_GATHER, false>(dtype, p, dY, Wt,
                                                p.splits > 1 ? part : dX, L->dnbr, (int)n, c_in, Kd, c_out,
                                                c_in, c_in, n * c_in, bytes, s, 0, 27, 0, 0, L->dnbr_t,
-                                               skip ? L->dorder : nullptr, skip ? L->dtilemask : nullptr);
+                                               skip ? L->dorder : nullptr, skip ? L->dtilemask : nullptr, n);
         if (st != HCH_OK) return st;
         if (p.splits > 1) st = launch_reduce(part, dX, n * c_in, p.splits, s);
         return st;
@@ -1548,7 +1593,8 @@ static hch_status conv_bwd_weight_impl(const hch_levels *levels, int32_t level, 
     if (algo == HCH_ALGO_FUSED) {
         const double bytes = (double)n * (108.0 + es * c_in + es * c_out) + 4.0 * wsize * p.splits;
         st = launch_gemm<hch::A_GATHER_T, false>(dtype, p, X, dY, dst,
-                                                 L->dnbr, Kc, c_out, (int)n, c_in, c_out, c_out, wsize, bytes, s, 0, 27, 0, 0, L->dnbr_t);
+                                                 L->dnbr, Kc, c_out, (int)n, c_in, c_out, c_out, wsize, bytes, s, 0, 27, 0, 0, L->dnbr_t,
+                                                 nullptr, nullptr, n);
     } else {
         void *col = workspace;
         if (!resident) {

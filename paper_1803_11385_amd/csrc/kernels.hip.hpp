@@ -662,7 +662,7 @@ template <> struct FVec<4> { typedef float type __attribute__((ext_vector_type(4
 template <int N> __device__ __forceinline__ float vget(const typename FVec<N>::type &v, int i) { return v[i]; }
 template <> __device__ __forceinline__ float vget<1>(const float &v, int) { return v; }
 
-template <typename TIN, int BM, int BN, int BK, int WM, int AMODE, bool B_KC, bool VEC, bool C_PLANES, bool SKIP = false>
+template <typename TIN, int BM, int BN, int BK, int WM, int AMODE, bool B_KC, bool VEC, bool C_PLANES, bool SKIP = false, bool LEAN = false>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(
     const TIN *__restrict__ A, const TIN *__restrict__ B, float *__restrict__ C,
     const int32_t *__restrict__ nbr, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
@@ -739,11 +739,19 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     __shared__ int32_t rowtile[SKIP ? BM : 1];        // the voxels behind this tile's rows
     int kbeg = (int)slice * k_per_split;
     int kend = min(K, kbeg + k_per_split);
+    uint32_t present = taps >= 32 ? 0xFFFFFFFFu : (1u << taps) - 1u;     // taps of the reduction, as a bit set
     if constexpr (SKIP) {
         const unsigned t64 = mtile * (BM / 64), n64 = (unsigned)((M + 63) / 64);
-        uint32_t present = tilemask[t64];
+        present = tilemask[t64];
         if (BM == 128 && t64 + 1 < n64) present |= tilemask[t64 + 1];
-        if (tid < 27 && ((present >> tid) & 1u)) tapmap[__popc(present & ((1u << tid) - 1u))] = (uint8_t)tid;
+        present = (uint32_t)__builtin_amdgcn_readfirstlane((int)present);    // the same for every lane: keep it scalar
+        if (tid < 32) {
+            // entry j: the j-th present tap; entries past the last one name tap 0, so that an
+            // index load for a reduction offset past the end still reads inside the index rows
+            uint32_t m = present;
+            for (int q = 0; q < tid && m; ++q) m &= m - 1u;
+            tapmap[tid] = m ? (uint8_t)(__ffs(m) - 1) : (uint8_t)0;
+        }
         if (tid < BM) rowtile[tid] = m0 + tid < M ? rowmap[m0 + tid] : 0;
         const int Kp = __popc(present) * c;
         const int per = ((Kp + (int)n_slices - 1) / (int)n_slices + BK - 1) / BK * BK;
@@ -798,15 +806,15 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
             if (AMODE == A_COLS) { a_ok[uu] = m0 + a_col < M; pa[uu] = A + (int64_t)(kbeg + r) * lda + m0 + a_col; }
             if (AMODE == A_GATHER) {
                 a_ok[uu] = m0 + r < M;
-                int64_t vox = m0 + r;
+                int64_t vox = min(m0 + r, M - 1);     // index loads are unconditional: stay inside
                 if constexpr (SKIP) vox = rowtile[r];
                 pn[uu] = nbr + vox * taps;
             }
             if (AMODE == A_GATHER_T) {
                 const int gi = m0 + a_col;
-                const int tap = gi / c;
-                cc_a = gi - tap * c;
-                a_ok[uu] = gi < M; pn[uu] = nbr + (int64_t)(kbeg + r) * taps + tap;
+                const int tap = min(gi / c, taps - 1);
+                cc_a = gi - (gi / c) * c;
+                a_ok[uu] = gi < M; pn[uu] = nbr + tap;
             }
         }
     }
@@ -842,19 +850,149 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
         }
     }
 
+    // ---- LEAN (float operands, vector path, gather modes; A_GATHER: c a multiple of BK, so that a
+    // tile lies within one tap).  A vector-ALU instruction and a matrix instruction of the same
+    // SIMD do not overlap on this chip: every address computation in the loop costs matrix time,
+    // 4 cycles of the 32 one instruction takes.  Here the loop computes next to nothing per lane:
+    // loads go through buffer descriptors, whose range check returns zeros for anything outside
+    // (no guards, no 64-bit pointers); what a tile changes is a scalar offset kept by the scalar
+    // unit (the tap, the channel block, the row of the weights); per lane there remains one
+    // multiply-add per gathered row -- its index times the row length.
+    // Rules kept below: a scalar offset never leaves its buffer (taps are clamped to present
+    // ones), so only the per-lane offset decides inside/outside; an absent neighbour (-1) gives a
+    // negative, i.e. huge unsigned, per-lane offset.  Values a load past the end of a reduction
+    // slice brings in are multiplied by zeros of the other operand or never multiplied.
+    [[maybe_unused]] __amdgpu_buffer_rsrc_t rs_idx, rs_a, rs_b;
+    [[maybe_unused]] int lv_idx[A_UNITS], lv_b[B_UNITS], lv_a = 0;     // per-lane byte offsets
+    [[maybe_unused]] uint32_t rem_i = 0, rem_b = 0;                    // taps still ahead: index / B stream
+    [[maybe_unused]] int cc_i = 0, cc_r = 0, cc_b = 0;                 // channel block within the tap, per stream
+    [[maybe_unused]] int64_t b_tap_lo = 0;
+    constexpr uint32_t LEAN_OUT = 0x80000000u;                          // a per-lane offset outside every buffer
+    if constexpr (LEAN) {
+        static_assert(VEC && GATHER && !C_PLANES && sizeof(TIN) == 4, "lean loop: float gathers on the vector path");
+        constexpr int SRD3 = 0x00020000;                               // raw buffer of dwords, gfx9 family
+        const int rowbytes = c * 4;
+        rs_a = __builtin_amdgcn_make_buffer_rsrc((void *)A, 0, (int)0x80000000u, SRD3);
+        if (AMODE == A_GATHER) {
+            // skip the taps before this slice's first tile
+            const int t0 = kbeg / c;
+            uint32_t m = present;
+            for (int q = 0; q < t0 && m; ++q) m &= m - 1u;
+            rem_i = rem_b = m;
+            cc_i = cc_r = cc_b = kbeg - t0 * c;
+            rs_idx = __builtin_amdgcn_make_buffer_rsrc((void *)nbr, 0, M * taps * 4, SRD3);
+            lv_a = a_col * 4;
+#pragma unroll
+            for (int uu = 0; uu < A_UNITS; ++uu) {
+                const int r = a_row0 + uu * A_RSTEP;
+                int vox = m0 + r;
+                if constexpr (SKIP) vox = rowtile[r];
+                lv_idx[uu] = m0 + r < M ? vox * taps * 4 : (int)LEAN_OUT;
+            }
+            if (B_KC) {
+                // B(k, j) = B[(k / c)*b_tap_stride + j*ldb + k % c]; with a negative tap stride the
+                // buffer starts at the last tap
+                b_tap_lo = b_tap_stride < 0 ? (int64_t)(taps - 1) * b_tap_stride : 0;
+                rs_b = __builtin_amdgcn_make_buffer_rsrc((void *)(B + b_tap_lo), 0,
+                                                         (int)(((int64_t)(taps - 1) * (b_tap_stride < 0 ? -b_tap_stride : b_tap_stride) + (int64_t)N * ldb) * 4), SRD3);
+#pragma unroll
+                for (int uu = 0; uu < B_UNITS; ++uu) {
+                    const int r = b_row0 + uu * B_RSTEP;
+                    lv_b[uu] = (r < BN && n0 + r < N) ? (int)(((int64_t)(n0 + r) * ldb + b_col) * 4) : (int)LEAN_OUT;
+                }
+            } else {
+                rs_b = __builtin_amdgcn_make_buffer_rsrc((void *)B, 0, (int)((int64_t)taps * c * ldb * 4), SRD3);
+#pragma unroll
+                for (int uu = 0; uu < B_UNITS; ++uu) {
+                    const int r = b_row0 + uu * B_RSTEP;
+                    lv_b[uu] = (r < BK && n0 + b_col < N) ? (int)(((int64_t)r * ldb + n0 + b_col) * 4) : (int)LEAN_OUT;
+                }
+            }
+        } else {
+            // A_GATHER_T: the reduction runs over the voxels of this slice; both the index rows and
+            // B are described from the slice's first voxel to its last, so the tail reads zeros
+            const int len = max(kend - kbeg, 0);
+            rs_idx = __builtin_amdgcn_make_buffer_rsrc((void *)(nbr + (int64_t)kbeg * taps), 0, len * taps * 4, SRD3);
+            rs_b = __builtin_amdgcn_make_buffer_rsrc((void *)(B + (int64_t)kbeg * ldb), 0, (int)((int64_t)len * ldb * 4), SRD3);
+            const int gi = m0 + a_col;
+            const int tap = min(gi / c, taps - 1);
+            lv_a = (gi - (gi / c) * c) * 4;
+#pragma unroll
+            for (int uu = 0; uu < A_UNITS; ++uu) lv_idx[uu] = ((a_row0 + uu * A_RSTEP) * taps + tap) * 4;
+#pragma unroll
+            for (int uu = 0; uu < B_UNITS; ++uu) {
+                const int r = b_row0 + uu * B_RSTEP;
+                lv_b[uu] = (r < BK && n0 + b_col < N) ? (int)(((int64_t)r * ldb + n0 + b_col) * 4) : (int)LEAN_OUT;
+            }
+        }
+        (void)rowbytes;
+    }
+    auto lean_tap = [&](uint32_t rem) { return rem ? __builtin_ctz(rem) : 0; };   // clamped: never outside
+    auto lean_fetch_idx = [&](int32_t *out) {
+        if constexpr (LEAN) {
+            const int soff = AMODE == A_GATHER ? __builtin_amdgcn_readfirstlane(lean_tap(rem_i) * 4) : 0;
+#pragma unroll
+            for (int uu = 0; uu < A_UNITS; ++uu) {
+                out[uu] = (int32_t)__builtin_amdgcn_raw_buffer_load_b32(rs_idx, lv_idx[uu], soff, 0);
+                if (AMODE == A_GATHER_T) lv_idx[uu] += BK * taps * 4;
+            }
+            if (AMODE == A_GATHER) {
+                cc_i += BK;
+                if (cc_i >= c) { cc_i = 0; rem_i &= rem_i - 1u; }
+            }
+        }
+    };
+    auto lean_fetch = [&](const int32_t *rows, f32x4 *ra, f32x4 *rb) {
+        if constexpr (LEAN) {
+            const int rowbytes = c * 4;
+            const int soff_a = AMODE == A_GATHER ? __builtin_amdgcn_readfirstlane(cc_r * 4) : 0;
+#pragma unroll
+            for (int uu = 0; uu < A_UNITS; ++uu) {
+                // index -1: a negative offset, outside the buffer, zeros
+                const int off = __mul24(rows[uu], rowbytes) + lv_a;
+                ra[uu] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs_a, off, soff_a, 0));
+            }
+            int soff_b = 0;
+            if (AMODE == A_GATHER) {
+                const int tap = lean_tap(rem_b);
+                if (B_KC) soff_b = (int)(((int64_t)tap * b_tap_stride - b_tap_lo + cc_b) * 4);
+                else soff_b = (tap * c + cc_b) * (int)ldb * 4;
+                soff_b = __builtin_amdgcn_readfirstlane(soff_b);
+            }
+#pragma unroll
+            for (int uu = 0; uu < B_UNITS; ++uu) {
+                rb[uu] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs_b, lv_b[uu], soff_b, 0));
+                if (AMODE == A_GATHER_T) lv_b[uu] += BK * (int)ldb * 4;
+            }
+            if (AMODE == A_GATHER) {
+                cc_r += BK; if (cc_r >= c) cc_r = 0;
+                cc_b += BK; if (cc_b >= c) { cc_b = 0; rem_b &= rem_b - 1u; }
+            }
+        }
+    };
+
     // Gather modes, stage 1: the index of the feature row behind each unit of the next tile
     // (-1 = nothing to load).  Issued ahead of the dependent row loads of stage 2.
     auto fetch_idx = [&](int32_t *out) {
         if (!GATHER || !VEC) return;
+        if constexpr (LEAN) { lean_fetch_idx(out); return; }
+        // The load itself is unconditional and always inside the index rows (rows and voxels
+        // clamped, tap columns valid); what lies outside the product becomes -1 afterwards.  With
+        // the choice made on the address instead, the compiler put each load behind a branch.
 #pragma unroll
         for (int uu = 0; uu < A_UNITS; ++uu) {
-            bool ok;
-            if (AMODE == A_GATHER) ok = a_ok[uu] && kn + a_col < kend;
-            else ok = a_ok[uu] && kn + a_row0 + uu * A_RSTEP < kend;
-            int tap_col = AMODE == A_GATHER ? tap_n : 0;
-            if constexpr (SKIP) tap_col = tapmap[min(tap_n, 31)];
-            out[uu] = *(ok ? pn[uu] + tap_col : &g_minus1);
-            if (AMODE == A_GATHER_T) pn[uu] += BK * taps;
+            if (AMODE == A_GATHER) {
+                const bool ok = a_ok[uu] && kn + a_col < kend;
+                int tap_col = min(tap_n, taps - 1);
+                if constexpr (SKIP) tap_col = tapmap[min(tap_n, 31)];
+                const int32_t j = pn[uu][tap_col];
+                out[uu] = ok ? j : -1;
+            } else {
+                const int kv = kn + a_row0 + uu * A_RSTEP;
+                const bool ok = a_ok[uu] && kv < kend;
+                const int32_t j = pn[uu][(int64_t)min(kv, K - 1) * taps];
+                out[uu] = ok ? j : -1;
+            }
         }
         if (AMODE == A_GATHER) {
             tap_n += dtap; cc_n += dcc;
@@ -868,6 +1006,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     // stage 2: the next tile into registers (zero outside the matrices); `rows` = the indices
     // stage 1 produced for this tile.  The generic path takes the tile's reduction index k0.
     auto fetch = [&](int k0, const int32_t *rows, f32x4 *ra, f32x4 *rb) {
+        if constexpr (LEAN) { lean_fetch(rows, ra, rb); return; }
         if (VEC) {
 #pragma unroll
             for (int uu = 0; uu < A_UNITS; ++uu) {
@@ -965,15 +1104,16 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
 #pragma unroll
         for (int uu = 0; uu < A_UNITS; ++uu)
             *reinterpret_cast<f32x4 *>(&As[(a_row0 + uu * A_RSTEP) * AS + a_col]) = ra[uu];
+        constexpr bool B_EVEN = (B_TOTAL % 256 == 0);     // every thread holds B_UNITS units of the tile
 #pragma unroll
         for (int uu = 0; uu < B_UNITS; ++uu) {
             const int r = b_row0 + uu * B_RSTEP;
             if (B_KC) {
-                if (r < BN) {
+                if (B_EVEN || r < BN) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) Bs[(b_col + e) * BS + r] = rb[uu][e];
                 }
-            } else if (r < BK) {
+            } else if (B_EVEN || r < BK) {
                 *reinterpret_cast<f32x4 *>(&Bs[r * BS + b_col]) = rb[uu];
             }
         }
@@ -1033,38 +1173,44 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     // Software pipeline over the tiles t = 0, 1, ... of this workgroup's reduction range, one
     // barrier per tile:
     //   iteration t:  operands of t: LDS stage t%2 -> registers;  MFMAs of t;
-    //                 registers(t+1) -> LDS stage (t+1)%2;  issue index loads of t+3, row loads of t+2;
-    //                 barrier.
-    // The two index register sets alternate (no copies, so nothing waits on an index load before
-    // the row loads that need it).
-    f32x4 ra[A_UNITS], rb[B_UNITS];
+    //                 registers(t+1) -> LDS stage (t+1)%2;  issue index loads of t+4, row loads of
+    //                 t+3 into the register set just emptied;  barrier.
+    // Loads are two tiles ahead of their use: a gathered row takes about as long to arrive as one
+    // iteration lasts, and with one tile of lead the store to LDS kept waiting for it.  The two
+    // register sets and the two index sets alternate (no copies).
+    // Nothing in the loop body is conditional: every load is guarded on its own (zeros past the
+    // end of the range), and with a fetch that some path skips the compiler must assume the
+    // registers it stores to LDS were loaded last, and waits for ALL outstanding loads there --
+    // which undoes the lead.  Tiles go in pairs (one per stage); an odd last tile follows the loop.
+    f32x4 ra0[A_UNITS], rb0[B_UNITS], ra1[A_UNITS], rb1[B_UNITS];
     int32_t rx[A_UNITS] = {}, ry[A_UNITS] = {};
-    auto iteration = [&](int k0, int stage, int32_t *use, int32_t *load) {
+    auto iteration = [&](int k0, int stage, f32x4 *sa, f32x4 *sb, int32_t *use, int32_t *load) {
         load_operands(stage);
         multiply();
-        if (k0 + BK < kend) {
-            stash(stage ^ 1, ra, rb);
-            if (k0 + 2 * BK < kend) {
-                fetch_idx(load);
-                fetch(k0 + 2 * BK, use, ra, rb);
-            }
-        }
+        stash(stage ^ 1, sa, sb);
+        fetch_idx(load);
+        fetch(k0 + 3 * BK, use, sa, sb);
         __syncthreads();
     };
     if (kbeg < kend) {
-        fetch_idx(ry);
-        fetch(kbeg, ry, ra, rb);
         fetch_idx(rx);
-        stash(0, ra, rb);
-        if (kbeg + BK < kend) {
-            fetch_idx(ry);
-            fetch(kbeg + BK, rx, ra, rb);
-        }
+        fetch(kbeg, rx, ra0, rb0);
+        fetch_idx(ry);
+        fetch(kbeg + BK, ry, ra1, rb1);
+        stash(0, ra0, rb0);
+        fetch_idx(rx);
+        fetch_idx(ry);                         // before the rows of tile 2, as in the loop: the
+        fetch(kbeg + 2 * BK, rx, ra0, rb0);    // waits there count the loads issued after it
         __syncthreads();
-    }
-    for (int k0 = kbeg; k0 < kend; k0 += 2 * BK) {
-        iteration(k0, 0, ry, rx);
-        if (k0 + BK < kend) iteration(k0 + BK, 1, rx, ry);
+        int k0 = kbeg;
+        for (; k0 + BK < kend; k0 += 2 * BK) {
+            iteration(k0, 0, ra1, rb1, ry, rx);
+            iteration(k0 + BK, 1, ra0, rb0, rx, ry);
+        }
+        if (k0 < kend) {
+            load_operands(0);
+            multiply();
+        }
     }
 
     // D layout of v_mfma_f32_16x16x4_f32: register e of lane l holds D[4*(l/16) + e][l%16].
