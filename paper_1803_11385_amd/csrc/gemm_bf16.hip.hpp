@@ -32,7 +32,7 @@ constexpr int BF16_BK = 64;   // reduction indices per tile = granularity of spl
 // 16-byte aligned and wholly inside or outside its matrix (lda, ldb, c multiples of 8; K, M or N
 // multiples of 8 where they bound a fast axis); k_per_split and b_wrap multiples of 64.
 // Units outside read a constant block of zeros; an absent neighbour (-1) likewise.
-template <int BM, int BN, int WM, int AMODE, bool B_KC>
+template <int BM, int BN, int WM, int AMODE, bool B_KC, bool LEAN = false>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, float *__restrict__ C,
     const int32_t *__restrict__ nbr, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
@@ -154,6 +154,100 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
             pb[uu] = B + (int64_t)(kbeg + b_r + uu) * ldb + n0 + b_c;
         }
     }
+    // ---- LEAN (gather modes; A_GATHER: c a multiple of 64, a tile lies within one tap): as in
+    // gemm_f32_kernel, loads through buffer descriptors with scalar offsets for what a tile
+    // changes and one multiply-add per gathered row and lane.  Here a matrix instruction takes 16
+    // cycles, so every vector instruction in the loop costs a quarter of one.
+    [[maybe_unused]] __amdgpu_buffer_rsrc_t rs_idx, rs_a, rs_b;
+    [[maybe_unused]] int lv_idx[A_UNITS], lv_b[B_UNITS], lv_a = 0;
+    [[maybe_unused]] int tap_i = 0, tap_bb = 0, cc_i = 0, cc_r = 0, cc_b = 0;
+    [[maybe_unused]] int64_t b_tap_lo = 0;
+    constexpr int LEAN_TAPS = 27;
+    constexpr uint32_t LEAN_OUT = 0x80000000u;
+    if constexpr (LEAN) {
+        static_assert(GATHER, "lean loop: gather modes");
+        constexpr int SRD3 = 0x00020000;
+        rs_a = __builtin_amdgcn_make_buffer_rsrc((void *)A, 0, (int)0x80000000u, SRD3);
+        if (AMODE == A_GATHER) {
+            tap_i = tap_bb = kbeg / c;
+            cc_i = cc_r = cc_b = kbeg - tap_i * c;
+            rs_idx = __builtin_amdgcn_make_buffer_rsrc((void *)nbr, 0, M * LEAN_TAPS * 4, SRD3);
+            lv_a = a_c * 2;
+#pragma unroll
+            for (int uu = 0; uu < A_UNITS; ++uu) {
+                const int r = m0 + a_r + 32 * uu;
+                lv_idx[uu] = r < M ? (int)((int64_t)r * idx_row_stride * 4) : (int)LEAN_OUT;
+            }
+            if (B_KC) {
+                b_tap_lo = b_tap_stride < 0 ? (int64_t)(LEAN_TAPS - 1) * b_tap_stride : 0;
+                rs_b = __builtin_amdgcn_make_buffer_rsrc((void *)(B + b_tap_lo), 0,
+                                                         (int)(((int64_t)(LEAN_TAPS - 1) * (b_tap_stride < 0 ? -b_tap_stride : b_tap_stride) + (int64_t)N * ldb) * 2), SRD3);
+#pragma unroll
+                for (int uu = 0; uu < B_UNITS; ++uu) {
+                    const int r = b_r + 32 * uu;
+                    lv_b[uu] = (r < BN && n0 + r < N) ? (int)(((int64_t)(n0 + r) * ldb + b_c) * 2) : (int)LEAN_OUT;
+                }
+            } else {
+                rs_b = __builtin_amdgcn_make_buffer_rsrc((void *)B, 0, (int)((int64_t)LEAN_TAPS * c * ldb * 2), SRD3);
+#pragma unroll
+                for (int uu = 0; uu < B_UNITS; ++uu)
+                    lv_b[uu] = (b_c < BN && n0 + b_c < N) ? (int)(((int64_t)(b_r + uu) * ldb + n0 + b_c) * 2) : (int)LEAN_OUT;
+            }
+        } else {
+            // A_GATHER_T: reduction over the voxels kbeg .. kend of this slice.  B is described from
+            // the slice's first row to its last: past the end it reads zeros, which is what makes
+            // the tail of the last tile vanish (the rows gathered there are real, finite data).
+            const int len = max(kend - kbeg, 0);
+            rs_idx = __builtin_amdgcn_make_buffer_rsrc((void *)nbr, 0, K * LEAN_TAPS * 4, SRD3);
+            rs_b = __builtin_amdgcn_make_buffer_rsrc((void *)(B + (int64_t)kbeg * ldb), 0, (int)((int64_t)len * ldb * 2), SRD3);
+            const int gi = m0 + a_c;
+            const int tap = min(gi / c, LEAN_TAPS - 1);
+            lv_a = (gi - (gi / c) * c) * 2;
+#pragma unroll
+            for (int uu = 0; uu < A_UNITS; ++uu)
+                lv_idx[uu] = (int)(((int64_t)(kbeg + a_r + uu) * idx_row_stride + (int64_t)tap * idx_tap_stride) * 4);
+#pragma unroll
+            for (int uu = 0; uu < B_UNITS; ++uu)
+                lv_b[uu] = (b_c < BN && n0 + b_c < N) ? (int)(((int64_t)(b_r + uu) * ldb + n0 + b_c) * 2) : (int)LEAN_OUT;
+        }
+    }
+    auto lean_fetch_idx = [&](int32_t *out) {
+        if constexpr (LEAN) {
+            const int soff = AMODE == A_GATHER ? __builtin_amdgcn_readfirstlane((int)((int64_t)min(tap_i, LEAN_TAPS - 1) * idx_tap_stride * 4)) : 0;
+#pragma unroll
+            for (int uu = 0; uu < A_UNITS; ++uu) {
+                out[uu] = (int32_t)__builtin_amdgcn_raw_buffer_load_b32(rs_idx, lv_idx[uu], soff, 0);
+                if (AMODE == A_GATHER_T) lv_idx[uu] += (int)(BK * idx_row_stride * 4);
+            }
+            if (AMODE == A_GATHER) { cc_i += BK; if (cc_i >= c) { cc_i = 0; ++tap_i; } }
+        }
+    };
+    auto lean_fetch = [&](const int32_t *rows, u32x4 *ra, u32x4 *rb) {
+        if constexpr (LEAN) {
+            const int rowbytes = c * 2;
+            const int soff_a = AMODE == A_GATHER ? __builtin_amdgcn_readfirstlane(cc_r * 2) : 0;
+#pragma unroll
+            for (int uu = 0; uu < A_UNITS; ++uu)
+                ra[uu] = __builtin_amdgcn_raw_buffer_load_b128(rs_a, __mul24(rows[uu], rowbytes) + lv_a, soff_a, 0);
+            int soff_b = 0;
+            if (AMODE == A_GATHER) {
+                const int tap = min(tap_bb, LEAN_TAPS - 1);
+                if (B_KC) soff_b = (int)(((int64_t)tap * b_tap_stride - b_tap_lo + cc_b) * 2);
+                else soff_b = (tap * c + cc_b) * (int)ldb * 2;
+                soff_b = __builtin_amdgcn_readfirstlane(soff_b);
+            }
+#pragma unroll
+            for (int uu = 0; uu < B_UNITS; ++uu) {
+                rb[uu] = __builtin_amdgcn_raw_buffer_load_b128(rs_b, lv_b[uu], soff_b, 0);
+                if (AMODE == A_GATHER_T) lv_b[uu] += BK * (int)ldb * 2;
+            }
+            if (AMODE == A_GATHER) {
+                cc_r += BK; if (cc_r >= c) cc_r = 0;
+                cc_b += BK; if (cc_b >= c) { cc_b = 0; ++tap_bb; }
+            }
+        }
+    };
+
     // LDS row of column j of the tile: the NT MFMA tiles of a wave take interleaved columns
     // (tile nt: columns li*NT + nt of the wave's stretch, so that a lane ends up with NT
     // neighbouring outputs), stored tile after tile so that 16 lanes read 16 consecutive rows
@@ -164,6 +258,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
 
     auto fetch_idx = [&](int32_t *out) {
         if (!GATHER) return;
+        if constexpr (LEAN) { lean_fetch_idx(out); return; }
 #pragma unroll
         for (int uu = 0; uu < A_UNITS; ++uu) {
             bool ok;
@@ -180,6 +275,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     };
 
     auto fetch = [&](const int32_t *rows, u32x4 *ra, u32x4 *rb) {
+        if constexpr (LEAN) { lean_fetch(rows, ra, rb); return; }
 #pragma unroll
         for (int uu = 0; uu < A_UNITS; ++uu) {
             const uint16_t *src;
@@ -275,36 +371,41 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
                         __builtin_bit_cast(bf16x8, oa[ks][mt]), __builtin_bit_cast(bf16x8, ob[ks][nt]), acc[mt][nt], 0, 0, 0);
     };
 
-    // software pipeline as in gemm_f32_kernel: one barrier per tile, registers one tile ahead of
-    // LDS, index loads one tile ahead of the row loads that need them
-    u32x4 ra[A_UNITS], rb[B_UNITS];
+    // software pipeline as in gemm_f32_kernel: one barrier per tile; loads two tiles ahead of the
+    // store to LDS that needs them (two register sets and two index sets that alternate); nothing
+    // in the loop body is conditional -- every load is guarded on its own and reads zeros past the
+    // end of the range -- so that the compiler's wait before a store to LDS covers the loads of
+    // that register set only.  Tiles go in pairs; an odd last tile follows the loop.
+    u32x4 ra0[A_UNITS], rb0[B_UNITS], ra1[A_UNITS], rb1[B_UNITS];
     int32_t rx[A_UNITS] = {}, ry[A_UNITS] = {};
-    auto iteration = [&](int k0, int stage, int32_t *use, int32_t *load) {
+    auto iteration = [&](int stage, u32x4 *sa, u32x4 *sb, int32_t *use, int32_t *load) {
         load_operands(stage);
         multiply();
-        if (k0 + BK < kend) {
-            stash(stage ^ 1, ra, rb);
-            if (k0 + 2 * BK < kend) {
-                fetch_idx(load);
-                fetch(use, ra, rb);
-            }
-        }
+        stash(stage ^ 1, sa, sb);
+        fetch_idx(load);
+        fetch(use, sa, sb);
         __syncthreads();
     };
     if (kbeg < kend) {
-        fetch_idx(ry);
-        fetch(ry, ra, rb);
+        int32_t rz[A_UNITS] = {};
         fetch_idx(rx);
-        stash(0, ra, rb);
-        if (kbeg + BK < kend) {
-            fetch_idx(ry);
-            fetch(rx, ra, rb);
-        }
+        fetch_idx(ry);
+        fetch_idx(rz);
+        fetch(rx, ra0, rb0);
+        fetch(ry, ra1, rb1);
+        stash(0, ra0, rb0);
+        fetch_idx(ry);
+        fetch(rz, ra0, rb0);
         __syncthreads();
-    }
-    for (int k0 = kbeg; k0 < kend; k0 += 2 * BK) {
-        iteration(k0, 0, ry, rx);
-        if (k0 + BK < kend) iteration(k0 + BK, 1, rx, ry);
+        int k0 = kbeg;
+        for (; k0 + BK < kend; k0 += 2 * BK) {
+            iteration(0, ra1, rb1, ry, rx);
+            iteration(1, ra0, rb0, rx, ry);
+        }
+        if (k0 < kend) {
+            load_operands(0);
+            multiply();
+        }
     }
 
     // D layout (as for every 16x16 fp32 result): register e of lane l holds D[4*(l/16) + e][l%16];

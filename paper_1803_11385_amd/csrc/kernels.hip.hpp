@@ -1193,14 +1193,19 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
         __syncthreads();
     };
     if (kbeg < kend) {
+        // start-up: the indices of tiles 0, 1, 2 are requested together and the rows of the three
+        // tiles after them, two memory latencies instead of one per tile; the order of the last
+        // requests (indices of tile 3, then rows of tile 2) is the loop's, whose waits count the
+        // loads issued after the one they need
+        int32_t rz[A_UNITS] = {};
         fetch_idx(rx);
-        fetch(kbeg, rx, ra0, rb0);
         fetch_idx(ry);
+        fetch_idx(rz);
+        fetch(kbeg, rx, ra0, rb0);
         fetch(kbeg + BK, ry, ra1, rb1);
         stash(0, ra0, rb0);
-        fetch_idx(rx);
-        fetch_idx(ry);                         // before the rows of tile 2, as in the loop: the
-        fetch(kbeg + 2 * BK, rx, ra0, rb0);    // waits there count the loads issued after it
+        fetch_idx(ry);
+        fetch(kbeg + 2 * BK, rz, ra0, rb0);
         __syncthreads();
         int k0 = kbeg;
         for (; k0 + BK < kend; k0 += 2 * BK) {
