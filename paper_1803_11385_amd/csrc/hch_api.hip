@@ -1052,18 +1052,30 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
     // operands stay below 2 GiB each, so that 32-bit byte offsets reach everything and a negative
     // offset is out of range; row indices must fit the 24-bit multiply.  Gathering along the
     // reduction axis a tile must lie within one tap (rows of a multiple of 32 channels).
-    constexpr bool lean_mode = (AMODE == hch::A_GATHER || (AMODE == hch::A_GATHER_T && !B_KC)) && sizeof(TIN) == 4;
+    constexpr bool gather_mode = (AMODE == hch::A_GATHER || AMODE == hch::A_GATHER_T);
+    constexpr bool lean_mode = (AMODE == hch::A_GATHER || AMODE == hch::A_ROWS || ((AMODE == hch::A_GATHER_T || AMODE == hch::A_COLS) && !B_KC)) &&
+                               sizeof(TIN) == 4;
     bool lean = false;
     if constexpr (lean_mode) {
         const int64_t lim = (int64_t)1 << 31;
-        const int64_t idx_rows = AMODE == hch::A_GATHER ? M : K;
-        int64_t b_bytes;
-        if (AMODE == hch::A_GATHER_T) b_bytes = (int64_t)K * ldb * 4;
-        else if (B_KC) b_bytes = ((int64_t)(taps - 1) * (b_tap_stride < 0 ? -b_tap_stride : b_tap_stride) + (int64_t)N * ldb) * 4;
-        else b_bytes = (int64_t)taps * lda * ldb * 4;
-        lean = vec && c_planes == 0 && taps == 27 && nbr && a_rows > 0 && a_rows < ((int64_t)1 << 23) && lda * 4 < ((int64_t)1 << 23) &&
-               a_rows * lda * 4 < lim && idx_rows * taps * 4 < lim && b_bytes < lim &&
-               (AMODE == hch::A_GATHER_T || (lda % 32 == 0 && (B_KC ? b_wrap == (int)lda : b_wrap == 0)));
+        if constexpr (gather_mode) {
+            const int64_t idx_rows = AMODE == hch::A_GATHER ? M : K;
+            int64_t b_bytes;
+            if (AMODE == hch::A_GATHER_T) b_bytes = (int64_t)K * ldb * 4;
+            else if (B_KC) b_bytes = ((int64_t)(taps - 1) * (b_tap_stride < 0 ? -b_tap_stride : b_tap_stride) + (int64_t)N * ldb) * 4;
+            else b_bytes = (int64_t)taps * lda * ldb * 4;
+            lean = vec && c_planes == 0 && taps == 27 && nbr && a_rows > 0 && a_rows < ((int64_t)1 << 23) && lda * 4 < ((int64_t)1 << 23) &&
+                   a_rows * lda * 4 < lim && idx_rows * taps * 4 < lim && b_bytes < lim &&
+                   (AMODE == hch::A_GATHER_T || (lda % 32 == 0 && (B_KC ? b_wrap == (int)lda : b_wrap == 0)));
+        } else {
+            // plain operands (the products of the columns algorithm): row-major A needs whole tiles,
+            // K and the slices multiples of 32; k-major A and B may end anywhere (their buffers are
+            // described slice by slice)
+            const int64_t a_bytes = (int64_t)(AMODE == hch::A_ROWS ? M : K) * lda * 4;
+            const int64_t b_bytes = (int64_t)(B_KC ? N : K) * ldb * 4;
+            lean = vec && c_planes == 0 && b_wrap == 0 && a_bytes < lim && b_bytes < lim &&
+                   (AMODE == hch::A_COLS || (K % 32 == 0 && (p.splits == 1 || p.k_per_split % 32 == 0)));
+        }
     }
     const int ln = lean ? 1 : 0;
     if (ids[ln][pl][v][cfg] < 0) {

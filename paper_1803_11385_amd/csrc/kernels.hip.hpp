@@ -867,9 +867,11 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     [[maybe_unused]] uint32_t rem_i = 0, rem_b = 0;                    // taps still ahead: index / B stream
     [[maybe_unused]] int cc_i = 0, cc_r = 0, cc_b = 0;                 // channel block within the tap, per stream
     [[maybe_unused]] int64_t b_tap_lo = 0;
+    [[maybe_unused]] int lv_au[A_UNITS];                               // per-lane byte offsets of A without a gather
+    [[maybe_unused]] int k_lean = 0, k_last = 0;                       // A_ROWS: next tile's first k, the last real tile's
     constexpr uint32_t LEAN_OUT = 0x80000000u;                          // a per-lane offset outside every buffer
     if constexpr (LEAN) {
-        static_assert(VEC && GATHER && !C_PLANES && sizeof(TIN) == 4, "lean loop: float gathers on the vector path");
+        static_assert(VEC && !C_PLANES && sizeof(TIN) == 4, "lean loop: float operands on the vector path");
         constexpr int SRD3 = 0x00020000;                               // raw buffer of dwords, gfx9 family
         const int rowbytes = c * 4;
         rs_a = __builtin_amdgcn_make_buffer_rsrc((void *)A, 0, (int)0x80000000u, SRD3);
@@ -908,6 +910,40 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
                     lv_b[uu] = (r < BK && n0 + b_col < N) ? (int)(((int64_t)r * ldb + n0 + b_col) * 4) : (int)LEAN_OUT;
                 }
             }
+        } else if (AMODE == A_ROWS) {
+            // plain row-major A (the column matrix, or dY): the reduction offset is a scalar.  The
+            // host guarantees whole tiles (K and the slices multiples of BK); a tile past the end
+            // of the range, which the pipeline requests and never multiplies, re-reads the last one.
+            rs_a = __builtin_amdgcn_make_buffer_rsrc((void *)A, 0, (int)((int64_t)M * lda * 4), SRD3);
+            k_lean = kbeg;
+            k_last = kbeg + max(0, (kend - kbeg - 1) / BK) * BK;
+#pragma unroll
+            for (int uu = 0; uu < A_UNITS; ++uu) {
+                const int r = a_row0 + uu * A_RSTEP;
+                lv_au[uu] = m0 + r < M ? (int)(((int64_t)(m0 + r) * lda + a_col) * 4) : (int)LEAN_OUT;
+            }
+            rs_b = __builtin_amdgcn_make_buffer_rsrc((void *)B, 0, (int)((int64_t)(B_KC ? N : K) * ldb * 4), SRD3);
+#pragma unroll
+            for (int uu = 0; uu < B_UNITS; ++uu) {
+                const int r = b_row0 + uu * B_RSTEP;
+                if (B_KC) lv_b[uu] = (r < BN && n0 + r < N) ? (int)(((int64_t)(n0 + r) * ldb + b_col) * 4) : (int)LEAN_OUT;
+                else lv_b[uu] = (r < BK && n0 + b_col < N) ? (int)(((int64_t)r * ldb + n0 + b_col) * 4) : (int)LEAN_OUT;
+            }
+        } else if (AMODE == A_COLS) {
+            // A(i, k) = A[k*lda + i], B(k, j) = B[k*ldb + j]: both described from the first to the
+            // last reduction index of this slice, so the tail of the last tile reads zeros; the
+            // tile's position advances in the per-lane offsets (the range check sees all of it)
+            const int len = max(kend - kbeg, 0);
+            rs_a = __builtin_amdgcn_make_buffer_rsrc((void *)(A + (int64_t)kbeg * lda), 0, (int)((int64_t)len * lda * 4), SRD3);
+            rs_b = __builtin_amdgcn_make_buffer_rsrc((void *)(B + (int64_t)kbeg * ldb), 0, (int)((int64_t)len * ldb * 4), SRD3);
+#pragma unroll
+            for (int uu = 0; uu < A_UNITS; ++uu)
+                lv_au[uu] = m0 + a_col < M ? (int)(((int64_t)(a_row0 + uu * A_RSTEP) * lda + m0 + a_col) * 4) : (int)LEAN_OUT;
+#pragma unroll
+            for (int uu = 0; uu < B_UNITS; ++uu) {
+                const int r = b_row0 + uu * B_RSTEP;
+                lv_b[uu] = (r < BK && n0 + b_col < N) ? (int)(((int64_t)r * ldb + n0 + b_col) * 4) : (int)LEAN_OUT;
+            }
         } else {
             // A_GATHER_T: the reduction runs over the voxels of this slice; both the index rows and
             // B are described from the slice's first voxel to its last, so the tail reads zeros
@@ -943,7 +979,32 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
         }
     };
     auto lean_fetch = [&](const int32_t *rows, f32x4 *ra, f32x4 *rb) {
-        if constexpr (LEAN) {
+        if constexpr (LEAN && !GATHER) {
+            if (AMODE == A_ROWS) {
+                const int kc = min(k_lean, k_last);
+                const int soff = __builtin_amdgcn_readfirstlane(kc * 4);
+                const int soff_b = __builtin_amdgcn_readfirstlane(B_KC ? kc * 4 : kc * (int)ldb * 4);
+#pragma unroll
+                for (int uu = 0; uu < A_UNITS; ++uu)
+                    ra[uu] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs_a, lv_au[uu], soff, 0));
+#pragma unroll
+                for (int uu = 0; uu < B_UNITS; ++uu)
+                    rb[uu] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs_b, lv_b[uu], soff_b, 0));
+                k_lean += BK;
+            } else {
+#pragma unroll
+                for (int uu = 0; uu < A_UNITS; ++uu) {
+                    ra[uu] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs_a, lv_au[uu], 0, 0));
+                    lv_au[uu] += BK * (int)lda * 4;
+                }
+#pragma unroll
+                for (int uu = 0; uu < B_UNITS; ++uu) {
+                    rb[uu] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs_b, lv_b[uu], 0, 0));
+                    lv_b[uu] += BK * (int)ldb * 4;
+                }
+            }
+        }
+        if constexpr (LEAN && GATHER) {
             const int rowbytes = c * 4;
             const int soff_a = AMODE == A_GATHER ? __builtin_amdgcn_readfirstlane(cc_r * 4) : 0;
 #pragma unroll
