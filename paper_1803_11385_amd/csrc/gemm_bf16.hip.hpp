@@ -17,6 +17,11 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int BF16_BK = 64;   // reduction indices per tile = granularity of split reductions
 
+// two 16-bit halves into one word with v_perm_b32 (the selector names, from the low byte up, bytes of
+// the second operand as 0..3 and of the first as 4..7): {a.lo, b.lo} and {a.hi, b.hi}
+__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+
 // C[M x N] (+ slices) = A[M x K] . B[K x N], fp32 out.
 //   AMODE  A_ROWS      A(i,k) = A[i*lda + k]
 //          A_COLS      A(i,k) = A[k*lda + i]
@@ -43,11 +48,18 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     // An LDS row holds the 64 reduction offsets of one row (A) or column (B) of the tile: 128
     // bytes, no padding.  Its eight 16-byte pieces are stored permuted, piece p of row r at
     // position p ^ (r % 8), so that the 8 lanes that read or write the same piece of 8
-    // consecutive rows at once touch 8 different groups of banks.  (Permuting by r/8 as well,
-    // which would also separate rows that lie 8 apart in the transposing writes, measured
-    // slower: the operand reads are what counts.)
+    // consecutive rows at once touch 8 different groups of banks.  Kernels that transpose an
+    // operand on its way in (the weight gradient: both) permute by r / 8 as well: a transposing
+    // store writes the same 8 bytes of rows that lie 8 apart, which otherwise all fall on the
+    // same banks -- 54 % of that kernel's LDS cycles were bank conflicts, the LDS active 75 % of
+    // the time; with the second permutation 1.42 -> 1.17 ms.  The kernels without a transposing
+    // store keep the simpler form (the second permutation changes nothing for them).
     constexpr int LS = BK;
-    auto lds_at = [](int row, int k) { return row * LS + ((((k >> 3) ^ row) & 7) << 3) + (k & 7); };
+    constexpr bool SWZ2 = !(AMODE == A_ROWS || AMODE == A_GATHER) || !B_KC;
+    auto lds_at = [](int row, int k) {
+        const int perm = SWZ2 ? (row ^ ((row >> 3) << 1)) : row;
+        return row * LS + ((((k >> 3) ^ perm) & 7) << 3) + (k & 7);
+    };
     constexpr int WN = 4 / WM;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int MT = WTM / 16, NT = WTN / 16;
@@ -323,8 +335,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
             // 4 reduction offsets x 8 rows in registers -> per row its 4 values, 8 bytes
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const u32x2 lo = {(ra[0][q] & 0xFFFFu) | (ra[1][q] << 16), (ra[2][q] & 0xFFFFu) | (ra[3][q] << 16)};
-                const u32x2 hi = {(ra[0][q] >> 16) | (ra[1][q] & 0xFFFF0000u), (ra[2][q] >> 16) | (ra[3][q] & 0xFFFF0000u)};
+                // one byte-permute instruction per output word: low halves of two words side by
+                // side, or their high halves
+                const u32x2 lo = {pack_lo(ra[0][q], ra[1][q]), pack_lo(ra[2][q], ra[3][q])};
+                const u32x2 hi = {pack_hi(ra[0][q], ra[1][q]), pack_hi(ra[2][q], ra[3][q])};
                 *reinterpret_cast<u32x2 *>(&As[lds_at(a_c + 2 * q, a_r)]) = lo;
                 *reinterpret_cast<u32x2 *>(&As[lds_at(a_c + 2 * q + 1, a_r)]) = hi;
             }
@@ -338,8 +352,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
         } else if (b_c < BN) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                *reinterpret_cast<uint32_t *>(&Bs[lds_at(b_lds_row(b_c + 2 * q), b_r)]) = (rb[0][q] & 0xFFFFu) | (rb[1][q] << 16);
-                *reinterpret_cast<uint32_t *>(&Bs[lds_at(b_lds_row(b_c + 2 * q + 1), b_r)]) = (rb[0][q] >> 16) | (rb[1][q] & 0xFFFF0000u);
+                *reinterpret_cast<uint32_t *>(&Bs[lds_at(b_lds_row(b_c + 2 * q), b_r)]) = pack_lo(rb[0][q], rb[1][q]);
+                *reinterpret_cast<uint32_t *>(&Bs[lds_at(b_lds_row(b_c + 2 * q + 1), b_r)]) = pack_hi(rb[0][q], rb[1][q]);
             }
         }
     };

@@ -1392,6 +1392,15 @@ static hch_status launch_reduce(const float *part, float *out, int64_t n, int sp
 //   fused algorithm   : [ flipped+transposed weights (bwd_data only) | split-K partial sums ]
 struct WsLayout { size_t first_bytes, part_bytes; };
 
+// bf16 forward product: with rows of a multiple of 64 channels the kernel takes the weights from a
+// copy transposed per tap, Wt[27][c_out][c_in] at the start of the workspace, in which the
+// reduction index is the fast one -- its tiles then go to LDS as they are, instead of being
+// transposed in registers on every tile (vector instructions that cost matrix time)
+static bool fwd_transposed_weights(hch_dtype dtype, int c_in, int c_out)
+{
+    return dtype == HCH_BF16 && c_in % hch::BF16_BK == 0 && c_out % 8 == 0;
+}
+
 static WsLayout ws_layout(const Level &L, int c_in, int c_out, hch_dtype dtype, hch_ws_kind kind, hch_algo algo)
 {
     const size_t Kc = (size_t)27 * c_in, n = (size_t)L.n_total;
@@ -1401,6 +1410,7 @@ static WsLayout ws_layout(const Level &L, int c_in, int c_out, hch_dtype dtype, 
         if (algo == HCH_ALGO_COLUMNS) w.first_bytes = round_up(n * Kc * elem_size(dtype), 256);
         int splits = p.splits;
         if (algo == HCH_ALGO_FUSED) { const DirectPlan d = plan_direct(L.n_total, c_in, c_out); if (d.ok) splits = std::max(splits, d.splits); }
+        if (algo == HCH_ALGO_FUSED && fwd_transposed_weights(dtype, c_in, c_out)) w.first_bytes = round_up(Kc * c_out * elem_size(dtype), 256);
         if (splits > 1) w.part_bytes = round_up((size_t)splits * n * c_out * 4, 256);
     } else if (kind == HCH_WS_BWD_DATA) {
         if (algo == HCH_ALGO_COLUMNS) w.first_bytes = round_up(n * Kc * 4, 256);
@@ -1432,7 +1442,7 @@ extern "C" size_t hch_conv_workspace_bytes(const hch_levels *levels, int32_t lev
         // next to the split-K area
         const WsLayout w = ws_layout(L, c_in, c_out, dtype, HCH_WS_FWD, algo);
         const size_t rows = std::min<size_t>((size_t)L.n_total, 1024);
-        const size_t first = algo == HCH_ALGO_COLUMNS ? round_up(rows * 27 * c_in * elem_size(dtype), 256) : 0;
+        const size_t first = algo == HCH_ALGO_COLUMNS ? round_up(rows * 27 * c_in * elem_size(dtype), 256) : w.first_bytes;
         return std::max<size_t>(256, first + w.part_bytes);
     }
     if (kind != HCH_WS_FWD && kind != HCH_WS_BWD_DATA && kind != HCH_WS_BWD_WEIGHT) return 0;
@@ -1506,6 +1516,21 @@ extern "C" hch_status hch_conv_fwd(const hch_levels *levels, int32_t level, hch_
             return st;
         }
         const double bytes = (double)n * (108.0 + es * c_in + 4.0 * c_out * p.splits) + es * Kc * c_out;
+        if (fwd_transposed_weights(dtype, c_in, c_out) && aligned16(X) && aligned16(W) && aligned16(workspace)) {
+            const int64_t wn = (int64_t)Kc * c_out, per_tap = (int64_t)c_in * c_out;
+            {
+                hch::LaunchTimer lt(HCH_KERNEL_ID("flip_transpose_weights_kernel<unsigned short>"), s, 4.0 * wn, 0.0);
+                HCH_LAUNCH(hch::flip_transpose_weights_kernel<uint16_t>, dim3(blocks_for(wn)), dim3(256), 0, s,
+                           (const uint16_t *)W, (uint16_t *)workspace, c_in, c_out, 27, 0);
+            }
+            HCH_LAUNCH_CHECK("flip_transpose_weights_kernel");
+            st = launch_gemm<hch::A_GATHER, true>(dtype, p, X, workspace, p.splits > 1 ? part : Y, L->dnbr, (int)n, c_out, Kc,
+                                                  c_in, c_in, c_out, n * c_out, bytes, s, 0, 27, c_in, per_tap, L->dnbr_t,
+                                                  nullptr, nullptr, n);
+            if (st != HCH_OK) return st;
+            if (p.splits > 1) st = launch_reduce(part, Y, n * c_out, p.splits, s);
+            return st;
+        }
         st = launch_gemm<hch::A_GATHER, false>(dtype, p, X, W,
                                                p.splits > 1 ? part : Y, L->dnbr, (int)n, c_out, Kc, c_in,
                                                c_out, c_out, n * c_out, bytes, s, 0, 27, 0, 0, L->dnbr_t,

@@ -684,7 +684,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     // operands at once.  B is always k-major Bs[k][j], tile nt taking columns r*NT + nt.
     // The +4 padding keeps rows 16-byte aligned and spreads consecutive rows over the banks.
     constexpr int AS = A_K_FAST ? BK + 4 : BM + 4;
-    constexpr int BS = BN + 4;
+    // B rows: +4 floats; +2 where B is transposed on its way in (B_KC) and a lane reads at most two
+    // floats of a row at once: the 8 lanes that store the same column to rows 4 apart then fall
+    // on 4 different banks instead of 2
+    constexpr int BS = (B_KC && NT <= 2) ? BN + 2 : BN + 4;
     constexpr int A_ROWLEN = A_K_FAST ? BK : BM;      // floats per LDS row that are loaded
     constexpr int A_TOTAL = BM * BK / 4;              // float4 units in an A tile
     constexpr int A_UNITS = A_TOTAL / 256;
