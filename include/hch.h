@@ -247,8 +247,9 @@ typedef enum {
  * (N_l x 27*c_in elements) and, for small levels, partial sums of a split reduction;
  * hch_conv_fwd accepts any size >= the HCH_WS_MIN value and walks the voxels in chunks when
  * given less than HCH_WS_FWD; the two backward calls need their full size.  With
- * HCH_ALGO_FUSED only the partial sums (and, for bwd_data, one rearranged copy of the
- * weights) live there. */
+ * HCH_ALGO_FUSED only the partial sums and one rearranged copy of the weights live there
+ * (bwd_data: flipped and transposed; fwd with bf16 inputs and c_in a multiple of 64:
+ * transposed per tap). */
 size_t hch_conv_workspace_bytes(const hch_levels *levels, int32_t level, int32_t c_in,
                                 int32_t c_out, hch_dtype dtype, hch_ws_kind kind, hch_algo algo);
 
@@ -480,6 +481,17 @@ hch_status hch_relu_bwd(const float *y, const float *dy, float *dx, int64_t n, v
  *   sink  DEVICE [workgroups * 256] float, overwritten.  Asynchronous on `stream`.
  */
 hch_status hch_probe_mfma(hch_dtype dtype, int32_t iters, int32_t workgroups, float *sink, void *stream);
+
+/*
+ * Measurement and test aid: the products of a convolution have two forms of their main loop,
+ * one that addresses memory with guarded 64-bit pointers and works for every shape, and a lean
+ * one (loads through buffer descriptors, scalar offsets) that the library takes when the
+ * operands allow it.  Both multiply the same tiles in the same order, so their results agree bit
+ * for bit; `enabled` = 0 makes every later call take the first form, 1 (the default) restores the
+ * choice.  Process-wide, not synchronised with calls running on other threads.  Returns the
+ * previous setting.
+ */
+int32_t hch_set_lean_loops(int32_t enabled);
 
 /*
  * Optional per-kernel timing, for benchmarks.  A kernel gets an id in [0, hch_kernel_count())

@@ -20,7 +20,7 @@ __all__ = [
     "hch_profile_reset", "hch_field_build", "hch_sconv_workspace_bytes", "hch_sconv_fwd", "hch_sconv_bwd_weight",
     "hch_sconv_bwd_data", "hch_avgpool_fwd", "hch_avgpool_bwd", "hch_build_levels_ratios",
     "hch_spool_max_fwd", "hch_spool_max_bwd", "hch_spool_avg_fwd", "hch_spool_avg_bwd", "hch_build_tap_major",
-    "hch_conv_bwd_weight_noalloc", "HCH_NOALLOC_SCRATCH_BYTES", "hch_probe_mfma",
+    "hch_conv_bwd_weight_noalloc", "HCH_NOALLOC_SCRATCH_BYTES", "hch_probe_mfma", "hch_set_lean_loops",
 ]
 
 HCH_F32, HCH_BF16 = 0, 1
@@ -43,8 +43,7 @@ exported_symbols = [
     "hch_sconv_bwd_data", "hch_avgpool_fwd", "hch_avgpool_bwd", "hch_build_levels_ratios",
     "hch_spool_max_fwd", "hch_spool_max_bwd", "hch_spool_avg_fwd", "hch_spool_avg_bwd", "hch_build_tap_major",
     "hch_conv_bwd_weight_noalloc",
-    "hch_conv_bwd_weight_noalloc",
-    "hch_probe_mfma",
+    "hch_probe_mfma", "hch_set_lean_loops",
 ]
 
 
@@ -129,6 +128,8 @@ def load_library():
     L.hch_relu_fwd.argtypes = [vp, vp, i64, vp]
     L.hch_relu_bwd.argtypes = [vp, vp, vp, i64, vp]
     L.hch_probe_mfma.argtypes = [C.c_int, i32, i32, vp, vp]
+    L.hch_set_lean_loops.argtypes = [i32]
+    L.hch_set_lean_loops.restype = i32
     L.hch_kernel_count.restype = i32
     L.hch_kernel_name.argtypes = [i32]
     L.hch_kernel_name.restype = C.c_char_p
@@ -622,6 +623,10 @@ def hch_relu_bwd(y, dy, dx, n, stream=None):
 def hch_probe_mfma(dtype, iters, workgroups, sink, stream=None):
     _check(load_library().hch_probe_mfma(_in_dtype(dtype), int(iters), int(workgroups),
                                          _dp(sink, "sink", _F32, workgroups * 256), _stream(stream)))
+
+
+def hch_set_lean_loops(enabled):
+    return int(load_library().hch_set_lean_loops(1 if enabled else 0))
 
 
 def hch_kernel_count():

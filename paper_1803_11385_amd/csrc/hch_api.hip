@@ -949,6 +949,9 @@ extern "C" hch_status hch_col2hash(const hch_levels *levels, int32_t level, cons
 static inline int k_gran(hch_dtype dtype) { return dtype == HCH_BF16 ? hch::BF16_BK : hch::GEMM_BK; }
 
 // tile shape and split of one product
+// hch_set_lean_loops: 0 = every product takes the pointer-based form of its main loop
+static std::atomic<int> g_lean_loops{1};
+
 struct GemmPlan {
     int bm, bn, wm;
     int splits, k_per_split;
@@ -1077,6 +1080,7 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
                    (AMODE == hch::A_COLS || (K % 32 == 0 && (p.splits == 1 || p.k_per_split % 32 == 0)));
         }
     }
+    if (!g_lean_loops.load(std::memory_order_relaxed)) lean = false;
     const int ln = lean ? 1 : 0;
     if (ids[ln][pl][v][cfg] < 0) {
         char nm[128];
@@ -1201,6 +1205,7 @@ static hch_status launch_gemm_bf16(const GemmPlan &p, const void *A, const void 
                a_rows * lda * 2 < lim && idx_rows * taps * 4 < lim && b_bytes < lim &&
                (AMODE == hch::A_GATHER_T || (lda % hch::BF16_BK == 0 && (B_KC ? b_wrap == (int)lda : b_wrap == 0)));
     }
+    if (!g_lean_loops.load(std::memory_order_relaxed)) lean = false;
     const bool big = lean && AMODE == hch::A_GATHER && p.bm == 128 && p.bn == 64 && p.splits == 1 && M >= 256 * 1024;
     static int ids[2][5] = {{-1, -1, -1, -1, -1}, {-1, -1, -1, -1, -1}};
     const int cfg = big ? 4 : (p.bm == 64 ? 0 : (p.bn == 16 ? 1 : (p.bn == 32 ? 2 : 3)));
@@ -2374,6 +2379,11 @@ extern "C" hch_status hch_relu_bwd(const float *y, const float *dy, float *dx, i
 // ---------------------------------------------------------------------------------------
 // per-kernel timing
 // ---------------------------------------------------------------------------------------
+
+extern "C" int32_t hch_set_lean_loops(int32_t enabled)
+{
+    return g_lean_loops.exchange(enabled ? 1 : 0);
+}
 
 extern "C" hch_status hch_probe_mfma(hch_dtype dtype, int32_t iters, int32_t workgroups, float *sink, void *stream)
 {

@@ -817,3 +817,46 @@ def test_general_conv_errors(case_batch64):
             hch.hch_field_build(case.glv, level, F, stride, pad, f, None)
     with pytest.raises(hch.HchError):
         hch.hch_field_build(case.glv, 0, 3, 1, 1, None, None)
+
+
+# --------------------------------------------------------------------------------------
+# the two forms of the products' main loop: same tiles, same order of sums, same bits
+# --------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("algo", [hch.HCH_ALGO_COLUMNS, hch.HCH_ALGO_FUSED, hch.HCH_ALGO_FUSED_DENSE],
+                         ids=["columns", "fused", "fused-dense"])
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+def test_lean_and_pointer_loops_agree_bit_for_bit(case_small, algo, bf16):
+    """hch_set_lean_loops(0) sends every product through the pointer-based loop; with channel
+    counts that qualify for the lean loop (multiples of 64) the outputs must not change by a bit.
+    Both levels: the finest has enough voxels for the wide tiles, the next is split along the
+    reduction."""
+    case = case_small
+    c_in, c_out = 64, 128
+    DT = hch.HCH_BF16 if bf16 else hch.HCH_F32
+    put = (lambda a: dev(S.bf16_bits(S.to_bf16_grid(a)).view(np.int16))) if bf16 else dev
+    for level in (0, 1):
+        n = case.olv[level].Ntot
+        X, G = put(S.gaussian((n, c_in), 1.0, 901 + level)), put(S.gaussian((n, c_out), 1.0, 903 + level))
+        W = put(S.gaussian((27, c_in, c_out), 0.1, 905 + level))
+
+        def ws(kind):
+            return workspace(hch.hch_conv_workspace_bytes(case.glv, level, c_in, c_out, DT, kind, algo))
+
+        outs = []
+        try:
+            for lean in (1, 0):
+                hch.hch_set_lean_loops(lean)
+                Y = torch.full((n, c_out), float("nan"), dtype=torch.float32, device="cuda")
+                dX = torch.full((n, c_in), float("nan"), dtype=torch.float32, device="cuda")
+                dW = torch.full((27, c_in, c_out), float("nan"), dtype=torch.float32, device="cuda")
+                hch.hch_conv_fwd(case.glv, level, DT, X, W, Y, c_in, c_out, ws(hch.HCH_WS_FWD), algo)
+                hch.hch_conv_bwd_data(case.glv, level, DT, G, W, dX, c_in, c_out, ws(hch.HCH_WS_BWD_DATA), algo)
+                hch.hch_conv_bwd_weight(case.glv, level, DT, X, G, dW, c_in, c_out, ws(hch.HCH_WS_BWD_WEIGHT), algo)
+                torch.cuda.synchronize()
+                outs.append((Y, dX, dW))
+        finally:
+            assert hch.hch_set_lean_loops(1) == 0
+        for a, b, what in zip(outs[0], outs[1], ("Y", "dX", "dW")):
+            assert not torch.isnan(a).any(), what
+            assert torch.equal(a, b), f"level {level} {what}: lean and pointer-based loops differ"
