@@ -1059,6 +1059,9 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
     constexpr bool lean_mode = (AMODE == hch::A_GATHER || AMODE == hch::A_ROWS || ((AMODE == hch::A_GATHER_T || AMODE == hch::A_COLS) && !B_KC)) &&
                                sizeof(TIN) == 4;
     bool lean = false;
+    // rows of 16 channels (not a multiple of 32): tiles of 16 reduction indices, one tap each
+    const bool lean16 = AMODE == hch::A_GATHER && !B_KC && lda % 32 == 16 && p.bm == 128 && p.bn == 32 &&
+                        (p.splits == 1 || p.k_per_split % 16 == 0);
     if constexpr (lean_mode) {
         const int64_t lim = (int64_t)1 << 31;
         if constexpr (gather_mode) {
@@ -1069,7 +1072,7 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
             else b_bytes = (int64_t)taps * lda * ldb * 4;
             lean = vec && c_planes == 0 && taps == 27 && nbr && a_rows > 0 && a_rows < ((int64_t)1 << 23) && lda * 4 < ((int64_t)1 << 23) &&
                    a_rows * lda * 4 < lim && idx_rows * taps * 4 < lim && b_bytes < lim &&
-                   (AMODE == hch::A_GATHER_T || (lda % 32 == 0 && (B_KC ? b_wrap == (int)lda : b_wrap == 0)));
+                   (AMODE == hch::A_GATHER_T || ((lda % 32 == 0 || lean16) && (B_KC ? b_wrap == (int)lda : b_wrap == 0)));
         } else {
             // plain operands (the products of the columns algorithm): row-major A needs whole tiles,
             // K and the slices multiples of 32; k-major A and B may end anywhere (their buffers are
@@ -1090,7 +1093,11 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
                  lean ? (pl == 2 ? ", true, true" : ", false, true") : (pl == 2 ? ", true" : ""));
         ids[ln][pl][v][cfg] = hch::Profiler::get().id_for(nm);
     }
-    hch::LaunchTimer lt(ids[ln][pl][v][cfg], s, alg_bytes, 2.0 * M * (double)N * K);
+    int kid = ids[ln][pl][v][cfg];
+    if (lean && lean16)
+        kid = tilemask ? HCH_KERNEL_ID("gemm_f32_kernel<float, 128, 32, 16, 4, 2, false, true, false, true, true>")
+                       : HCH_KERNEL_ID("gemm_f32_kernel<float, 128, 32, 16, 4, 2, false, true, false, false, true>");
+    hch::LaunchTimer lt(kid, s, alg_bytes, 2.0 * M * (double)N * K);
 #define HCH_GEMM_ARGS (const TIN *)A, (const TIN *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split, c_split_stride, c_vec_ok, \
                       m_tiles, c_planes, taps, b_wrap, b_tap_stride, rowmap, tilemask, flat
 #define HCH_GEMM_CASE(BM_, BN_, BK_, WM_, VEC_, PL_)                                                                \
@@ -1109,6 +1116,14 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
     HCH_LAUNCH((hch::gemm_f32_kernel<TIN, BM_, BN_, 32, WM_, AMODE, B_KC, true, false, SKIP_, true>), grid, dim3(256), 0, s, HCH_GEMM_ARGS)
     if constexpr (lean_mode) {
         if (lean) {
+            if constexpr (AMODE == hch::A_GATHER && !B_KC) {
+                if (lean16) {
+                    if (tilemask) HCH_LAUNCH((hch::gemm_f32_kernel<TIN, 128, 32, 16, 4, AMODE, B_KC, true, false, true, true>), grid, dim3(256), 0, s, HCH_GEMM_ARGS);
+                    else HCH_LAUNCH((hch::gemm_f32_kernel<TIN, 128, 32, 16, 4, AMODE, B_KC, true, false, false, true>), grid, dim3(256), 0, s, HCH_GEMM_ARGS);
+                    HCH_LAUNCH_CHECK("gemm_f32_kernel");
+                    return HCH_OK;
+                }
+            }
             if constexpr (AMODE == hch::A_GATHER) {
                 if (tilemask) {
                     if (p.bm == 64) HCH_GEMM_LEAN_CASE(64, 64, 2, true);
