@@ -825,14 +825,15 @@ def test_general_conv_errors(case_batch64):
 
 @pytest.mark.parametrize("algo", [hch.HCH_ALGO_COLUMNS, hch.HCH_ALGO_FUSED, hch.HCH_ALGO_FUSED_DENSE],
                          ids=["columns", "fused", "fused-dense"])
-@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
-def test_lean_and_pointer_loops_agree_bit_for_bit(case_small, algo, bf16):
+@pytest.mark.parametrize("c_in,c_out,bf16", [(64, 128, False), (64, 128, True), (16, 32, False), (32, 16, False)],
+                         ids=["f32-64-128", "bf16-64-128", "f32-16-32", "f32-32-16"])
+def test_lean_and_pointer_loops_agree_bit_for_bit(case_small, algo, c_in, c_out, bf16):
     """hch_set_lean_loops(0) sends every product through the pointer-based loop; with channel
-    counts that qualify for the lean loop (multiples of 64) the outputs must not change by a bit.
+    counts that qualify for the lean loop (rows of a multiple of 32 channels, of 16 for the
+    forward product's 16-wide tiles, of 64 with bf16) the outputs must not change by a bit.
     Both levels: the finest has enough voxels for the wide tiles, the next is split along the
     reduction."""
     case = case_small
-    c_in, c_out = 64, 128
     DT = hch.HCH_BF16 if bf16 else hch.HCH_F32
     put = (lambda a: dev(S.bf16_bits(S.to_bf16_grid(a)).view(np.int16))) if bf16 else dev
     for level in (0, 1):
