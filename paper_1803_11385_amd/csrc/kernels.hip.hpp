@@ -90,16 +90,24 @@ __device__ __forceinline__ uint32_t psh_offset(const PshView &L, unsigned Rv, un
 }
 // Step 2: the slot record of a position with residues (xm,ym,zm) mod m, given its offset cell
 // (Eq.1, Eq.5).
-__device__ __forceinline__ const uint32_t *psh_slot(const PshView &L, unsigned Mv, unsigned m, uint32_t ph,
-                                                    unsigned xm, unsigned ym, unsigned zm)
+__device__ __forceinline__ unsigned psh_slot_index(unsigned Mv, unsigned m, uint32_t ph,
+                                                   unsigned xm, unsigned ym, unsigned zm)
 {
     unsigned hx = xm + (ph & 255u);         if (hx >= m) hx -= m;
     unsigned hy = ym + ((ph >> 8) & 255u);  if (hy >= m) hy -= m;
     unsigned hz = zm + ((ph >> 16) & 255u); if (hz >= m) hz -= m;
-    return L.slot3 + (size_t)SLOT_WORDS * (size_t)(Mv + (hx * m + hy) * m + hz);
+    return Mv + (hx * m + hy) * m + hz;
+}
+__device__ __forceinline__ const uint32_t *psh_slot(const PshView &L, unsigned Mv, unsigned m, uint32_t ph,
+                                                    unsigned xm, unsigned ym, unsigned zm)
+{
+    return L.slot3 + (size_t)SLOT_WORDS * (size_t)psh_slot_index(Mv, m, ph, xm, ym, zm);
 }
 // the record itself: one aligned 16-byte load
-__device__ __forceinline__ u32x4 psh_record(const uint32_t *rec) { return *reinterpret_cast<const u32x4 *>(rec); }
+// (the three words in use, as a 12-byte load of the 16-byte aligned record: a register that a load
+// fills and nothing reads is handed out again at once, and whoever gets it must wait for the load)
+typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+__device__ __forceinline__ u32x3 psh_record(const uint32_t *rec) { return *reinterpret_cast<const u32x3 *>(rec); }
 // Step 3: the local data index if the record is occupied and tagged with (x,y,z), else -1
 // (Section 3.1: redundant slot, or a slot that belongs to another position).
 __device__ __forceinline__ int32_t psh_match(uint32_t h, uint32_t xy, uint32_t zz,
@@ -210,6 +218,7 @@ __global__ __launch_bounds__(256) void neighbour_kernel(
     __syncthreads();
     xlo = min(min(xrange[0], xrange[1]), min(xrange[2], xrange[3]));
     xhi = max(max(xrange[4], xrange[5]), max(xrange[6], xrange[7]));
+    if (!live) x = (unsigned)xlo;                      // lanes past the end: a position whose offset plane is staged
     // planes of Phi to stage: residues res0, res0 + 1, ... (mod r) of x' = xlo - 1 .. xhi + 1
     const unsigned r2 = r * r;
     const unsigned planes = min((unsigned)(xhi - xlo + 3), r);
@@ -226,41 +235,92 @@ __global__ __launch_bounds__(256) void neighbour_kernel(
     }
     __syncthreads();
 
+    // Probes run in three rounds of 9 (dx, dy) columns each: dz = 0 first, then dz = -1 and dz = +1.
+    // Between them neighbouring lanes exchange results: when the voxel of the next lane sits at
+    // (x, y, z+1) -- the usual case for data ordered by position, checked on the coordinates, not
+    // assumed -- its dz = 0 results ARE this voxel's dz = +1 results (and the other way round for
+    // the lane before), every one of them the outcome of a hash probe.  A lane that got a round's
+    // results this way points its loads of that round at the first record of the model's table
+    // instead: same instructions, one cache line for all such lanes of a wavefront (the number of
+    // requests is what bounds this kernel).  Lanes past the end of the model do so in every round.
     int32_t out[27];
-    if (live) {
+    {
         unsigned xm[3], ym[3], zm[3], xr[3], yr[3], zr[3];
         residues3(x % m, m, xm); residues3(y % m, m, ym); residues3(z % m, m, zm);
         residues3(x % r, r, xr); residues3(y % r, r, yr); residues3(z % r, r, zr);
-        // one x-plane of 9 neighbours at a time: 9 offset reads, then 9 record loads, then the
-        // comparisons.  Positions outside the grid are probed too (their residues are valid
-        // table coordinates) and discarded afterwards, so there is no branch between the loads.
+        unsigned plane[3];                               // where the staged plane of x-1, x, x+1 starts in LDS
 #pragma unroll
-        for (int a = 0; a < 3; ++a) {
-            uint32_t ph[9];
-            if (staged) {
-                unsigned pl = xr[a] >= res0 ? xr[a] - res0 : xr[a] + r - res0;
-                const uint32_t *plane = lds + pl * r2;
-#pragma unroll
-                for (int q = 0; q < 9; ++q) ph[q] = plane[yr[q / 3] * r + zr[q % 3]];
-            } else {
-#pragma unroll
-                for (int q = 0; q < 9; ++q) ph[q] = psh_offset(L, Rv, r, xr[a], yr[q / 3], zr[q % 3]);
-            }
+        for (int a = 0; a < 3; ++a) plane[a] = (xr[a] >= res0 ? xr[a] - res0 : xr[a] + r - res0) * r2;
+        // Positions outside the grid are probed too (their residues are valid table coordinates)
+        // and discarded afterwards, so there is no branch between the loads of a round.
+        // step 2 and 3 of a round: 9 record loads back to back, then the comparisons
+        auto records = [&](const int dzi, const bool need, const uint32_t *ph) {
             uint32_t rh[9], rxy[9], rz[9];
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int q = 0; q < 9; ++q) {
-                if (a == 1 && q == 4) continue;          // the voxel itself
-                const u32x4 rec = psh_record(psh_slot(L, Mv, m, ph[q], xm[a], ym[q / 3], zm[q % 3]));
+                if (dzi == 1 && q == 4) continue;        // the voxel itself
+                unsigned slot = psh_slot_index(Mv, m, ph[q], xm[q / 3], ym[q % 3], zm[dzi]);
+                asm("" : "+v"(slot));                    // computed by every lane: the choice below stays a select
+                // a lane that does not need the record reads the table's first one (one line for all such lanes)
+                const u32x3 rec = psh_record(L.slot3 + (size_t)SLOT_WORDS * (size_t)(need ? slot : Mv));
                 rh[q] = rec[0]; rxy[q] = rec[1]; rz[q] = rec[2];
             }
+            __builtin_amdgcn_sched_barrier(0);           // all loads of the round issued before anything uses one
 #pragma unroll
             for (int q = 0; q < 9; ++q) {
-                if (a == 1 && q == 4) { out[13] = base + i; continue; }
-                const unsigned qx = x + a - 1, qy = y + q / 3 - 1, qz = z + q % 3 - 1;   // wrap below 0
+                if (dzi == 1 && q == 4) { out[13] = base + i; continue; }
+                const unsigned qx = x + q / 3 - 1, qy = y + q % 3 - 1, qz = z + dzi - 1;   // wrap below 0
                 const int32_t h = psh_match(rh[q], rxy[q], rz[q], qx, qy, qz);
                 const bool inside = (qx < u) & (qy < u) & (qz < u);
-                out[a * 9 + q] = (inside & (h >= 0)) ? base + h : -1;                    // Eq.6
+                if (need) out[q * 3 + dzi] = (inside & (h >= 0)) ? base + h : -1;       // Eq.6
             }
+        };
+        // step 1, the offset cells: from the staged planes, or from memory
+        auto round_staged = [&](const int dzi, const bool need) {
+            uint32_t ph[9];
+#pragma unroll
+            for (int q = 0; q < 9; ++q) ph[q] = lds[plane[q / 3] + yr[q % 3] * r + zr[dzi]];
+            records(dzi, need, ph);
+        };
+        auto round_memory = [&](const int dzi, const bool need) {
+            uint32_t ph[9];
+#pragma unroll
+            for (int q = 0; q < 9; ++q) {
+                unsigned cell = Rv + (xr[q / 3] * r + yr[q % 3]) * r + zr[dzi];
+                asm("" : "+v"(cell));
+                ph[q] = L.phi4[need ? cell : Rv];
+            }
+            records(dzi, need, ph);
+        };
+        bool above = false, below = false;
+        auto exchange = [&]() {
+            const int ln = threadIdx.x & 63;
+            const unsigned nx = (unsigned)__shfl_down((int)x, 1), ny = (unsigned)__shfl_down((int)y, 1), nz = (unsigned)__shfl_down((int)z, 1);
+            above = live & (ln < 63) & (i + 1 < n) & (nx == x) & (ny == y) & (nz == z + 1u);
+            below = (__shfl_up((int)above, 1) != 0) & (ln > 0);
+#pragma unroll
+            for (int q = 0; q < 9; ++q) {
+                const int32_t mid = out[q * 3 + 1];
+                const int32_t up = __shfl_down(mid, 1), dn = __shfl_up(mid, 1);
+                if (above) out[q * 3 + 2] = up;
+                if (below) out[q * 3 + 0] = dn;
+            }
+        };
+#pragma unroll
+        for (int k = 0; k < 27; ++k) out[k] = -1;
+        // the two ways to read the offset cells never share a basic block: the waits of the one
+        // with loads from memory would otherwise land between the record loads of the other
+        if (staged) {
+            round_staged(1, live);
+            exchange();
+            round_staged(0, live & !below);
+            round_staged(2, live & !above);
+        } else {
+            round_memory(1, live);
+            exchange();
+            round_memory(0, live & !below);
+            round_memory(2, live & !above);
         }
     }
     __syncthreads();                                  // every thread is done with the offset planes
@@ -448,7 +508,7 @@ __global__ __launch_bounds__(256) void child_kernel(
     for (int q = 0; q < 8; ++q) ph[q] = psh_offset(Lf, Rv, r, xr[q >> 2], yr[(q >> 1) & 1], zr[q & 1]);
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-        const u32x4 rec = psh_record(psh_slot(Lf, Mv, m, ph[q], xm[q >> 2], ym[(q >> 1) & 1], zm[q & 1]));
+        const u32x3 rec = psh_record(psh_slot(Lf, Mv, m, ph[q], xm[q >> 2], ym[(q >> 1) & 1], zm[q & 1]));
         rh[q] = rec[0]; rxy[q] = rec[1]; rz[q] = rec[2];
     }
 #pragma unroll
@@ -468,7 +528,7 @@ __device__ __forceinline__ int32_t psh_lookup(const PshView &L, int v, unsigned 
 {
     const unsigned m = (unsigned)L.mbar[v], r = (unsigned)L.rbar[v];
     const uint32_t ph = psh_offset(L, (unsigned)L.R[v], r, x % r, y % r, z % r);
-    const u32x4 rec = psh_record(psh_slot(L, (unsigned)L.M[v], m, ph, x % m, y % m, z % m));
+    const u32x3 rec = psh_record(psh_slot(L, (unsigned)L.M[v], m, ph, x % m, y % m, z % m));
     const int32_t h = psh_match(rec[0], rec[1], rec[2], x, y, z);
     return h >= 0 ? L.N[v] + h : -1;
 }

@@ -304,6 +304,33 @@ def test_permuted_input_tables_and_lists(oracle, case_permuted, case_batch64):
     assert np.array_equal(case.glv.info(0).device_nbr27(), np.where(nb_sorted >= 0, inv[np.maximum(nb_sorted, 0)], -1))
 
 
+def test_neighbour_lists_with_short_sorted_runs(oracle):
+    """Neighbouring lanes of the index-list kernel hand each other results when their voxels are
+    z-neighbours.  Here every model's sorted voxel list is cut into runs of 1-7 voxels, the runs
+    shuffled and every third one reversed: lanes with a z-neighbour above only, below only, on
+    both sides and on neither sit side by side, also across wavefront and tile boundaries."""
+    coords, offs, _ = S.config_batch(2)
+    rng = np.random.default_rng(1618)
+    pieces = []
+    for v in range(len(offs) - 1):
+        a, b = int(offs[v]), int(offs[v + 1])
+        cuts = [a]
+        while cuts[-1] < b:
+            cuts.append(min(b, cuts[-1] + int(rng.integers(1, 8))))
+        runs = [np.arange(cuts[q], cuts[q + 1]) for q in range(len(cuts) - 1)]
+        runs = [r[::-1] if q % 3 == 2 else r for q, r in enumerate(runs)]
+        pieces += [runs[q] for q in rng.permutation(len(runs))]
+    perm = np.concatenate(pieces)
+    assert np.array_equal(np.sort(perm), np.arange(coords.shape[0]))
+    case = Case(oracle, np.ascontiguousarray(coords[perm]), offs, 64, 3)
+    for l, L in enumerate(case.olv):
+        info = case.glv.info(l)
+        assert np.array_equal(info.device_coords(), L.coords)
+        assert np.array_equal(info.device_nbr27(), oracle.neighbours(L)), f"nbr27 level {l}"
+        if l > 0:
+            assert np.array_equal(info.device_child8(), oracle.children(case.olv[l - 1], L)), f"child8 level {l}"
+
+
 @pytest.mark.parametrize("algo", ALGOS, ids=ALGO_IDS)
 @pytest.mark.parametrize("c_in,c_out", [(4, 32), (16, 4), (32, 64)])
 def test_permuted_input_conv_and_pool(oracle, case_permuted, c_in, c_out, algo):
