@@ -1678,7 +1678,6 @@ static hch_status conv_bwd_weight_impl(const hch_levels *levels, int32_t level, 
     const Level *L;
     const bool resident = algo == HCH_ALGO_COLUMNS_RESIDENT;     // the column matrix is in the workspace already
     if (resident) algo = HCH_ALGO_COLUMNS;
-    const bool skip = algo == HCH_ALGO_FUSED;
     if (algo == HCH_ALGO_FUSED_DENSE) algo = HCH_ALGO_FUSED;
     hch_status st = conv_args(levels, level, dtype, X, dY, dW, c_in, c_out, workspace, algo, &L, who);
     if (st != HCH_OK) return st;

@@ -167,7 +167,7 @@ __device__ __forceinline__ int find_entry(const int32_t *__restrict__ prefix, in
 
 // "Pre-stored neighbour information": for every voxel the global data indices of its 27
 // neighbours p + (dx,dy,dz), tap k = (dx+1)*9 + (dy+1)*3 + (dz+1), or -1 (empty, or outside
-// the grid: never hashed).  This is the index side of the stride-1 traversal of Algorithm 1.
+// the grid).  This is the index side of the stride-1 traversal of Algorithm 1.
 // One thread per voxel: the six residues are computed once and stepped to the neighbours.  Tiles
 // [tile_first, tile_first + n_tiles) are processed, numbered XCD-contiguously: the tiles of one
 // model (whose tables are a few hundred KB) then stay in one XCD's L2.
@@ -176,9 +176,10 @@ __device__ __forceinline__ int find_entry(const int32_t *__restrict__ prefix, in
 // kernel is bound by the number of such cache accesses, not by bytes.  The offset cells a tile
 // needs are the planes x' mod r of Phi for x' in [xmin - 1, xmax + 1] over the tile's voxels; when
 // these fit (a tile of voxels that lie close together in x: always the case for data ordered by
-// position, and for small tables) they are copied to LDS once, with coalesced loads, and the 26
+// position, and for small tables) they are copied to LDS once, with coalesced loads, and the
 // offset reads of every voxel come from there; otherwise the cells are read from memory as the
-// slot records are.  The centre tap is the voxel itself.  Results are kept in registers until
+// slot records are.  The centre tap is the voxel itself; lanes whose voxels are z-neighbours hand
+// each other results (below), so a voxel makes 8 to 26 probes.  Results are kept in registers until
 // all probes of the workgroup are done, then go through the same LDS space so that the rows are
 // written coalesced.
 constexpr int NBR_LDS_WORDS = 256 * 27;
