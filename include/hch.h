@@ -460,12 +460,19 @@ hch_status hch_avgpool_bwd(const hch_levels *levels, int32_t level_in, const flo
  *                       then not stored (a training step needs only their sign, which Y has).
  *   hch_pool_relu_bwd:  dY = hch_relu_bwd(A, hch_pool_bwd(dP, argmax)), written completely.
  *                       Only the sign of A is read, so Y may be passed in its place.
+ *   hch_pool_relu_bwd_pooled:  the same result from the pooled rows P (DEVICE [N_coarse][c]) that
+ *                       hch_relu_pool_fwd wrote with this argmax: the child a switch names
+ *                       carries the maximum, so A[argmax[o][ch]][ch] = P[o][ch] and P's sign
+ *                       decides.  Neither A nor Y is read: a training step need not keep them.
  */
 hch_status hch_relu_pool_fwd(const hch_levels *levels, int32_t level_in, const float *Y, float *A,
                              float *P, int32_t *argmax, int32_t c, void *stream);
 hch_status hch_pool_relu_bwd(const hch_levels *levels, int32_t level_in, const float *dP,
                              const int32_t *argmax, const float *A, float *dY, int32_t c,
                              void *stream);
+hch_status hch_pool_relu_bwd_pooled(const hch_levels *levels, int32_t level_in, const float *dP,
+                                    const int32_t *argmax, const float *P, float *dY, int32_t c,
+                                    void *stream);
 
 /* Element-wise ReLU over a compact data array of n floats (Section 4, "other CNN
  * operations"): y = max(x, 0);  backward dx = (y > 0) ? dy : 0.  In-place use is allowed. */

@@ -15,7 +15,7 @@ __all__ = [
     "hch_build_levels", "hch_build_levels_device", "hch_build_tables_host", "hch_build_neighbours",
     "hch_build_neighbours_range", "hch_hash2col", "hch_col2hash", "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data",
     "hch_conv_bwd_weight", "hch_pool_fwd", "hch_pool_bwd", "hch_relu_fwd", "hch_relu_bwd", "hch_relu_pool_fwd",
-    "hch_pool_relu_bwd", "hch_deconv_fwd", "hch_deconv_bwd_data", "hch_deconv_bwd_weight",
+    "hch_pool_relu_bwd", "hch_pool_relu_bwd_pooled", "hch_deconv_fwd", "hch_deconv_bwd_data", "hch_deconv_bwd_weight",
     "hch_unpool_fwd", "hch_unpool_bwd", "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
     "hch_profile_reset", "hch_field_build", "hch_sconv_workspace_bytes", "hch_sconv_fwd", "hch_sconv_bwd_weight",
     "hch_sconv_bwd_data", "hch_avgpool_fwd", "hch_avgpool_bwd", "hch_build_levels_ratios",
@@ -37,7 +37,7 @@ exported_symbols = [
     "hch_col2hash",
     "hch_conv_workspace_bytes", "hch_conv_fwd", "hch_conv_bwd_data", "hch_conv_bwd_weight",
     "hch_pool_fwd", "hch_pool_bwd", "hch_relu_fwd", "hch_relu_bwd", "hch_relu_pool_fwd",
-    "hch_pool_relu_bwd", "hch_deconv_fwd", "hch_deconv_bwd_data", "hch_deconv_bwd_weight",
+    "hch_pool_relu_bwd", "hch_pool_relu_bwd_pooled", "hch_deconv_fwd", "hch_deconv_bwd_data", "hch_deconv_bwd_weight",
     "hch_unpool_fwd", "hch_unpool_bwd", "hch_kernel_count", "hch_kernel_name", "hch_profile_enable", "hch_profile_read",
     "hch_profile_reset", "hch_field_build", "hch_sconv_workspace_bytes", "hch_sconv_fwd", "hch_sconv_bwd_weight",
     "hch_sconv_bwd_data", "hch_avgpool_fwd", "hch_avgpool_bwd", "hch_build_levels_ratios",
@@ -125,6 +125,7 @@ def load_library():
     L.hch_pool_bwd.argtypes = [vp, i32, vp, vp, vp, i32, vp]
     L.hch_relu_pool_fwd.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
     L.hch_pool_relu_bwd.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
+    L.hch_pool_relu_bwd_pooled.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
     L.hch_relu_fwd.argtypes = [vp, vp, i64, vp]
     L.hch_relu_bwd.argtypes = [vp, vp, vp, i64, vp]
     L.hch_probe_mfma.argtypes = [C.c_int, i32, i32, vp, vp]
@@ -528,6 +529,13 @@ def hch_pool_relu_bwd(levels, level_in, dP, argmax, A, dY, c, stream=None):
     _check(load_library().hch_pool_relu_bwd(levels.handle, level_in, _dp(dP, "dP", _F32, nc * c),
                                             _dp(argmax, "argmax", _I32, nc * c), _dp(A, "A", _F32, nf * c),
                                             _dp(dY, "dY", _F32, nf * c), c, _stream(stream)))
+
+
+def hch_pool_relu_bwd_pooled(levels, level_in, dP, argmax, P, dY, c, stream=None):
+    nf, nc = _pool_rows(levels, level_in)
+    _check(load_library().hch_pool_relu_bwd_pooled(levels.handle, level_in, _dp(dP, "dP", _F32, nc * c),
+                                                   _dp(argmax, "argmax", _I32, nc * c), _dp(P, "P", _F32, nc * c),
+                                                   _dp(dY, "dY", _F32, nf * c), c, _stream(stream)))
 
 
 def hch_field_build(levels, level_in, F, stride, pad, field, field_t, stream=None):

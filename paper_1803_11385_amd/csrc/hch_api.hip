@@ -1930,33 +1930,51 @@ extern "C" hch_status hch_relu_pool_fwd(const hch_levels *levels, int32_t level_
     return HCH_OK;
 }
 
+// shared by the two forms of the fused backward step: `sign` holds fine rows (A or Y) or, pooled, the rows P
+static hch_status pool_relu_bwd_impl(const hch_levels *levels, int32_t level_in, const float *dP,
+                                     const int32_t *argmax, const float *sign, bool pooled, float *dY, int32_t c,
+                                     void *stream, const char *who)
+{
+    if (!levels || level_in < 0 || level_in + 1 >= (int32_t)levels->lv.size())
+        return fail(HCH_EINVAL, std::string(who) + ": level_in must have a coarser level");
+    if (!dP || !argmax || !sign || !dY || c <= 0) return fail(HCH_EINVAL, std::string(who) + ": bad argument");
+    const Level &Lc = levels->lv[level_in + 1];
+    const Level &Lf = levels->lv[level_in];
+    if (Lc.ratio != 2) return fail(HCH_EUNSUPPORTED, std::string(who) + ": these two levels are not in ratio 2; use hch_field_build with hch_spool_* / hch_sconv_*");
+    if (!Lc.dchild) return fail(HCH_EINVAL, std::string(who) + ": levels were built without device tables");
+    const bool vec = c % 4 == 0 && aligned16(dP) && aligned16(argmax) && aligned16(sign) && aligned16(dY);
+    const int64_t items = Lc.n_total * (vec ? c / 4 : c);
+    if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, std::string(who) + ": too large");
+    {
+        // per fine voxel: its gradient row out (and its row in, unless the pooled rows stand in);
+        // per coarse voxel: 8 indices, gradient and switch rows (and the pooled row) in
+        const double bytes = (double)Lf.n_total * (pooled ? 4.0 : 8.0) * c + (double)Lc.n_total * (32.0 + (pooled ? 12.0 : 8.0) * c);
+        const int kid = pooled ? (vec ? HCH_KERNEL_ID("pool_relu_bwd_kernel<4, true>") : HCH_KERNEL_ID("pool_relu_bwd_kernel<1, true>"))
+                               : (vec ? HCH_KERNEL_ID("pool_relu_bwd_kernel<4>") : HCH_KERNEL_ID("pool_relu_bwd_kernel<1>"));
+        hch::LaunchTimer lt(kid, (hipStream_t)stream, bytes, 0.0);
+#define HCH_POOL_RELU_BWD(VEC_, POOLED_)                                                                             \
+    HCH_LAUNCH((hch::pool_relu_bwd_kernel<VEC_, POOLED_>), dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream, \
+                       dP, argmax, Lc.dchild, sign, dY, Lc.n_total, c)
+        if (pooled) { if (vec) HCH_POOL_RELU_BWD(4, true); else HCH_POOL_RELU_BWD(1, true); }
+        else { if (vec) HCH_POOL_RELU_BWD(4, false); else HCH_POOL_RELU_BWD(1, false); }
+#undef HCH_POOL_RELU_BWD
+    }
+    HCH_LAUNCH_CHECK("pool_relu_bwd_kernel");
+    return HCH_OK;
+}
+
 extern "C" hch_status hch_pool_relu_bwd(const hch_levels *levels, int32_t level_in, const float *dP,
                                         const int32_t *argmax, const float *A, float *dY, int32_t c,
                                         void *stream)
 {
-    if (!levels || level_in < 0 || level_in + 1 >= (int32_t)levels->lv.size())
-        return fail(HCH_EINVAL, "hch_pool_relu_bwd: level_in must have a coarser level");
-    if (!dP || !argmax || !A || !dY || c <= 0) return fail(HCH_EINVAL, "hch_pool_relu_bwd: bad argument");
-    const Level &Lc = levels->lv[level_in + 1];
-    const Level &Lf = levels->lv[level_in];
-    if (Lc.ratio != 2) return fail(HCH_EUNSUPPORTED, "hch_pool_relu_bwd: these two levels are not in ratio 2; use hch_field_build with hch_spool_* / hch_sconv_*");
-    if (!Lc.dchild) return fail(HCH_EINVAL, "hch_pool_relu_bwd: levels were built without device tables");
-    const bool vec = c % 4 == 0 && aligned16(dP) && aligned16(argmax) && aligned16(A) && aligned16(dY);
-    const int64_t items = Lc.n_total * (vec ? c / 4 : c);
-    if (items > MAX_GRID_ITEMS) return fail(HCH_EUNSUPPORTED, "hch_pool_relu_bwd: too large");
-    {
-        const double bytes = (double)Lf.n_total * 8.0 * c + (double)Lc.n_total * (32.0 + 8.0 * c);
-        hch::LaunchTimer lt(vec ? HCH_KERNEL_ID("pool_relu_bwd_kernel<4>") : HCH_KERNEL_ID("pool_relu_bwd_kernel<1>"),
-                            (hipStream_t)stream, bytes, 0.0);
-        if (vec)
-            HCH_LAUNCH(hch::pool_relu_bwd_kernel<4>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
-                               dP, argmax, Lc.dchild, A, dY, Lc.n_total, c);
-        else
-            HCH_LAUNCH(hch::pool_relu_bwd_kernel<1>, dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream,
-                               dP, argmax, Lc.dchild, A, dY, Lc.n_total, c);
-    }
-    HCH_LAUNCH_CHECK("pool_relu_bwd_kernel");
-    return HCH_OK;
+    return pool_relu_bwd_impl(levels, level_in, dP, argmax, A, false, dY, c, stream, "hch_pool_relu_bwd");
+}
+
+extern "C" hch_status hch_pool_relu_bwd_pooled(const hch_levels *levels, int32_t level_in, const float *dP,
+                                               const int32_t *argmax, const float *P, float *dY, int32_t c,
+                                               void *stream)
+{
+    return pool_relu_bwd_impl(levels, level_in, dP, argmax, P, true, dY, c, stream, "hch_pool_relu_bwd_pooled");
 }
 
 // ---------------------------------------------------------------------------------------

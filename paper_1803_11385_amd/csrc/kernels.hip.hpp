@@ -1855,7 +1855,10 @@ __global__ __launch_bounds__(256) void relu_pool_fwd_kernel(
 // Max-pool backward followed by ReLU backward in one pass:
 // dY[j][ch] = (argmax[o][ch] == j and A[j][ch] > 0) ? dP[o][ch] : 0 for child j of coarse voxel o.
 // Only the sign of A is used, so the values before the ReLU serve as well.
-template <int VEC>
+// POOLED: `A` holds the pooled rows P[o][ch] of the forward pass instead ([n_coarse][c]): the child
+// the switch names carries the maximum, A[argmax[o][ch]][ch] = P[o][ch], so its sign is P's and
+// the fine rows need not be read (nor kept) at all.
+template <int VEC, bool POOLED = false>
 __global__ __launch_bounds__(256) void pool_relu_bwd_kernel(
     const float *__restrict__ dP, const int32_t *__restrict__ argmax, const int32_t *__restrict__ child8,
     const float *__restrict__ A, float *__restrict__ dY, int64_t n_coarse, int c)
@@ -1883,15 +1886,33 @@ __global__ __launch_bounds__(256) void pool_relu_bwd_kernel(
 #pragma unroll
         for (int e = 0; e < VEC; ++e) { g[e] = dP[o * c + u * VEC + e]; a[e] = argmax[o * c + u * VEC + e]; }
     }
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const float *s = j[k] >= 0 ? A + (int64_t)j[k] * c + u * VEC : zsrc;
+    if constexpr (POOLED) {
+        // the pooled row decides once for all children: a channel whose maximum is not positive passes nothing
+        float pv[VEC];
         if constexpr (VEC == 4) {
-            const f32x4 t = *reinterpret_cast<const f32x4 *>(s);
-            x[k][0] = t[0]; x[k][1] = t[1]; x[k][2] = t[2]; x[k][3] = t[3];
+            const f32x4 t = *reinterpret_cast<const f32x4 *>(A + o * c + u * 4);
+            pv[0] = t[0]; pv[1] = t[1]; pv[2] = t[2]; pv[3] = t[3];
         } else {
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) x[k][e] = s[e];
+            for (int e = 0; e < VEC; ++e) pv[e] = A[o * c + u * VEC + e];
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) g[e] = pv[e] > 0.f ? g[e] : 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) x[k][e] = 1.f;
+    } else {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float *s = j[k] >= 0 ? A + (int64_t)j[k] * c + u * VEC : zsrc;
+            if constexpr (VEC == 4) {
+                const f32x4 t = *reinterpret_cast<const f32x4 *>(s);
+                x[k][0] = t[0]; x[k][1] = t[1]; x[k][2] = t[2]; x[k][3] = t[3];
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) x[k][e] = s[e];
+            }
         }
     }
 #pragma unroll

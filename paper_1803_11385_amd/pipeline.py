@@ -101,7 +101,7 @@ class Encoder:
         main = torch.cuda.current_stream()
         for l in reversed(range(self.L)):
             if self.fuse_pointwise:
-                B.hch_pool_relu_bwd(self.levels, l, self.dX[l + 1], self.sw[l], self.Y[l], self.dY[l], ch[l + 1])
+                B.hch_pool_relu_bwd_pooled(self.levels, l, self.dX[l + 1], self.sw[l], self.X[l + 1], self.dY[l], ch[l + 1])
             else:
                 B.hch_pool_bwd(self.levels, l, self.dX[l + 1], self.sw[l], self.dA[l], ch[l + 1])
                 B.hch_relu_bwd(self.A[l], self.dA[l], self.dY[l], self.dY[l].numel())

@@ -413,6 +413,10 @@ def test_fused_relu_pool(oracle, case_batch64, c):
     dY2 = torch.full_like(dY, float("nan"))
     hch.hch_pool_relu_bwd(case.glv, 0, dev(dP), sw2, dev(Yin), dY2, c)
     assert torch.equal(dY2, dY)
+    # ... or from the pooled rows alone
+    dY3 = torch.full_like(dY, float("nan"))
+    hch.hch_pool_relu_bwd_pooled(case.glv, 0, dev(dP), sw2, P2, dY3, c)
+    assert torch.equal(dY3, dY)
 
 
 def test_relu():
