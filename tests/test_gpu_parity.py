@@ -452,6 +452,15 @@ def test_error_paths(case_sphere):
     with pytest.raises(hch.HchError) as ei:
         hch.hch_hash2col(case.glv, 0, hch.HCH_F32, X, 3, n - 5, 10, Y)
     assert ei.value.status == 1
+    n1 = case.olv[1].Ntot
+    dP = torch.zeros((n1, 16), dtype=torch.float32, device="cuda")
+    sw = torch.zeros((n1, 16), dtype=torch.int32, device="cuda")
+    with pytest.raises(hch.HchError) as ei:
+        hch.hch_pool_relu_bwd_pooled(case.glv, 1, dP, sw, dP, Y, 16)      # no coarser level below level 1
+    assert ei.value.status == 1
+    with pytest.raises(hch.HchError) as ei:
+        hch.hch_pool_relu_bwd_pooled(case.glv, 0, dP, sw, dP[: n1 - 1], Y, 16)   # pooled rows one short
+    assert ei.value.status == 1
 
 
 def test_weight_gradient_from_resident_columns(case_small):
