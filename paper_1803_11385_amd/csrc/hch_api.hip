@@ -1087,10 +1087,11 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
     const int ln = lean ? 1 : 0;
     if (ids[ln][pl][v][cfg] < 0) {
         char nm[128];
-        snprintf(nm, sizeof nm, "gemm_f32_kernel<%s, %d, %d, 32, %d, %d, %s, %s, %s%s>",
+        // all eleven template arguments, as a profiler prints the instantiation
+        snprintf(nm, sizeof nm, "gemm_f32_kernel<%s, %d, %d, 32, %d, %d, %s, %s, %s, %s, %s>",
                  sizeof(TIN) == 4 ? "float" : "unsigned short", p.bm, p.bm == 64 ? 64 : p.bn, p.wm,
                  (int)AMODE, B_KC ? "true" : "false", v ? "true" : "false", pl == 1 ? "true" : "false",
-                 lean ? (pl == 2 ? ", true, true" : ", false, true") : (pl == 2 ? ", true" : ""));
+                 pl == 2 ? "true" : "false", lean ? "true" : "false");
         ids[ln][pl][v][cfg] = hch::Profiler::get().id_for(nm);
     }
     int kid = ids[ln][pl][v][cfg];
@@ -1227,8 +1228,8 @@ static hch_status launch_gemm_bf16(const GemmPlan &p, const void *A, const void 
     const int ln = lean ? 1 : 0;
     if (ids[ln][cfg] < 0) {
         char nm[128];
-        snprintf(nm, sizeof nm, "gemm_bf16_kernel<%d, %d, %d, %d, %s%s>", big ? 256 : p.bm, p.bm == 64 ? 64 : p.bn, p.wm,
-                 (int)AMODE, B_KC ? "true" : "false", lean ? ", true" : "");
+        snprintf(nm, sizeof nm, "gemm_bf16_kernel<%d, %d, %d, %d, %s, %s>", big ? 256 : p.bm, p.bm == 64 ? 64 : p.bn, p.wm,
+                 (int)AMODE, B_KC ? "true" : "false", lean ? "true" : "false");
         ids[ln][cfg] = hch::Profiler::get().id_for(nm);
     }
     hch::LaunchTimer lt(ids[ln][cfg], s, alg_bytes, 2.0 * M * (double)N * K);
@@ -1342,7 +1343,7 @@ static hch_status launch_direct(const DirectPlan &d, const float *X, const int32
     const int b = d.check ? 1 : 0, k = skip ? 1 : 0;
     if (ids[k][b] < 0) {
         char nm[96];
-        snprintf(nm, sizeof nm, "conv_direct_kernel<%d, %d, %d, %s%s>", d.rt, d.nt, d.S, d.check ? "true" : "false", skip ? ", true" : "");
+        snprintf(nm, sizeof nm, "conv_direct_kernel<%d, %d, %d, %s, %s>", d.rt, d.nt, d.S, d.check ? "true" : "false", skip ? "true" : "false");
         ids[k][b] = hch::Profiler::get().id_for(nm);
     }
     hch::LaunchTimer lt(ids[k][b], s, alg_bytes, 2.0 * M * (double)N * 27.0 * c);
@@ -1374,7 +1375,7 @@ static hch_status launch_narrow4(const float *X, const int32_t *nbr, const float
     const int cc = c / 16;
     int kid;
     if (skip) kid = cc == 1 ? HCH_KERNEL_ID("conv_narrow4_kernel<1, true>") : (cc == 2 ? HCH_KERNEL_ID("conv_narrow4_kernel<2, true>") : HCH_KERNEL_ID("conv_narrow4_kernel<4, true>"));
-    else kid = cc == 1 ? HCH_KERNEL_ID("conv_narrow4_kernel<1>") : (cc == 2 ? HCH_KERNEL_ID("conv_narrow4_kernel<2>") : HCH_KERNEL_ID("conv_narrow4_kernel<4>"));
+    else kid = cc == 1 ? HCH_KERNEL_ID("conv_narrow4_kernel<1, false>") : (cc == 2 ? HCH_KERNEL_ID("conv_narrow4_kernel<2, false>") : HCH_KERNEL_ID("conv_narrow4_kernel<4, false>"));
     hch::LaunchTimer lt(kid, s, alg_bytes, 2.0 * M * 4.0 * 27.0 * c);
 #define HCH_NARROW_CASE(CC_)                                                                                          \
     do {                                                                                                                \
@@ -1950,7 +1951,7 @@ static hch_status pool_relu_bwd_impl(const hch_levels *levels, int32_t level_in,
         // per coarse voxel: 8 indices, gradient and switch rows (and the pooled row) in
         const double bytes = (double)Lf.n_total * (pooled ? 4.0 : 8.0) * c + (double)Lc.n_total * (32.0 + (pooled ? 12.0 : 8.0) * c);
         const int kid = pooled ? (vec ? HCH_KERNEL_ID("pool_relu_bwd_kernel<4, true>") : HCH_KERNEL_ID("pool_relu_bwd_kernel<1, true>"))
-                               : (vec ? HCH_KERNEL_ID("pool_relu_bwd_kernel<4>") : HCH_KERNEL_ID("pool_relu_bwd_kernel<1>"));
+                               : (vec ? HCH_KERNEL_ID("pool_relu_bwd_kernel<4, false>") : HCH_KERNEL_ID("pool_relu_bwd_kernel<1, false>"));
         hch::LaunchTimer lt(kid, (hipStream_t)stream, bytes, 0.0);
 #define HCH_POOL_RELU_BWD(VEC_, POOLED_)                                                                             \
     HCH_LAUNCH((hch::pool_relu_bwd_kernel<VEC_, POOLED_>), dim3(blocks_for(items)), dim3(256), 0, (hipStream_t)stream, \
