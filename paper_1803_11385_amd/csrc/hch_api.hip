@@ -1098,6 +1098,8 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
     if (lean && lean16)
         kid = tilemask ? HCH_KERNEL_ID("gemm_f32_kernel<float, 128, 32, 16, 4, 2, false, true, false, true, true>")
                        : HCH_KERNEL_ID("gemm_f32_kernel<float, 128, 32, 16, 4, 2, false, true, false, false, true>");
+    const bool short_k = AMODE == hch::A_ROWS && B_KC && pl == 1 && vec && p.bm == 128 && K <= 16 && p.splits == 1;
+    if (short_k) kid = HCH_KERNEL_ID("gemm_f32_kernel<float, 128, 64, 16, 4, 0, true, true, true, false, false>");
     hch::LaunchTimer lt(kid, s, alg_bytes, 2.0 * M * (double)N * K);
 #define HCH_GEMM_ARGS (const TIN *)A, (const TIN *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split, c_split_stride, c_vec_ok, \
                       m_tiles, c_planes, taps, b_wrap, b_tap_stride, rowmap, tilemask, flat
@@ -1107,7 +1109,11 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
     HCH_LAUNCH((hch::gemm_f32_kernel<TIN, BM_, BN_, 32, WM_, hch::A_GATHER, B_KC, true, false, true>), grid, dim3(256), 0, s, HCH_GEMM_ARGS)
     if constexpr (AMODE == hch::A_ROWS && B_KC) {
         if (pl == 1) {
-            if (vec) { if (p.bm == 64) HCH_GEMM_CASE(64, 64, 32, 2, true, true); else HCH_GEMM_CASE(128, 64, 32, 4, true, true); }
+            if (vec) {
+                if (p.bm == 64) HCH_GEMM_CASE(64, 64, 32, 2, true, true);
+                else if (short_k) HCH_GEMM_CASE(128, 64, 16, 4, true, true);      // a reduction of at most 16: one half-size tile
+                else HCH_GEMM_CASE(128, 64, 32, 4, true, true);
+            }
             else HCH_GEMM_CASE(128, 64, 32, 4, false, true);
             HCH_LAUNCH_CHECK("gemm_f32_kernel");
             return HCH_OK;

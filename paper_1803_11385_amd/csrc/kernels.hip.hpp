@@ -1280,9 +1280,16 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                        for (int nt = 0; nt < NT; ++nt)
-                            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(
-                                vget<4>(oa[slab * MT + mt], e), vget<NT>(ob[slab * 4 + e], nt), acc[mt][nt], 0, 0, 0);
+                        for (int nt = 0; nt < NT; ++nt) {
+                            // plane-wise output: the operands change places, which transposes the
+                            // 16x16 result in the registers (see the stores below)
+                            if constexpr (C_PLANES)
+                                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(
+                                    vget<NT>(ob[slab * 4 + e], nt), vget<4>(oa[slab * MT + mt], e), acc[mt][nt], 0, 0, 0);
+                            else
+                                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(
+                                    vget<4>(oa[slab * MT + mt], e), vget<NT>(ob[slab * 4 + e], nt), acc[mt][nt], 0, 0, 0);
+                        }
         } else {
 #pragma unroll
             for (int kk = 0; kk < BK / 4; ++kk)
@@ -1349,19 +1356,26 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     // C_PLANES: the output is stored plane by plane, C[j / c_planes][i][j % c_planes] (a
     // lane's NT <= 4 columns start at a multiple of NT and c_planes is a multiple of 4, so they
     // share a plane); else row-major with leading dimension ldc
-    const int gj = n0 + wn * WTN + li * NT;
+    // C_PLANES (row-major A only): the product was computed transposed, register e of lane l holds
+    // D[l%16][4*(l/16) + e]: the 16 lanes of a group hold 16 consecutive rows of the same NT
+    // columns, and a store instruction writes 16 rows x 16 bytes = 256 contiguous bytes of a plane
+    // (untransposed, the rows of one instruction lie 4 apart and every 16-byte piece is a request
+    // of its own: 112 -> see the measurements).
+    static_assert(!C_PLANES || A_K_FAST, "plane-wise output: row-major A");
+    int gj = n0 + wn * WTN + li * NT;
     int64_t row_stride = ldc, col_off = gj;
-    if constexpr (C_PLANES) {
-        const int pl = gj / c_planes;
-        row_stride = c_planes;
-        col_off = (int64_t)pl * M * c_planes + (gj - pl * c_planes);
-    }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int r = 4 * lk + e;
+            const int r = C_PLANES ? li : 4 * lk + e;
             const int gi = m0 + wm * WTM + (A_K_FAST ? mt * 16 + r : r * MT + mt);
+            if constexpr (C_PLANES) {
+                gj = n0 + wn * WTN + (4 * lk + e) * NT;
+                const int pl = gj / c_planes;
+                row_stride = c_planes;
+                col_off = (int64_t)pl * M * c_planes + (gj - pl * c_planes);
+            }
             if (gi >= M) continue;
             int64_t orow = gi;
             if constexpr (SKIP) orow = rowtile[gi - m0];
