@@ -1015,7 +1015,8 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
                                 const int32_t *nbr, int M, int N, int K, int64_t lda, int64_t ldb,
                                 int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s,
                                 int c_planes = 0, int taps = 27, int b_wrap = 0, int64_t b_tap_stride = 0,
-                                const int32_t *rowmap = nullptr, const uint32_t *tilemask = nullptr, int64_t a_rows = 0)
+                                const int32_t *rowmap = nullptr, const uint32_t *tilemask = nullptr, int64_t a_rows = 0,
+                                const uint32_t *rowmask = nullptr, int mask_c = 1)
 {
     if (M <= 0 || N <= 0) return HCH_OK;
     GemmPlan p = plan;
@@ -1102,7 +1103,7 @@ static hch_status launch_gemm_t(const GemmPlan &plan, const void *A, const void 
     if (short_k) kid = HCH_KERNEL_ID("gemm_f32_kernel<float, 128, 64, 16, 4, 0, true, true, true, false, false>");
     hch::LaunchTimer lt(kid, s, alg_bytes, 2.0 * M * (double)N * K);
 #define HCH_GEMM_ARGS (const TIN *)A, (const TIN *)B, C, nbr, M, N, K, lda, ldb, ldc, p.k_per_split, c_split_stride, c_vec_ok, \
-                      m_tiles, c_planes, taps, b_wrap, b_tap_stride, rowmap, tilemask, flat
+                      m_tiles, c_planes, taps, b_wrap, b_tap_stride, rowmap, tilemask, flat, rowmask, mask_c
 #define HCH_GEMM_CASE(BM_, BN_, BK_, WM_, VEC_, PL_)                                                                \
     HCH_LAUNCH((hch::gemm_f32_kernel<TIN, BM_, BN_, BK_, WM_, AMODE, B_KC, VEC_, PL_>), grid, dim3(256), 0, s, HCH_GEMM_ARGS)
 #define HCH_GEMM_SKIP_CASE(BM_, BN_, WM_)                                                                           \
@@ -1291,14 +1292,16 @@ static hch_status launch_gemm(hch_dtype dtype, const GemmPlan &p, const void *A,
                               int64_t ldc, int64_t c_split_stride, double alg_bytes, hipStream_t s,
                               int c_planes = 0, int taps = 27, int b_wrap = 0, int64_t b_tap_stride = 0,
                               const int32_t *nbr_t = nullptr, const int32_t *rowmap = nullptr, const uint32_t *tilemask = nullptr,
-                              int64_t a_rows = 0 /* rows of the gathered matrix; 0: not known, no lean loop */)
+                              int64_t a_rows = 0 /* rows of the gathered matrix; 0: not known, no lean loop */,
+                              const uint32_t *rowmask = nullptr /* per output row: which groups of mask_c columns to store (fp32 kernel) */,
+                              int mask_c = 1)
 {
     if (dtype == HCH_BF16 && bf16_mfma_ok<AMODE, B_KC>(p, A, B, M, N, K, lda, ldb, c_planes, b_wrap))
         return launch_gemm_bf16<AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, taps, b_wrap, b_tap_stride, nbr_t, a_rows);
     if (dtype == HCH_BF16)
         return launch_gemm_t<uint16_t, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps, b_wrap, b_tap_stride);
     return launch_gemm_t<float, AMODE, B_KC>(p, A, B, C, nbr, M, N, K, lda, ldb, ldc, c_split_stride, alg_bytes, s, c_planes, taps, b_wrap, b_tap_stride,
-                                             rowmap, tilemask, a_rows);
+                                             rowmap, tilemask, a_rows, rowmask, mask_c);
 }
 
 // Register-direct gathered product (conv_direct_kernel): shape-only part of the plan, shared by
@@ -1664,15 +1667,25 @@ extern "C" hch_status hch_conv_bwd_data(const hch_levels *levels, int32_t level,
     float *dcol = (float *)workspace;
     // dcol[N x Kc] = dY[N x c_out] . W^T   (W is [Kc x c_out]: its rows are B's columns)
     const GemmPlan p = plan_rows(n, Kc, c_out, false, k_gran(dtype));
-    const double bytes = es * ((double)n * c_out + (double)Kc * c_out) + 4.0 * (double)n * Kc;
     // with few input channels dcol is stored tap-major ([27][n][c_in]) between the two kernels:
     // the gather then reads, tap by tap, 16- or 32-byte pieces of nearly consecutive rows that
     // lie next to each other, instead of one such piece out of every 27*c_in-float row.  (With
     // 16 channels or more a piece fills its own memory sectors and the row-major store of the
     // product is the cheaper one: measured.)
     const bool planes = c_in % 4 == 0 && c_in <= 8 && aligned16(dX);
+    // Algorithm 2 adds dcol[i][k] to voxel nbr[i][k] and drops it where there is none: in the
+    // tap-major form those pieces (two thirds of dcol at the finest level) are not stored; the
+    // per-voxel bit sets of existing neighbours come with the index lists.  (Row-major, with 16 or
+    // more channels, leaving pieces out of the rows made the product slower by more than the
+    // gather gained: 96 -> 111 us and 45 -> 31 us at level 1, 72 -> 81 and 13 -> 13 at level 2.)
+    const bool masked = planes && L->dmask27 != nullptr;
+    const uint32_t *rowmask = masked ? L->dmask27 : nullptr;
+    // bytes: dY and W in; of dcol the pieces that have a destination, and 4 per row for the bit set (all of dcol without it)
+    const double bytes = es * ((double)n * c_out + (double)Kc * c_out) +
+                         (masked ? 4.0 * ((double)L->nbr_valid * c_in + (double)n) : 4.0 * (double)n * Kc);
     st = launch_gemm<hch::A_ROWS, true>(dtype, p, dY, W, dcol, nullptr,
-                                        (int)n, Kc, c_out, c_out, c_out, Kc, 0, bytes, s, planes ? c_in : 0);
+                                        (int)n, Kc, c_out, c_out, c_out, Kc, 0, bytes, s, planes ? c_in : 0,
+                                        27, 0, 0, nullptr, nullptr, nullptr, 0, rowmask, c_in);
     if (st != HCH_OK) return st;
     return do_col2hash(*L, dcol, c_in, dX, planes, s);
 }

@@ -729,7 +729,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     const int32_t *__restrict__ nbr, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
     int k_per_split, int64_t c_split_stride, int c_vec_ok, unsigned m_tiles, int c_planes, int taps,
     int b_wrap, int64_t b_tap_stride, const int32_t *__restrict__ rowmap, const uint32_t *__restrict__ tilemask,
-    int flat_slices)
+    int flat_slices, const uint32_t *__restrict__ rowmask, int mask_c)
 {
     constexpr int WN = 4 / WM;
     constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
@@ -1379,6 +1379,11 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
             if (gi >= M) continue;
             int64_t orow = gi;
             if constexpr (SKIP) orow = rowtile[gi - m0];
+            // rowmask (the data-gradient product of the columns algorithm): columns come in groups
+            // of mask_c, one group per tap, and bit t of rowmask[row] says whether the row has
+            // neighbour t.  The group of a row without it would be added to nothing (Algorithm 2
+            // drops it), so it is not stored either.
+            if (rowmask != nullptr && !((rowmask[orow] >> (gj / mask_c)) & 1u)) continue;
             float *dst = C + orow * row_stride + col_off;
             if (NT == 4 && c_vec_ok && gj + 4 <= N) {
                 *reinterpret_cast<f32x4 *>(dst) = f32x4{acc[mt][0][e], acc[mt][1 % NT][e], acc[mt][2 % NT][e], acc[mt][3 % NT][e]};

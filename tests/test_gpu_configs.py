@@ -44,7 +44,8 @@ def close(got, want, what, tol):
 
 
 def workspace(nbytes):
-    t = torch.empty(int(nbytes) + 256, dtype=torch.uint8, device="cuda")
+    # every byte 0xFF (NaN as a float, -1 as an index): a read of something the library did not write shows
+    t = torch.full((int(nbytes) + 256,), 255, dtype=torch.uint8, device="cuda")
     off = (-t.data_ptr()) % 256
     return t[off: off + int(nbytes)]
 

@@ -29,7 +29,8 @@ def assert_close(got, want, tol=TOL_F32, what=""):
 
 
 def workspace(nbytes):
-    t = torch.empty(max(nbytes, 256) + 256, dtype=torch.uint8, device="cuda")
+    # every byte 0xFF (NaN as a float, -1 as an index): a read of something the library did not write shows
+    t = torch.full((max(nbytes, 256) + 256,), 255, dtype=torch.uint8, device="cuda")
     off = (-t.data_ptr()) % 256
     return t[off: off + max(nbytes, 256)]
 
